@@ -1,0 +1,166 @@
+/*
+ * ssm.h -- C ABI of libssmscan: the sequence-parallel training pass of the S5-style diagonal
+ * state-space layer with episode resets, for one AMD MI355X (gfx950).
+ *
+ * Paper: "Accelerating Model-Based Reinforcement Learning with State-Space World Models".
+ * The layer is the discrete linear system of the Preliminaries ("State-Space Models", Eq. 3)
+ *        x_t = Abar x_{t-1} + Bbar u_t,        y_t = Cbar x_t + Dbar u_t
+ * with a diagonal complex Abar, evaluated over the whole sequence by the associative scan of
+ * Eq. 4-7, with the resettable elements and operator of the Methodology ("State-Space World
+ * Model", Eq. 9-10) so that an episode boundary cuts the state.
+ *
+ * Conventions for every entry point
+ *   - All array pointers are DEVICE pointers owned by the caller.  The library never allocates,
+ *     frees or keeps them.  The only exception is marked "host".
+ *   - complex64 = interleaved {float re, im} (bit-compatible with std::complex<float>).
+ *     Arrays are dense, row-major, innermost index last.  Complex arrays must be 8-byte aligned,
+ *     float arrays 4-byte aligned, the workspace 256-byte aligned.
+ *   - Bt sequences, L steps, H = width of u and y (real), P = number of complex diagonal states.
+ *   - is_first[b,t] != 0 marks a step whose incoming state is dropped (the flag element
+ *     1 - c_k of Eq. 9): x_t = Bbar u_t there.  is_first[b,0] != 0 makes x0[b] irrelevant.
+ *   - Calls validate their arguments on the host first and return an error code before any
+ *     launch; otherwise they enqueue kernels on `stream` (a hipStream_t, NULL = default stream)
+ *     and return without waiting.  No exceptions, no abort, no global mutable state: concurrent
+ *     calls are safe as long as they use distinct workspaces.
+ *   - Outputs are overwritten, never accumulated into.  Outputs must not alias inputs.
+ *   - The workspace must hold at least ssm_workspace_bytes(...) bytes; its contents are scratch
+ *     and need not be initialised or preserved between calls.
+ *   - Gradient of the real loss l w.r.t. a complex quantity q is returned as
+ *     dl/dRe(q) + i dl/dIm(q).
+ */
+#ifndef SSM_H_
+#define SSM_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct { float re, im; } ssm_c64;
+
+typedef enum {
+    SSM_OK = 0,
+    SSM_ERR_INVALID_ARG = 1,  /* NULL required pointer, non-positive dimension, misalignment */
+    SSM_ERR_WORKSPACE = 2,    /* workspace NULL or smaller than ssm_workspace_bytes()        */
+    SSM_ERR_UNSUPPORTED = 3,  /* dimension beyond SSM_MAX_*                                   */
+    SSM_ERR_HIP = 4,          /* a HIP runtime call or kernel launch failed                   */
+    SSM_ERR_SCAN_TIMEOUT = 5  /* reported by ssm_workspace_status(): a cross-block wait gave up */
+} ssm_status;
+
+#define SSM_MAX_WIDTH 65536          /* largest H and largest P                        */
+#define SSM_MAX_TOKENS 2147483647LL  /* largest Bt * L                                 */
+#define SSM_MAX_ELEMS (1LL << 40)    /* largest Bt * L * max(H, 2P)                    */
+
+/* Number of per-stage timings written by the *_profiled calls (see below). */
+#define SSM_FWD_STAGES 4
+#define SSM_BWD_STAGES 8
+
+/* Static description of an error code. Never NULL. */
+const char *ssm_strerror(int status);
+
+/* Library version, major * 100 + minor. */
+int ssm_version(void);
+
+/* Scratch bytes the forward (want_bwd = 0) or the gradient pass (want_bwd != 0) needs for the
+ * given shape.  Returns 0 for an invalid or unsupported shape.  Pure host function.           */
+size_t ssm_workspace_bytes(int64_t Bt, int64_t L, int64_t H, int64_t P, int want_bwd);
+
+/* Zero-order-hold discretisation of the diagonal continuous system (Eq. 2 -> Eq. 3; the paper
+ * only says the discrete matrices are functions of the continuous ones and the step, ZOH is the
+ * reading used here):  Delta_p = exp(log_delta_p),  A_bar_p = exp(Lambda_p Delta_p),
+ * B_bar[p,:] = (A_bar_p - 1)/Lambda_p * B[p,:]  (limit Delta_p * B[p,:] as Lambda_p -> 0).
+ *   in : Lambda [P] c64, B [P,H] c64 (may be NULL iff B_bar is NULL), log_delta [P] f32
+ *   out: A_bar [P] c64, B_bar [P,H] c64 (may be NULL)                                        */
+ssm_status ssm_discretize(const ssm_c64 *Lambda, const ssm_c64 *B, const float *log_delta,
+                          int64_t P, int64_t H, ssm_c64 *A_bar, ssm_c64 *B_bar, void *stream);
+
+/* Forward pass of the layer over Bt sequences (Eq. 3 computed by the scan of Eq. 4-7 with the
+ * reset operator of Eq. 10; the scan elements carry Bbar u_k, Eq. 6):
+ *   x[b,t,:] = (is_first[b,t] ? 0 : A_bar (.) x[b,t-1,:]) + B_bar u[b,t,:],   x[b,-1,:] = x0[b,:]
+ *   y[b,t,:] = Re(C x[b,t,:]) + D (.) u[b,t,:]
+ *   in : Lambda [P] c64, B [P,H] c64, C [H,P] c64, D [H] f32, log_delta [P] f32,
+ *        u [Bt,L,H] f32, is_first [Bt,L] u8 (NULL = no resets), x0 [Bt,P] c64 (NULL = zeros)
+ *   out: y [Bt,L,H] f32; x [Bt,L,P] c64, the states, needed by ssm_scan_bwd (NULL allowed when
+ *        no gradient pass follows); x_last [Bt,P] c64 = x[:,L-1,:] (NULL allowed), usable as the
+ *        x0 of a call that continues the same sequences.                                        */
+ssm_status ssm_scan_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, const float *D,
+                        const float *log_delta, const float *u, const uint8_t *is_first,
+                        const ssm_c64 *x0, int64_t Bt, int64_t L, int64_t H, int64_t P,
+                        float *y, ssm_c64 *x, ssm_c64 *x_last,
+                        void *workspace, size_t ws_bytes, void *stream);
+
+/* Gradient pass matching ssm_scan_fwd for the loss l = sum(dy * y): a reverse-time scan of the
+ * adjoint state chi_t = C^H dy_t + [not is_first_{t+1}] conj(A_bar) (.) chi_{t+1} with the same
+ * reset operator (Eq. 10) run backwards, then the adjoints of the two projections and of the
+ * discretisation.  The paper trains the layer with Adam and back-propagates first-order gradients
+ * through the dynamics (Methodology, world-model loss and actor loss) without spelling this out.
+ *   in : the eight inputs of the forward call with the same shapes, x [Bt,L,P] c64 as saved by
+ *        the forward call, dy [Bt,L,H] f32
+ *   out: du [Bt,L,H] f32, dLambda [P] c64, dB [P,H] c64, dC [H,P] c64, dD [H] f32,
+ *        dlog_delta [P] f32, dx0 [Bt,P] c64 (NULL allowed)                                      */
+ssm_status ssm_scan_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, const float *D,
+                        const float *log_delta, const float *u, const uint8_t *is_first,
+                        const ssm_c64 *x0, int64_t Bt, int64_t L, int64_t H, int64_t P,
+                        const ssm_c64 *x, const float *dy,
+                        float *du, ssm_c64 *dLambda, ssm_c64 *dB, ssm_c64 *dC, float *dD,
+                        float *dlog_delta, ssm_c64 *dx0,
+                        void *workspace, size_t ws_bytes, void *stream);
+
+/* The resettable scan alone (Eq. 4 with the elements of Eq. 9 and the operator of Eq. 10) on
+ * already projected elements, in place:  on entry v[b,t,p] holds the second component of the
+ * scan element (Bbar u_t)_p, on return the state x[b,t,p].
+ *   in : A_bar [P] c64 (any value, including 0), is_first [Bt,L] u8 or NULL, x0 [Bt,P] or NULL
+ *   io : v [Bt,L,P] c64
+ *   out: x_last [Bt,P] c64 (NULL allowed)
+ * Workspace: ssm_workspace_bytes(Bt, L, 1, P, 0) suffices.                                     */
+ssm_status ssm_scan_states(const ssm_c64 *A_bar, ssm_c64 *v, const uint8_t *is_first,
+                           const ssm_c64 *x0, int64_t Bt, int64_t L, int64_t P, ssm_c64 *x_last,
+                           void *workspace, size_t ws_bytes, void *stream);
+
+/* The reverse-time scan of the gradient pass alone, in place: on entry gx[b,t,p] = (C^H dy_t)_p,
+ * on return chi[b,t,p].  Also reduces dA_bar[p] = sum_{b,t} [not is_first[b,t]] conj(x[b,t-1,p])
+ * chi[b,t,p] (x[b,-1] = x0[b]) and dx0[b,p] = [not is_first[b,0]] conj(A_bar_p) chi[b,0,p].
+ *   in : A_bar [P], x [Bt,L,P], is_first or NULL, x0 or NULL
+ *   io : gx [Bt,L,P]
+ *   out: dA_bar [P] c64, dx0 [Bt,P] c64 (NULL allowed)
+ * Workspace: ssm_workspace_bytes(Bt, L, 1, P, 1) suffices.                                     */
+ssm_status ssm_scan_states_reverse(const ssm_c64 *A_bar, ssm_c64 *gx, const ssm_c64 *x,
+                                   const uint8_t *is_first, const ssm_c64 *x0,
+                                   int64_t Bt, int64_t L, int64_t P, ssm_c64 *dA_bar, ssm_c64 *dx0,
+                                   void *workspace, size_t ws_bytes, void *stream);
+
+/* Measurement aids: the same code path as ssm_scan_fwd / ssm_scan_bwd, with a HIP event recorded
+ * on `stream` around every kernel.  They wait for the stream before returning and write the
+ * milliseconds of each stage to the HOST array stage_ms:
+ *   forward : [0] discretise+pack, [1] input projection, [2] scan, [3] output projection
+ *   backward: [0] discretise+pack, [1] gx = C^H dy, [2] dC partials, [3] dD partials,
+ *             [4] reverse scan, [5] du, [6] dBbar partials, [7] parameter epilogue               */
+ssm_status ssm_scan_fwd_profiled(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C,
+                                 const float *D, const float *log_delta, const float *u,
+                                 const uint8_t *is_first, const ssm_c64 *x0,
+                                 int64_t Bt, int64_t L, int64_t H, int64_t P,
+                                 float *y, ssm_c64 *x, ssm_c64 *x_last,
+                                 void *workspace, size_t ws_bytes, void *stream,
+                                 float *stage_ms /* host, [SSM_FWD_STAGES] */);
+ssm_status ssm_scan_bwd_profiled(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C,
+                                 const float *D, const float *log_delta, const float *u,
+                                 const uint8_t *is_first, const ssm_c64 *x0,
+                                 int64_t Bt, int64_t L, int64_t H, int64_t P,
+                                 const ssm_c64 *x, const float *dy,
+                                 float *du, ssm_c64 *dLambda, ssm_c64 *dB, ssm_c64 *dC, float *dD,
+                                 float *dlog_delta, ssm_c64 *dx0,
+                                 void *workspace, size_t ws_bytes, void *stream,
+                                 float *stage_ms /* host, [SSM_BWD_STAGES] */);
+
+/* Waits for `stream` and reports whether any scan launched with this workspace since its last
+ * use gave up a bounded cross-block wait (SSM_ERR_SCAN_TIMEOUT; the outputs of that call are
+ * then invalid) or SSM_OK.  Long sequences are split over several workgroups that hand their
+ * running state forward; every such wait is bounded so that a kernel always terminates.        */
+ssm_status ssm_workspace_status(const void *workspace, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SSM_H_ */

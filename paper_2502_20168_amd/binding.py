@@ -1,0 +1,264 @@
+"""Thin Python binding of libssmscan.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (include/ssm.h).  Tensors are torch
+tensors that live on the GPU; torch is used for device memory and for the current stream and for
+nothing else -- all arithmetic of the layer runs in the HIP kernels of the library.  There is no
+CPU fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libssmscan.so")
+
+SSM_OK = 0
+SSM_ERR_INVALID_ARG = 1
+SSM_ERR_WORKSPACE = 2
+SSM_ERR_UNSUPPORTED = 3
+SSM_ERR_HIP = 4
+SSM_ERR_SCAN_TIMEOUT = 5
+SSM_FWD_STAGES = 4
+SSM_BWD_STAGES = 8
+FWD_STAGE_NAMES = ("discretize_pack", "project_in", "scan", "project_out")
+BWD_STAGE_NAMES = ("discretize_pack", "gx", "dC_partials", "dD_partials", "reverse_scan", "du",
+                   "dBbar_partials", "param_epilogue")
+
+EXPORTS = ("ssm_strerror", "ssm_version", "ssm_workspace_bytes", "ssm_discretize", "ssm_scan_fwd",
+           "ssm_scan_bwd", "ssm_scan_states", "ssm_scan_states_reverse", "ssm_scan_fwd_profiled",
+           "ssm_scan_bwd_profiled", "ssm_workspace_status")
+
+_lib = None
+_vp, _i64, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t
+
+
+class SsmError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__("%s: %s (status %d)" % (where, strerror(code), code))
+
+
+def lib():
+    """The loaded C-ABI library.  Raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("libssmscan.so is not built: run `python -c \"import __graft_entry__ as g; "
+                              "g.build()\"` or `python paper_2502_20168_amd/build.py` first")
+        L = ctypes.CDLL(LIB_PATH)
+        L.ssm_strerror.restype = ctypes.c_char_p
+        L.ssm_strerror.argtypes = [ctypes.c_int]
+        L.ssm_version.restype = ctypes.c_int
+        L.ssm_workspace_bytes.restype = _sz
+        L.ssm_workspace_bytes.argtypes = [_i64, _i64, _i64, _i64, ctypes.c_int]
+        L.ssm_discretize.restype = ctypes.c_int
+        L.ssm_discretize.argtypes = [_vp, _vp, _vp, _i64, _i64, _vp, _vp, _vp]
+        fwd = [_vp] * 8 + [_i64] * 4 + [_vp] * 3 + [_vp, _sz, _vp]
+        bwd = [_vp] * 8 + [_i64] * 4 + [_vp] * 2 + [_vp] * 7 + [_vp, _sz, _vp]
+        L.ssm_scan_fwd.restype = ctypes.c_int
+        L.ssm_scan_fwd.argtypes = fwd
+        L.ssm_scan_bwd.restype = ctypes.c_int
+        L.ssm_scan_bwd.argtypes = bwd
+        L.ssm_scan_fwd_profiled.restype = ctypes.c_int
+        L.ssm_scan_fwd_profiled.argtypes = fwd + [_vp]
+        L.ssm_scan_bwd_profiled.restype = ctypes.c_int
+        L.ssm_scan_bwd_profiled.argtypes = bwd + [_vp]
+        L.ssm_scan_states.restype = ctypes.c_int
+        L.ssm_scan_states.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _sz, _vp]
+        L.ssm_scan_states_reverse.restype = ctypes.c_int
+        L.ssm_scan_states_reverse.argtypes = [_vp] * 5 + [_i64] * 3 + [_vp, _vp, _vp, _sz, _vp]
+        L.ssm_workspace_status.restype = ctypes.c_int
+        L.ssm_workspace_status.argtypes = [_vp, _vp]
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().ssm_strerror(int(code)).decode()
+
+
+def ssm_version() -> int:
+    return int(lib().ssm_version())
+
+
+def ssm_workspace_bytes(Bt: int, L: int, H: int, P: int, want_bwd: bool) -> int:
+    return int(lib().ssm_workspace_bytes(Bt, L, H, P, 1 if want_bwd else 0))
+
+
+# ------------------------------------------------------------------ torch marshalling
+def _torch():
+    import torch
+    return torch
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    torch = _torch()
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _chk(t, dtype, shape, name):
+    torch = _torch()
+    if t is None:
+        return
+    if not t.is_cuda or t.dtype != dtype or tuple(t.shape) != tuple(shape) or not t.is_contiguous():
+        raise ValueError("%s must be a contiguous cuda tensor of dtype %s and shape %s, got %s %s on %s"
+                         % (name, dtype, tuple(shape), t.dtype, tuple(t.shape), t.device))
+
+
+def alloc_workspace(Bt, L, H, P, want_bwd, device="cuda"):
+    torch = _torch()
+    n = ssm_workspace_bytes(Bt, L, H, P, want_bwd)
+    if n == 0:
+        raise SsmError(SSM_ERR_UNSUPPORTED, "ssm_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def _check_inputs(Lambda, B, C, D, log_delta, u, is_first, x0):
+    torch = _torch()
+    if u.dim() != 3 or Lambda.dim() != 1:
+        raise ValueError("u must be [Bt,L,H] and Lambda [P]")
+    Bt, L, H = u.shape
+    P = Lambda.shape[0]
+    _chk(Lambda, torch.complex64, (P,), "Lambda")
+    _chk(B, torch.complex64, (P, H), "B")
+    _chk(C, torch.complex64, (H, P), "C")
+    _chk(D, torch.float32, (H,), "D")
+    _chk(log_delta, torch.float32, (P,), "log_delta")
+    _chk(u, torch.float32, (Bt, L, H), "u")
+    _chk(is_first, torch.uint8, (Bt, L), "is_first")
+    _chk(x0, torch.complex64, (Bt, P), "x0")
+    return Bt, L, H, P
+
+
+def ssm_discretize(Lambda, B, log_delta, stream=None):
+    """Returns (A_bar [P], B_bar [P,H]); B may be None (then B_bar is None)."""
+    torch = _torch()
+    P = Lambda.shape[0]
+    _chk(Lambda, torch.complex64, (P,), "Lambda")
+    _chk(log_delta, torch.float32, (P,), "log_delta")
+    H = 1 if B is None else B.shape[1]
+    _chk(B, torch.complex64, (P, H), "B")
+    A_bar = torch.empty_like(Lambda)
+    B_bar = None if B is None else torch.empty_like(B)
+    rc = lib().ssm_discretize(_ptr(Lambda), _ptr(B), _ptr(log_delta), P, H, _ptr(A_bar), _ptr(B_bar),
+                              _stream(stream))
+    if rc != SSM_OK:
+        raise SsmError(rc, "ssm_discretize")
+    return A_bar, B_bar
+
+
+def ssm_scan_fwd(Lambda, B, C, D, log_delta, u, is_first=None, x0=None, *, want_x=True,
+                 want_x_last=True, workspace=None, stream=None, out=None,
+                 profile=False) -> Dict[str, object]:
+    """Forward pass.  Returns dict(y, x or None, x_last or None[, stage_ms])."""
+    torch = _torch()
+    Bt, L, H, P = _check_inputs(Lambda, B, C, D, log_delta, u, is_first, x0)
+    out = out or {}
+    y = out.get("y") if out.get("y") is not None else torch.empty_like(u)
+    x = out.get("x") if out.get("x") is not None else (
+        torch.empty((Bt, L, P), dtype=torch.complex64, device=u.device) if want_x else None)
+    x_last = out.get("x_last") if out.get("x_last") is not None else (
+        torch.empty((Bt, P), dtype=torch.complex64, device=u.device) if want_x_last else None)
+    ws = workspace if workspace is not None else alloc_workspace(Bt, L, H, P, False, u.device)
+    args = [_ptr(Lambda), _ptr(B), _ptr(C), _ptr(D), _ptr(log_delta), _ptr(u), _ptr(is_first), _ptr(x0),
+            Bt, L, H, P, _ptr(y), _ptr(x), _ptr(x_last), _ptr(ws), ws.numel(), _stream(stream)]
+    res = {"y": y, "x": x, "x_last": x_last}
+    if profile:
+        ms = (ctypes.c_float * SSM_FWD_STAGES)()
+        rc = lib().ssm_scan_fwd_profiled(*args, ctypes.cast(ms, ctypes.c_void_p))
+        res["stage_ms"] = list(ms)
+    else:
+        rc = lib().ssm_scan_fwd(*args)
+    if rc != SSM_OK:
+        raise SsmError(rc, "ssm_scan_fwd")
+    return res
+
+
+def ssm_scan_bwd(Lambda, B, C, D, log_delta, u, is_first, x0, x, dy, *, want_dx0=True,
+                 workspace=None, stream=None, out=None, profile=False) -> Dict[str, object]:
+    """Gradient pass.  Returns dict(du, dLambda, dB, dC, dD, dlog_delta, dx0 or None[, stage_ms])."""
+    torch = _torch()
+    Bt, L, H, P = _check_inputs(Lambda, B, C, D, log_delta, u, is_first, x0)
+    _chk(x, torch.complex64, (Bt, L, P), "x")
+    _chk(dy, torch.float32, (Bt, L, H), "dy")
+    out = out or {}
+
+    def get(name, like=None, shape=None, dtype=None):
+        if out.get(name) is not None:
+            return out[name]
+        return torch.empty_like(like) if like is not None else torch.empty(shape, dtype=dtype, device=u.device)
+
+    res = {
+        "du": get("du", like=u), "dLambda": get("dLambda", like=Lambda), "dB": get("dB", like=B),
+        "dC": get("dC", like=C), "dD": get("dD", like=D), "dlog_delta": get("dlog_delta", like=log_delta),
+        "dx0": get("dx0", shape=(Bt, P), dtype=torch.complex64) if want_dx0 else None,
+    }
+    ws = workspace if workspace is not None else alloc_workspace(Bt, L, H, P, True, u.device)
+    args = [_ptr(Lambda), _ptr(B), _ptr(C), _ptr(D), _ptr(log_delta), _ptr(u), _ptr(is_first), _ptr(x0),
+            Bt, L, H, P, _ptr(x), _ptr(dy), _ptr(res["du"]), _ptr(res["dLambda"]), _ptr(res["dB"]),
+            _ptr(res["dC"]), _ptr(res["dD"]), _ptr(res["dlog_delta"]), _ptr(res["dx0"]),
+            _ptr(ws), ws.numel(), _stream(stream)]
+    if profile:
+        ms = (ctypes.c_float * SSM_BWD_STAGES)()
+        rc = lib().ssm_scan_bwd_profiled(*args, ctypes.cast(ms, ctypes.c_void_p))
+        res["stage_ms"] = list(ms)
+    else:
+        rc = lib().ssm_scan_bwd(*args)
+    if rc != SSM_OK:
+        raise SsmError(rc, "ssm_scan_bwd")
+    return res
+
+
+def ssm_scan_states(A_bar, v, is_first=None, x0=None, *, want_x_last=True, workspace=None, stream=None):
+    """In-place resettable scan of v [Bt,L,P] (becomes x).  Returns (v, x_last or None)."""
+    torch = _torch()
+    Bt, L, P = v.shape
+    _chk(A_bar, torch.complex64, (P,), "A_bar")
+    _chk(v, torch.complex64, (Bt, L, P), "v")
+    _chk(is_first, torch.uint8, (Bt, L), "is_first")
+    _chk(x0, torch.complex64, (Bt, P), "x0")
+    x_last = torch.empty((Bt, P), dtype=torch.complex64, device=v.device) if want_x_last else None
+    ws = workspace if workspace is not None else alloc_workspace(Bt, L, 1, P, False, v.device)
+    rc = lib().ssm_scan_states(_ptr(A_bar), _ptr(v), _ptr(is_first), _ptr(x0), Bt, L, P, _ptr(x_last),
+                               _ptr(ws), ws.numel(), _stream(stream))
+    if rc != SSM_OK:
+        raise SsmError(rc, "ssm_scan_states")
+    return v, x_last
+
+
+def ssm_scan_states_reverse(A_bar, gx, x, is_first=None, x0=None, *, want_dx0=True, workspace=None,
+                            stream=None):
+    """In-place reverse scan of gx [Bt,L,P] (becomes chi).  Returns (gx, dA_bar, dx0 or None)."""
+    torch = _torch()
+    Bt, L, P = gx.shape
+    _chk(A_bar, torch.complex64, (P,), "A_bar")
+    _chk(gx, torch.complex64, (Bt, L, P), "gx")
+    _chk(x, torch.complex64, (Bt, L, P), "x")
+    _chk(is_first, torch.uint8, (Bt, L), "is_first")
+    _chk(x0, torch.complex64, (Bt, P), "x0")
+    dA = torch.empty_like(A_bar)
+    dx0 = torch.empty((Bt, P), dtype=torch.complex64, device=gx.device) if want_dx0 else None
+    ws = workspace if workspace is not None else alloc_workspace(Bt, L, 1, P, True, gx.device)
+    rc = lib().ssm_scan_states_reverse(_ptr(A_bar), _ptr(gx), _ptr(x), _ptr(is_first), _ptr(x0), Bt, L, P,
+                                       _ptr(dA), _ptr(dx0), _ptr(ws), ws.numel(), _stream(stream))
+    if rc != SSM_OK:
+        raise SsmError(rc, "ssm_scan_states_reverse")
+    return gx, dA, dx0
+
+
+def ssm_workspace_status(workspace, stream=None) -> int:
+    return int(lib().ssm_workspace_status(_ptr(workspace), _stream(stream)))
+
+
+# ------------------------------------------------------------------ convenience for tests/bench
+def to_device(inp: Dict[str, Optional[object]], device="cuda") -> Dict[str, Optional[object]]:
+    """numpy dict from the workload generator -> dict of cuda tensors (None stays None)."""
+    torch = _torch()
+    return {k: (None if v is None else torch.from_numpy(v).to(device)) for k, v in inp.items()}

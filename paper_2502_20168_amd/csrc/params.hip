@@ -1,0 +1,224 @@
+// Parameter-sized kernels: zero-order-hold discretisation with operand packing for the
+// projection GEMMs, the column dot product behind dD, and the adjoint of the discretisation.
+// The handful of transcendental evaluations per state run in double precision: they are
+// P-sized (a few hundred values), and the (exp(z) - 1)/z quotient cancels badly in fp32 for the
+// small |Lambda Delta| that slowly decaying states have.
+#include "ssm_internal.h"
+
+namespace ssm {
+
+struct Zoh {
+    double delta;
+    double lr, li;   // Abar = exp(Lambda Delta)
+    double gr, gi;   // g = (Abar - 1)/Lambda = Delta * expm1(z)/z
+    double zr, zi;   // z = Lambda Delta
+};
+
+__device__ __forceinline__ void cdiv(double ar, double ai, double br, double bi, double &qr, double &qi)
+{
+    const double den = br * br + bi * bi;
+    qr = (ar * br + ai * bi) / den;
+    qi = (ai * br - ar * bi) / den;
+}
+
+__device__ Zoh zoh_discretize(float2 Lambda, float log_delta)
+{
+    Zoh o;
+    o.delta = exp((double)log_delta);
+    o.zr = (double)Lambda.x * o.delta;
+    o.zi = (double)Lambda.y * o.delta;
+    const double ea = exp(o.zr), cb = cos(o.zi), sb = sin(o.zi), sh = sin(0.5 * o.zi);
+    o.lr = ea * cb;
+    o.li = ea * sb;
+    // exp(z) - 1 with the cancellation removed: expm1(a) cos b - 2 sin^2(b/2) + i e^a sin b
+    const double er = expm1(o.zr) * cb - 2.0 * sh * sh, ei = ea * sb;
+    if (o.zr == 0.0 && o.zi == 0.0) {
+        o.gr = o.delta; o.gi = 0.0;
+    } else {
+        double qr, qi;
+        cdiv(er, ei, o.zr, o.zi, qr, qi);
+        o.gr = o.delta * qr; o.gi = o.delta * qi;
+    }
+    return o;
+}
+
+// Workgroups [0, P): state p -> Abar_p, packed Bbar rows 2p, 2p+1 (and the interleaved complex
+// Bbar when asked).  Workgroups [P, P+H): row h of C -> (Re, -Im) interleaved.
+__global__ void __launch_bounds__(256) prep_kernel(PrepArgs a)
+{
+    const int blk = blockIdx.x, tid = threadIdx.x;
+    if (blk == 0 && tid == 0 && a.hdr) {
+        a.hdr->ticket_fwd = 0; a.hdr->ticket_rev = 0; a.hdr->err = 0; a.hdr->magic = 0x53534d31u;
+    }
+    if (blk < a.P) {
+        const int p = blk;
+        const Zoh z = zoh_discretize(a.Lambda[p], a.log_delta[p]);
+        const float gr = (float)z.gr, gi = (float)z.gi;
+        if (tid == 0 && a.lam_bar) a.lam_bar[p] = make_float2((float)z.lr, (float)z.li);
+        if (a.B) {
+            for (int h = tid; h < a.H; h += 256) {
+                const float2 bv = a.B[(long)p * a.H + h];
+                const float re = gr * bv.x - gi * bv.y, im = gr * bv.y + gi * bv.x;
+                if (a.Bbar_ri) {
+                    a.Bbar_ri[(long)(2 * p) * a.H + h] = re;
+                    a.Bbar_ri[(long)(2 * p + 1) * a.H + h] = im;
+                }
+                if (a.Bbar_c64) a.Bbar_c64[(long)p * a.H + h] = make_float2(re, im);
+            }
+        }
+    } else if (a.Cc) {
+        const int h = blk - a.P;
+        const float2 *src = a.C + (long)h * a.P;
+        float2 *dst = reinterpret_cast<float2 *>(a.Cc) + (long)h * a.P;
+        for (int p = tid; p < a.P; p += 256) {
+            const float2 c = src[p];
+            dst[p] = make_float2(c.x, -c.y);
+        }
+    }
+}
+
+hipError_t launch_prep(const PrepArgs &a, hipStream_t s)
+{
+    const unsigned blocks = (unsigned)(a.P + (a.Cc ? a.H : 0));
+    hipLaunchKernelGGL(prep_kernel, dim3(blocks), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// partial[s][h] = sum_{t in slab s} a[t,h] * b[t,h]      (dD = sum_t dy_t (.) u_t)
+// workgroup = 64 columns x 4 row phases
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) coldot_kernel(ColDotArgs a)
+{
+    __shared__ float red[256];
+    const int tid = threadIdx.x;
+    const int col = blockIdx.x * 64 + (tid & 63), ph = tid >> 6;
+    const int slab = blockIdx.y;
+    const long rows_per = (a.T + a.nslab - 1) / a.nslab;
+    const long r0 = slab * rows_per, r1 = min((long)a.T, r0 + rows_per);
+    float s = 0.f;
+    if (col < a.H)
+        for (long t = r0 + ph; t < r1; t += 4) s = fmaf(a.a[t * a.H + col], a.b[t * a.H + col], s);
+    red[tid] = s;
+    __syncthreads();
+    if (ph == 0 && col < a.H)
+        a.partial[(long)slab * a.H + col] = (red[tid] + red[tid + 64]) + (red[tid + 128] + red[tid + 192]);
+}
+
+int coldot_slabs(int64_t T)
+{
+    int64_t n = (T + 63) / 64;
+    if (n > 64) n = 64;
+    if (n < 1) n = 1;
+    return (int)n;
+}
+
+hipError_t launch_coldot(const ColDotArgs &a, hipStream_t s)
+{
+    hipLaunchKernelGGL(coldot_kernel, dim3((unsigned)((a.H + 63) / 64), (unsigned)a.nslab), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// Adjoint of the discretisation and final reduction of the split partial sums.
+//   workgroups [0, P): state p.   dBbar[p,h] = sum of the K-split slabs (rows 2p, 2p+1);
+//       dB[p,h] = conj(g_p) dBbar[p,h];  dg_p = sum_h conj(B[p,h]) dBbar[p,h];
+//       dAbar_p = sum of the reverse scan's partial rows;
+//       dLambda_p = conj(Delta Abar) dAbar + conj(Delta^2 psi'(z)) dg,   psi(z) = (e^z - 1)/z
+//       dlog_delta_p = Delta * Re(conj(Lambda Abar) dAbar + conj(Abar) dg)
+//   workgroups [P, P+H): row h of dC = sum of its slabs with the imaginary part negated
+//       (dC[h,p] = sum_t dy[t,h] conj(x[t,p])), and dD[h] = sum of the column-dot slabs.
+// ---------------------------------------------------------------------------------------------
+__device__ void psi_prime(double zr, double zi, double er, double ei, double &pr, double &pi)
+{
+    // psi'(z) = (z e^z - e^z + 1)/z^2 = sum_k z^k (k+1)/(k+2)!
+    if (zr * zr + zi * zi < 0.25) {
+        double tr = 0.5, ti = 0.0;
+        pr = 0.5; pi = 0.0;
+        for (int k = 1; k < 32; ++k) {
+            const double c = (double)(k + 1) / ((double)k * (double)(k + 2));
+            const double nr = (tr * zr - ti * zi) * c, ni = (tr * zi + ti * zr) * c;
+            tr = nr; ti = ni;
+            pr += tr; pi += ti;
+        }
+    } else {
+        // (e^z - psi(z))/z with psi = expm1(z)/z; er, ei = e^z
+        const double sh = sin(0.5 * zi);
+        const double mr = expm1(zr) * cos(zi) - 2.0 * sh * sh, mi = ei;
+        double psr, psi_;
+        cdiv(mr, mi, zr, zi, psr, psi_);
+        cdiv(er - psr, ei - psi_, zr, zi, pr, pi);
+    }
+}
+
+__global__ void __launch_bounds__(256) epilogue_kernel(EpilogueArgs a)
+{
+    __shared__ double red_r[256], red_i[256];
+    const int blk = blockIdx.x, tid = threadIdx.x;
+    const long PH2 = 2L * a.P * a.H;
+    if (blk < a.P) {
+        const int p = blk;
+        const Zoh z = zoh_discretize(a.Lambda[p], a.log_delta[p]);
+        const float gr = (float)z.gr, gi = (float)z.gi;
+        double dgr = 0.0, dgi = 0.0;
+        for (int h = tid; h < a.H; h += 256) {
+            float sr = 0.f, si = 0.f;
+            for (int s = 0; s < a.nsplit_B; ++s) {
+                sr += a.dBbar_part[s * PH2 + (long)(2 * p) * a.H + h];
+                si += a.dBbar_part[s * PH2 + (long)(2 * p + 1) * a.H + h];
+            }
+            // conj(g) * dBbar
+            a.dB[(long)p * a.H + h] = make_float2(gr * sr + gi * si, gr * si - gi * sr);
+            const float2 bv = a.B[(long)p * a.H + h];
+            // conj(B) * dBbar
+            dgr += (double)bv.x * sr + (double)bv.y * si;
+            dgi += (double)bv.x * si - (double)bv.y * sr;
+        }
+        red_r[tid] = dgr; red_i[tid] = dgi;
+        __syncthreads();
+        for (int w = 128; w > 0; w >>= 1) {
+            if (tid < w) { red_r[tid] += red_r[tid + w]; red_i[tid] += red_i[tid + w]; }
+            __syncthreads();
+        }
+        if (tid == 0) {
+            dgr = red_r[0]; dgi = red_i[0];
+            double ar = 0.0, ai = 0.0;                    // dAbar
+            for (long i = 0; i < a.npart; ++i) {
+                ar += (double)a.dAbar_part[i * a.P + p].x;
+                ai += (double)a.dAbar_part[i * a.P + p].y;
+            }
+            const double Lr = a.Lambda[p].x, Li = a.Lambda[p].y, d = z.delta;
+            double pr, pi;
+            psi_prime(z.zr, z.zi, z.lr, z.li, pr, pi);
+            // conj(d * Abar) * dAbar + conj(d^2 psi') * dg
+            const double c1r = d * z.lr, c1i = d * z.li, c2r = d * d * pr, c2i = d * d * pi;
+            const double dLr = (c1r * ar + c1i * ai) + (c2r * dgr + c2i * dgi);
+            const double dLi = (c1r * ai - c1i * ar) + (c2r * dgi - c2i * dgr);
+            a.dLambda[p] = make_float2((float)dLr, (float)dLi);
+            // Re(conj(Lambda Abar) dAbar + conj(Abar) dg)
+            const double mr = Lr * z.lr - Li * z.li, mi = Lr * z.li + Li * z.lr;
+            const double dDelta = (mr * ar + mi * ai) + (z.lr * dgr + z.li * dgi);
+            a.dlog_delta[p] = (float)(d * dDelta);
+        }
+    } else {
+        const int h = blk - a.P;
+        for (int j = tid; j < 2 * a.P; j += 256) {
+            float s = 0.f;
+            for (int sidx = 0; sidx < a.nsplit_C; ++sidx) s += a.dC_part[sidx * PH2 + (long)h * 2 * a.P + j];
+            reinterpret_cast<float *>(a.dC)[(long)h * 2 * a.P + j] = (j & 1) ? -s : s;
+        }
+        if (tid == 0) {
+            float s = 0.f;
+            for (int sl = 0; sl < a.nslab; ++sl) s += a.dD_part[(long)sl * a.H + h];
+            a.dD[h] = s;
+        }
+    }
+}
+
+hipError_t launch_epilogue(const EpilogueArgs &a, hipStream_t s)
+{
+    hipLaunchKernelGGL(epilogue_kernel, dim3((unsigned)(a.P + a.H)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace ssm

@@ -1,0 +1,313 @@
+// Resettable scan over the sequence dimension, forward and reverse time (gfx950).
+//
+// What is computed: the inclusive scan of Eq. 4 over the elements (Abar, Bbar u_k, reset flag)
+// of Eq. 9 under the operator of Eq. 10.  For a diagonal Abar the products are element-wise, so
+// every (sequence, state) pair is an independent lane.  Three nested levels combine partial
+// results with that operator:
+//   1. a thread walks SCAN_E consecutive steps held in registers (loads are coalesced over the
+//      state index: neighbouring threads own neighbouring states of the same step);
+//   2. the cy chunks of a workgroup exchange their (product, state) aggregates through LDS;
+//   3. workgroups along time exchange aggregates through descriptors in global memory with a
+//      decoupled look-back: each publishes its own aggregate before it waits for anything, then
+//      fetches the aggregates of the earlier workgroups of its group (one per thread, all in
+//      flight at once) plus the inclusive state that closes the previous group.
+// Logical workgroup ids come from an atomic ticket, so a workgroup only ever waits for
+// workgroups that started before it, and every wait is bounded by spin_limit.
+//
+// The reverse scan runs the same operator over reversed time with conj(Abar):
+//   chi_t = gx_t + [not is_first_{t+1}] conj(Abar) chi_{t+1}
+// and additionally reduces dAbar += [not is_first_t] conj(x_{t-1}) chi_t.
+#include "ssm_internal.h"
+
+namespace ssm {
+
+__device__ __forceinline__ float2 cmul(float2 a, float2 b)
+{
+    return make_float2(a.x * b.x - a.y * b.y, a.x * b.y + a.y * b.x);
+}
+// a * b + c
+__device__ __forceinline__ float2 cfma(float2 a, float2 b, float2 c)
+{
+    return make_float2(fmaf(a.x, b.x, fmaf(-a.y, b.y, c.x)), fmaf(a.x, b.y, fmaf(a.y, b.x, c.y)));
+}
+
+__device__ __forceinline__ void store_c64_agent(float2 *p, float2 v)
+{
+    unsigned long long bits = ((unsigned long long)__float_as_uint(v.y) << 32) | __float_as_uint(v.x);
+    __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), bits, __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float2 load_c64_agent(const float2 *p)
+{
+    unsigned long long bits = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p),
+                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_float2(__uint_as_float((unsigned)(bits & 0xffffffffu)), __uint_as_float((unsigned)(bits >> 32)));
+}
+
+template <bool REV>
+__global__ void __launch_bounds__(SCAN_THREADS) scan_kernel(ScanArgs a)
+{
+    constexpr int E = SCAN_E;
+    __shared__ float2 sA[SCAN_THREADS];
+    __shared__ float2 sS[SCAN_THREADS];
+    __shared__ float2 sX[SCAN_THREADS];
+    __shared__ unsigned s_id;
+
+    const int tid = threadIdx.x;
+    unsigned id;
+    if (a.nTB > 1) {
+        if (tid == 0) s_id = atomicAdd(a.ticket, 1u);
+        __syncthreads();
+        id = s_id;
+    } else {
+        id = blockIdx.x;
+    }
+    // time index slowest: all first-in-time workgroups start before any second-in-time one
+    const int px = id % a.nPX;
+    const int b = (id / a.nPX) % a.Bt;
+    const int tb = id / (a.nPX * a.Bt);
+    const int lane = tid % a.pxb, chunk = tid / a.pxb;
+    const int p = px * a.pxb + lane;
+    const bool active = p < a.P;
+    const int L = a.L;
+    const int s0 = (tb * a.cy + chunk) * E;          // first logical step of this thread
+    const int len = max(0, min(E, L - s0));
+    const long rowbase = (long)b * L;
+
+    float2 lam = active ? a.lam[p] : make_float2(0.f, 0.f);
+    if (REV) lam.y = -lam.y;
+
+    // logical step s <-> time t: forward t = s, reverse t = L-1-s
+    float2 val[E];
+    float2 xp[REV ? E : 1];
+    unsigned rmask = 0;   // bit e: the incoming state of logical step s0+e is dropped
+    unsigned mmask = 0;   // reverse only, bit e: is_first at the time of logical step s0+e
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        val[e] = make_float2(0.f, 0.f);
+        if constexpr (REV) xp[e] = make_float2(0.f, 0.f);
+        if (e < len) {
+            const int s = s0 + e;
+            const int t = REV ? (L - 1 - s) : s;
+            if (active) {
+                val[e] = a.in[(rowbase + t) * a.P + p];
+                if constexpr (REV) {
+                    if (t > 0) xp[e] = a.xsaved[(rowbase + t - 1) * a.P + p];
+                    else if (a.x0) xp[e] = a.x0[(long)b * a.P + p];
+                }
+            }
+            if (a.is_first) {
+                const unsigned f = a.is_first[rowbase + t] != 0;
+                if (REV) {
+                    mmask |= f << e;
+                    // the flag that cuts chi_{t+1} -> chi_t is is_first[t+1], i.e. the flag of
+                    // the previous logical step
+                    if (e + 1 < E) rmask |= f << (e + 1);
+                } else {
+                    rmask |= f << e;
+                }
+            }
+        }
+    }
+    if (REV && a.is_first && len > 0 && s0 > 0) {
+        // flag of logical step s0-1 (time L-s0) cuts the carry into this thread's first step
+        rmask |= (unsigned)(a.is_first[rowbase + (L - s0)] != 0);
+    }
+
+    // ---- level 1, first pass: aggregate of the thread's steps for zero incoming state
+    float2 A = make_float2(1.f, 0.f), S = make_float2(0.f, 0.f);
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        if (e < len) {
+            if ((rmask >> e) & 1u) { S = val[e]; A = make_float2(0.f, 0.f); }
+            else { S = cfma(lam, S, val[e]); A = cmul(A, lam); }
+        }
+    }
+    sA[tid] = A;
+    sS[tid] = S;
+    __syncthreads();
+
+    // ---- level 2: exclusive combine over the earlier chunks of this workgroup
+    float2 Aex = make_float2(1.f, 0.f), Sex = make_float2(0.f, 0.f);
+    for (int j = 0; j < chunk; ++j) {
+        const float2 Aj = sA[j * a.pxb + lane], Sj = sS[j * a.pxb + lane];
+        Sex = cfma(Aj, Sex, Sj);
+        Aex = cmul(Aj, Aex);
+    }
+
+    // ---- level 3: incoming state of the workgroup.
+    // Workgroups along time form groups of G = cy.  The incoming state is always evaluated in
+    // one canonical order, whatever the timing: start from the inclusive state of the last
+    // workgroup of the previous group (x0 / zero for the first group) and fold the aggregates of
+    // the earlier workgroups of the own group over it.  Results are therefore bitwise
+    // reproducible.  Every workgroup publishes its aggregate before it waits for anything; the
+    // last workgroup of a group also publishes its inclusive state.
+    const int G = a.cy;
+    const int sg0 = (tb / G) * G;
+    const bool lastchunk = (chunk == a.cy - 1);
+    const size_t desc_stride = (size_t)a.nPX * a.Bt * a.pxb;     // descriptors per time step of workgroups
+    ScanDesc *mine = a.desc + ((size_t)id * a.pxb + lane);
+    float2 Ablk = make_float2(0.f, 0.f), Sblk = make_float2(0.f, 0.f), Xin = make_float2(0.f, 0.f);
+    if (lastchunk) {
+        Ablk = cmul(A, Aex);
+        Sblk = cfma(A, Sex, S);
+        if (a.nTB > 1 && tb + 1 < a.nTB) {
+            store_c64_agent(&mine->A, Ablk);
+            store_c64_agent(&mine->S, Sblk);
+            __hip_atomic_store(&mine->status, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (sg0 == 0 && !REV && a.x0 && active) Xin = a.x0[(long)b * a.P + p];
+    }
+    if (tb > 0) {                                    // uniform over the workgroup
+        __syncthreads();                             // level 2 has finished reading sA / sS
+        // thread (lane, chunk) fetches the aggregate of workgroup sg0 + chunk of this lane
+        float2 Aj = make_float2(1.f, 0.f), Sj = make_float2(0.f, 0.f);
+        const int j = sg0 + chunk;
+        if (j < tb) {
+            const ScanDesc *pred = mine - (size_t)(tb - j) * desc_stride;
+            unsigned st = 0, spins = 0;
+            while (true) {
+                st = __hip_atomic_load(&pred->status, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+                if (st != 0 || spins >= a.spin_limit) break;
+                ++spins;
+                __builtin_amdgcn_s_sleep(2);
+            }
+            if (st == 0) atomicOr(a.err, 1u);        // gave up: flag it and finish anyway
+            else { Aj = load_c64_agent(&pred->A); Sj = load_c64_agent(&pred->S); }
+        }
+        sA[tid] = Aj;
+        sS[tid] = Sj;
+        if (lastchunk && sg0 > 0) {
+            const ScanDesc *pred = mine - (size_t)(tb - sg0 + 1) * desc_stride;
+            unsigned st = 0, spins = 0;
+            while (true) {
+                st = __hip_atomic_load(&pred->status, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+                if (st == 2 || spins >= a.spin_limit) break;
+                ++spins;
+                __builtin_amdgcn_s_sleep(2);
+            }
+            if (st != 2) atomicOr(a.err, 1u);
+            else Xin = load_c64_agent(&pred->incl);
+        }
+        __syncthreads();
+        if (lastchunk) {
+            const int n = tb - sg0;
+            for (int c = 0; c < n; ++c) Xin = cfma(sA[c * a.pxb + lane], Xin, sS[c * a.pxb + lane]);
+        }
+    }
+    if (lastchunk) {
+        if (a.nTB > 1 && tb + 1 < a.nTB && (tb + 1) % G == 0) {
+            store_c64_agent(&mine->incl, cfma(Ablk, Xin, Sblk));
+            __hip_atomic_store(&mine->status, 2u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        sX[lane] = Xin;
+    }
+    __syncthreads();
+
+    // ---- level 1, second pass: the states themselves
+    float2 xs = cfma(Aex, sX[lane], Sex);
+    float2 acc = make_float2(0.f, 0.f);
+#pragma unroll
+    for (int e = 0; e < E; ++e) {
+        if (e < len) {
+            const int s = s0 + e;
+            const int t = REV ? (L - 1 - s) : s;
+            xs = ((rmask >> e) & 1u) ? val[e] : cfma(lam, xs, val[e]);
+            if (active) {
+                a.out[(rowbase + t) * a.P + p] = xs;
+                if constexpr (REV) {
+                    if (!((mmask >> e) & 1u)) {
+                        // conj(x_{t-1}) * chi_t
+                        acc.x += xp[e].x * xs.x + xp[e].y * xs.y;
+                        acc.y += xp[e].x * xs.y - xp[e].y * xs.x;
+                    }
+                    if (t == 0 && a.dx0)
+                        a.dx0[(long)b * a.P + p] =
+                            ((mmask >> e) & 1u) ? make_float2(0.f, 0.f) : cmul(lam, xs);
+                } else {
+                    if (t == L - 1 && a.x_last) a.x_last[(long)b * a.P + p] = xs;
+                }
+            }
+        }
+    }
+
+    if (REV) {
+        // sum the chunks' contributions to dAbar; one partial row per (sequence, workgroup in time)
+        sA[tid] = acc;
+        __syncthreads();
+        if (chunk == 0 && active) {
+            float2 sum = make_float2(0.f, 0.f);
+            for (int j = 0; j < a.cy; ++j) {
+                sum.x += sA[j * a.pxb + lane].x;
+                sum.y += sA[j * a.pxb + lane].y;
+            }
+            a.partial[((size_t)b * a.nTB + tb) * a.P + p] = sum;
+        }
+    }
+}
+
+ScanPlan plan_scan(int64_t Bt, int64_t L, int64_t P)
+{
+    ScanPlan pl;
+    // as many chunks per workgroup as the sequence can use, at most 16 (16 lanes = one 128-byte
+    // line of complex64 per step)
+    int cy = 1;
+    while (cy < 16 && (int64_t)cy * SCAN_E < L) cy *= 2;
+    pl.cy = cy;
+    pl.pxb = SCAN_THREADS / cy;
+    pl.nPX = (int)((P + pl.pxb - 1) / pl.pxb);
+    pl.nTB = (int)((L + (int64_t)cy * SCAN_E - 1) / ((int64_t)cy * SCAN_E));
+    pl.nblocks = (int64_t)pl.nPX * Bt * pl.nTB;
+    pl.desc_bytes = pl.nTB > 1 ? (size_t)pl.nblocks * pl.pxb * sizeof(ScanDesc) : 0;
+    pl.partial_elems = (size_t)Bt * pl.nTB * P;
+    return pl;
+}
+
+hipError_t launch_scan(const ScanArgs &a, bool reverse, hipStream_t s)
+{
+    const int64_t nblocks = (int64_t)a.nPX * a.Bt * a.nTB;
+    if (nblocks <= 0 || nblocks > 0x7fffffffLL || a.pxb * a.cy != SCAN_THREADS) return hipErrorInvalidValue;
+    if (reverse)
+        hipLaunchKernelGGL(scan_kernel<true>, dim3((unsigned)nblocks), dim3(SCAN_THREADS), 0, s, a);
+    else
+        hipLaunchKernelGGL(scan_kernel<false>, dim3((unsigned)nblocks), dim3(SCAN_THREADS), 0, s, a);
+    return hipGetLastError();
+}
+
+__global__ void __launch_bounds__(256) clear_kernel(WsHeader *hdr, uint4 *desc, size_t n16)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (i == 0) {
+        hdr->ticket_fwd = 0; hdr->ticket_rev = 0; hdr->err = 0; hdr->magic = 0x53534d31u;
+    }
+    for (size_t j = i; j < n16; j += (size_t)gridDim.x * 256) desc[j] = make_uint4(0, 0, 0, 0);
+}
+
+hipError_t launch_clear(WsHeader *hdr, ScanDesc *desc, size_t ndesc, hipStream_t s)
+{
+    const size_t n16 = ndesc * sizeof(ScanDesc) / 16;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks < 1) blocks = 1;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(clear_kernel, dim3((unsigned)blocks), dim3(256), 0, s, hdr,
+                       reinterpret_cast<uint4 *>(desc), n16);
+    return hipGetLastError();
+}
+
+__global__ void __launch_bounds__(256) reduce_partials_kernel(const float2 *partial, long n, long P, float2 *out)
+{
+    const long p = (long)blockIdx.x * 256 + threadIdx.x;
+    if (p >= P) return;
+    float2 s = make_float2(0.f, 0.f);
+    for (long i = 0; i < n; ++i) { s.x += partial[i * P + p].x; s.y += partial[i * P + p].y; }
+    out[p] = s;
+}
+
+hipError_t launch_reduce_partials(const float2 *partial, int64_t n, int64_t P, float2 *out, hipStream_t s)
+{
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s,
+                       partial, (long)n, (long)P, out);
+    return hipGetLastError();
+}
+
+}  // namespace ssm

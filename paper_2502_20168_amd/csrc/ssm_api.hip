@@ -1,0 +1,465 @@
+// Host side of libssmscan: argument validation, workspace layout and the kernel sequences of
+// the forward and the gradient pass.  See include/ssm.h for the contract of every entry point.
+#include "../../include/ssm.h"
+#include "ssm_internal.h"
+
+#include <cstdlib>
+#include <vector>
+
+using namespace ssm;
+
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
+
+struct Layout {
+    ScanPlan plan;
+    int splitC, splitB, nslab;
+    size_t hdr, lam, Bri, Cc, xbuf, chi, desc, dCpart, dBpart, dApart, dDpart, total;
+};
+
+ssm_status check_dims(int64_t Bt, int64_t L, int64_t H, int64_t P)
+{
+    if (Bt <= 0 || L <= 0 || H <= 0 || P <= 0) return SSM_ERR_INVALID_ARG;
+    if (H > SSM_MAX_WIDTH || P > SSM_MAX_WIDTH) return SSM_ERR_UNSUPPORTED;
+    if (Bt > SSM_MAX_TOKENS || L > SSM_MAX_TOKENS || Bt > SSM_MAX_TOKENS / L) return SSM_ERR_UNSUPPORTED;
+    const int64_t w = H > 2 * P ? H : 2 * P;
+    if (Bt * L > SSM_MAX_ELEMS / w) return SSM_ERR_UNSUPPORTED;
+    return SSM_OK;
+}
+
+ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, Layout &o)
+{
+    ssm_status st = check_dims(Bt, L, H, P);
+    if (st != SSM_OK) return st;
+    const size_t T = (size_t)Bt * L;
+    o.plan = plan_scan(Bt, L, P);
+    if (o.plan.nblocks > 0x7fffffffLL) return SSM_ERR_UNSUPPORTED;
+    o.splitC = gemm_pick_splits(H, 2 * P, (int64_t)T);
+    o.splitB = gemm_pick_splits(2 * P, H, (int64_t)T);
+    o.nslab = coldot_slabs((int64_t)T);
+    size_t off = 0;
+    o.hdr = off; off += up(sizeof(WsHeader));
+    o.lam = off; off += up((size_t)P * 8);
+    o.Bri = off; off += up((size_t)2 * P * H * 4);
+    o.Cc = off; off += up((size_t)2 * P * H * 4);
+    o.desc = off; off += up(o.plan.desc_bytes);
+    o.xbuf = o.chi = o.dCpart = o.dBpart = o.dApart = o.dDpart = 0;
+    if (!bwd) {
+        o.xbuf = off; off += up(T * P * 8);
+    } else {
+        o.chi = off; off += up(T * P * 8);
+        o.dCpart = off; off += up((size_t)o.splitC * 2 * P * H * 4);
+        o.dBpart = off; off += up((size_t)o.splitB * 2 * P * H * 4);
+        o.dApart = off; off += up(o.plan.partial_elems * 8);
+        o.dDpart = off; off += up((size_t)o.nslab * H * 4);
+    }
+    o.total = off;
+    return SSM_OK;
+}
+
+inline bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+uint32_t spin_limit()
+{
+    // upper bound on the polls of one cross-workgroup wait (each poll sleeps ~128 clocks)
+    const char *e = std::getenv("SSM_SPIN_LIMIT");
+    if (e && *e) return (uint32_t)std::strtoul(e, nullptr, 10);
+    return 1u << 20;
+}
+
+// Records an event on the stream around every stage when timing is requested.
+struct StageTimer {
+    hipStream_t s;
+    std::vector<hipEvent_t> ev;
+    bool ok = true;
+    explicit StageTimer(hipStream_t st) : s(st) {}
+    void mark()
+    {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) { ok = false; return; }
+        if (hipEventRecord(e, s) != hipSuccess) ok = false;
+        ev.push_back(e);
+    }
+    bool finish(float *ms, int n)
+    {
+        if (hipStreamSynchronize(s) != hipSuccess) ok = false;
+        for (int i = 0; i < n; ++i) {
+            ms[i] = 0.f;
+            if (ok && i + 1 < (int)ev.size() && hipEventElapsedTime(&ms[i], ev[i], ev[i + 1]) != hipSuccess) ok = false;
+        }
+        for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+        ev.clear();
+        return ok;
+    }
+};
+#define MARK() do { if (timer) timer->mark(); } while (0)
+#define HIP_TRY(expr) do { if ((expr) != hipSuccess) return SSM_ERR_HIP; } while (0)
+
+ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, const float *D,
+                   const float *log_delta, const float *u, const uint8_t *is_first, const ssm_c64 *x0,
+                   int64_t Bt, int64_t L, int64_t H, int64_t P, float *y, ssm_c64 *x, ssm_c64 *x_last,
+                   void *workspace, size_t ws_bytes, hipStream_t s, StageTimer *timer)
+{
+    if (!Lambda || !B || !C || !D || !log_delta || !u || !y) return SSM_ERR_INVALID_ARG;
+    Layout lo;
+    ssm_status st = make_layout(Bt, L, H, P, false, lo);
+    if (st != SSM_OK) return st;
+    if (misaligned(Lambda, 8) || misaligned(B, 8) || misaligned(C, 8) || misaligned(D, 4) ||
+        misaligned(log_delta, 4) || misaligned(u, 4) || misaligned(y, 4) || misaligned(x, 8) ||
+        misaligned(x0, 8) || misaligned(x_last, 8))
+        return SSM_ERR_INVALID_ARG;
+    if (!workspace || misaligned(workspace, ALIGN) || ws_bytes < lo.total) return SSM_ERR_WORKSPACE;
+
+    char *ws = static_cast<char *>(workspace);
+    WsHeader *hdr = reinterpret_cast<WsHeader *>(ws + lo.hdr);
+    float2 *lam = reinterpret_cast<float2 *>(ws + lo.lam);
+    float *Bri = reinterpret_cast<float *>(ws + lo.Bri);
+    float *Cc = reinterpret_cast<float *>(ws + lo.Cc);
+    ScanDesc *desc = reinterpret_cast<ScanDesc *>(ws + lo.desc);
+    float2 *xs = x ? reinterpret_cast<float2 *>(x) : reinterpret_cast<float2 *>(ws + lo.xbuf);
+    const int T = (int)(Bt * L);
+
+    MARK();
+    if (lo.plan.nTB > 1)
+        HIP_TRY(launch_clear(hdr, desc, lo.plan.desc_bytes / sizeof(ScanDesc), s));
+    PrepArgs pa{};
+    pa.Lambda = reinterpret_cast<const float2 *>(Lambda); pa.B = reinterpret_cast<const float2 *>(B);
+    pa.C = reinterpret_cast<const float2 *>(C); pa.log_delta = log_delta;
+    pa.P = (int)P; pa.H = (int)H; pa.lam_bar = lam; pa.Bbar_ri = Bri; pa.Cc = Cc; pa.Bbar_c64 = nullptr;
+    pa.hdr = lo.plan.nTB > 1 ? nullptr : hdr;
+    HIP_TRY(launch_prep(pa, s));
+    MARK();
+
+    // v[t, 2p+c] = sum_h u[t,h] * Bbar_ri[2p+c, h]      (second scan-element component, Eq. 6)
+    GemmArgs g1{};
+    g1.A = u; g1.lda = H; g1.a_kcontig = 1;
+    g1.B = Bri; g1.ldb = H; g1.b_kcontig = 1;
+    g1.C = reinterpret_cast<float *>(xs); g1.ldc = 2 * P;
+    g1.M = T; g1.N = (int)(2 * P); g1.K = (int)H; g1.splits = 1;
+    HIP_TRY(launch_gemm(g1, s));
+    MARK();
+
+    ScanArgs sa{};
+    sa.in = xs; sa.out = xs; sa.lam = lam; sa.is_first = is_first;
+    sa.x0 = reinterpret_cast<const float2 *>(x0); sa.x_last = reinterpret_cast<float2 *>(x_last);
+    sa.desc = desc; sa.ticket = &hdr->ticket_fwd; sa.err = &hdr->err;
+    sa.Bt = (int)Bt; sa.L = (int)L; sa.P = (int)P;
+    sa.pxb = lo.plan.pxb; sa.cy = lo.plan.cy; sa.nPX = lo.plan.nPX; sa.nTB = lo.plan.nTB;
+    sa.spin_limit = spin_limit();
+    HIP_TRY(launch_scan(sa, false, s));
+    MARK();
+
+    // y[t,h] = sum_p (Re C[h,p] x_re - Im C[h,p] x_im) + D[h] u[t,h]       (Eq. 3, second line)
+    GemmArgs g2{};
+    g2.A = reinterpret_cast<const float *>(xs); g2.lda = 2 * P; g2.a_kcontig = 1;
+    g2.B = Cc; g2.ldb = 2 * P; g2.b_kcontig = 1;
+    g2.C = y; g2.ldc = H; g2.diag = D; g2.E = u; g2.lde = H;
+    g2.M = T; g2.N = (int)H; g2.K = (int)(2 * P); g2.splits = 1;
+    HIP_TRY(launch_gemm(g2, s));
+    MARK();
+    return SSM_OK;
+}
+
+ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, const float *D,
+                   const float *log_delta, const float *u, const uint8_t *is_first, const ssm_c64 *x0,
+                   int64_t Bt, int64_t L, int64_t H, int64_t P, const ssm_c64 *x, const float *dy,
+                   float *du, ssm_c64 *dLambda, ssm_c64 *dB, ssm_c64 *dC, float *dD, float *dlog_delta,
+                   ssm_c64 *dx0, void *workspace, size_t ws_bytes, hipStream_t s, StageTimer *timer)
+{
+    if (!Lambda || !B || !C || !D || !log_delta || !u || !x || !dy || !du || !dLambda || !dB || !dC ||
+        !dD || !dlog_delta)
+        return SSM_ERR_INVALID_ARG;
+    Layout lo;
+    ssm_status st = make_layout(Bt, L, H, P, true, lo);
+    if (st != SSM_OK) return st;
+    if (misaligned(Lambda, 8) || misaligned(B, 8) || misaligned(C, 8) || misaligned(D, 4) ||
+        misaligned(log_delta, 4) || misaligned(u, 4) || misaligned(x, 8) || misaligned(dy, 4) ||
+        misaligned(du, 4) || misaligned(dLambda, 8) || misaligned(dB, 8) || misaligned(dC, 8) ||
+        misaligned(dD, 4) || misaligned(dlog_delta, 4) || misaligned(dx0, 8) || misaligned(x0, 8))
+        return SSM_ERR_INVALID_ARG;
+    if (!workspace || misaligned(workspace, ALIGN) || ws_bytes < lo.total) return SSM_ERR_WORKSPACE;
+
+    char *ws = static_cast<char *>(workspace);
+    WsHeader *hdr = reinterpret_cast<WsHeader *>(ws + lo.hdr);
+    float2 *lam = reinterpret_cast<float2 *>(ws + lo.lam);
+    float *Bri = reinterpret_cast<float *>(ws + lo.Bri);
+    float *Cc = reinterpret_cast<float *>(ws + lo.Cc);
+    ScanDesc *desc = reinterpret_cast<ScanDesc *>(ws + lo.desc);
+    float2 *chi = reinterpret_cast<float2 *>(ws + lo.chi);
+    float *dCpart = reinterpret_cast<float *>(ws + lo.dCpart);
+    float *dBpart = reinterpret_cast<float *>(ws + lo.dBpart);
+    float2 *dApart = reinterpret_cast<float2 *>(ws + lo.dApart);
+    float *dDpart = reinterpret_cast<float *>(ws + lo.dDpart);
+    const int T = (int)(Bt * L);
+    const float *xf = reinterpret_cast<const float *>(x);
+
+    MARK();
+    if (lo.plan.nTB > 1)
+        HIP_TRY(launch_clear(hdr, desc, lo.plan.desc_bytes / sizeof(ScanDesc), s));
+    PrepArgs pa{};
+    pa.Lambda = reinterpret_cast<const float2 *>(Lambda); pa.B = reinterpret_cast<const float2 *>(B);
+    pa.C = reinterpret_cast<const float2 *>(C); pa.log_delta = log_delta;
+    pa.P = (int)P; pa.H = (int)H; pa.lam_bar = lam; pa.Bbar_ri = Bri; pa.Cc = Cc; pa.Bbar_c64 = nullptr;
+    pa.hdr = lo.plan.nTB > 1 ? nullptr : hdr;
+    HIP_TRY(launch_prep(pa, s));
+    MARK();
+
+    // gx[t, 2p+c] = sum_h dy[t,h] * Cc[h, 2p+c]           (C^H dy_t)
+    GemmArgs g3{};
+    g3.A = dy; g3.lda = H; g3.a_kcontig = 1;
+    g3.B = Cc; g3.ldb = 2 * P; g3.b_kcontig = 0;
+    g3.C = reinterpret_cast<float *>(chi); g3.ldc = 2 * P;
+    g3.M = T; g3.N = (int)(2 * P); g3.K = (int)H; g3.splits = 1;
+    HIP_TRY(launch_gemm(g3, s));
+    MARK();
+
+    // dC slabs: [h, 2p+c] = sum_t dy[t,h] * x[t, 2p+c]
+    GemmArgs g4{};
+    g4.A = dy; g4.lda = H; g4.a_kcontig = 0;
+    g4.B = xf; g4.ldb = 2 * P; g4.b_kcontig = 0;
+    g4.C = dCpart; g4.ldc = 2 * P;
+    g4.M = (int)H; g4.N = (int)(2 * P); g4.K = T; g4.splits = lo.splitC;
+    HIP_TRY(launch_gemm(g4, s));
+    MARK();
+
+    ColDotArgs cd{};
+    cd.a = dy; cd.b = u; cd.T = T; cd.H = (int)H; cd.nslab = lo.nslab; cd.partial = dDpart;
+    HIP_TRY(launch_coldot(cd, s));
+    MARK();
+
+    ScanArgs sa{};
+    sa.in = chi; sa.out = chi; sa.lam = lam; sa.is_first = is_first;
+    sa.x0 = reinterpret_cast<const float2 *>(x0);
+    sa.xsaved = reinterpret_cast<const float2 *>(x); sa.partial = dApart;
+    sa.dx0 = reinterpret_cast<float2 *>(dx0);
+    sa.desc = desc; sa.ticket = &hdr->ticket_rev; sa.err = &hdr->err;
+    sa.Bt = (int)Bt; sa.L = (int)L; sa.P = (int)P;
+    sa.pxb = lo.plan.pxb; sa.cy = lo.plan.cy; sa.nPX = lo.plan.nPX; sa.nTB = lo.plan.nTB;
+    sa.spin_limit = spin_limit();
+    HIP_TRY(launch_scan(sa, true, s));
+    MARK();
+
+    // du[t,h] = sum_{p,c} chi[t, 2p+c] * Bbar_ri[2p+c, h] + D[h] dy[t,h]      (Re(Bbar^H chi) + D dy)
+    GemmArgs g5{};
+    g5.A = reinterpret_cast<const float *>(chi); g5.lda = 2 * P; g5.a_kcontig = 1;
+    g5.B = Bri; g5.ldb = H; g5.b_kcontig = 0;
+    g5.C = du; g5.ldc = H; g5.diag = D; g5.E = dy; g5.lde = H;
+    g5.M = T; g5.N = (int)H; g5.K = (int)(2 * P); g5.splits = 1;
+    HIP_TRY(launch_gemm(g5, s));
+    MARK();
+
+    // dBbar slabs: [2p+c, h] = sum_t chi[t, 2p+c] * u[t,h]
+    GemmArgs g6{};
+    g6.A = reinterpret_cast<const float *>(chi); g6.lda = 2 * P; g6.a_kcontig = 0;
+    g6.B = u; g6.ldb = H; g6.b_kcontig = 0;
+    g6.C = dBpart; g6.ldc = H;
+    g6.M = (int)(2 * P); g6.N = (int)H; g6.K = T; g6.splits = lo.splitB;
+    HIP_TRY(launch_gemm(g6, s));
+    MARK();
+
+    EpilogueArgs ea{};
+    ea.Lambda = reinterpret_cast<const float2 *>(Lambda); ea.B = reinterpret_cast<const float2 *>(B);
+    ea.log_delta = log_delta; ea.P = (int)P; ea.H = (int)H;
+    ea.dBbar_part = dBpart; ea.nsplit_B = lo.splitB;
+    ea.dC_part = dCpart; ea.nsplit_C = lo.splitC;
+    ea.dAbar_part = dApart; ea.npart = (int64_t)Bt * lo.plan.nTB;
+    ea.dD_part = dDpart; ea.nslab = lo.nslab;
+    ea.dLambda = reinterpret_cast<float2 *>(dLambda); ea.dB = reinterpret_cast<float2 *>(dB);
+    ea.dC = reinterpret_cast<float2 *>(dC); ea.dD = dD; ea.dlog_delta = dlog_delta;
+    HIP_TRY(launch_epilogue(ea, s));
+    MARK();
+    return SSM_OK;
+}
+
+struct ScanOnlyLayout { ScanPlan plan; size_t hdr, desc, dApart, total; };
+
+ssm_status make_scan_layout(int64_t Bt, int64_t L, int64_t P, bool rev, ScanOnlyLayout &o)
+{
+    ssm_status st = check_dims(Bt, L, 1, P);
+    if (st != SSM_OK) return st;
+    o.plan = plan_scan(Bt, L, P);
+    if (o.plan.nblocks > 0x7fffffffLL) return SSM_ERR_UNSUPPORTED;
+    size_t off = 0;
+    o.hdr = off; off += up(sizeof(WsHeader));
+    o.desc = off; off += up(o.plan.desc_bytes);
+    o.dApart = off; if (rev) off += up(o.plan.partial_elems * 8);
+    o.total = off;
+    return SSM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *ssm_strerror(int status)
+{
+    switch (status) {
+    case SSM_OK: return "ok";
+    case SSM_ERR_INVALID_ARG: return "invalid argument (null required pointer, non-positive dimension or misaligned array)";
+    case SSM_ERR_WORKSPACE: return "workspace missing, misaligned or smaller than ssm_workspace_bytes()";
+    case SSM_ERR_UNSUPPORTED: return "dimension beyond the supported limits";
+    case SSM_ERR_HIP: return "HIP runtime call or kernel launch failed";
+    case SSM_ERR_SCAN_TIMEOUT: return "a bounded cross-workgroup wait in the scan gave up; outputs invalid";
+    default: return "unknown status";
+    }
+}
+
+int ssm_version(void) { return 100; }
+
+size_t ssm_workspace_bytes(int64_t Bt, int64_t L, int64_t H, int64_t P, int want_bwd)
+{
+    Layout lo;
+    if (make_layout(Bt, L, H, P, want_bwd != 0, lo) != SSM_OK) return 0;
+    return lo.total;
+}
+
+ssm_status ssm_discretize(const ssm_c64 *Lambda, const ssm_c64 *B, const float *log_delta,
+                          int64_t P, int64_t H, ssm_c64 *A_bar, ssm_c64 *B_bar, void *stream)
+{
+    if (!Lambda || !log_delta || !A_bar || (B_bar && !B)) return SSM_ERR_INVALID_ARG;
+    if (P <= 0 || H <= 0) return SSM_ERR_INVALID_ARG;
+    if (P > SSM_MAX_WIDTH || H > SSM_MAX_WIDTH) return SSM_ERR_UNSUPPORTED;
+    if (misaligned(Lambda, 8) || misaligned(B, 8) || misaligned(log_delta, 4) || misaligned(A_bar, 8) ||
+        misaligned(B_bar, 8))
+        return SSM_ERR_INVALID_ARG;
+    PrepArgs pa{};
+    pa.Lambda = reinterpret_cast<const float2 *>(Lambda);
+    pa.B = B_bar ? reinterpret_cast<const float2 *>(B) : nullptr;
+    pa.log_delta = log_delta; pa.P = (int)P; pa.H = (int)H;
+    pa.lam_bar = reinterpret_cast<float2 *>(A_bar);
+    pa.Bbar_c64 = reinterpret_cast<float2 *>(B_bar);
+    HIP_TRY(launch_prep(pa, static_cast<hipStream_t>(stream)));
+    return SSM_OK;
+}
+
+ssm_status ssm_scan_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, const float *D,
+                        const float *log_delta, const float *u, const uint8_t *is_first,
+                        const ssm_c64 *x0, int64_t Bt, int64_t L, int64_t H, int64_t P,
+                        float *y, ssm_c64 *x, ssm_c64 *x_last, void *workspace, size_t ws_bytes, void *stream)
+{
+    return run_fwd(Lambda, B, C, D, log_delta, u, is_first, x0, Bt, L, H, P, y, x, x_last, workspace,
+                   ws_bytes, static_cast<hipStream_t>(stream), nullptr);
+}
+
+ssm_status ssm_scan_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, const float *D,
+                        const float *log_delta, const float *u, const uint8_t *is_first,
+                        const ssm_c64 *x0, int64_t Bt, int64_t L, int64_t H, int64_t P,
+                        const ssm_c64 *x, const float *dy, float *du, ssm_c64 *dLambda, ssm_c64 *dB,
+                        ssm_c64 *dC, float *dD, float *dlog_delta, ssm_c64 *dx0,
+                        void *workspace, size_t ws_bytes, void *stream)
+{
+    return run_bwd(Lambda, B, C, D, log_delta, u, is_first, x0, Bt, L, H, P, x, dy, du, dLambda, dB, dC,
+                   dD, dlog_delta, dx0, workspace, ws_bytes, static_cast<hipStream_t>(stream), nullptr);
+}
+
+ssm_status ssm_scan_fwd_profiled(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C,
+                                 const float *D, const float *log_delta, const float *u,
+                                 const uint8_t *is_first, const ssm_c64 *x0,
+                                 int64_t Bt, int64_t L, int64_t H, int64_t P,
+                                 float *y, ssm_c64 *x, ssm_c64 *x_last,
+                                 void *workspace, size_t ws_bytes, void *stream, float *stage_ms)
+{
+    if (!stage_ms) return SSM_ERR_INVALID_ARG;
+    StageTimer timer(static_cast<hipStream_t>(stream));
+    ssm_status st = run_fwd(Lambda, B, C, D, log_delta, u, is_first, x0, Bt, L, H, P, y, x, x_last,
+                            workspace, ws_bytes, static_cast<hipStream_t>(stream), &timer);
+    const bool ok = timer.finish(stage_ms, SSM_FWD_STAGES);
+    if (st != SSM_OK) return st;
+    return ok ? SSM_OK : SSM_ERR_HIP;
+}
+
+ssm_status ssm_scan_bwd_profiled(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C,
+                                 const float *D, const float *log_delta, const float *u,
+                                 const uint8_t *is_first, const ssm_c64 *x0,
+                                 int64_t Bt, int64_t L, int64_t H, int64_t P,
+                                 const ssm_c64 *x, const float *dy,
+                                 float *du, ssm_c64 *dLambda, ssm_c64 *dB, ssm_c64 *dC, float *dD,
+                                 float *dlog_delta, ssm_c64 *dx0,
+                                 void *workspace, size_t ws_bytes, void *stream, float *stage_ms)
+{
+    if (!stage_ms) return SSM_ERR_INVALID_ARG;
+    StageTimer timer(static_cast<hipStream_t>(stream));
+    ssm_status st = run_bwd(Lambda, B, C, D, log_delta, u, is_first, x0, Bt, L, H, P, x, dy, du, dLambda,
+                            dB, dC, dD, dlog_delta, dx0, workspace, ws_bytes,
+                            static_cast<hipStream_t>(stream), &timer);
+    const bool ok = timer.finish(stage_ms, SSM_BWD_STAGES);
+    if (st != SSM_OK) return st;
+    return ok ? SSM_OK : SSM_ERR_HIP;
+}
+
+ssm_status ssm_scan_states(const ssm_c64 *A_bar, ssm_c64 *v, const uint8_t *is_first,
+                           const ssm_c64 *x0, int64_t Bt, int64_t L, int64_t P, ssm_c64 *x_last,
+                           void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!A_bar || !v) return SSM_ERR_INVALID_ARG;
+    ScanOnlyLayout lo;
+    ssm_status st = make_scan_layout(Bt, L, P, false, lo);
+    if (st != SSM_OK) return st;
+    if (misaligned(A_bar, 8) || misaligned(v, 8) || misaligned(x0, 8) || misaligned(x_last, 8))
+        return SSM_ERR_INVALID_ARG;
+    if (!workspace || misaligned(workspace, ALIGN) || ws_bytes < lo.total) return SSM_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    WsHeader *hdr = reinterpret_cast<WsHeader *>(ws + lo.hdr);
+    ScanDesc *desc = reinterpret_cast<ScanDesc *>(ws + lo.desc);
+    HIP_TRY(launch_clear(hdr, desc, lo.plan.desc_bytes / sizeof(ScanDesc), s));
+    ScanArgs sa{};
+    sa.in = reinterpret_cast<const float2 *>(v); sa.out = reinterpret_cast<float2 *>(v);
+    sa.lam = reinterpret_cast<const float2 *>(A_bar); sa.is_first = is_first;
+    sa.x0 = reinterpret_cast<const float2 *>(x0); sa.x_last = reinterpret_cast<float2 *>(x_last);
+    sa.desc = desc; sa.ticket = &hdr->ticket_fwd; sa.err = &hdr->err;
+    sa.Bt = (int)Bt; sa.L = (int)L; sa.P = (int)P;
+    sa.pxb = lo.plan.pxb; sa.cy = lo.plan.cy; sa.nPX = lo.plan.nPX; sa.nTB = lo.plan.nTB;
+    sa.spin_limit = spin_limit();
+    HIP_TRY(launch_scan(sa, false, s));
+    return SSM_OK;
+}
+
+ssm_status ssm_scan_states_reverse(const ssm_c64 *A_bar, ssm_c64 *gx, const ssm_c64 *x,
+                                   const uint8_t *is_first, const ssm_c64 *x0,
+                                   int64_t Bt, int64_t L, int64_t P, ssm_c64 *dA_bar, ssm_c64 *dx0,
+                                   void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!A_bar || !gx || !x || !dA_bar) return SSM_ERR_INVALID_ARG;
+    ScanOnlyLayout lo;
+    ssm_status st = make_scan_layout(Bt, L, P, true, lo);
+    if (st != SSM_OK) return st;
+    if (misaligned(A_bar, 8) || misaligned(gx, 8) || misaligned(x, 8) || misaligned(x0, 8) ||
+        misaligned(dA_bar, 8) || misaligned(dx0, 8))
+        return SSM_ERR_INVALID_ARG;
+    if (!workspace || misaligned(workspace, ALIGN) || ws_bytes < lo.total) return SSM_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    WsHeader *hdr = reinterpret_cast<WsHeader *>(ws + lo.hdr);
+    ScanDesc *desc = reinterpret_cast<ScanDesc *>(ws + lo.desc);
+    float2 *dApart = reinterpret_cast<float2 *>(ws + lo.dApart);
+    HIP_TRY(launch_clear(hdr, desc, lo.plan.desc_bytes / sizeof(ScanDesc), s));
+    ScanArgs sa{};
+    sa.in = reinterpret_cast<const float2 *>(gx); sa.out = reinterpret_cast<float2 *>(gx);
+    sa.lam = reinterpret_cast<const float2 *>(A_bar); sa.is_first = is_first;
+    sa.x0 = reinterpret_cast<const float2 *>(x0);
+    sa.xsaved = reinterpret_cast<const float2 *>(x); sa.partial = dApart;
+    sa.dx0 = reinterpret_cast<float2 *>(dx0);
+    sa.desc = desc; sa.ticket = &hdr->ticket_rev; sa.err = &hdr->err;
+    sa.Bt = (int)Bt; sa.L = (int)L; sa.P = (int)P;
+    sa.pxb = lo.plan.pxb; sa.cy = lo.plan.cy; sa.nPX = lo.plan.nPX; sa.nTB = lo.plan.nTB;
+    sa.spin_limit = spin_limit();
+    HIP_TRY(launch_scan(sa, true, s));
+    HIP_TRY(launch_reduce_partials(dApart, (int64_t)Bt * lo.plan.nTB, P,
+                                   reinterpret_cast<float2 *>(dA_bar), s));
+    return SSM_OK;
+}
+
+ssm_status ssm_workspace_status(const void *workspace, void *stream)
+{
+    if (!workspace) return SSM_ERR_WORKSPACE;
+    HIP_TRY(hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+    WsHeader h{};
+    HIP_TRY(hipMemcpy(&h, workspace, sizeof(h), hipMemcpyDeviceToHost));
+    if (h.magic != 0x53534d31u) return SSM_ERR_INVALID_ARG;   // no call has used this workspace
+    return h.err ? SSM_ERR_SCAN_TIMEOUT : SSM_OK;
+}
+
+}  // extern "C"

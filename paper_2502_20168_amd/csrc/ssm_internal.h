@@ -1,0 +1,110 @@
+// Internal declarations shared by the translation units of libssmscan (gfx950 only).
+// Nothing here is part of the C ABI; see include/ssm.h for that.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace ssm {
+
+// ---------------------------------------------------------------------------------------------
+// fp32 MFMA GEMM:  C[m,n] = sum_k A(m,k) * B(n,k)  (+ diag[n] * E[m,n])
+// A(m,k) = a_kcontig ? A[m*lda + k] : A[k*lda + m];  B(n,k) = b_kcontig ? B[n*ldb + k] : B[k*ldb + n]
+// splits > 1: split z covers a contiguous K range and writes its own slab C + z*M*ldc
+// (no epilogue term in that case); the caller reduces the slabs.
+// ---------------------------------------------------------------------------------------------
+struct GemmArgs {
+    const float *A; int64_t lda; int a_kcontig;
+    const float *B; int64_t ldb; int b_kcontig;
+    float *C; int64_t ldc;
+    const float *diag; const float *E; int64_t lde;
+    int M, N, K, splits;
+};
+hipError_t launch_gemm(const GemmArgs &g, hipStream_t s);
+// number of K splits used for a reduction over `K` rows with an M x N result
+int gemm_pick_splits(int64_t M, int64_t N, int64_t K);
+
+// ---------------------------------------------------------------------------------------------
+// Resettable scan over the sequence dimension (forward and reverse time).
+// One thread owns SCAN_E consecutive steps of one (sequence, state) lane; a workgroup of 256
+// threads is laid out as cy chunks x pxb lanes and so covers cy*SCAN_E steps of pxb states;
+// longer sequences use several workgroups along time that hand their running state forward
+// through descriptors in global memory (decoupled look-back).
+// ---------------------------------------------------------------------------------------------
+constexpr int SCAN_E = 16;
+constexpr int SCAN_THREADS = 256;
+
+struct ScanDesc {            // one per (workgroup, lane); 32 bytes
+    float2 A;                // product of the transition over the workgroup's steps (0 after a reset)
+    float2 S;                // state at the end of the workgroup's steps for zero incoming state
+    float2 incl;             // state at the end of the workgroup's steps, incoming state included
+    uint32_t status;         // 0 = nothing, 1 = (A,S) valid, 2 = incl valid
+    uint32_t pad;
+};
+
+struct ScanPlan {
+    int pxb, cy;             // lanes and chunks per workgroup (pxb * cy == SCAN_THREADS)
+    int nPX, nTB;            // workgroups along the state and the time dimension
+    int64_t nblocks;         // nPX * Bt * nTB
+    size_t desc_bytes;       // 0 when nTB == 1
+    size_t partial_elems;    // Bt * nTB * P complex partial sums of the reverse scan
+};
+ScanPlan plan_scan(int64_t Bt, int64_t L, int64_t P);
+
+struct WsHeader {            // first 256 bytes of every workspace
+    uint32_t ticket_fwd, ticket_rev, err, magic;
+};
+
+struct ScanArgs {
+    const float2 *in;        // v (forward) or gx (reverse), [Bt,L,P]
+    float2 *out;             // x (forward) or chi (reverse); may alias `in`
+    const float2 *lam;       // A_bar [P]
+    const uint8_t *is_first; // [Bt,L] or null
+    const float2 *x0;        // [Bt,P] or null
+    float2 *x_last;          // forward only, or null
+    const float2 *xsaved;    // reverse only: states x [Bt,L,P]
+    float2 *partial;         // reverse only: [Bt*nTB, P]
+    float2 *dx0;             // reverse only, or null
+    ScanDesc *desc;
+    uint32_t *ticket;
+    uint32_t *err;
+    int Bt, L, P, pxb, cy, nPX, nTB;
+    uint32_t spin_limit;
+};
+hipError_t launch_scan(const ScanArgs &a, bool reverse, hipStream_t s);
+hipError_t launch_clear(WsHeader *hdr, ScanDesc *desc, size_t ndesc, hipStream_t s);
+// out[p] = sum_i partial[i*P + p]
+hipError_t launch_reduce_partials(const float2 *partial, int64_t n, int64_t P, float2 *out, hipStream_t s);
+
+// ---------------------------------------------------------------------------------------------
+// Parameter-sized kernels
+// ---------------------------------------------------------------------------------------------
+struct PrepArgs {
+    const float2 *Lambda; const float2 *B; const float2 *C; const float *log_delta;
+    int P, H;
+    float2 *lam_bar;         // [P]
+    float *Bbar_ri;          // [2P, H]: row 2p = Re(g_p B[p,:]), row 2p+1 = Im(g_p B[p,:]); may be null
+    float *Cc;               // [H, 2P]: (Re C[h,p], -Im C[h,p]) interleaved; may be null
+    float2 *Bbar_c64;        // [P, H] interleaved complex, for ssm_discretize; may be null
+    WsHeader *hdr;           // cleared when non-null
+};
+hipError_t launch_prep(const PrepArgs &a, hipStream_t s);
+
+struct ColDotArgs {          // partial[s][h] = sum over the rows of slab s of a[t,h] * b[t,h]
+    const float *a; const float *b; int64_t T; int H; int nslab; float *partial;
+};
+hipError_t launch_coldot(const ColDotArgs &a, hipStream_t s);
+int coldot_slabs(int64_t T);
+
+struct EpilogueArgs {
+    const float2 *Lambda; const float2 *B; const float *log_delta; int P, H;
+    const float *dBbar_part; int nsplit_B;   // [nsplit_B][2P][H]
+    const float *dC_part; int nsplit_C;      // [nsplit_C][H][2P]  (sum_t dy x_re, sum_t dy x_im)
+    const float2 *dAbar_part; int64_t npart; // [npart][P]
+    const float *dD_part; int nslab;         // [nslab][H]
+    float2 *dLambda; float2 *dB; float2 *dC; float *dD; float *dlog_delta;
+};
+hipError_t launch_epilogue(const EpilogueArgs &a, hipStream_t s);
+
+}  // namespace ssm
