@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of the resettable S5 scan layer on one MI355X.
+
+One "step" is one pass of the whole hot path -- forward (discretise, input projection, resettable
+scan, output projection) plus the gradient pass (C^H dy, reverse scan, du, parameter gradients)
+-- over one synthetic world-model-shaped batch (Bt=16, L=256, H=P=512) that is already resident
+in HBM.  Prints ONE JSON line:
+  metric/value : whole-job throughput in Mtokens/s (token = one (sequence, step) pair)
+  roofline     : the dominant kernel (the fp32 MFMA GEMM that produces the dC / dBbar partial
+                 sums, two launches per step) against the fp32 matrix peak, its duration measured
+                 with HIP events on the launch stream inside the library's *_profiled entry points
+  scan_roofline: the two scan kernels against the HBM peak (algorithmic bytes / event time),
+                 warm (buffers resident in the 256 MB last-level cache) and cold (rotating over
+                 more than 1 GiB of distinct buffers)
+  cpu_baseline : the float64 CPU oracle timed on the host cores on a bounded sample
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
+PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, help="index into the benchmark configurations")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-iters", type=int, default=30)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2502_20168_amd import binding as ssm
+    from paper_2502_20168_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    ssm.lib()                                  # fail loudly if the HIP library is missing
+    w = wl.CONFIGS[args.config]
+    Bt, L, H, P = w.Bt, w.L, w.H, w.P
+    T = w.tokens
+    inp = wl.gen_inputs(w)
+    d = ssm.to_device(inp)
+    par = (d["Lambda"], d["B"], d["C"], d["D"], d["log_delta"])
+
+    ws_f = ssm.alloc_workspace(Bt, L, H, P, False)
+    ws_b = ssm.alloc_workspace(Bt, L, H, P, True)
+    out_f = {"y": torch.empty_like(d["u"]),
+             "x": torch.empty((Bt, L, P), dtype=torch.complex64, device="cuda"),
+             "x_last": torch.empty((Bt, P), dtype=torch.complex64, device="cuda")}
+    out_b = {"du": torch.empty_like(d["u"]), "dLambda": torch.empty_like(d["Lambda"]),
+             "dB": torch.empty_like(d["B"]), "dC": torch.empty_like(d["C"]), "dD": torch.empty_like(d["D"]),
+             "dlog_delta": torch.empty_like(d["log_delta"]),
+             "dx0": torch.empty((Bt, P), dtype=torch.complex64, device="cuda")}
+
+    def step(profile=False):
+        f = ssm.ssm_scan_fwd(*par, d["u"], d["is_first"], d["x0"], workspace=ws_f, out=out_f, profile=profile)
+        b = ssm.ssm_scan_bwd(*par, d["u"], d["is_first"], d["x0"], out_f["x"], d["dy"], workspace=ws_b,
+                             out=out_b, profile=profile)
+        return f, b
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    mtok = T / (ms_per_step * 1e-3) / 1e6
+    assert ssm.ssm_workspace_status(ws_f) == ssm.SSM_OK and ssm.ssm_workspace_status(ws_b) == ssm.SSM_OK
+
+    # ---- per-kernel durations from HIP events recorded on the launch stream (library side)
+    fs = np.zeros(ssm.SSM_FWD_STAGES)
+    bs = np.zeros(ssm.SSM_BWD_STAGES)
+    for _ in range(args.profile_iters):
+        f, b = step(profile=True)
+        fs += np.array(f["stage_ms"])
+        bs += np.array(b["stage_ms"])
+    fs /= args.profile_iters
+    bs /= args.profile_iters
+    stages = {"fwd_" + n: round(float(v) * 1e3, 2) for n, v in zip(ssm.FWD_STAGE_NAMES, fs)}
+    stages.update({"bwd_" + n: round(float(v) * 1e3, 2) for n, v in zip(ssm.BWD_STAGE_NAMES, bs)})
+
+    gemm_flops = 2.0 * T * (2 * P) * H                    # every one of the six projections
+    # dominant kernel: the K=T reduction GEMM (both operands row-contiguous), launched twice per step
+    dom_ms = 0.5 * (bs[2] + bs[6])
+    dom_tflops = gemm_flops / (dom_ms * 1e-3) / 1e12
+    gemm_ms = {"project_in": fs[1], "project_out": fs[3], "gx": bs[1], "dC": bs[2], "du": bs[5], "dBbar": bs[6]}
+    roofline = {"kernel": "gemm_f32_kernel<128,128,16,false,false,false> (dC and dBbar partial sums)",
+                "bound": "mfma", "achieved": round(dom_tflops, 2), "peak": PEAK_FP32_MFMA_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(dom_tflops / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": None,
+                "flops_per_launch": gemm_flops, "avg_launch_us": round(float(dom_ms) * 1e3, 2),
+                "all_gemms_tflops": {k: round(gemm_flops / (v * 1e-3) / 1e12, 2) for k, v in gemm_ms.items()}}
+
+    # ---- scan kernels against the HBM roofline: algorithmic bytes = 16 B (forward: read v, write x)
+    # and 24 B (reverse: read gx, read x, write chi) per (token, state)
+    fwd_bytes, rev_bytes = 16.0 * T * P, 24.0 * T * P
+    scan = {"bound": "hbm", "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "fwd_bytes_per_launch": fwd_bytes, "rev_bytes_per_launch": rev_bytes,
+            "in_path_fwd_us": round(float(fs[2]) * 1e3, 2), "in_path_rev_us": round(float(bs[4]) * 1e3, 2),
+            "in_path_fwd_GBs": round(fwd_bytes / (fs[2] * 1e-3) / 1e9, 1),
+            "in_path_rev_GBs": round(rev_bytes / (bs[4] * 1e-3) / 1e9, 1)}
+    scan.update(scan_cold_warm(ssm, torch, d, Bt, L, P, fwd_bytes, rev_bytes))
+    scan["frac"] = round(scan["cold_fwd_GBs"] / PEAK_HBM_GBS, 4)
+
+    result = {
+        "metric": "ssm_scan_fwd_bwd_throughput", "value": round(mtok, 3), "unit": "Mtokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s: Bt=%d L=%d H=%d P=%d fwd+bwd, fp32 I/O, complex64 state, seed %d"
+                               % (w.name, Bt, L, H, P, w.seed), "tokens_per_step": T},
+        "roofline": roofline, "scan_roofline": scan, "stage_us": stages,
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, inp)
+    print(json.dumps(result))
+
+
+def scan_cold_warm(ssm, torch, d, Bt, L, P, fwd_bytes, rev_bytes, iters=40):
+    """Times the two scan kernels alone through the scan-level entry points with HIP events on the
+    launch stream: warm = one buffer set reused, cold = rotating over > 1 GiB of buffers so that
+    neither L2 nor the 256 MB last-level cache holds the data of the next launch."""
+    A_bar, _ = ssm.ssm_discretize(d["Lambda"], None, d["log_delta"])
+    A_bar = A_bar * 0.5      # the same buffer is scanned in place many times: keep the values bounded
+    set_bytes = Bt * L * P * 8
+    nsets = max(2, int((1 << 30) // set_bytes) + 1)
+    vs = [torch.randn((Bt, L, P), dtype=torch.complex64, device="cuda") * 0.05 for _ in range(nsets)]
+    xs = [torch.randn((Bt, L, P), dtype=torch.complex64, device="cuda") * 0.05 for _ in range(min(nsets, 8))]
+    ws_f = ssm.alloc_workspace(Bt, L, 1, P, False)
+    ws_r = ssm.alloc_workspace(Bt, L, 1, P, True)
+
+    def timed(fn, rotate):
+        # clear + scan (+ tiny reduce) are enqueued per call; events bracket a batch of calls
+        for i in range(5):
+            fn(i % nsets if rotate else 0)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(iters):
+            fn((5 + i) % nsets if rotate else 0)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    f = lambda i: ssm.ssm_scan_states(A_bar, vs[i], d["is_first"], d["x0"], want_x_last=False, workspace=ws_f)
+    r = lambda i: ssm.ssm_scan_states_reverse(A_bar, vs[i], xs[i % len(xs)], d["is_first"], d["x0"],
+                                              want_dx0=False, workspace=ws_r)
+    out = {}
+    for name, fn, nbytes in (("fwd", f, fwd_bytes), ("rev", r, rev_bytes)):
+        for mode in ("warm", "cold"):
+            ms = timed(fn, mode == "cold")
+            out["%s_%s_us" % (mode, name)] = round(ms * 1e3, 2)
+            out["%s_%s_GBs" % (mode, name)] = round(nbytes / (ms * 1e-3) / 1e9, 1)
+    out["note"] = ("warm/cold figures time clear+scan launches of the scan-level entry points back to back; "
+                   "in_path figures are single launches between events inside the full pass")
+    return out
+
+
+def cpu_baseline(w, inp):
+    """The float64 oracle (plain C, OpenMP over sequences) on the first sequences of the same batch."""
+    from oracle import ssm_oracle as orc
+    cores = max(1, min(len(os.sched_getaffinity(0)), orc.max_threads()))
+    nseq = min(w.Bt, max(cores, 4))
+    sub = {k: (v[:nseq] if (v is not None and k in ("u", "is_first", "dy", "x0")) else v) for k, v in inp.items()}
+    threads = min(cores, nseq)
+    t0 = time.perf_counter()
+    orc.run_workload(sub, True, nthreads=threads)
+    dt = time.perf_counter() - t0
+    return {"value": round(nseq * w.L / dt / 1e6, 5), "unit": "Mtokens/s", "cores": threads, "kind": "oracle",
+            "seconds": round(dt, 2),
+            "sample": "float64 oracle forward + gradient pass on the first %d of %d sequences of the same batch"
+                      % (nseq, w.Bt)}
+
+
+if __name__ == "__main__":
+    main()
