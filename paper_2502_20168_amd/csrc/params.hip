@@ -151,6 +151,33 @@ __device__ void psi_prime(double zr, double zi, double er, double ei, double &pr
     }
 }
 
+// fixed-order sum of n slabs (stride apart) with four loads in flight
+__device__ __forceinline__ float sum_slabs(const float *base, long stride, int n)
+{
+    float s = 0.f;
+    int i = 0;
+    for (; i + 4 <= n; i += 4) {
+        const float v0 = base[(long)i * stride], v1 = base[(long)(i + 1) * stride];
+        const float v2 = base[(long)(i + 2) * stride], v3 = base[(long)(i + 3) * stride];
+        s = (((s + v0) + v1) + v2) + v3;
+    }
+    for (; i < n; ++i) s += base[(long)i * stride];
+    return s;
+}
+
+// deterministic tree sum of one double pair per thread; result valid in thread 0
+__device__ __forceinline__ void block_sum2(double *red_r, double *red_i, double &r, double &i, int tid)
+{
+    __syncthreads();
+    red_r[tid] = r; red_i[tid] = i;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if (tid < w) { red_r[tid] += red_r[tid + w]; red_i[tid] += red_i[tid + w]; }
+        __syncthreads();
+    }
+    r = red_r[0]; i = red_i[0];
+}
+
 __global__ void __launch_bounds__(256) epilogue_kernel(EpilogueArgs a)
 {
     __shared__ double red_r[256], red_i[256];
@@ -162,11 +189,8 @@ __global__ void __launch_bounds__(256) epilogue_kernel(EpilogueArgs a)
         const float gr = (float)z.gr, gi = (float)z.gi;
         double dgr = 0.0, dgi = 0.0;
         for (int h = tid; h < a.H; h += 256) {
-            float sr = 0.f, si = 0.f;
-            for (int s = 0; s < a.nsplit_B; ++s) {
-                sr += a.dBbar_part[s * PH2 + (long)(2 * p) * a.H + h];
-                si += a.dBbar_part[s * PH2 + (long)(2 * p + 1) * a.H + h];
-            }
+            const float sr = sum_slabs(a.dBbar_part + (long)(2 * p) * a.H + h, PH2, a.nsplit_B);
+            const float si = sum_slabs(a.dBbar_part + (long)(2 * p + 1) * a.H + h, PH2, a.nsplit_B);
             // conj(g) * dBbar
             a.dB[(long)p * a.H + h] = make_float2(gr * sr + gi * si, gr * si - gi * sr);
             const float2 bv = a.B[(long)p * a.H + h];
@@ -174,19 +198,14 @@ __global__ void __launch_bounds__(256) epilogue_kernel(EpilogueArgs a)
             dgr += (double)bv.x * sr + (double)bv.y * si;
             dgi += (double)bv.x * si - (double)bv.y * sr;
         }
-        red_r[tid] = dgr; red_i[tid] = dgi;
-        __syncthreads();
-        for (int w = 128; w > 0; w >>= 1) {
-            if (tid < w) { red_r[tid] += red_r[tid + w]; red_i[tid] += red_i[tid + w]; }
-            __syncthreads();
+        block_sum2(red_r, red_i, dgr, dgi, tid);
+        double ar = 0.0, ai = 0.0;                    // dAbar: partial rows of the reverse scan
+        for (long i = tid; i < a.npart; i += 256) {
+            ar += (double)a.dAbar_part[i * a.P + p].x;
+            ai += (double)a.dAbar_part[i * a.P + p].y;
         }
+        block_sum2(red_r, red_i, ar, ai, tid);
         if (tid == 0) {
-            dgr = red_r[0]; dgi = red_i[0];
-            double ar = 0.0, ai = 0.0;                    // dAbar
-            for (long i = 0; i < a.npart; ++i) {
-                ar += (double)a.dAbar_part[i * a.P + p].x;
-                ai += (double)a.dAbar_part[i * a.P + p].y;
-            }
             const double Lr = a.Lambda[p].x, Li = a.Lambda[p].y, d = z.delta;
             double pr, pi;
             psi_prime(z.zr, z.zi, z.lr, z.li, pr, pi);
@@ -203,15 +222,13 @@ __global__ void __launch_bounds__(256) epilogue_kernel(EpilogueArgs a)
     } else {
         const int h = blk - a.P;
         for (int j = tid; j < 2 * a.P; j += 256) {
-            float s = 0.f;
-            for (int sidx = 0; sidx < a.nsplit_C; ++sidx) s += a.dC_part[sidx * PH2 + (long)h * 2 * a.P + j];
+            const float s = sum_slabs(a.dC_part + (long)h * 2 * a.P + j, PH2, a.nsplit_C);
             reinterpret_cast<float *>(a.dC)[(long)h * 2 * a.P + j] = (j & 1) ? -s : s;
         }
-        if (tid == 0) {
-            float s = 0.f;
-            for (int sl = 0; sl < a.nslab; ++sl) s += a.dD_part[(long)sl * a.H + h];
-            a.dD[h] = s;
-        }
+        double sd = 0.0, unused = 0.0;
+        for (int sl = tid; sl < a.nslab; sl += 256) sd += (double)a.dD_part[(long)sl * a.H + h];
+        block_sum2(red_r, red_i, sd, unused, tid);
+        if (tid == 0) a.dD[h] = (float)sd;
     }
 }
 
