@@ -1,0 +1,510 @@
+// fp32-accurate GEMM on the bf16 matrix cores of gfx950 (three-way operand split).
+//
+//   C[m,n] = sum_k A(m,k) * B(n,k)  (+ diag[n] * E[m,n]),   A, B, C fp32
+//
+// Every fp32 operand value a is split exactly into three bf16 numbers a = a1 + a2 + a3
+// (a1 = trunc_bf16(a), a2 = trunc_bf16(a - a1), a3 = a - a1 - a2; 8 + 8 + 8 mantissa bits).  The
+// product a*b is then accumulated in fp32 from the six partial products whose weight is at
+// least 2^-16 of the leading one (a1b1, a1b2, a2b1, a1b3, a2b2, a3b1); the three dropped ones
+// are below 2^-24 |a||b|, i.e. at the level of one fp32 rounding.  Each partial product of two
+// bf16 numbers is exact in fp32, so the result has fp32-class accuracy, while the six
+// v_mfma_f32_32x32x16_bf16 (32 cycles for 32x32x16 MACs) cost 192 cycles where the fp32 matrix
+// instruction needs 512 cycles for the same 32x32x16 block.
+//
+// The split happens once per staged element, between the global load and the LDS store; LDS
+// holds three bf16 planes per operand as [row][k] (k contiguous, row stride BK+8 halves so that
+// the 16-byte fragment reads of 16 consecutive rows fall into distinct banks).
+#pragma once
+
+#include "gemm_f32_kernel.h"
+
+namespace ssm {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+struct Split4 { bf16x4 p[3]; };
+
+// Exact three-way split of four floats by truncation: a1 = the upper 16 bits of a, a2 = the
+// upper 16 bits of a - a1, a3 = a - a1 - a2 (which has at most 8 significant bits left, so its
+// upper 16 bits hold it exactly).  Only full-rate integer/float VALU operations are used; two
+// bf16 values are packed with one byte permute.
+__device__ __forceinline__ Split4 split3(float4 v)
+{
+    const unsigned x[4] = {__float_as_uint(v.x), __float_as_uint(v.y), __float_as_uint(v.z), __float_as_uint(v.w)};
+    unsigned h[4], m[4], l[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        h[i] = x[i] & 0xffff0000u;
+        const float r1 = __uint_as_float(x[i]) - __uint_as_float(h[i]);
+        m[i] = __float_as_uint(r1) & 0xffff0000u;
+        const float r2 = r1 - __uint_as_float(m[i]);
+        l[i] = __float_as_uint(r2);
+    }
+    // bytes 2,3 of the first source become the low half, bytes 2,3 of the second the high half
+    union { unsigned u[2]; bf16x4 b; } ph, pm, pl;
+    ph.u[0] = __builtin_amdgcn_perm(h[1], h[0], 0x07060302u); ph.u[1] = __builtin_amdgcn_perm(h[3], h[2], 0x07060302u);
+    pm.u[0] = __builtin_amdgcn_perm(m[1], m[0], 0x07060302u); pm.u[1] = __builtin_amdgcn_perm(m[3], m[2], 0x07060302u);
+    pl.u[0] = __builtin_amdgcn_perm(l[1], l[0], 0x07060302u); pl.u[1] = __builtin_amdgcn_perm(l[3], l[2], 0x07060302u);
+    Split4 o;
+    o.p[0] = ph.b; o.p[1] = pm.b; o.p[2] = pl.b;
+    return o;
+}
+
+// Stages one R x BK fp32 operand tile: global -> registers (fp32) -> split -> three LDS planes.
+// k-contiguous source: a thread handles units of 1 row x 4 k.  Row-contiguous source: units of
+// 4 rows x KU k (KU float4 loads, transposed in registers), KU = 4 or 2; neighbouring lanes take
+// neighbouring k blocks of the same rows, so that their LDS writes fall into distinct banks while
+// the lanes that share a k row still read one contiguous 128-byte line.
+template <int R, int BK, bool KC, int NT>
+struct SplitLoader {
+    static constexpr int NV = R * BK / 4 / NT;
+    static_assert(NV >= 1 && NV * NT * 4 == R * BK, "tile must be a multiple of the workgroup's float4 loads");
+    static constexpr int KU = (NV % 4 == 0) ? 4 : 2;
+    static_assert(KC || NV % KU == 0, "row-contiguous operands are staged in 4 x KU blocks");
+    static constexpr int S = BK + 8;              // plane row stride in halves
+    static constexpr int PLANE = R * S;           // halves per plane
+    float4 r[NV];
+
+    template <bool FAST>
+    __device__ __forceinline__ void load(const float *__restrict__ X, long ld, int row0, int rows, int k0,
+                                         int kend, int tid)
+    {
+        if (KC) {
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const int idx = tid + i * NT;
+                const int row = idx / (BK / 4), kq = idx % (BK / 4);
+                const long gr = row0 + row;
+                const int k = k0 + 4 * kq;
+                if (FAST) {
+                    r[i] = *reinterpret_cast<const float4 *>(X + gr * ld + k);
+                } else {
+                    float t[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) t[j] = (gr < rows && k + j < kend) ? X[gr * ld + k + j] : 0.f;
+                    r[i] = make_float4(t[0], t[1], t[2], t[3]);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < NV / KU; ++u) {
+                const int idx = tid + u * NT;
+                const int kq = idx % (BK / KU), rq = idx / (BK / KU);
+                const long gr = row0 + 4 * rq;
+#pragma unroll
+                for (int j = 0; j < KU; ++j) {
+                    const long k = k0 + KU * kq + j;
+                    if (FAST) {
+                        r[KU * u + j] = *reinterpret_cast<const float4 *>(X + k * ld + gr);
+                    } else {
+                        float t[4];
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) t[q] = (gr + q < rows && k < kend) ? X[k * ld + gr + q] : 0.f;
+                        r[KU * u + j] = make_float4(t[0], t[1], t[2], t[3]);
+                    }
+                }
+            }
+        }
+    }
+
+    __device__ __forceinline__ void store(__bf16 *lds, int tid) const
+    {
+        if (KC) {
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const int idx = tid + i * NT;
+                const int row = idx / (BK / 4), kq = idx % (BK / 4);
+                const Split4 sp = split3(r[i]);
+#pragma unroll
+                for (int s = 0; s < 3; ++s)
+                    *reinterpret_cast<bf16x4 *>(lds + s * PLANE + row * S + 4 * kq) = sp.p[s];
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < NV / KU; ++u) {
+                const int idx = tid + u * NT;
+                const int kq = idx % (BK / KU), rq = idx / (BK / KU);
+                // r[KU*u + j] holds rows 4rq..4rq+3 at k = KU*kq + j: transpose the block in registers
+                float blk[4][4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float4 c = (j < KU) ? r[KU * u + (j < KU ? j : 0)] : make_float4(0.f, 0.f, 0.f, 0.f);
+                    blk[0][j] = c.x; blk[1][j] = c.y; blk[2][j] = c.z; blk[3][j] = c.w;
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const Split4 sp = split3(make_float4(blk[q][0], blk[q][1], blk[q][2], blk[q][3]));
+#pragma unroll
+                    for (int s = 0; s < 3; ++s) {
+                        __bf16 *dst = lds + s * PLANE + (4 * rq + q) * S + KU * kq;
+                        if (KU == 4) {
+                            *reinterpret_cast<bf16x4 *>(dst) = sp.p[s];
+                        } else {
+                            bf16x2 two;
+                            two[0] = sp.p[s][0]; two[1] = sp.p[s][1];
+                            *reinterpret_cast<bf16x2 *>(dst) = two;
+                        }
+                    }
+                }
+            }
+        }
+    }
+};
+
+template <int BM, int BN, int BK, int WGM, int WGN, bool AKC, bool BKC, bool EPI, bool FAST>
+__device__ __forceinline__ void gemm_bf16x3_tile(const GemmDev &g, __bf16 *As, __bf16 *Bs, int m0, int n0,
+                                                 int z, int kbeg, int kend)
+{
+    constexpr int NT = 64 * WGM * WGN;
+    using LA = SplitLoader<BM, BK, AKC, NT>;
+    using LB = SplitLoader<BN, BK, BKC, NT>;
+    constexpr int S = BK + 8;
+    constexpr int STAGE_A = 3 * LA::PLANE, STAGE_B = 3 * LB::PLANE;
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int MI = WM / 32, NI = WN / 32;
+    static_assert(MI >= 1 && NI >= 1 && WM % 32 == 0 && WN % 32 == 0 && BK % 16 == 0, "bad tile");
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, l = tid & 63;
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int li = l & 31, hh = l >> 5;
+
+    LA la;
+    LB lb;
+    v16f acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    const int nk = (kend > kbeg) ? (kend - kbeg + BK - 1) / BK : 0;
+    if (nk > 0) {
+        la.template load<FAST>(g.A, g.lda, m0, g.M, kbeg, kend, tid);
+        lb.template load<FAST>(g.B, g.ldb, n0, g.N, kbeg, kend, tid);
+        la.store(As, tid);
+        lb.store(Bs, tid);
+    }
+    __syncthreads();
+
+    for (int kt = 0; kt < nk; ++kt) {
+        const int cur = kt & 1;
+        if (kt + 1 < nk) {
+            la.template load<FAST>(g.A, g.lda, m0, g.M, kbeg + (kt + 1) * BK, kend, tid);
+            lb.template load<FAST>(g.B, g.ldb, n0, g.N, kbeg + (kt + 1) * BK, kend, tid);
+        }
+        // lane (li, hh) of a 32x32x16 bf16 MFMA holds row/column li, k = 8*hh .. 8*hh+7
+        const __bf16 *as = As + cur * STAGE_A + (wm * WM + li) * S + 8 * hh;
+        const __bf16 *bs = Bs + cur * STAGE_B + (wn * WN + li) * S + 8 * hh;
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 a[MI][3], b[NI][3];
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int s = 0; s < 3; ++s)
+                    a[i][s] = *reinterpret_cast<const bf16x8 *>(as + s * LA::PLANE + i * 32 * S + ks * 16);
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int s = 0; s < 3; ++s)
+                    b[j][s] = *reinterpret_cast<const bf16x8 *>(bs + s * LB::PLANE + j * 32 * S + ks * 16);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    v16f c = acc[i][j];
+                    // small partial products first
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][2], b[j][0], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][1], b[j][1], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][0], b[j][2], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][1], b[j][0], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][0], b[j][1], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][0], b[j][0], c, 0, 0, 0);
+                    acc[i][j] = c;
+                }
+        }
+        if (kt + 1 < nk) {
+            la.store(As + (cur ^ 1) * STAGE_A, tid);
+            lb.store(Bs + (cur ^ 1) * STAGE_B, tid);
+        }
+        __syncthreads();
+    }
+
+    float *Cz = g.C + (long)z * g.M * g.ldc;
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int col = n0 + wn * WN + j * 32 + li;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const long row = m0 + wm * WM + i * 32 + 8 * (r / 4) + 4 * hh + (r % 4);
+                if (FAST || (row < g.M && col < g.N)) {
+                    float v = acc[i][j][r];
+                    if (EPI) v += g.diag[col] * g.E[row * g.lde + col];
+                    Cz[row * g.ldc + col] = v;
+                }
+            }
+        }
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, bool AKC, bool BKC, bool EPI>
+__global__ void __launch_bounds__(64 * WGM * WGN) gemm_bf16x3_kernel(GemmDev g)
+{
+    constexpr int STAGE_A = 3 * BM * (BK + 8), STAGE_B = 3 * BN * (BK + 8);
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    __bf16 *As = reinterpret_cast<__bf16 *>(smem_raw);
+    __bf16 *Bs = As + 2 * STAGE_A;
+    (void)STAGE_B;
+
+    const int id = blockIdx.x;
+    const int tile = (id % 8) * g.per_xcd + id / 8;
+    if (tile >= g.ntm * g.ntn) return;
+    const int tm = tile / g.ntn, tn = tile % g.ntn;
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int z = blockIdx.y;
+    const int kbeg = z * g.kper;
+    const int kend = min(g.K, kbeg + g.kper);
+
+    const bool fast = (g.lda % 4 == 0) && ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0) &&
+                      (g.ldb % 4 == 0) && ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0) &&
+                      (m0 + BM <= g.M) && (n0 + BN <= g.N) && ((kend - kbeg) % BK == 0);
+    if (fast)
+        gemm_bf16x3_tile<BM, BN, BK, WGM, WGN, AKC, BKC, EPI, true>(g, As, Bs, m0, n0, z, kbeg, kend);
+    else
+        gemm_bf16x3_tile<BM, BN, BK, WGM, WGN, AKC, BKC, EPI, false>(g, As, Bs, m0, n0, z, kbeg, kend);
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, bool AKC, bool BKC, bool EPI>
+hipError_t launch_gemm_bf16x3_variant(const GemmArgs &a, hipStream_t s)
+{
+    GemmDev g;
+    g.A = a.A; g.lda = a.lda; g.B = a.B; g.ldb = a.ldb; g.C = a.C; g.ldc = a.ldc;
+    g.diag = a.diag; g.E = a.E; g.lde = a.lde;
+    g.M = a.M; g.N = a.N; g.K = a.K;
+    const int splits = a.splits < 1 ? 1 : a.splits;
+    int kper = (a.K + splits - 1) / splits;
+    kper = (kper + BK - 1) / BK * BK;
+    g.kper = kper;
+    g.ntm = (a.M + BM - 1) / BM;
+    g.ntn = (a.N + BN - 1) / BN;
+    const long ntiles = (long)g.ntm * g.ntn;
+    g.per_xcd = (int)((ntiles + 7) / 8);
+    constexpr size_t smem = (size_t)2 * 3 * (BM + BN) * (BK + 8) * sizeof(__bf16);
+    static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS of a gfx950 CU");
+    auto kern = gemm_bf16x3_kernel<BM, BN, BK, WGM, WGN, AKC, BKC, EPI>;
+    if (smem > 64 * 1024) {
+        // raising the dynamic LDS limit is idempotent; doing it once per instantiation is enough
+        static bool raised = false;
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+    }
+    dim3 grid((unsigned)(g.per_xcd * 8), (unsigned)splits, 1);
+    hipLaunchKernelGGL(kern, grid, dim3(64 * WGM * WGN), smem, s, g);
+    return hipGetLastError();
+}
+
+
+// ---------------------------------------------------------------------------------------------
+// Wavefront-specialised variant: a workgroup has WGM*WGN consumer wavefronts that only read
+// operand fragments from LDS and issue MFMAs, and NP producer wavefronts that only stage tiles
+// (global load -> three-way split -> LDS).  A producer and a consumer share each SIMD, so the
+// VALU work of the split co-executes with the matrix instructions of the other wavefront.
+// LDS holds NS stages; in iteration kt the producers fill the stage of tile kt+NS-1 while the
+// consumers work on tile kt, with one workgroup barrier per K tile.
+// ---------------------------------------------------------------------------------------------
+template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, bool AKC, bool BKC, bool EPI, bool FAST>
+__device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *smem, int m0, int n0, int z,
+                                                    int kbeg, int kend)
+{
+    constexpr int NC = WGM * WGN;                 // consumer wavefronts
+    constexpr int PT = 64 * NP;                   // producer threads
+    using LA = SplitLoader<BM, BK, AKC, PT>;
+    using LB = SplitLoader<BN, BK, BKC, PT>;
+    constexpr int S = BK + 8;
+    constexpr int STAGE_A = 3 * LA::PLANE, STAGE_B = 3 * LB::PLANE, STAGE = STAGE_A + STAGE_B;
+    constexpr int WM = BM / WGM, WN = BN / WGN;
+    constexpr int MI = WM / 32, NI = WN / 32;
+    static_assert(MI >= 1 && NI >= 1 && WM % 32 == 0 && WN % 32 == 0 && BK % 16 == 0 && NS >= 2, "bad tile");
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6;
+    const int nk = (kend > kbeg) ? (kend - kbeg + BK - 1) / BK : 0;
+
+    if (wave >= NC) {
+        // ------------------------------------------------------------------ producers
+        // Two register sets: while tile t is split and stored, the loads of tiles t+1 and t+2
+        // are in flight, which covers the global latency with two K tiles of matrix work.
+        const int ptid = tid - 64 * NC;
+        LA la[2];
+        LB lb[2];
+        auto fetch = [&](int set, int t) {
+            la[set].template load<FAST>(g.A, g.lda, m0, g.M, kbeg + t * BK, kend, ptid);
+            lb[set].template load<FAST>(g.B, g.ldb, n0, g.N, kbeg + t * BK, kend, ptid);
+        };
+        auto stash = [&](int set, int t) {
+            __bf16 *st = smem + (t % NS) * STAGE;
+            la[set].store(st, ptid);
+            lb[set].store(st + STAGE_A, ptid);
+        };
+        // prologue: tiles 0 .. NS-2 into their stages (NS - 1 is 1 or 2 or 3; sets alternate)
+        if (0 < nk) fetch(0, 0);
+        if (1 < nk) fetch(1, 1);
+#pragma unroll
+        for (int t = 0; t < NS - 1; ++t) {
+            if (t < nk) {
+                stash(t & 1, t);
+                if (t + 2 < nk) fetch(t & 1, t + 2);
+            }
+        }
+        __syncthreads();
+        // steady state: iteration kt stages tile t = kt + NS - 1 from register set t & 1
+        int kt = 0;
+        for (; kt + 1 < nk; kt += 2) {
+            {
+                const int t = kt + NS - 1;
+                if (t < nk) { stash((NS - 1) & 1, t); if (t + 2 < nk) fetch((NS - 1) & 1, t + 2); }
+            }
+            __syncthreads();
+            {
+                const int t = kt + NS;
+                if (t < nk) { stash(NS & 1, t); if (t + 2 < nk) fetch(NS & 1, t + 2); }
+            }
+            __syncthreads();
+        }
+        if (kt < nk) {
+            const int t = kt + NS - 1;
+            if (t < nk) stash((NS - 1) & 1, t);
+            __syncthreads();
+        }
+        return;
+    }
+
+    // ---------------------------------------------------------------------- consumers
+    const int l = tid & 63;
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int li = l & 31, hh = l >> 5;
+    v16f acc[MI][NI];
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+        const __bf16 *st = smem + (kt % NS) * STAGE;
+        const __bf16 *as = st + (wm * WM + li) * S + 8 * hh;
+        const __bf16 *bs = st + STAGE_A + (wn * WN + li) * S + 8 * hh;
+#pragma unroll
+        for (int ks = 0; ks < BK / 16; ++ks) {
+            bf16x8 a[MI][3], b[NI][3];
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int s = 0; s < 3; ++s)
+                    a[i][s] = *reinterpret_cast<const bf16x8 *>(as + s * LA::PLANE + i * 32 * S + ks * 16);
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int s = 0; s < 3; ++s)
+                    b[j][s] = *reinterpret_cast<const bf16x8 *>(bs + s * LB::PLANE + j * 32 * S + ks * 16);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j) {
+                    v16f c = acc[i][j];
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][2], b[j][0], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][1], b[j][1], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][0], b[j][2], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][1], b[j][0], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][0], b[j][1], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][0], b[j][0], c, 0, 0, 0);
+                    acc[i][j] = c;
+                }
+        }
+        __syncthreads();
+    }
+
+    float *Cz = g.C + (long)z * g.M * g.ldc;
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+            const int col = n0 + wn * WN + j * 32 + li;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const long row = m0 + wm * WM + i * 32 + 8 * (r / 4) + 4 * hh + (r % 4);
+                if (FAST || (row < g.M && col < g.N)) {
+                    float v = acc[i][j][r];
+                    if (EPI) v += g.diag[col] * g.E[row * g.lde + col];
+                    Cz[row * g.ldc + col] = v;
+                }
+            }
+        }
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, bool AKC, bool BKC, bool EPI>
+__global__ void __launch_bounds__(64 * (WGM * WGN + NP)) gemm_bf16x3_ws_kernel(GemmDev g)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);
+    const int id = blockIdx.x;
+    const int tile = (id % 8) * g.per_xcd + id / 8;
+    if (tile >= g.ntm * g.ntn) return;
+    const int tm = tile / g.ntn, tn = tile % g.ntn;
+    const int m0 = tm * BM, n0 = tn * BN;
+    const int z = blockIdx.y;
+    const int kbeg = z * g.kper;
+    const int kend = min(g.K, kbeg + g.kper);
+    const bool fast = (g.lda % 4 == 0) && ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0) &&
+                      (g.ldb % 4 == 0) && ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0) &&
+                      (m0 + BM <= g.M) && (n0 + BN <= g.N) && ((kend - kbeg) % BK == 0);
+    if (fast)
+        gemm_bf16x3_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, AKC, BKC, EPI, true>(g, smem, m0, n0, z, kbeg, kend);
+    else
+        gemm_bf16x3_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, AKC, BKC, EPI, false>(g, smem, m0, n0, z, kbeg, kend);
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, bool AKC, bool BKC, bool EPI>
+hipError_t launch_gemm_bf16x3_ws_variant(const GemmArgs &a, hipStream_t s)
+{
+    GemmDev g;
+    g.A = a.A; g.lda = a.lda; g.B = a.B; g.ldb = a.ldb; g.C = a.C; g.ldc = a.ldc;
+    g.diag = a.diag; g.E = a.E; g.lde = a.lde;
+    g.M = a.M; g.N = a.N; g.K = a.K;
+    const int splits = a.splits < 1 ? 1 : a.splits;
+    int kper = (a.K + splits - 1) / splits;
+    kper = (kper + BK - 1) / BK * BK;
+    g.kper = kper;
+    g.ntm = (a.M + BM - 1) / BM;
+    g.ntn = (a.N + BN - 1) / BN;
+    const long ntiles = (long)g.ntm * g.ntn;
+    g.per_xcd = (int)((ntiles + 7) / 8);
+    constexpr size_t smem = (size_t)NS * 3 * (BM + BN) * (BK + 8) * sizeof(__bf16);
+    static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS of a gfx950 CU");
+    auto kern = gemm_bf16x3_ws_kernel<BM, BN, BK, WGM, WGN, NP, NS, AKC, BKC, EPI>;
+    if (smem > 64 * 1024) {
+        static bool raised = false;
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+    }
+    dim3 grid((unsigned)(g.per_xcd * 8), (unsigned)splits, 1);
+    hipLaunchKernelGGL(kern, grid, dim3(64 * (WGM * WGN + NP)), smem, s, g);
+    return hipGetLastError();
+}
+
+}  // namespace ssm

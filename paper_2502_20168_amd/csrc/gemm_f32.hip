@@ -1,5 +1,13 @@
-// Tile selection and launch of the fp32 MFMA GEMM (kernel template in gemm_f32_kernel.h).
-#include "gemm_f32_kernel.h"
+// Tile selection and launch of the projection GEMMs.
+//
+// Two kernels compute the same fp32-in / fp32-out product:
+//   * gemm_bf16x3_ws_kernel (default): exact three-way bf16 split of both operands, six bf16
+//     MFMAs per k block accumulated in fp32 -- fp32-class accuracy at 2.7x the fp32 matrix rate;
+//   * gemm_f32_kernel: plain fp32 MFMA, selected with the environment variable SSM_GEMM_F32=1
+//     (kept as the reference point for the measurement of the default kernel).
+#include "gemm_bf16x3_kernel.h"
+
+#include <cstdlib>
 
 namespace ssm {
 
@@ -17,7 +25,7 @@ int gemm_pick_splits(int64_t M, int64_t N, int64_t K)
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN>
-static hipError_t dispatch_layout(const GemmArgs &a, hipStream_t s)
+static hipError_t dispatch_f32(const GemmArgs &a, hipStream_t s)
 {
     const bool epi = a.diag != nullptr;
     if (a.a_kcontig && a.b_kcontig)
@@ -31,20 +39,47 @@ static hipError_t dispatch_layout(const GemmArgs &a, hipStream_t s)
     return hipErrorInvalidValue;
 }
 
+template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS>
+static hipError_t dispatch_bf16x3(const GemmArgs &a, hipStream_t s)
+{
+    const bool epi = a.diag != nullptr;
+    if (a.a_kcontig && a.b_kcontig)
+        return epi ? launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, true, true, true>(a, s)
+                   : launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, true, true, false>(a, s);
+    if (a.a_kcontig && !a.b_kcontig)
+        return epi ? launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, true, false, true>(a, s)
+                   : launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, true, false, false>(a, s);
+    if (!a.a_kcontig && !a.b_kcontig && !epi)
+        return launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, false, false, false>(a, s);
+    return hipErrorInvalidValue;
+}
+
+static bool use_f32_mfma()
+{
+    const char *e = std::getenv("SSM_GEMM_F32");
+    return e && e[0] == '1';
+}
+
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
 {
     if (a.M <= 0 || a.N <= 0 || a.K <= 0) return hipErrorInvalidValue;
     if (a.splits > 1 && a.diag) return hipErrorInvalidValue;
-    // Measured on MI355X at the benchmark shapes: 128x128 tiles with 8 wavefronts are best when
-    // they give at least one workgroup per CU; otherwise 64x64 tiles (several workgroups per CU).
     const long splits = a.splits < 1 ? 1 : a.splits;
     const long tiles128 = (long)((a.M + 127) / 128) * ((a.N + 127) / 128) * splits;
-    if (tiles128 >= 256) {
-        if (a.a_kcontig && a.b_kcontig) return dispatch_layout<128, 128, 32, 4, 2>(a, s);
-        return dispatch_layout<128, 128, 16, 4, 2>(a, s);
+    if (use_f32_mfma()) {
+        // measured on MI355X: 128x128 tiles with 8 wavefronts when they give every CU a workgroup,
+        // 64x64 tiles otherwise
+        if (tiles128 >= 256) {
+            if (a.a_kcontig && a.b_kcontig) return dispatch_f32<128, 128, 32, 4, 2>(a, s);
+            return dispatch_f32<128, 128, 16, 4, 2>(a, s);
+        }
+        if (a.a_kcontig && a.b_kcontig) return dispatch_f32<64, 64, 32, 2, 2>(a, s);
+        return dispatch_f32<64, 64, 16, 2, 2>(a, s);
     }
-    if (a.a_kcontig && a.b_kcontig) return dispatch_layout<64, 64, 32, 2, 2>(a, s);
-    return dispatch_layout<64, 64, 16, 2, 2>(a, s);
+    // measured on MI355X at the benchmark shapes: 128x128x32 tiles, 4 consumer + 4 producer
+    // wavefronts; 128x64 tiles when the wide tile would leave CUs without work
+    if (tiles128 >= 200) return dispatch_bf16x3<128, 128, 32, 2, 2, 4, 2>(a, s);
+    return dispatch_bf16x3<128, 64, 32, 4, 1, 4, 2>(a, s);
 }
 
 }  // namespace ssm
