@@ -27,6 +27,9 @@
  *     and need not be initialised or preserved between calls.
  *   - Gradient of the real loss l w.r.t. a complex quantity q is returned as
  *     dl/dRe(q) + i dl/dIm(q).
+ *   - Two environment variables are read at call time: SSM_GEMM_F32=1 runs the projections on
+ *     the fp32 matrix instruction instead of the (equally accurate, faster) three-way bf16 split;
+ *     SSM_SPIN_LIMIT=<n> bounds the polls of a cross-workgroup wait in the scan (default 2^20).
  */
 #ifndef SSM_H_
 #define SSM_H_
@@ -55,7 +58,7 @@ typedef enum {
 
 /* Number of per-stage timings written by the *_profiled calls (see below). */
 #define SSM_FWD_STAGES 4
-#define SSM_BWD_STAGES 8
+#define SSM_BWD_STAGES 7
 
 /* Static description of an error code. Never NULL. */
 const char *ssm_strerror(int status);
@@ -135,8 +138,8 @@ ssm_status ssm_scan_states_reverse(const ssm_c64 *A_bar, ssm_c64 *gx, const ssm_
  * on `stream` around every kernel.  They wait for the stream before returning and write the
  * milliseconds of each stage to the HOST array stage_ms:
  *   forward : [0] discretise+pack, [1] input projection, [2] scan, [3] output projection
- *   backward: [0] discretise+pack, [1] gx = C^H dy, [2] dC partials, [3] dD partials,
- *             [4] reverse scan, [5] du, [6] dBbar partials, [7] parameter epilogue               */
+ *   backward: [0] discretise+pack and dD partials, [1] gx = C^H dy, [2] dC partials,
+ *             [3] reverse scan, [4] du, [5] dBbar partials, [6] parameter epilogue               */
 ssm_status ssm_scan_fwd_profiled(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C,
                                  const float *D, const float *log_delta, const float *u,
                                  const uint8_t *is_first, const ssm_c64 *x0,

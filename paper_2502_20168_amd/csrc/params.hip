@@ -42,8 +42,38 @@ __device__ Zoh zoh_discretize(float2 Lambda, float log_delta)
     return o;
 }
 
+// ---------------------------------------------------------------------------------------------
+// partial[s][h] = sum_{t in slab s} a[t,h] * b[t,h]      (dD = sum_t dy_t (.) u_t)
+// workgroup = 64 columns x 4 row phases
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void coldot_block(const ColDotArgs &a, int colblock, int slab)
+{
+    __shared__ float red[256];
+    const int tid = threadIdx.x;
+    const int col = colblock * 64 + (tid & 63), ph = tid >> 6;
+    const long rows_per = (a.T + a.nslab - 1) / a.nslab;
+    const long r0 = slab * rows_per, r1 = min((long)a.T, r0 + rows_per);
+    float s = 0.f;
+    if (col < a.H) {
+        long t = r0 + ph;
+        for (; t + 12 < r1; t += 16) {           // four independent row pairs in flight
+            const float a0 = a.a[t * a.H + col], b0 = a.b[t * a.H + col];
+            const float a1 = a.a[(t + 4) * a.H + col], b1 = a.b[(t + 4) * a.H + col];
+            const float a2 = a.a[(t + 8) * a.H + col], b2 = a.b[(t + 8) * a.H + col];
+            const float a3 = a.a[(t + 12) * a.H + col], b3 = a.b[(t + 12) * a.H + col];
+            s = fmaf(a0, b0, s); s = fmaf(a1, b1, s); s = fmaf(a2, b2, s); s = fmaf(a3, b3, s);
+        }
+        for (; t < r1; t += 4) s = fmaf(a.a[t * a.H + col], a.b[t * a.H + col], s);
+    }
+    red[tid] = s;
+    __syncthreads();
+    if (ph == 0 && col < a.H)
+        a.partial[(long)slab * a.H + col] = (red[tid] + red[tid + 64]) + (red[tid + 128] + red[tid + 192]);
+}
+
 // Workgroups [0, P): state p -> Abar_p, packed Bbar rows 2p, 2p+1 (and the interleaved complex
-// Bbar when asked).  Workgroups [P, P+H): row h of C -> (Re, -Im) interleaved.
+// Bbar when asked).  Workgroups [P, P+H): row h of C -> (Re, -Im) interleaved.  Further workgroups
+// (gradient pass only): the column-dot slabs behind dD.
 __global__ void __launch_bounds__(256) prep_kernel(PrepArgs a)
 {
     const int blk = blockIdx.x, tid = threadIdx.x;
@@ -66,7 +96,7 @@ __global__ void __launch_bounds__(256) prep_kernel(PrepArgs a)
                 if (a.Bbar_c64) a.Bbar_c64[(long)p * a.H + h] = make_float2(re, im);
             }
         }
-    } else if (a.Cc) {
+    } else if (blk < a.P + a.H) {
         const int h = blk - a.P;
         const float2 *src = a.C + (long)h * a.P;
         float2 *dst = reinterpret_cast<float2 *>(a.Cc) + (long)h * a.P;
@@ -74,35 +104,25 @@ __global__ void __launch_bounds__(256) prep_kernel(PrepArgs a)
             const float2 c = src[p];
             dst[p] = make_float2(c.x, -c.y);
         }
+    } else {
+        // column-dot slabs of the gradient pass share this launch (they depend on nothing here)
+        const int cb = blk - (a.P + a.H);
+        coldot_block(a.cd, cb % a.cd_colblocks, cb / a.cd_colblocks);
     }
 }
 
-hipError_t launch_prep(const PrepArgs &a, hipStream_t s)
+hipError_t launch_prep(const PrepArgs &a_in, hipStream_t s)
 {
-    const unsigned blocks = (unsigned)(a.P + (a.Cc ? a.H : 0));
+    PrepArgs a = a_in;
+    a.cd_colblocks = 0;
+    unsigned blocks = (unsigned)(a.P + (a.Cc ? a.H : 0));
+    if (a.cd.partial) {
+        if (!a.Cc) return hipErrorInvalidValue;       // block ranges assume the C rows are present
+        a.cd_colblocks = (a.cd.H + 63) / 64;
+        blocks += (unsigned)(a.cd_colblocks * a.cd.nslab);
+    }
     hipLaunchKernelGGL(prep_kernel, dim3(blocks), dim3(256), 0, s, a);
     return hipGetLastError();
-}
-
-// ---------------------------------------------------------------------------------------------
-// partial[s][h] = sum_{t in slab s} a[t,h] * b[t,h]      (dD = sum_t dy_t (.) u_t)
-// workgroup = 64 columns x 4 row phases
-// ---------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) coldot_kernel(ColDotArgs a)
-{
-    __shared__ float red[256];
-    const int tid = threadIdx.x;
-    const int col = blockIdx.x * 64 + (tid & 63), ph = tid >> 6;
-    const int slab = blockIdx.y;
-    const long rows_per = (a.T + a.nslab - 1) / a.nslab;
-    const long r0 = slab * rows_per, r1 = min((long)a.T, r0 + rows_per);
-    float s = 0.f;
-    if (col < a.H)
-        for (long t = r0 + ph; t < r1; t += 4) s = fmaf(a.a[t * a.H + col], a.b[t * a.H + col], s);
-    red[tid] = s;
-    __syncthreads();
-    if (ph == 0 && col < a.H)
-        a.partial[(long)slab * a.H + col] = (red[tid] + red[tid + 64]) + (red[tid + 128] + red[tid + 192]);
 }
 
 int coldot_slabs(int64_t T)
@@ -111,12 +131,6 @@ int coldot_slabs(int64_t T)
     if (n > 64) n = 64;
     if (n < 1) n = 1;
     return (int)n;
-}
-
-hipError_t launch_coldot(const ColDotArgs &a, hipStream_t s)
-{
-    hipLaunchKernelGGL(coldot_kernel, dim3((unsigned)((a.H + 63) / 64), (unsigned)a.nslab), dim3(256), 0, s, a);
-    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -151,11 +165,18 @@ __device__ void psi_prime(double zr, double zi, double er, double ei, double &pr
     }
 }
 
-// fixed-order sum of n slabs (stride apart) with four loads in flight
+// fixed-order sum of n slabs (stride apart) with up to eight loads in flight
 __device__ __forceinline__ float sum_slabs(const float *base, long stride, int n)
 {
     float s = 0.f;
     int i = 0;
+    for (; i + 8 <= n; i += 8) {
+        float v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = base[(long)(i + j) * stride];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s += v[j];
+    }
     for (; i + 4 <= n; i += 4) {
         const float v0 = base[(long)i * stride], v1 = base[(long)(i + 1) * stride];
         const float v2 = base[(long)(i + 2) * stride], v3 = base[(long)(i + 3) * stride];

@@ -80,38 +80,51 @@ __global__ void __launch_bounds__(SCAN_THREADS) scan_kernel(ScanArgs a)
     // logical step s <-> time t: forward t = s, reverse t = L-1-s
     float2 val[E];
     float2 xp[REV ? E : 1];
-    unsigned rmask = 0;   // bit e: the incoming state of logical step s0+e is dropped
-    unsigned mmask = 0;   // reverse only, bit e: is_first at the time of logical step s0+e
 #pragma unroll
     for (int e = 0; e < E; ++e) {
         val[e] = make_float2(0.f, 0.f);
         if constexpr (REV) xp[e] = make_float2(0.f, 0.f);
-        if (e < len) {
+        if (e < len && active) {
             const int s = s0 + e;
             const int t = REV ? (L - 1 - s) : s;
-            if (active) {
-                val[e] = a.in[(rowbase + t) * a.P + p];
-                if constexpr (REV) {
-                    if (t > 0) xp[e] = a.xsaved[(rowbase + t - 1) * a.P + p];
-                    else if (a.x0) xp[e] = a.x0[(long)b * a.P + p];
-                }
-            }
-            if (a.is_first) {
-                const unsigned f = a.is_first[rowbase + t] != 0;
-                if (REV) {
-                    mmask |= f << e;
-                    // the flag that cuts chi_{t+1} -> chi_t is is_first[t+1], i.e. the flag of
-                    // the previous logical step
-                    if (e + 1 < E) rmask |= f << (e + 1);
-                } else {
-                    rmask |= f << e;
-                }
+            val[e] = a.in[(rowbase + t) * a.P + p];
+            if constexpr (REV) {
+                if (t > 0) xp[e] = a.xsaved[(rowbase + t - 1) * a.P + p];
+                else if (a.x0) xp[e] = a.x0[(long)b * a.P + p];
             }
         }
     }
-    if (REV && a.is_first && len > 0 && s0 > 0) {
-        // flag of logical step s0-1 (time L-s0) cuts the carry into this thread's first step
-        rmask |= (unsigned)(a.is_first[rowbase + (L - s0)] != 0);
+
+    // flags of the thread's steps as a bit mask (bit e = is_first at the time of logical step s0+e)
+    unsigned fmask = 0;
+    if (a.is_first && len > 0) {
+        const int tlo = REV ? (L - s0 - len) : s0;             // lowest time index of the chunk
+        const uint8_t *fp = a.is_first + rowbase + tlo;
+        if (len == E && (reinterpret_cast<uintptr_t>(fp) & 15) == 0) {
+            const uint4 w = *reinterpret_cast<const uint4 *>(fp);
+            const unsigned ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const unsigned f = ((ww[j >> 2] >> (8 * (j & 3))) & 0xffu) != 0;
+                fmask |= f << (REV ? (E - 1 - j) : j);
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < E; ++e)
+                if (e < len) {
+                    const int t = REV ? (L - 1 - (s0 + e)) : (s0 + e);
+                    fmask |= (unsigned)(a.is_first[rowbase + t] != 0) << e;
+                }
+        }
+    }
+    // rmask bit e: the incoming state of logical step s0+e is dropped.
+    // forward: the step's own flag.  reverse: the flag that cuts chi_{t+1} -> chi_t is
+    // is_first[t+1], i.e. the flag of the previous logical step.
+    unsigned rmask = fmask;
+    const unsigned mmask = fmask;                               // reverse only: is_first at the step itself
+    if (REV) {
+        rmask = fmask << 1;
+        if (a.is_first && len > 0 && s0 > 0) rmask |= (unsigned)(a.is_first[rowbase + (L - s0)] != 0);
     }
 
     // ---- level 1, first pass: aggregate of the thread's steps for zero incoming state

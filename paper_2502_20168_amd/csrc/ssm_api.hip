@@ -203,6 +203,8 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     pa.C = reinterpret_cast<const float2 *>(C); pa.log_delta = log_delta;
     pa.P = (int)P; pa.H = (int)H; pa.lam_bar = lam; pa.Bbar_ri = Bri; pa.Cc = Cc; pa.Bbar_c64 = nullptr;
     pa.hdr = lo.plan.nTB > 1 ? nullptr : hdr;
+    // dD slabs: sum_t dy[t,h] u[t,h] over row slabs, in the same launch
+    pa.cd.a = dy; pa.cd.b = u; pa.cd.T = T; pa.cd.H = (int)H; pa.cd.nslab = lo.nslab; pa.cd.partial = dDpart;
     HIP_TRY(launch_prep(pa, s));
     MARK();
 
@@ -222,11 +224,6 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     g4.C = dCpart; g4.ldc = 2 * P;
     g4.M = (int)H; g4.N = (int)(2 * P); g4.K = T; g4.splits = lo.splitC;
     HIP_TRY(launch_gemm(g4, s));
-    MARK();
-
-    ColDotArgs cd{};
-    cd.a = dy; cd.b = u; cd.T = T; cd.H = (int)H; cd.nslab = lo.nslab; cd.partial = dDpart;
-    HIP_TRY(launch_coldot(cd, s));
     MARK();
 
     ScanArgs sa{};

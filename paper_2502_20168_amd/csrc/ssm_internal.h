@@ -80,6 +80,11 @@ hipError_t launch_reduce_partials(const float2 *partial, int64_t n, int64_t P, f
 // ---------------------------------------------------------------------------------------------
 // Parameter-sized kernels
 // ---------------------------------------------------------------------------------------------
+struct ColDotArgs {          // partial[s][h] = sum over the rows of slab s of a[t,h] * b[t,h]
+    const float *a; const float *b; int64_t T; int H; int nslab; float *partial;
+};
+int coldot_slabs(int64_t T);
+
 struct PrepArgs {
     const float2 *Lambda; const float2 *B; const float2 *C; const float *log_delta;
     int P, H;
@@ -88,14 +93,12 @@ struct PrepArgs {
     float *Cc;               // [H, 2P]: (Re C[h,p], -Im C[h,p]) interleaved; may be null
     float2 *Bbar_c64;        // [P, H] interleaved complex, for ssm_discretize; may be null
     WsHeader *hdr;           // cleared when non-null
+    ColDotArgs cd;           // cd.partial non-null: the launch also computes the column-dot slabs
+    int cd_colblocks;        // set by launch_prep
 };
 hipError_t launch_prep(const PrepArgs &a, hipStream_t s);
 
-struct ColDotArgs {          // partial[s][h] = sum over the rows of slab s of a[t,h] * b[t,h]
-    const float *a; const float *b; int64_t T; int H; int nslab; float *partial;
-};
-hipError_t launch_coldot(const ColDotArgs &a, hipStream_t s);
-int coldot_slabs(int64_t T);
+
 
 struct EpilogueArgs {
     const float2 *Lambda; const float2 *B; const float *log_delta; int P, H;
