@@ -78,7 +78,7 @@ __global__ void __launch_bounds__(256) prep_kernel(PrepArgs a)
 {
     const int blk = blockIdx.x, tid = threadIdx.x;
     if (blk == 0 && tid == 0 && a.hdr) {
-        a.hdr->ticket_fwd = 0; a.hdr->ticket_rev = 0; a.hdr->err = 0; a.hdr->magic = 0x53534d31u;
+        a.hdr->err = 0; a.hdr->magic = 0x53534d31u;
     }
     if (blk < a.P) {
         const int p = blk;

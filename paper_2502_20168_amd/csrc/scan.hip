@@ -11,8 +11,10 @@
 //      decoupled look-back: each publishes its own aggregate before it waits for anything, then
 //      fetches the aggregates of the earlier workgroups of its group (one per thread, all in
 //      flight at once) plus the inclusive state that closes the previous group.
-// Logical workgroup ids come from an atomic ticket, so a workgroup only ever waits for
-// workgroups that started before it, and every wait is bounded by spin_limit.
+// Logical time-block ids come from an atomic ticket per chain, so a workgroup only ever waits
+// for workgroups that started before it, and every wait is bounded by spin_limit.
+// Workgroups whose steps carry no flag at all take a guard-free path (plain recurrence, pointer
+// stepping, Abar^16 by squaring): the kernel is issue bound otherwise, not memory bound.
 //
 // The reverse scan runs the same operator over reversed time with conj(Abar):
 //   chi_t = gx_t + [not is_first_{t+1}] conj(Abar) chi_{t+1}
@@ -31,17 +33,53 @@ __device__ __forceinline__ float2 cfma(float2 a, float2 b, float2 c)
     return make_float2(fmaf(a.x, b.x, fmaf(-a.y, b.y, c.x)), fmaf(a.x, b.y, fmaf(a.y, b.x, c.y)));
 }
 
-__device__ __forceinline__ void store_c64_agent(float2 *p, float2 v)
+// Cross-workgroup hand-over without fences: every descriptor word is one 64-bit value that
+// carries a float in its upper half and a tag in its lower half, written and read with relaxed
+// device-scope atomics (write-through / cache-bypassing accesses).  A word whose tag is non-zero
+// is complete by construction, so no ordering between different words is ever needed and no
+// cache write-back or invalidate is paid.
+//   tag 1: aggregate (state for zero incoming state), no reset among the workgroup's steps
+//   tag 2: aggregate, a reset among the steps (the product of the transition is zero)
+//   tag 3: inclusive state
+__device__ __forceinline__ void publish_word(unsigned long long *w, float v, unsigned tag)
 {
-    unsigned long long bits = ((unsigned long long)__float_as_uint(v.y) << 32) | __float_as_uint(v.x);
-    __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), bits, __ATOMIC_RELAXED,
+    __hip_atomic_store(w, ((unsigned long long)__float_as_uint(v) << 32) | tag, __ATOMIC_RELAXED,
                        __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ float2 load_c64_agent(const float2 *p)
+__device__ __forceinline__ unsigned long long poll_word(const unsigned long long *w)
 {
-    unsigned long long bits = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p),
-                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return make_float2(__uint_as_float((unsigned)(bits & 0xffffffffu)), __uint_as_float((unsigned)(bits >> 32)));
+    return __hip_atomic_load(w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float word_value(unsigned long long w) { return __uint_as_float((unsigned)(w >> 32)); }
+__device__ __forceinline__ unsigned word_tag(unsigned long long w) { return (unsigned)(w & 0xffffffffu); }
+
+// Waits (bounded) until both words of a pair carry a tag >= min_tag.  Returns false on give-up.
+__device__ __forceinline__ bool wait_pair(const unsigned long long *w, unsigned min_tag, unsigned spin_limit,
+                                          float2 &value, unsigned &tag)
+{
+    unsigned spins = 0;
+    while (true) {
+        const unsigned long long w0 = poll_word(w), w1 = poll_word(w + 1);
+        if (word_tag(w0) >= min_tag && word_tag(w1) >= min_tag) {
+            value = make_float2(word_value(w0), word_value(w1));
+            tag = word_tag(w0);
+            return true;
+        }
+        if (spins >= spin_limit) return false;
+        ++spins;
+        __builtin_amdgcn_s_sleep(2);
+    }
+}
+
+// Abar^(16 * cy) for cy a power of two, in double so that the power itself adds no error
+__device__ __forceinline__ float2 pow_block(float2 lam, int cy)
+{
+    double r = lam.x, i = lam.y;
+    for (int n = 1; n < SCAN_E * cy; n *= 2) {
+        const double nr = r * r - i * i, ni = 2.0 * r * i;
+        r = nr; i = ni;
+    }
+    return make_float2((float)r, (float)i);
 }
 
 template <bool REV>
@@ -54,9 +92,15 @@ __global__ void __launch_bounds__(SCAN_THREADS) scan_kernel(ScanArgs a)
     __shared__ unsigned s_id;
 
     const int tid = threadIdx.x;
+    const int nchains = a.nPX * a.Bt;
     unsigned id;
     if (a.nTB > 1) {
-        if (tid == 0) s_id = atomicAdd(a.ticket, 1u);
+        // One ticket counter per (sequence, state block) chain: the i-th workgroup of a chain to
+        // start takes time block i, so its predecessors along time have started before it.
+        if (tid == 0) {
+            const unsigned chain = blockIdx.x % nchains;
+            s_id = atomicAdd(a.ticket + (size_t)chain * SCAN_TICKET_STRIDE, 1u) * nchains + chain;
+        }
         __syncthreads();
         id = s_id;
     } else {
@@ -65,7 +109,7 @@ __global__ void __launch_bounds__(SCAN_THREADS) scan_kernel(ScanArgs a)
     // time index slowest: all first-in-time workgroups start before any second-in-time one
     const int px = id % a.nPX;
     const int b = (id / a.nPX) % a.Bt;
-    const int tb = id / (a.nPX * a.Bt);
+    const int tb = id / nchains;
     const int lane = tid % a.pxb, chunk = tid / a.pxb;
     const int p = px * a.pxb + lane;
     const bool active = p < a.P;
@@ -73,6 +117,10 @@ __global__ void __launch_bounds__(SCAN_THREADS) scan_kernel(ScanArgs a)
     const int s0 = (tb * a.cy + chunk) * E;          // first logical step of this thread
     const int len = max(0, min(E, L - s0));
     const long rowbase = (long)b * L;
+    // every thread of the workgroup owns E steps of a valid state: no guards needed
+    const bool full = ((tb + 1) * a.cy * E <= L) && ((px + 1) * a.pxb <= a.P);
+    const long stride = REV ? -(long)a.P : (long)a.P;            // elements between consecutive logical steps
+    const long first = (rowbase + (REV ? (L - 1 - s0) : s0)) * a.P + p;   // element of logical step s0
 
     float2 lam = active ? a.lam[p] : make_float2(0.f, 0.f);
     if (REV) lam.y = -lam.y;
@@ -80,17 +128,31 @@ __global__ void __launch_bounds__(SCAN_THREADS) scan_kernel(ScanArgs a)
     // logical step s <-> time t: forward t = s, reverse t = L-1-s
     float2 val[E];
     float2 xp[REV ? E : 1];
+    if (full) {
+        const float2 *src = a.in + first;
 #pragma unroll
-    for (int e = 0; e < E; ++e) {
-        val[e] = make_float2(0.f, 0.f);
-        if constexpr (REV) xp[e] = make_float2(0.f, 0.f);
-        if (e < len && active) {
-            const int s = s0 + e;
-            const int t = REV ? (L - 1 - s) : s;
-            val[e] = a.in[(rowbase + t) * a.P + p];
-            if constexpr (REV) {
-                if (t > 0) xp[e] = a.xsaved[(rowbase + t - 1) * a.P + p];
-                else if (a.x0) xp[e] = a.x0[(long)b * a.P + p];
+        for (int e = 0; e < E; ++e) val[e] = src[e * stride];
+        if constexpr (REV) {
+            // state before each step: x[t-1]; only the very last logical step can have t = 0
+            const float2 *xs = a.xsaved + first - a.P;
+#pragma unroll
+            for (int e = 0; e < E - 1; ++e) xp[e] = xs[e * stride];
+            if (s0 + E < L) xp[E - 1] = xs[(E - 1) * stride];
+            else xp[E - 1] = a.x0 ? a.x0[(long)b * a.P + p] : make_float2(0.f, 0.f);
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            val[e] = make_float2(0.f, 0.f);
+            if constexpr (REV) xp[e] = make_float2(0.f, 0.f);
+            if (e < len && active) {
+                const int s = s0 + e;
+                const int t = REV ? (L - 1 - s) : s;
+                val[e] = a.in[(rowbase + t) * a.P + p];
+                if constexpr (REV) {
+                    if (t > 0) xp[e] = a.xsaved[(rowbase + t - 1) * a.P + p];
+                    else if (a.x0) xp[e] = a.x0[(long)b * a.P + p];
+                }
             }
         }
     }
@@ -126,14 +188,35 @@ __global__ void __launch_bounds__(SCAN_THREADS) scan_kernel(ScanArgs a)
         rmask = fmask << 1;
         if (a.is_first && len > 0 && s0 > 0) rmask |= (unsigned)(a.is_first[rowbase + (L - s0)] != 0);
     }
+    // wavefront-uniform: no flag anywhere in the steps of this wavefront -> plain recurrence
+    const bool plain = full && (__builtin_amdgcn_ballot_w64((rmask | mmask) != 0) == 0);
 
     // ---- level 1, first pass: aggregate of the thread's steps for zero incoming state
     float2 A = make_float2(1.f, 0.f), S = make_float2(0.f, 0.f);
+    static_assert(E == 16, "Abar^E below is four squarings");
+    if (full) {
+        if (plain) {
 #pragma unroll
-    for (int e = 0; e < E; ++e) {
-        if (e < len) {
-            if ((rmask >> e) & 1u) { S = val[e]; A = make_float2(0.f, 0.f); }
-            else { S = cfma(lam, S, val[e]); A = cmul(A, lam); }
+            for (int e = 0; e < E; ++e) S = cfma(lam, S, val[e]);
+        } else {
+            // branch-free: a reset zeroes the multiplier of that step
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                const bool r = (rmask >> e) & 1u;
+                const float2 le = make_float2(r ? 0.f : lam.x, r ? 0.f : lam.y);
+                S = cfma(le, S, val[e]);
+            }
+        }
+        float2 l2 = cmul(lam, lam);
+        l2 = cmul(l2, l2); l2 = cmul(l2, l2); l2 = cmul(l2, l2);
+        A = (rmask & 0xffffu) ? make_float2(0.f, 0.f) : l2;
+    } else {
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            if (e < len) {
+                if ((rmask >> e) & 1u) { S = val[e]; A = make_float2(0.f, 0.f); }
+                else { S = cfma(lam, S, val[e]); A = cmul(A, lam); }
+            }
         }
     }
     sA[tid] = A;
@@ -154,20 +237,21 @@ __global__ void __launch_bounds__(SCAN_THREADS) scan_kernel(ScanArgs a)
     // workgroup of the previous group (x0 / zero for the first group) and fold the aggregates of
     // the earlier workgroups of the own group over it.  Results are therefore bitwise
     // reproducible.  Every workgroup publishes its aggregate before it waits for anything; the
-    // last workgroup of a group also publishes its inclusive state.
+    // last workgroup of a group also publishes its inclusive state.  Every predecessor covers
+    // exactly cy*E steps, so its transition product is Abar^(cy*E) or zero (tag 2).
     const int G = a.cy;
     const int sg0 = (tb / G) * G;
     const bool lastchunk = (chunk == a.cy - 1);
-    const size_t desc_stride = (size_t)a.nPX * a.Bt * a.pxb;     // descriptors per time step of workgroups
+    const size_t desc_stride = (size_t)nchains * a.pxb;          // descriptors per time block
     ScanDesc *mine = a.desc + ((size_t)id * a.pxb + lane);
     float2 Ablk = make_float2(0.f, 0.f), Sblk = make_float2(0.f, 0.f), Xin = make_float2(0.f, 0.f);
     if (lastchunk) {
         Ablk = cmul(A, Aex);
         Sblk = cfma(A, Sex, S);
         if (a.nTB > 1 && tb + 1 < a.nTB) {
-            store_c64_agent(&mine->A, Ablk);
-            store_c64_agent(&mine->S, Sblk);
-            __hip_atomic_store(&mine->status, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+            const unsigned tag = (Ablk.x == 0.f && Ablk.y == 0.f) ? 2u : 1u;
+            publish_word(&mine->agg[0], Sblk.x, tag);
+            publish_word(&mine->agg[1], Sblk.y, tag);
         }
         if (sg0 == 0 && !REV && a.x0 && active) Xin = a.x0[(long)b * a.P + p];
     }
@@ -178,29 +262,22 @@ __global__ void __launch_bounds__(SCAN_THREADS) scan_kernel(ScanArgs a)
         const int j = sg0 + chunk;
         if (j < tb) {
             const ScanDesc *pred = mine - (size_t)(tb - j) * desc_stride;
-            unsigned st = 0, spins = 0;
-            while (true) {
-                st = __hip_atomic_load(&pred->status, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
-                if (st != 0 || spins >= a.spin_limit) break;
-                ++spins;
-                __builtin_amdgcn_s_sleep(2);
+            unsigned tag = 0;
+            if (!wait_pair(pred->agg, 1u, a.spin_limit, Sj, tag)) {
+                atomicOr(a.err, 1u);                 // gave up: flag it and finish anyway
+                Sj = make_float2(0.f, 0.f);
+            } else {
+                Aj = (tag == 2u) ? make_float2(0.f, 0.f) : pow_block(lam, a.cy);
             }
-            if (st == 0) atomicOr(a.err, 1u);        // gave up: flag it and finish anyway
-            else { Aj = load_c64_agent(&pred->A); Sj = load_c64_agent(&pred->S); }
         }
         sA[tid] = Aj;
         sS[tid] = Sj;
         if (lastchunk && sg0 > 0) {
             const ScanDesc *pred = mine - (size_t)(tb - sg0 + 1) * desc_stride;
-            unsigned st = 0, spins = 0;
-            while (true) {
-                st = __hip_atomic_load(&pred->status, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
-                if (st == 2 || spins >= a.spin_limit) break;
-                ++spins;
-                __builtin_amdgcn_s_sleep(2);
-            }
-            if (st != 2) atomicOr(a.err, 1u);
-            else Xin = load_c64_agent(&pred->incl);
+            unsigned tag = 0;
+            float2 incl;
+            if (!wait_pair(pred->incl, 3u, a.spin_limit, incl, tag)) atomicOr(a.err, 1u);
+            else Xin = incl;
         }
         __syncthreads();
         if (lastchunk) {
@@ -210,8 +287,9 @@ __global__ void __launch_bounds__(SCAN_THREADS) scan_kernel(ScanArgs a)
     }
     if (lastchunk) {
         if (a.nTB > 1 && tb + 1 < a.nTB && (tb + 1) % G == 0) {
-            store_c64_agent(&mine->incl, cfma(Ablk, Xin, Sblk));
-            __hip_atomic_store(&mine->status, 2u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+            const float2 incl = cfma(Ablk, Xin, Sblk);
+            publish_word(&mine->incl[0], incl.x, 3u);
+            publish_word(&mine->incl[1], incl.y, 3u);
         }
         sX[lane] = Xin;
     }
@@ -220,25 +298,61 @@ __global__ void __launch_bounds__(SCAN_THREADS) scan_kernel(ScanArgs a)
     // ---- level 1, second pass: the states themselves
     float2 xs = cfma(Aex, sX[lane], Sex);
     float2 acc = make_float2(0.f, 0.f);
+    if (full) {
+        float2 *dst = a.out + first;
+        if (plain) {
 #pragma unroll
-    for (int e = 0; e < E; ++e) {
-        if (e < len) {
-            const int s = s0 + e;
-            const int t = REV ? (L - 1 - s) : s;
-            xs = ((rmask >> e) & 1u) ? val[e] : cfma(lam, xs, val[e]);
-            if (active) {
-                a.out[(rowbase + t) * a.P + p] = xs;
+            for (int e = 0; e < E; ++e) {
+                xs = cfma(lam, xs, val[e]);
+                dst[e * stride] = xs;
                 if constexpr (REV) {
-                    if (!((mmask >> e) & 1u)) {
-                        // conj(x_{t-1}) * chi_t
-                        acc.x += xp[e].x * xs.x + xp[e].y * xs.y;
-                        acc.y += xp[e].x * xs.y - xp[e].y * xs.x;
+                    // conj(x_{t-1}) * chi_t
+                    acc.x = fmaf(xp[e].x, xs.x, fmaf(xp[e].y, xs.y, acc.x));
+                    acc.y = fmaf(xp[e].x, xs.y, fmaf(-xp[e].y, xs.x, acc.y));
+                }
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < E; ++e) {
+                const bool r = (rmask >> e) & 1u;
+                const float2 le = make_float2(r ? 0.f : lam.x, r ? 0.f : lam.y);
+                xs = cfma(le, xs, val[e]);
+                dst[e * stride] = xs;
+                if constexpr (REV) {
+                    const bool m = (mmask >> e) & 1u;
+                    const float2 q = make_float2(m ? 0.f : xp[e].x, m ? 0.f : xp[e].y);
+                    acc.x = fmaf(q.x, xs.x, fmaf(q.y, xs.y, acc.x));
+                    acc.y = fmaf(q.x, xs.y, fmaf(-q.y, xs.x, acc.y));
+                }
+            }
+        }
+        if constexpr (REV) {
+            if (s0 + E == L && a.dx0)
+                a.dx0[(long)b * a.P + p] = ((mmask >> (E - 1)) & 1u) ? make_float2(0.f, 0.f) : cmul(lam, xs);
+        } else {
+            if (s0 + E == L && a.x_last) a.x_last[(long)b * a.P + p] = xs;
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            if (e < len) {
+                const int s = s0 + e;
+                const int t = REV ? (L - 1 - s) : s;
+                xs = ((rmask >> e) & 1u) ? val[e] : cfma(lam, xs, val[e]);
+                if (active) {
+                    a.out[(rowbase + t) * a.P + p] = xs;
+                    if constexpr (REV) {
+                        if (!((mmask >> e) & 1u)) {
+                            // conj(x_{t-1}) * chi_t
+                            acc.x += xp[e].x * xs.x + xp[e].y * xs.y;
+                            acc.y += xp[e].x * xs.y - xp[e].y * xs.x;
+                        }
+                        if (t == 0 && a.dx0)
+                            a.dx0[(long)b * a.P + p] =
+                                ((mmask >> e) & 1u) ? make_float2(0.f, 0.f) : cmul(lam, xs);
+                    } else {
+                        if (t == L - 1 && a.x_last) a.x_last[(long)b * a.P + p] = xs;
                     }
-                    if (t == 0 && a.dx0)
-                        a.dx0[(long)b * a.P + p] =
-                            ((mmask >> e) & 1u) ? make_float2(0.f, 0.f) : cmul(lam, xs);
-                } else {
-                    if (t == L - 1 && a.x_last) a.x_last[(long)b * a.P + p] = xs;
                 }
             }
         }
@@ -271,6 +385,8 @@ ScanPlan plan_scan(int64_t Bt, int64_t L, int64_t P)
     pl.nPX = (int)((P + pl.pxb - 1) / pl.pxb);
     pl.nTB = (int)((L + (int64_t)cy * SCAN_E - 1) / ((int64_t)cy * SCAN_E));
     pl.nblocks = (int64_t)pl.nPX * Bt * pl.nTB;
+    // look-back scratch: ticket counters (one per chain, 64 bytes apart) followed by descriptors
+    pl.ticket_bytes = pl.nTB > 1 ? (size_t)pl.nPX * Bt * SCAN_TICKET_STRIDE * sizeof(uint32_t) : 0;
     pl.desc_bytes = pl.nTB > 1 ? (size_t)pl.nblocks * pl.pxb * sizeof(ScanDesc) : 0;
     pl.partial_elems = (size_t)Bt * pl.nTB * P;
     return pl;
@@ -287,23 +403,24 @@ hipError_t launch_scan(const ScanArgs &a, bool reverse, hipStream_t s)
     return hipGetLastError();
 }
 
+// zeroes the header and the 16-byte words of the ticket counters + descriptors that follow it
 __global__ void __launch_bounds__(256) clear_kernel(WsHeader *hdr, uint4 *desc, size_t n16)
 {
     const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (i == 0) {
-        hdr->ticket_fwd = 0; hdr->ticket_rev = 0; hdr->err = 0; hdr->magic = 0x53534d31u;
+        hdr->err = 0; hdr->magic = 0x53534d31u;
     }
     for (size_t j = i; j < n16; j += (size_t)gridDim.x * 256) desc[j] = make_uint4(0, 0, 0, 0);
 }
 
-hipError_t launch_clear(WsHeader *hdr, ScanDesc *desc, size_t ndesc, hipStream_t s)
+hipError_t launch_clear(WsHeader *hdr, void *scratch, size_t scratch_bytes, hipStream_t s)
 {
-    const size_t n16 = ndesc * sizeof(ScanDesc) / 16;
+    const size_t n16 = scratch_bytes / 16;
+    uint4 *desc = static_cast<uint4 *>(scratch);
     size_t blocks = (n16 + 255) / 256;
     if (blocks < 1) blocks = 1;
     if (blocks > 1024) blocks = 1024;
-    hipLaunchKernelGGL(clear_kernel, dim3((unsigned)blocks), dim3(256), 0, s, hdr,
-                       reinterpret_cast<uint4 *>(desc), n16);
+    hipLaunchKernelGGL(clear_kernel, dim3((unsigned)blocks), dim3(256), 0, s, hdr, desc, n16);
     return hipGetLastError();
 }
 

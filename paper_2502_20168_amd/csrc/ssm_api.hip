@@ -16,7 +16,7 @@ inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 struct Layout {
     ScanPlan plan;
     int splitC, splitB, nslab;
-    size_t hdr, lam, Bri, Cc, xbuf, chi, desc, dCpart, dBpart, dApart, dDpart, total;
+    size_t hdr, lam, Bri, Cc, xbuf, chi, ticket, desc, dCpart, dBpart, dApart, dDpart, total;
 };
 
 ssm_status check_dims(int64_t Bt, int64_t L, int64_t H, int64_t P)
@@ -44,6 +44,7 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
     o.lam = off; off += up((size_t)P * 8);
     o.Bri = off; off += up((size_t)2 * P * H * 4);
     o.Cc = off; off += up((size_t)2 * P * H * 4);
+    o.ticket = off; off += up(o.plan.ticket_bytes);       // tickets and descriptors are contiguous
     o.desc = off; off += up(o.plan.desc_bytes);
     o.xbuf = o.chi = o.dCpart = o.dBpart = o.dApart = o.dDpart = 0;
     if (!bwd) {
@@ -123,7 +124,7 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
 
     MARK();
     if (lo.plan.nTB > 1)
-        HIP_TRY(launch_clear(hdr, desc, lo.plan.desc_bytes / sizeof(ScanDesc), s));
+        HIP_TRY(launch_clear(hdr, ws + lo.ticket, lo.desc + up(lo.plan.desc_bytes) - lo.ticket, s));
     PrepArgs pa{};
     pa.Lambda = reinterpret_cast<const float2 *>(Lambda); pa.B = reinterpret_cast<const float2 *>(B);
     pa.C = reinterpret_cast<const float2 *>(C); pa.log_delta = log_delta;
@@ -144,7 +145,7 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     ScanArgs sa{};
     sa.in = xs; sa.out = xs; sa.lam = lam; sa.is_first = is_first;
     sa.x0 = reinterpret_cast<const float2 *>(x0); sa.x_last = reinterpret_cast<float2 *>(x_last);
-    sa.desc = desc; sa.ticket = &hdr->ticket_fwd; sa.err = &hdr->err;
+    sa.desc = desc; sa.ticket = reinterpret_cast<uint32_t *>(ws + lo.ticket); sa.err = &hdr->err;
     sa.Bt = (int)Bt; sa.L = (int)L; sa.P = (int)P;
     sa.pxb = lo.plan.pxb; sa.cy = lo.plan.cy; sa.nPX = lo.plan.nPX; sa.nTB = lo.plan.nTB;
     sa.spin_limit = spin_limit();
@@ -197,7 +198,7 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
 
     MARK();
     if (lo.plan.nTB > 1)
-        HIP_TRY(launch_clear(hdr, desc, lo.plan.desc_bytes / sizeof(ScanDesc), s));
+        HIP_TRY(launch_clear(hdr, ws + lo.ticket, lo.desc + up(lo.plan.desc_bytes) - lo.ticket, s));
     PrepArgs pa{};
     pa.Lambda = reinterpret_cast<const float2 *>(Lambda); pa.B = reinterpret_cast<const float2 *>(B);
     pa.C = reinterpret_cast<const float2 *>(C); pa.log_delta = log_delta;
@@ -231,7 +232,7 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     sa.x0 = reinterpret_cast<const float2 *>(x0);
     sa.xsaved = reinterpret_cast<const float2 *>(x); sa.partial = dApart;
     sa.dx0 = reinterpret_cast<float2 *>(dx0);
-    sa.desc = desc; sa.ticket = &hdr->ticket_rev; sa.err = &hdr->err;
+    sa.desc = desc; sa.ticket = reinterpret_cast<uint32_t *>(ws + lo.ticket); sa.err = &hdr->err;
     sa.Bt = (int)Bt; sa.L = (int)L; sa.P = (int)P;
     sa.pxb = lo.plan.pxb; sa.cy = lo.plan.cy; sa.nPX = lo.plan.nPX; sa.nTB = lo.plan.nTB;
     sa.spin_limit = spin_limit();
@@ -270,7 +271,7 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     return SSM_OK;
 }
 
-struct ScanOnlyLayout { ScanPlan plan; size_t hdr, desc, dApart, total; };
+struct ScanOnlyLayout { ScanPlan plan; size_t hdr, ticket, desc, dApart, total; };
 
 ssm_status make_scan_layout(int64_t Bt, int64_t L, int64_t P, bool rev, ScanOnlyLayout &o)
 {
@@ -280,6 +281,7 @@ ssm_status make_scan_layout(int64_t Bt, int64_t L, int64_t P, bool rev, ScanOnly
     if (o.plan.nblocks > 0x7fffffffLL) return SSM_ERR_UNSUPPORTED;
     size_t off = 0;
     o.hdr = off; off += up(sizeof(WsHeader));
+    o.ticket = off; off += up(o.plan.ticket_bytes);
     o.desc = off; off += up(o.plan.desc_bytes);
     o.dApart = off; if (rev) off += up(o.plan.partial_elems * 8);
     o.total = off;
@@ -401,12 +403,12 @@ ssm_status ssm_scan_states(const ssm_c64 *A_bar, ssm_c64 *v, const uint8_t *is_f
     char *ws = static_cast<char *>(workspace);
     WsHeader *hdr = reinterpret_cast<WsHeader *>(ws + lo.hdr);
     ScanDesc *desc = reinterpret_cast<ScanDesc *>(ws + lo.desc);
-    HIP_TRY(launch_clear(hdr, desc, lo.plan.desc_bytes / sizeof(ScanDesc), s));
+    HIP_TRY(launch_clear(hdr, ws + lo.ticket, lo.desc + up(lo.plan.desc_bytes) - lo.ticket, s));
     ScanArgs sa{};
     sa.in = reinterpret_cast<const float2 *>(v); sa.out = reinterpret_cast<float2 *>(v);
     sa.lam = reinterpret_cast<const float2 *>(A_bar); sa.is_first = is_first;
     sa.x0 = reinterpret_cast<const float2 *>(x0); sa.x_last = reinterpret_cast<float2 *>(x_last);
-    sa.desc = desc; sa.ticket = &hdr->ticket_fwd; sa.err = &hdr->err;
+    sa.desc = desc; sa.ticket = reinterpret_cast<uint32_t *>(ws + lo.ticket); sa.err = &hdr->err;
     sa.Bt = (int)Bt; sa.L = (int)L; sa.P = (int)P;
     sa.pxb = lo.plan.pxb; sa.cy = lo.plan.cy; sa.nPX = lo.plan.nPX; sa.nTB = lo.plan.nTB;
     sa.spin_limit = spin_limit();
@@ -432,14 +434,14 @@ ssm_status ssm_scan_states_reverse(const ssm_c64 *A_bar, ssm_c64 *gx, const ssm_
     WsHeader *hdr = reinterpret_cast<WsHeader *>(ws + lo.hdr);
     ScanDesc *desc = reinterpret_cast<ScanDesc *>(ws + lo.desc);
     float2 *dApart = reinterpret_cast<float2 *>(ws + lo.dApart);
-    HIP_TRY(launch_clear(hdr, desc, lo.plan.desc_bytes / sizeof(ScanDesc), s));
+    HIP_TRY(launch_clear(hdr, ws + lo.ticket, lo.desc + up(lo.plan.desc_bytes) - lo.ticket, s));
     ScanArgs sa{};
     sa.in = reinterpret_cast<const float2 *>(gx); sa.out = reinterpret_cast<float2 *>(gx);
     sa.lam = reinterpret_cast<const float2 *>(A_bar); sa.is_first = is_first;
     sa.x0 = reinterpret_cast<const float2 *>(x0);
     sa.xsaved = reinterpret_cast<const float2 *>(x); sa.partial = dApart;
     sa.dx0 = reinterpret_cast<float2 *>(dx0);
-    sa.desc = desc; sa.ticket = &hdr->ticket_rev; sa.err = &hdr->err;
+    sa.desc = desc; sa.ticket = reinterpret_cast<uint32_t *>(ws + lo.ticket); sa.err = &hdr->err;
     sa.Bt = (int)Bt; sa.L = (int)L; sa.P = (int)P;
     sa.pxb = lo.plan.pxb; sa.cy = lo.plan.cy; sa.nPX = lo.plan.nPX; sa.nTB = lo.plan.nTB;
     sa.spin_limit = spin_limit();

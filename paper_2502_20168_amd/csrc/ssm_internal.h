@@ -34,26 +34,26 @@ int gemm_pick_splits(int64_t M, int64_t N, int64_t K);
 // ---------------------------------------------------------------------------------------------
 constexpr int SCAN_E = 16;
 constexpr int SCAN_THREADS = 256;
+constexpr int SCAN_TICKET_STRIDE = 16;   // uint32 slots between the ticket counters of two chains
 
-struct ScanDesc {            // one per (workgroup, lane); 32 bytes
-    float2 A;                // product of the transition over the workgroup's steps (0 after a reset)
-    float2 S;                // state at the end of the workgroup's steps for zero incoming state
-    float2 incl;             // state at the end of the workgroup's steps, incoming state included
-    uint32_t status;         // 0 = nothing, 1 = (A,S) valid, 2 = incl valid
-    uint32_t pad;
+struct ScanDesc {            // one per (workgroup, lane); 32 bytes; every word = (float << 32) | tag
+    unsigned long long agg[2];   // re, im of the state at the end of the workgroup's steps for zero
+                                 // incoming state; tag 1 = no reset among the steps, tag 2 = reset
+    unsigned long long incl[2];  // re, im of that state with the incoming state included; tag 3
 };
 
 struct ScanPlan {
     int pxb, cy;             // lanes and chunks per workgroup (pxb * cy == SCAN_THREADS)
     int nPX, nTB;            // workgroups along the state and the time dimension
     int64_t nblocks;         // nPX * Bt * nTB
+    size_t ticket_bytes;     // per-chain ticket counters, 0 when nTB == 1
     size_t desc_bytes;       // 0 when nTB == 1
     size_t partial_elems;    // Bt * nTB * P complex partial sums of the reverse scan
 };
 ScanPlan plan_scan(int64_t Bt, int64_t L, int64_t P);
 
 struct WsHeader {            // first 256 bytes of every workspace
-    uint32_t ticket_fwd, ticket_rev, err, magic;
+    uint32_t err, magic;
 };
 
 struct ScanArgs {
@@ -67,13 +67,14 @@ struct ScanArgs {
     float2 *partial;         // reverse only: [Bt*nTB, P]
     float2 *dx0;             // reverse only, or null
     ScanDesc *desc;
-    uint32_t *ticket;
+    uint32_t *ticket;        // per-chain counters, SCAN_TICKET_STRIDE apart (nTB > 1 only)
     uint32_t *err;
     int Bt, L, P, pxb, cy, nPX, nTB;
     uint32_t spin_limit;
 };
 hipError_t launch_scan(const ScanArgs &a, bool reverse, hipStream_t s);
-hipError_t launch_clear(WsHeader *hdr, ScanDesc *desc, size_t ndesc, hipStream_t s);
+// zeroes the header and `scratch_bytes` (a multiple of 16) of ticket counters + descriptors
+hipError_t launch_clear(WsHeader *hdr, void *scratch, size_t scratch_bytes, hipStream_t s);
 // out[p] = sum_i partial[i*P + p]
 hipError_t launch_reduce_partials(const float2 *partial, int64_t n, int64_t P, float2 *out, hipStream_t s);
 
