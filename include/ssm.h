@@ -58,7 +58,7 @@ typedef enum {
 
 /* Number of per-stage timings written by the *_profiled calls (see below). */
 #define SSM_FWD_STAGES 4
-#define SSM_BWD_STAGES 7
+#define SSM_BWD_STAGES 6
 
 /* Static description of an error code. Never NULL. */
 const char *ssm_strerror(int status);
@@ -138,8 +138,8 @@ ssm_status ssm_scan_states_reverse(const ssm_c64 *A_bar, ssm_c64 *gx, const ssm_
  * on `stream` around every kernel.  They wait for the stream before returning and write the
  * milliseconds of each stage to the HOST array stage_ms:
  *   forward : [0] discretise+pack, [1] input projection, [2] scan, [3] output projection
- *   backward: [0] discretise+pack and dD partials, [1] gx = C^H dy, [2] dC partials,
- *             [3] reverse scan, [4] du, [5] dBbar partials, [6] parameter epilogue               */
+ *   backward: [0] discretise+pack and dD partials, [1] gx = C^H dy, [2] reverse scan, [3] du,
+ *             [4] dC and dBbar partials (one launch), [5] parameter epilogue                    */
 ssm_status ssm_scan_fwd_profiled(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C,
                                  const float *D, const float *log_delta, const float *u,
                                  const uint8_t *is_first, const ssm_c64 *x0,

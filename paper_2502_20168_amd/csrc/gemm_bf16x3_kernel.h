@@ -453,17 +453,21 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
         }
 }
 
+// One launch can carry two independent problems of the same layout (used for the two K = T
+// reductions of the gradient pass): blockIdx.y < splits0 works on g0, the rest on g1.
 template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, bool AKC, bool BKC, bool EPI>
-__global__ void __launch_bounds__(64 * (WGM * WGN + NP)) gemm_bf16x3_ws_kernel(GemmDev g)
+__global__ void __launch_bounds__(64 * (WGM * WGN + NP)) gemm_bf16x3_ws_kernel(GemmDev g0, GemmDev g1, int splits0)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);
+    const bool second = (int)blockIdx.y >= splits0;
+    const GemmDev g = second ? g1 : g0;
     const int id = blockIdx.x;
     const int tile = (id % 8) * g.per_xcd + id / 8;
-    if (tile >= g.ntm * g.ntn) return;
+    if (id >= 8 * g.per_xcd || tile >= g.ntm * g.ntn) return;
     const int tm = tile / g.ntn, tn = tile % g.ntn;
     const int m0 = tm * BM, n0 = tn * BN;
-    const int z = blockIdx.y;
+    const int z = second ? (int)blockIdx.y - splits0 : (int)blockIdx.y;
     const int kbeg = z * g.kper;
     const int kend = min(g.K, kbeg + g.kper);
     const bool fast = (g.lda % 4 == 0) && ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0) &&
@@ -475,8 +479,8 @@ __global__ void __launch_bounds__(64 * (WGM * WGN + NP)) gemm_bf16x3_ws_kernel(G
         gemm_bf16x3_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, AKC, BKC, EPI, false>(g, smem, m0, n0, z, kbeg, kend);
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, bool AKC, bool BKC, bool EPI>
-hipError_t launch_gemm_bf16x3_ws_variant(const GemmArgs &a, hipStream_t s)
+template <int BM, int BN, int BK>
+inline GemmDev make_gemm_dev(const GemmArgs &a)
 {
     GemmDev g;
     g.A = a.A; g.lda = a.lda; g.B = a.B; g.ldb = a.ldb; g.C = a.C; g.ldc = a.ldc;
@@ -490,10 +494,22 @@ hipError_t launch_gemm_bf16x3_ws_variant(const GemmArgs &a, hipStream_t s)
     g.ntn = (a.N + BN - 1) / BN;
     const long ntiles = (long)g.ntm * g.ntn;
     g.per_xcd = (int)((ntiles + 7) / 8);
+    return g;
+}
+
+// b == nullptr: one problem.  Otherwise two problems with the same operand layouts, no epilogue.
+template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, bool AKC, bool BKC, bool EPI>
+hipError_t launch_gemm_bf16x3_ws_variant(const GemmArgs &a, hipStream_t s, const GemmArgs *b = nullptr)
+{
+    const GemmDev g0 = make_gemm_dev<BM, BN, BK>(a);
+    const GemmDev g1 = b ? make_gemm_dev<BM, BN, BK>(*b) : g0;
+    const int splits0 = a.splits < 1 ? 1 : a.splits;
+    const int splits1 = b ? (b->splits < 1 ? 1 : b->splits) : 0;
     constexpr size_t smem = (size_t)NS * 3 * (BM + BN) * (BK + 8) * sizeof(__bf16);
     static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS of a gfx950 CU");
     auto kern = gemm_bf16x3_ws_kernel<BM, BN, BK, WGM, WGN, NP, NS, AKC, BKC, EPI>;
     if (smem > 64 * 1024) {
+        // raising the dynamic LDS limit is idempotent; doing it once per instantiation is enough
         static bool raised = false;
         if (!raised) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -502,8 +518,9 @@ hipError_t launch_gemm_bf16x3_ws_variant(const GemmArgs &a, hipStream_t s)
             raised = true;
         }
     }
-    dim3 grid((unsigned)(g.per_xcd * 8), (unsigned)splits, 1);
-    hipLaunchKernelGGL(kern, grid, dim3(64 * (WGM * WGN + NP)), smem, s, g);
+    const int gx = 8 * (g0.per_xcd > g1.per_xcd ? g0.per_xcd : g1.per_xcd);
+    dim3 grid((unsigned)gx, (unsigned)(splits0 + splits1), 1);
+    hipLaunchKernelGGL(kern, grid, dim3(64 * (WGM * WGN + NP)), smem, s, g0, g1, splits0);
     return hipGetLastError();
 }
 

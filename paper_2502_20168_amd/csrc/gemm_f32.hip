@@ -13,10 +13,11 @@ namespace ssm {
 
 int gemm_pick_splits(int64_t M, int64_t N, int64_t K)
 {
-    // long reductions with a small result: enough K splits to give every CU a workgroup, keeping
-    // at least 256 rows of K per split
+    // long reductions with a small result: enough K splits to give half of the CUs a workgroup
+    // (the two reductions of the gradient pass share one launch), keeping at least 256 rows of
+    // K per split
     const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
-    int64_t s = (256 + tiles - 1) / tiles;
+    int64_t s = (128 + tiles - 1) / tiles;
     const int64_t maxs = (K + 255) / 256;
     if (s > maxs) s = maxs;
     if (s > 64) s = 64;
@@ -40,8 +41,13 @@ static hipError_t dispatch_f32(const GemmArgs &a, hipStream_t s)
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS>
-static hipError_t dispatch_bf16x3(const GemmArgs &a, hipStream_t s)
+static hipError_t dispatch_bf16x3(const GemmArgs &a, hipStream_t s, const GemmArgs *b = nullptr)
 {
+    if (b) {
+        if (a.a_kcontig || a.b_kcontig || b->a_kcontig || b->b_kcontig || a.diag || b->diag)
+            return hipErrorInvalidValue;
+        return launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, false, false, false>(a, s, b);
+    }
     const bool epi = a.diag != nullptr;
     if (a.a_kcontig && a.b_kcontig)
         return epi ? launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, true, true, true>(a, s)
@@ -80,6 +86,17 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
     // wavefronts; 128x64 tiles when the wide tile would leave CUs without work
     if (tiles128 >= 200) return dispatch_bf16x3<128, 128, 32, 2, 2, 4, 2>(a, s);
     return dispatch_bf16x3<128, 64, 32, 4, 1, 4, 2>(a, s);
+}
+
+// Two K = T reductions (both operands row-contiguous, no epilogue) in one launch.
+hipError_t launch_gemm_pair(const GemmArgs &a, const GemmArgs &b, hipStream_t s)
+{
+    if (a.M <= 0 || a.N <= 0 || a.K <= 0 || b.M <= 0 || b.N <= 0 || b.K <= 0) return hipErrorInvalidValue;
+    if (use_f32_mfma()) {
+        hipError_t e = launch_gemm(a, s);
+        return e != hipSuccess ? e : launch_gemm(b, s);
+    }
+    return dispatch_bf16x3<128, 128, 32, 2, 2, 4, 2>(a, s, &b);
 }
 
 }  // namespace ssm

@@ -218,15 +218,6 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     HIP_TRY(launch_gemm(g3, s));
     MARK();
 
-    // dC slabs: [h, 2p+c] = sum_t dy[t,h] * x[t, 2p+c]
-    GemmArgs g4{};
-    g4.A = dy; g4.lda = H; g4.a_kcontig = 0;
-    g4.B = xf; g4.ldb = 2 * P; g4.b_kcontig = 0;
-    g4.C = dCpart; g4.ldc = 2 * P;
-    g4.M = (int)H; g4.N = (int)(2 * P); g4.K = T; g4.splits = lo.splitC;
-    HIP_TRY(launch_gemm(g4, s));
-    MARK();
-
     ScanArgs sa{};
     sa.in = chi; sa.out = chi; sa.lam = lam; sa.is_first = is_first;
     sa.x0 = reinterpret_cast<const float2 *>(x0);
@@ -248,13 +239,19 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     HIP_TRY(launch_gemm(g5, s));
     MARK();
 
-    // dBbar slabs: [2p+c, h] = sum_t chi[t, 2p+c] * u[t,h]
+    // dC slabs: [h, 2p+c] = sum_t dy[t,h] * x[t, 2p+c]
+    GemmArgs g4{};
+    g4.A = dy; g4.lda = H; g4.a_kcontig = 0;
+    g4.B = xf; g4.ldb = 2 * P; g4.b_kcontig = 0;
+    g4.C = dCpart; g4.ldc = 2 * P;
+    g4.M = (int)H; g4.N = (int)(2 * P); g4.K = T; g4.splits = lo.splitC;
+    // dBbar slabs: [2p+c, h] = sum_t chi[t, 2p+c] * u[t,h]   (same launch as the dC slabs)
     GemmArgs g6{};
     g6.A = reinterpret_cast<const float *>(chi); g6.lda = 2 * P; g6.a_kcontig = 0;
     g6.B = u; g6.ldb = H; g6.b_kcontig = 0;
     g6.C = dBpart; g6.ldc = H;
     g6.M = (int)(2 * P); g6.N = (int)H; g6.K = T; g6.splits = lo.splitB;
-    HIP_TRY(launch_gemm(g6, s));
+    HIP_TRY(launch_gemm_pair(g4, g6, s));
     MARK();
 
     EpilogueArgs ea{};

@@ -22,6 +22,8 @@ struct GemmArgs {
     int M, N, K, splits;
 };
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t s);
+// two independent reductions with row-contiguous operands and no epilogue in one launch
+hipError_t launch_gemm_pair(const GemmArgs &a, const GemmArgs &b, hipStream_t s);
 // number of K splits used for a reduction over `K` rows with an M x N result
 int gemm_pick_splits(int64_t M, int64_t N, int64_t K);
 
