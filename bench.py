@@ -6,9 +6,10 @@ scan, output projection) plus the gradient pass (C^H dy, reverse scan, du, param
 -- over one synthetic world-model-shaped batch (Bt=16, L=256, H=P=512) that is already resident
 in HBM.  Prints ONE JSON line:
   metric/value : whole-job throughput in Mtokens/s (token = one (sequence, step) pair)
-  roofline     : the dominant kernel (the fp32 MFMA GEMM that produces the dC / dBbar partial
-                 sums, two launches per step) against the fp32 matrix peak, its duration measured
-                 with HIP events on the launch stream inside the library's *_profiled entry points
+  roofline     : the dominant kernel (the projection GEMM: fp32 in/out, three-way bf16 operand
+                 split, six bf16 MFMAs per k block) against the bf16 matrix peak, its duration
+                 measured with HIP events on the launch stream inside the library's *_profiled
+                 entry points; the fp32-equivalent rate is given next to it
   scan_roofline: the two scan kernels against the HBM peak (algorithmic bytes / event time),
                  warm (buffers resident in the 256 MB last-level cache) and cold (rotating over
                  more than 1 GiB of distinct buffers)
@@ -26,6 +27,11 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix
+PEAK_BF16_MFMA_TFLOPS = 2500.0 # MI355X dense bf16 matrix
+BF16_PRODUCTS = 6              # bf16 MFMA products the GEMM issues per fp32 multiply-add
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see
+# profiles/); None until measured
+TRAFFIC_PROJECT_IN = None
 
 
 def main():
@@ -97,16 +103,30 @@ def main():
     stages = {"fwd_" + n: round(float(v) * 1e3, 2) for n, v in zip(ssm.FWD_STAGE_NAMES, fs)}
     stages.update({"bwd_" + n: round(float(v) * 1e3, 2) for n, v in zip(ssm.BWD_STAGE_NAMES, bs)})
 
-    gemm_flops = 2.0 * T * (2 * P) * H                    # every one of the six projections
-    # dominant kernel: the K=T reduction GEMM (both operands row-contiguous), launched twice per step
-    dom_ms = bs[4]
-    dom_tflops = gemm_flops / (dom_ms * 1e-3) / 1e12
+    gemm_flops = 2.0 * T * (2 * P) * H                    # fp32 flops of every one of the six projections
+    # Dominant kernel: gemm_bf16x3_ws_kernel.  Its largest share of the step is the instantiation for
+    # a k-contiguous A operand (input projection; 128x128x32 tiles).  Algorithmic work of the kernel =
+    # the six bf16 partial products per multiply-add that the exact three-way split needs.
+    f32_path = os.environ.get("SSM_GEMM_F32", "") == "1"
+    dom_ms = fs[1]
+    dom_fp32_tflops = gemm_flops / (dom_ms * 1e-3) / 1e12
     gemm_ms = {"project_in": fs[1], "project_out": fs[3], "gx": bs[1], "du": bs[3], "dC_dBbar_pair(2 gemms)": bs[4] / 2}
-    roofline = {"kernel": "gemm_f32_kernel<128,128,16,false,false,false> (dC and dBbar partial sums)",
-                "bound": "mfma", "achieved": round(dom_tflops, 2), "peak": PEAK_FP32_MFMA_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(dom_tflops / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": None,
-                "flops_per_launch": gemm_flops, "avg_launch_us": round(float(dom_ms) * 1e3, 2),
-                "all_gemms_tflops": {k: round(gemm_flops / (v * 1e-3) / 1e12, 2) for k, v in gemm_ms.items()}}
+    if f32_path:
+        roofline = {"kernel": "gemm_f32_kernel<128,128,32,4,2,true,true,false> (input projection)",
+                    "bound": "mfma", "achieved": round(dom_fp32_tflops, 2), "peak": PEAK_FP32_MFMA_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(dom_fp32_tflops / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": None}
+    else:
+        ach = BF16_PRODUCTS * dom_fp32_tflops
+        roofline = {"kernel": "gemm_bf16x3_ws_kernel<128,128,32,2,2,4,2,true,true,false> (input projection)",
+                    "bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(ach / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": TRAFFIC_PROJECT_IN,
+                    "note": "achieved counts the 6 bf16 MFMA products per fp32 multiply-add that the kernel "
+                            "executes by design; fp32-equivalent rate and its ratio to the fp32 matrix peak below",
+                    "fp32_equivalent_tflops": round(dom_fp32_tflops, 2),
+                    "fp32_equivalent_over_fp32_matrix_peak": round(dom_fp32_tflops / PEAK_FP32_MFMA_TFLOPS, 4)}
+    roofline.update({"flops_per_launch_fp32": gemm_flops, "avg_launch_us": round(float(dom_ms) * 1e3, 2),
+                     "all_gemms_fp32_equivalent_tflops": {k: round(gemm_flops / (v * 1e-3) / 1e12, 2)
+                                                          for k, v in gemm_ms.items()}})
 
     # ---- scan kernels against the HBM roofline: algorithmic bytes = 16 B (forward: read v, write x)
     # and 24 B (reverse: read gx, read x, write chi) per (token, state)
@@ -118,11 +138,15 @@ def main():
             "in_path_rev_GBs": round(rev_bytes / (bs[2] * 1e-3) / 1e9, 1)}
     scan.update(scan_cold_warm(ssm, torch, d, Bt, L, P, fwd_bytes, rev_bytes))
     scan["frac"] = round(scan["cold_fwd_GBs"] / PEAK_HBM_GBS, 4)
+    scan["frac_of_copy_kernel_cold"] = round(scan["cold_fwd_GBs"] / scan["copy_cold_GBs"], 4)
 
     result = {
         "metric": "ssm_scan_fwd_bwd_throughput", "value": round(mtok, 3), "unit": "Mtokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32",
+        "arith": "fp32 I/O and accumulation; projections on " + ("fp32 MFMA" if f32_path else
+                 "bf16 MFMA with an exact 3-way bf16 split of both operands (fp32-class accuracy)"),
         "data": "synthetic",
         "config": {"workload": "%s: Bt=%d L=%d H=%d P=%d fwd+bwd, fp32 I/O, complex64 state, seed %d"
                                % (w.name, Bt, L, H, P, w.seed), "tokens_per_step": T},
@@ -163,6 +187,13 @@ def scan_cold_warm(ssm, torch, d, Bt, L, P, fwd_bytes, rev_bytes, iters=40):
     r = lambda i: ssm.ssm_scan_states_reverse(A_bar, vs[i], xs[i % len(xs)], d["is_first"], d["x0"],
                                               want_dx0=False, workspace=ws_r)
     out = {}
+    # plain device copy of the same bytes as the forward scan (read 8 B + write 8 B per element): what the
+    # memory system gives a dependency-free kernel at this size
+    cp = lambda i: vs[(i + 1) % nsets].copy_(vs[i])
+    for mode in ("warm", "cold"):
+        ms = timed(cp, mode == "cold")
+        out["copy_%s_us" % mode] = round(ms * 1e3, 2)
+        out["copy_%s_GBs" % mode] = round(fwd_bytes / (ms * 1e-3) / 1e9, 1)
     for name, fn, nbytes in (("fwd", f, fwd_bytes), ("rev", r, rev_bytes)):
         for mode in ("warm", "cold"):
             ms = timed(fn, mode == "cold")

@@ -456,18 +456,34 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
 // One launch can carry two independent problems of the same layout (used for the two K = T
 // reductions of the gradient pass): blockIdx.y < splits0 works on g0, the rest on g1.
 template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, bool AKC, bool BKC, bool EPI>
-__global__ void __launch_bounds__(64 * (WGM * WGN + NP)) gemm_bf16x3_ws_kernel(GemmDev g0, GemmDev g1, int splits0)
+__global__ void __launch_bounds__(64 * (WGM * WGN + NP)) gemm_bf16x3_ws_kernel(GemmDev g0, GemmDev g1, int splits0,
+                                                                                 int splits_total, int xcd_split)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);
-    const bool second = (int)blockIdx.y >= splits0;
+    // Workgroup ids are dealt round-robin to the 8 XCDs (id % 8).  Without K splits, XCD x gets
+    // the contiguous band of tiles [x*per_xcd, (x+1)*per_xcd) so that it re-reads only its band
+    // of A from its own L2.  With K splits (xcd_split != 0) every XCD instead owns whole K slabs:
+    // all tiles of one (problem, split) pair run on the same XCD(s), so each operand element is
+    // fetched from memory once instead of once per tile band.
+    int zz, tile;
+    if (xcd_split) {
+        const int id = blockIdx.x, xcd = id % 8, j = id / 8;
+        const int S = splits_total;
+        if (S % 8 == 0) { zz = xcd + 8 * (j % (S / 8)); tile = j / (S / 8); }
+        else { zz = xcd % S; tile = j * (8 / S) + xcd / S; }             // 8 % S == 0
+    } else {
+        zz = blockIdx.y;
+        const int id = blockIdx.x;
+        const GemmDev &gg = (zz >= splits0) ? g1 : g0;
+        tile = (id < 8 * gg.per_xcd) ? (id % 8) * gg.per_xcd + id / 8 : -1;
+    }
+    const bool second = zz >= splits0;
     const GemmDev g = second ? g1 : g0;
-    const int id = blockIdx.x;
-    const int tile = (id % 8) * g.per_xcd + id / 8;
-    if (id >= 8 * g.per_xcd || tile >= g.ntm * g.ntn) return;
+    if (tile < 0 || tile >= g.ntm * g.ntn) return;
     const int tm = tile / g.ntn, tn = tile % g.ntn;
     const int m0 = tm * BM, n0 = tn * BN;
-    const int z = second ? (int)blockIdx.y - splits0 : (int)blockIdx.y;
+    const int z = second ? zz - splits0 : zz;
     const int kbeg = z * g.kper;
     const int kend = min(g.K, kbeg + g.kper);
     const bool fast = (g.lda % 4 == 0) && ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0) &&
@@ -518,9 +534,21 @@ hipError_t launch_gemm_bf16x3_ws_variant(const GemmArgs &a, hipStream_t s, const
             raised = true;
         }
     }
-    const int gx = 8 * (g0.per_xcd > g1.per_xcd ? g0.per_xcd : g1.per_xcd);
-    dim3 grid((unsigned)gx, (unsigned)(splits0 + splits1), 1);
-    hipLaunchKernelGGL(kern, grid, dim3(64 * (WGM * WGN + NP)), smem, s, g0, g1, splits0);
+    const int S = splits0 + splits1;
+    const long nt0 = (long)g0.ntm * g0.ntn, nt1 = (long)g1.ntm * g1.ntn;
+    const long ntmax = nt0 > nt1 ? nt0 : nt1;
+    // K-slab-per-XCD mapping needs the split count to divide 8 or be a multiple of it
+    const int xcd_split = (S > 1 && (S % 8 == 0 || 8 % S == 0)) ? 1 : 0;
+    dim3 grid;
+    if (xcd_split) {
+        // flat grid: (tiles rounded so that every XCD slot exists) x splits
+        const long per = (S % 8 == 0) ? ntmax * (S / 8) : (ntmax + (8 / S) - 1) / (8 / S);
+        grid = dim3((unsigned)(8 * per), 1, 1);
+    } else {
+        const int gx = 8 * (g0.per_xcd > g1.per_xcd ? g0.per_xcd : g1.per_xcd);
+        grid = dim3((unsigned)gx, (unsigned)S, 1);
+    }
+    hipLaunchKernelGGL(kern, grid, dim3(64 * (WGM * WGN + NP)), smem, s, g0, g1, splits0, S, xcd_split);
     return hipGetLastError();
 }
 
