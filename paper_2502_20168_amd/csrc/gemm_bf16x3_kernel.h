@@ -54,14 +54,14 @@ __device__ __forceinline__ Split4 split3(float4 v)
 
 // Stages one R x BK fp32 operand tile: global -> registers (fp32) -> split -> three LDS planes.
 // k-contiguous source: a thread handles units of 1 row x 4 k.  Row-contiguous source: units of
-// 4 rows x KU k (KU float4 loads, transposed in registers), KU = 4 or 2; neighbouring lanes take
+// 4 rows x KU k (KU float4 loads, transposed in registers), KU = 4, 2 or 1; neighbouring lanes take
 // neighbouring k blocks of the same rows, so that their LDS writes fall into distinct banks while
 // the lanes that share a k row still read one contiguous 128-byte line.
 template <int R, int BK, bool KC, int NT>
 struct SplitLoader {
     static constexpr int NV = R * BK / 4 / NT;
     static_assert(NV >= 1 && NV * NT * 4 == R * BK, "tile must be a multiple of the workgroup's float4 loads");
-    static constexpr int KU = (NV % 4 == 0) ? 4 : 2;
+    static constexpr int KU = (NV % 4 == 0) ? 4 : (NV % 2 == 0) ? 2 : 1;
     static_assert(KC || NV % KU == 0, "row-contiguous operands are staged in 4 x KU blocks");
     static constexpr int S = BK + 8;              // plane row stride in halves
     static constexpr int PLANE = R * S;           // halves per plane
@@ -141,10 +141,12 @@ struct SplitLoader {
                         __bf16 *dst = lds + s * PLANE + (4 * rq + q) * S + KU * kq;
                         if (KU == 4) {
                             *reinterpret_cast<bf16x4 *>(dst) = sp.p[s];
-                        } else {
+                        } else if (KU == 2) {
                             bf16x2 two;
                             two[0] = sp.p[s][0]; two[1] = sp.p[s][1];
                             *reinterpret_cast<bf16x2 *>(dst) = two;
+                        } else {
+                            *dst = sp.p[s][0];
                         }
                     }
                 }

@@ -83,9 +83,10 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
         return dispatch_f32<64, 64, 16, 2, 2>(a, s);
     }
     // measured on MI355X at the benchmark shapes: 128x128x32 tiles, 4 consumer + 4 producer
-    // wavefronts; 128x64 tiles when the wide tile would leave CUs without work
+    // wavefronts; 64x128 tiles with 8 producer wavefronts (staging per multiply-add is 1.5x there)
+    // when the wide tile would leave CUs without work
     if (tiles128 >= 200) return dispatch_bf16x3<128, 128, 32, 2, 2, 4, 2>(a, s);
-    return dispatch_bf16x3<128, 64, 32, 4, 1, 4, 2>(a, s);
+    return dispatch_bf16x3<64, 128, 32, 2, 2, 8, 2>(a, s);
 }
 
 // Two K = T reductions (both operands row-contiguous, no epilogue) in one launch.
