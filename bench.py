@@ -199,8 +199,9 @@ def scan_cold_warm(ssm, torch, d, Bt, L, P, fwd_bytes, rev_bytes, iters=40):
             ms = timed(fn, mode == "cold")
             out["%s_%s_us" % (mode, name)] = round(ms * 1e3, 2)
             out["%s_%s_GBs" % (mode, name)] = round(nbytes / (ms * 1e-3) / 1e9, 1)
-    out["note"] = ("warm/cold figures time clear+scan launches of the scan-level entry points back to back; "
-                   "in_path figures are single launches between events inside the full pass")
+    out["note"] = ("warm/cold figures time launches of the scan-level entry points back to back (the reverse one "
+                   "includes its small partial-sum reduction kernel); in_path figures are single launches between "
+                   "events inside the full pass")
     return out
 
 

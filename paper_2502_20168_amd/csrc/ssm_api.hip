@@ -400,7 +400,8 @@ ssm_status ssm_scan_states(const ssm_c64 *A_bar, ssm_c64 *v, const uint8_t *is_f
     char *ws = static_cast<char *>(workspace);
     WsHeader *hdr = reinterpret_cast<WsHeader *>(ws + lo.hdr);
     ScanDesc *desc = reinterpret_cast<ScanDesc *>(ws + lo.desc);
-    HIP_TRY(launch_clear(hdr, ws + lo.ticket, lo.desc + up(lo.plan.desc_bytes) - lo.ticket, s));
+    if (lo.plan.nTB > 1)
+        HIP_TRY(launch_clear(hdr, ws + lo.ticket, lo.desc + up(lo.plan.desc_bytes) - lo.ticket, s));
     ScanArgs sa{};
     sa.in = reinterpret_cast<const float2 *>(v); sa.out = reinterpret_cast<float2 *>(v);
     sa.lam = reinterpret_cast<const float2 *>(A_bar); sa.is_first = is_first;
@@ -431,7 +432,8 @@ ssm_status ssm_scan_states_reverse(const ssm_c64 *A_bar, ssm_c64 *gx, const ssm_
     WsHeader *hdr = reinterpret_cast<WsHeader *>(ws + lo.hdr);
     ScanDesc *desc = reinterpret_cast<ScanDesc *>(ws + lo.desc);
     float2 *dApart = reinterpret_cast<float2 *>(ws + lo.dApart);
-    HIP_TRY(launch_clear(hdr, ws + lo.ticket, lo.desc + up(lo.plan.desc_bytes) - lo.ticket, s));
+    if (lo.plan.nTB > 1)
+        HIP_TRY(launch_clear(hdr, ws + lo.ticket, lo.desc + up(lo.plan.desc_bytes) - lo.ticket, s));
     ScanArgs sa{};
     sa.in = reinterpret_cast<const float2 *>(gx); sa.out = reinterpret_cast<float2 *>(gx);
     sa.lam = reinterpret_cast<const float2 *>(A_bar); sa.is_first = is_first;

@@ -70,7 +70,7 @@ struct ScanArgs {
     float2 *dx0;             // reverse only, or null
     ScanDesc *desc;
     uint32_t *ticket;        // per-chain counters, SCAN_TICKET_STRIDE apart (nTB > 1 only)
-    uint32_t *err;
+    uint32_t *err;           // &WsHeader::err (the magic word follows it)
     int Bt, L, P, pxb, cy, nPX, nTB;
     uint32_t spin_limit;
 };
