@@ -255,3 +255,41 @@ def test_bounded_wait_reports_instead_of_hanging():
     out = ssm.ssm_scan_fwd(d["Lambda"], d["B"], d["C"], d["D"], d["log_delta"], d["u"], d["is_first"], d["x0"],
                            workspace=ws)
     assert ssm.ssm_workspace_status(ws) == ssm.SSM_OK
+
+
+def test_two_stacked_layers_at_the_vision_shape():
+    """Vision-task shape of the paper's hyper-parameter table (layer width 1024, state 512, two SSM
+    layers): layer 2 consumes layer 1's output, the gradient pass chains back through both.  The
+    oracle is chained the same way, so this checks H != P at the large width and back-to-back calls
+    on one stream sharing a workspace."""
+    import torch
+    Bt, L, H, P = 8, 64, 1024, 512
+    w1 = wl.custom("vision_l1", Bt, L, H, P, p_reset=0.02, force_first=True, seed=31)
+    w2 = wl.custom("vision_l2", Bt, L, H, P, p_reset=0.02, force_first=True, seed=32)
+    i1, i2 = wl.gen_inputs(w1), wl.gen_inputs(w2)
+    i2["is_first"] = i1["is_first"]                       # same episode boundaries for both layers
+    # oracle: forward 1 -> forward 2 -> backward 2 -> backward 1
+    nt = 8
+    r1 = orc.forward(i1["Lambda"], i1["B"], i1["C"], i1["D"], i1["log_delta"], i1["u"], i1["is_first"], None, nt)
+    u2 = r1["y"].astype(np.float32)                        # layer 2 sees the fp32-rounded activations
+    r2 = orc.forward(i2["Lambda"], i2["B"], i2["C"], i2["D"], i2["log_delta"], u2, i2["is_first"], None, nt)
+    g2 = orc.backward(i2["Lambda"], i2["B"], i2["C"], i2["D"], i2["log_delta"], u2, i2["is_first"], None,
+                      r2["x"], i2["dy"], nt)
+    g1 = orc.backward(i1["Lambda"], i1["B"], i1["C"], i1["D"], i1["log_delta"], i1["u"], i1["is_first"], None,
+                      r1["x"], g2["du"].astype(np.float32), nt)
+    d1, d2 = ssm.to_device(i1), ssm.to_device(i2)
+    ws_f = ssm.alloc_workspace(Bt, L, H, P, False)
+    ws_b = ssm.alloc_workspace(Bt, L, H, P, True)
+    f1 = ssm.ssm_scan_fwd(d1["Lambda"], d1["B"], d1["C"], d1["D"], d1["log_delta"], d1["u"], d1["is_first"], None,
+                          workspace=ws_f)
+    f2 = ssm.ssm_scan_fwd(d2["Lambda"], d2["B"], d2["C"], d2["D"], d2["log_delta"], f1["y"], d1["is_first"], None,
+                          workspace=ws_f)
+    b2 = ssm.ssm_scan_bwd(d2["Lambda"], d2["B"], d2["C"], d2["D"], d2["log_delta"], f1["y"], d1["is_first"], None,
+                          f2["x"], d2["dy"], workspace=ws_b)
+    b1 = ssm.ssm_scan_bwd(d1["Lambda"], d1["B"], d1["C"], d1["D"], d1["log_delta"], d1["u"], d1["is_first"], None,
+                          f1["x"], b2["du"], workspace=ws_b)
+    torch.cuda.synchronize()
+    assert_close(f2["y"].cpu().numpy(), r2["y"], TOL_FWD, "layer 2 y")
+    assert_close(b2["dC"].cpu().numpy(), g2["dC"], TOL_GRAD, "layer 2 dC")
+    for k in ("du", "dLambda", "dB", "dC", "dD", "dlog_delta"):
+        assert_close(b1[k].cpu().numpy(), g1[k], TOL_GRAD, "layer 1 " + k)
