@@ -134,6 +134,25 @@ ssm_status ssm_scan_states_reverse(const ssm_c64 *A_bar, ssm_c64 *gx, const ssm_
                                    int64_t Bt, int64_t L, int64_t P, ssm_c64 *dA_bar, ssm_c64 *dx0,
                                    void *workspace, size_t ws_bytes, void *stream);
 
+/* Step (recurrent) mode: one transition of the sequence model, x_t, y_t = SSM(u_t, is_first_t,
+ * x_{t-1}) (the sequence-model line of Eq. 8), as the imagination roll-out of the actor-critic
+ * stage needs it: there the next input depends on the previous output, so the H roll-out steps
+ * cannot be scanned (Methodology, "Actor-Critic Learning", Eq. 13).
+ *   x[b,:] = (is_first[b] ? 0 : A_bar (.) x_prev[b,:]) + B_bar u[b,:],   y[b,:] = Re(C x[b,:]) + D (.) u[b,:]
+ * The discretised, packed parameters are prepared once per roll-out into a caller-owned plan
+ * buffer of ssm_step_plan_bytes(H, P) bytes (256-byte aligned) and reused by every step.
+ *   ssm_step_prepare  in : Lambda [P] c64, B [P,H] c64, C [H,P] c64, log_delta [P] f32;  out: plan
+ *   ssm_step          in : plan, D [H] f32, u [Bt,H] f32, x_prev [Bt,P] c64 (NULL = zeros),
+ *                          is_first [Bt] u8 (NULL = none)
+ *                     out: x [Bt,P] c64 (must not alias x_prev), y [Bt,H] f32                     */
+size_t ssm_step_plan_bytes(int64_t H, int64_t P);
+ssm_status ssm_step_prepare(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C,
+                            const float *log_delta, int64_t H, int64_t P,
+                            void *plan, size_t plan_bytes, void *stream);
+ssm_status ssm_step(const void *plan, size_t plan_bytes, const float *D, const float *u,
+                    const ssm_c64 *x_prev, const uint8_t *is_first, int64_t Bt, int64_t H, int64_t P,
+                    ssm_c64 *x, float *y, void *stream);
+
 /* Measurement aids: the same code path as ssm_scan_fwd / ssm_scan_bwd, with a HIP event recorded
  * on `stream` around every kernel.  They wait for the stream before returning and write the
  * milliseconds of each stage to the HOST array stage_ms:

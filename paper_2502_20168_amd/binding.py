@@ -27,7 +27,7 @@ BWD_STAGE_NAMES = ("discretize_pack_dD", "gx", "reverse_scan", "du", "dC_dBbar_p
 
 EXPORTS = ("ssm_strerror", "ssm_version", "ssm_workspace_bytes", "ssm_discretize", "ssm_scan_fwd",
            "ssm_scan_bwd", "ssm_scan_states", "ssm_scan_states_reverse", "ssm_scan_fwd_profiled",
-           "ssm_scan_bwd_profiled", "ssm_workspace_status")
+           "ssm_scan_bwd_profiled", "ssm_workspace_status", "ssm_step_plan_bytes", "ssm_step_prepare", "ssm_step")
 
 _lib = None
 _vp, _i64, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t
@@ -70,6 +70,12 @@ def lib():
         L.ssm_scan_states_reverse.argtypes = [_vp] * 5 + [_i64] * 3 + [_vp, _vp, _vp, _sz, _vp]
         L.ssm_workspace_status.restype = ctypes.c_int
         L.ssm_workspace_status.argtypes = [_vp, _vp]
+        L.ssm_step_plan_bytes.restype = _sz
+        L.ssm_step_plan_bytes.argtypes = [_i64, _i64]
+        L.ssm_step_prepare.restype = ctypes.c_int
+        L.ssm_step_prepare.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _vp, _sz, _vp]
+        L.ssm_step.restype = ctypes.c_int
+        L.ssm_step.argtypes = [_vp, _sz, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp]
         _lib = L
     return _lib
 
@@ -250,6 +256,45 @@ def ssm_scan_states_reverse(A_bar, gx, x, is_first=None, x0=None, *, want_dx0=Tr
     if rc != SSM_OK:
         raise SsmError(rc, "ssm_scan_states_reverse")
     return gx, dA, dx0
+
+
+def ssm_step_plan_bytes(H: int, P: int) -> int:
+    return int(lib().ssm_step_plan_bytes(H, P))
+
+
+def ssm_step_prepare(Lambda, B, C, log_delta, stream=None):
+    """Discretise and pack the parameters once per roll-out.  Returns the plan (a cuda byte tensor)."""
+    torch = _torch()
+    P, H = B.shape
+    _chk(Lambda, torch.complex64, (P,), "Lambda")
+    _chk(B, torch.complex64, (P, H), "B")
+    _chk(C, torch.complex64, (H, P), "C")
+    _chk(log_delta, torch.float32, (P,), "log_delta")
+    plan = torch.empty(ssm_step_plan_bytes(H, P), dtype=torch.uint8, device=B.device)
+    rc = lib().ssm_step_prepare(_ptr(Lambda), _ptr(B), _ptr(C), _ptr(log_delta), H, P, _ptr(plan), plan.numel(),
+                                _stream(stream))
+    if rc != SSM_OK:
+        raise SsmError(rc, "ssm_step_prepare")
+    return plan
+
+
+def ssm_step(plan, D, u, x_prev=None, is_first=None, *, P=None, x=None, y=None, stream=None):
+    """One transition.  u [Bt,H], x_prev [Bt,P] or None, is_first [Bt] u8 or None.  Returns (x, y)."""
+    torch = _torch()
+    Bt, H = u.shape
+    if P is None:
+        P = x_prev.shape[1] if x_prev is not None else x.shape[1]
+    _chk(D, torch.float32, (H,), "D")
+    _chk(u, torch.float32, (Bt, H), "u")
+    _chk(x_prev, torch.complex64, (Bt, P), "x_prev")
+    _chk(is_first, torch.uint8, (Bt,), "is_first")
+    x = x if x is not None else torch.empty((Bt, P), dtype=torch.complex64, device=u.device)
+    y = y if y is not None else torch.empty_like(u)
+    rc = lib().ssm_step(_ptr(plan), plan.numel(), _ptr(D), _ptr(u), _ptr(x_prev), _ptr(is_first), Bt, H, P,
+                        _ptr(x), _ptr(y), _stream(stream))
+    if rc != SSM_OK:
+        raise SsmError(rc, "ssm_step")
+    return x, y
 
 
 def ssm_workspace_status(workspace, stream=None) -> int:

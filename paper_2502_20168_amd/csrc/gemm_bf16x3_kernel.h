@@ -155,175 +155,15 @@ struct SplitLoader {
     }
 };
 
-template <int BM, int BN, int BK, int WGM, int WGN, bool AKC, bool BKC, bool EPI, bool FAST>
-__device__ __forceinline__ void gemm_bf16x3_tile(const GemmDev &g, __bf16 *As, __bf16 *Bs, int m0, int n0,
-                                                 int z, int kbeg, int kend)
-{
-    constexpr int NT = 64 * WGM * WGN;
-    using LA = SplitLoader<BM, BK, AKC, NT>;
-    using LB = SplitLoader<BN, BK, BKC, NT>;
-    constexpr int S = BK + 8;
-    constexpr int STAGE_A = 3 * LA::PLANE, STAGE_B = 3 * LB::PLANE;
-    constexpr int WM = BM / WGM, WN = BN / WGN;
-    constexpr int MI = WM / 32, NI = WN / 32;
-    static_assert(MI >= 1 && NI >= 1 && WM % 32 == 0 && WN % 32 == 0 && BK % 16 == 0, "bad tile");
-
-    const int tid = threadIdx.x;
-    const int wave = tid >> 6, l = tid & 63;
-    const int wm = wave / WGN, wn = wave % WGN;
-    const int li = l & 31, hh = l >> 5;
-
-    LA la;
-    LB lb;
-    v16f acc[MI][NI];
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    const int nk = (kend > kbeg) ? (kend - kbeg + BK - 1) / BK : 0;
-    if (nk > 0) {
-        la.template load<FAST>(g.A, g.lda, m0, g.M, kbeg, kend, tid);
-        lb.template load<FAST>(g.B, g.ldb, n0, g.N, kbeg, kend, tid);
-        la.store(As, tid);
-        lb.store(Bs, tid);
-    }
-    __syncthreads();
-
-    for (int kt = 0; kt < nk; ++kt) {
-        const int cur = kt & 1;
-        if (kt + 1 < nk) {
-            la.template load<FAST>(g.A, g.lda, m0, g.M, kbeg + (kt + 1) * BK, kend, tid);
-            lb.template load<FAST>(g.B, g.ldb, n0, g.N, kbeg + (kt + 1) * BK, kend, tid);
-        }
-        // lane (li, hh) of a 32x32x16 bf16 MFMA holds row/column li, k = 8*hh .. 8*hh+7
-        const __bf16 *as = As + cur * STAGE_A + (wm * WM + li) * S + 8 * hh;
-        const __bf16 *bs = Bs + cur * STAGE_B + (wn * WN + li) * S + 8 * hh;
-#pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 a[MI][3], b[NI][3];
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int s = 0; s < 3; ++s)
-                    a[i][s] = *reinterpret_cast<const bf16x8 *>(as + s * LA::PLANE + i * 32 * S + ks * 16);
-#pragma unroll
-            for (int j = 0; j < NI; ++j)
-#pragma unroll
-                for (int s = 0; s < 3; ++s)
-                    b[j][s] = *reinterpret_cast<const bf16x8 *>(bs + s * LB::PLANE + j * 32 * S + ks * 16);
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int j = 0; j < NI; ++j) {
-                    v16f c = acc[i][j];
-                    // small partial products first
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][2], b[j][0], c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][1], b[j][1], c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][0], b[j][2], c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][1], b[j][0], c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][0], b[j][1], c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][0], b[j][0], c, 0, 0, 0);
-                    acc[i][j] = c;
-                }
-        }
-        if (kt + 1 < nk) {
-            la.store(As + (cur ^ 1) * STAGE_A, tid);
-            lb.store(Bs + (cur ^ 1) * STAGE_B, tid);
-        }
-        __syncthreads();
-    }
-
-    float *Cz = g.C + (long)z * g.M * g.ldc;
-#pragma unroll
-    for (int i = 0; i < MI; ++i)
-#pragma unroll
-        for (int j = 0; j < NI; ++j) {
-            const int col = n0 + wn * WN + j * 32 + li;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const long row = m0 + wm * WM + i * 32 + 8 * (r / 4) + 4 * hh + (r % 4);
-                if (FAST || (row < g.M && col < g.N)) {
-                    float v = acc[i][j][r];
-                    if (EPI) v += g.diag[col] * g.E[row * g.lde + col];
-                    Cz[row * g.ldc + col] = v;
-                }
-            }
-        }
-}
-
-template <int BM, int BN, int BK, int WGM, int WGN, bool AKC, bool BKC, bool EPI>
-__global__ void __launch_bounds__(64 * WGM * WGN) gemm_bf16x3_kernel(GemmDev g)
-{
-    constexpr int STAGE_A = 3 * BM * (BK + 8), STAGE_B = 3 * BN * (BK + 8);
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    __bf16 *As = reinterpret_cast<__bf16 *>(smem_raw);
-    __bf16 *Bs = As + 2 * STAGE_A;
-    (void)STAGE_B;
-
-    const int id = blockIdx.x;
-    const int tile = (id % 8) * g.per_xcd + id / 8;
-    if (tile >= g.ntm * g.ntn) return;
-    const int tm = tile / g.ntn, tn = tile % g.ntn;
-    const int m0 = tm * BM, n0 = tn * BN;
-    const int z = blockIdx.y;
-    const int kbeg = z * g.kper;
-    const int kend = min(g.K, kbeg + g.kper);
-
-    const bool fast = (g.lda % 4 == 0) && ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0) &&
-                      (g.ldb % 4 == 0) && ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0) &&
-                      (m0 + BM <= g.M) && (n0 + BN <= g.N) && ((kend - kbeg) % BK == 0);
-    if (fast)
-        gemm_bf16x3_tile<BM, BN, BK, WGM, WGN, AKC, BKC, EPI, true>(g, As, Bs, m0, n0, z, kbeg, kend);
-    else
-        gemm_bf16x3_tile<BM, BN, BK, WGM, WGN, AKC, BKC, EPI, false>(g, As, Bs, m0, n0, z, kbeg, kend);
-}
-
-template <int BM, int BN, int BK, int WGM, int WGN, bool AKC, bool BKC, bool EPI>
-hipError_t launch_gemm_bf16x3_variant(const GemmArgs &a, hipStream_t s)
-{
-    GemmDev g;
-    g.A = a.A; g.lda = a.lda; g.B = a.B; g.ldb = a.ldb; g.C = a.C; g.ldc = a.ldc;
-    g.diag = a.diag; g.E = a.E; g.lde = a.lde;
-    g.M = a.M; g.N = a.N; g.K = a.K;
-    const int splits = a.splits < 1 ? 1 : a.splits;
-    int kper = (a.K + splits - 1) / splits;
-    kper = (kper + BK - 1) / BK * BK;
-    g.kper = kper;
-    g.ntm = (a.M + BM - 1) / BM;
-    g.ntn = (a.N + BN - 1) / BN;
-    const long ntiles = (long)g.ntm * g.ntn;
-    g.per_xcd = (int)((ntiles + 7) / 8);
-    constexpr size_t smem = (size_t)2 * 3 * (BM + BN) * (BK + 8) * sizeof(__bf16);
-    static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS of a gfx950 CU");
-    auto kern = gemm_bf16x3_kernel<BM, BN, BK, WGM, WGN, AKC, BKC, EPI>;
-    if (smem > 64 * 1024) {
-        // raising the dynamic LDS limit is idempotent; doing it once per instantiation is enough
-        static bool raised = false;
-        if (!raised) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-            if (e != hipSuccess) return e;
-            raised = true;
-        }
-    }
-    dim3 grid((unsigned)(g.per_xcd * 8), (unsigned)splits, 1);
-    hipLaunchKernelGGL(kern, grid, dim3(64 * WGM * WGN), smem, s, g);
-    return hipGetLastError();
-}
-
-
 // ---------------------------------------------------------------------------------------------
-// Wavefront-specialised variant: a workgroup has WGM*WGN consumer wavefronts that only read
+// Wavefront specialisation: a workgroup has WGM*WGN consumer wavefronts that only read
 // operand fragments from LDS and issue MFMAs, and NP producer wavefronts that only stage tiles
 // (global load -> three-way split -> LDS).  A producer and a consumer share each SIMD, so the
 // VALU work of the split co-executes with the matrix instructions of the other wavefront.
 // LDS holds NS stages; in iteration kt the producers fill the stage of tile kt+NS-1 while the
 // consumers work on tile kt, with one workgroup barrier per K tile.
 // ---------------------------------------------------------------------------------------------
-template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, bool AKC, bool BKC, bool EPI, bool FAST>
+template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, bool AKC, bool BKC, int EPI, bool FAST>
 __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *smem, int m0, int n0, int z,
                                                     int kbeg, int kend)
 {
@@ -448,7 +288,7 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
                 const long row = m0 + wm * WM + i * 32 + 8 * (r / 4) + 4 * hh + (r % 4);
                 if (FAST || (row < g.M && col < g.N)) {
                     float v = acc[i][j][r];
-                    if (EPI) v += g.diag[col] * g.E[row * g.lde + col];
+                    v += gemm_epilogue_term<EPI>(g, row, col);
                     Cz[row * g.ldc + col] = v;
                 }
             }
@@ -457,7 +297,7 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
 
 // One launch can carry two independent problems of the same layout (used for the two K = T
 // reductions of the gradient pass): blockIdx.y < splits0 works on g0, the rest on g1.
-template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, bool AKC, bool BKC, bool EPI>
+template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, bool AKC, bool BKC, int EPI>
 __global__ void __launch_bounds__(64 * (WGM * WGN + NP)) gemm_bf16x3_ws_kernel(GemmDev g0, GemmDev g1, int splits0,
                                                                                  int splits_total, int xcd_split)
 {
@@ -502,7 +342,7 @@ inline GemmDev make_gemm_dev(const GemmArgs &a)
 {
     GemmDev g;
     g.A = a.A; g.lda = a.lda; g.B = a.B; g.ldb = a.ldb; g.C = a.C; g.ldc = a.ldc;
-    g.diag = a.diag; g.E = a.E; g.lde = a.lde;
+    g.diag = a.diag; g.E = a.E; g.lde = a.lde; g.rowflag = a.rowflag;
     g.M = a.M; g.N = a.N; g.K = a.K;
     const int splits = a.splits < 1 ? 1 : a.splits;
     int kper = (a.K + splits - 1) / splits;
@@ -516,7 +356,7 @@ inline GemmDev make_gemm_dev(const GemmArgs &a)
 }
 
 // b == nullptr: one problem.  Otherwise two problems with the same operand layouts, no epilogue.
-template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, bool AKC, bool BKC, bool EPI>
+template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, bool AKC, bool BKC, int EPI>
 hipError_t launch_gemm_bf16x3_ws_variant(const GemmArgs &a, hipStream_t s, const GemmArgs *b = nullptr)
 {
     const GemmDev g0 = make_gemm_dev<BM, BN, BK>(a);

@@ -28,7 +28,11 @@ int gemm_pick_splits(int64_t M, int64_t N, int64_t K)
 template <int BM, int BN, int BK, int WGM, int WGN>
 static hipError_t dispatch_f32(const GemmArgs &a, hipStream_t s)
 {
-    const bool epi = a.diag != nullptr;
+    const bool epi = a.epilogue == 1;
+    if (a.epilogue == 2) {
+        if (a.a_kcontig && a.b_kcontig) return launch_gemm_variant<BM, BN, BK, WGM, WGN, true, true, 2>(a, s);
+        return hipErrorInvalidValue;
+    }
     if (a.a_kcontig && a.b_kcontig)
         return epi ? launch_gemm_variant<BM, BN, BK, WGM, WGN, true, true, true>(a, s)
                    : launch_gemm_variant<BM, BN, BK, WGM, WGN, true, true, false>(a, s);
@@ -44,11 +48,16 @@ template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS>
 static hipError_t dispatch_bf16x3(const GemmArgs &a, hipStream_t s, const GemmArgs *b = nullptr)
 {
     if (b) {
-        if (a.a_kcontig || a.b_kcontig || b->a_kcontig || b->b_kcontig || a.diag || b->diag)
+        if (a.a_kcontig || a.b_kcontig || b->a_kcontig || b->b_kcontig || a.epilogue || b->epilogue)
             return hipErrorInvalidValue;
         return launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, false, false, false>(a, s, b);
     }
-    const bool epi = a.diag != nullptr;
+    const bool epi = a.epilogue == 1;
+    if (a.epilogue == 2) {
+        if (a.a_kcontig && a.b_kcontig)
+            return launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, true, true, 2>(a, s);
+        return hipErrorInvalidValue;
+    }
     if (a.a_kcontig && a.b_kcontig)
         return epi ? launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, true, true, true>(a, s)
                    : launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, true, true, false>(a, s);
@@ -69,7 +78,8 @@ static bool use_f32_mfma()
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
 {
     if (a.M <= 0 || a.N <= 0 || a.K <= 0) return hipErrorInvalidValue;
-    if (a.splits > 1 && a.diag) return hipErrorInvalidValue;
+    if (a.splits > 1 && a.epilogue) return hipErrorInvalidValue;
+    if (a.epilogue < 0 || a.epilogue > 2 || (a.epilogue && (!a.diag || !a.E))) return hipErrorInvalidValue;
     const long splits = a.splits < 1 ? 1 : a.splits;
     const long tiles128 = (long)((a.M + 127) / 128) * ((a.N + 127) / 128) * splits;
     if (use_f32_mfma()) {

@@ -25,9 +25,29 @@ struct GemmDev {
     const float *B; long ldb;
     float *C; long ldc;
     const float *diag; const float *E; long lde;
+    const uint8_t *rowflag;
     int M, N, K, kper;      // kper: K range per split (multiple of the K tile)
     int ntm, ntn, per_xcd;
 };
+
+// Term added to the accumulator when an output element is stored.
+//   EPI 0: nothing
+//   EPI 1: diag[col] * E[row, col]                       (D (.) u and D (.) dy)
+//   EPI 2: columns are interleaved (re, im) pairs of complex states; diag holds Abar as
+//          interleaved complex; adds [not rowflag[row]] * (Abar_p * E_p)[re or im]: the carried
+//          state Abar x_{t-1} of one recurrence step (Eq. 3, first line)
+template <int EPI>
+__device__ __forceinline__ float gemm_epilogue_term(const GemmDev &g, long row, int col)
+{
+    if (EPI == 1) return g.diag[col] * g.E[row * g.lde + col];
+    if (EPI == 2) {
+        if (g.rowflag && g.rowflag[row]) return 0.f;
+        const float lr = g.diag[col & ~1], li = g.diag[col | 1];
+        const float own = g.E[row * g.lde + col], other = g.E[row * g.lde + (col ^ 1)];
+        return (col & 1) ? fmaf(lr, own, li * other) : fmaf(lr, own, -li * other);
+    }
+    return 0.f;
+}
 
 // Stages one R x BK operand tile through registers.
 // KC = true : global X[row*ld + k]  (k contiguous)   -> float4 along k, transposed into LDS
@@ -98,7 +118,7 @@ struct TileLoader {
 // its scattered 4-byte writes spread over the banks, a multiple of 4 for the 16-byte writes.
 template <int R, bool KC> struct LdsStride { static constexpr int value = KC ? R + 1 : R + 4; };
 
-template <int BM, int BN, int BK, int WGM, int WGN, bool AKC, bool BKC, bool EPI, bool FAST>
+template <int BM, int BN, int BK, int WGM, int WGN, bool AKC, bool BKC, int EPI, bool FAST>
 __device__ __forceinline__ void gemm_tile(const GemmDev &g, float *As, float *Bs, int m0, int n0, int z,
                                           int kbeg, int kend)
 {
@@ -174,14 +194,14 @@ __device__ __forceinline__ void gemm_tile(const GemmDev &g, float *As, float *Bs
                 const long row = m0 + wm * WM + i * 32 + 8 * (r / 4) + 4 * hh + (r % 4);
                 if (FAST || (row < g.M && col < g.N)) {
                     float v = acc[i][j][r];
-                    if (EPI) v += g.diag[col] * g.E[row * g.lde + col];
+                    v += gemm_epilogue_term<EPI>(g, row, col);
                     Cz[row * g.ldc + col] = v;
                 }
             }
         }
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, bool AKC, bool BKC, bool EPI>
+template <int BM, int BN, int BK, int WGM, int WGN, bool AKC, bool BKC, int EPI>
 __global__ void __launch_bounds__(64 * WGM * WGN) gemm_f32_kernel(GemmDev g)
 {
     constexpr int SA = LdsStride<BM, AKC>::value, SB = LdsStride<BN, BKC>::value;
@@ -209,12 +229,12 @@ __global__ void __launch_bounds__(64 * WGM * WGN) gemm_f32_kernel(GemmDev g)
         gemm_tile<BM, BN, BK, WGM, WGN, AKC, BKC, EPI, false>(g, As, Bs, m0, n0, z, kbeg, kend);
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, bool AKC, bool BKC, bool EPI>
+template <int BM, int BN, int BK, int WGM, int WGN, bool AKC, bool BKC, int EPI>
 hipError_t launch_gemm_variant(const GemmArgs &a, hipStream_t s)
 {
     GemmDev g;
     g.A = a.A; g.lda = a.lda; g.B = a.B; g.ldb = a.ldb; g.C = a.C; g.ldc = a.ldc;
-    g.diag = a.diag; g.E = a.E; g.lde = a.lde;
+    g.diag = a.diag; g.E = a.E; g.lde = a.lde; g.rowflag = a.rowflag;
     g.M = a.M; g.N = a.N; g.K = a.K;
     const int splits = a.splits < 1 ? 1 : a.splits;
     int kper = (a.K + splits - 1) / splits;

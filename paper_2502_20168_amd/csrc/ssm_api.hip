@@ -156,7 +156,7 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     GemmArgs g2{};
     g2.A = reinterpret_cast<const float *>(xs); g2.lda = 2 * P; g2.a_kcontig = 1;
     g2.B = Cc; g2.ldb = 2 * P; g2.b_kcontig = 1;
-    g2.C = y; g2.ldc = H; g2.diag = D; g2.E = u; g2.lde = H;
+    g2.C = y; g2.ldc = H; g2.diag = D; g2.E = u; g2.lde = H; g2.epilogue = 1;
     g2.M = T; g2.N = (int)H; g2.K = (int)(2 * P); g2.splits = 1;
     HIP_TRY(launch_gemm(g2, s));
     MARK();
@@ -234,7 +234,7 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     GemmArgs g5{};
     g5.A = reinterpret_cast<const float *>(chi); g5.lda = 2 * P; g5.a_kcontig = 1;
     g5.B = Bri; g5.ldb = H; g5.b_kcontig = 0;
-    g5.C = du; g5.ldc = H; g5.diag = D; g5.E = dy; g5.lde = H;
+    g5.C = du; g5.ldc = H; g5.diag = D; g5.E = dy; g5.lde = H; g5.epilogue = 1;
     g5.M = T; g5.N = (int)H; g5.K = (int)(2 * P); g5.splits = 1;
     HIP_TRY(launch_gemm(g5, s));
     MARK();
@@ -447,6 +447,87 @@ ssm_status ssm_scan_states_reverse(const ssm_c64 *A_bar, ssm_c64 *gx, const ssm_
     HIP_TRY(launch_scan(sa, true, s));
     HIP_TRY(launch_reduce_partials(dApart, (int64_t)Bt * lo.plan.nTB, P,
                                    reinterpret_cast<float2 *>(dA_bar), s));
+    return SSM_OK;
+}
+
+namespace {
+struct StepPlan { size_t lam, Bri, Cc, total; };
+bool make_step_plan(int64_t H, int64_t P, StepPlan &o)
+{
+    if (H <= 0 || P <= 0 || H > SSM_MAX_WIDTH || P > SSM_MAX_WIDTH) return false;
+    size_t off = 0;
+    o.lam = off; off += up((size_t)P * 8);
+    o.Bri = off; off += up((size_t)2 * P * H * 4);
+    o.Cc = off; off += up((size_t)2 * P * H * 4);
+    o.total = off;
+    return true;
+}
+}  // namespace
+
+size_t ssm_step_plan_bytes(int64_t H, int64_t P)
+{
+    StepPlan pl;
+    return make_step_plan(H, P, pl) ? pl.total : 0;
+}
+
+ssm_status ssm_step_prepare(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C,
+                            const float *log_delta, int64_t H, int64_t P,
+                            void *plan, size_t plan_bytes, void *stream)
+{
+    if (!Lambda || !B || !C || !log_delta) return SSM_ERR_INVALID_ARG;
+    if (H <= 0 || P <= 0) return SSM_ERR_INVALID_ARG;
+    StepPlan pl;
+    if (!make_step_plan(H, P, pl)) return SSM_ERR_UNSUPPORTED;
+    if (misaligned(Lambda, 8) || misaligned(B, 8) || misaligned(C, 8) || misaligned(log_delta, 4))
+        return SSM_ERR_INVALID_ARG;
+    if (!plan || misaligned(plan, ALIGN) || plan_bytes < pl.total) return SSM_ERR_WORKSPACE;
+    char *pb = static_cast<char *>(plan);
+    PrepArgs pa{};
+    pa.Lambda = reinterpret_cast<const float2 *>(Lambda); pa.B = reinterpret_cast<const float2 *>(B);
+    pa.C = reinterpret_cast<const float2 *>(C); pa.log_delta = log_delta;
+    pa.P = (int)P; pa.H = (int)H;
+    pa.lam_bar = reinterpret_cast<float2 *>(pb + pl.lam);
+    pa.Bbar_ri = reinterpret_cast<float *>(pb + pl.Bri);
+    pa.Cc = reinterpret_cast<float *>(pb + pl.Cc);
+    HIP_TRY(launch_prep(pa, static_cast<hipStream_t>(stream)));
+    return SSM_OK;
+}
+
+ssm_status ssm_step(const void *plan, size_t plan_bytes, const float *D, const float *u,
+                    const ssm_c64 *x_prev, const uint8_t *is_first, int64_t Bt, int64_t H, int64_t P,
+                    ssm_c64 *x, float *y, void *stream)
+{
+    if (!D || !u || !x || !y) return SSM_ERR_INVALID_ARG;
+    ssm_status st = check_dims(Bt, 1, H, P);
+    if (st != SSM_OK) return st;
+    StepPlan pl;
+    if (!make_step_plan(H, P, pl)) return SSM_ERR_UNSUPPORTED;
+    if (misaligned(D, 4) || misaligned(u, 4) || misaligned(x_prev, 8) || misaligned(x, 8) || misaligned(y, 4) ||
+        (x_prev && x_prev == x))
+        return SSM_ERR_INVALID_ARG;
+    if (!plan || misaligned(plan, ALIGN) || plan_bytes < pl.total) return SSM_ERR_WORKSPACE;
+    const char *pb = static_cast<const char *>(plan);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // x = Bbar u (+ Abar (.) x_prev where the sequence continues)          (Eq. 3, first line)
+    GemmArgs g1{};
+    g1.A = u; g1.lda = H; g1.a_kcontig = 1;
+    g1.B = reinterpret_cast<const float *>(pb + pl.Bri); g1.ldb = H; g1.b_kcontig = 1;
+    g1.C = reinterpret_cast<float *>(x); g1.ldc = 2 * P;
+    g1.M = (int)Bt; g1.N = (int)(2 * P); g1.K = (int)H; g1.splits = 1;
+    if (x_prev) {
+        g1.epilogue = 2;
+        g1.diag = reinterpret_cast<const float *>(pb + pl.lam);
+        g1.E = reinterpret_cast<const float *>(x_prev); g1.lde = 2 * P;
+        g1.rowflag = is_first;
+    }
+    HIP_TRY(launch_gemm(g1, s));
+    // y = Re(C x) + D (.) u                                                 (Eq. 3, second line)
+    GemmArgs g2{};
+    g2.A = reinterpret_cast<const float *>(x); g2.lda = 2 * P; g2.a_kcontig = 1;
+    g2.B = reinterpret_cast<const float *>(pb + pl.Cc); g2.ldb = 2 * P; g2.b_kcontig = 1;
+    g2.C = y; g2.ldc = H; g2.diag = D; g2.E = u; g2.lde = H; g2.epilogue = 1;
+    g2.M = (int)Bt; g2.N = (int)H; g2.K = (int)(2 * P); g2.splits = 1;
+    HIP_TRY(launch_gemm(g2, s));
     return SSM_OK;
 }
 

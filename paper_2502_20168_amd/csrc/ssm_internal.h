@@ -9,7 +9,9 @@
 namespace ssm {
 
 // ---------------------------------------------------------------------------------------------
-// fp32 MFMA GEMM:  C[m,n] = sum_k A(m,k) * B(n,k)  (+ diag[n] * E[m,n])
+// Projection GEMM:  C[m,n] = sum_k A(m,k) * B(n,k)  (+ epilogue term)
+// epilogue 0: none; 1: + diag[n] * E[m,n]; 2: + [not rowflag[m]] * (Abar (.) E)[m,n] with diag = Abar
+// as interleaved complex and the columns of C and E interleaved (re, im) pairs (one recurrence step)
 // A(m,k) = a_kcontig ? A[m*lda + k] : A[k*lda + m];  B(n,k) = b_kcontig ? B[n*ldb + k] : B[k*ldb + n]
 // splits > 1: split z covers a contiguous K range and writes its own slab C + z*M*ldc
 // (no epilogue term in that case); the caller reduces the slabs.
@@ -19,6 +21,7 @@ struct GemmArgs {
     const float *B; int64_t ldb; int b_kcontig;
     float *C; int64_t ldc;
     const float *diag; const float *E; int64_t lde;
+    int epilogue; const uint8_t *rowflag;
     int M, N, K, splits;
 };
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t s);

@@ -108,6 +108,16 @@ def test_other_entry_points_argument_errors(lib):
     assert lib.ssm_scan_states_reverse(FAKE, FAKE, FAKE, None, None, 2, 8, 4, FAKE, None, FAKE, 16,
                                        None) == ssm.SSM_ERR_WORKSPACE
     assert lib.ssm_workspace_status(None, None) == ssm.SSM_ERR_WORKSPACE
+    # step mode
+    need = ssm.ssm_step_plan_bytes(4, 4)
+    assert need > 0 and ssm.ssm_step_plan_bytes(0, 4) == 0 and ssm.ssm_step_plan_bytes(4, 1 << 17) == 0
+    assert lib.ssm_step_prepare(None, FAKE, FAKE, FAKE, 4, 4, FAKE, need, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_step_prepare(FAKE, FAKE, FAKE, FAKE, 4, 4, FAKE, need - 1, None) == ssm.SSM_ERR_WORKSPACE
+    assert lib.ssm_step_prepare(FAKE, FAKE, FAKE, FAKE, 4, 4, None, need, None) == ssm.SSM_ERR_WORKSPACE
+    assert lib.ssm_step(FAKE, need, None, FAKE, None, None, 2, 4, 4, FAKE, FAKE, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_step(FAKE, need, FAKE, FAKE, None, None, 0, 4, 4, FAKE, FAKE, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_step(FAKE, need - 1, FAKE, FAKE, None, None, 2, 4, 4, FAKE, FAKE, None) == ssm.SSM_ERR_WORKSPACE
+    assert lib.ssm_step(FAKE, need, FAKE, FAKE, FAKE + 512, None, 2, 4, 4, FAKE + 512, FAKE, None) == ssm.SSM_ERR_INVALID_ARG
 
 
 def test_binding_refuses_cpu_tensors(lib):

@@ -293,3 +293,30 @@ def test_two_stacked_layers_at_the_vision_shape():
     assert_close(b2["dC"].cpu().numpy(), g2["dC"], TOL_GRAD, "layer 2 dC")
     for k in ("du", "dLambda", "dB", "dC", "dD", "dlog_delta"):
         assert_close(b1[k].cpu().numpy(), g1[k], TOL_GRAD, "layer 1 " + k)
+
+
+@pytest.mark.parametrize("Bt,H,P,steps", [(1024, 512, 512, 10), (37, 50, 33, 6)])
+def test_step_mode_rollout_equals_oracle_sequence(Bt, H, P, steps):
+    """Imagination-style roll-out: `steps` dependent calls of ssm_step, each fed the previous
+    state, against the oracle run over the same inputs as one sequence (stepping and scanning
+    reach the same states)."""
+    import torch
+    w = wl.custom("step", Bt, steps, H, P, p_reset=0.1, with_x0=True, seed=23)
+    inp = wl.gen_inputs(w)
+    ref = orc.forward(inp["Lambda"], inp["B"], inp["C"], inp["D"], inp["log_delta"], inp["u"], inp["is_first"],
+                      inp["x0"], nthreads=8)
+    d = ssm.to_device(inp)
+    plan = ssm.ssm_step_prepare(d["Lambda"], d["B"], d["C"], d["log_delta"])
+    x = d["x0"]
+    ys = []
+    for t in range(steps):
+        x, y = ssm.ssm_step(plan, d["D"], d["u"][:, t].contiguous(), x, d["is_first"][:, t].contiguous())
+        ys.append(y)
+    torch.cuda.synchronize()
+    y_all = torch.stack(ys, 1).cpu().numpy()
+    assert_close(y_all, ref["y"], TOL_FWD, "step y")
+    assert_close(x.cpu().numpy(), ref["x_last"], TOL_FWD, "step x")
+    # no previous state and no flags: x = Bbar u
+    x1, y1 = ssm.ssm_step(plan, d["D"], d["u"][:, 0].contiguous(), None, None, P=P)
+    ref1 = orc.forward(inp["Lambda"], inp["B"], inp["C"], inp["D"], inp["log_delta"], inp["u"][:, :1], None, None)
+    assert_close(y1.cpu().numpy()[:, None], ref1["y"], TOL_FWD, "step y (no state)")
