@@ -110,14 +110,15 @@ def main():
     f32_path = os.environ.get("SSM_GEMM_F32", "") == "1"
     dom_ms = fs[1]
     dom_fp32_tflops = gemm_flops / (dom_ms * 1e-3) / 1e12
-    gemm_ms = {"project_in": fs[1], "project_out": fs[3], "gx": bs[1], "du": bs[3], "dC_dBbar_pair(2 gemms)": bs[4] / 2}
+    gemm_ms = {"project_in": fs[1], "project_out": fs[3], "gx_with_dC(2 gemms)": bs[1] / 2,
+               "du_with_dBbar(2 gemms)": bs[3] / 2}
     if f32_path:
         roofline = {"kernel": "gemm_f32_kernel<128,128,32,4,2,true,true,false> (input projection)",
                     "bound": "mfma", "achieved": round(dom_fp32_tflops, 2), "peak": PEAK_FP32_MFMA_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(dom_fp32_tflops / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": None}
     else:
         ach = BF16_PRODUCTS * dom_fp32_tflops
-        roofline = {"kernel": "gemm_bf16x3_ws_kernel<128,128,32,2,2,4,2,true,true,false> (input projection)",
+        roofline = {"kernel": "gemm_bf16x3_ws_kernel<128,128,32,2,2,8,2,3,-1> (input projection)",
                     "bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(ach / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": TRAFFIC_PROJECT_IN,
                     "note": "achieved counts the 6 bf16 MFMA products per fp32 multiply-add that the kernel "

@@ -58,7 +58,7 @@ typedef enum {
 
 /* Number of per-stage timings written by the *_profiled calls (see below). */
 #define SSM_FWD_STAGES 4
-#define SSM_BWD_STAGES 6
+#define SSM_BWD_STAGES 5
 
 /* Static description of an error code. Never NULL. */
 const char *ssm_strerror(int status);
@@ -157,8 +157,9 @@ ssm_status ssm_step(const void *plan, size_t plan_bytes, const float *D, const f
  * on `stream` around every kernel.  They wait for the stream before returning and write the
  * milliseconds of each stage to the HOST array stage_ms:
  *   forward : [0] discretise+pack, [1] input projection, [2] scan, [3] output projection
- *   backward: [0] discretise+pack and dD partials, [1] gx = C^H dy, [2] reverse scan, [3] du,
- *             [4] dC and dBbar partials (one launch), [5] parameter epilogue                    */
+ *   backward: [0] discretise+pack and dD partials, [1] gx = C^H dy with the dC partials (one
+ *             launch), [2] reverse scan, [3] du with the dBbar partials (one launch),
+ *             [4] parameter epilogue                                                            */
 ssm_status ssm_scan_fwd_profiled(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C,
                                  const float *D, const float *log_delta, const float *u,
                                  const uint8_t *is_first, const ssm_c64 *x0,

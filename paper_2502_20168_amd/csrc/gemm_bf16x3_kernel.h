@@ -165,7 +165,7 @@ struct SplitLoader {
 // ---------------------------------------------------------------------------------------------
 template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, bool AKC, bool BKC, int EPI, bool FAST>
 __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *smem, int m0, int n0, int z,
-                                                    int kbeg, int kend)
+                                                    int kbeg, int kend, int rot)
 {
     constexpr int NC = WGM * WGN;                 // consumer wavefronts
     constexpr int PT = 64 * NP;                   // producer threads
@@ -188,9 +188,13 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
         const int ptid = tid - 64 * NC;
         LA la[2];
         LB lb[2];
+        // The K tiles are visited in an order rotated by `rot`: workgroups that run side by side
+        // then read different 128-byte segments of their rows at any moment.  With a row pitch that
+        // is a multiple of 4 KB they would otherwise all hit the same memory channel.
         auto fetch = [&](int set, int t) {
-            la[set].template load<FAST>(g.A, g.lda, m0, g.M, kbeg + t * BK, kend, ptid);
-            lb[set].template load<FAST>(g.B, g.ldb, n0, g.N, kbeg + t * BK, kend, ptid);
+            const int k0 = kbeg + ((t + rot) % nk) * BK;
+            la[set].template load<FAST>(g.A, g.lda, m0, g.M, k0, kend, ptid);
+            lb[set].template load<FAST>(g.B, g.ldb, n0, g.N, k0, kend, ptid);
         };
         auto stash = [&](int set, int t) {
             __bf16 *st = smem + (t % NS) * STAGE;
@@ -242,39 +246,88 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
+    // Software pipeline over the 16-wide k steps: the fragments of step s+1 are requested from LDS
+    // before the 6*MI*NI matrix instructions of step s are issued, so the LDS latency (there is no
+    // second consumer wavefront on the SIMD to hide it) overlaps with matrix work.  At the last
+    // step of a K tile the workgroup barrier comes first: it both releases the stage just read
+    // (all its reads have completed, they feed the instructions about to be issued) and
+    // guarantees that the next stage is filled.
+    constexpr int KS = BK / 16;
+    bf16x8 fa[2][MI][3], fb[2][NI][3];
+    auto fetch_frags = [&](int set, int kt, int ks) {
         const __bf16 *st = smem + (kt % NS) * STAGE;
-        const __bf16 *as = st + (wm * WM + li) * S + 8 * hh;
-        const __bf16 *bs = st + STAGE_A + (wn * WN + li) * S + 8 * hh;
+        const __bf16 *as = st + (wm * WM + li) * S + 8 * hh + ks * 16;
+        const __bf16 *bs = st + STAGE_A + (wn * WN + li) * S + 8 * hh + ks * 16;
 #pragma unroll
-        for (int ks = 0; ks < BK / 16; ++ks) {
-            bf16x8 a[MI][3], b[NI][3];
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int s = 0; s < 3; ++s)
+                fa[set][i][s] = *reinterpret_cast<const bf16x8 *>(as + s * LA::PLANE + i * 32 * S);
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+            for (int s = 0; s < 3; ++s)
+                fb[set][j][s] = *reinterpret_cast<const bf16x8 *>(bs + s * LB::PLANE + j * 32 * S);
+    };
+    // the six products of one accumulator keep their order (smallest first); the MI*NI
+    // accumulators alternate so that consecutive matrix instructions are independent
+    auto multiply = [&](int set) {
+        constexpr int PA[6] = {2, 1, 0, 1, 0, 0}, PB[6] = {0, 1, 2, 0, 1, 0};
+#pragma unroll
+        for (int p = 0; p < 6; ++p)
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
-                for (int s = 0; s < 3; ++s)
-                    a[i][s] = *reinterpret_cast<const bf16x8 *>(as + s * LA::PLANE + i * 32 * S + ks * 16);
+                for (int j = 0; j < NI; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i][PA[p]], fb[set][j][PB[p]],
+                                                                        acc[i][j], 0, 0, 0);
+    };
+    static_assert(KS % 2 == 0 || KS == 1, "k steps per tile: 1 or even");
+    // issue order of one k step: a fragment read in the shadow of every second matrix
+    // instruction (a burst of reads would keep the wavefront from issuing matrix work)
+    auto interleave = [&]() {
 #pragma unroll
-            for (int j = 0; j < NI; ++j)
-#pragma unroll
-                for (int s = 0; s < 3; ++s)
-                    b[j][s] = *reinterpret_cast<const bf16x8 *>(bs + s * LB::PLANE + j * 32 * S + ks * 16);
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int j = 0; j < NI; ++j) {
-                    v16f c = acc[i][j];
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][2], b[j][0], c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][1], b[j][1], c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][0], b[j][2], c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][1], b[j][0], c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][0], b[j][1], c, 0, 0, 0);
-                    c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i][0], b[j][0], c, 0, 0, 0);
-                    acc[i][j] = c;
-                }
+        for (int q = 0; q < 3 * (MI + NI); ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, (6 * MI * NI) / (3 * (MI + NI)), 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
-        __syncthreads();
+    };
+
+    __syncthreads();
+    if (nk > 0) fetch_frags(0, 0, 0);
+    if (KS == 1) {
+        // one k step per tile: the register set alternates with the tile
+        int kt = 0;
+        for (; kt + 1 < nk; kt += 2) {
+            __syncthreads();
+            fetch_frags(1, kt + 1, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(0);
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+            if (kt + 2 < nk) fetch_frags(0, kt + 2, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (kt < nk) {
+            __syncthreads();
+            multiply(0);
+        }
+    } else {
+        for (int kt = 0; kt < nk; ++kt) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                if (ks + 1 < KS) {
+                    fetch_frags((ks + 1) & 1, kt, ks + 1);
+                } else {
+                    __syncthreads();
+                    fetch_frags(0, kt + 1, 0);   // past the last tile: a harmless read of a stale stage
+                }
+                multiply(ks & 1);
+                interleave();
+            }
+        }
     }
 
     float *Cz = g.C + (long)z * g.M * g.ldc;
@@ -295,46 +348,57 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
         }
 }
 
-// One launch can carry two independent problems of the same layout (used for the two K = T
-// reductions of the gradient pass): blockIdx.y < splits0 works on g0, the rest on g1.
-template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, bool AKC, bool BKC, int EPI>
-__global__ void __launch_bounds__(64 * (WGM * WGN + NP)) gemm_bf16x3_ws_kernel(GemmDev g0, GemmDev g1, int splits0,
-                                                                                 int splits_total, int xcd_split)
+// Operand layouts and epilogue of one problem, packed into one template argument.
+constexpr int gemm_layout(bool akc, bool bkc, int epi) { return (akc ? 1 : 0) | (bkc ? 2 : 0) | (epi << 2); }
+
+// Work item (tile, split) of the workgroup in slot q of XCD x.  Workgroup ids are dealt
+// round-robin to the 8 XCDs (id % 8), each with its own L2:
+//   mode 0 (no K splits): XCD x owns the contiguous band of tiles [x*nx, (x+1)*nx), so it re-reads
+//          only its band of A from its own L2;
+//   modes 1-3 (K splits): every XCD owns whole K slabs (or a contiguous run of tiles inside
+//          one), so each operand element is fetched from memory once instead of once per tile band.
+__device__ __forceinline__ void gemm_place(const GemmDev &g, int x, int q, int &z, int &tile)
 {
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);
-    // Workgroup ids are dealt round-robin to the 8 XCDs (id % 8).  Without K splits, XCD x gets
-    // the contiguous band of tiles [x*per_xcd, (x+1)*per_xcd) so that it re-reads only its band
-    // of A from its own L2.  With K splits (xcd_split != 0) every XCD instead owns whole K slabs:
-    // all tiles of one (problem, split) pair run on the same XCD(s), so each operand element is
-    // fetched from memory once instead of once per tile band.
-    int zz, tile;
-    if (xcd_split) {
-        const int id = blockIdx.x, xcd = id % 8, j = id / 8;
-        const int S = splits_total;
-        if (S % 8 == 0) { zz = xcd + 8 * (j % (S / 8)); tile = j / (S / 8); }
-        else { zz = xcd % S; tile = j * (8 / S) + xcd / S; }             // 8 % S == 0
-    } else {
-        zz = blockIdx.y;
-        const int id = blockIdx.x;
-        const GemmDev &gg = (zz >= splits0) ? g1 : g0;
-        tile = (id < 8 * gg.per_xcd) ? (id % 8) * gg.per_xcd + id / 8 : -1;
-    }
-    const bool second = zz >= splits0;
-    const GemmDev g = second ? g1 : g0;
-    if (tile < 0 || tile >= g.ntm * g.ntn) return;
+    if (g.mode == 0) { z = 0; tile = x * g.nx + q; }
+    else if (g.mode == 1) { z = x + 8 * (q % g.mpar); tile = q / g.mpar; }        // splits = 8 * mpar
+    else if (g.mode == 2) { z = x % g.splits; tile = q * g.mpar + x / g.splits; } // 8 = splits * mpar
+    else { const int item = x * g.nx + q; z = item / (g.ntm * g.ntn); tile = item % (g.ntm * g.ntn); }
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int LAY>
+__device__ __forceinline__ void gemm_bf16x3_ws_problem(const GemmDev &g, __bf16 *smem, int x, int q)
+{
+    constexpr bool AKC = (LAY & 1) != 0, BKC = (LAY & 2) != 0;
+    constexpr int EPI = LAY >> 2;
+    int z, tile;
+    gemm_place(g, x, q, z, tile);
+    if (q >= g.nx || z >= g.splits || tile >= g.ntm * g.ntn) return;
     const int tm = tile / g.ntn, tn = tile % g.ntn;
     const int m0 = tm * BM, n0 = tn * BN;
-    const int z = second ? zz - splits0 : zz;
     const int kbeg = z * g.kper;
     const int kend = min(g.K, kbeg + g.kper);
     const bool fast = (g.lda % 4 == 0) && ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0) &&
                       (g.ldb % 4 == 0) && ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0) &&
                       (m0 + BM <= g.M) && (n0 + BN <= g.N) && ((kend - kbeg) % BK == 0);
     if (fast)
-        gemm_bf16x3_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, AKC, BKC, EPI, true>(g, smem, m0, n0, z, kbeg, kend);
+        gemm_bf16x3_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, AKC, BKC, EPI, true>(g, smem, m0, n0, z, kbeg, kend, q + 4 * x);
     else
-        gemm_bf16x3_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, AKC, BKC, EPI, false>(g, smem, m0, n0, z, kbeg, kend);
+        gemm_bf16x3_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, AKC, BKC, EPI, false>(g, smem, m0, n0, z, kbeg, kend, q + 4 * x);
+}
+
+// One launch carries one problem (LAY1 < 0) or two independent ones (used for the gradient
+// pass, where pairs of products have the same inputs ready at the same time and one of them
+// alone would leave compute units idle).  The slots of the first problem come first in every XCD.
+template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int LAY0, int LAY1>
+__global__ void __launch_bounds__(64 * (WGM * WGN + NP)) gemm_bf16x3_ws_kernel(GemmDev g0, GemmDev g1)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);
+    const int x = blockIdx.x % 8, q = blockIdx.x / 8;
+    if (LAY1 < 0 || q < g1.slot0)
+        gemm_bf16x3_ws_problem<BM, BN, BK, WGM, WGN, NP, NS, LAY0>(g0, smem, x, q);
+    else
+        gemm_bf16x3_ws_problem<BM, BN, BK, WGM, WGN, NP, NS, (LAY1 < 0 ? LAY0 : LAY1)>(g1, smem, x, q - g1.slot0);
 }
 
 template <int BM, int BN, int BK>
@@ -352,20 +416,26 @@ inline GemmDev make_gemm_dev(const GemmArgs &a)
     g.ntn = (a.N + BN - 1) / BN;
     const long ntiles = (long)g.ntm * g.ntn;
     g.per_xcd = (int)((ntiles + 7) / 8);
+    g.splits = splits;
+    g.slot0 = 0;
+    if (splits == 1) { g.mode = 0; g.mpar = 0; g.nx = g.per_xcd; }
+    else if (splits % 8 == 0) { g.mode = 1; g.mpar = splits / 8; g.nx = (int)(ntiles * g.mpar); }
+    else if (8 % splits == 0) { g.mode = 2; g.mpar = 8 / splits; g.nx = (int)((ntiles + g.mpar - 1) / g.mpar); }
+    else { g.mode = 3; g.mpar = 0; g.nx = (int)((ntiles * splits + 7) / 8); }
     return g;
 }
 
-// b == nullptr: one problem.  Otherwise two problems with the same operand layouts, no epilogue.
-template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, bool AKC, bool BKC, int EPI>
+// b == nullptr: one problem (LAY1 is ignored and must be -1).
+template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int LAY0, int LAY1 = -1>
 hipError_t launch_gemm_bf16x3_ws_variant(const GemmArgs &a, hipStream_t s, const GemmArgs *b = nullptr)
 {
-    const GemmDev g0 = make_gemm_dev<BM, BN, BK>(a);
-    const GemmDev g1 = b ? make_gemm_dev<BM, BN, BK>(*b) : g0;
-    const int splits0 = a.splits < 1 ? 1 : a.splits;
-    const int splits1 = b ? (b->splits < 1 ? 1 : b->splits) : 0;
+    GemmDev g0 = make_gemm_dev<BM, BN, BK>(a);
+    GemmDev g1 = b ? make_gemm_dev<BM, BN, BK>(*b) : g0;
+    if ((LAY1 >= 0) != (b != nullptr)) return hipErrorInvalidValue;
+    g1.slot0 = g0.nx;
     constexpr size_t smem = (size_t)NS * 3 * (BM + BN) * (BK + 8) * sizeof(__bf16);
     static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS of a gfx950 CU");
-    auto kern = gemm_bf16x3_ws_kernel<BM, BN, BK, WGM, WGN, NP, NS, AKC, BKC, EPI>;
+    auto kern = gemm_bf16x3_ws_kernel<BM, BN, BK, WGM, WGN, NP, NS, LAY0, LAY1>;
     if (smem > 64 * 1024) {
         // raising the dynamic LDS limit is idempotent; doing it once per instantiation is enough
         static bool raised = false;
@@ -376,21 +446,9 @@ hipError_t launch_gemm_bf16x3_ws_variant(const GemmArgs &a, hipStream_t s, const
             raised = true;
         }
     }
-    const int S = splits0 + splits1;
-    const long nt0 = (long)g0.ntm * g0.ntn, nt1 = (long)g1.ntm * g1.ntn;
-    const long ntmax = nt0 > nt1 ? nt0 : nt1;
-    // K-slab-per-XCD mapping needs the split count to divide 8 or be a multiple of it
-    const int xcd_split = (S > 1 && (S % 8 == 0 || 8 % S == 0)) ? 1 : 0;
-    dim3 grid;
-    if (xcd_split) {
-        // flat grid: (tiles rounded so that every XCD slot exists) x splits
-        const long per = (S % 8 == 0) ? ntmax * (S / 8) : (ntmax + (8 / S) - 1) / (8 / S);
-        grid = dim3((unsigned)(8 * per), 1, 1);
-    } else {
-        const int gx = 8 * (g0.per_xcd > g1.per_xcd ? g0.per_xcd : g1.per_xcd);
-        grid = dim3((unsigned)gx, (unsigned)S, 1);
-    }
-    hipLaunchKernelGGL(kern, grid, dim3(64 * (WGM * WGN + NP)), smem, s, g0, g1, splits0, S, xcd_split);
+    const long slots = (long)g0.nx + (b ? g1.nx : 0);
+    if (slots <= 0 || 8 * slots > 0x7fffffffL) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(8 * slots)), dim3(64 * (WGM * WGN + NP)), smem, s, g0, g1);
     return hipGetLastError();
 }
 

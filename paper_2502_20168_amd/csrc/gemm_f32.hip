@@ -11,13 +11,14 @@
 
 namespace ssm {
 
-int gemm_pick_splits(int64_t M, int64_t N, int64_t K)
+int gemm_pick_splits(int64_t M, int64_t N, int64_t K, int64_t partner_tiles)
 {
-    // long reductions with a small result: enough K splits to give half of the CUs a workgroup
-    // (the two reductions of the gradient pass share one launch), keeping at least 256 rows of
-    // K per split
+    // A long reduction with a small result shares its launch with a product of partner_tiles
+    // 128x128 tiles: enough K splits that the two together fill the last round of workgroups
+    // on the 256 CUs, keeping at least 256 rows of K per split.
     const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
-    int64_t s = (128 + tiles - 1) / tiles;
+    const int64_t target = 256 - partner_tiles % 256;
+    int64_t s = (target + tiles / 2) / tiles;
     const int64_t maxs = (K + 255) / 256;
     if (s > maxs) s = maxs;
     if (s > 64) s = 64;
@@ -44,29 +45,27 @@ static hipError_t dispatch_f32(const GemmArgs &a, hipStream_t s)
     return hipErrorInvalidValue;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS>
-static hipError_t dispatch_bf16x3(const GemmArgs &a, hipStream_t s, const GemmArgs *b = nullptr)
+// Layout code of a problem, or -1 when the bf16x3 kernel has no instantiation for it.
+static int layout_of(const GemmArgs &a)
 {
-    if (b) {
-        if (a.a_kcontig || a.b_kcontig || b->a_kcontig || b->b_kcontig || a.epilogue || b->epilogue)
-            return hipErrorInvalidValue;
-        return launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, false, false, false>(a, s, b);
+    if (a.epilogue == 2) return (a.a_kcontig && a.b_kcontig) ? gemm_layout(true, true, 2) : -1;
+    if (a.a_kcontig) return gemm_layout(true, a.b_kcontig != 0, a.epilogue);
+    if (!a.b_kcontig && !a.epilogue) return gemm_layout(false, false, 0);
+    return -1;
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS>
+static hipError_t dispatch_bf16x3(const GemmArgs &a, hipStream_t s)
+{
+    switch (layout_of(a)) {
+#define SSM_CASE(akc, bkc, epi) \
+    case gemm_layout(akc, bkc, epi): \
+        return launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, gemm_layout(akc, bkc, epi)>(a, s);
+        SSM_CASE(true, true, 0) SSM_CASE(true, true, 1) SSM_CASE(true, true, 2)
+        SSM_CASE(true, false, 0) SSM_CASE(true, false, 1) SSM_CASE(false, false, 0)
+#undef SSM_CASE
+    default: return hipErrorInvalidValue;
     }
-    const bool epi = a.epilogue == 1;
-    if (a.epilogue == 2) {
-        if (a.a_kcontig && a.b_kcontig)
-            return launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, true, true, 2>(a, s);
-        return hipErrorInvalidValue;
-    }
-    if (a.a_kcontig && a.b_kcontig)
-        return epi ? launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, true, true, true>(a, s)
-                   : launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, true, true, false>(a, s);
-    if (a.a_kcontig && !a.b_kcontig)
-        return epi ? launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, true, false, true>(a, s)
-                   : launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, true, false, false>(a, s);
-    if (!a.a_kcontig && !a.b_kcontig && !epi)
-        return launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, false, false, false>(a, s);
-    return hipErrorInvalidValue;
 }
 
 static bool use_f32_mfma()
@@ -92,22 +91,29 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
         if (a.a_kcontig && a.b_kcontig) return dispatch_f32<64, 64, 32, 2, 2>(a, s);
         return dispatch_f32<64, 64, 16, 2, 2>(a, s);
     }
-    // measured on MI355X at the benchmark shapes: 128x128x32 tiles, 4 consumer + 4 producer
-    // wavefronts; 64x128 tiles with 8 producer wavefronts (staging per multiply-add is 1.5x there)
-    // when the wide tile would leave CUs without work
-    if (tiles128 >= 200) return dispatch_bf16x3<128, 128, 32, 2, 2, 4, 2>(a, s);
+    // measured on MI355X at the benchmark shapes: 128x128x32 tiles with 4 consumer and 8 producer
+    // wavefronts; 64x128 tiles (staging per multiply-add is 1.5x there) when the wide tile would
+    // leave CUs without work
+    if (tiles128 >= 200) return dispatch_bf16x3<128, 128, 32, 2, 2, 8, 2>(a, s);
     return dispatch_bf16x3<64, 128, 32, 2, 2, 8, 2>(a, s);
 }
 
-// Two K = T reductions (both operands row-contiguous, no epilogue) in one launch.
+// Two independent problems in one launch of 128x128 tiles.  The pairs of the gradient pass:
+//   C^H dy (row-major A, B read along N)          with  dy^T x  (K = T reduction in slabs)
+//   Bbar^H chi + D dy (same layout, epilogue 1)   with  chi^T u (K = T reduction in slabs)
 hipError_t launch_gemm_pair(const GemmArgs &a, const GemmArgs &b, hipStream_t s)
 {
     if (a.M <= 0 || a.N <= 0 || a.K <= 0 || b.M <= 0 || b.N <= 0 || b.K <= 0) return hipErrorInvalidValue;
-    if (use_f32_mfma()) {
-        hipError_t e = launch_gemm(a, s);
-        return e != hipSuccess ? e : launch_gemm(b, s);
+    if ((a.splits > 1 && a.epilogue) || (b.splits > 1 && b.epilogue)) return hipErrorInvalidValue;
+    if (!use_f32_mfma()) {
+        constexpr int NN0 = gemm_layout(true, false, 0), NN1 = gemm_layout(true, false, 1),
+                      TN0 = gemm_layout(false, false, 0);
+        const int la = layout_of(a), lb = layout_of(b);
+        if (la == NN0 && lb == TN0) return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, NN0, TN0>(a, s, &b);
+        if (la == NN1 && lb == TN0) return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, NN1, TN0>(a, s, &b);
     }
-    return dispatch_bf16x3<128, 128, 32, 2, 2, 4, 2>(a, s, &b);
+    hipError_t e = launch_gemm(a, s);
+    return e != hipSuccess ? e : launch_gemm(b, s);
 }
 
 }  // namespace ssm

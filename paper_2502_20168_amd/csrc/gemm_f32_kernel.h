@@ -28,6 +28,9 @@ struct GemmDev {
     const uint8_t *rowflag;
     int M, N, K, kper;      // kper: K range per split (multiple of the K tile)
     int ntm, ntn, per_xcd;
+    // placement of the (tile, split) work items on the 8 XCDs (bf16x3 kernel): slots per XCD,
+    // mapping mode and its parameter, first slot of this problem in a shared launch
+    int splits, nx, mode, mpar, slot0;
 };
 
 // Term added to the accumulator when an output element is stored.

@@ -36,8 +36,9 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
     const size_t T = (size_t)Bt * L;
     o.plan = plan_scan(Bt, L, P);
     if (o.plan.nblocks > 0x7fffffffLL) return SSM_ERR_UNSUPPORTED;
-    o.splitC = gemm_pick_splits(H, 2 * P, (int64_t)T);
-    o.splitB = gemm_pick_splits(2 * P, H, (int64_t)T);
+    const int64_t rows128 = ((int64_t)T + 127) / 128;
+    o.splitC = gemm_pick_splits(H, 2 * P, (int64_t)T, rows128 * ((2 * P + 127) / 128));   // shares C^H dy's launch
+    o.splitB = gemm_pick_splits(2 * P, H, (int64_t)T, rows128 * ((H + 127) / 128));       // shares Bbar^H chi's launch
     o.nslab = coldot_slabs((int64_t)T);
     size_t off = 0;
     o.hdr = off; off += up(sizeof(WsHeader));
@@ -215,7 +216,13 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     g3.B = Cc; g3.ldb = 2 * P; g3.b_kcontig = 0;
     g3.C = reinterpret_cast<float *>(chi); g3.ldc = 2 * P;
     g3.M = T; g3.N = (int)(2 * P); g3.K = (int)H; g3.splits = 1;
-    HIP_TRY(launch_gemm(g3, s));
+    // dC slabs: [h, 2p+c] = sum_t dy[t,h] * x[t, 2p+c]    (needs only saved states: same launch)
+    GemmArgs g4{};
+    g4.A = dy; g4.lda = H; g4.a_kcontig = 0;
+    g4.B = xf; g4.ldb = 2 * P; g4.b_kcontig = 0;
+    g4.C = dCpart; g4.ldc = 2 * P;
+    g4.M = (int)H; g4.N = (int)(2 * P); g4.K = T; g4.splits = lo.splitC;
+    HIP_TRY(launch_gemm_pair(g3, g4, s));
     MARK();
 
     ScanArgs sa{};
@@ -236,22 +243,13 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     g5.B = Bri; g5.ldb = H; g5.b_kcontig = 0;
     g5.C = du; g5.ldc = H; g5.diag = D; g5.E = dy; g5.lde = H; g5.epilogue = 1;
     g5.M = T; g5.N = (int)H; g5.K = (int)(2 * P); g5.splits = 1;
-    HIP_TRY(launch_gemm(g5, s));
-    MARK();
-
-    // dC slabs: [h, 2p+c] = sum_t dy[t,h] * x[t, 2p+c]
-    GemmArgs g4{};
-    g4.A = dy; g4.lda = H; g4.a_kcontig = 0;
-    g4.B = xf; g4.ldb = 2 * P; g4.b_kcontig = 0;
-    g4.C = dCpart; g4.ldc = 2 * P;
-    g4.M = (int)H; g4.N = (int)(2 * P); g4.K = T; g4.splits = lo.splitC;
-    // dBbar slabs: [2p+c, h] = sum_t chi[t, 2p+c] * u[t,h]   (same launch as the dC slabs)
+    // dBbar slabs: [2p+c, h] = sum_t chi[t, 2p+c] * u[t,h]   (same launch)
     GemmArgs g6{};
     g6.A = reinterpret_cast<const float *>(chi); g6.lda = 2 * P; g6.a_kcontig = 0;
     g6.B = u; g6.ldb = H; g6.b_kcontig = 0;
     g6.C = dBpart; g6.ldc = H;
     g6.M = (int)(2 * P); g6.N = (int)H; g6.K = T; g6.splits = lo.splitB;
-    HIP_TRY(launch_gemm_pair(g4, g6, s));
+    HIP_TRY(launch_gemm_pair(g5, g6, s));
     MARK();
 
     EpilogueArgs ea{};

@@ -25,10 +25,12 @@ struct GemmArgs {
     int M, N, K, splits;
 };
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t s);
-// two independent reductions with row-contiguous operands and no epilogue in one launch
+// two independent problems in one launch (falls back to two launches for layouts without a
+// paired instantiation)
 hipError_t launch_gemm_pair(const GemmArgs &a, const GemmArgs &b, hipStream_t s);
-// number of K splits used for a reduction over `K` rows with an M x N result
-int gemm_pick_splits(int64_t M, int64_t N, int64_t K);
+// number of K splits for a reduction over K rows with an M x N result that shares its launch
+// with a product of partner_tiles 128x128 tiles
+int gemm_pick_splits(int64_t M, int64_t N, int64_t K, int64_t partner_tiles);
 
 // ---------------------------------------------------------------------------------------------
 // Resettable scan over the sequence dimension (forward and reverse time).
