@@ -165,7 +165,7 @@ struct SplitLoader {
 // ---------------------------------------------------------------------------------------------
 template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, bool AKC, bool BKC, int EPI, bool FAST>
 __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *smem, int m0, int n0, int z,
-                                                    int kbeg, int kend, int rot)
+                                                    int kbeg, int kend)
 {
     constexpr int NC = WGM * WGN;                 // consumer wavefronts
     constexpr int PT = 64 * NP;                   // producer threads
@@ -188,13 +188,9 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
         const int ptid = tid - 64 * NC;
         LA la[2];
         LB lb[2];
-        // The K tiles are visited in an order rotated by `rot`: workgroups that run side by side
-        // then read different 128-byte segments of their rows at any moment.  With a row pitch that
-        // is a multiple of 4 KB they would otherwise all hit the same memory channel.
         auto fetch = [&](int set, int t) {
-            const int k0 = kbeg + ((t + rot) % nk) * BK;
-            la[set].template load<FAST>(g.A, g.lda, m0, g.M, k0, kend, ptid);
-            lb[set].template load<FAST>(g.B, g.ldb, n0, g.N, k0, kend, ptid);
+            la[set].template load<FAST>(g.A, g.lda, m0, g.M, kbeg + t * BK, kend, ptid);
+            lb[set].template load<FAST>(g.B, g.ldb, n0, g.N, kbeg + t * BK, kend, ptid);
         };
         auto stash = [&](int set, int t) {
             __bf16 *st = smem + (t % NS) * STAGE;
@@ -381,9 +377,9 @@ __device__ __forceinline__ void gemm_bf16x3_ws_problem(const GemmDev &g, __bf16 
                       (g.ldb % 4 == 0) && ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0) &&
                       (m0 + BM <= g.M) && (n0 + BN <= g.N) && ((kend - kbeg) % BK == 0);
     if (fast)
-        gemm_bf16x3_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, AKC, BKC, EPI, true>(g, smem, m0, n0, z, kbeg, kend, q + 4 * x);
+        gemm_bf16x3_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, AKC, BKC, EPI, true>(g, smem, m0, n0, z, kbeg, kend);
     else
-        gemm_bf16x3_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, AKC, BKC, EPI, false>(g, smem, m0, n0, z, kbeg, kend, q + 4 * x);
+        gemm_bf16x3_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, AKC, BKC, EPI, false>(g, smem, m0, n0, z, kbeg, kend);
 }
 
 // One launch carries one problem (LAY1 < 0) or two independent ones (used for the gradient
