@@ -153,6 +153,40 @@ ssm_status ssm_step(const void *plan, size_t plan_bytes, const float *D, const f
                     const ssm_c64 *x_prev, const uint8_t *is_first, int64_t Bt, int64_t H, int64_t P,
                     ssm_c64 *x, float *y, void *stream);
 
+/* Bootstrapped lambda-return, the critic's target of the actor-critic stage ("Actor-Critic
+ * Training", Eq. 14):
+ *   V_t = r_t + gamma c_t ((1 - lambda) v_t + lambda V_{t+1}),   V_T = v_T
+ * a reverse-time linear recurrence with a coefficient that changes every step.  Arrays are
+ * TIME-MAJOR [T, N] f32 (row t = step t of N imagined trajectories, as a roll-out produces them);
+ * row T-1 is the paper's last step, whose return is the value itself.  The value that enters step
+ * t is v_t as printed (a caller who bootstraps with v_{t+1} passes the shifted array).
+ *   ssm_lambda_return      in : reward, cont, value [T,N];                    out: ret [T,N]
+ *   ssm_lambda_return_bwd  in : cont, value, ret (from the forward call), dret [T,N]
+ *                          out: dreward, dcont, dvalue [T,N] = gradients of sum(dret (.) ret)
+ *                               (first-order gradients through the imagined trajectory)
+ * No workspace.  Outputs must not alias inputs.                                                 */
+ssm_status ssm_lambda_return(const float *reward, const float *cont, const float *value,
+                             float gamma, float lambda, int64_t T, int64_t N, float *ret, void *stream);
+ssm_status ssm_lambda_return_bwd(const float *cont, const float *value, const float *ret,
+                                 const float *dret, float gamma, float lambda, int64_t T, int64_t N,
+                                 float *dreward, float *dcont, float *dvalue, void *stream);
+
+/* half-GLU gate of the S5 sequence layer (appendix "S5 Sequence Layer"):
+ *   x1 = GELU(u),   y = u (.) sigmoid(W^T x1)       i.e. y[t,j] = u[t,j] sigmoid(sum_i W[i,j] x1[t,i])
+ * with the exact Gaussian GELU x Phi(x).  u, y [T,H] f32 row-major (T = Bt*L tokens), W [H,H] f32.
+ *   ssm_half_glu_fwd  in : u (16-byte aligned), W;   out: y, gate [T,H] = sigmoid(W^T x1) (NULL
+ *                          allowed when no gradient pass follows)
+ *   ssm_half_glu_bwd  in : u, W, gate (from the forward call), dy [T,H] (16-byte aligned)
+ *                     out: du [T,H], dW [H,H] = gradients of sum(dy (.) y)
+ * Workspace: ssm_half_glu_workspace_bytes(T, H, want_bwd) bytes, 256-byte aligned (0 = invalid
+ * or unsupported shape).  Outputs must not alias inputs or the workspace.                        */
+size_t ssm_half_glu_workspace_bytes(int64_t T, int64_t H, int want_bwd);
+ssm_status ssm_half_glu_fwd(const float *u, const float *W, int64_t T, int64_t H,
+                            float *y, float *gate, void *workspace, size_t ws_bytes, void *stream);
+ssm_status ssm_half_glu_bwd(const float *u, const float *W, const float *gate, const float *dy,
+                            int64_t T, int64_t H, float *du, float *dW,
+                            void *workspace, size_t ws_bytes, void *stream);
+
 /* Measurement aids: the same code path as ssm_scan_fwd / ssm_scan_bwd, with a HIP event recorded
  * on `stream` around every kernel.  They wait for the stream before returning and write the
  * milliseconds of each stage to the HOST array stage_ms:

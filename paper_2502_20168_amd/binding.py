@@ -27,7 +27,9 @@ BWD_STAGE_NAMES = ("discretize_pack_dD", "gx_dC_partials", "reverse_scan", "du_d
 
 EXPORTS = ("ssm_strerror", "ssm_version", "ssm_workspace_bytes", "ssm_discretize", "ssm_scan_fwd",
            "ssm_scan_bwd", "ssm_scan_states", "ssm_scan_states_reverse", "ssm_scan_fwd_profiled",
-           "ssm_scan_bwd_profiled", "ssm_workspace_status", "ssm_step_plan_bytes", "ssm_step_prepare", "ssm_step")
+           "ssm_scan_bwd_profiled", "ssm_workspace_status", "ssm_step_plan_bytes", "ssm_step_prepare", "ssm_step",
+           "ssm_lambda_return", "ssm_lambda_return_bwd", "ssm_half_glu_workspace_bytes", "ssm_half_glu_fwd",
+           "ssm_half_glu_bwd")
 
 _lib = None
 _vp, _i64, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t
@@ -76,6 +78,17 @@ def lib():
         L.ssm_step_prepare.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _vp, _sz, _vp]
         L.ssm_step.restype = ctypes.c_int
         L.ssm_step.argtypes = [_vp, _sz, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp]
+        _f = ctypes.c_float
+        L.ssm_lambda_return.restype = ctypes.c_int
+        L.ssm_lambda_return.argtypes = [_vp, _vp, _vp, _f, _f, _i64, _i64, _vp, _vp]
+        L.ssm_lambda_return_bwd.restype = ctypes.c_int
+        L.ssm_lambda_return_bwd.argtypes = [_vp, _vp, _vp, _vp, _f, _f, _i64, _i64, _vp, _vp, _vp, _vp]
+        L.ssm_half_glu_workspace_bytes.restype = _sz
+        L.ssm_half_glu_workspace_bytes.argtypes = [_i64, _i64, ctypes.c_int]
+        L.ssm_half_glu_fwd.restype = ctypes.c_int
+        L.ssm_half_glu_fwd.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp, _vp, _sz, _vp]
+        L.ssm_half_glu_bwd.restype = ctypes.c_int
+        L.ssm_half_glu_bwd.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _vp, _vp, _vp, _sz, _vp]
         _lib = L
     return _lib
 
@@ -295,6 +308,81 @@ def ssm_step(plan, D, u, x_prev=None, is_first=None, *, P=None, x=None, y=None, 
     if rc != SSM_OK:
         raise SsmError(rc, "ssm_step")
     return x, y
+
+
+def ssm_lambda_return(reward, cont, value, gamma: float, lam: float, *, ret=None, stream=None):
+    """Time-major [T, N] float32 tensors.  Returns ret [T, N]."""
+    torch = _torch()
+    T, N = reward.shape
+    for name, t in (("reward", reward), ("cont", cont), ("value", value), ("ret", ret)):
+        _chk(t, torch.float32, (T, N), name)
+    ret = ret if ret is not None else torch.empty_like(reward)
+    rc = lib().ssm_lambda_return(_ptr(reward), _ptr(cont), _ptr(value), gamma, lam, T, N, _ptr(ret), _stream(stream))
+    if rc != SSM_OK:
+        raise SsmError(rc, "ssm_lambda_return")
+    return ret
+
+
+def ssm_lambda_return_bwd(cont, value, ret, dret, gamma: float, lam: float, *, stream=None):
+    """Returns (dreward, dcont, dvalue), each [T, N]."""
+    torch = _torch()
+    T, N = cont.shape
+    for name, t in (("cont", cont), ("value", value), ("ret", ret), ("dret", dret)):
+        _chk(t, torch.float32, (T, N), name)
+    dr, dc, dv = torch.empty_like(cont), torch.empty_like(cont), torch.empty_like(cont)
+    rc = lib().ssm_lambda_return_bwd(_ptr(cont), _ptr(value), _ptr(ret), _ptr(dret), gamma, lam, T, N,
+                                     _ptr(dr), _ptr(dc), _ptr(dv), _stream(stream))
+    if rc != SSM_OK:
+        raise SsmError(rc, "ssm_lambda_return_bwd")
+    return dr, dc, dv
+
+
+def ssm_half_glu_workspace_bytes(T: int, H: int, want_bwd: bool) -> int:
+    return int(lib().ssm_half_glu_workspace_bytes(T, H, 1 if want_bwd else 0))
+
+
+def _glu_workspace(T, H, want_bwd, device):
+    torch = _torch()
+    n = ssm_half_glu_workspace_bytes(T, H, want_bwd)
+    if n == 0:
+        raise SsmError(SSM_ERR_UNSUPPORTED, "ssm_half_glu_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def ssm_half_glu_fwd(u, W, *, want_gate=True, workspace=None, y=None, gate=None, stream=None):
+    """u [T, H], W [H, H] float32.  Returns (y, gate); gate is None unless asked for."""
+    torch = _torch()
+    T, H = u.shape
+    _chk(u, torch.float32, (T, H), "u")
+    _chk(W, torch.float32, (H, H), "W")
+    _chk(y, torch.float32, (T, H), "y")
+    _chk(gate, torch.float32, (T, H), "gate")
+    ws = workspace if workspace is not None else _glu_workspace(T, H, False, u.device)
+    y = y if y is not None else torch.empty_like(u)
+    if gate is None and want_gate:
+        gate = torch.empty_like(u)
+    rc = lib().ssm_half_glu_fwd(_ptr(u), _ptr(W), T, H, _ptr(y), _ptr(gate), _ptr(ws), ws.numel(), _stream(stream))
+    if rc != SSM_OK:
+        raise SsmError(rc, "ssm_half_glu_fwd")
+    return y, gate
+
+
+def ssm_half_glu_bwd(u, W, gate, dy, *, workspace=None, du=None, dW=None, stream=None):
+    """Returns (du [T, H], dW [H, H])."""
+    torch = _torch()
+    T, H = u.shape
+    for name, t in (("u", u), ("gate", gate), ("dy", dy), ("du", du)):
+        _chk(t, torch.float32, (T, H), name)
+    _chk(W, torch.float32, (H, H), "W")
+    _chk(dW, torch.float32, (H, H), "dW")
+    ws = workspace if workspace is not None else _glu_workspace(T, H, True, u.device)
+    du = du if du is not None else torch.empty_like(u)
+    dW = dW if dW is not None else torch.empty_like(W)
+    rc = lib().ssm_half_glu_bwd(_ptr(u), _ptr(W), _ptr(gate), _ptr(dy), T, H, _ptr(du), _ptr(dW), _ptr(ws), ws.numel(),
+                                _stream(stream))
+    if rc != SSM_OK:
+        raise SsmError(rc, "ssm_half_glu_bwd")
+    return du, dW
 
 
 def ssm_workspace_status(workspace, stream=None) -> int:

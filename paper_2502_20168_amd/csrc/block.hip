@@ -1,0 +1,268 @@
+// Operations around the SSM layer (gfx950): the bootstrapped lambda-return of the actor-critic
+// section and the half-GLU gate of the S5 sequence layer (appendix), with their adjoints.
+#include "../../include/ssm.h"
+#include "ssm_internal.h"
+
+namespace ssm {
+namespace {
+
+constexpr size_t ALIGN = 256;
+inline size_t up(size_t n) { return (n + ALIGN - 1) / ALIGN * ALIGN; }
+inline bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+#define HIP_TRY(expr) do { if ((expr) != hipSuccess) return SSM_ERR_HIP; } while (0)
+
+// ---------------------------------------------------------------------------------------------
+// lambda-return:  V_t = r_t + gamma c_t ((1 - lambda) v_t + lambda V_{t+1}),  V_T = v_T.
+// Time-major arrays [T, N]; one thread per trajectory walks time backwards.  Neighbouring
+// threads read neighbouring trajectories of the same step, so every access is one coalesced
+// row segment; the only serial dependency is one fused multiply-add per step.
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) lambda_return_kernel(const float *__restrict__ r, const float *__restrict__ c,
+                                                            const float *__restrict__ v, float gamma, float lam,
+                                                            long T, long N, float *__restrict__ ret)
+{
+    const long n = (long)blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    float V = v[(T - 1) * N + n];
+    ret[(T - 1) * N + n] = V;
+    const float gl = gamma * lam, g1 = gamma * (1.f - lam);
+    long t = T - 2;
+    for (; t >= 3; t -= 4) {
+        // the loads of four steps do not depend on V: issue them together
+        float rr[4], cc[4], vv[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const long i = (t - j) * N + n;
+            rr[j] = r[i]; cc[j] = c[i]; vv[j] = v[i];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            // r + c (g1 v) + (c gl) V
+            V = fmaf(cc[j] * gl, V, fmaf(cc[j], g1 * vv[j], rr[j]));
+            ret[(t - j) * N + n] = V;
+        }
+    }
+    for (; t >= 0; --t) {
+        const long i = t * N + n;
+        const float cv = c[i];
+        V = fmaf(cv * gl, V, fmaf(cv, g1 * v[i], r[i]));
+        ret[i] = V;
+    }
+}
+
+// Adjoint: G_t = dret_t + gamma lambda c_{t-1} G_{t-1} walks time forwards;
+// dr_t = G_t, dc_t = G_t gamma ((1-lambda) v_t + lambda V_{t+1}), dv_t = G_t gamma c_t (1-lambda) for t < T-1;
+// the last step has dv = G and no reward / continue gradient.
+__global__ void __launch_bounds__(256) lambda_return_bwd_kernel(const float *__restrict__ c, const float *__restrict__ v,
+                                                                const float *__restrict__ ret, const float *__restrict__ dret,
+                                                                float gamma, float lam, long T, long N,
+                                                                float *__restrict__ dr, float *__restrict__ dc,
+                                                                float *__restrict__ dv)
+{
+    const long n = (long)blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    const float gl = gamma * lam, g1 = gamma * (1.f - lam);
+    float G = 0.f, cprev = 0.f;
+    for (long t = 0; t < T - 1; ++t) {
+        const long i = t * N + n;
+        const float cv = c[i];
+        G = fmaf(gl * cprev, G, dret[i]);
+        dr[i] = G;
+        dc[i] = G * fmaf(gl, ret[i + N], g1 * v[i]);
+        dv[i] = G * (g1 * cv);
+        cprev = cv;
+    }
+    const long i = (T - 1) * N + n;
+    G = fmaf(gl * cprev, G, dret[i]);
+    dr[i] = 0.f;
+    dc[i] = 0.f;
+    dv[i] = G;
+}
+
+// ---------------------------------------------------------------------------------------------
+// half-GLU:  x1 = GELU(u),  y = u (.) sigmoid(x1 W).
+// The element-wise halves run as small streaming kernels (float4 per thread); the products run
+// on the projection GEMM with the gate fused into its store (epilogues 3 and 4).
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float gelu_exact(float x)
+{
+    // x Phi(x) with Phi(x) = erfc(-x / sqrt 2) / 2 (no cancellation in the lower tail)
+    return 0.5f * x * erfcf(-0.70710678118654752f * x);
+}
+
+__global__ void __launch_bounds__(256) gelu_kernel(const float4 *__restrict__ u, float4 *__restrict__ x1, long n4,
+                                                   const float *__restrict__ ut, float *__restrict__ x1t, long n)
+{
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i < n4) {
+        const float4 a = u[i];
+        x1[i] = make_float4(gelu_exact(a.x), gelu_exact(a.y), gelu_exact(a.z), gelu_exact(a.w));
+    }
+    const long j = 4 * n4 + i;                           // the up to three elements past the last float4
+    if (i < 4 && j < n) x1t[j] = gelu_exact(ut[j]);
+}
+
+// x1 = GELU(u) and dz = dy u s (1 - s) in one pass (s = the gate saved by the forward call)
+__global__ void __launch_bounds__(256) gate_bwd_prep_kernel(const float *__restrict__ u, const float *__restrict__ s,
+                                                            const float *__restrict__ dy, float *__restrict__ x1,
+                                                            float *__restrict__ dz, long n)
+{
+    const long i0 = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i0 + 4 <= n) {
+        const float4 a = *reinterpret_cast<const float4 *>(u + i0);
+        const float4 g = *reinterpret_cast<const float4 *>(s + i0);
+        const float4 d = *reinterpret_cast<const float4 *>(dy + i0);
+        *reinterpret_cast<float4 *>(x1 + i0) =
+            make_float4(gelu_exact(a.x), gelu_exact(a.y), gelu_exact(a.z), gelu_exact(a.w));
+        *reinterpret_cast<float4 *>(dz + i0) =
+            make_float4(d.x * a.x * (g.x * (1.f - g.x)), d.y * a.y * (g.y * (1.f - g.y)),
+                        d.z * a.z * (g.z * (1.f - g.z)), d.w * a.w * (g.w * (1.f - g.w)));
+    } else {
+        for (long i = i0; i < n; ++i) {
+            x1[i] = gelu_exact(u[i]);
+            dz[i] = dy[i] * u[i] * (s[i] * (1.f - s[i]));
+        }
+    }
+}
+
+// fixed-order sum of the K-split slabs of a product
+__global__ void __launch_bounds__(256) sum_slabs_kernel(const float *__restrict__ part, long n, int nslab,
+                                                        float *__restrict__ out)
+{
+    const long i = (long)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    float acc = 0.f;
+    for (int z = 0; z < nslab; ++z) acc += part[(long)z * n + i];
+    out[i] = acc;
+}
+
+struct GluLayout { size_t x1, dz, dWpart, total; int splits; };
+
+bool make_glu_layout(int64_t T, int64_t H, bool bwd, GluLayout &o)
+{
+    if (T <= 0 || H <= 0 || H > SSM_MAX_WIDTH || T > SSM_MAX_TOKENS || T > SSM_MAX_ELEMS / H) return false;
+    size_t off = 0;
+    o.x1 = off; off += up((size_t)T * H * 4);
+    o.dz = o.dWpart = 0; o.splits = 1;
+    if (bwd) {
+        o.dz = off; off += up((size_t)T * H * 4);
+        o.splits = gemm_pick_splits(H, H, T, 0);
+        o.dWpart = off; off += up((size_t)o.splits * H * H * 4);
+    }
+    o.total = off;
+    return true;
+}
+
+}  // namespace
+}  // namespace ssm
+
+using namespace ssm;
+
+extern "C" {
+
+ssm_status ssm_lambda_return(const float *reward, const float *cont, const float *value, float gamma,
+                             float lambda, int64_t T, int64_t N, float *ret, void *stream)
+{
+    if (!reward || !cont || !value || !ret) return SSM_ERR_INVALID_ARG;
+    if (T <= 0 || N <= 0) return SSM_ERR_INVALID_ARG;
+    if (T > SSM_MAX_TOKENS || N > SSM_MAX_TOKENS || T > SSM_MAX_ELEMS / N) return SSM_ERR_UNSUPPORTED;
+    if (misaligned(reward, 4) || misaligned(cont, 4) || misaligned(value, 4) || misaligned(ret, 4))
+        return SSM_ERR_INVALID_ARG;
+    const unsigned blocks = (unsigned)((N + 255) / 256);
+    hipLaunchKernelGGL(lambda_return_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       reward, cont, value, gamma, lambda, (long)T, (long)N, ret);
+    HIP_TRY(hipGetLastError());
+    return SSM_OK;
+}
+
+ssm_status ssm_lambda_return_bwd(const float *cont, const float *value, const float *ret, const float *dret,
+                                 float gamma, float lambda, int64_t T, int64_t N,
+                                 float *dreward, float *dcont, float *dvalue, void *stream)
+{
+    if (!cont || !value || !ret || !dret || !dreward || !dcont || !dvalue) return SSM_ERR_INVALID_ARG;
+    if (T <= 0 || N <= 0) return SSM_ERR_INVALID_ARG;
+    if (T > SSM_MAX_TOKENS || N > SSM_MAX_TOKENS || T > SSM_MAX_ELEMS / N) return SSM_ERR_UNSUPPORTED;
+    if (misaligned(cont, 4) || misaligned(value, 4) || misaligned(ret, 4) || misaligned(dret, 4) ||
+        misaligned(dreward, 4) || misaligned(dcont, 4) || misaligned(dvalue, 4))
+        return SSM_ERR_INVALID_ARG;
+    const unsigned blocks = (unsigned)((N + 255) / 256);
+    hipLaunchKernelGGL(lambda_return_bwd_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       cont, value, ret, dret, gamma, lambda, (long)T, (long)N, dreward, dcont, dvalue);
+    HIP_TRY(hipGetLastError());
+    return SSM_OK;
+}
+
+size_t ssm_half_glu_workspace_bytes(int64_t T, int64_t H, int want_bwd)
+{
+    GluLayout lo;
+    return make_glu_layout(T, H, want_bwd != 0, lo) ? lo.total : 0;
+}
+
+ssm_status ssm_half_glu_fwd(const float *u, const float *W, int64_t T, int64_t H, float *y, float *gate,
+                            void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!u || !W || !y) return SSM_ERR_INVALID_ARG;
+    if (T <= 0 || H <= 0) return SSM_ERR_INVALID_ARG;
+    GluLayout lo;
+    if (!make_glu_layout(T, H, false, lo)) return SSM_ERR_UNSUPPORTED;
+    if (misaligned(u, 16) || misaligned(W, 4) || misaligned(y, 4) || misaligned(gate, 4)) return SSM_ERR_INVALID_ARG;
+    if (!workspace || misaligned(workspace, ALIGN) || ws_bytes < lo.total) return SSM_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float *x1 = reinterpret_cast<float *>(static_cast<char *>(workspace) + lo.x1);
+    const long n = (long)T * H, n4 = n / 4;
+    const long threads = n4 > 4 ? n4 : 4;
+    hipLaunchKernelGGL(gelu_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s,
+                       reinterpret_cast<const float4 *>(u), reinterpret_cast<float4 *>(x1), n4, u, x1, n);
+    HIP_TRY(hipGetLastError());
+    // y[t, j] = u[t, j] sigmoid(sum_i x1[t, i] W[i, j])
+    GemmArgs g{};
+    g.A = x1; g.lda = H; g.a_kcontig = 1;
+    g.B = W; g.ldb = H; g.b_kcontig = 0;
+    g.C = y; g.ldc = H; g.E = u; g.lde = H; g.C2 = gate; g.epilogue = 3;
+    g.M = (int)T; g.N = (int)H; g.K = (int)H; g.splits = 1;
+    HIP_TRY(launch_gemm(g, s));
+    return SSM_OK;
+}
+
+ssm_status ssm_half_glu_bwd(const float *u, const float *W, const float *gate, const float *dy,
+                            int64_t T, int64_t H, float *du, float *dW,
+                            void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!u || !W || !gate || !dy || !du || !dW) return SSM_ERR_INVALID_ARG;
+    if (T <= 0 || H <= 0) return SSM_ERR_INVALID_ARG;
+    GluLayout lo;
+    if (!make_glu_layout(T, H, true, lo)) return SSM_ERR_UNSUPPORTED;
+    if (misaligned(u, 16) || misaligned(W, 4) || misaligned(gate, 16) || misaligned(dy, 16) || misaligned(du, 4) ||
+        misaligned(dW, 4))
+        return SSM_ERR_INVALID_ARG;
+    if (!workspace || misaligned(workspace, ALIGN) || ws_bytes < lo.total) return SSM_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    float *x1 = reinterpret_cast<float *>(ws + lo.x1);
+    float *dz = reinterpret_cast<float *>(ws + lo.dz);
+    float *dWpart = reinterpret_cast<float *>(ws + lo.dWpart);
+    const long n = (long)T * H;
+    hipLaunchKernelGGL(gate_bwd_prep_kernel, dim3((unsigned)(((n + 3) / 4 + 255) / 256)), dim3(256), 0, s, u, gate, dy, x1,
+                       dz, n);
+    HIP_TRY(hipGetLastError());
+    // du[t, i] = dy[t, i] s[t, i] + GELU'(u[t, i]) sum_j dz[t, j] W[i, j]
+    GemmArgs g{};
+    g.A = dz; g.lda = H; g.a_kcontig = 1;
+    g.B = W; g.ldb = H; g.b_kcontig = 1;
+    g.C = du; g.ldc = H; g.E = dy; g.E2 = gate; g.E3 = u; g.lde = H; g.epilogue = 4;
+    g.M = (int)T; g.N = (int)H; g.K = (int)H; g.splits = 1;
+    HIP_TRY(launch_gemm(g, s));
+    // dW[i, j] = sum_t x1[t, i] dz[t, j]: reduction over tokens in K slabs, then a fixed-order sum
+    GemmArgs h{};
+    h.A = x1; h.lda = H; h.a_kcontig = 0;
+    h.B = dz; h.ldb = H; h.b_kcontig = 0;
+    h.C = dWpart; h.ldc = H;
+    h.M = (int)H; h.N = (int)H; h.K = (int)T; h.splits = lo.splits;
+    HIP_TRY(launch_gemm(h, s));
+    const long nw = (long)H * H;
+    hipLaunchKernelGGL(sum_slabs_kernel, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, s, dWpart, nw, lo.splits, dW);
+    HIP_TRY(hipGetLastError());
+    return SSM_OK;
+}
+
+}  // extern "C"

@@ -336,9 +336,7 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
             for (int r = 0; r < 16; ++r) {
                 const long row = m0 + wm * WM + i * 32 + 8 * (r / 4) + 4 * hh + (r % 4);
                 if (FAST || (row < g.M && col < g.N)) {
-                    float v = acc[i][j][r];
-                    v += gemm_epilogue_term<EPI>(g, row, col);
-                    Cz[row * g.ldc + col] = v;
+                    Cz[row * g.ldc + col] = gemm_epilogue_apply<EPI>(g, row, col, acc[i][j][r]);
                 }
             }
         }
@@ -403,6 +401,7 @@ inline GemmDev make_gemm_dev(const GemmArgs &a)
     GemmDev g;
     g.A = a.A; g.lda = a.lda; g.B = a.B; g.ldb = a.ldb; g.C = a.C; g.ldc = a.ldc;
     g.diag = a.diag; g.E = a.E; g.lde = a.lde; g.rowflag = a.rowflag;
+    g.E2 = a.E2; g.E3 = a.E3; g.C2 = a.C2;
     g.M = a.M; g.N = a.N; g.K = a.K;
     const int splits = a.splits < 1 ? 1 : a.splits;
     int kper = (a.K + splits - 1) / splits;

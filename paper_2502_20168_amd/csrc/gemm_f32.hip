@@ -49,6 +49,8 @@ static hipError_t dispatch_f32(const GemmArgs &a, hipStream_t s)
 static int layout_of(const GemmArgs &a)
 {
     if (a.epilogue == 2) return (a.a_kcontig && a.b_kcontig) ? gemm_layout(true, true, 2) : -1;
+    if (a.epilogue == 3) return (a.a_kcontig && !a.b_kcontig) ? gemm_layout(true, false, 3) : -1;
+    if (a.epilogue == 4) return (a.a_kcontig && a.b_kcontig) ? gemm_layout(true, true, 4) : -1;
     if (a.a_kcontig) return gemm_layout(true, a.b_kcontig != 0, a.epilogue);
     if (!a.b_kcontig && !a.epilogue) return gemm_layout(false, false, 0);
     return -1;
@@ -63,6 +65,7 @@ static hipError_t dispatch_bf16x3(const GemmArgs &a, hipStream_t s)
         return launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, gemm_layout(akc, bkc, epi)>(a, s);
         SSM_CASE(true, true, 0) SSM_CASE(true, true, 1) SSM_CASE(true, true, 2)
         SSM_CASE(true, false, 0) SSM_CASE(true, false, 1) SSM_CASE(false, false, 0)
+        SSM_CASE(true, false, 3) SSM_CASE(true, true, 4)
 #undef SSM_CASE
     default: return hipErrorInvalidValue;
     }
@@ -78,10 +81,12 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
 {
     if (a.M <= 0 || a.N <= 0 || a.K <= 0) return hipErrorInvalidValue;
     if (a.splits > 1 && a.epilogue) return hipErrorInvalidValue;
-    if (a.epilogue < 0 || a.epilogue > 2 || (a.epilogue && (!a.diag || !a.E))) return hipErrorInvalidValue;
+    if (a.epilogue < 0 || a.epilogue > 4 || (a.epilogue && !a.E)) return hipErrorInvalidValue;
+    if ((a.epilogue == 1 || a.epilogue == 2) && !a.diag) return hipErrorInvalidValue;
+    if (a.epilogue == 4 && (!a.E2 || !a.E3)) return hipErrorInvalidValue;
     const long splits = a.splits < 1 ? 1 : a.splits;
     const long tiles128 = (long)((a.M + 127) / 128) * ((a.N + 127) / 128) * splits;
-    if (use_f32_mfma()) {
+    if (use_f32_mfma() && a.epilogue < 3) {              // the gate epilogues exist for bf16x3 only
         // measured on MI355X: 128x128 tiles with 8 wavefronts when they give every CU a workgroup,
         // 64x64 tiles otherwise
         if (tiles128 >= 256) {

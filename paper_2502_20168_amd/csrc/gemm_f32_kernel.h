@@ -25,6 +25,7 @@ struct GemmDev {
     const float *B; long ldb;
     float *C; long ldc;
     const float *diag; const float *E; long lde;
+    const float *E2; const float *E3; float *C2;    // gate epilogues (pitch lde / ldc)
     const uint8_t *rowflag;
     int M, N, K, kper;      // kper: K range per split (multiple of the K tile)
     int ntm, ntn, per_xcd;
@@ -33,23 +34,50 @@ struct GemmDev {
     int splits, nx, mode, mpar, slot0;
 };
 
-// Term added to the accumulator when an output element is stored.
-//   EPI 0: nothing
-//   EPI 1: diag[col] * E[row, col]                       (D (.) u and D (.) dy)
+// Value stored for an output element whose accumulated product is v.
+//   EPI 0: v
+//   EPI 1: v + diag[col] * E[row, col]                   (D (.) u and D (.) dy)
 //   EPI 2: columns are interleaved (re, im) pairs of complex states; diag holds Abar as
 //          interleaved complex; adds [not rowflag[row]] * (Abar_p * E_p)[re or im]: the carried
 //          state Abar x_{t-1} of one recurrence step (Eq. 3, first line)
-template <int EPI>
-__device__ __forceinline__ float gemm_epilogue_term(const GemmDev &g, long row, int col)
+//   EPI 3: half-GLU gate (S5 sequence layer appendix): s = sigmoid(v) is kept in C2 when asked
+//          and the stored value is E[row, col] * s        (E = the gated input u)
+//   EPI 4: adjoint of the gate with respect to its input: E * E2 + v * GELU'(E3)
+//          (E = dy, E2 = the saved gate s, E3 = u; v = the product dz W^T)
+__device__ __forceinline__ float gelu_derivative(float x)
 {
-    if (EPI == 1) return g.diag[col] * g.E[row * g.lde + col];
+    // d/dx [x Phi(x)] = Phi(x) + x phi(x)
+    const float cdf = 0.5f * erfcf(-0.70710678118654752f * x);
+    const float pdf = 0.39894228040143268f * __expf(-0.5f * x * x);
+    return fmaf(x, pdf, cdf);
+}
+__device__ __forceinline__ float sigmoidf(float z)
+{
+    // e^-|z| never overflows; both branches are exact rewrites of 1 / (1 + e^-z)
+    const float e = __expf(-fabsf(z));
+    const float r = 1.f / (1.f + e);
+    return z >= 0.f ? r : e * r;
+}
+template <int EPI>
+__device__ __forceinline__ float gemm_epilogue_apply(const GemmDev &g, long row, int col, float v)
+{
+    if (EPI == 1) return v + g.diag[col] * g.E[row * g.lde + col];
     if (EPI == 2) {
-        if (g.rowflag && g.rowflag[row]) return 0.f;
+        if (g.rowflag && g.rowflag[row]) return v;
         const float lr = g.diag[col & ~1], li = g.diag[col | 1];
         const float own = g.E[row * g.lde + col], other = g.E[row * g.lde + (col ^ 1)];
-        return (col & 1) ? fmaf(lr, own, li * other) : fmaf(lr, own, -li * other);
+        return v + ((col & 1) ? fmaf(lr, own, li * other) : fmaf(lr, own, -li * other));
     }
-    return 0.f;
+    if (EPI == 3) {
+        const float s = sigmoidf(v);
+        if (g.C2) g.C2[row * g.ldc + col] = s;
+        return g.E[row * g.lde + col] * s;
+    }
+    if (EPI == 4) {
+        const long i = row * g.lde + col;
+        return fmaf(v, gelu_derivative(g.E3[i]), g.E[i] * g.E2[i]);
+    }
+    return v;
 }
 
 // Stages one R x BK operand tile through registers.
@@ -196,9 +224,7 @@ __device__ __forceinline__ void gemm_tile(const GemmDev &g, float *As, float *Bs
             for (int r = 0; r < 16; ++r) {
                 const long row = m0 + wm * WM + i * 32 + 8 * (r / 4) + 4 * hh + (r % 4);
                 if (FAST || (row < g.M && col < g.N)) {
-                    float v = acc[i][j][r];
-                    v += gemm_epilogue_term<EPI>(g, row, col);
-                    Cz[row * g.ldc + col] = v;
+                    Cz[row * g.ldc + col] = gemm_epilogue_apply<EPI>(g, row, col, acc[i][j][r]);
                 }
             }
         }
@@ -238,6 +264,7 @@ hipError_t launch_gemm_variant(const GemmArgs &a, hipStream_t s)
     GemmDev g;
     g.A = a.A; g.lda = a.lda; g.B = a.B; g.ldb = a.ldb; g.C = a.C; g.ldc = a.ldc;
     g.diag = a.diag; g.E = a.E; g.lde = a.lde; g.rowflag = a.rowflag;
+    g.E2 = a.E2; g.E3 = a.E3; g.C2 = a.C2;
     g.M = a.M; g.N = a.N; g.K = a.K;
     const int splits = a.splits < 1 ? 1 : a.splits;
     int kper = (a.K + splits - 1) / splits;

@@ -11,7 +11,9 @@ namespace ssm {
 // ---------------------------------------------------------------------------------------------
 // Projection GEMM:  C[m,n] = sum_k A(m,k) * B(n,k)  (+ epilogue term)
 // epilogue 0: none; 1: + diag[n] * E[m,n]; 2: + [not rowflag[m]] * (Abar (.) E)[m,n] with diag = Abar
-// as interleaved complex and the columns of C and E interleaved (re, im) pairs (one recurrence step)
+// as interleaved complex and the columns of C and E interleaved (re, im) pairs (one recurrence step);
+// 3: C = E (.) sigmoid(product), sigmoid kept in C2 when non-null (half-GLU gate);
+// 4: C = E (.) E2 + product (.) GELU'(E3) (adjoint of the gate with respect to its input)
 // A(m,k) = a_kcontig ? A[m*lda + k] : A[k*lda + m];  B(n,k) = b_kcontig ? B[n*ldb + k] : B[k*ldb + n]
 // splits > 1: split z covers a contiguous K range and writes its own slab C + z*M*ldc
 // (no epilogue term in that case); the caller reduces the slabs.
@@ -22,6 +24,7 @@ struct GemmArgs {
     float *C; int64_t ldc;
     const float *diag; const float *E; int64_t lde;
     int epilogue; const uint8_t *rowflag;
+    const float *E2; const float *E3; float *C2;     // epilogues 3 and 4 (gate), pitch lde / ldc
     int M, N, K, splits;
 };
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t s);

@@ -106,3 +106,30 @@ def custom(name: str, Bt: int, L: int, H: int, P: int, *, backward: bool = True,
     """Ad-hoc workload for edge-case tests (ragged sizes, all-reset, ...)."""
     return Workload(name, Bt, L, H, P, backward, p_reset, force_first, with_x0,
                     lam_re_lo, lam_re_hi, seed)
+
+
+def gen_returns(T: int, N: int, seed: int = 0, p_end: float = 0.05) -> Dict[str, np.ndarray]:
+    """Seeded synthetic imagination roll-out for the lambda-return, time-major [T, N] float32:
+    rewards and critic values ~ N(0,1); continuation flags sampled in {0, 1} with
+    P(episode end) = p_end for the even trajectories and continuous probabilities U(0,1) for
+    the odd ones; dret ~ N(0,1).  Draw order: reward, cont_binary, cont_prob, value, dret."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    reward = rng.normal(size=(T, N))
+    cb = (rng.random(size=(T, N)) >= p_end).astype(np.float64)
+    cp = rng.random(size=(T, N))
+    cont = np.where((np.arange(N) % 2 == 0)[None, :], cb, cp)
+    value = rng.normal(size=(T, N))
+    dret = rng.normal(size=(T, N))
+    f = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+    return {"reward": f(reward), "cont": f(cont), "value": f(value), "dret": f(dret)}
+
+
+def gen_half_glu(T: int, H: int, seed: int = 0) -> Dict[str, np.ndarray]:
+    """Seeded synthetic input of the half-GLU gate: u, dy ~ N(0,1) [T, H]; W ~ N(0, 1/sqrt(H))
+    [H, H] (the scale of a freshly initialised linear layer).  Draw order: u, W, dy."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    u = rng.normal(size=(T, H))
+    W = rng.normal(size=(H, H)) / np.sqrt(H)
+    dy = rng.normal(size=(T, H))
+    f = lambda a: np.ascontiguousarray(a, dtype=np.float32)
+    return {"u": f(u), "W": f(W), "dy": f(dy)}

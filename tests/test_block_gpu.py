@@ -1,0 +1,105 @@
+"""GPU parity of the lambda-return and the half-GLU gate (and their adjoints) with the float64
+oracle, element by element through the C ABI."""
+import numpy as np
+import pytest
+
+from oracle import block_oracle as borc
+from paper_2502_20168_amd import workloads as wl
+from parity_util import TOL_FWD, TOL_GRAD, assert_close
+
+pytestmark = pytest.mark.gpu
+
+GAMMA, LAM = 0.997, 0.95
+
+
+def _dev(d):
+    import torch
+    return {k: torch.from_numpy(v).cuda() for k, v in d.items()}
+
+
+# several blocks and a ragged tail in N; T from the degenerate single step to beyond the unrolled loop
+RETURN_SHAPES = [(16, 1024), (1, 5), (2, 7), (5, 300), (33, 4097), (15, 65536), (256, 513)]
+
+
+@pytest.mark.parametrize("T,N", RETURN_SHAPES)
+def test_lambda_return_matches_oracle(T, N):
+    import torch
+    from paper_2502_20168_amd import binding as ssm
+    inp = wl.gen_returns(T, N, seed=T * 7919 + N)
+    d = _dev(inp)
+    ret = ssm.ssm_lambda_return(d["reward"], d["cont"], d["value"], GAMMA, LAM)
+    dr, dc, dv = ssm.ssm_lambda_return_bwd(d["cont"], d["value"], ret, d["dret"], GAMMA, LAM)
+    torch.cuda.synchronize()
+    ref = borc.lambda_return(inp["reward"], inp["cont"], inp["value"], GAMMA, LAM)
+    rdr, rdc, rdv = borc.lambda_return_grad(inp["reward"], inp["cont"], inp["value"], GAMMA, LAM, inp["dret"])
+    ret = ret.cpu().numpy()
+    assert np.array_equal(ret[-1], inp["value"][-1])          # V_T = v_T exactly
+    assert_close(ret, ref, TOL_FWD, "ret")
+    assert_close(dv.cpu().numpy(), rdv, TOL_GRAD, "dvalue")
+    if T > 1:
+        assert_close(dr.cpu().numpy(), rdr, TOL_GRAD, "dreward")
+        assert_close(dc.cpu().numpy(), rdc, TOL_GRAD, "dcont")
+    assert not dr[-1].any().item() and not dc[-1].any().item()
+
+
+def test_lambda_return_extremes_of_lambda():
+    import torch
+    from paper_2502_20168_amd import binding as ssm
+    inp = wl.gen_returns(12, 777, seed=5)
+    d = _dev(inp)
+    for lam in (0.0, 1.0):
+        ret = ssm.ssm_lambda_return(d["reward"], d["cont"], d["value"], 0.9, lam).cpu().numpy()
+        assert_close(ret, borc.lambda_return(inp["reward"], inp["cont"], inp["value"], 0.9, lam), TOL_FWD, "ret")
+    # an episode end (c = 0) cuts the return: V_k = r_k exactly
+    k = 4
+    d["cont"][k] = 0.0
+    ret = ssm.ssm_lambda_return(d["reward"], d["cont"], d["value"], 0.9, 0.95)
+    torch.cuda.synchronize()
+    assert torch.equal(ret[k], d["reward"][k])
+
+
+# (T, H): the benchmark shape, ragged tiles, a width that is no multiple of 4 (scalar tails and the
+# guarded GEMM path), the vision width
+GLU_SHAPES = [(4096, 512), (128, 32), (300, 96), (1000, 257), (2048, 1024), (5, 3)]
+
+
+@pytest.mark.parametrize("T,H", GLU_SHAPES)
+def test_half_glu_matches_oracle(T, H):
+    import torch
+    from paper_2502_20168_amd import binding as ssm
+    inp = wl.gen_half_glu(T, H, seed=T + 31 * H)
+    d = _dev(inp)
+    y, gate = ssm.ssm_half_glu_fwd(d["u"], d["W"])
+    du, dW = ssm.ssm_half_glu_bwd(d["u"], d["W"], gate, d["dy"])
+    torch.cuda.synchronize()
+    ref_y = borc.half_glu(inp["u"], inp["W"])
+    ref_gate = borc.sigmoid(borc.gelu(inp["u"]) @ inp["W"].astype(np.float64))
+    ref_du, ref_dW = borc.half_glu_grad(inp["u"], inp["W"], inp["dy"])
+    assert_close(y.cpu().numpy(), ref_y, TOL_FWD, "y")
+    assert_close(gate.cpu().numpy(), ref_gate, TOL_FWD, "gate")
+    assert_close(du.cpu().numpy(), ref_du, TOL_GRAD, "du")
+    assert_close(dW.cpu().numpy(), ref_dW, TOL_GRAD, "dW")
+
+
+def test_half_glu_zero_weights_and_no_gate_output():
+    import torch
+    from paper_2502_20168_amd import binding as ssm
+    inp = wl.gen_half_glu(260, 64, seed=3)
+    d = _dev(inp)
+    y, gate = ssm.ssm_half_glu_fwd(d["u"], torch.zeros_like(d["W"]), want_gate=False)
+    torch.cuda.synchronize()
+    assert gate is None
+    assert torch.equal(y, 0.5 * d["u"])                       # sigmoid(0) = 1/2 exactly
+
+
+def test_half_glu_is_bitwise_repeatable():
+    import torch
+    from paper_2502_20168_amd import binding as ssm
+    d = _dev(wl.gen_half_glu(1024, 256, seed=4))
+    outs = []
+    for _ in range(2):
+        y, gate = ssm.ssm_half_glu_fwd(d["u"], d["W"])
+        du, dW = ssm.ssm_half_glu_bwd(d["u"], d["W"], gate, d["dy"])
+        torch.cuda.synchronize()
+        outs.append((y.clone(), du.clone(), dW.clone()))
+    assert all(torch.equal(a, b) for a, b in zip(*outs))

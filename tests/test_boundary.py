@@ -120,6 +120,33 @@ def test_other_entry_points_argument_errors(lib):
     assert lib.ssm_step(FAKE, need, FAKE, FAKE, FAKE + 512, None, 2, 4, 4, FAKE + 512, FAKE, None) == ssm.SSM_ERR_INVALID_ARG
 
 
+def test_block_entry_points_argument_errors(lib):
+    # lambda-return: no workspace, errors before any launch
+    assert lib.ssm_lambda_return(None, FAKE, FAKE, 0.9, 0.9, 4, 8, FAKE, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_lambda_return(FAKE, FAKE, FAKE, 0.9, 0.9, 0, 8, FAKE, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_lambda_return(FAKE, FAKE, FAKE, 0.9, 0.9, 4, 8, None, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_lambda_return(FAKE, FAKE + 2, FAKE, 0.9, 0.9, 4, 8, FAKE, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_lambda_return(FAKE, FAKE, FAKE, 0.9, 0.9, 1 << 31, 8, FAKE, None) == ssm.SSM_ERR_UNSUPPORTED
+    assert lib.ssm_lambda_return_bwd(FAKE, FAKE, FAKE, None, 0.9, 0.9, 4, 8, FAKE, FAKE, FAKE,
+                                     None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_lambda_return_bwd(FAKE, FAKE, FAKE, FAKE, 0.9, 0.9, 4, -1, FAKE, FAKE, FAKE,
+                                     None) == ssm.SSM_ERR_INVALID_ARG
+    # half-GLU
+    need_f, need_b = ssm.ssm_half_glu_workspace_bytes(64, 32, False), ssm.ssm_half_glu_workspace_bytes(64, 32, True)
+    assert 64 * 32 * 4 <= need_f < need_b
+    assert ssm.ssm_half_glu_workspace_bytes(0, 32, False) == 0 and ssm.ssm_half_glu_workspace_bytes(64, 1 << 17, True) == 0
+    assert lib.ssm_half_glu_fwd(None, FAKE, 64, 32, FAKE, None, FAKE, need_f, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_half_glu_fwd(FAKE, FAKE, 64, 0, FAKE, None, FAKE, need_f, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_half_glu_fwd(FAKE + 4, FAKE, 64, 32, FAKE, None, FAKE, need_f, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_half_glu_fwd(FAKE, FAKE, 64, 32, FAKE, None, FAKE, need_f - 1, None) == ssm.SSM_ERR_WORKSPACE
+    assert lib.ssm_half_glu_fwd(FAKE, FAKE, 64, 32, FAKE, None, None, need_f, None) == ssm.SSM_ERR_WORKSPACE
+    assert lib.ssm_half_glu_fwd(FAKE, FAKE, 64, 1 << 17, FAKE, None, FAKE, need_f, None) == ssm.SSM_ERR_UNSUPPORTED
+    assert lib.ssm_half_glu_bwd(FAKE, FAKE, None, FAKE, 64, 32, FAKE, FAKE, FAKE, need_b, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_half_glu_bwd(FAKE, FAKE, FAKE, FAKE, 64, 32, FAKE, FAKE, FAKE, need_f, None) == ssm.SSM_ERR_WORKSPACE
+    assert lib.ssm_half_glu_bwd(FAKE, FAKE, FAKE, FAKE + 8, 64, 32, FAKE, FAKE, FAKE, need_b,
+                                None) == ssm.SSM_ERR_INVALID_ARG
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import numpy as np
     import torch
