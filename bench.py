@@ -152,10 +152,70 @@ def main():
         "config": {"workload": "%s: Bt=%d L=%d H=%d P=%d fwd+bwd, fp32 I/O, complex64 state, seed %d"
                                % (w.name, Bt, L, H, P, w.seed), "tokens_per_step": T},
         "roofline": roofline, "scan_roofline": scan, "stage_us": stages,
+        "block_ops": block_ops(ssm, torch, wl, T, H),
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, inp)
     print(json.dumps(result))
+
+
+def graph_time_ms(torch, fn, iters):
+    """Average duration of one fn(i) call, i = 0 .. iters-1, on the GPU: the calls are captured into
+    one HIP graph and the graph is replayed, so the launches follow each other without the host's
+    per-call cost (argument marshalling takes about as long as one of the small kernels runs).
+    Events bracket one replay."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        for i in range(3):
+            fn(i)
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            for i in range(iters):
+                fn(3 + i)
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def block_ops(ssm, torch, wl, T, H, iters=20):
+    """The two operations around the layer at the benchmark shape: half-GLU gate on [T, H] tokens
+    (one H x H product forward, two in the gradient pass) and the lambda-return of an imagined
+    roll-out (horizon 16, 65536 trajectories)."""
+    d = {k: torch.from_numpy(v).cuda() for k, v in wl.gen_half_glu(T, H, seed=0).items()}
+    ws_f = torch.empty(ssm.ssm_half_glu_workspace_bytes(T, H, False), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(ssm.ssm_half_glu_workspace_bytes(T, H, True), dtype=torch.uint8, device="cuda")
+    y, gate, du, dW = torch.empty_like(d["u"]), torch.empty_like(d["u"]), torch.empty_like(d["u"]), torch.empty_like(d["W"])
+    f_ms = graph_time_ms(torch, lambda i: ssm.ssm_half_glu_fwd(d["u"], d["W"], workspace=ws_f, y=y, gate=gate), iters)
+    b_ms = graph_time_ms(torch, lambda i: ssm.ssm_half_glu_bwd(d["u"], d["W"], gate, d["dy"], workspace=ws_b,
+                                                                du=du, dW=dW), iters)
+    flops = 2.0 * T * H * H
+    hor, ntraj = 16, 65536
+    r = {k: torch.from_numpy(v).cuda() for k, v in wl.gen_returns(hor, ntraj, seed=0).items()}
+    ret = torch.empty_like(r["reward"])
+    lf_ms = graph_time_ms(torch, lambda i: ssm.ssm_lambda_return(r["reward"], r["cont"], r["value"], 0.997, 0.95,
+                                                                  ret=ret), iters)
+    lb_ms = graph_time_ms(torch, lambda i: ssm.ssm_lambda_return_bwd(r["cont"], r["value"], ret, r["dret"], 0.997,
+                                                                      0.95), iters)
+    n = hor * ntraj
+    return {"half_glu": {"shape": "T=%d H=%d" % (T, H), "fwd_us": round(f_ms * 1e3, 2), "bwd_us": round(b_ms * 1e3, 2),
+                         "fwd_fp32_equivalent_tflops": round(flops / (f_ms * 1e-3) / 1e12, 1),
+                         "bwd_fp32_equivalent_tflops": round(2 * flops / (b_ms * 1e-3) / 1e12, 1),
+                         "note": "fwd = GELU pass + one product with the gate in its store; bwd = element-wise "
+                                 "pass + two products + slab sum"},
+            "lambda_return": {"shape": "T=%d N=%d (time-major)" % (hor, ntraj), "fwd_us": round(lf_ms * 1e3, 2),
+                              "bwd_us": round(lb_ms * 1e3, 2),
+                              "fwd_GBs": round(16.0 * n / (lf_ms * 1e-3) / 1e9, 1),
+                              "bwd_GBs": round(28.0 * n / (lb_ms * 1e-3) / 1e9, 1),
+                              "note": "algorithmic bytes: fwd 3 reads + 1 write, bwd 4 reads + 3 writes of 4 B per "
+                                      "(step, trajectory); buffers stay in the last-level cache (warm)"}}
 
 
 def scan_cold_warm(ssm, torch, d, Bt, L, P, fwd_bytes, rev_bytes, iters=40):
@@ -172,28 +232,7 @@ def scan_cold_warm(ssm, torch, d, Bt, L, P, fwd_bytes, rev_bytes, iters=40):
     ws_r = ssm.alloc_workspace(Bt, L, 1, P, True)
 
     def timed(fn, rotate):
-        # The calls are captured into one HIP graph and the graph is replayed: the launches then
-        # follow each other on the GPU without the host's per-call cost (argument marshalling takes
-        # about as long as one of these kernels runs).  Events bracket one replay.
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.stream(side):
-            for i in range(3):
-                fn(i % nsets if rotate else 0)
-            torch.cuda.synchronize()
-            with torch.cuda.graph(graph, stream=side):
-                for i in range(iters):
-                    fn((3 + i) % nsets if rotate else 0)
-        torch.cuda.synchronize()
-        graph.replay()
-        torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        graph.replay()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / iters
+        return graph_time_ms(torch, lambda i: fn(i % nsets if rotate else 0), iters)
 
     f = lambda i: ssm.ssm_scan_states(A_bar, vs[i], d["is_first"], d["x0"], want_x_last=False, workspace=ws_f)
     r = lambda i: ssm.ssm_scan_states_reverse(A_bar, vs[i], xs[i % len(xs)], d["is_first"], d["x0"],
