@@ -29,9 +29,11 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix
 PEAK_BF16_MFMA_TFLOPS = 2500.0 # MI355X dense bf16 matrix
 BF16_PRODUCTS = 6              # bf16 MFMA products the GEMM issues per fp32 multiply-add
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see
-# profiles/); None until measured
-TRAFFIC_PROJECT_IN = None
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what
+# the same counters read for a copy-like kernel of known size (profiles/gemm_bf16x3_scan_cfg2_fwd_bwd.md):
+# 24.4 MiB read + 16.2 MiB written; algorithmic 10 MiB (u 8 + Bbar 2, the latter once per XCD) + 16 MiB
+TRAFFIC_PROJECT_IN = {"read_bytes": 25.6e6, "write_bytes": 17.0e6, "algorithmic_read_bytes": 10.5e6,
+                      "algorithmic_write_bytes": 16.8e6, "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, see profiles/"}
 
 
 def main():

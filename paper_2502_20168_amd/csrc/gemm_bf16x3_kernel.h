@@ -67,6 +67,15 @@ struct SplitLoader {
     static constexpr int PLANE = R * S;           // halves per plane
     float4 r[NV];
 
+    // k-contiguous source: row handled by the g-th group of BK/4 lanes.  With BK = 32 a group
+    // writes 64 contiguous bytes (16 banks) per plane and the row stride is 80 bytes, so
+    // neighbouring groups take rows 4 apart (80*4 = 16 banks mod 32): their writes then tile the 32
+    // banks exactly, where consecutive rows would overlap in 4 banks.
+    static __device__ __forceinline__ int kc_row(int g)
+    {
+        return (BK == 32 && R % 4 == 0) ? (g % (R / 4)) * 4 + g / (R / 4) : g;
+    }
+
     template <bool FAST>
     __device__ __forceinline__ void load(const float *__restrict__ X, long ld, int row0, int rows, int k0,
                                          int kend, int tid)
@@ -75,7 +84,7 @@ struct SplitLoader {
 #pragma unroll
             for (int i = 0; i < NV; ++i) {
                 const int idx = tid + i * NT;
-                const int row = idx / (BK / 4), kq = idx % (BK / 4);
+                const int row = kc_row(idx / (BK / 4)), kq = idx % (BK / 4);
                 const long gr = row0 + row;
                 const int k = k0 + 4 * kq;
                 if (FAST) {
@@ -115,7 +124,7 @@ struct SplitLoader {
 #pragma unroll
             for (int i = 0; i < NV; ++i) {
                 const int idx = tid + i * NT;
-                const int row = idx / (BK / 4), kq = idx % (BK / 4);
+                const int row = kc_row(idx / (BK / 4)), kq = idx % (BK / 4);
                 const Split4 sp = split3(r[i]);
 #pragma unroll
                 for (int s = 0; s < 3; ++s)
