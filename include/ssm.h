@@ -153,6 +153,20 @@ ssm_status ssm_step(const void *plan, size_t plan_bytes, const float *D, const f
                     const ssm_c64 *x_prev, const uint8_t *is_first, int64_t Bt, int64_t H, int64_t P,
                     ssm_c64 *x, float *y, void *stream);
 
+/* Adjoint of one ssm_step with respect to its input and its incoming state: the first-order
+ * gradients that the actor's loss sends back through the imagined trajectory ("Actor-Critic
+ * Training": gradients are backpropagated through the dynamics model).  The world model's
+ * parameters are fixed in that stage, so no parameter gradients are formed.
+ *   gx[b,:]      = C^H dy[b,:] + dx[b,:]               (total gradient with respect to x_t)
+ *   dx_prev[b,:] = [not is_first[b]] conj(A_bar) (.) gx[b,:]
+ *   du[b,:]      = Re(B_bar^H gx[b,:]) + D (.) dy[b,:]
+ *   in : plan (from ssm_step_prepare), D [H], dy [Bt,H] f32, dx [Bt,P] c64 (gradient arriving from
+ *        step t+1, NULL = zeros), is_first [Bt] u8 (the flags of THIS step, NULL = none)
+ *   out: gx [Bt,P] c64, du [Bt,H] f32, dx_prev [Bt,P] c64 (NULL allowed); gx, dx, dx_prev distinct */
+ssm_status ssm_step_bwd(const void *plan, size_t plan_bytes, const float *D, const float *dy,
+                        const ssm_c64 *dx, const uint8_t *is_first, int64_t Bt, int64_t H, int64_t P,
+                        ssm_c64 *gx, float *du, ssm_c64 *dx_prev, void *stream);
+
 /* Bootstrapped lambda-return, the critic's target of the actor-critic stage ("Actor-Critic
  * Training", Eq. 14):
  *   V_t = r_t + gamma c_t ((1 - lambda) v_t + lambda V_{t+1}),   V_T = v_T

@@ -28,7 +28,7 @@ BWD_STAGE_NAMES = ("discretize_pack_dD", "gx_dC_partials", "reverse_scan", "du_d
 EXPORTS = ("ssm_strerror", "ssm_version", "ssm_workspace_bytes", "ssm_discretize", "ssm_scan_fwd",
            "ssm_scan_bwd", "ssm_scan_states", "ssm_scan_states_reverse", "ssm_scan_fwd_profiled",
            "ssm_scan_bwd_profiled", "ssm_workspace_status", "ssm_step_plan_bytes", "ssm_step_prepare", "ssm_step",
-           "ssm_lambda_return", "ssm_lambda_return_bwd", "ssm_half_glu_workspace_bytes", "ssm_half_glu_fwd",
+           "ssm_step_bwd", "ssm_lambda_return", "ssm_lambda_return_bwd", "ssm_half_glu_workspace_bytes", "ssm_half_glu_fwd",
            "ssm_half_glu_bwd")
 
 _lib = None
@@ -78,6 +78,8 @@ def lib():
         L.ssm_step_prepare.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _vp, _sz, _vp]
         L.ssm_step.restype = ctypes.c_int
         L.ssm_step.argtypes = [_vp, _sz, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp]
+        L.ssm_step_bwd.restype = ctypes.c_int
+        L.ssm_step_bwd.argtypes = [_vp, _sz, _vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp, _vp, _vp]
         _f = ctypes.c_float
         L.ssm_lambda_return.restype = ctypes.c_int
         L.ssm_lambda_return.argtypes = [_vp, _vp, _vp, _f, _f, _i64, _i64, _vp, _vp]
@@ -308,6 +310,24 @@ def ssm_step(plan, D, u, x_prev=None, is_first=None, *, P=None, x=None, y=None, 
     if rc != SSM_OK:
         raise SsmError(rc, "ssm_step")
     return x, y
+
+
+def ssm_step_bwd(plan, D, dy, dx=None, is_first=None, *, P, want_dx_prev=True, stream=None):
+    """Adjoint of one transition.  dy [Bt,H], dx [Bt,P] or None.  Returns (gx, du, dx_prev)."""
+    torch = _torch()
+    Bt, H = dy.shape
+    _chk(D, torch.float32, (H,), "D")
+    _chk(dy, torch.float32, (Bt, H), "dy")
+    _chk(dx, torch.complex64, (Bt, P), "dx")
+    _chk(is_first, torch.uint8, (Bt,), "is_first")
+    gx = torch.empty((Bt, P), dtype=torch.complex64, device=dy.device)
+    du = torch.empty_like(dy)
+    dx_prev = torch.empty_like(gx) if want_dx_prev else None
+    rc = lib().ssm_step_bwd(_ptr(plan), plan.numel(), _ptr(D), _ptr(dy), _ptr(dx), _ptr(is_first), Bt, H, P,
+                            _ptr(gx), _ptr(du), _ptr(dx_prev), _stream(stream))
+    if rc != SSM_OK:
+        raise SsmError(rc, "ssm_step_bwd")
+    return gx, du, dx_prev
 
 
 def ssm_lambda_return(reward, cont, value, gamma: float, lam: float, *, ret=None, stream=None):

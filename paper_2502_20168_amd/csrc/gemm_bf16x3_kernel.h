@@ -344,8 +344,18 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const long row = m0 + wm * WM + i * 32 + 8 * (r / 4) + 4 * hh + (r % 4);
-                if (FAST || (row < g.M && col < g.N)) {
-                    Cz[row * g.ldc + col] = gemm_epilogue_apply<EPI>(g, row, col, acc[i][j][r]);
+                const bool inb = FAST || (row < g.M && col < g.N);
+                if constexpr (EPI == 5) {
+                    // the partner column (col ^ 1) of a complex pair lives in the neighbouring lane
+                    float v = acc[i][j][r];
+                    if (inb && g.E) v += g.E[row * g.lde + col];
+                    const float other = __shfl_xor(v, 1);
+                    if (inb) {
+                        Cz[row * g.ldc + col] = v;
+                        if (g.C2) g.C2[row * g.ldc + col] = gemm_carry_adjoint(g, row, col, v, other);
+                    }
+                } else {
+                    if (inb) Cz[row * g.ldc + col] = gemm_epilogue_apply<EPI>(g, row, col, acc[i][j][r]);
                 }
             }
         }

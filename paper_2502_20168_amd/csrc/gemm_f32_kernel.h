@@ -44,6 +44,10 @@ struct GemmDev {
 //          and the stored value is E[row, col] * s        (E = the gated input u)
 //   EPI 4: adjoint of the gate with respect to its input: E * E2 + v * GELU'(E3)
 //          (E = dy, E2 = the saved gate s, E3 = u; v = the product dz W^T)
+//   EPI 5 (bf16x3 kernel only, handled where the tile is stored because it needs the partner
+//          column): adjoint of one recurrence step.  Columns are (re, im) pairs; the stored value is
+//          g = v + E (E = the gradient that arrives from the next step, may be null) and C2 gets
+//          [not rowflag[row]] conj(Abar) g, the gradient handed to the previous step (diag = Abar)
 __device__ __forceinline__ float gelu_derivative(float x)
 {
     // d/dx [x Phi(x)] = Phi(x) + x phi(x)
@@ -78,6 +82,13 @@ __device__ __forceinline__ float gemm_epilogue_apply(const GemmDev &g, long row,
         return fmaf(v, gelu_derivative(g.E3[i]), g.E[i] * g.E2[i]);
     }
     return v;
+}
+// second output of EPI 5: (conj(Abar_p) g_p)[re or im] given the element's own part and its partner's
+__device__ __forceinline__ float gemm_carry_adjoint(const GemmDev &g, long row, int col, float own, float other)
+{
+    if (g.rowflag && g.rowflag[row]) return 0.f;
+    const float lr = g.diag[col & ~1], li = g.diag[col | 1];
+    return (col & 1) ? fmaf(lr, own, -li * other) : fmaf(lr, own, li * other);
 }
 
 // Stages one R x BK operand tile through registers.

@@ -529,6 +529,41 @@ ssm_status ssm_step(const void *plan, size_t plan_bytes, const float *D, const f
     return SSM_OK;
 }
 
+ssm_status ssm_step_bwd(const void *plan, size_t plan_bytes, const float *D, const float *dy,
+                        const ssm_c64 *dx, const uint8_t *is_first, int64_t Bt, int64_t H, int64_t P,
+                        ssm_c64 *gx, float *du, ssm_c64 *dx_prev, void *stream)
+{
+    if (!D || !dy || !gx || !du) return SSM_ERR_INVALID_ARG;
+    ssm_status st = check_dims(Bt, 1, H, P);
+    if (st != SSM_OK) return st;
+    StepPlan pl;
+    if (!make_step_plan(H, P, pl)) return SSM_ERR_UNSUPPORTED;
+    if (misaligned(D, 4) || misaligned(dy, 4) || misaligned(dx, 8) || misaligned(gx, 8) || misaligned(du, 4) ||
+        misaligned(dx_prev, 8) || (dx && (dx == gx || dx == dx_prev)) || (dx_prev && dx_prev == gx))
+        return SSM_ERR_INVALID_ARG;
+    if (!plan || misaligned(plan, ALIGN) || plan_bytes < pl.total) return SSM_ERR_WORKSPACE;
+    const char *pb = static_cast<const char *>(plan);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // gx = C^H dy + dx;  dx_prev = [not is_first] conj(Abar) (.) gx
+    GemmArgs g1{};
+    g1.A = dy; g1.lda = H; g1.a_kcontig = 1;
+    g1.B = reinterpret_cast<const float *>(pb + pl.Cc); g1.ldb = 2 * P; g1.b_kcontig = 0;
+    g1.C = reinterpret_cast<float *>(gx); g1.ldc = 2 * P;
+    g1.E = reinterpret_cast<const float *>(dx); g1.lde = 2 * P;
+    g1.C2 = reinterpret_cast<float *>(dx_prev);
+    g1.diag = reinterpret_cast<const float *>(pb + pl.lam); g1.rowflag = is_first; g1.epilogue = 5;
+    g1.M = (int)Bt; g1.N = (int)(2 * P); g1.K = (int)H; g1.splits = 1;
+    HIP_TRY(launch_gemm(g1, s));
+    // du = Re(Bbar^H gx) + D (.) dy
+    GemmArgs g2{};
+    g2.A = reinterpret_cast<const float *>(gx); g2.lda = 2 * P; g2.a_kcontig = 1;
+    g2.B = reinterpret_cast<const float *>(pb + pl.Bri); g2.ldb = H; g2.b_kcontig = 0;
+    g2.C = du; g2.ldc = H; g2.diag = D; g2.E = dy; g2.lde = H; g2.epilogue = 1;
+    g2.M = (int)Bt; g2.N = (int)H; g2.K = (int)(2 * P); g2.splits = 1;
+    HIP_TRY(launch_gemm(g2, s));
+    return SSM_OK;
+}
+
 ssm_status ssm_workspace_status(const void *workspace, void *stream)
 {
     if (!workspace) return SSM_ERR_WORKSPACE;

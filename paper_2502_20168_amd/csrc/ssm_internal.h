@@ -13,7 +13,9 @@ namespace ssm {
 // epilogue 0: none; 1: + diag[n] * E[m,n]; 2: + [not rowflag[m]] * (Abar (.) E)[m,n] with diag = Abar
 // as interleaved complex and the columns of C and E interleaved (re, im) pairs (one recurrence step);
 // 3: C = E (.) sigmoid(product), sigmoid kept in C2 when non-null (half-GLU gate);
-// 4: C = E (.) E2 + product (.) GELU'(E3) (adjoint of the gate with respect to its input)
+// 4: C = E (.) E2 + product (.) GELU'(E3) (adjoint of the gate with respect to its input);
+// 5: C = product + E (E may be null), C2 = [not rowflag[m]] conj(Abar) (.) C with diag = Abar and complex
+//    (re, im) column pairs (adjoint of one recurrence step)
 // A(m,k) = a_kcontig ? A[m*lda + k] : A[k*lda + m];  B(n,k) = b_kcontig ? B[n*ldb + k] : B[k*ldb + n]
 // splits > 1: split z covers a contiguous K range and writes its own slab C + z*M*ldc
 // (no epilogue term in that case); the caller reduces the slabs.

@@ -118,6 +118,13 @@ def test_other_entry_points_argument_errors(lib):
     assert lib.ssm_step(FAKE, need, FAKE, FAKE, None, None, 0, 4, 4, FAKE, FAKE, None) == ssm.SSM_ERR_INVALID_ARG
     assert lib.ssm_step(FAKE, need - 1, FAKE, FAKE, None, None, 2, 4, 4, FAKE, FAKE, None) == ssm.SSM_ERR_WORKSPACE
     assert lib.ssm_step(FAKE, need, FAKE, FAKE, FAKE + 512, None, 2, 4, 4, FAKE + 512, FAKE, None) == ssm.SSM_ERR_INVALID_ARG
+    G = FAKE + 4096
+    assert lib.ssm_step_bwd(FAKE, need, FAKE, None, None, None, 2, 4, 4, G, FAKE, None, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_step_bwd(FAKE, need, FAKE, FAKE, None, None, 2, 4, 4, None, FAKE, None, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_step_bwd(FAKE, need, FAKE, FAKE, None, None, 2, 0, 4, G, FAKE, None, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_step_bwd(FAKE, need - 1, FAKE, FAKE, None, None, 2, 4, 4, G, FAKE, None, None) == ssm.SSM_ERR_WORKSPACE
+    assert lib.ssm_step_bwd(FAKE, need, FAKE, FAKE, G, None, 2, 4, 4, G, FAKE, None, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_step_bwd(FAKE, need, FAKE, FAKE, None, None, 2, 4, 4, G, FAKE, G, None) == ssm.SSM_ERR_INVALID_ARG
 
 
 def test_block_entry_points_argument_errors(lib):

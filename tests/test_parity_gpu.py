@@ -320,3 +320,35 @@ def test_step_mode_rollout_equals_oracle_sequence(Bt, H, P, steps):
     x1, y1 = ssm.ssm_step(plan, d["D"], d["u"][:, 0].contiguous(), None, None, P=P)
     ref1 = orc.forward(inp["Lambda"], inp["B"], inp["C"], inp["D"], inp["log_delta"], inp["u"][:, :1], None, None)
     assert_close(y1.cpu().numpy()[:, None], ref1["y"], TOL_FWD, "step y (no state)")
+
+
+@pytest.mark.parametrize("Bt,H,P,steps", [(1024, 512, 512, 10), (37, 50, 33, 6)])
+def test_step_mode_adjoint_rollout_equals_oracle_gradient(Bt, H, P, steps):
+    """First-order gradients through an imagined trajectory: `steps` dependent calls of
+    ssm_step_bwd in reverse order, each fed the state gradient of the step after it, against the
+    oracle's gradient pass over the same inputs as one sequence (du of every step, and the
+    gradient that reaches the initial state)."""
+    import torch
+    w = wl.custom("stepb", Bt, steps, H, P, backward=True, p_reset=0.1, with_x0=True, seed=29)
+    inp = wl.gen_inputs(w)
+    par = (inp["Lambda"], inp["B"], inp["C"], inp["D"], inp["log_delta"])
+    ref_f = orc.forward(*par, inp["u"], inp["is_first"], inp["x0"], nthreads=8)
+    ref_b = orc.backward(*par, inp["u"], inp["is_first"], inp["x0"], ref_f["x"], inp["dy"], nthreads=8)
+    d = ssm.to_device(inp)
+    plan = ssm.ssm_step_prepare(d["Lambda"], d["B"], d["C"], d["log_delta"])
+    dx, dus = None, []
+    for t in reversed(range(steps)):
+        _, du, dx = ssm.ssm_step_bwd(plan, d["D"], d["dy"][:, t].contiguous(), dx, d["is_first"][:, t].contiguous(), P=P)
+        dus.append(du)
+    torch.cuda.synchronize()
+    du_all = torch.stack(dus[::-1], 1).cpu().numpy()
+    assert_close(du_all, ref_b["du"], TOL_GRAD, "step du")
+    assert_close(dx.cpu().numpy(), ref_b["dx0"], TOL_GRAD, "step dx0")
+    # no incoming gradient, no flags, no dx_prev wanted: du = Re(Bbar^H C^H dy) + D dy
+    gx, du1, none = ssm.ssm_step_bwd(plan, d["D"], d["dy"][:, steps - 1].contiguous(), None, None, P=P,
+                                     want_dx_prev=False)
+    ref1 = orc.backward(*par, inp["u"][:, :1], None, None,
+                        orc.forward(*par, inp["u"][:, :1], None, None)["x"], inp["dy"][:, steps - 1:steps])
+    torch.cuda.synchronize()
+    assert none is None
+    assert_close(du1.cpu().numpy()[:, None], ref1["du"], TOL_GRAD, "step du (single)")
