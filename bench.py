@@ -155,6 +155,7 @@ def main():
                                % (w.name, Bt, L, H, P, w.seed), "tokens_per_step": T},
         "roofline": roofline, "scan_roofline": scan, "stage_us": stages,
         "block_ops": block_ops(ssm, torch, wl, T, H),
+        "step_mode": step_mode(ssm, torch, d, H, P),
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, inp)
@@ -185,6 +186,31 @@ def graph_time_ms(torch, fn, iters):
     e1.record()
     torch.cuda.synchronize()
     return e0.elapsed_time(e1) / iters
+
+
+def step_mode(ssm, torch, d, H, P, Bt=1024, horizon=10):
+    """Imagination-shaped use of the layer: `horizon` dependent one-step calls over Bt trajectories
+    (each step consumes the state of the step before it), then the adjoint steps in reverse order."""
+    plan = ssm.ssm_step_prepare(d["Lambda"], d["B"], d["C"], d["log_delta"])
+    u = torch.randn((horizon, Bt, H), device="cuda")
+    dy = torch.randn((horizon, Bt, H), device="cuda")
+    xs = [torch.zeros((Bt, P), dtype=torch.complex64, device="cuda") for _ in range(horizon + 1)]
+    ys = torch.empty_like(u)
+
+    def rollout(i):
+        for t in range(horizon):
+            ssm.ssm_step(plan, d["D"], u[t], xs[t], None, x=xs[t + 1], y=ys[t])
+
+    def adjoint(i):
+        dx = None
+        for t in reversed(range(horizon)):
+            _, _, dx = ssm.ssm_step_bwd(plan, d["D"], dy[t], dx, None, P=P)
+
+    f_ms = graph_time_ms(torch, rollout, 5) / horizon
+    b_ms = graph_time_ms(torch, adjoint, 5) / horizon
+    return {"shape": "Bt=%d H=%d P=%d horizon=%d" % (Bt, H, P, horizon), "fwd_us_per_step": round(f_ms * 1e3, 2),
+            "bwd_us_per_step": round(b_ms * 1e3, 2),
+            "note": "dependent steps (two GEMM launches each), replayed as one HIP graph; latency bound"}
 
 
 def block_ops(ssm, torch, wl, T, H, iters=20):

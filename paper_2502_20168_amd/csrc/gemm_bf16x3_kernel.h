@@ -177,6 +177,8 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
                                                     int kbeg, int kend)
 {
     constexpr int NC = WGM * WGN;                 // consumer wavefronts
+    constexpr int PF = 2;                         // K tiles of global loads in flight per producer
+                                                  // (3, 4 and 6 measured: 1-5 % slower)
     constexpr int PT = 64 * NP;                   // producer threads
     using LA = SplitLoader<BM, BK, AKC, PT>;
     using LB = SplitLoader<BN, BK, BKC, PT>;
@@ -192,11 +194,11 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
 
     if (wave >= NC) {
         // ------------------------------------------------------------------ producers
-        // Two register sets: while tile t is split and stored, the loads of tiles t+1 and t+2
-        // are in flight, which covers the global latency with two K tiles of matrix work.
+        // PF register sets: while tile t is split and stored, the loads of tiles t+1 .. t+PF are in
+        // flight, which covers the global latency with PF K tiles of matrix work.
         const int ptid = tid - 64 * NC;
-        LA la[2];
-        LB lb[2];
+        LA la[PF];
+        LB lb[PF];
         auto fetch = [&](int set, int t) {
             la[set].template load<FAST>(g.A, g.lda, m0, g.M, kbeg + t * BK, kend, ptid);
             lb[set].template load<FAST>(g.B, g.ldb, n0, g.N, kbeg + t * BK, kend, ptid);
@@ -206,35 +208,32 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
             la[set].store(st, ptid);
             lb[set].store(st + STAGE_A, ptid);
         };
-        // prologue: tiles 0 .. NS-2 into their stages (NS - 1 is 1 or 2 or 3; sets alternate)
-        if (0 < nk) fetch(0, 0);
-        if (1 < nk) fetch(1, 1);
+#pragma unroll
+        for (int j = 0; j < PF; ++j)
+            if (j < nk) fetch(j, j);
+        // prologue: tiles 0 .. NS-2 into their stages
 #pragma unroll
         for (int t = 0; t < NS - 1; ++t) {
             if (t < nk) {
-                stash(t & 1, t);
-                if (t + 2 < nk) fetch(t & 1, t + 2);
+                stash(t % PF, t);
+                if (t + PF < nk) fetch(t % PF, t + PF);
             }
         }
         __syncthreads();
-        // steady state: iteration kt stages tile t = kt + NS - 1 from register set t & 1
-        int kt = 0;
-        for (; kt + 1 < nk; kt += 2) {
-            {
-                const int t = kt + NS - 1;
-                if (t < nk) { stash((NS - 1) & 1, t); if (t + 2 < nk) fetch((NS - 1) & 1, t + 2); }
+        // steady state: iteration kt stages tile t = kt + NS - 1 from register set t % PF (kt is a
+        // multiple of PF at the top of the unrolled body, so the set index is a constant there)
+        for (int kt = 0; kt < nk; kt += PF) {
+#pragma unroll
+            for (int j = 0; j < PF; ++j) {
+                if (kt + j < nk) {
+                    const int t = kt + j + NS - 1;
+                    if (t < nk) {
+                        stash((j + NS - 1) % PF, t);
+                        if (t + PF < nk) fetch((j + NS - 1) % PF, t + PF);
+                    }
+                    __syncthreads();
+                }
             }
-            __syncthreads();
-            {
-                const int t = kt + NS;
-                if (t < nk) { stash(NS & 1, t); if (t + 2 < nk) fetch(NS & 1, t + 2); }
-            }
-            __syncthreads();
-        }
-        if (kt < nk) {
-            const int t = kt + NS - 1;
-            if (t < nk) stash((NS - 1) & 1, t);
-            __syncthreads();
         }
         return;
     }
