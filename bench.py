@@ -93,6 +93,19 @@ def main():
     mtok = T / (ms_per_step * 1e-3) / 1e6
     assert ssm.ssm_workspace_status(ws_f) == ssm.SSM_OK and ssm.ssm_workspace_status(ws_b) == ssm.SSM_OK
 
+    # ---- distribution of single steps: one event pair per step (adds a little per-step overhead)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for e0, e1 in evs:
+        e0.record()
+        step()
+        e1.record()
+    torch.cuda.synchronize()
+    per_step = np.sort(np.array([e0.elapsed_time(e1) for e0, e1 in evs])) * 1e3
+    step_dist = {"median_us": round(float(np.median(per_step)), 1),
+                 "p10_us": round(float(per_step[int(0.1 * (len(per_step) - 1))]), 1),
+                 "p90_us": round(float(per_step[int(0.9 * (len(per_step) - 1))]), 1),
+                 "note": "HIP events around every single step (forward + gradient pass)"}
+
     # ---- per-kernel durations from HIP events recorded on the launch stream (library side)
     fs = np.zeros(ssm.SSM_FWD_STAGES)
     bs = np.zeros(ssm.SSM_BWD_STAGES)
@@ -153,13 +166,29 @@ def main():
         "data": "synthetic",
         "config": {"workload": "%s: Bt=%d L=%d H=%d P=%d fwd+bwd, fp32 I/O, complex64 state, seed %d"
                                % (w.name, Bt, L, H, P, w.seed), "tokens_per_step": T},
-        "roofline": roofline, "scan_roofline": scan, "stage_us": stages,
+        "roofline": roofline, "scan_roofline": scan, "stage_us": stages, "step_time": step_dist,
+        "composite_hbm": {"algorithmic_bytes_per_step": compulsory_bytes(Bt, L, H, P),
+                          "GBs": round(compulsory_bytes(Bt, L, H, P) / (ms_per_step * 1e-3) / 1e9, 1),
+                          "frac_of_hbm_peak": round(compulsory_bytes(Bt, L, H, P) / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                          "note": "whole forward + gradient pass against the HBM peak, for reference only: the path "
+                                  "is matrix-core bound (about 290 flop per compulsory byte at this shape)"},
         "block_ops": block_ops(ssm, torch, wl, T, H),
         "step_mode": step_mode(ssm, torch, d, H, P),
     }
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, inp)
     print(json.dumps(result))
+
+
+def compulsory_bytes(Bt, L, H, P):
+    """Bytes the method itself must move per forward + gradient pass with everything fused that can be:
+    forward u, y, x (saved) and the flags; gradient pass dy, u, x, du and the flags; parameters read twice
+    and their gradients written once."""
+    T = Bt * L
+    fwd = T * (4 * H + 4 * H + 8 * P + 1)
+    bwd = T * (4 * H + 4 * H + 8 * P + 4 * H + 1)
+    par = 2 * (16 * P * H) + 16 * P * H
+    return float(fwd + bwd + par)
 
 
 def graph_time_ms(torch, fn, iters):
@@ -295,8 +324,16 @@ def cpu_baseline(w, inp):
     t0 = time.perf_counter()
     orc.run_workload(sub, True, nthreads=threads)
     dt = time.perf_counter() - t0
+    # single-threaded leg on a smaller sample
+    n1 = min(nseq, 2)
+    sub1 = {k: (v[:n1] if (v is not None and k in ("u", "is_first", "dy", "x0")) else v) for k, v in inp.items()}
+    t0 = time.perf_counter()
+    orc.run_workload(sub1, True, nthreads=1)
+    dt1 = time.perf_counter() - t0
     return {"value": round(nseq * w.L / dt / 1e6, 5), "unit": "Mtokens/s", "cores": threads, "kind": "oracle",
             "seconds": round(dt, 2),
+            "single_thread_value": round(n1 * w.L / dt1 / 1e6, 5), "single_thread_seconds": round(dt1, 2),
+            "single_thread_sample": "first %d sequences" % n1,
             "sample": "float64 oracle forward + gradient pass on the first %d of %d sequences of the same batch"
                       % (nseq, w.Bt)}
 
