@@ -27,8 +27,11 @@
  *     and need not be initialised or preserved between calls.
  *   - Gradient of the real loss l w.r.t. a complex quantity q is returned as
  *     dl/dRe(q) + i dl/dIm(q).
- *   - Two environment variables are read at call time: SSM_GEMM_F32=1 runs the projections on
+ *   - Three environment variables are read at call time: SSM_GEMM_F32=1 runs the projections on
  *     the fp32 matrix instruction instead of the (equally accurate, faster) three-way bf16 split;
+ *     SSM_GEMM_SPLIT=2 is an opt-in reduced-precision mode of the projections (two bf16 planes per
+ *     operand, three partial products: a product is good to 2^-16 instead of 2^-23; results stay
+ *     inside the 1e-4 / 1e-3 tolerances of the benchmark configurations, the default is 3);
  *     SSM_SPIN_LIMIT=<n> bounds the polls of a cross-workgroup wait in the scan (default 2^20).
  */
 #ifndef SSM_H_

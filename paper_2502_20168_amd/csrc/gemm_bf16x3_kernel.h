@@ -52,12 +52,36 @@ __device__ __forceinline__ Split4 split3(float4 v)
     return o;
 }
 
-// Stages one R x BK fp32 operand tile: global -> registers (fp32) -> split -> three LDS planes.
+// Two-plane split with round-to-nearest (v_cvt_pk_bf16_f32): a1 = rn_bf16(a), a2 = rn_bf16(a - a1);
+// |a - a1 - a2| <= 2^-18 |a|.  Used by the reduced-precision mode (three products a1b1, a1b2, a2b1:
+// relative error of a product below 2^-16), never by the default path.
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ Split4 split2(float4 v)
+{
+    Split4 o;
+    const f32x2 lo = {v.x, v.y}, hi = {v.z, v.w};
+    union { bf16x2 b; unsigned u; } a0, a1, b0, b1;
+    a0.b = __builtin_convertvector(lo, bf16x2);
+    a1.b = __builtin_convertvector(hi, bf16x2);
+    const f32x2 rlo = {v.x - __uint_as_float(a0.u << 16), v.y - __uint_as_float(a0.u & 0xffff0000u)};
+    const f32x2 rhi = {v.z - __uint_as_float(a1.u << 16), v.w - __uint_as_float(a1.u & 0xffff0000u)};
+    b0.b = __builtin_convertvector(rlo, bf16x2);
+    b1.b = __builtin_convertvector(rhi, bf16x2);
+    union { unsigned u[2]; bf16x4 b; } p0, p1;
+    p0.u[0] = a0.u; p0.u[1] = a1.u;
+    p1.u[0] = b0.u; p1.u[1] = b1.u;
+    o.p[0] = p0.b; o.p[1] = p1.b; o.p[2] = p1.b;
+    return o;
+}
+template <int NPL>
+__device__ __forceinline__ Split4 split_planes(float4 v) { return NPL == 3 ? split3(v) : split2(v); }
+
+// Stages one R x BK fp32 operand tile: global -> registers (fp32) -> split -> NPL LDS planes.
 // k-contiguous source: a thread handles units of 1 row x 4 k.  Row-contiguous source: units of
 // 4 rows x KU k (KU float4 loads, transposed in registers), KU = 4, 2 or 1; neighbouring lanes take
 // neighbouring k blocks of the same rows, so that their LDS writes fall into distinct banks while
 // the lanes that share a k row still read one contiguous 128-byte line.
-template <int R, int BK, bool KC, int NT>
+template <int R, int BK, bool KC, int NT, int NPL>
 struct SplitLoader {
     static constexpr int NV = R * BK / 4 / NT;
     static_assert(NV >= 1 && NV * NT * 4 == R * BK, "tile must be a multiple of the workgroup's float4 loads");
@@ -125,9 +149,9 @@ struct SplitLoader {
             for (int i = 0; i < NV; ++i) {
                 const int idx = tid + i * NT;
                 const int row = kc_row(idx / (BK / 4)), kq = idx % (BK / 4);
-                const Split4 sp = split3(r[i]);
+                const Split4 sp = split_planes<NPL>(r[i]);
 #pragma unroll
-                for (int s = 0; s < 3; ++s)
+                for (int s = 0; s < NPL; ++s)
                     *reinterpret_cast<bf16x4 *>(lds + s * PLANE + row * S + 4 * kq) = sp.p[s];
             }
         } else {
@@ -144,9 +168,9 @@ struct SplitLoader {
                 }
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const Split4 sp = split3(make_float4(blk[q][0], blk[q][1], blk[q][2], blk[q][3]));
+                    const Split4 sp = split_planes<NPL>(make_float4(blk[q][0], blk[q][1], blk[q][2], blk[q][3]));
 #pragma unroll
-                    for (int s = 0; s < 3; ++s) {
+                    for (int s = 0; s < NPL; ++s) {
                         __bf16 *dst = lds + s * PLANE + (4 * rq + q) * S + KU * kq;
                         if (KU == 4) {
                             *reinterpret_cast<bf16x4 *>(dst) = sp.p[s];
@@ -172,7 +196,7 @@ struct SplitLoader {
 // LDS holds NS stages; in iteration kt the producers fill the stage of tile kt+NS-1 while the
 // consumers work on tile kt, with one workgroup barrier per K tile.
 // ---------------------------------------------------------------------------------------------
-template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, bool AKC, bool BKC, int EPI, bool FAST>
+template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL, bool AKC, bool BKC, int EPI, bool FAST>
 __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *smem, int m0, int n0, int z,
                                                     int kbeg, int kend)
 {
@@ -180,10 +204,11 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
     constexpr int PF = 2;                         // K tiles of global loads in flight per producer
                                                   // (3, 4 and 6 measured: 1-5 % slower)
     constexpr int PT = 64 * NP;                   // producer threads
-    using LA = SplitLoader<BM, BK, AKC, PT>;
-    using LB = SplitLoader<BN, BK, BKC, PT>;
+    using LA = SplitLoader<BM, BK, AKC, PT, NPL>;
+    using LB = SplitLoader<BN, BK, BKC, PT, NPL>;
+    static_assert(NPL == 2 || NPL == 3, "two or three bf16 planes per operand");
     constexpr int S = BK + 8;
-    constexpr int STAGE_A = 3 * LA::PLANE, STAGE_B = 3 * LB::PLANE, STAGE = STAGE_A + STAGE_B;
+    constexpr int STAGE_A = NPL * LA::PLANE, STAGE_B = NPL * LB::PLANE, STAGE = STAGE_A + STAGE_B;
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int MI = WM / 32, NI = WN / 32;
     static_assert(MI >= 1 && NI >= 1 && WM % 32 == 0 && WN % 32 == 0 && BK % 16 == 0 && NS >= 2, "bad tile");
@@ -257,7 +282,7 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
     // (all its reads have completed, they feed the instructions about to be issued) and
     // guarantees that the next stage is filled.
     constexpr int KS = BK / 16;
-    bf16x8 fa[2][MI][3], fb[2][NI][3];
+    bf16x8 fa[2][MI][NPL], fb[2][NI][NPL];
     auto fetch_frags = [&](int set, int kt, int ks) {
         const __bf16 *st = smem + (kt % NS) * STAGE;
         const __bf16 *as = st + (wm * WM + li) * S + 8 * hh + ks * 16;
@@ -265,34 +290,39 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int s = 0; s < 3; ++s)
+            for (int s = 0; s < NPL; ++s)
                 fa[set][i][s] = *reinterpret_cast<const bf16x8 *>(as + s * LA::PLANE + i * 32 * S);
 #pragma unroll
         for (int j = 0; j < NI; ++j)
 #pragma unroll
-            for (int s = 0; s < 3; ++s)
+            for (int s = 0; s < NPL; ++s)
                 fb[set][j][s] = *reinterpret_cast<const bf16x8 *>(bs + s * LB::PLANE + j * 32 * S);
     };
     // the six products of one accumulator keep their order (smallest first); the MI*NI
     // accumulators alternate so that consecutive matrix instructions are independent
     auto multiply = [&](int set) {
-        constexpr int PA[6] = {2, 1, 0, 1, 0, 0}, PB[6] = {0, 1, 2, 0, 1, 0};
+        // three planes: a3b1, a2b2, a1b3, a2b1, a1b2, a1b1;  two planes: a2b1, a1b2, a1b1
+        constexpr int NPROD = NPL == 3 ? 6 : 3;
+        constexpr int PA3[6] = {2, 1, 0, 1, 0, 0}, PB3[6] = {0, 1, 2, 0, 1, 0};
+        constexpr int PA2[3] = {1, 0, 0}, PB2[3] = {0, 1, 0};
 #pragma unroll
-        for (int p = 0; p < 6; ++p)
+        for (int p = 0; p < NPROD; ++p)
 #pragma unroll
             for (int i = 0; i < MI; ++i)
 #pragma unroll
-                for (int j = 0; j < NI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i][PA[p]], fb[set][j][PB[p]],
-                                                                        acc[i][j], 0, 0, 0);
+                for (int j = 0; j < NI; ++j) {
+                    const int pa = NPL == 3 ? PA3[p] : PA2[p % 3], pb = NPL == 3 ? PB3[p] : PB2[p % 3];
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i][pa], fb[set][j][pb], acc[i][j], 0, 0, 0);
+                }
     };
     static_assert(KS % 2 == 0 || KS == 1, "k steps per tile: 1 or even");
     // issue order of one k step: a fragment read in the shadow of every second matrix
     // instruction (a burst of reads would keep the wavefront from issuing matrix work)
     auto interleave = [&]() {
+        constexpr int NREAD = NPL * (MI + NI), NMFMA = (NPL == 3 ? 6 : 3) * MI * NI;
 #pragma unroll
-        for (int q = 0; q < 3 * (MI + NI); ++q) {
-            __builtin_amdgcn_sched_group_barrier(0x008, (6 * MI * NI) / (3 * (MI + NI)), 0);
+        for (int q = 0; q < NREAD; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, NMFMA / NREAD > 0 ? NMFMA / NREAD : 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
     };
@@ -377,7 +407,7 @@ __device__ __forceinline__ void gemm_place(const GemmDev &g, int x, int q, int &
     else { const int item = x * g.nx + q; z = item / (g.ntm * g.ntn); tile = item % (g.ntm * g.ntn); }
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int LAY>
+template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL, int LAY>
 __device__ __forceinline__ void gemm_bf16x3_ws_problem(const GemmDev &g, __bf16 *smem, int x, int q)
 {
     constexpr bool AKC = (LAY & 1) != 0, BKC = (LAY & 2) != 0;
@@ -393,24 +423,24 @@ __device__ __forceinline__ void gemm_bf16x3_ws_problem(const GemmDev &g, __bf16 
                       (g.ldb % 4 == 0) && ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0) &&
                       (m0 + BM <= g.M) && (n0 + BN <= g.N) && ((kend - kbeg) % BK == 0);
     if (fast)
-        gemm_bf16x3_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, AKC, BKC, EPI, true>(g, smem, m0, n0, z, kbeg, kend);
+        gemm_bf16x3_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, NPL, AKC, BKC, EPI, true>(g, smem, m0, n0, z, kbeg, kend);
     else
-        gemm_bf16x3_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, AKC, BKC, EPI, false>(g, smem, m0, n0, z, kbeg, kend);
+        gemm_bf16x3_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, NPL, AKC, BKC, EPI, false>(g, smem, m0, n0, z, kbeg, kend);
 }
 
 // One launch carries one problem (LAY1 < 0) or two independent ones (used for the gradient
 // pass, where pairs of products have the same inputs ready at the same time and one of them
 // alone would leave compute units idle).  The slots of the first problem come first in every XCD.
-template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int LAY0, int LAY1>
+template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL, int LAY0, int LAY1>
 __global__ void __launch_bounds__(64 * (WGM * WGN + NP)) gemm_bf16x3_ws_kernel(GemmDev g0, GemmDev g1)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);
     const int x = blockIdx.x % 8, q = blockIdx.x / 8;
     if (LAY1 < 0 || q < g1.slot0)
-        gemm_bf16x3_ws_problem<BM, BN, BK, WGM, WGN, NP, NS, LAY0>(g0, smem, x, q);
+        gemm_bf16x3_ws_problem<BM, BN, BK, WGM, WGN, NP, NS, NPL, LAY0>(g0, smem, x, q);
     else
-        gemm_bf16x3_ws_problem<BM, BN, BK, WGM, WGN, NP, NS, (LAY1 < 0 ? LAY0 : LAY1)>(g1, smem, x, q - g1.slot0);
+        gemm_bf16x3_ws_problem<BM, BN, BK, WGM, WGN, NP, NS, NPL, (LAY1 < 0 ? LAY0 : LAY1)>(g1, smem, x, q - g1.slot0);
 }
 
 template <int BM, int BN, int BK>
@@ -439,16 +469,16 @@ inline GemmDev make_gemm_dev(const GemmArgs &a)
 }
 
 // b == nullptr: one problem (LAY1 is ignored and must be -1).
-template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int LAY0, int LAY1 = -1>
+template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL, int LAY0, int LAY1 = -1>
 hipError_t launch_gemm_bf16x3_ws_variant(const GemmArgs &a, hipStream_t s, const GemmArgs *b = nullptr)
 {
     GemmDev g0 = make_gemm_dev<BM, BN, BK>(a);
     GemmDev g1 = b ? make_gemm_dev<BM, BN, BK>(*b) : g0;
     if ((LAY1 >= 0) != (b != nullptr)) return hipErrorInvalidValue;
     g1.slot0 = g0.nx;
-    constexpr size_t smem = (size_t)NS * 3 * (BM + BN) * (BK + 8) * sizeof(__bf16);
+    constexpr size_t smem = (size_t)NS * NPL * (BM + BN) * (BK + 8) * sizeof(__bf16);
     static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS of a gfx950 CU");
-    auto kern = gemm_bf16x3_ws_kernel<BM, BN, BK, WGM, WGN, NP, NS, LAY0, LAY1>;
+    auto kern = gemm_bf16x3_ws_kernel<BM, BN, BK, WGM, WGN, NP, NS, NPL, LAY0, LAY1>;
     if (smem > 64 * 1024) {
         // raising the dynamic LDS limit is idempotent; doing it once per instantiation is enough
         static bool raised = false;

@@ -57,13 +57,13 @@ static int layout_of(const GemmArgs &a)
     return -1;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS>
+template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL>
 static hipError_t dispatch_bf16x3(const GemmArgs &a, hipStream_t s)
 {
     switch (layout_of(a)) {
 #define SSM_CASE(akc, bkc, epi) \
     case gemm_layout(akc, bkc, epi): \
-        return launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, gemm_layout(akc, bkc, epi)>(a, s);
+        return launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, NPL, gemm_layout(akc, bkc, epi)>(a, s);
         SSM_CASE(true, true, 0) SSM_CASE(true, true, 1) SSM_CASE(true, true, 2)
         SSM_CASE(true, false, 0) SSM_CASE(true, false, 1) SSM_CASE(false, false, 0)
         SSM_CASE(true, false, 3) SSM_CASE(true, true, 4) SSM_CASE(true, false, 5)
@@ -76,6 +76,14 @@ static bool use_f32_mfma()
 {
     const char *e = std::getenv("SSM_GEMM_F32");
     return e && e[0] == '1';
+}
+
+// SSM_GEMM_SPLIT=2 selects the reduced-precision mode: two bf16 planes per operand and three
+// products (relative error of a product below 2^-16 instead of 2^-23).  Default: three planes.
+static bool use_two_planes()
+{
+    const char *e = std::getenv("SSM_GEMM_SPLIT");
+    return e && e[0] == '2';
 }
 
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
@@ -101,8 +109,12 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
     // measured on MI355X at the benchmark shapes: 128x128x32 tiles with 4 consumer and 8 producer
     // wavefronts; 64x128 tiles (staging per multiply-add is 1.5x there) when the wide tile would
     // leave CUs without work
-    if (tiles128 >= 200) return dispatch_bf16x3<128, 128, 32, 2, 2, 8, 2>(a, s);
-    return dispatch_bf16x3<64, 128, 32, 2, 2, 8, 2>(a, s);
+    if (use_two_planes()) {
+        if (tiles128 >= 200) return dispatch_bf16x3<128, 128, 32, 2, 2, 8, 2, 2>(a, s);
+        return dispatch_bf16x3<64, 128, 32, 2, 2, 8, 2, 2>(a, s);
+    }
+    if (tiles128 >= 200) return dispatch_bf16x3<128, 128, 32, 2, 2, 8, 2, 3>(a, s);
+    return dispatch_bf16x3<64, 128, 32, 2, 2, 8, 2, 3>(a, s);
 }
 
 // Two independent problems in one launch of 128x128 tiles.  The pairs of the gradient pass:
@@ -116,8 +128,13 @@ hipError_t launch_gemm_pair(const GemmArgs &a, const GemmArgs &b, hipStream_t s)
         constexpr int NN0 = gemm_layout(true, false, 0), NN1 = gemm_layout(true, false, 1),
                       TN0 = gemm_layout(false, false, 0);
         const int la = layout_of(a), lb = layout_of(b);
-        if (la == NN0 && lb == TN0) return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, NN0, TN0>(a, s, &b);
-        if (la == NN1 && lb == TN0) return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, NN1, TN0>(a, s, &b);
+        if (use_two_planes()) {
+            if (la == NN0 && lb == TN0) return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, NN0, TN0>(a, s, &b);
+            if (la == NN1 && lb == TN0) return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, NN1, TN0>(a, s, &b);
+        } else {
+            if (la == NN0 && lb == TN0) return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 3, NN0, TN0>(a, s, &b);
+            if (la == NN1 && lb == TN0) return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 3, NN1, TN0>(a, s, &b);
+        }
     }
     hipError_t e = launch_gemm(a, s);
     return e != hipSuccess ? e : launch_gemm(b, s);
