@@ -44,6 +44,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="index into the benchmark configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-iters", type=int, default=30)
+    ap.add_argument("--path-only", action="store_true",
+                    help="skip the sections beside the hot path (reduced-precision mode, block_ops, step_mode): "
+                         "used for the rocprofv3 runs so that every kernel in the trace belongs to one role")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -108,7 +111,7 @@ def main():
 
     # ---- the opt-in reduced-precision mode of the projections, timed the same way (never `value`)
     two_plane = None
-    if os.environ.get("SSM_GEMM_F32", "") != "1" and os.environ.get("SSM_GEMM_SPLIT", "") != "2":
+    if not args.path_only and os.environ.get("SSM_GEMM_F32", "") != "1" and os.environ.get("SSM_GEMM_SPLIT", "") != "2":
         os.environ["SSM_GEMM_SPLIT"] = "2"
         try:
             for _ in range(args.warmup):
@@ -154,7 +157,7 @@ def main():
                     "unit": "TFLOP/s", "frac": round(dom_fp32_tflops / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": None}
     else:
         ach = BF16_PRODUCTS * dom_fp32_tflops
-        roofline = {"kernel": "gemm_bf16x3_ws_kernel<128,128,32,2,2,8,2,3,-1> (input projection)",
+        roofline = {"kernel": "gemm_bf16x3_ws_kernel<128,128,32,2,2,8,2,3,3,-1> (input projection)",
                     "bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(ach / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": TRAFFIC_PROJECT_IN,
                     "note": "achieved counts the 6 bf16 MFMA products per fp32 multiply-add that the kernel "
@@ -194,9 +197,10 @@ def main():
                           "note": "whole forward + gradient pass against the HBM peak, for reference only: the path "
                                   "is matrix-core bound (about 290 flop per compulsory byte at this shape)"},
         "reduced_precision_mode": two_plane,
-        "block_ops": block_ops(ssm, torch, wl, T, H),
-        "step_mode": step_mode(ssm, torch, d, H, P),
     }
+    if not args.path_only:
+        result["block_ops"] = block_ops(ssm, torch, wl, T, H)
+        result["step_mode"] = step_mode(ssm, torch, d, H, P)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, inp)
     print(json.dumps(result))
