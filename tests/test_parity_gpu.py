@@ -62,6 +62,31 @@ def test_edge_shapes(case):
     check_workload(w, backward=True)
 
 
+def _random_shapes(n, seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = []
+    for i in range(n):
+        Bt = int(rng.integers(1, 10))
+        L = int(rng.choice([rng.integers(1, 40), rng.integers(40, 300), rng.integers(300, 900)]))
+        H = int(rng.choice([rng.integers(1, 20), rng.integers(20, 200), 4 * rng.integers(5, 60)]))
+        P = int(rng.choice([rng.integers(1, 20), rng.integers(20, 150), 2 * rng.integers(8, 90)]))
+        out.append(("rand%d" % i, Bt, L, H, P, float(rng.choice([0.0, 0.02, 0.3])), bool(rng.integers(0, 2)),
+                    bool(rng.integers(0, 2)), 100 + i))
+    return out
+
+
+RANDOM_SHAPES = _random_shapes(16, 20250220)
+
+
+@pytest.mark.parametrize("case", RANDOM_SHAPES, ids=["%s_%dx%dx%dx%d" % c[:5] for c in RANDOM_SHAPES])
+def test_seeded_random_shapes(case):
+    """Shapes nobody picked by hand: every combination of ragged tiles, guarded and fast GEMM paths,
+    one or several workgroups along time, flags and initial states that the seeded draw produces."""
+    name, Bt, L, H, P, pr, ff, x0, seed = case
+    print("random shape", case, flush=True)
+    check_workload(wl.custom(name, Bt, L, H, P, p_reset=pr, force_first=ff, with_x0=x0, seed=seed), backward=True)
+
+
 def test_reset_at_last_step_and_x0_with_first_step_reset():
     w = wl.custom("last", 3, 50, 16, 24, with_x0=True, seed=3)
     inp = wl.gen_inputs(w)
