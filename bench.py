@@ -201,6 +201,7 @@ def main():
     if not args.path_only:
         result["block_ops"] = block_ops(ssm, torch, wl, T, H)
         result["step_mode"] = step_mode(ssm, torch, d, H, P)
+        result["s5_block"] = s5_block(ssm, torch, wl, d, Bt, L, H, P)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, inp)
     print(json.dumps(result))
@@ -266,6 +267,23 @@ def step_mode(ssm, torch, d, H, P, Bt=1024, horizon=10):
     return {"shape": "Bt=%d H=%d P=%d horizon=%d" % (Bt, H, P, horizon), "fwd_us_per_step": round(f_ms * 1e3, 2),
             "bwd_us_per_step": round(b_ms * 1e3, 2),
             "note": "dependent steps (two GEMM launches each), replayed as one HIP graph; latency bound"}
+
+
+def s5_block(ssm, torch, wl, d, Bt, L, H, P, iters=10):
+    """SSM layer + half-GLU gate through ssm_block_fwd / ssm_block_bwd at the benchmark shape."""
+    W = torch.from_numpy(wl.gen_half_glu(4, H, seed=1)["W"]).cuda()
+    par = (d["Lambda"], d["B"], d["C"], d["D"], d["log_delta"], W)
+    ws_f = torch.empty(ssm.ssm_block_workspace_bytes(Bt, L, H, P, False), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(ssm.ssm_block_workspace_bytes(Bt, L, H, P, True), dtype=torch.uint8, device="cuda")
+    f = ssm.ssm_block_fwd(*par, d["u"], d["is_first"], d["x0"], workspace=ws_f)
+    f_ms = graph_time_ms(torch, lambda i: ssm.ssm_block_fwd(*par, d["u"], d["is_first"], d["x0"], workspace=ws_f), iters)
+    b_ms = graph_time_ms(torch, lambda i: ssm.ssm_block_bwd(*par, d["u"], d["is_first"], d["x0"], f["x"], f["y"], f["gate"],
+                                                            d["dy"], workspace=ws_b), iters)
+    T = Bt * L
+    return {"shape": "Bt=%d L=%d H=%d P=%d" % (Bt, L, H, P), "fwd_us": round(f_ms * 1e3, 1), "bwd_us": round(b_ms * 1e3, 1),
+            "Mtokens_per_s": round(T / ((f_ms + b_ms) * 1e-3) / 1e6, 2),
+            "note": "layer + gate, forward and gradient pass, replayed as HIP graphs (includes the binding's output "
+                    "allocations inside the graph); GELU of the layer output is formed in the output projection's store"}
 
 
 def block_ops(ssm, torch, wl, T, H, iters=20):

@@ -204,6 +204,28 @@ ssm_status ssm_half_glu_bwd(const float *u, const float *W, const float *gate, c
                             int64_t T, int64_t H, float *du, float *dW,
                             void *workspace, size_t ws_bytes, void *stream);
 
+/* The S5 sequence layer as the appendix draws it from the parts the text defines: the resettable SSM
+ * layer followed by the half-GLU gate, out = y (.) sigmoid(W^T GELU(y)) with y the layer's output.
+ * The output projection stores GELU(y) next to y, so the gate costs one more product and no
+ * separate element-wise pass.  Arguments as in ssm_scan_fwd / ssm_scan_bwd and ssm_half_glu_*.
+ *   ssm_block_fwd  out: y [Bt,L,H] (the layer's output, needed by the gradient pass), out [Bt,L,H],
+ *                       gate [Bt,L,H] (NULL allowed when no gradient pass follows), x, x_last
+ *   ssm_block_bwd  in : x, y, gate (from the forward call), dout [Bt,L,H] (16-byte aligned, as y and gate)
+ *                  out: the gradients of ssm_scan_bwd and dW [H,H]
+ * Workspace: ssm_block_workspace_bytes(Bt, L, H, P, want_bwd).  ssm_workspace_status applies.   */
+size_t ssm_block_workspace_bytes(int64_t Bt, int64_t L, int64_t H, int64_t P, int want_bwd);
+ssm_status ssm_block_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, const float *D,
+                         const float *log_delta, const float *W, const float *u, const uint8_t *is_first,
+                         const ssm_c64 *x0, int64_t Bt, int64_t L, int64_t H, int64_t P,
+                         float *y, float *out, float *gate, ssm_c64 *x, ssm_c64 *x_last,
+                         void *workspace, size_t ws_bytes, void *stream);
+ssm_status ssm_block_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, const float *D,
+                         const float *log_delta, const float *W, const float *u, const uint8_t *is_first,
+                         const ssm_c64 *x0, int64_t Bt, int64_t L, int64_t H, int64_t P,
+                         const ssm_c64 *x, const float *y, const float *gate, const float *dout,
+                         float *du, ssm_c64 *dLambda, ssm_c64 *dB, ssm_c64 *dC, float *dD, float *dlog_delta,
+                         ssm_c64 *dx0, float *dW, void *workspace, size_t ws_bytes, void *stream);
+
 /* Measurement aids: the same code path as ssm_scan_fwd / ssm_scan_bwd, with a HIP event recorded
  * on `stream` around every kernel.  They wait for the stream before returning and write the
  * milliseconds of each stage to the HOST array stage_ms:

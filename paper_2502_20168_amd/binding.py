@@ -29,7 +29,7 @@ EXPORTS = ("ssm_strerror", "ssm_version", "ssm_workspace_bytes", "ssm_discretize
            "ssm_scan_bwd", "ssm_scan_states", "ssm_scan_states_reverse", "ssm_scan_fwd_profiled",
            "ssm_scan_bwd_profiled", "ssm_workspace_status", "ssm_step_plan_bytes", "ssm_step_prepare", "ssm_step",
            "ssm_step_bwd", "ssm_lambda_return", "ssm_lambda_return_bwd", "ssm_half_glu_workspace_bytes", "ssm_half_glu_fwd",
-           "ssm_half_glu_bwd")
+           "ssm_half_glu_bwd", "ssm_block_workspace_bytes", "ssm_block_fwd", "ssm_block_bwd")
 
 _lib = None
 _vp, _i64, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t
@@ -91,6 +91,12 @@ def lib():
         L.ssm_half_glu_fwd.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp, _vp, _sz, _vp]
         L.ssm_half_glu_bwd.restype = ctypes.c_int
         L.ssm_half_glu_bwd.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _vp, _vp, _vp, _sz, _vp]
+        L.ssm_block_workspace_bytes.restype = _sz
+        L.ssm_block_workspace_bytes.argtypes = [_i64, _i64, _i64, _i64, ctypes.c_int]
+        L.ssm_block_fwd.restype = ctypes.c_int
+        L.ssm_block_fwd.argtypes = [_vp] * 9 + [_i64] * 4 + [_vp] * 5 + [_vp, _sz, _vp]
+        L.ssm_block_bwd.restype = ctypes.c_int
+        L.ssm_block_bwd.argtypes = [_vp] * 9 + [_i64] * 4 + [_vp] * 4 + [_vp] * 8 + [_vp, _sz, _vp]
         _lib = L
     return _lib
 
@@ -401,8 +407,70 @@ def ssm_half_glu_bwd(u, W, gate, dy, *, workspace=None, du=None, dW=None, stream
     rc = lib().ssm_half_glu_bwd(_ptr(u), _ptr(W), _ptr(gate), _ptr(dy), T, H, _ptr(du), _ptr(dW), _ptr(ws), ws.numel(),
                                 _stream(stream))
     if rc != SSM_OK:
-        raise SsmError(rc, "ssm_half_glu_bwd")
+        raise SsmError(rc, "ssm_half_glu_bwd", "ssm_block_workspace_bytes", "ssm_block_fwd", "ssm_block_bwd")
     return du, dW
+
+
+def ssm_block_workspace_bytes(Bt: int, L: int, H: int, P: int, want_bwd: bool) -> int:
+    return int(lib().ssm_block_workspace_bytes(Bt, L, H, P, 1 if want_bwd else 0))
+
+
+def _block_workspace(Bt, L, H, P, want_bwd, device):
+    torch = _torch()
+    n = ssm_block_workspace_bytes(Bt, L, H, P, want_bwd)
+    if n == 0:
+        raise SsmError(SSM_ERR_UNSUPPORTED, "ssm_block_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def ssm_block_fwd(Lambda, B, C, D, log_delta, W, u, is_first=None, x0=None, *, want_gate=True, workspace=None,
+                  stream=None):
+    """SSM layer followed by the half-GLU gate.  Returns dict(y, out, gate, x, x_last)."""
+    torch = _torch()
+    Bt, L, H = u.shape
+    P = Lambda.shape[0]
+    _chk(Lambda, torch.complex64, (P,), "Lambda")
+    _chk(B, torch.complex64, (P, H), "B")
+    _chk(C, torch.complex64, (H, P), "C")
+    _chk(D, torch.float32, (H,), "D")
+    _chk(log_delta, torch.float32, (P,), "log_delta")
+    _chk(W, torch.float32, (H, H), "W")
+    _chk(u, torch.float32, (Bt, L, H), "u")
+    _chk(is_first, torch.uint8, (Bt, L), "is_first")
+    _chk(x0, torch.complex64, (Bt, P), "x0")
+    ws = workspace if workspace is not None else _block_workspace(Bt, L, H, P, False, u.device)
+    y, out = torch.empty_like(u), torch.empty_like(u)
+    gate = torch.empty_like(u) if want_gate else None
+    x = torch.empty((Bt, L, P), dtype=torch.complex64, device=u.device)
+    x_last = torch.empty((Bt, P), dtype=torch.complex64, device=u.device)
+    rc = lib().ssm_block_fwd(_ptr(Lambda), _ptr(B), _ptr(C), _ptr(D), _ptr(log_delta), _ptr(W), _ptr(u), _ptr(is_first),
+                             _ptr(x0), Bt, L, H, P, _ptr(y), _ptr(out), _ptr(gate), _ptr(x), _ptr(x_last),
+                             _ptr(ws), ws.numel(), _stream(stream))
+    if rc != SSM_OK:
+        raise SsmError(rc, "ssm_block_fwd")
+    return {"y": y, "out": out, "gate": gate, "x": x, "x_last": x_last}
+
+
+def ssm_block_bwd(Lambda, B, C, D, log_delta, W, u, is_first, x0, x, y, gate, dout, *, workspace=None, stream=None):
+    """Gradient pass of ssm_block_fwd.  Returns dict(du, dLambda, dB, dC, dD, dlog_delta, dx0, dW)."""
+    torch = _torch()
+    Bt, L, H = u.shape
+    P = Lambda.shape[0]
+    for name, t in (("u", u), ("y", y), ("gate", gate), ("dout", dout)):
+        _chk(t, torch.float32, (Bt, L, H), name)
+    _chk(x, torch.complex64, (Bt, L, P), "x")
+    _chk(W, torch.float32, (H, H), "W")
+    ws = workspace if workspace is not None else _block_workspace(Bt, L, H, P, True, u.device)
+    o = {"du": torch.empty_like(u), "dLambda": torch.empty_like(Lambda), "dB": torch.empty_like(B),
+         "dC": torch.empty_like(C), "dD": torch.empty_like(D), "dlog_delta": torch.empty_like(log_delta),
+         "dx0": torch.empty((Bt, P), dtype=torch.complex64, device=u.device), "dW": torch.empty_like(W)}
+    rc = lib().ssm_block_bwd(_ptr(Lambda), _ptr(B), _ptr(C), _ptr(D), _ptr(log_delta), _ptr(W), _ptr(u), _ptr(is_first),
+                             _ptr(x0), Bt, L, H, P, _ptr(x), _ptr(y), _ptr(gate), _ptr(dout),
+                             _ptr(o["du"]), _ptr(o["dLambda"]), _ptr(o["dB"]), _ptr(o["dC"]), _ptr(o["dD"]),
+                             _ptr(o["dlog_delta"]), _ptr(o["dx0"]), _ptr(o["dW"]), _ptr(ws), ws.numel(), _stream(stream))
+    if rc != SSM_OK:
+        raise SsmError(rc, "ssm_block_bwd")
+    return o
 
 
 def ssm_workspace_status(workspace, stream=None) -> int:

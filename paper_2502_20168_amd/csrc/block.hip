@@ -2,6 +2,7 @@
 // section and the half-GLU gate of the S5 sequence layer (appendix), with their adjoints.
 #include "../../include/ssm.h"
 #include "ssm_internal.h"
+#include "gemm_f32_kernel.h"
 
 namespace ssm {
 namespace {
@@ -84,11 +85,7 @@ __global__ void __launch_bounds__(256) lambda_return_bwd_kernel(const float *__r
 // The element-wise halves run as small streaming kernels (float4 per thread); the products run
 // on the projection GEMM with the gate fused into its store (epilogues 3 and 4).
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ float gelu_exact(float x)
-{
-    // x Phi(x) with Phi(x) = erfc(-x / sqrt 2) / 2 (no cancellation in the lower tail)
-    return 0.5f * x * erfcf(-0.70710678118654752f * x);
-}
+__device__ __forceinline__ float gelu_exact(float x) { return gelu_value(x); }
 
 __global__ void __launch_bounds__(256) gelu_kernel(const float4 *__restrict__ u, float4 *__restrict__ x1, long n4,
                                                    const float *__restrict__ ut, float *__restrict__ x1t, long n)

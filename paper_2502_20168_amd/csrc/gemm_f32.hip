@@ -51,6 +51,7 @@ static int layout_of(const GemmArgs &a)
     if (a.epilogue == 2) return (a.a_kcontig && a.b_kcontig) ? gemm_layout(true, true, 2) : -1;
     if (a.epilogue == 3) return (a.a_kcontig && !a.b_kcontig) ? gemm_layout(true, false, 3) : -1;
     if (a.epilogue == 4) return (a.a_kcontig && a.b_kcontig) ? gemm_layout(true, true, 4) : -1;
+    if (a.epilogue == 6) return (a.a_kcontig && a.b_kcontig) ? gemm_layout(true, true, 6) : -1;
     if (a.epilogue == 5) return (a.a_kcontig && !a.b_kcontig && a.N % 2 == 0) ? gemm_layout(true, false, 5) : -1;
     if (a.a_kcontig) return gemm_layout(true, a.b_kcontig != 0, a.epilogue);
     if (!a.b_kcontig && !a.epilogue) return gemm_layout(false, false, 0);
@@ -66,7 +67,7 @@ static hipError_t dispatch_bf16x3(const GemmArgs &a, hipStream_t s)
         return launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, NPL, gemm_layout(akc, bkc, epi)>(a, s);
         SSM_CASE(true, true, 0) SSM_CASE(true, true, 1) SSM_CASE(true, true, 2)
         SSM_CASE(true, false, 0) SSM_CASE(true, false, 1) SSM_CASE(false, false, 0)
-        SSM_CASE(true, false, 3) SSM_CASE(true, true, 4) SSM_CASE(true, false, 5)
+        SSM_CASE(true, false, 3) SSM_CASE(true, true, 4) SSM_CASE(true, false, 5) SSM_CASE(true, true, 6)
 #undef SSM_CASE
     default: return hipErrorInvalidValue;
     }
@@ -90,9 +91,10 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
 {
     if (a.M <= 0 || a.N <= 0 || a.K <= 0) return hipErrorInvalidValue;
     if (a.splits > 1 && a.epilogue) return hipErrorInvalidValue;
-    if (a.epilogue < 0 || a.epilogue > 5 || (a.epilogue && a.epilogue != 5 && !a.E)) return hipErrorInvalidValue;
+    if (a.epilogue < 0 || a.epilogue > 6 || (a.epilogue && a.epilogue != 5 && !a.E)) return hipErrorInvalidValue;
     if (a.epilogue == 5 && a.C2 && !a.diag) return hipErrorInvalidValue;
-    if ((a.epilogue == 1 || a.epilogue == 2) && !a.diag) return hipErrorInvalidValue;
+    if ((a.epilogue == 1 || a.epilogue == 2 || a.epilogue == 6) && !a.diag) return hipErrorInvalidValue;
+    if (a.epilogue == 6 && !a.C2) return hipErrorInvalidValue;
     if (a.epilogue == 4 && (!a.E2 || !a.E3)) return hipErrorInvalidValue;
     const long splits = a.splits < 1 ? 1 : a.splits;
     const long tiles128 = (long)((a.M + 127) / 128) * ((a.N + 127) / 128) * splits;

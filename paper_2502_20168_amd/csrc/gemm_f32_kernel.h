@@ -44,6 +44,8 @@ struct GemmDev {
 //          and the stored value is E[row, col] * s        (E = the gated input u)
 //   EPI 4: adjoint of the gate with respect to its input: E * E2 + v * GELU'(E3)
 //          (E = dy, E2 = the saved gate s, E3 = u; v = the product dz W^T)
+//   EPI 6: v + diag[col] * E[row, col] as EPI 1, and GELU of that value into C2 (the output
+//          projection feeding the half-GLU gate of the S5 block)
 //   EPI 5 (bf16x3 kernel only, handled where the tile is stored because it needs the partner
 //          column): adjoint of one recurrence step.  Columns are (re, im) pairs; the stored value is
 //          g = v + E (E = the gradient that arrives from the next step, may be null) and C2 gets
@@ -54,6 +56,11 @@ __device__ __forceinline__ float gelu_derivative(float x)
     const float cdf = 0.5f * erfcf(-0.70710678118654752f * x);
     const float pdf = 0.39894228040143268f * __expf(-0.5f * x * x);
     return fmaf(x, pdf, cdf);
+}
+__device__ __forceinline__ float gelu_value(float x)
+{
+    // x Phi(x) with Phi(x) = erfc(-x / sqrt 2) / 2 (no cancellation in the lower tail)
+    return 0.5f * x * erfcf(-0.70710678118654752f * x);
 }
 __device__ __forceinline__ float sigmoidf(float z)
 {
@@ -80,6 +87,11 @@ __device__ __forceinline__ float gemm_epilogue_apply(const GemmDev &g, long row,
     if (EPI == 4) {
         const long i = row * g.lde + col;
         return fmaf(v, gelu_derivative(g.E3[i]), g.E[i] * g.E2[i]);
+    }
+    if (EPI == 6) {
+        const float y = v + g.diag[col] * g.E[row * g.lde + col];
+        g.C2[row * g.ldc + col] = gelu_value(y);
+        return y;
     }
     return v;
 }

@@ -102,7 +102,7 @@ struct StageTimer {
 ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, const float *D,
                    const float *log_delta, const float *u, const uint8_t *is_first, const ssm_c64 *x0,
                    int64_t Bt, int64_t L, int64_t H, int64_t P, float *y, ssm_c64 *x, ssm_c64 *x_last,
-                   void *workspace, size_t ws_bytes, hipStream_t s, StageTimer *timer)
+                   void *workspace, size_t ws_bytes, hipStream_t s, StageTimer *timer, float *gelu_y = nullptr)
 {
     if (!Lambda || !B || !C || !D || !log_delta || !u || !y) return SSM_ERR_INVALID_ARG;
     Layout lo;
@@ -158,6 +158,7 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     g2.A = reinterpret_cast<const float *>(xs); g2.lda = 2 * P; g2.a_kcontig = 1;
     g2.B = Cc; g2.ldb = 2 * P; g2.b_kcontig = 1;
     g2.C = y; g2.ldc = H; g2.diag = D; g2.E = u; g2.lde = H; g2.epilogue = 1;
+    if (gelu_y) { g2.epilogue = 6; g2.C2 = gelu_y; }       // the S5 block: GELU(y) for the gate, same store
     g2.M = T; g2.N = (int)H; g2.K = (int)(2 * P); g2.splits = 1;
     HIP_TRY(launch_gemm(g2, s));
     MARK();
@@ -562,6 +563,87 @@ ssm_status ssm_step_bwd(const void *plan, size_t plan_bytes, const float *D, con
     g2.M = (int)Bt; g2.N = (int)H; g2.K = (int)(2 * P); g2.splits = 1;
     HIP_TRY(launch_gemm(g2, s));
     return SSM_OK;
+}
+
+namespace {
+struct BlockLayout { size_t ssm, x1, glu, dypre, total; };
+bool make_block_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, BlockLayout &o)
+{
+    Layout lo;
+    if (make_layout(Bt, L, H, P, bwd, lo) != SSM_OK) return false;
+    const size_t TH = up((size_t)Bt * L * H * 4);
+    size_t off = 0;
+    o.ssm = off; off += up(lo.total);
+    o.x1 = o.glu = o.dypre = 0;
+    if (!bwd) {
+        o.x1 = off; off += TH;
+    } else {
+        const size_t g = ssm_half_glu_workspace_bytes(Bt * L, H, 1);
+        if (g == 0) return false;
+        o.glu = off; off += up(g);
+        o.dypre = off; off += TH;
+    }
+    o.total = off;
+    return true;
+}
+}  // namespace
+
+size_t ssm_block_workspace_bytes(int64_t Bt, int64_t L, int64_t H, int64_t P, int want_bwd)
+{
+    BlockLayout bl;
+    return make_block_layout(Bt, L, H, P, want_bwd != 0, bl) ? bl.total : 0;
+}
+
+ssm_status ssm_block_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, const float *D,
+                         const float *log_delta, const float *W, const float *u, const uint8_t *is_first,
+                         const ssm_c64 *x0, int64_t Bt, int64_t L, int64_t H, int64_t P,
+                         float *y, float *out, float *gate, ssm_c64 *x, ssm_c64 *x_last,
+                         void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!W || !out || !y) return SSM_ERR_INVALID_ARG;
+    ssm_status st = check_dims(Bt, L, H, P);
+    if (st != SSM_OK) return st;
+    BlockLayout bl;
+    if (!make_block_layout(Bt, L, H, P, false, bl)) return SSM_ERR_UNSUPPORTED;
+    if (misaligned(W, 4) || misaligned(out, 4) || misaligned(gate, 4)) return SSM_ERR_INVALID_ARG;
+    if (!workspace || misaligned(workspace, ALIGN) || ws_bytes < bl.total) return SSM_ERR_WORKSPACE;
+    char *ws = static_cast<char *>(workspace);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float *x1 = reinterpret_cast<float *>(ws + bl.x1);
+    // the layer; its output projection also stores x1 = GELU(y)
+    st = run_fwd(Lambda, B, C, D, log_delta, u, is_first, x0, Bt, L, H, P, y, x, x_last, ws + bl.ssm, bl.x1 - bl.ssm, s,
+                 nullptr, x1);
+    if (st != SSM_OK) return st;
+    // out[t, j] = y[t, j] sigmoid(sum_i x1[t, i] W[i, j])
+    GemmArgs g{};
+    g.A = x1; g.lda = H; g.a_kcontig = 1;
+    g.B = W; g.ldb = H; g.b_kcontig = 0;
+    g.C = out; g.ldc = H; g.E = y; g.lde = H; g.C2 = gate; g.epilogue = 3;
+    g.M = (int)(Bt * L); g.N = (int)H; g.K = (int)H; g.splits = 1;
+    HIP_TRY(launch_gemm(g, s));
+    return SSM_OK;
+}
+
+ssm_status ssm_block_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, const float *D,
+                         const float *log_delta, const float *W, const float *u, const uint8_t *is_first,
+                         const ssm_c64 *x0, int64_t Bt, int64_t L, int64_t H, int64_t P,
+                         const ssm_c64 *x, const float *y, const float *gate, const float *dout,
+                         float *du, ssm_c64 *dLambda, ssm_c64 *dB, ssm_c64 *dC, float *dD, float *dlog_delta,
+                         ssm_c64 *dx0, float *dW, void *workspace, size_t ws_bytes, void *stream)
+{
+    if (!W || !y || !gate || !dout || !dW) return SSM_ERR_INVALID_ARG;
+    ssm_status st = check_dims(Bt, L, H, P);
+    if (st != SSM_OK) return st;
+    BlockLayout bl;
+    if (!make_block_layout(Bt, L, H, P, true, bl)) return SSM_ERR_UNSUPPORTED;
+    if (!workspace || misaligned(workspace, ALIGN) || ws_bytes < bl.total) return SSM_ERR_WORKSPACE;
+    char *ws = static_cast<char *>(workspace);
+    float *dypre = reinterpret_cast<float *>(ws + bl.dypre);
+    // the gate's adjoint turns dout into the gradient of the layer's output, then the layer's own pass
+    st = ssm_half_glu_bwd(y, W, gate, dout, Bt * L, H, dypre, dW, ws + bl.glu, bl.dypre - bl.glu, stream);
+    if (st != SSM_OK) return st;
+    return run_bwd(Lambda, B, C, D, log_delta, u, is_first, x0, Bt, L, H, P, x, dypre, du, dLambda, dB, dC, dD,
+                   dlog_delta, dx0, ws + bl.ssm, bl.glu - bl.ssm, static_cast<hipStream_t>(stream), nullptr);
 }
 
 ssm_status ssm_workspace_status(const void *workspace, void *stream)

@@ -14,6 +14,7 @@ namespace ssm {
 // as interleaved complex and the columns of C and E interleaved (re, im) pairs (one recurrence step);
 // 3: C = E (.) sigmoid(product), sigmoid kept in C2 when non-null (half-GLU gate);
 // 4: C = E (.) E2 + product (.) GELU'(E3) (adjoint of the gate with respect to its input);
+// 6: as 1, and C2 = GELU(C) (output projection that feeds the half-GLU gate);
 // 5: C = product + E (E may be null), C2 = [not rowflag[m]] conj(Abar) (.) C with diag = Abar and complex
 //    (re, im) column pairs (adjoint of one recurrence step)
 // A(m,k) = a_kcontig ? A[m*lda + k] : A[k*lda + m];  B(n,k) = b_kcontig ? B[n*ldb + k] : B[k*ldb + n]

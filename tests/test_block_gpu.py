@@ -103,3 +103,38 @@ def test_half_glu_is_bitwise_repeatable():
         torch.cuda.synchronize()
         outs.append((y.clone(), du.clone(), dW.clone()))
     assert all(torch.equal(a, b) for a, b in zip(*outs))
+
+
+@pytest.mark.parametrize("Bt,L,H,P", [(16, 256, 512, 512), (3, 129, 50, 33), (2, 600, 96, 40)])
+def test_s5_block_matches_oracle_composition(Bt, L, H, P):
+    """SSM layer + half-GLU gate in one call (GELU of the layer's output formed in the output
+    projection's store) against the two oracles composed: forward outputs, then every gradient."""
+    import torch
+    from oracle import ssm_oracle as sorc
+    from paper_2502_20168_amd import binding as ssm
+    w = wl.custom("block", Bt, L, H, P, backward=True, p_reset=0.02, force_first=True, with_x0=True, seed=41)
+    inp = wl.gen_inputs(w)
+    W = wl.gen_half_glu(4, H, seed=42)["W"]
+    par = (inp["Lambda"], inp["B"], inp["C"], inp["D"], inp["log_delta"])
+    rf = sorc.forward(*par, inp["u"], inp["is_first"], inp["x0"], nthreads=8)
+    y2 = rf["y"].reshape(Bt * L, H)
+    ref_out = borc.half_glu(y2, W).reshape(Bt, L, H)
+    dy_pre, ref_dW = borc.half_glu_grad(y2, W, inp["dy"].reshape(Bt * L, H))
+    rb = sorc.backward(*par, inp["u"], inp["is_first"], inp["x0"], rf["x"], dy_pre.reshape(Bt, L, H), nthreads=8)
+    d = ssm.to_device(inp)
+    Wd = torch.from_numpy(W).cuda()
+    f = ssm.ssm_block_fwd(d["Lambda"], d["B"], d["C"], d["D"], d["log_delta"], Wd, d["u"], d["is_first"], d["x0"])
+    b = ssm.ssm_block_bwd(d["Lambda"], d["B"], d["C"], d["D"], d["log_delta"], Wd, d["u"], d["is_first"], d["x0"],
+                          f["x"], f["y"], f["gate"], d["dy"])
+    torch.cuda.synchronize()
+    assert_close(f["y"].cpu().numpy(), rf["y"], TOL_FWD, "block y")
+    assert_close(f["out"].cpu().numpy(), ref_out, TOL_FWD, "block out")
+    assert_close(f["x_last"].cpu().numpy(), rf["x_last"], TOL_FWD, "block x_last")
+    assert_close(b["dW"].cpu().numpy(), ref_dW, TOL_GRAD, "block dW")
+    for k in ("du", "dLambda", "dB", "dC", "dD", "dlog_delta", "dx0"):
+        assert_close(b[k].cpu().numpy(), rb[k], TOL_GRAD, "block " + k)
+    # the fused call equals the two separate calls bit for bit
+    f2 = ssm.ssm_scan_fwd(d["Lambda"], d["B"], d["C"], d["D"], d["log_delta"], d["u"], d["is_first"], d["x0"])
+    out2, gate2 = ssm.ssm_half_glu_fwd(f2["y"].reshape(Bt * L, H), Wd)
+    torch.cuda.synchronize()
+    assert torch.equal(f2["y"], f["y"]) and torch.equal(out2.reshape(Bt, L, H), f["out"])

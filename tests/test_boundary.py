@@ -154,6 +154,20 @@ def test_block_entry_points_argument_errors(lib):
                                 None) == ssm.SSM_ERR_INVALID_ARG
 
 
+def test_s5_block_argument_errors(lib):
+    need_f, need_b = ssm.ssm_block_workspace_bytes(2, 8, 4, 4, False), ssm.ssm_block_workspace_bytes(2, 8, 4, 4, True)
+    assert need_f > ssm.ssm_workspace_bytes(2, 8, 4, 4, False) and need_b > ssm.ssm_workspace_bytes(2, 8, 4, 4, True)
+    assert ssm.ssm_block_workspace_bytes(2, 0, 4, 4, False) == 0
+    F = [FAKE] * 9
+    assert lib.ssm_block_fwd(*F, 2, 8, 4, 4, FAKE, None, None, FAKE, None, FAKE, need_f, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_block_fwd(*F, 2, 8, 4, 4, None, FAKE, None, FAKE, None, FAKE, need_f, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_block_fwd(*F, 2, 8, 4, 4, FAKE, FAKE, None, FAKE, None, FAKE, need_f - 1, None) == ssm.SSM_ERR_WORKSPACE
+    assert lib.ssm_block_fwd(*F, 2, 8, 0, 4, FAKE, FAKE, None, FAKE, None, FAKE, need_f, None) == ssm.SSM_ERR_INVALID_ARG
+    Gd = [FAKE] * 8
+    assert lib.ssm_block_bwd(*F, 2, 8, 4, 4, FAKE, FAKE, FAKE, None, *Gd, FAKE, need_b, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_block_bwd(*F, 2, 8, 4, 4, FAKE, FAKE, FAKE, FAKE, *Gd, FAKE, need_b - 1, None) == ssm.SSM_ERR_WORKSPACE
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import numpy as np
     import torch
