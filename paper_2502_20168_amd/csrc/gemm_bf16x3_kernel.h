@@ -18,6 +18,8 @@
 
 #include "gemm_f32_kernel.h"
 
+#include <atomic>
+
 namespace ssm {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -480,13 +482,18 @@ hipError_t launch_gemm_bf16x3_ws_variant(const GemmArgs &a, hipStream_t s, const
     static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS of a gfx950 CU");
     auto kern = gemm_bf16x3_ws_kernel<BM, BN, BK, WGM, WGN, NP, NS, NPL, LAY0, LAY1>;
     if (smem > 64 * 1024) {
-        // raising the dynamic LDS limit is idempotent; doing it once per instantiation is enough
-        static bool raised = false;
-        if (!raised) {
-            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        // raising the dynamic LDS limit is idempotent; once per instantiation and device is enough
+        // (the attribute belongs to the device's copy of the kernel)
+        constexpr int MAXDEV = 64;
+        static std::atomic<bool> raised[MAXDEV];
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= MAXDEV || !raised[dev].load(std::memory_order_acquire)) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)smem);
             if (e != hipSuccess) return e;
-            raised = true;
+            if (dev >= 0 && dev < MAXDEV) raised[dev].store(true, std::memory_order_release);
         }
     }
     const long slots = (long)g0.nx + (b ? g1.nx : 0);

@@ -108,15 +108,18 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
         if (a.a_kcontig && a.b_kcontig) return dispatch_f32<64, 64, 32, 2, 2>(a, s);
         return dispatch_f32<64, 64, 16, 2, 2>(a, s);
     }
-    // measured on MI355X at the benchmark shapes: 128x128x32 tiles with 4 consumer and 8 producer
-    // wavefronts; 64x128 tiles (staging per multiply-add is 1.5x there) when the wide tile would
-    // leave CUs without work
+    // measured on MI355X: 128x128x32 tiles with 4 consumer and 8 producer wavefronts when they give
+    // (nearly) every CU a workgroup; else 64x128x32 tiles (staging per multiply-add is 1.5x there);
+    // else, for the small products of step mode, 64x64x64 tiles (fewer, longer K steps)
+    const long tiles64x128 = (long)((a.M + 63) / 64) * ((a.N + 127) / 128) * splits;
     if (use_two_planes()) {
         if (tiles128 >= 200) return dispatch_bf16x3<128, 128, 32, 2, 2, 8, 2, 2>(a, s);
-        return dispatch_bf16x3<64, 128, 32, 2, 2, 8, 2, 2>(a, s);
+        if (tiles64x128 >= 200) return dispatch_bf16x3<64, 128, 32, 2, 2, 8, 2, 2>(a, s);
+        return dispatch_bf16x3<64, 64, 64, 2, 2, 8, 2, 2>(a, s);
     }
     if (tiles128 >= 200) return dispatch_bf16x3<128, 128, 32, 2, 2, 8, 2, 3>(a, s);
-    return dispatch_bf16x3<64, 128, 32, 2, 2, 8, 2, 3>(a, s);
+    if (tiles64x128 >= 200) return dispatch_bf16x3<64, 128, 32, 2, 2, 8, 2, 3>(a, s);
+    return dispatch_bf16x3<64, 64, 64, 2, 2, 8, 2, 3>(a, s);
 }
 
 // Two independent problems in one launch of 128x128 tiles.  The pairs of the gradient pass:
