@@ -87,6 +87,14 @@ def test_seeded_random_shapes(case):
     check_workload(wl.custom(name, Bt, L, H, P, p_reset=pr, force_first=ff, with_x0=x0, seed=seed), backward=True)
 
 
+@pytest.mark.parametrize("Bt,L,H,P", [(2, 5, 8, 65536), (2, 5, 65536, 4), (1, 300, 4, 8192)])
+def test_maximum_widths(Bt, L, H, P):
+    """The widest state and layer the library accepts (SSM_MAX_WIDTH = 65536) with few tokens: index
+    arithmetic, grids with tens of thousands of workgroups along the width, one lane group per
+    state block of the scan."""
+    check_workload(wl.custom("maxw", Bt, L, H, P, p_reset=0.1, with_x0=True, seed=77), backward=True)
+
+
 def test_reset_at_last_step_and_x0_with_first_step_reset():
     w = wl.custom("last", 3, 50, 16, 24, with_x0=True, seed=3)
     inp = wl.gen_inputs(w)
