@@ -181,7 +181,7 @@ def main():
     scan["frac_of_copy_kernel_cold"] = round(scan["cold_fwd_GBs"] / scan["copy_cold_GBs"], 4)
 
     result = {
-        "metric": "ssm_scan_fwd_bwd_throughput", "value": round(mtok, 3), "unit": "Mtokens/s",
+        "metric": "SSM scan fwd+bwd Mtokens/s (B=16, L=256, H=P=512); achieved HBM GB/s in scan_roofline and composite_hbm", "value": round(mtok, 3), "unit": "Mtokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32",
