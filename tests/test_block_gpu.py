@@ -138,3 +138,20 @@ def test_s5_block_matches_oracle_composition(Bt, L, H, P):
     out2, gate2 = ssm.ssm_half_glu_fwd(f2["y"].reshape(Bt * L, H), Wd)
     torch.cuda.synchronize()
     assert torch.equal(f2["y"], f["y"]) and torch.equal(out2.reshape(Bt, L, H), f["out"])
+
+
+def _block_random_shapes(n, seed):
+    rng = np.random.Generator(np.random.PCG64(seed))
+    return [(int(rng.integers(1, 3000)), int(rng.choice([rng.integers(1, 40), rng.integers(40, 400), 4 * rng.integers(8, 130)])))
+            for _ in range(n)]
+
+
+@pytest.mark.parametrize("T,H", _block_random_shapes(8, 424242))
+def test_half_glu_seeded_random_shapes(T, H):
+    test_half_glu_matches_oracle(T, H)
+
+
+@pytest.mark.parametrize("T,N", [(int(t), int(n)) for t, n in
+                                 np.random.Generator(np.random.PCG64(7)).integers([1, 1], [70, 9000], size=(8, 2))])
+def test_lambda_return_seeded_random_shapes(T, N):
+    test_lambda_return_matches_oracle(T, N)

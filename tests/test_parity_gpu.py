@@ -411,3 +411,50 @@ def test_step_mode_adjoint_rollout_equals_oracle_gradient(Bt, H, P, steps):
     torch.cuda.synchronize()
     assert none is None
     assert_close(du1.cpu().numpy()[:, None], ref1["du"], TOL_GRAD, "step du (single)")
+
+
+@pytest.mark.parametrize("Bt,L,H,P", [(4, 256, 128, 96), (2, 1500, 64, 80)])
+def test_captured_graph_replays_equal_eager(Bt, L, H, P):
+    """The non-profiled entry points only enqueue kernels (no allocation, no memset, no wait), so
+    one forward + gradient pass can be captured into a HIP graph.  Every replay, with eager work
+    and synchronisations of the program in between, must reproduce the eager results bit for bit
+    (second shape: several workgroups along time, i.e. the clear kernel and the look-back)."""
+    import torch
+    w = wl.custom("graph", Bt, L, H, P, backward=True, p_reset=0.01, with_x0=True, seed=61)
+    d = ssm.to_device(wl.gen_inputs(w))
+    par = (d["Lambda"], d["B"], d["C"], d["D"], d["log_delta"])
+    ws_f = ssm.alloc_workspace(Bt, L, H, P, False)
+    ws_b = ssm.alloc_workspace(Bt, L, H, P, True)
+    out_f = {"y": torch.empty_like(d["u"]), "x": torch.empty((Bt, L, P), dtype=torch.complex64, device="cuda"),
+             "x_last": torch.empty((Bt, P), dtype=torch.complex64, device="cuda")}
+    out_b = {"du": torch.empty_like(d["u"]), "dLambda": torch.empty_like(d["Lambda"]), "dB": torch.empty_like(d["B"]),
+             "dC": torch.empty_like(d["C"]), "dD": torch.empty_like(d["D"]),
+             "dlog_delta": torch.empty_like(d["log_delta"]),
+             "dx0": torch.empty((Bt, P), dtype=torch.complex64, device="cuda")}
+
+    def step():
+        ssm.ssm_scan_fwd(*par, d["u"], d["is_first"], d["x0"], workspace=ws_f, out=out_f)
+        ssm.ssm_scan_bwd(*par, d["u"], d["is_first"], d["x0"], out_f["x"], d["dy"], workspace=ws_b, out=out_b)
+
+    step()
+    torch.cuda.synchronize()
+    ref = {k: v.clone() for k, v in list(out_f.items()) + list(out_b.items())}
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()
+        torch.cuda.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for v in list(out_f.values()) + list(out_b.values()):
+            v.zero_()                                   # eager work between the replays
+        junk = torch.randn(1 << 20, device="cuda").sum().item()
+        assert np.isfinite(junk)
+        graph.replay()
+        torch.cuda.synchronize()
+        for k, v in list(out_f.items()) + list(out_b.items()):
+            assert torch.equal(v, ref[k]), "replay %d differs from the eager result in %s" % (rep, k)
+        assert ssm.ssm_workspace_status(ws_f) == ssm.SSM_OK and ssm.ssm_workspace_status(ws_b) == ssm.SSM_OK
