@@ -159,7 +159,9 @@ def main():
         ach = BF16_PRODUCTS * dom_fp32_tflops
         roofline = {"kernel": "gemm_bf16x3_ws_kernel<128,128,32,2,2,8,2,3,3,-1> (input projection)",
                     "bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(ach / PEAK_BF16_MFMA_TFLOPS, 4), "traffic": TRAFFIC_PROJECT_IN,
+                    "frac": round(ach / PEAK_BF16_MFMA_TFLOPS, 4),
+                    "traffic": TRAFFIC_PROJECT_IN["read_bytes"] + TRAFFIC_PROJECT_IN["write_bytes"],
+                    "traffic_detail": TRAFFIC_PROJECT_IN,
                     "note": "achieved counts the 6 bf16 MFMA products per fp32 multiply-add that the kernel "
                             "executes by design; fp32-equivalent rate and its ratio to the fp32 matrix peak below",
                     "fp32_equivalent_tflops": round(dom_fp32_tflops, 2),
