@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libssmscan.so")
 SOURCES = ["ssm_api.hip", "gemm_f32.hip", "scan.hip", "params.hip", "block.hip"]
 HEADERS = [os.path.join(CSRC, "ssm_internal.h"), os.path.join(CSRC, "gemm_f32_kernel.h"),
-           os.path.join(CSRC, "gemm_bf16x3_kernel.h"),
+           os.path.join(CSRC, "gemm_bf16x3_kernel.h"), os.path.join(CSRC, "lookback.h"),
            os.path.join(os.path.dirname(HERE), "include", "ssm.h")]
 # packed-fp32 instructions are switched off on purpose (target feature removed for device code)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

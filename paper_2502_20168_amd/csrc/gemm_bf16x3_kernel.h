@@ -17,6 +17,7 @@
 #pragma once
 
 #include "gemm_f32_kernel.h"
+#include "lookback.h"
 
 #include <atomic>
 
@@ -191,6 +192,156 @@ struct SplitLoader {
 };
 
 // ---------------------------------------------------------------------------------------------
+// Epilogue 7: resettable scan over the rows of a 128 x 128 output tile (128 steps of 64 complex
+// states of one sequence).  The 256 consumer threads are 64 lanes x 4 chunks of 32 steps:
+//   1. the accumulators go through LDS so that a thread owns 32 consecutive steps of one lane;
+//   2. per-thread pass for zero incoming state, chunk aggregates combined through LDS;
+//   3. the tile's aggregate (state for zero incoming state, reset tag) is published as tagged
+//      64-bit words before any wait; the tiles of the same sequence and column block that come
+//      earlier in time are folded in time order from the sequence start (x0 or zero), which is one
+//      canonical order whatever the timing, so results are bitwise reproducible;
+//   4. second per-thread pass writes the states (and x_last at the sequence end).
+// Every predecessor sits in an earlier slot of the same XCD (placement mode 5), i.e. it was
+// dispatched earlier and publishes without waiting for anything, and every wait is bounded.
+// ---------------------------------------------------------------------------------------------
+constexpr int SCAN_TILE = 128;                       // rows and columns of the tile
+constexpr int SCAN_TS = SCAN_TILE + 4;               // LDS row stride of the staged tile (floats)
+constexpr int SCAN_MAX_CHAIN = 32;                   // tiles per sequence the fold can take
+constexpr size_t SCAN_LDS_BYTES = (size_t)SCAN_TILE * SCAN_TS * 4   // staged tile
+                                  + 4 * 64 * 8 + 4 * 64 * 4          // chunk states and reset tags
+                                  + SCAN_MAX_CHAIN * 64 * 8 + SCAN_MAX_CHAIN * 64 * 4   // predecessors
+                                  + 64 * 8;                          // incoming state per lane
+
+struct ScanLds {
+    float *tile; float2 *cS; unsigned *cAny; float2 *pS; unsigned *pAny; float2 *sX;
+    __device__ explicit ScanLds(void *base)
+    {
+        char *p = static_cast<char *>(base);
+        tile = reinterpret_cast<float *>(p); p += (size_t)SCAN_TILE * SCAN_TS * 4;
+        cS = reinterpret_cast<float2 *>(p); p += 4 * 64 * 8;
+        cAny = reinterpret_cast<unsigned *>(p); p += 4 * 64 * 4;
+        pS = reinterpret_cast<float2 *>(p); p += SCAN_MAX_CHAIN * 64 * 8;
+        pAny = reinterpret_cast<unsigned *>(p); p += SCAN_MAX_CHAIN * 64 * 4;
+        sX = reinterpret_cast<float2 *>(p);
+    }
+};
+
+// producers only keep the consumers company at the workgroup barriers of the scan epilogue
+__device__ __forceinline__ void scan_epilogue_barriers(bool has_pred)
+{
+    __syncthreads();
+    __syncthreads();
+    __syncthreads();
+    if (has_pred) __syncthreads();
+    __syncthreads();
+}
+
+// tid: 0..255 (consumer thread); the tile is staged in lds.tile on entry (after the first two barriers)
+__device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanLds &lds, int tid, int m0, int n0, int tile)
+{
+    constexpr int RC = 32;                                   // steps per thread
+    const ScanEpilogue &a = g.scan;
+    const int c = tid & 63, q = tid >> 6;
+    const int p = n0 / 2 + c;
+    const bool active = p < a.P;
+    const int b = m0 / a.L, tmL = (m0 % a.L) / SCAN_TILE, nt = a.L / SCAN_TILE;
+    const int tn = tile % g.ntn;
+    const int t0 = tmL * SCAN_TILE + q * RC;                 // first step of this thread
+    const float2 lam = active ? a.lam[p] : make_float2(0.f, 0.f);
+
+    float2 val[RC];
+#pragma unroll
+    for (int e = 0; e < RC; ++e) val[e] = *reinterpret_cast<const float2 *>(lds.tile + (q * RC + e) * SCAN_TS + 2 * c);
+    unsigned rmask = 0;
+    if (a.is_first) {
+        const uint8_t *fp = a.is_first + (long)b * a.L + t0;
+        if ((reinterpret_cast<uintptr_t>(fp) & 15) == 0) {
+            const uint4 w0 = *reinterpret_cast<const uint4 *>(fp), w1 = *reinterpret_cast<const uint4 *>(fp + 16);
+            if ((w0.x | w0.y | w0.z | w0.w | w1.x | w1.y | w1.z | w1.w) != 0) {
+                const unsigned ww[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+#pragma unroll
+                for (int j = 0; j < RC; ++j) rmask |= (unsigned)(((ww[j >> 2] >> (8 * (j & 3))) & 0xffu) != 0) << j;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < RC; ++j) rmask |= (unsigned)(fp[j] != 0) << j;
+        }
+    }
+    // pass 1: state after the thread's steps for zero incoming state (a reset zeroes the multiplier)
+    float2 S = make_float2(0.f, 0.f);
+#pragma unroll
+    for (int e = 0; e < RC; ++e) {
+        const bool r = (rmask >> e) & 1u;
+        const float2 le = make_float2(r ? 0.f : lam.x, r ? 0.f : lam.y);
+        S = cfma(le, S, val[e]);
+    }
+    float2 l32 = cmul(lam, lam);                             // Abar^32 by five squarings
+    l32 = cmul(l32, l32); l32 = cmul(l32, l32); l32 = cmul(l32, l32); l32 = cmul(l32, l32);
+    lds.cS[q * 64 + c] = S;
+    lds.cAny[q * 64 + c] = rmask != 0;
+    __syncthreads();                                                                       // barrier 3
+    // exclusive combine over the earlier chunks of the tile
+    float2 Aex = make_float2(1.f, 0.f), Sex = make_float2(0.f, 0.f);
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+        const float2 Sj = lds.cS[j * 64 + c];
+        const float2 Aj = lds.cAny[j * 64 + c] ? make_float2(0.f, 0.f) : l32;
+        const float2 nS = cfma(Aj, Sex, Sj), nA = cmul(Aj, Aex);
+        if (j < q) { Sex = nS; Aex = nA; }
+    }
+    const bool leader = (q == 3);
+    const bool has_pred = tmL > 0;
+    float2 l128 = cmul(l32, l32); l128 = cmul(l128, l128);
+    if (leader) {
+        const float2 Ath = (rmask != 0) ? make_float2(0.f, 0.f) : l32;
+        const float2 Stile = cfma(Ath, Sex, S);
+        const bool any_tile = (rmask != 0) || (Aex.x == 0.f && Aex.y == 0.f);
+        if (active && tmL + 1 < nt) {
+            unsigned long long *mine = a.desc + ((size_t)tile * 64 + c) * 2;
+            publish_word(mine, Stile.x, any_tile ? 2u : 1u);
+            publish_word(mine + 1, Stile.y, any_tile ? 2u : 1u);
+        }
+    }
+    if (has_pred) {
+        // thread (c, q) fetches the aggregates of tiles q, q+4, ... of this chain
+        for (int j = q; j < tmL; j += 4) {
+            float2 Sj = make_float2(0.f, 0.f);
+            unsigned tag = 2;
+            if (active) {
+                const size_t ptile = (size_t)(b * nt + j) * g.ntn + tn;
+                if (!wait_pair(a.desc + (ptile * 64 + c) * 2, 1u, a.spin_limit, Sj, tag)) {
+                    atomicOr(a.err, 1u);                 // gave up: flag it and finish anyway
+                    Sj = make_float2(0.f, 0.f); tag = 2;
+                }
+            }
+            lds.pS[j * 64 + c] = Sj;
+            lds.pAny[j * 64 + c] = (tag == 2u);
+        }
+        __syncthreads();                                                                   // barrier 4 (only with predecessors)
+    }
+    if (leader) {
+        float2 X = (a.x0 && active) ? a.x0[(long)b * a.P + p] : make_float2(0.f, 0.f);
+        for (int j = 0; j < tmL; ++j) {
+            const float2 Aj = lds.pAny[j * 64 + c] ? make_float2(0.f, 0.f) : l128;
+            X = cfma(Aj, X, lds.pS[j * 64 + c]);
+        }
+        lds.sX[c] = X;
+    }
+    __syncthreads();                                                                       // barrier 5
+    // pass 2: the states themselves
+    float2 xs = cfma(Aex, lds.sX[c], Sex);
+    float2 *dst = reinterpret_cast<float2 *>(g.C) + ((long)b * a.L + t0) * a.P + p;
+#pragma unroll
+    for (int e = 0; e < RC; ++e) {
+        const bool r = (rmask >> e) & 1u;
+        const float2 le = make_float2(r ? 0.f : lam.x, r ? 0.f : lam.y);
+        xs = cfma(le, xs, val[e]);
+        if (active) dst[(long)e * a.P] = xs;
+    }
+    if (active && a.x_last && t0 + RC == a.L) a.x_last[(long)b * a.P + p] = xs;
+}
+
+// ---------------------------------------------------------------------------------------------
 // Wavefront specialisation: a workgroup has WGM*WGN consumer wavefronts that only read
 // operand fragments from LDS and issue MFMAs, and NP producer wavefronts that only stage tiles
 // (global load -> three-way split -> LDS).  A producer and a consumer share each SIMD, so the
@@ -200,7 +351,7 @@ struct SplitLoader {
 // ---------------------------------------------------------------------------------------------
 template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL, bool AKC, bool BKC, int EPI, bool FAST>
 __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *smem, int m0, int n0, int z,
-                                                    int kbeg, int kend)
+                                                    int kbeg, int kend, int scan_tile)
 {
     constexpr int NC = WGM * WGN;                 // consumer wavefronts
     constexpr int PF = 2;                         // K tiles of global loads in flight per producer
@@ -262,6 +413,7 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
                 }
             }
         }
+        if constexpr (EPI == 7) scan_epilogue_barriers((m0 % g.scan.L) >= SCAN_TILE);
         return;
     }
 
@@ -366,6 +518,21 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
         }
     }
 
+    if constexpr (EPI == 7) {
+        static_assert(EPI != 7 || (BM == SCAN_TILE && BN == SCAN_TILE && NC == 4), "scan epilogue: 128x128 tile, 4 consumers");
+        const ScanLds lds(smem);
+        __syncthreads();                             // barrier 1: every wavefront has left the K loop, LDS is free
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+                    lds.tile[(wm * WM + i * 32 + 8 * (r / 4) + 4 * hh + (r % 4)) * SCAN_TS + wn * WN + j * 32 + li] = acc[i][j][r];
+        __syncthreads();                             // barrier 2: the tile is staged
+        scan_epilogue_body(g, lds, tid, m0, n0, scan_tile);
+        return;
+    }
     float *Cz = g.C + (long)z * g.M * g.ldc;
 #pragma unroll
     for (int i = 0; i < MI; ++i)
@@ -400,13 +567,25 @@ constexpr int gemm_layout(bool akc, bool bkc, int epi) { return (akc ? 1 : 0) | 
 //   mode 0 (no K splits): XCD x owns the contiguous band of tiles [x*nx, (x+1)*nx), so it re-reads
 //          only its band of A from its own L2;
 //   modes 1-3 (K splits): every XCD owns whole K slabs (or a contiguous run of tiles inside
-//          one), so each operand element is fetched from memory once instead of once per tile band.
+//          one), so each operand element is fetched from memory once instead of once per tile band;
+//   mode 5: see below.
 __device__ __forceinline__ void gemm_place(const GemmDev &g, int x, int q, int &z, int &tile)
 {
     if (g.mode == 0) { z = 0; tile = x * g.nx + q; }
     else if (g.mode == 1) { z = x + 8 * (q % g.mpar); tile = q / g.mpar; }        // splits = 8 * mpar
     else if (g.mode == 2) { z = x % g.splits; tile = q * g.mpar + x / g.splits; } // 8 = splits * mpar
-    else { const int item = x * g.nx + q; z = item / (g.ntm * g.ntn); tile = item % (g.ntm * g.ntn); }
+    else if (g.mode == 3) { const int item = x * g.nx + q; z = item / (g.ntm * g.ntn); tile = item % (g.ntm * g.ntn); }
+    else {
+        // mode 5 (scan epilogue): a unit = the tiles of one sequence and column group, time-major;
+        // units are dealt to the XCDs, so a tile only ever waits for tiles in earlier slots of its
+        // own XCD, which were dispatched before it
+        const int per_unit = g.sc_nt * g.sc_cpu;
+        const int uid = x + 8 * (q / per_unit), r = q % per_unit;
+        const int b = uid / g.sc_ncg, cg = uid % g.sc_ncg;
+        const int tn = cg * g.sc_cpu + r % g.sc_cpu;
+        z = 0;
+        tile = (uid < g.sc_units && tn < g.ntn) ? (b * g.sc_nt + r / g.sc_cpu) * g.ntn + tn : g.ntm * g.ntn;
+    }
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL, int LAY>
@@ -425,9 +604,9 @@ __device__ __forceinline__ void gemm_bf16x3_ws_problem(const GemmDev &g, __bf16 
                       (g.ldb % 4 == 0) && ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0) &&
                       (m0 + BM <= g.M) && (n0 + BN <= g.N) && ((kend - kbeg) % BK == 0);
     if (fast)
-        gemm_bf16x3_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, NPL, AKC, BKC, EPI, true>(g, smem, m0, n0, z, kbeg, kend);
+        gemm_bf16x3_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, NPL, AKC, BKC, EPI, true>(g, smem, m0, n0, z, kbeg, kend, tile);
     else
-        gemm_bf16x3_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, NPL, AKC, BKC, EPI, false>(g, smem, m0, n0, z, kbeg, kend);
+        gemm_bf16x3_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, NPL, AKC, BKC, EPI, false>(g, smem, m0, n0, z, kbeg, kend, tile);
 }
 
 // One launch carries one problem (LAY1 < 0) or two independent ones (used for the gradient
@@ -467,6 +646,19 @@ inline GemmDev make_gemm_dev(const GemmArgs &a)
     else if (splits % 8 == 0) { g.mode = 1; g.mpar = splits / 8; g.nx = (int)(ntiles * g.mpar); }
     else if (8 % splits == 0) { g.mode = 2; g.mpar = 8 / splits; g.nx = (int)((ntiles + g.mpar - 1) / g.mpar); }
     else { g.mode = 3; g.mpar = 0; g.nx = (int)((ntiles * splits + 7) / 8); }
+    g.scan = a.scan;
+    g.sc_nt = g.sc_cpu = g.sc_ncg = g.sc_units = 0;
+    if (a.epilogue == 7) {
+        const int nseq = a.M / a.scan.L;
+        g.sc_nt = a.scan.L / BM;
+        int ncg = nseq >= 8 ? 1 : (8 + nseq - 1) / nseq;
+        if (ncg > g.ntn) ncg = g.ntn;
+        g.sc_ncg = ncg;
+        g.sc_cpu = (g.ntn + ncg - 1) / ncg;
+        g.sc_units = nseq * ncg;
+        g.mode = 5; g.mpar = 0;
+        g.nx = ((g.sc_units + 7) / 8) * g.sc_nt * g.sc_cpu;
+    }
     return g;
 }
 
@@ -478,7 +670,9 @@ hipError_t launch_gemm_bf16x3_ws_variant(const GemmArgs &a, hipStream_t s, const
     GemmDev g1 = b ? make_gemm_dev<BM, BN, BK>(*b) : g0;
     if ((LAY1 >= 0) != (b != nullptr)) return hipErrorInvalidValue;
     g1.slot0 = g0.nx;
-    constexpr size_t smem = (size_t)NS * NPL * (BM + BN) * (BK + 8) * sizeof(__bf16);
+    constexpr size_t stage_bytes = (size_t)NS * NPL * (BM + BN) * (BK + 8) * sizeof(__bf16);
+    constexpr bool scans = ((LAY0 >> 2) == 7) || (LAY1 >= 0 && (LAY1 >> 2) == 7);
+    constexpr size_t smem = (scans && SCAN_LDS_BYTES > stage_bytes) ? SCAN_LDS_BYTES : stage_bytes;
     static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS of a gfx950 CU");
     auto kern = gemm_bf16x3_ws_kernel<BM, BN, BK, WGM, WGN, NP, NS, NPL, LAY0, LAY1>;
     if (smem > 64 * 1024) {

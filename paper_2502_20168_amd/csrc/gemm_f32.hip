@@ -87,9 +87,42 @@ static bool use_two_planes()
     return e && e[0] == '2';
 }
 
+bool gemm_scan_shape_ok(int64_t Bt, int64_t L, int64_t P)
+{
+    // 128-row tiles that never straddle two sequences, a bounded chain of tiles per sequence, and
+    // enough tiles that the plain product would use 128x128 tiles anyway
+    if (L % SCAN_TILE != 0 || L / SCAN_TILE > SCAN_MAX_CHAIN) return false;
+    const int64_t tiles = (Bt * L / SCAN_TILE) * ((2 * P + SCAN_TILE - 1) / SCAN_TILE);
+    return tiles >= 200 && tiles * 64 <= 0x7fffffffLL;
+}
+
+bool gemm_can_scan(int64_t Bt, int64_t L, int64_t P)
+{
+    // SSM_FUSED_SCAN=0 keeps the projection and the scan as two kernels (for comparison)
+    const char *e = std::getenv("SSM_FUSED_SCAN");
+    if (e && e[0] == '0') return false;
+    return !use_f32_mfma() && gemm_scan_shape_ok(Bt, L, P);
+}
+
+size_t gemm_scan_desc_bytes(int64_t Bt, int64_t L, int64_t P)
+{
+    const int64_t tiles = (Bt * L / SCAN_TILE) * ((2 * P + SCAN_TILE - 1) / SCAN_TILE);
+    return (size_t)tiles * 64 * 2 * sizeof(unsigned long long);
+}
+
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
 {
     if (a.M <= 0 || a.N <= 0 || a.K <= 0) return hipErrorInvalidValue;
+    if (a.epilogue == 7) {
+        // the input projection that scans its own output: 128x128 tiles only
+        if (!a.a_kcontig || !a.b_kcontig || a.splits > 1 || use_f32_mfma() || !a.scan.lam || !a.scan.desc || !a.scan.err ||
+            a.scan.L <= 0 || a.scan.L % SCAN_TILE != 0 || a.scan.L / SCAN_TILE > SCAN_MAX_CHAIN || a.M % a.scan.L != 0 ||
+            a.N != 2 * a.scan.P)
+            return hipErrorInvalidValue;
+        if (use_two_planes())
+            return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, gemm_layout(true, true, 7)>(a, s);
+        return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 3, gemm_layout(true, true, 7)>(a, s);
+    }
     if (a.splits > 1 && a.epilogue) return hipErrorInvalidValue;
     if (a.epilogue < 0 || a.epilogue > 6 || (a.epilogue && a.epilogue != 5 && !a.E)) return hipErrorInvalidValue;
     if (a.epilogue == 5 && a.C2 && !a.diag) return hipErrorInvalidValue;

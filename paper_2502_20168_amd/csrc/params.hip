@@ -104,6 +104,15 @@ __global__ void __launch_bounds__(256) prep_kernel(PrepArgs a)
             const float2 c = src[p];
             dst[p] = make_float2(c.x, -c.y);
         }
+    } else if (a.zero16 && blk >= a.zero_block0) {
+        // clears the tagged words that the scanning input projection will publish into
+        const size_t per = 256 * 8;
+        const size_t i0 = (size_t)(blk - a.zero_block0) * per + tid;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const size_t i = i0 + (size_t)j * 256;
+            if (i < a.n16) a.zero16[i] = make_uint4(0, 0, 0, 0);
+        }
     } else {
         // column-dot slabs of the gradient pass share this launch (they depend on nothing here)
         const int cb = blk - (a.P + a.H);
@@ -120,6 +129,14 @@ hipError_t launch_prep(const PrepArgs &a_in, hipStream_t s)
         if (!a.Cc) return hipErrorInvalidValue;       // block ranges assume the C rows are present
         a.cd_colblocks = (a.cd.H + 63) / 64;
         blocks += (unsigned)(a.cd_colblocks * a.cd.nslab);
+    }
+    a.zero_block0 = 0;
+    if (a.zero16 && a.n16 > 0) {
+        if (!a.Cc) return hipErrorInvalidValue;       // block ranges assume the C rows are present
+        a.zero_block0 = (int)blocks;
+        blocks += (unsigned)((a.n16 + 256 * 8 - 1) / (256 * 8));
+    } else {
+        a.zero16 = nullptr;
     }
     hipLaunchKernelGGL(prep_kernel, dim3(blocks), dim3(256), 0, s, a);
     return hipGetLastError();

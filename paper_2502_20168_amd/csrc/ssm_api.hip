@@ -16,7 +16,7 @@ inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 struct Layout {
     ScanPlan plan;
     int splitC, splitB, nslab;
-    size_t hdr, lam, Bri, Cc, xbuf, chi, ticket, desc, dCpart, dBpart, dApart, dDpart, total;
+    size_t hdr, lam, Bri, Cc, xbuf, chi, ticket, desc, dCpart, dBpart, dApart, dDpart, fdesc, fdesc_bytes, total;
 };
 
 ssm_status check_dims(int64_t Bt, int64_t L, int64_t H, int64_t P)
@@ -47,8 +47,12 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
     o.Cc = off; off += up((size_t)2 * P * H * 4);
     o.ticket = off; off += up(o.plan.ticket_bytes);       // tickets and descriptors are contiguous
     o.desc = off; off += up(o.plan.desc_bytes);
-    o.xbuf = o.chi = o.dCpart = o.dBpart = o.dApart = o.dDpart = 0;
+    o.xbuf = o.chi = o.dCpart = o.dBpart = o.dApart = o.dDpart = o.fdesc = o.fdesc_bytes = 0;
     if (!bwd) {
+        if (gemm_scan_shape_ok(Bt, L, P)) {          // tagged words of the scanning input projection
+            o.fdesc_bytes = gemm_scan_desc_bytes(Bt, L, P);
+            o.fdesc = off; off += up(o.fdesc_bytes);
+        }
         o.xbuf = off; off += up(T * P * 8);
     } else {
         o.chi = off; off += up(T * P * 8);
@@ -123,14 +127,18 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     float2 *xs = x ? reinterpret_cast<float2 *>(x) : reinterpret_cast<float2 *>(ws + lo.xbuf);
     const int T = (int)(Bt * L);
 
+    // Shapes whose sequences are whole numbers of 128-row tiles: the input projection scans its own
+    // output tile and stores the states directly (no scan kernel, Bbar u never goes to memory).
+    const bool fused = lo.fdesc_bytes != 0 && gemm_can_scan(Bt, L, P);
     MARK();
-    if (lo.plan.nTB > 1)
+    if (!fused && lo.plan.nTB > 1)
         HIP_TRY(launch_clear(hdr, ws + lo.ticket, lo.desc + up(lo.plan.desc_bytes) - lo.ticket, s));
     PrepArgs pa{};
     pa.Lambda = reinterpret_cast<const float2 *>(Lambda); pa.B = reinterpret_cast<const float2 *>(B);
     pa.C = reinterpret_cast<const float2 *>(C); pa.log_delta = log_delta;
     pa.P = (int)P; pa.H = (int)H; pa.lam_bar = lam; pa.Bbar_ri = Bri; pa.Cc = Cc; pa.Bbar_c64 = nullptr;
-    pa.hdr = lo.plan.nTB > 1 ? nullptr : hdr;
+    pa.hdr = (fused || lo.plan.nTB == 1) ? hdr : nullptr;
+    if (fused) { pa.zero16 = reinterpret_cast<uint4 *>(ws + lo.fdesc); pa.n16 = lo.fdesc_bytes / 16; }
     HIP_TRY(launch_prep(pa, s));
     MARK();
 
@@ -140,17 +148,26 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     g1.B = Bri; g1.ldb = H; g1.b_kcontig = 1;
     g1.C = reinterpret_cast<float *>(xs); g1.ldc = 2 * P;
     g1.M = T; g1.N = (int)(2 * P); g1.K = (int)H; g1.splits = 1;
+    if (fused) {
+        g1.epilogue = 7;
+        g1.scan.lam = lam; g1.scan.is_first = is_first;
+        g1.scan.x0 = reinterpret_cast<const float2 *>(x0); g1.scan.x_last = reinterpret_cast<float2 *>(x_last);
+        g1.scan.desc = reinterpret_cast<unsigned long long *>(ws + lo.fdesc); g1.scan.err = &hdr->err;
+        g1.scan.L = (int)L; g1.scan.P = (int)P; g1.scan.spin_limit = spin_limit();
+    }
     HIP_TRY(launch_gemm(g1, s));
     MARK();
 
-    ScanArgs sa{};
-    sa.in = xs; sa.out = xs; sa.lam = lam; sa.is_first = is_first;
-    sa.x0 = reinterpret_cast<const float2 *>(x0); sa.x_last = reinterpret_cast<float2 *>(x_last);
-    sa.desc = desc; sa.ticket = reinterpret_cast<uint32_t *>(ws + lo.ticket); sa.err = &hdr->err;
-    sa.Bt = (int)Bt; sa.L = (int)L; sa.P = (int)P;
-    sa.pxb = lo.plan.pxb; sa.cy = lo.plan.cy; sa.nPX = lo.plan.nPX; sa.nTB = lo.plan.nTB;
-    sa.spin_limit = spin_limit();
-    HIP_TRY(launch_scan(sa, false, s));
+    if (!fused) {
+        ScanArgs sa{};
+        sa.in = xs; sa.out = xs; sa.lam = lam; sa.is_first = is_first;
+        sa.x0 = reinterpret_cast<const float2 *>(x0); sa.x_last = reinterpret_cast<float2 *>(x_last);
+        sa.desc = desc; sa.ticket = reinterpret_cast<uint32_t *>(ws + lo.ticket); sa.err = &hdr->err;
+        sa.Bt = (int)Bt; sa.L = (int)L; sa.P = (int)P;
+        sa.pxb = lo.plan.pxb; sa.cy = lo.plan.cy; sa.nPX = lo.plan.nPX; sa.nTB = lo.plan.nTB;
+        sa.spin_limit = spin_limit();
+        HIP_TRY(launch_scan(sa, false, s));
+    }
     MARK();
 
     // y[t,h] = sum_p (Re C[h,p] x_re - Im C[h,p] x_im) + D[h] u[t,h]       (Eq. 3, second line)

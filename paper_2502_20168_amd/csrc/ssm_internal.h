@@ -15,12 +15,28 @@ namespace ssm {
 // 3: C = E (.) sigmoid(product), sigmoid kept in C2 when non-null (half-GLU gate);
 // 4: C = E (.) E2 + product (.) GELU'(E3) (adjoint of the gate with respect to its input);
 // 6: as 1, and C2 = GELU(C) (output projection that feeds the half-GLU gate);
+// 7: the resettable scan over the rows of the output tile (see ScanEpilogue): C = states;
 // 5: C = product + E (E may be null), C2 = [not rowflag[m]] conj(Abar) (.) C with diag = Abar and complex
 //    (re, im) column pairs (adjoint of one recurrence step)
 // A(m,k) = a_kcontig ? A[m*lda + k] : A[k*lda + m];  B(n,k) = b_kcontig ? B[n*ldb + k] : B[k*ldb + n]
 // splits > 1: split z covers a contiguous K range and writes its own slab C + z*M*ldc
 // (no epilogue term in that case); the caller reduces the slabs.
 // ---------------------------------------------------------------------------------------------
+// Epilogue 7 of the projection GEMM: the resettable scan (Eq. 4 with the elements of Eq. 9 and the
+// operator of Eq. 10) over the rows of the output tile itself, so that the input projection stores
+// the states x directly and Bbar u never goes to memory.  Rows are tokens (Bt sequences of L steps,
+// L a multiple of the 128-row tile), columns (re, im) pairs of P states.
+struct ScanEpilogue {
+    const float2 *lam;            // [P] Abar
+    const uint8_t *is_first;      // [Bt*L] or null
+    const float2 *x0;             // [Bt, P] or null
+    float2 *x_last;               // [Bt, P] or null
+    unsigned long long *desc;     // [M/128 * ceil(N/128) * 64][2] tagged aggregate words, zero on entry
+    unsigned *err;                // set when a bounded wait gives up
+    int L, P;
+    unsigned spin_limit;
+};
+
 struct GemmArgs {
     const float *A; int64_t lda; int a_kcontig;
     const float *B; int64_t ldb; int b_kcontig;
@@ -29,7 +45,14 @@ struct GemmArgs {
     int epilogue; const uint8_t *rowflag;
     const float *E2; const float *E3; float *C2;     // epilogues 3 and 4 (gate), pitch lde / ldc
     int M, N, K, splits;
+    ScanEpilogue scan;                               // epilogue 7
 };
+// the input projection can scan its own output (epilogue 7) for this shape (shape only), and
+// whether it will on this call (shape and environment)
+bool gemm_scan_shape_ok(int64_t Bt, int64_t L, int64_t P);
+bool gemm_can_scan(int64_t Bt, int64_t L, int64_t P);
+// bytes of tagged words epilogue 7 needs (zeroed before the launch)
+size_t gemm_scan_desc_bytes(int64_t Bt, int64_t L, int64_t P);
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t s);
 // two independent problems in one launch (falls back to two launches for layouts without a
 // paired instantiation)
@@ -109,6 +132,8 @@ struct PrepArgs {
     WsHeader *hdr;           // cleared when non-null
     ColDotArgs cd;           // cd.partial non-null: the launch also computes the column-dot slabs
     int cd_colblocks;        // set by launch_prep
+    uint4 *zero16; size_t n16;   // region to clear in the same launch (tagged words of epilogue 7), may be null
+    int zero_block0;         // set by launch_prep: first workgroup of the clearing range
 };
 hipError_t launch_prep(const PrepArgs &a, hipStream_t s);
 
