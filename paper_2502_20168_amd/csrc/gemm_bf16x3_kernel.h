@@ -227,32 +227,43 @@ struct ScanLds {
 };
 
 // producers only keep the consumers company at the workgroup barriers of the scan epilogue
-__device__ __forceinline__ void scan_epilogue_barriers(bool has_pred)
+template <bool REV>
+__device__ __forceinline__ void scan_epilogue_barriers(const GemmDev &g, int m0)
 {
+    const int tmL = (m0 % g.scan.L) / SCAN_TILE, nt = g.scan.L / SCAN_TILE;
+    const bool has_pred = REV ? (tmL + 1 < nt) : (tmL > 0);
     __syncthreads();
     __syncthreads();
     __syncthreads();
     if (has_pred) __syncthreads();
     __syncthreads();
+    if (REV) __syncthreads();
 }
 
-// tid: 0..255 (consumer thread); the tile is staged in lds.tile on entry (after the first two barriers)
+// tid: 0..255 (consumer thread); the tile is staged in lds.tile on entry (after the first two barriers).
+// REV: the scan of the gradient pass, chi_t = gx_t + [not is_first_{t+1}] conj(Abar) chi_{t+1}, which
+// walks time backwards (later chunks and later tiles are the predecessors) and also reduces
+// dAbar += [not is_first_t] conj(x_{t-1}) chi_t per tile and writes dx0.
+template <bool REV>
 __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanLds &lds, int tid, int m0, int n0, int tile)
 {
     constexpr int RC = 32;                                   // steps per thread
     const ScanEpilogue &a = g.scan;
     const int c = tid & 63, q = tid >> 6;
+    const int ql = REV ? 3 - q : q;                          // chunk index in scan order
     const int p = n0 / 2 + c;
     const bool active = p < a.P;
     const int b = m0 / a.L, tmL = (m0 % a.L) / SCAN_TILE, nt = a.L / SCAN_TILE;
     const int tn = tile % g.ntn;
-    const int t0 = tmL * SCAN_TILE + q * RC;                 // first step of this thread
-    const float2 lam = active ? a.lam[p] : make_float2(0.f, 0.f);
+    const int t0 = tmL * SCAN_TILE + q * RC;                 // lowest time index of this thread's steps
+    float2 lam = active ? a.lam[p] : make_float2(0.f, 0.f);
+    if (REV) lam.y = -lam.y;
 
     float2 val[RC];
 #pragma unroll
     for (int e = 0; e < RC; ++e) val[e] = *reinterpret_cast<const float2 *>(lds.tile + (q * RC + e) * SCAN_TS + 2 * c);
-    unsigned rmask = 0;
+    // fmask bit e: is_first at time t0 + e
+    unsigned fmask = 0;
     if (a.is_first) {
         const uint8_t *fp = a.is_first + (long)b * a.L + t0;
         if ((reinterpret_cast<uintptr_t>(fp) & 15) == 0) {
@@ -260,70 +271,82 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
             if ((w0.x | w0.y | w0.z | w0.w | w1.x | w1.y | w1.z | w1.w) != 0) {
                 const unsigned ww[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
 #pragma unroll
-                for (int j = 0; j < RC; ++j) rmask |= (unsigned)(((ww[j >> 2] >> (8 * (j & 3))) & 0xffu) != 0) << j;
+                for (int j = 0; j < RC; ++j) fmask |= (unsigned)(((ww[j >> 2] >> (8 * (j & 3))) & 0xffu) != 0) << j;
             }
         } else {
 #pragma unroll
-            for (int j = 0; j < RC; ++j) rmask |= (unsigned)(fp[j] != 0) << j;
+            for (int j = 0; j < RC; ++j) fmask |= (unsigned)(fp[j] != 0) << j;
         }
+    }
+    // rmask bit e: the state that flows into the step at time t0 + e is dropped.  Forward: the
+    // step's own flag.  Reverse: the flag of the next time step (nothing flows in at the sequence end).
+    unsigned rmask = fmask;
+    if (REV) {
+        unsigned next = 1;
+        if (t0 + RC < a.L) next = a.is_first ? (unsigned)(a.is_first[(long)b * a.L + t0 + RC] != 0) : 0u;
+        rmask = (fmask >> 1) | (next << 31);
     }
     // pass 1: state after the thread's steps for zero incoming state (a reset zeroes the multiplier)
     float2 S = make_float2(0.f, 0.f);
 #pragma unroll
-    for (int e = 0; e < RC; ++e) {
+    for (int i = 0; i < RC; ++i) {
+        const int e = REV ? RC - 1 - i : i;
         const bool r = (rmask >> e) & 1u;
         const float2 le = make_float2(r ? 0.f : lam.x, r ? 0.f : lam.y);
         S = cfma(le, S, val[e]);
     }
     float2 l32 = cmul(lam, lam);                             // Abar^32 by five squarings
     l32 = cmul(l32, l32); l32 = cmul(l32, l32); l32 = cmul(l32, l32); l32 = cmul(l32, l32);
-    lds.cS[q * 64 + c] = S;
-    lds.cAny[q * 64 + c] = rmask != 0;
+    lds.cS[ql * 64 + c] = S;
+    lds.cAny[ql * 64 + c] = rmask != 0;
     __syncthreads();                                                                       // barrier 3
-    // exclusive combine over the earlier chunks of the tile
+    // exclusive combine over the chunks that come earlier in scan order
     float2 Aex = make_float2(1.f, 0.f), Sex = make_float2(0.f, 0.f);
 #pragma unroll
     for (int j = 0; j < 3; ++j) {
         const float2 Sj = lds.cS[j * 64 + c];
         const float2 Aj = lds.cAny[j * 64 + c] ? make_float2(0.f, 0.f) : l32;
         const float2 nS = cfma(Aj, Sex, Sj), nA = cmul(Aj, Aex);
-        if (j < q) { Sex = nS; Aex = nA; }
+        if (j < ql) { Sex = nS; Aex = nA; }
     }
-    const bool leader = (q == 3);
-    const bool has_pred = tmL > 0;
+    const bool leader = (ql == 3);
+    const int npred = REV ? nt - 1 - tmL : tmL;              // tiles of the chain that come earlier in scan order
+    const bool has_succ = REV ? (tmL > 0) : (tmL + 1 < nt);
     float2 l128 = cmul(l32, l32); l128 = cmul(l128, l128);
     if (leader) {
         const float2 Ath = (rmask != 0) ? make_float2(0.f, 0.f) : l32;
         const float2 Stile = cfma(Ath, Sex, S);
         const bool any_tile = (rmask != 0) || (Aex.x == 0.f && Aex.y == 0.f);
-        if (active && tmL + 1 < nt) {
+        if (active && has_succ) {
             unsigned long long *mine = a.desc + ((size_t)tile * 64 + c) * 2;
             publish_word(mine, Stile.x, any_tile ? 2u : 1u);
             publish_word(mine + 1, Stile.y, any_tile ? 2u : 1u);
         }
     }
-    if (has_pred) {
-        // thread (c, q) fetches the aggregates of tiles q, q+4, ... of this chain
-        for (int j = q; j < tmL; j += 4) {
+    if (npred > 0) {
+        // thread (c, q) fetches the aggregates of predecessors q, q+4, ... (k-th predecessor in scan
+        // order = tile k of the sequence forward, tile nt-1-k in reverse)
+        for (int k = q; k < npred; k += 4) {
             float2 Sj = make_float2(0.f, 0.f);
             unsigned tag = 2;
             if (active) {
+                const int j = REV ? nt - 1 - k : k;
                 const size_t ptile = (size_t)(b * nt + j) * g.ntn + tn;
                 if (!wait_pair(a.desc + (ptile * 64 + c) * 2, 1u, a.spin_limit, Sj, tag)) {
                     atomicOr(a.err, 1u);                 // gave up: flag it and finish anyway
                     Sj = make_float2(0.f, 0.f); tag = 2;
                 }
             }
-            lds.pS[j * 64 + c] = Sj;
-            lds.pAny[j * 64 + c] = (tag == 2u);
+            lds.pS[k * 64 + c] = Sj;
+            lds.pAny[k * 64 + c] = (tag == 2u);
         }
         __syncthreads();                                                                   // barrier 4 (only with predecessors)
     }
     if (leader) {
-        float2 X = (a.x0 && active) ? a.x0[(long)b * a.P + p] : make_float2(0.f, 0.f);
-        for (int j = 0; j < tmL; ++j) {
-            const float2 Aj = lds.pAny[j * 64 + c] ? make_float2(0.f, 0.f) : l128;
-            X = cfma(Aj, X, lds.pS[j * 64 + c]);
+        float2 X = (!REV && a.x0 && active) ? a.x0[(long)b * a.P + p] : make_float2(0.f, 0.f);
+        for (int k = 0; k < npred; ++k) {
+            const float2 Aj = lds.pAny[k * 64 + c] ? make_float2(0.f, 0.f) : l128;
+            X = cfma(Aj, X, lds.pS[k * 64 + c]);
         }
         lds.sX[c] = X;
     }
@@ -331,14 +354,54 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
     // pass 2: the states themselves
     float2 xs = cfma(Aex, lds.sX[c], Sex);
     float2 *dst = reinterpret_cast<float2 *>(g.C) + ((long)b * a.L + t0) * a.P + p;
+    if (!REV) {
 #pragma unroll
-    for (int e = 0; e < RC; ++e) {
-        const bool r = (rmask >> e) & 1u;
-        const float2 le = make_float2(r ? 0.f : lam.x, r ? 0.f : lam.y);
-        xs = cfma(le, xs, val[e]);
-        if (active) dst[(long)e * a.P] = xs;
+        for (int e = 0; e < RC; ++e) {
+            const bool r = (rmask >> e) & 1u;
+            const float2 le = make_float2(r ? 0.f : lam.x, r ? 0.f : lam.y);
+            xs = cfma(le, xs, val[e]);
+            if (active) dst[(long)e * a.P] = xs;
+        }
+        if (active && a.x_last && t0 + RC == a.L) a.x_last[(long)b * a.P + p] = xs;
+    } else {
+        // also dAbar += [not is_first_t] conj(x_{t-1}) chi_t; x_{-1} = x0 (zero when absent)
+        const float2 *xprev = a.xsaved + ((long)b * a.L + t0 - 1) * a.P + p;      // x_{t0-1}; valid for e >= 1 or t0 > 0
+        float2 acc = make_float2(0.f, 0.f);
+#pragma unroll
+        for (int blk = RC / 8 - 1; blk >= 0; --blk) {
+            float2 xp[8];                                  // eight loads in flight
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int e = blk * 8 + j;
+                xp[j] = make_float2(0.f, 0.f);
+                if (active) {
+                    if (t0 + e > 0) xp[j] = xprev[(long)e * a.P];
+                    else if (a.x0) xp[j] = a.x0[(long)b * a.P + p];
+                }
+            }
+#pragma unroll
+            for (int j = 7; j >= 0; --j) {
+                const int e = blk * 8 + j;
+                const bool r = (rmask >> e) & 1u;
+                const float2 le = make_float2(r ? 0.f : lam.x, r ? 0.f : lam.y);
+                xs = cfma(le, xs, val[e]);
+                if (active) dst[(long)e * a.P] = xs;
+                const bool m = (fmask >> e) & 1u;
+                const float2 qv = make_float2(m ? 0.f : xp[j].x, m ? 0.f : xp[j].y);
+                acc.x = fmaf(qv.x, xs.x, fmaf(qv.y, xs.y, acc.x));
+                acc.y = fmaf(qv.x, xs.y, fmaf(-qv.y, xs.x, acc.y));
+            }
+        }
+        // lam holds conj(Abar) here: dx0 = [not is_first_0] conj(Abar) chi_0
+        if (active && a.dx0 && t0 == 0) a.dx0[(long)b * a.P + p] = (fmask & 1u) ? make_float2(0.f, 0.f) : cmul(lam, xs);
+        lds.cS[q * 64 + c] = acc;                          // (barrier 5 is behind every reader of cS)
+        __syncthreads();                                                                   // barrier 6 (reverse only)
+        if (q == 0 && active) {
+            float2 sum = make_float2(0.f, 0.f);
+            for (int j = 0; j < 4; ++j) { sum.x += lds.cS[j * 64 + c].x; sum.y += lds.cS[j * 64 + c].y; }
+            a.partial[((size_t)b * nt + tmL) * a.P + p] = sum;
+        }
     }
-    if (active && a.x_last && t0 + RC == a.L) a.x_last[(long)b * a.P + p] = xs;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -413,7 +476,7 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
                 }
             }
         }
-        if constexpr (EPI == 7) scan_epilogue_barriers((m0 % g.scan.L) >= SCAN_TILE);
+        if constexpr (EPI == 7 || EPI == 8) scan_epilogue_barriers<EPI == 8>(g, m0);
         return;
     }
 
@@ -518,8 +581,8 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
         }
     }
 
-    if constexpr (EPI == 7) {
-        static_assert(EPI != 7 || (BM == SCAN_TILE && BN == SCAN_TILE && NC == 4), "scan epilogue: 128x128 tile, 4 consumers");
+    if constexpr (EPI == 7 || EPI == 8) {
+        static_assert(BM == SCAN_TILE && BN == SCAN_TILE && NC == 4, "scan epilogue: 128x128 tile, 4 consumers");
         const ScanLds lds(smem);
         __syncthreads();                             // barrier 1: every wavefront has left the K loop, LDS is free
 #pragma unroll
@@ -530,7 +593,7 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
                 for (int r = 0; r < 16; ++r)
                     lds.tile[(wm * WM + i * 32 + 8 * (r / 4) + 4 * hh + (r % 4)) * SCAN_TS + wn * WN + j * 32 + li] = acc[i][j][r];
         __syncthreads();                             // barrier 2: the tile is staged
-        scan_epilogue_body(g, lds, tid, m0, n0, scan_tile);
+        scan_epilogue_body<EPI == 8>(g, lds, tid, m0, n0, scan_tile);
         return;
     }
     float *Cz = g.C + (long)z * g.M * g.ldc;
@@ -584,7 +647,9 @@ __device__ __forceinline__ void gemm_place(const GemmDev &g, int x, int q, int &
         const int b = uid / g.sc_ncg, cg = uid % g.sc_ncg;
         const int tn = cg * g.sc_cpu + r % g.sc_cpu;
         z = 0;
-        tile = (uid < g.sc_units && tn < g.ntn) ? (b * g.sc_nt + r / g.sc_cpu) * g.ntn + tn : g.ntm * g.ntn;
+        const int tslot = r / g.sc_cpu;                 // time-ordered slot; the reverse scan starts at the sequence end
+        const int tmL = g.sc_rev ? g.sc_nt - 1 - tslot : tslot;
+        tile = (uid < g.sc_units && tn < g.ntn) ? (b * g.sc_nt + tmL) * g.ntn + tn : g.ntm * g.ntn;
     }
 }
 
@@ -647,8 +712,9 @@ inline GemmDev make_gemm_dev(const GemmArgs &a)
     else if (8 % splits == 0) { g.mode = 2; g.mpar = 8 / splits; g.nx = (int)((ntiles + g.mpar - 1) / g.mpar); }
     else { g.mode = 3; g.mpar = 0; g.nx = (int)((ntiles * splits + 7) / 8); }
     g.scan = a.scan;
-    g.sc_nt = g.sc_cpu = g.sc_ncg = g.sc_units = 0;
-    if (a.epilogue == 7) {
+    g.sc_nt = g.sc_cpu = g.sc_ncg = g.sc_units = g.sc_rev = 0;
+    if (a.epilogue == 7 || a.epilogue == 8) {
+        g.sc_rev = a.epilogue == 8;
         const int nseq = a.M / a.scan.L;
         g.sc_nt = a.scan.L / BM;
         int ncg = nseq >= 8 ? 1 : (8 + nseq - 1) / nseq;
@@ -671,7 +737,7 @@ hipError_t launch_gemm_bf16x3_ws_variant(const GemmArgs &a, hipStream_t s, const
     if ((LAY1 >= 0) != (b != nullptr)) return hipErrorInvalidValue;
     g1.slot0 = g0.nx;
     constexpr size_t stage_bytes = (size_t)NS * NPL * (BM + BN) * (BK + 8) * sizeof(__bf16);
-    constexpr bool scans = ((LAY0 >> 2) == 7) || (LAY1 >= 0 && (LAY1 >> 2) == 7);
+    constexpr bool scans = ((LAY0 >> 2) >= 7) || (LAY1 >= 0 && (LAY1 >> 2) >= 7);
     constexpr size_t smem = (scans && SCAN_LDS_BYTES > stage_bytes) ? SCAN_LDS_BYTES : stage_bytes;
     static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS of a gfx950 CU");
     auto kern = gemm_bf16x3_ws_kernel<BM, BN, BK, WGM, WGN, NP, NS, NPL, LAY0, LAY1>;

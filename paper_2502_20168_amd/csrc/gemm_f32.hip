@@ -53,6 +53,8 @@ static int layout_of(const GemmArgs &a)
     if (a.epilogue == 4) return (a.a_kcontig && a.b_kcontig) ? gemm_layout(true, true, 4) : -1;
     if (a.epilogue == 6) return (a.a_kcontig && a.b_kcontig) ? gemm_layout(true, true, 6) : -1;
     if (a.epilogue == 5) return (a.a_kcontig && !a.b_kcontig && a.N % 2 == 0) ? gemm_layout(true, false, 5) : -1;
+    if (a.epilogue == 7) return (a.a_kcontig && a.b_kcontig) ? gemm_layout(true, true, 7) : -1;
+    if (a.epilogue == 8) return (a.a_kcontig && !a.b_kcontig) ? gemm_layout(true, false, 8) : -1;
     if (a.a_kcontig) return gemm_layout(true, a.b_kcontig != 0, a.epilogue);
     if (!a.b_kcontig && !a.epilogue) return gemm_layout(false, false, 0);
     return -1;
@@ -96,12 +98,30 @@ bool gemm_scan_shape_ok(int64_t Bt, int64_t L, int64_t P)
     return tiles >= 200 && tiles * 64 <= 0x7fffffffLL;
 }
 
+// SSM_FUSED_SCAN=0 keeps every projection and its scan as two kernels, =1 fuses only the forward
+// pair (both for comparison); default: forward and gradient pass fused.
 bool gemm_can_scan(int64_t Bt, int64_t L, int64_t P)
 {
-    // SSM_FUSED_SCAN=0 keeps the projection and the scan as two kernels (for comparison)
     const char *e = std::getenv("SSM_FUSED_SCAN");
     if (e && e[0] == '0') return false;
     return !use_f32_mfma() && gemm_scan_shape_ok(Bt, L, P);
+}
+
+bool gemm_can_scan_reverse(int64_t Bt, int64_t L, int64_t P)
+{
+    const char *e = std::getenv("SSM_FUSED_SCAN");
+    if (e && (e[0] == '0' || e[0] == '1')) return false;
+    return !use_f32_mfma() && gemm_scan_shape_ok(Bt, L, P);
+}
+
+// argument checks shared by the two scanning epilogues
+static bool scan_args_ok(const GemmArgs &a)
+{
+    if (a.splits > 1 || use_f32_mfma() || !a.scan.lam || !a.scan.desc || !a.scan.err) return false;
+    if (a.scan.L <= 0 || a.scan.L % SCAN_TILE != 0 || a.scan.L / SCAN_TILE > SCAN_MAX_CHAIN) return false;
+    if (a.M % a.scan.L != 0 || a.N != 2 * a.scan.P || !a.a_kcontig) return false;
+    if (a.epilogue == 7) return a.b_kcontig != 0;
+    return !a.b_kcontig && a.scan.xsaved && a.scan.partial;
 }
 
 size_t gemm_scan_desc_bytes(int64_t Bt, int64_t L, int64_t P)
@@ -115,13 +135,17 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
     if (a.M <= 0 || a.N <= 0 || a.K <= 0) return hipErrorInvalidValue;
     if (a.epilogue == 7) {
         // the input projection that scans its own output: 128x128 tiles only
-        if (!a.a_kcontig || !a.b_kcontig || a.splits > 1 || use_f32_mfma() || !a.scan.lam || !a.scan.desc || !a.scan.err ||
-            a.scan.L <= 0 || a.scan.L % SCAN_TILE != 0 || a.scan.L / SCAN_TILE > SCAN_MAX_CHAIN || a.M % a.scan.L != 0 ||
-            a.N != 2 * a.scan.P)
-            return hipErrorInvalidValue;
+        if (!scan_args_ok(a)) return hipErrorInvalidValue;
         if (use_two_planes())
             return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, gemm_layout(true, true, 7)>(a, s);
         return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 3, gemm_layout(true, true, 7)>(a, s);
+    }
+    if (a.epilogue == 8) {
+        // C^H dy that runs the reverse scan on its own output
+        if (!scan_args_ok(a)) return hipErrorInvalidValue;
+        if (use_two_planes())
+            return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, gemm_layout(true, false, 8)>(a, s);
+        return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 3, gemm_layout(true, false, 8)>(a, s);
     }
     if (a.splits > 1 && a.epilogue) return hipErrorInvalidValue;
     if (a.epilogue < 0 || a.epilogue > 6 || (a.epilogue && a.epilogue != 5 && !a.E)) return hipErrorInvalidValue;
@@ -156,7 +180,8 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
 }
 
 // Two independent problems in one launch of 128x128 tiles.  The pairs of the gradient pass:
-//   C^H dy (row-major A, B read along N)          with  dy^T x  (K = T reduction in slabs)
+//   C^H dy (row-major A, B read along N; plain or running the reverse scan on its output)
+//                                                 with  dy^T x  (K = T reduction in slabs)
 //   Bbar^H chi + D dy (same layout, epilogue 1)   with  chi^T u (K = T reduction in slabs)
 hipError_t launch_gemm_pair(const GemmArgs &a, const GemmArgs &b, hipStream_t s)
 {
@@ -164,12 +189,15 @@ hipError_t launch_gemm_pair(const GemmArgs &a, const GemmArgs &b, hipStream_t s)
     if ((a.splits > 1 && a.epilogue) || (b.splits > 1 && b.epilogue)) return hipErrorInvalidValue;
     if (!use_f32_mfma()) {
         constexpr int NN0 = gemm_layout(true, false, 0), NN1 = gemm_layout(true, false, 1),
-                      TN0 = gemm_layout(false, false, 0);
+                      NN8 = gemm_layout(true, false, 8), TN0 = gemm_layout(false, false, 0);
         const int la = layout_of(a), lb = layout_of(b);
+        if (la == NN8 && !scan_args_ok(a)) return hipErrorInvalidValue;
         if (use_two_planes()) {
+            if (la == NN8 && lb == TN0) return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, NN8, TN0>(a, s, &b);
             if (la == NN0 && lb == TN0) return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, NN0, TN0>(a, s, &b);
             if (la == NN1 && lb == TN0) return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, NN1, TN0>(a, s, &b);
         } else {
+            if (la == NN8 && lb == TN0) return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 3, NN8, TN0>(a, s, &b);
             if (la == NN0 && lb == TN0) return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 3, NN0, TN0>(a, s, &b);
             if (la == NN1 && lb == TN0) return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 3, NN1, TN0>(a, s, &b);
         }

@@ -35,7 +35,7 @@ struct GemmDev {
     // epilogue 7 (scan over the tile's rows): tiles per sequence, column tiles per unit, column
     // groups per sequence, number of units (a unit = the chains of one sequence and column group)
     ScanEpilogue scan;
-    int sc_nt, sc_cpu, sc_ncg, sc_units;
+    int sc_nt, sc_cpu, sc_ncg, sc_units, sc_rev;
 };
 
 // Value stored for an output element whose accumulated product is v.

@@ -48,17 +48,20 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
     o.ticket = off; off += up(o.plan.ticket_bytes);       // tickets and descriptors are contiguous
     o.desc = off; off += up(o.plan.desc_bytes);
     o.xbuf = o.chi = o.dCpart = o.dBpart = o.dApart = o.dDpart = o.fdesc = o.fdesc_bytes = 0;
+    size_t dA_elems = o.plan.partial_elems;
+    if (gemm_scan_shape_ok(Bt, L, P)) {              // tagged words of a projection that scans its own output
+        o.fdesc_bytes = gemm_scan_desc_bytes(Bt, L, P);
+        o.fdesc = off; off += up(o.fdesc_bytes);
+        const size_t per_tile = (size_t)Bt * (L / 128) * P;        // one dAbar row per 128-step tile
+        if (per_tile > dA_elems) dA_elems = per_tile;
+    }
     if (!bwd) {
-        if (gemm_scan_shape_ok(Bt, L, P)) {          // tagged words of the scanning input projection
-            o.fdesc_bytes = gemm_scan_desc_bytes(Bt, L, P);
-            o.fdesc = off; off += up(o.fdesc_bytes);
-        }
         o.xbuf = off; off += up(T * P * 8);
     } else {
         o.chi = off; off += up(T * P * 8);
         o.dCpart = off; off += up((size_t)o.splitC * 2 * P * H * 4);
         o.dBpart = off; off += up((size_t)o.splitB * 2 * P * H * 4);
-        o.dApart = off; off += up(o.plan.partial_elems * 8);
+        o.dApart = off; off += up(dA_elems * 8);
         o.dDpart = off; off += up((size_t)o.nslab * H * 4);
     }
     o.total = off;
@@ -215,14 +218,18 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     const int T = (int)(Bt * L);
     const float *xf = reinterpret_cast<const float *>(x);
 
+    // Shapes whose sequences are whole numbers of 128-row tiles: C^H dy runs the reverse scan on its
+    // own output tile (chi stored directly, dAbar rows per tile, no scan kernel).
+    const bool fused = lo.fdesc_bytes != 0 && gemm_can_scan_reverse(Bt, L, P);
     MARK();
-    if (lo.plan.nTB > 1)
+    if (!fused && lo.plan.nTB > 1)
         HIP_TRY(launch_clear(hdr, ws + lo.ticket, lo.desc + up(lo.plan.desc_bytes) - lo.ticket, s));
     PrepArgs pa{};
     pa.Lambda = reinterpret_cast<const float2 *>(Lambda); pa.B = reinterpret_cast<const float2 *>(B);
     pa.C = reinterpret_cast<const float2 *>(C); pa.log_delta = log_delta;
     pa.P = (int)P; pa.H = (int)H; pa.lam_bar = lam; pa.Bbar_ri = Bri; pa.Cc = Cc; pa.Bbar_c64 = nullptr;
-    pa.hdr = lo.plan.nTB > 1 ? nullptr : hdr;
+    pa.hdr = (fused || lo.plan.nTB == 1) ? hdr : nullptr;
+    if (fused) { pa.zero16 = reinterpret_cast<uint4 *>(ws + lo.fdesc); pa.n16 = lo.fdesc_bytes / 16; }
     // dD slabs: sum_t dy[t,h] u[t,h] over row slabs, in the same launch
     pa.cd.a = dy; pa.cd.b = u; pa.cd.T = T; pa.cd.H = (int)H; pa.cd.nslab = lo.nslab; pa.cd.partial = dDpart;
     HIP_TRY(launch_prep(pa, s));
@@ -234,6 +241,15 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     g3.B = Cc; g3.ldb = 2 * P; g3.b_kcontig = 0;
     g3.C = reinterpret_cast<float *>(chi); g3.ldc = 2 * P;
     g3.M = T; g3.N = (int)(2 * P); g3.K = (int)H; g3.splits = 1;
+    if (fused) {
+        g3.epilogue = 8;
+        g3.scan.lam = lam; g3.scan.is_first = is_first;
+        g3.scan.x0 = reinterpret_cast<const float2 *>(x0);
+        g3.scan.xsaved = reinterpret_cast<const float2 *>(x); g3.scan.partial = dApart;
+        g3.scan.dx0 = reinterpret_cast<float2 *>(dx0);
+        g3.scan.desc = reinterpret_cast<unsigned long long *>(ws + lo.fdesc); g3.scan.err = &hdr->err;
+        g3.scan.L = (int)L; g3.scan.P = (int)P; g3.scan.spin_limit = spin_limit();
+    }
     // dC slabs: [h, 2p+c] = sum_t dy[t,h] * x[t, 2p+c]    (needs only saved states: same launch)
     GemmArgs g4{};
     g4.A = dy; g4.lda = H; g4.a_kcontig = 0;
@@ -243,16 +259,18 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     HIP_TRY(launch_gemm_pair(g3, g4, s));
     MARK();
 
-    ScanArgs sa{};
-    sa.in = chi; sa.out = chi; sa.lam = lam; sa.is_first = is_first;
-    sa.x0 = reinterpret_cast<const float2 *>(x0);
-    sa.xsaved = reinterpret_cast<const float2 *>(x); sa.partial = dApart;
-    sa.dx0 = reinterpret_cast<float2 *>(dx0);
-    sa.desc = desc; sa.ticket = reinterpret_cast<uint32_t *>(ws + lo.ticket); sa.err = &hdr->err;
-    sa.Bt = (int)Bt; sa.L = (int)L; sa.P = (int)P;
-    sa.pxb = lo.plan.pxb; sa.cy = lo.plan.cy; sa.nPX = lo.plan.nPX; sa.nTB = lo.plan.nTB;
-    sa.spin_limit = spin_limit();
-    HIP_TRY(launch_scan(sa, true, s));
+    if (!fused) {
+        ScanArgs sa{};
+        sa.in = chi; sa.out = chi; sa.lam = lam; sa.is_first = is_first;
+        sa.x0 = reinterpret_cast<const float2 *>(x0);
+        sa.xsaved = reinterpret_cast<const float2 *>(x); sa.partial = dApart;
+        sa.dx0 = reinterpret_cast<float2 *>(dx0);
+        sa.desc = desc; sa.ticket = reinterpret_cast<uint32_t *>(ws + lo.ticket); sa.err = &hdr->err;
+        sa.Bt = (int)Bt; sa.L = (int)L; sa.P = (int)P;
+        sa.pxb = lo.plan.pxb; sa.cy = lo.plan.cy; sa.nPX = lo.plan.nPX; sa.nTB = lo.plan.nTB;
+        sa.spin_limit = spin_limit();
+        HIP_TRY(launch_scan(sa, true, s));
+    }
     MARK();
 
     // du[t,h] = sum_{p,c} chi[t, 2p+c] * Bbar_ri[2p+c, h] + D[h] dy[t,h]      (Re(Bbar^H chi) + D dy)
@@ -275,7 +293,7 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     ea.log_delta = log_delta; ea.P = (int)P; ea.H = (int)H;
     ea.dBbar_part = dBpart; ea.nsplit_B = lo.splitB;
     ea.dC_part = dCpart; ea.nsplit_C = lo.splitC;
-    ea.dAbar_part = dApart; ea.npart = (int64_t)Bt * lo.plan.nTB;
+    ea.dAbar_part = dApart; ea.npart = fused ? (int64_t)Bt * (L / 128) : (int64_t)Bt * lo.plan.nTB;
     ea.dD_part = dDpart; ea.nslab = lo.nslab;
     ea.dLambda = reinterpret_cast<float2 *>(dLambda); ea.dB = reinterpret_cast<float2 *>(dB);
     ea.dC = reinterpret_cast<float2 *>(dC); ea.dD = dD; ea.dlog_delta = dlog_delta;

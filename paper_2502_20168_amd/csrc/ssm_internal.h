@@ -16,6 +16,7 @@ namespace ssm {
 // 4: C = E (.) E2 + product (.) GELU'(E3) (adjoint of the gate with respect to its input);
 // 6: as 1, and C2 = GELU(C) (output projection that feeds the half-GLU gate);
 // 7: the resettable scan over the rows of the output tile (see ScanEpilogue): C = states;
+// 8: the reverse-time scan of the gradient pass over the rows of the output tile: C = chi;
 // 5: C = product + E (E may be null), C2 = [not rowflag[m]] conj(Abar) (.) C with diag = Abar and complex
 //    (re, im) column pairs (adjoint of one recurrence step)
 // A(m,k) = a_kcontig ? A[m*lda + k] : A[k*lda + m];  B(n,k) = b_kcontig ? B[n*ldb + k] : B[k*ldb + n]
@@ -30,7 +31,10 @@ struct ScanEpilogue {
     const float2 *lam;            // [P] Abar
     const uint8_t *is_first;      // [Bt*L] or null
     const float2 *x0;             // [Bt, P] or null
-    float2 *x_last;               // [Bt, P] or null
+    float2 *x_last;               // [Bt, P] or null (forward)
+    const float2 *xsaved;         // [Bt, L, P] states of the forward pass (reverse, epilogue 8)
+    float2 *partial;              // [Bt * L/128, P] per-tile rows of dAbar (reverse)
+    float2 *dx0;                  // [Bt, P] or null (reverse)
     unsigned long long *desc;     // [M/128 * ceil(N/128) * 64][2] tagged aggregate words, zero on entry
     unsigned *err;                // set when a bounded wait gives up
     int L, P;
@@ -45,13 +49,15 @@ struct GemmArgs {
     int epilogue; const uint8_t *rowflag;
     const float *E2; const float *E3; float *C2;     // epilogues 3 and 4 (gate), pitch lde / ldc
     int M, N, K, splits;
-    ScanEpilogue scan;                               // epilogue 7
+    ScanEpilogue scan;                               // epilogues 7 and 8
 };
 // the input projection can scan its own output (epilogue 7) for this shape (shape only), and
 // whether it will on this call (shape and environment)
 bool gemm_scan_shape_ok(int64_t Bt, int64_t L, int64_t P);
 bool gemm_can_scan(int64_t Bt, int64_t L, int64_t P);
-// bytes of tagged words epilogue 7 needs (zeroed before the launch)
+// the same for C^H dy with the reverse scan of the gradient pass (epilogue 8)
+bool gemm_can_scan_reverse(int64_t Bt, int64_t L, int64_t P);
+// bytes of tagged words epilogues 7 and 8 need (zeroed before the launch)
 size_t gemm_scan_desc_bytes(int64_t Bt, int64_t L, int64_t P);
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t s);
 // two independent problems in one launch (falls back to two launches for layouts without a

@@ -9,6 +9,7 @@ from paper_2502_20168_amd import workloads as wl
 from tests.parity_util import (GRAD_KEYS, TOL_FWD, TOL_GRAD, assert_close, check_workload, run_gpu)
 
 pytestmark = pytest.mark.gpu
+FWD_KEYS_ALL = ("y", "x", "x_last") + GRAD_KEYS
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -93,6 +94,60 @@ def test_maximum_widths(Bt, L, H, P):
     arithmetic, grids with tens of thousands of workgroups along the width, one lane group per
     state block of the scan."""
     check_workload(wl.custom("maxw", Bt, L, H, P, p_reset=0.1, with_x0=True, seed=77), backward=True)
+
+
+# Shapes whose sequences are whole numbers of 128-step tiles and that fill the chip: here the input
+# projection and C^H dy run the scans on their own output tiles (chains of tiles with look-back).
+SCANNING_TILES = [
+    # name, Bt, L, H, P, p_reset, force_first, with_x0
+    ("two_tiles_per_sequence", 16, 256, 24, 512, 0.02, True, True),
+    ("chain_of_32_tiles", 1, 4096, 16, 512, 0.002, False, True),
+    ("ragged_state_width", 4, 512, 48, 840, 0.05, False, True),
+    ("three_sequences_column_groups", 3, 1024, 40, 600, 0.01, True, False),
+    ("seven_sequences", 7, 512, 20, 520, 0.0, False, True),
+    ("every_step_resets", 8, 256, 16, 1024, 1.0, True, True),
+    ("no_reset_no_x0", 8, 384, 16, 640, 0.0, False, False),
+]
+
+
+@pytest.mark.parametrize("mode", ["default", "forward_only", "separate_kernels"])
+@pytest.mark.parametrize("case", SCANNING_TILES, ids=[c[0] for c in SCANNING_TILES])
+def test_projections_that_scan_their_own_tiles(case, mode, monkeypatch):
+    name, Bt, L, H, P, pr, ff, x0 = case
+    print("scanning tiles", case, mode, flush=True)
+    if mode != "default":
+        monkeypatch.setenv("SSM_FUSED_SCAN", "1" if mode == "forward_only" else "0")
+    else:
+        monkeypatch.delenv("SSM_FUSED_SCAN", raising=False)
+    check_workload(wl.custom(name, Bt, L, H, P, p_reset=pr, force_first=ff, with_x0=x0, seed=31), backward=True)
+
+
+def test_resets_on_the_edges_of_tiles_and_chunks():
+    """Flags at the first and last step of 128-step tiles and of the 32-step runs one lane owns,
+    at step 0 with an initial state, and at the last step of the sequence."""
+    w = wl.custom("edges", 8, 512, 16, 1024, with_x0=True, seed=41)
+    inp = wl.gen_inputs(w)
+    fl = np.zeros((8, 512), np.uint8)
+    fl[0, [127, 128, 129]] = 1
+    fl[1, [0, 31, 32, 33, 255, 256]] = 1
+    fl[2, [511]] = 1
+    fl[3, [128, 384]] = 1
+    fl[4, [127, 383, 510]] = 1
+    fl[5, [1, 2, 3, 64, 96, 160]] = 1
+    fl[6, :] = 0
+    fl[7, 256:] = 1
+    inp["is_first"] = fl
+    check_workload(w, backward=True, inp=inp)
+
+
+def test_scanning_tiles_are_bitwise_repeatable():
+    import torch
+    w = wl.custom("repeat", 8, 512, 32, 640, p_reset=0.02, with_x0=True, seed=43)
+    inp = wl.gen_inputs(w)
+    a = run_gpu(inp, True)
+    b = run_gpu(inp, True)
+    for k in FWD_KEYS_ALL:
+        assert np.array_equal(a[k], b[k]), k
 
 
 def test_reset_at_last_step_and_x0_with_first_step_reset():
