@@ -7,12 +7,14 @@ scan, output projection) plus the gradient pass (C^H dy, reverse scan, du, param
 in HBM.  Prints ONE JSON line:
   metric/value : whole-job throughput in Mtokens/s (token = one (sequence, step) pair)
   roofline     : the dominant kernel (the projection GEMM: fp32 in/out, three-way bf16 operand
-                 split, six bf16 MFMAs per k block) against the bf16 matrix peak, its duration
-                 measured with HIP events on the launch stream inside the library's *_profiled
-                 entry points; the fp32-equivalent rate is given next to it
+                 split, six bf16 MFMAs per k block; the launch with the largest share of the
+                 step) against the bf16 matrix peak, its duration measured with HIP events on
+                 the launch stream inside the library's *_profiled entry points; the
+                 fp32-equivalent rate is given next to it, and every launch of the kernel below
   scan_roofline: the two scan kernels against the HBM peak (algorithmic bytes / event time),
                  warm (buffers resident in the 256 MB last-level cache) and cold (rotating over
-                 more than 1 GiB of distinct buffers)
+                 more than 1 GiB of distinct buffers); at shapes where the projections scan
+                 their own output tiles these kernels are not in the path and are timed alone
   cpu_baseline : the float64 CPU oracle timed on the host cores on a bounded sample
 """
 import argparse
@@ -29,11 +31,13 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix
 PEAK_BF16_MFMA_TFLOPS = 2500.0 # MI355X dense bf16 matrix
 BF16_PRODUCTS = 6              # bf16 MFMA products the GEMM issues per fp32 multiply-add
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what
-# the same counters read for a copy-like kernel of known size (profiles/gemm_bf16x3_scan_cfg2_fwd_bwd.md):
-# 24.4 MiB read + 16.2 MiB written; algorithmic 10 MiB (u 8 + Bbar 2, the latter once per XCD) + 16 MiB
-TRAFFIC_PROJECT_IN = {"read_bytes": 25.6e6, "write_bytes": 17.0e6, "algorithmic_read_bytes": 10.5e6,
-                      "algorithmic_write_bytes": 16.8e6, "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, see profiles/"}
+# HBM bytes per launch of the dominant kernel at config 2 (the launch that computes Re(Bbar^H chi) + D dy
+# and the dBbar slabs) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same counters
+# read for a copy-like kernel of known size (profiles/gemm_bf16x3_scan_cfg2_fwd_bwd.md): 78.2 MiB read +
+# 16.2 MiB written; algorithmic 50 MiB (chi 16 + Bbar 2 + dy 8 for du; chi 16 + u 8 for the slabs) + 16 MiB
+# (du 8 + the dBbar slabs 8)
+TRAFFIC_DU_DBBAR = {"read_bytes": 82.0e6, "write_bytes": 17.0e6, "algorithmic_read_bytes": 52.4e6,
+                    "algorithmic_write_bytes": 16.8e6, "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, see profiles/"}
 
 
 def main():
@@ -143,44 +147,73 @@ def main():
     stages.update({"bwd_" + n: round(float(v) * 1e3, 2) for n, v in zip(ssm.BWD_STAGE_NAMES, bs)})
 
     gemm_flops = 2.0 * T * (2 * P) * H                    # fp32 flops of every one of the six projections
-    # Dominant kernel: gemm_bf16x3_ws_kernel.  Its largest share of the step is the instantiation for
-    # a k-contiguous A operand (input projection; 128x128x32 tiles).  Algorithmic work of the kernel =
-    # the six bf16 partial products per multiply-add that the exact three-way split needs.
     f32_path = os.environ.get("SSM_GEMM_F32", "") == "1"
-    dom_ms = fs[1]
-    dom_fp32_tflops = gemm_flops / (dom_ms * 1e-3) / 1e12
-    gemm_ms = {"project_in": fs[1], "project_out": fs[3], "gx_with_dC(2 gemms)": bs[1] / 2,
-               "du_with_dBbar(2 gemms)": bs[3] / 2}
+    fused_env = os.environ.get("SSM_FUSED_SCAN", "")
+    shape_scans = (L % 128 == 0 and L // 128 <= 32 and (T // 128) * ((2 * P + 127) // 128) >= 200 and not f32_path)
+    fwd_fused = shape_scans and fused_env != "0"
+    rev_fused = shape_scans and fused_env not in ("0", "1")
+    npl = 2 if os.environ.get("SSM_GEMM_SPLIT", "") == "2" else 3
+    kern = lambda tile, lay0, lay1: "gemm_bf16x3_ws_kernel<%s,2,2,8,2,%d,%d,%d>" % (tile, npl, lay0, lay1)
+    big = (T // 128) * ((2 * P + 127) // 128) >= 200
+    out_tile = "128,128,32" if ((T + 127) // 128) * ((H + 127) // 128) >= 200 else \
+               ("64,128,32" if ((T + 63) // 64) * ((H + 127) // 128) >= 200 else "64,64,64")
+    in_tile = "128,128,32" if big else ("64,128,32" if ((T + 63) // 64) * ((2 * P + 127) // 128) >= 200 else "64,64,64")
+    # every launch of the projection kernel in one step: role, instantiation, fp32 flops, duration
+    launches = [
+        {"role": "input projection" + (" + forward scan in the tile" if fwd_fused else ""),
+         "kernel": kern(in_tile, 31 if fwd_fused else 3, -1), "gemms": 1, "ms": fs[1]},
+        {"role": "output projection + D u", "kernel": kern(out_tile, 7, -1), "gemms": 1, "ms": fs[3]},
+        {"role": "C^H dy" + (" + reverse scan in the tile" if rev_fused else "") + " and the dC slabs, one launch",
+         "kernel": kern("128,128,32", 33 if rev_fused else 1, 0), "gemms": 2, "ms": bs[1]},
+        {"role": "Re(Bbar^H chi) + D dy and the dBbar slabs, one launch",
+         "kernel": kern("128,128,32", 5, 0), "gemms": 2, "ms": bs[3]},
+    ]
+    for l in launches:
+        l["fp32_flops"] = l["gemms"] * gemm_flops
+        l["fp32_equivalent_tflops"] = round(l["fp32_flops"] / (l["ms"] * 1e-3) / 1e12, 2)
+        l["us"] = round(float(l.pop("ms")) * 1e3, 2)
+    # Dominant kernel = the launch of gemm_bf16x3_ws_kernel with the largest share of the step.  Its
+    # algorithmic work: the six bf16 partial products per multiply-add that the exact three-way
+    # split needs (three in the opt-in two-plane mode).
+    dom = max(launches, key=lambda l: l["us"])
+    dom_fp32_tflops = dom["fp32_flops"] / (dom["us"] * 1e-6) / 1e12
     if f32_path:
-        roofline = {"kernel": "gemm_f32_kernel<128,128,32,4,2,true,true,false> (input projection)",
+        roofline = {"kernel": "gemm_f32_kernel (%s)" % dom["role"],
                     "bound": "mfma", "achieved": round(dom_fp32_tflops, 2), "peak": PEAK_FP32_MFMA_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(dom_fp32_tflops / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": None}
     else:
-        ach = BF16_PRODUCTS * dom_fp32_tflops
-        roofline = {"kernel": "gemm_bf16x3_ws_kernel<128,128,32,2,2,8,2,3,3,-1> (input projection)",
+        products = 3 if npl == 2 else BF16_PRODUCTS
+        ach = products * dom_fp32_tflops
+        is_du = dom["kernel"] == kern("128,128,32", 5, 0) and npl == 3 and args.config == 2
+        roofline = {"kernel": "%s (%s)" % (dom["kernel"], dom["role"]),
                     "bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(ach / PEAK_BF16_MFMA_TFLOPS, 4),
-                    "traffic": TRAFFIC_PROJECT_IN["read_bytes"] + TRAFFIC_PROJECT_IN["write_bytes"],
-                    "traffic_detail": TRAFFIC_PROJECT_IN,
-                    "note": "achieved counts the 6 bf16 MFMA products per fp32 multiply-add that the kernel "
-                            "executes by design; fp32-equivalent rate and its ratio to the fp32 matrix peak below",
+                    "traffic": (TRAFFIC_DU_DBBAR["read_bytes"] + TRAFFIC_DU_DBBAR["write_bytes"]) if is_du else None,
+                    "traffic_detail": TRAFFIC_DU_DBBAR if is_du else None,
+                    "note": "achieved counts the %d bf16 MFMA products per fp32 multiply-add that the kernel "
+                            "executes by design; fp32-equivalent rate and its ratio to the fp32 matrix peak below" % products,
                     "fp32_equivalent_tflops": round(dom_fp32_tflops, 2),
                     "fp32_equivalent_over_fp32_matrix_peak": round(dom_fp32_tflops / PEAK_FP32_MFMA_TFLOPS, 4)}
-    roofline.update({"flops_per_launch_fp32": gemm_flops, "avg_launch_us": round(float(dom_ms) * 1e3, 2),
-                     "all_gemms_fp32_equivalent_tflops": {k: round(gemm_flops / (v * 1e-3) / 1e12, 2)
-                                                          for k, v in gemm_ms.items()}})
+    roofline.update({"flops_per_launch_fp32": dom["fp32_flops"], "avg_launch_us": dom["us"],
+                     "all_launches": launches})
 
-    # ---- scan kernels against the HBM roofline: algorithmic bytes = 16 B (forward: read v, write x)
-    # and 24 B (reverse: read gx, read x, write chi) per (token, state)
+    # ---- scans against the HBM roofline: algorithmic bytes = 16 B (forward: read v, write x) and
+    # 24 B (reverse: read gx, read x, write chi) per (token, state).  Where the projections scan their
+    # own tiles there is no scan kernel in the path; the scan-level entry points are timed on their own.
     fwd_bytes, rev_bytes = 16.0 * T * P, 24.0 * T * P
     scan = {"bound": "hbm", "peak": PEAK_HBM_GBS, "unit": "GB/s",
             "fwd_bytes_per_launch": fwd_bytes, "rev_bytes_per_launch": rev_bytes,
-            "in_path_fwd_us": round(float(fs[2]) * 1e3, 2), "in_path_rev_us": round(float(bs[2]) * 1e3, 2),
-            "in_path_fwd_GBs": round(fwd_bytes / (fs[2] * 1e-3) / 1e9, 1),
-            "in_path_rev_GBs": round(rev_bytes / (bs[2] * 1e-3) / 1e9, 1)}
+            "in_path": {"fwd": "inside the input projection" if fwd_fused else "scan_kernel<false>",
+                        "rev": "inside the C^H dy launch" if rev_fused else "scan_kernel<true>"},
+            "in_path_fwd_us": None if fwd_fused else round(float(fs[2]) * 1e3, 2),
+            "in_path_rev_us": None if rev_fused else round(float(bs[2]) * 1e3, 2),
+            "in_path_fwd_GBs": None if fwd_fused else round(fwd_bytes / (fs[2] * 1e-3) / 1e9, 1),
+            "in_path_rev_GBs": None if rev_fused else round(rev_bytes / (bs[2] * 1e-3) / 1e9, 1)}
     scan.update(scan_cold_warm(ssm, torch, d, Bt, L, P, fwd_bytes, rev_bytes))
     scan["frac"] = round(scan["cold_fwd_GBs"] / PEAK_HBM_GBS, 4)
     scan["frac_of_copy_kernel_cold"] = round(scan["cold_fwd_GBs"] / scan["copy_cold_GBs"], 4)
+    if (fwd_fused or rev_fused) and not args.path_only:
+        scan["separate_kernels"] = separate_scan_kernels(step, args.warmup, args.steps, T, torch, time)
 
     result = {
         "metric": "SSM scan fwd+bwd Mtokens/s (B=16, L=256, H=P=512); achieved HBM GB/s in scan_roofline and composite_hbm", "value": round(mtok, 3), "unit": "Mtokens/s",
@@ -207,6 +240,30 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, inp)
     print(json.dumps(result))
+
+
+def separate_scan_kernels(step, warmup, steps, T, torch, time):
+    """The same step with SSM_FUSED_SCAN=0 (projections and scans as separate kernels), for comparison."""
+    old = os.environ.get("SSM_FUSED_SCAN")
+    os.environ["SSM_FUSED_SCAN"] = "0"
+    try:
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) / steps * 1e3
+    finally:
+        if old is None:
+            os.environ.pop("SSM_FUSED_SCAN", None)
+        else:
+            os.environ["SSM_FUSED_SCAN"] = old
+    step()                                                  # leave the default path's results in the buffers
+    torch.cuda.synchronize()
+    return {"ms_per_step": round(ms, 4), "Mtokens_per_s": round(T / (ms * 1e-3) / 1e6, 3),
+            "note": "SSM_FUSED_SCAN=0: scan_kernel<false> / scan_kernel<true> between the projections"}
 
 
 def compulsory_bytes(Bt, L, H, P):

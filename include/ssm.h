@@ -27,12 +27,17 @@
  *     and need not be initialised or preserved between calls.
  *   - Gradient of the real loss l w.r.t. a complex quantity q is returned as
  *     dl/dRe(q) + i dl/dIm(q).
- *   - Three environment variables are read at call time: SSM_GEMM_F32=1 runs the projections on
+ *   - Four environment variables are read at call time: SSM_GEMM_F32=1 runs the projections on
  *     the fp32 matrix instruction instead of the (equally accurate, faster) three-way bf16 split;
  *     SSM_GEMM_SPLIT=2 is an opt-in reduced-precision mode of the projections (two bf16 planes per
  *     operand, three partial products: a product is good to 2^-16 instead of 2^-23; results stay
  *     inside the 1e-4 / 1e-3 tolerances of the benchmark configurations, the default is 3);
- *     SSM_SPIN_LIMIT=<n> bounds the polls of a cross-workgroup wait in the scan (default 2^20).
+ *     SSM_SPIN_LIMIT=<n> bounds the polls of a cross-workgroup wait in the scan (default 2^20);
+ *     SSM_FUSED_SCAN selects where the scans run when every sequence is a whole number of 128-step
+ *     tiles (L % 128 == 0, L <= 4096) and the batch fills the chip: by default the input projection
+ *     and C^H dy scan their own output tiles (no scan kernel, no round trip of Bbar u and C^H dy
+ *     through memory); =1 does so only in the forward pass, =0 keeps projections and scans as
+ *     separate kernels.  All three settings meet the same tolerances; results differ by rounding.
  */
 #ifndef SSM_H_
 #define SSM_H_
@@ -232,7 +237,9 @@ ssm_status ssm_block_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 
  *   forward : [0] discretise+pack, [1] input projection, [2] scan, [3] output projection
  *   backward: [0] discretise+pack and dD partials, [1] gx = C^H dy with the dC partials (one
  *             launch), [2] reverse scan, [3] du with the dBbar partials (one launch),
- *             [4] parameter epilogue                                                            */
+ *             [4] parameter epilogue
+ * Where a projection scans its own output tiles (see SSM_FUSED_SCAN above) stage [2] holds no kernel
+ * and reads as the few microseconds between two events; the scan's time is inside stage [1].     */
 ssm_status ssm_scan_fwd_profiled(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C,
                                  const float *D, const float *log_delta, const float *u,
                                  const uint8_t *is_first, const ssm_c64 *x0,
