@@ -371,6 +371,41 @@ def test_bounded_wait_reports_instead_of_hanging():
     assert ssm.ssm_workspace_status(ws) == ssm.SSM_OK
 
 
+def test_bounded_wait_inside_the_scanning_projections():
+    """The same for the waits along the chain of tiles of a sequence (32 tiles here) inside the input
+    projection and inside C^H dy: with a spin limit of zero both passes terminate, report or are right."""
+    import os
+    w = wl.custom("spin0_tiles", 1, 4096, 16, 512, p_reset=0.001, with_x0=True, seed=5)
+    inp = wl.gen_inputs(w)
+    d = ssm.to_device(inp)
+    par = (d["Lambda"], d["B"], d["C"], d["D"], d["log_delta"])
+    ws_f = ssm.alloc_workspace(w.Bt, w.L, w.H, w.P, False)
+    ws_b = ssm.alloc_workspace(w.Bt, w.L, w.H, w.P, True)
+    good = ssm.ssm_scan_fwd(*par, d["u"], d["is_first"], d["x0"], workspace=ws_f)
+    assert ssm.ssm_workspace_status(ws_f) == ssm.SSM_OK
+    x_good = good["x"].clone()
+    os.environ["SSM_SPIN_LIMIT"] = "0"
+    try:
+        out = ssm.ssm_scan_fwd(*par, d["u"], d["is_first"], d["x0"], workspace=ws_f)
+        st_f = ssm.ssm_workspace_status(ws_f)
+        grads = ssm.ssm_scan_bwd(*par, d["u"], d["is_first"], d["x0"], x_good, d["dy"], workspace=ws_b)
+        st_b = ssm.ssm_workspace_status(ws_b)
+    finally:
+        os.environ.pop("SSM_SPIN_LIMIT", None)
+    assert st_f in (ssm.SSM_OK, ssm.SSM_ERR_SCAN_TIMEOUT) and st_b in (ssm.SSM_OK, ssm.SSM_ERR_SCAN_TIMEOUT)
+    ref = orc.run_workload(inp, True)
+    if st_f == ssm.SSM_OK:
+        assert_close(out["y"].cpu().numpy(), ref["y"], TOL_FWD, "spin0 tiles y")
+    if st_b == ssm.SSM_OK:
+        assert_close(grads["du"].cpu().numpy(), ref["du"], TOL_GRAD, "spin0 tiles du")
+    # with the default limit the same calls on the same workspaces are clean and right
+    out = ssm.ssm_scan_fwd(*par, d["u"], d["is_first"], d["x0"], workspace=ws_f)
+    grads = ssm.ssm_scan_bwd(*par, d["u"], d["is_first"], d["x0"], out["x"], d["dy"], workspace=ws_b)
+    assert ssm.ssm_workspace_status(ws_f) == ssm.SSM_OK and ssm.ssm_workspace_status(ws_b) == ssm.SSM_OK
+    assert_close(out["y"].cpu().numpy(), ref["y"], TOL_FWD, "tiles y")
+    assert_close(grads["dLambda"].cpu().numpy(), ref["dLambda"], TOL_GRAD, "tiles dLambda")
+
+
 def test_two_stacked_layers_at_the_vision_shape():
     """Vision-task shape of the paper's hyper-parameter table (layer width 1024, state 512, two SSM
     layers): layer 2 consumes layer 1's output, the gradient pass chains back through both.  The
