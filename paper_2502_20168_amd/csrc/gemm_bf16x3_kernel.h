@@ -207,8 +207,10 @@ struct SplitLoader {
 constexpr int SCAN_TILE = 128;                       // rows and columns of the tile
 constexpr int SCAN_TS = SCAN_TILE + 4;               // LDS row stride of the staged tile (floats)
 constexpr int SCAN_MAX_CHAIN = 32;                   // tiles per sequence the fold can take
+constexpr int SCAN_WAVES = 8;                        // wavefronts that scan: the consumers and the first producers
+constexpr int SCAN_RC = SCAN_TILE / SCAN_WAVES;      // consecutive steps per thread
 constexpr size_t SCAN_LDS_BYTES = (size_t)SCAN_TILE * SCAN_TS * 4   // staged tile
-                                  + 4 * 64 * 8 + 4 * 64 * 4          // chunk states and reset tags
+                                  + SCAN_WAVES * 64 * 8 + SCAN_WAVES * 64 * 4   // chunk states and reset tags
                                   + SCAN_MAX_CHAIN * 64 * 8 + SCAN_MAX_CHAIN * 64 * 4   // predecessors
                                   + 64 * 8;                          // incoming state per lane
 
@@ -218,8 +220,8 @@ struct ScanLds {
     {
         char *p = static_cast<char *>(base);
         tile = reinterpret_cast<float *>(p); p += (size_t)SCAN_TILE * SCAN_TS * 4;
-        cS = reinterpret_cast<float2 *>(p); p += 4 * 64 * 8;
-        cAny = reinterpret_cast<unsigned *>(p); p += 4 * 64 * 4;
+        cS = reinterpret_cast<float2 *>(p); p += SCAN_WAVES * 64 * 8;
+        cAny = reinterpret_cast<unsigned *>(p); p += SCAN_WAVES * 64 * 4;
         pS = reinterpret_cast<float2 *>(p); p += SCAN_MAX_CHAIN * 64 * 8;
         pAny = reinterpret_cast<unsigned *>(p); p += SCAN_MAX_CHAIN * 64 * 4;
         sX = reinterpret_cast<float2 *>(p);
@@ -240,17 +242,21 @@ __device__ __forceinline__ void scan_epilogue_barriers(const GemmDev &g, int m0)
     if (REV) __syncthreads();
 }
 
-// tid: 0..255 (consumer thread); the tile is staged in lds.tile on entry (after the first two barriers).
+// tid: 0 .. 64*SCAN_WAVES-1 (the consumers and the first producer wavefronts: the scan is bound by
+// the issue rate of dependent multiply-adds, so eight wavefronts with 16 steps per lane finish a pass
+// in about half the time of four with 32); the tile is staged in lds.tile on entry (after the first
+// two barriers).
 // REV: the scan of the gradient pass, chi_t = gx_t + [not is_first_{t+1}] conj(Abar) chi_{t+1}, which
 // walks time backwards (later chunks and later tiles are the predecessors) and also reduces
 // dAbar += [not is_first_t] conj(x_{t-1}) chi_t per tile and writes dx0.
 template <bool REV>
 __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanLds &lds, int tid, int m0, int n0, int tile)
 {
-    constexpr int RC = 32;                                   // steps per thread
+    constexpr int RC = SCAN_RC, NCH = SCAN_WAVES;
+    static_assert(RC == 16, "flag loads and the powers of Abar below assume 16 steps per lane");
     const ScanEpilogue &a = g.scan;
     const int c = tid & 63, q = tid >> 6;
-    const int ql = REV ? 3 - q : q;                          // chunk index in scan order
+    const int ql = REV ? NCH - 1 - q : q;                    // chunk index in scan order
     const int p = n0 / 2 + c;
     const bool active = p < a.P;
     const int b = m0 / a.L, tmL = (m0 % a.L) / SCAN_TILE, nt = a.L / SCAN_TILE;
@@ -267,9 +273,9 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
     if (a.is_first) {
         const uint8_t *fp = a.is_first + (long)b * a.L + t0;
         if ((reinterpret_cast<uintptr_t>(fp) & 15) == 0) {
-            const uint4 w0 = *reinterpret_cast<const uint4 *>(fp), w1 = *reinterpret_cast<const uint4 *>(fp + 16);
-            if ((w0.x | w0.y | w0.z | w0.w | w1.x | w1.y | w1.z | w1.w) != 0) {
-                const unsigned ww[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+            const uint4 w0 = *reinterpret_cast<const uint4 *>(fp);
+            if ((w0.x | w0.y | w0.z | w0.w) != 0) {
+                const unsigned ww[4] = {w0.x, w0.y, w0.z, w0.w};
 #pragma unroll
                 for (int j = 0; j < RC; ++j) fmask |= (unsigned)(((ww[j >> 2] >> (8 * (j & 3))) & 0xffu) != 0) << j;
             }
@@ -284,7 +290,7 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
     if (REV) {
         unsigned next = 1;
         if (t0 + RC < a.L) next = a.is_first ? (unsigned)(a.is_first[(long)b * a.L + t0 + RC] != 0) : 0u;
-        rmask = (fmask >> 1) | (next << 31);
+        rmask = (fmask >> 1) | (next << (RC - 1));
     }
     // pass 1: state after the thread's steps for zero incoming state (a reset zeroes the multiplier)
     float2 S = make_float2(0.f, 0.f);
@@ -295,26 +301,27 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
         const float2 le = make_float2(r ? 0.f : lam.x, r ? 0.f : lam.y);
         S = cfma(le, S, val[e]);
     }
-    float2 l32 = cmul(lam, lam);                             // Abar^32 by five squarings
-    l32 = cmul(l32, l32); l32 = cmul(l32, l32); l32 = cmul(l32, l32); l32 = cmul(l32, l32);
+    float2 lrc = cmul(lam, lam);                             // Abar^16 by four squarings
+    lrc = cmul(lrc, lrc); lrc = cmul(lrc, lrc); lrc = cmul(lrc, lrc);
     lds.cS[ql * 64 + c] = S;
     lds.cAny[ql * 64 + c] = rmask != 0;
     __syncthreads();                                                                       // barrier 3
     // exclusive combine over the chunks that come earlier in scan order
     float2 Aex = make_float2(1.f, 0.f), Sex = make_float2(0.f, 0.f);
 #pragma unroll
-    for (int j = 0; j < 3; ++j) {
+    for (int j = 0; j < NCH - 1; ++j) {
         const float2 Sj = lds.cS[j * 64 + c];
-        const float2 Aj = lds.cAny[j * 64 + c] ? make_float2(0.f, 0.f) : l32;
+        const float2 Aj = lds.cAny[j * 64 + c] ? make_float2(0.f, 0.f) : lrc;
         const float2 nS = cfma(Aj, Sex, Sj), nA = cmul(Aj, Aex);
         if (j < ql) { Sex = nS; Aex = nA; }
     }
-    const bool leader = (ql == 3);
+    const bool leader = (ql == NCH - 1);
     const int npred = REV ? nt - 1 - tmL : tmL;              // tiles of the chain that come earlier in scan order
     const bool has_succ = REV ? (tmL > 0) : (tmL + 1 < nt);
-    float2 l128 = cmul(l32, l32); l128 = cmul(l128, l128);
+    float2 l128 = cmul(lrc, lrc);                            // Abar^128 by three more squarings
+    l128 = cmul(l128, l128); l128 = cmul(l128, l128);
     if (leader) {
-        const float2 Ath = (rmask != 0) ? make_float2(0.f, 0.f) : l32;
+        const float2 Ath = (rmask != 0) ? make_float2(0.f, 0.f) : lrc;
         const float2 Stile = cfma(Ath, Sex, S);
         const bool any_tile = (rmask != 0) || (Aex.x == 0.f && Aex.y == 0.f);
         if (active && has_succ) {
@@ -324,9 +331,9 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
         }
     }
     if (npred > 0) {
-        // thread (c, q) fetches the aggregates of predecessors q, q+4, ... (k-th predecessor in scan
+        // thread (c, q) fetches the aggregates of predecessors q, q+NCH, ... (k-th predecessor in scan
         // order = tile k of the sequence forward, tile nt-1-k in reverse)
-        for (int k = q; k < npred; k += 4) {
+        for (int k = q; k < npred; k += NCH) {
             float2 Sj = make_float2(0.f, 0.f);
             unsigned tag = 2;
             if (active) {
@@ -398,7 +405,7 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
         __syncthreads();                                                                   // barrier 6 (reverse only)
         if (q == 0 && active) {
             float2 sum = make_float2(0.f, 0.f);
-            for (int j = 0; j < 4; ++j) { sum.x += lds.cS[j * 64 + c].x; sum.y += lds.cS[j * 64 + c].y; }
+            for (int j = 0; j < NCH; ++j) { sum.x += lds.cS[j * 64 + c].x; sum.y += lds.cS[j * 64 + c].y; }
             a.partial[((size_t)b * nt + tmL) * a.P + p] = sum;
         }
     }
@@ -476,7 +483,17 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
                 }
             }
         }
-        if constexpr (EPI == 7 || EPI == 8) scan_epilogue_barriers<EPI == 8>(g, m0);
+        if constexpr (EPI == 7 || EPI == 8) {
+            static_assert(EPI < 7 || (NC + NP >= SCAN_WAVES && NC <= SCAN_WAVES), "wavefronts of the scan epilogue");
+            if (wave < SCAN_WAVES) {
+                // the first producers scan with the consumers: barriers 1 and 2 frame the staging of the tile
+                __syncthreads();
+                __syncthreads();
+                scan_epilogue_body<EPI == 8>(g, ScanLds(smem), tid, m0, n0, scan_tile);
+            } else {
+                scan_epilogue_barriers<EPI == 8>(g, m0);
+            }
+        }
         return;
     }
 
