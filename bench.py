@@ -196,6 +196,10 @@ def main():
                     "fp32_equivalent_over_fp32_matrix_peak": round(dom_fp32_tflops / PEAK_FP32_MFMA_TFLOPS, 4)}
     roofline.update({"flops_per_launch_fp32": dom["fp32_flops"], "avg_launch_us": dom["us"],
                      "all_launches": launches})
+    if not f32_path:
+        roofline["measured_matrix_only"] = mfma_only_rate(ssm, torch, dom["us"])
+        roofline["frac_of_measured_matrix_only"] = round(
+            roofline["achieved"] / roofline["measured_matrix_only"]["launch_like_the_dominant_one"]["TFLOPs"], 4)
 
     # ---- scans against the HBM roofline: algorithmic bytes = 16 B (forward: read v, write x) and
     # 24 B (reverse: read gx, read x, write chi) per (token, state).  Where the projections scan their
@@ -240,6 +244,33 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, inp)
     print(json.dumps(result))
+
+
+def mfma_only_rate(ssm, torch, dom_us):
+    """The projection kernel's matrix-instruction stream alone (ssm_mfma_probe: one wavefront per SIMD
+    on all 256 CUs, register operands with changing bits): what the matrix cores sustain on this
+    device, at the clock they hold under that load, for a launch as long as the dominant one and for
+    a long one.  Context for roofline.frac, whose peak is the published 2.4 GHz figure."""
+    flops_per_iter = 256 * 4 * 24 * 2.0 * 32 * 32 * 16
+    out = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
+    res = {}
+    # 24 matrix instructions of 8 passes take 768 cycles: about 0.4 us per iteration
+    for label, iters in (("launch_like_the_dominant_one", max(8, int(dom_us / 0.42))), ("long_launch", 4000)):
+        for _ in range(3):
+            ssm.ssm_mfma_probe(256, iters, out=out)
+        torch.cuda.synchronize()
+        reps = 10
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            ssm.ssm_mfma_probe(256, iters, out=out)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        res[label] = {"iters": iters, "us": round(us, 2), "TFLOPs": round(flops_per_iter * iters / (us * 1e-6) / 1e12, 1)}
+    res["note"] = ("bf16 32x32x16 matrix instructions only, 256 workgroups x 4 wavefronts; includes the launch; "
+                   "the published peak assumes 2.4 GHz")
+    return res
 
 
 def separate_scan_kernels(step, warmup, steps, T, torch, time):

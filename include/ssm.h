@@ -231,6 +231,14 @@ ssm_status ssm_block_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 
                          float *du, ssm_c64 *dLambda, ssm_c64 *dB, ssm_c64 *dC, float *dD, float *dlog_delta,
                          ssm_c64 *dx0, float *dW, void *workspace, size_t ws_bytes, void *stream);
 
+/* Measurement aid for the roofline of the projection kernel (no operation of the paper): launches
+ * `workgroups` workgroups of four wavefronts that issue nothing but the bf16 matrix instructions of
+ * the projection kernel's inner loop (24 v_mfma_f32_32x32x16_bf16 per iteration and wavefront, on
+ * register operands whose bits change every iteration) for `iters` iterations.  The caller times
+ * the launch; the work is workgroups * 4 * iters * 24 * 2*32*32*16 flops.  out: device, at least
+ * workgroups * 256 floats (receives checksums).  workgroups <= 65536, iters <= 2^24.              */
+ssm_status ssm_mfma_probe(int64_t workgroups, int64_t iters, float *out, void *stream);
+
 /* Measurement aids: the same code path as ssm_scan_fwd / ssm_scan_bwd, with a HIP event recorded
  * on `stream` around every kernel.  They wait for the stream before returning and write the
  * milliseconds of each stage to the HOST array stage_ms:

@@ -29,7 +29,7 @@ EXPORTS = ("ssm_strerror", "ssm_version", "ssm_workspace_bytes", "ssm_discretize
            "ssm_scan_bwd", "ssm_scan_states", "ssm_scan_states_reverse", "ssm_scan_fwd_profiled",
            "ssm_scan_bwd_profiled", "ssm_workspace_status", "ssm_step_plan_bytes", "ssm_step_prepare", "ssm_step",
            "ssm_step_bwd", "ssm_lambda_return", "ssm_lambda_return_bwd", "ssm_half_glu_workspace_bytes", "ssm_half_glu_fwd",
-           "ssm_half_glu_bwd", "ssm_block_workspace_bytes", "ssm_block_fwd", "ssm_block_bwd")
+           "ssm_half_glu_bwd", "ssm_block_workspace_bytes", "ssm_block_fwd", "ssm_block_bwd", "ssm_mfma_probe")
 
 _lib = None
 _vp, _i64, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t
@@ -91,6 +91,8 @@ def lib():
         L.ssm_half_glu_fwd.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp, _vp, _sz, _vp]
         L.ssm_half_glu_bwd.restype = ctypes.c_int
         L.ssm_half_glu_bwd.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _vp, _vp, _vp, _sz, _vp]
+        L.ssm_mfma_probe.restype = ctypes.c_int
+        L.ssm_mfma_probe.argtypes = [_i64, _i64, _vp, _vp]
         L.ssm_block_workspace_bytes.restype = _sz
         L.ssm_block_workspace_bytes.argtypes = [_i64, _i64, _i64, _i64, ctypes.c_int]
         L.ssm_block_fwd.restype = ctypes.c_int
@@ -363,6 +365,19 @@ def ssm_lambda_return_bwd(cont, value, ret, dret, gamma: float, lam: float, *, s
     return dr, dc, dv
 
 
+def ssm_mfma_probe(workgroups: int, iters: int, *, out=None, stream=None):
+    """Launches the matrix-instruction-only probe; returns the checksum tensor [workgroups * 256]."""
+    torch = _torch()
+    if out is None:
+        out = torch.empty(max(int(workgroups), 1) * 256, dtype=torch.float32, device="cuda")
+    if not out.is_cuda or out.dtype != torch.float32 or not out.is_contiguous() or out.numel() < int(workgroups) * 256:
+        raise ValueError("out must be a contiguous cuda float32 tensor of at least workgroups * 256 elements")
+    rc = lib().ssm_mfma_probe(int(workgroups), int(iters), _ptr(out), _stream(stream))
+    if rc != SSM_OK:
+        raise SsmError(rc, "ssm_mfma_probe")
+    return out
+
+
 def ssm_half_glu_workspace_bytes(T: int, H: int, want_bwd: bool) -> int:
     return int(lib().ssm_half_glu_workspace_bytes(T, H, 1 if want_bwd else 0))
 
@@ -407,7 +422,7 @@ def ssm_half_glu_bwd(u, W, gate, dy, *, workspace=None, du=None, dW=None, stream
     rc = lib().ssm_half_glu_bwd(_ptr(u), _ptr(W), _ptr(gate), _ptr(dy), T, H, _ptr(du), _ptr(dW), _ptr(ws), ws.numel(),
                                 _stream(stream))
     if rc != SSM_OK:
-        raise SsmError(rc, "ssm_half_glu_bwd", "ssm_block_workspace_bytes", "ssm_block_fwd", "ssm_block_bwd")
+        raise SsmError(rc, "ssm_half_glu_bwd", "ssm_block_workspace_bytes", "ssm_block_fwd", "ssm_block_bwd", "ssm_mfma_probe")
     return du, dW
 
 

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libssmscan.so")
-SOURCES = ["ssm_api.hip", "gemm_f32.hip", "scan.hip", "params.hip", "block.hip"]
+SOURCES = ["ssm_api.hip", "gemm_f32.hip", "scan.hip", "params.hip", "block.hip", "probe.hip"]
 HEADERS = [os.path.join(CSRC, "ssm_internal.h"), os.path.join(CSRC, "gemm_f32_kernel.h"),
            os.path.join(CSRC, "gemm_bf16x3_kernel.h"), os.path.join(CSRC, "lookback.h"),
            os.path.join(os.path.dirname(HERE), "include", "ssm.h")]

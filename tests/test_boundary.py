@@ -168,6 +168,14 @@ def test_s5_block_argument_errors(lib):
     assert lib.ssm_block_bwd(*F, 2, 8, 4, 4, FAKE, FAKE, FAKE, FAKE, *Gd, FAKE, need_b - 1, None) == ssm.SSM_ERR_WORKSPACE
 
 
+def test_mfma_probe_argument_errors(lib):
+    assert lib.ssm_mfma_probe(256, 10, None, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_mfma_probe(0, 10, FAKE, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_mfma_probe(256, 0, FAKE, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_mfma_probe(65537, 10, FAKE, None) == ssm.SSM_ERR_UNSUPPORTED
+    assert lib.ssm_mfma_probe(256, (1 << 24) + 1, FAKE, None) == ssm.SSM_ERR_UNSUPPORTED
+
+
 def test_binding_refuses_cpu_tensors(lib):
     import numpy as np
     import torch

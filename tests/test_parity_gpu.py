@@ -406,6 +406,17 @@ def test_bounded_wait_inside_the_scanning_projections():
     assert_close(grads["dLambda"].cpu().numpy(), ref["dLambda"], TOL_GRAD, "tiles dLambda")
 
 
+def test_matrix_instruction_probe_runs_and_is_repeatable():
+    """The measurement aid behind the benchmark's matrix-core ceiling: finite checksums, the same on
+    every run (its operands come from a counter-based hash, not from memory)."""
+    import torch
+    a = ssm.ssm_mfma_probe(64, 50).clone()
+    b = ssm.ssm_mfma_probe(64, 50)
+    torch.cuda.synchronize()
+    assert a.shape == (64 * 256,) and bool(torch.isfinite(a).all()) and bool(a.abs().max() > 0)
+    assert torch.equal(a, b)
+
+
 def test_two_stacked_layers_at_the_vision_shape():
     """Vision-task shape of the paper's hyper-parameter table (layer width 1024, state 512, two SSM
     layers): layer 2 consumes layer 1's output, the gradient pass chains back through both.  The
