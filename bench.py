@@ -149,7 +149,8 @@ def main():
     gemm_flops = 2.0 * T * (2 * P) * H                    # fp32 flops of every one of the six projections
     f32_path = os.environ.get("SSM_GEMM_F32", "") == "1"
     fused_env = os.environ.get("SSM_FUSED_SCAN", "")
-    shape_scans = (L % 128 == 0 and L // 128 <= 32 and (T // 128) * ((2 * P + 127) // 128) >= 200 and not f32_path)
+    shape_scans = (((L % 128 == 0 and L // 128 <= 32) or (L in (16, 32, 64) and T % 128 == 0))
+                   and (T // 128) * ((2 * P + 127) // 128) >= 200 and not f32_path)
     fwd_fused = shape_scans and fused_env != "0"
     rev_fused = shape_scans and fused_env not in ("0", "1")
     npl = 2 if os.environ.get("SSM_GEMM_SPLIT", "") == "2" else 3

@@ -233,7 +233,7 @@ template <bool REV>
 __device__ __forceinline__ void scan_epilogue_barriers(const GemmDev &g, int m0)
 {
     const int tmL = (m0 % g.scan.L) / SCAN_TILE, nt = g.scan.L / SCAN_TILE;
-    const bool has_pred = REV ? (tmL + 1 < nt) : (tmL > 0);
+    const bool has_pred = g.scan.L >= SCAN_TILE && (REV ? (tmL + 1 < nt) : (tmL > 0));
     __syncthreads();
     __syncthreads();
     __syncthreads();
@@ -259,9 +259,14 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
     const int ql = REV ? NCH - 1 - q : q;                    // chunk index in scan order
     const int p = n0 / 2 + c;
     const bool active = p < a.P;
-    const int b = m0 / a.L, tmL = (m0 % a.L) / SCAN_TILE, nt = a.L / SCAN_TILE;
+    // A tile is either one piece of a chain of tiles of one sequence (L a multiple of 128) or holds
+    // 128/L whole sequences (L = 16, 32, 64): then there is no chain, a sequence starts at a chunk
+    // boundary inside the tile and its incoming state is x0 (forward) or zero (reverse).
+    const bool whole_seqs = a.L < SCAN_TILE;
+    const int row0 = m0 + q * RC;                            // token index of this thread's first step
+    const int b = row0 / a.L, t0 = row0 % a.L;               // its sequence and its lowest time index
+    const int tmL = whole_seqs ? 0 : (m0 % a.L) / SCAN_TILE, nt = whole_seqs ? 1 : a.L / SCAN_TILE;
     const int tn = tile % g.ntn;
-    const int t0 = tmL * SCAN_TILE + q * RC;                 // lowest time index of this thread's steps
     float2 lam = active ? a.lam[p] : make_float2(0.f, 0.f);
     if (REV) lam.y = -lam.y;
 
@@ -271,7 +276,7 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
     // fmask bit e: is_first at time t0 + e
     unsigned fmask = 0;
     if (a.is_first) {
-        const uint8_t *fp = a.is_first + (long)b * a.L + t0;
+        const uint8_t *fp = a.is_first + row0;
         if ((reinterpret_cast<uintptr_t>(fp) & 15) == 0) {
             const uint4 w0 = *reinterpret_cast<const uint4 *>(fp);
             if ((w0.x | w0.y | w0.z | w0.w) != 0) {
@@ -289,7 +294,7 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
     unsigned rmask = fmask;
     if (REV) {
         unsigned next = 1;
-        if (t0 + RC < a.L) next = a.is_first ? (unsigned)(a.is_first[(long)b * a.L + t0 + RC] != 0) : 0u;
+        if (t0 + RC < a.L) next = a.is_first ? (unsigned)(a.is_first[(long)row0 + RC] != 0) : 0u;
         rmask = (fmask >> 1) | (next << (RC - 1));
     }
     // pass 1: state after the thread's steps for zero incoming state (a reset zeroes the multiplier)
@@ -306,16 +311,18 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
     lds.cS[ql * 64 + c] = S;
     lds.cAny[ql * 64 + c] = rmask != 0;
     __syncthreads();                                                                       // barrier 3
-    // exclusive combine over the chunks that come earlier in scan order
+    // exclusive combine over the chunks of the same sequence that come earlier in scan order
+    const int before = whole_seqs ? (REV ? (a.L - RC - t0) / RC : t0 / RC) : ql;
+    const int ql_first = ql - before;
     float2 Aex = make_float2(1.f, 0.f), Sex = make_float2(0.f, 0.f);
 #pragma unroll
     for (int j = 0; j < NCH - 1; ++j) {
         const float2 Sj = lds.cS[j * 64 + c];
         const float2 Aj = lds.cAny[j * 64 + c] ? make_float2(0.f, 0.f) : lrc;
         const float2 nS = cfma(Aj, Sex, Sj), nA = cmul(Aj, Aex);
-        if (j < ql) { Sex = nS; Aex = nA; }
+        if (j >= ql_first && j < ql) { Sex = nS; Aex = nA; }
     }
-    const bool leader = (ql == NCH - 1);
+    const bool leader = (ql == NCH - 1) && !whole_seqs;
     const int npred = REV ? nt - 1 - tmL : tmL;              // tiles of the chain that come earlier in scan order
     const bool has_succ = REV ? (tmL > 0) : (tmL + 1 < nt);
     float2 l128 = cmul(lrc, lrc);                            // Abar^128 by three more squarings
@@ -359,8 +366,10 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
     }
     __syncthreads();                                                                       // barrier 5
     // pass 2: the states themselves
-    float2 xs = cfma(Aex, lds.sX[c], Sex);
-    float2 *dst = reinterpret_cast<float2 *>(g.C) + ((long)b * a.L + t0) * a.P + p;
+    float2 Xin = lds.sX[c];
+    if (whole_seqs) Xin = (!REV && a.x0 && active) ? a.x0[(long)b * a.P + p] : make_float2(0.f, 0.f);
+    float2 xs = cfma(Aex, Xin, Sex);
+    float2 *dst = reinterpret_cast<float2 *>(g.C) + (long)row0 * a.P + p;
     if (!REV) {
 #pragma unroll
         for (int e = 0; e < RC; ++e) {
@@ -372,7 +381,7 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
         if (active && a.x_last && t0 + RC == a.L) a.x_last[(long)b * a.P + p] = xs;
     } else {
         // also dAbar += [not is_first_t] conj(x_{t-1}) chi_t; x_{-1} = x0 (zero when absent)
-        const float2 *xprev = a.xsaved + ((long)b * a.L + t0 - 1) * a.P + p;      // x_{t0-1}; valid for e >= 1 or t0 > 0
+        const float2 *xprev = a.xsaved + ((long)row0 - 1) * a.P + p;             // x_{t0-1}; valid for e >= 1 or t0 > 0
         float2 acc = make_float2(0.f, 0.f);
 #pragma unroll
         for (int blk = RC / 8 - 1; blk >= 0; --blk) {
@@ -406,7 +415,7 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
         if (q == 0 && active) {
             float2 sum = make_float2(0.f, 0.f);
             for (int j = 0; j < NCH; ++j) { sum.x += lds.cS[j * 64 + c].x; sum.y += lds.cS[j * 64 + c].y; }
-            a.partial[((size_t)b * nt + tmL) * a.P + p] = sum;
+            a.partial[(size_t)(m0 / SCAN_TILE) * a.P + p] = sum;
         }
     }
 }
@@ -730,7 +739,7 @@ inline GemmDev make_gemm_dev(const GemmArgs &a)
     else { g.mode = 3; g.mpar = 0; g.nx = (int)((ntiles * splits + 7) / 8); }
     g.scan = a.scan;
     g.sc_nt = g.sc_cpu = g.sc_ncg = g.sc_units = g.sc_rev = 0;
-    if (a.epilogue == 7 || a.epilogue == 8) {
+    if ((a.epilogue == 7 || a.epilogue == 8) && a.scan.L >= BM) {
         g.sc_rev = a.epilogue == 8;
         const int nseq = a.M / a.scan.L;
         g.sc_nt = a.scan.L / BM;

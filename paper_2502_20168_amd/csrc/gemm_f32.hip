@@ -91,9 +91,12 @@ static bool use_two_planes()
 
 bool gemm_scan_shape_ok(int64_t Bt, int64_t L, int64_t P)
 {
-    // 128-row tiles that never straddle two sequences, a bounded chain of tiles per sequence, and
-    // enough tiles that the plain product would use 128x128 tiles anyway
-    if (L % SCAN_TILE != 0 || L / SCAN_TILE > SCAN_MAX_CHAIN) return false;
+    // 128-row tiles that hold a piece of one sequence (a bounded chain of tiles per sequence) or a
+    // whole number of sequences made of whole 16-step chunks, and enough tiles that the plain
+    // product would use 128x128 tiles anyway
+    const bool chain = L % SCAN_TILE == 0 && L / SCAN_TILE <= SCAN_MAX_CHAIN;
+    const bool whole = L < SCAN_TILE && SCAN_TILE % L == 0 && L % SCAN_RC == 0 && (Bt * L) % SCAN_TILE == 0;
+    if (!chain && !whole) return false;
     const int64_t tiles = (Bt * L / SCAN_TILE) * ((2 * P + SCAN_TILE - 1) / SCAN_TILE);
     return tiles >= 200 && tiles * 64 <= 0x7fffffffLL;
 }
@@ -117,15 +120,19 @@ bool gemm_can_scan_reverse(int64_t Bt, int64_t L, int64_t P)
 // argument checks shared by the two scanning epilogues
 static bool scan_args_ok(const GemmArgs &a)
 {
-    if (a.splits > 1 || use_f32_mfma() || !a.scan.lam || !a.scan.desc || !a.scan.err) return false;
-    if (a.scan.L <= 0 || a.scan.L % SCAN_TILE != 0 || a.scan.L / SCAN_TILE > SCAN_MAX_CHAIN) return false;
-    if (a.M % a.scan.L != 0 || a.N != 2 * a.scan.P || !a.a_kcontig) return false;
+    if (a.splits > 1 || use_f32_mfma() || !a.scan.lam || !a.scan.err || a.scan.L <= 0) return false;
+    const int L = a.scan.L;
+    const bool chain = L % SCAN_TILE == 0 && L / SCAN_TILE <= SCAN_MAX_CHAIN && a.scan.desc;
+    const bool whole = L < SCAN_TILE && SCAN_TILE % L == 0 && L % SCAN_RC == 0 && a.M % SCAN_TILE == 0;
+    if (!chain && !whole) return false;
+    if (a.M % L != 0 || a.N != 2 * a.scan.P || !a.a_kcontig) return false;
     if (a.epilogue == 7) return a.b_kcontig != 0;
     return !a.b_kcontig && a.scan.xsaved && a.scan.partial;
 }
 
 size_t gemm_scan_desc_bytes(int64_t Bt, int64_t L, int64_t P)
 {
+    if (L < SCAN_TILE) return 0;                     // whole sequences per tile: nothing is handed over
     const int64_t tiles = (Bt * L / SCAN_TILE) * ((2 * P + SCAN_TILE - 1) / SCAN_TILE);
     return (size_t)tiles * 64 * 2 * sizeof(unsigned long long);
 }

@@ -52,7 +52,7 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
     if (gemm_scan_shape_ok(Bt, L, P)) {              // tagged words of a projection that scans its own output
         o.fdesc_bytes = gemm_scan_desc_bytes(Bt, L, P);
         o.fdesc = off; off += up(o.fdesc_bytes);
-        const size_t per_tile = (size_t)Bt * (L / 128) * P;        // one dAbar row per 128-step tile
+        const size_t per_tile = (size_t)(Bt * L / 128) * P;        // one dAbar row per 128-row tile
         if (per_tile > dA_elems) dA_elems = per_tile;
     }
     if (!bwd) {
@@ -132,7 +132,7 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
 
     // Shapes whose sequences are whole numbers of 128-row tiles: the input projection scans its own
     // output tile and stores the states directly (no scan kernel, Bbar u never goes to memory).
-    const bool fused = lo.fdesc_bytes != 0 && gemm_can_scan(Bt, L, P);
+    const bool fused = gemm_can_scan(Bt, L, P);
     MARK();
     if (!fused && lo.plan.nTB > 1)
         HIP_TRY(launch_clear(hdr, ws + lo.ticket, lo.desc + up(lo.plan.desc_bytes) - lo.ticket, s));
@@ -141,7 +141,7 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     pa.C = reinterpret_cast<const float2 *>(C); pa.log_delta = log_delta;
     pa.P = (int)P; pa.H = (int)H; pa.lam_bar = lam; pa.Bbar_ri = Bri; pa.Cc = Cc; pa.Bbar_c64 = nullptr;
     pa.hdr = (fused || lo.plan.nTB == 1) ? hdr : nullptr;
-    if (fused) { pa.zero16 = reinterpret_cast<uint4 *>(ws + lo.fdesc); pa.n16 = lo.fdesc_bytes / 16; }
+    if (fused && lo.fdesc_bytes) { pa.zero16 = reinterpret_cast<uint4 *>(ws + lo.fdesc); pa.n16 = lo.fdesc_bytes / 16; }
     HIP_TRY(launch_prep(pa, s));
     MARK();
 
@@ -220,7 +220,7 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
 
     // Shapes whose sequences are whole numbers of 128-row tiles: C^H dy runs the reverse scan on its
     // own output tile (chi stored directly, dAbar rows per tile, no scan kernel).
-    const bool fused = lo.fdesc_bytes != 0 && gemm_can_scan_reverse(Bt, L, P);
+    const bool fused = gemm_can_scan_reverse(Bt, L, P);
     MARK();
     if (!fused && lo.plan.nTB > 1)
         HIP_TRY(launch_clear(hdr, ws + lo.ticket, lo.desc + up(lo.plan.desc_bytes) - lo.ticket, s));
@@ -229,7 +229,7 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     pa.C = reinterpret_cast<const float2 *>(C); pa.log_delta = log_delta;
     pa.P = (int)P; pa.H = (int)H; pa.lam_bar = lam; pa.Bbar_ri = Bri; pa.Cc = Cc; pa.Bbar_c64 = nullptr;
     pa.hdr = (fused || lo.plan.nTB == 1) ? hdr : nullptr;
-    if (fused) { pa.zero16 = reinterpret_cast<uint4 *>(ws + lo.fdesc); pa.n16 = lo.fdesc_bytes / 16; }
+    if (fused && lo.fdesc_bytes) { pa.zero16 = reinterpret_cast<uint4 *>(ws + lo.fdesc); pa.n16 = lo.fdesc_bytes / 16; }
     // dD slabs: sum_t dy[t,h] u[t,h] over row slabs, in the same launch
     pa.cd.a = dy; pa.cd.b = u; pa.cd.T = T; pa.cd.H = (int)H; pa.cd.nslab = lo.nslab; pa.cd.partial = dDpart;
     HIP_TRY(launch_prep(pa, s));
@@ -293,7 +293,7 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     ea.log_delta = log_delta; ea.P = (int)P; ea.H = (int)H;
     ea.dBbar_part = dBpart; ea.nsplit_B = lo.splitB;
     ea.dC_part = dCpart; ea.nsplit_C = lo.splitC;
-    ea.dAbar_part = dApart; ea.npart = fused ? (int64_t)Bt * (L / 128) : (int64_t)Bt * lo.plan.nTB;
+    ea.dAbar_part = dApart; ea.npart = fused ? Bt * L / 128 : (int64_t)Bt * lo.plan.nTB;
     ea.dD_part = dDpart; ea.nslab = lo.nslab;
     ea.dLambda = reinterpret_cast<float2 *>(dLambda); ea.dB = reinterpret_cast<float2 *>(dB);
     ea.dC = reinterpret_cast<float2 *>(dC); ea.dD = dD; ea.dlog_delta = dlog_delta;

@@ -107,6 +107,11 @@ SCANNING_TILES = [
     ("seven_sequences", 7, 512, 20, 520, 0.0, False, True),
     ("every_step_resets", 8, 256, 16, 1024, 1.0, True, True),
     ("no_reset_no_x0", 8, 384, 16, 640, 0.0, False, False),
+    # several whole sequences per 128-token tile: no chain, a sequence starts at a chunk inside the tile
+    ("eight_sequences_per_tile", 256, 16, 16, 1024, 0.05, False, True),
+    ("four_sequences_per_tile", 128, 32, 24, 520, 0.05, True, True),
+    ("two_sequences_per_tile", 64, 64, 16, 1024, 0.03, False, False),
+    ("one_sequence_per_tile", 32, 128, 16, 1024, 0.02, False, True),
 ]
 
 
