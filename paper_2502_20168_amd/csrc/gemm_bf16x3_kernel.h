@@ -192,15 +192,20 @@ struct SplitLoader {
 };
 
 // ---------------------------------------------------------------------------------------------
-// Epilogue 7: resettable scan over the rows of a 128 x 128 output tile (128 steps of 64 complex
-// states of one sequence).  The 256 consumer threads are 64 lanes x 4 chunks of 32 steps:
-//   1. the accumulators go through LDS so that a thread owns 32 consecutive steps of one lane;
+// Epilogues 7 and 8: resettable scan (forward, or the reverse one of the gradient pass) over the
+// rows of a 128 x 128 output tile: 128 steps of 64 complex states, either a piece of one sequence
+// (L a multiple of 128; the pieces form a chain) or 128/L whole sequences (L = 16, 32, 64).
+// 512 threads (the consumers and the first four producer wavefronts) are 64 lanes x 8 chunks of
+// 16 steps:
+//   1. the accumulators go through LDS so that a thread owns 16 consecutive steps of one lane;
 //   2. per-thread pass for zero incoming state, chunk aggregates combined through LDS;
-//   3. the tile's aggregate (state for zero incoming state, reset tag) is published as tagged
-//      64-bit words before any wait; the tiles of the same sequence and column block that come
-//      earlier in time are folded in time order from the sequence start (x0 or zero), which is one
-//      canonical order whatever the timing, so results are bitwise reproducible;
-//   4. second per-thread pass writes the states (and x_last at the sequence end).
+//   3. chain of tiles: the tile's aggregate (state for zero incoming state, reset tag) is
+//      published as tagged 64-bit words before any wait; the tiles of the same sequence and column
+//      block that come earlier in scan order are folded in that order from the sequence start (x0
+//      or zero), which is one canonical order whatever the timing, so results are bitwise
+//      reproducible;
+//   4. second per-thread pass writes the states (forward: x_last at the sequence end; reverse: the
+//      per-tile row of dAbar and dx0).
 // Every predecessor sits in an earlier slot of the same XCD (placement mode 5), i.e. it was
 // dispatched earlier and publishes without waiting for anything, and every wait is bounded.
 // ---------------------------------------------------------------------------------------------
@@ -228,7 +233,7 @@ struct ScanLds {
     }
 };
 
-// producers only keep the consumers company at the workgroup barriers of the scan epilogue
+// the wavefronts that do not scan only keep the others company at the workgroup barriers of the epilogue
 template <bool REV>
 __device__ __forceinline__ void scan_epilogue_barriers(const GemmDev &g, int m0)
 {
