@@ -145,6 +145,29 @@ def test_resets_on_the_edges_of_tiles_and_chunks():
     check_workload(w, backward=True, inp=inp)
 
 
+def test_flag_array_at_an_odd_address():
+    """is_first only needs byte alignment: the 16-byte flag loads of the scanning tiles and of the
+    scan kernel must fall back to byte loads for a buffer that starts at an odd address."""
+    import torch
+    for Bt, L, H, P in ((8, 256, 16, 1024), (128, 16, 16, 1024), (3, 200, 16, 48)):
+        w = wl.custom("oddflags", Bt, L, H, P, p_reset=0.05, with_x0=True, seed=47)
+        inp = wl.gen_inputs(w)
+        ref = orc.run_workload(inp, True, nthreads=4)
+        d = ssm.to_device(inp)
+        raw = torch.zeros(Bt * L + 3, dtype=torch.uint8, device="cuda")
+        flags = raw[3:].view(Bt, L)
+        flags.copy_(d["is_first"])
+        assert flags.data_ptr() % 2 == 1 and flags.is_contiguous()
+        par = (d["Lambda"], d["B"], d["C"], d["D"], d["log_delta"])
+        fwd = ssm.ssm_scan_fwd(*par, d["u"], flags, d["x0"])
+        bwd = ssm.ssm_scan_bwd(*par, d["u"], flags, d["x0"], fwd["x"], d["dy"])
+        torch.cuda.synchronize()
+        assert_close(fwd["x"].cpu().numpy(), ref["x"], TOL_FWD, "odd flags x")
+        assert_close(fwd["y"].cpu().numpy(), ref["y"], TOL_FWD, "odd flags y")
+        for k in GRAD_KEYS:
+            assert_close(bwd[k].cpu().numpy(), ref[k], TOL_GRAD, "odd flags " + k)
+
+
 def test_scanning_tiles_are_bitwise_repeatable():
     import torch
     w = wl.custom("repeat", 8, 512, 32, 640, p_reset=0.02, with_x0=True, seed=43)
