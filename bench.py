@@ -156,6 +156,9 @@ def main():
     npl = 2 if os.environ.get("SSM_GEMM_SPLIT", "") == "2" else 3
     kern = lambda tile, lay0, lay1: "gemm_bf16x3_ws_kernel<%s,2,2,8,2,%d,%d,%d>" % (tile, npl, lay0, lay1)
     big = (T // 128) * ((2 * P + 127) // 128) >= 200
+    t128 = ((T + 127) // 128) * ((H + 127) // 128)
+    out_split = (not f32_path and t128 < 200 and 2 * t128 >= 200 and P >= 64 and (2 * P) % 64 == 0
+                 and os.environ.get("SSM_SPLIT_OUT", "") != "0")
     out_tile = "128,128,32" if ((T + 127) // 128) * ((H + 127) // 128) >= 200 else \
                ("64,128,32" if ((T + 63) // 64) * ((H + 127) // 128) >= 200 else "64,64,64")
     in_tile = "128,128,32" if big else ("64,128,32" if ((T + 63) // 64) * ((2 * P + 127) // 128) >= 200 else "64,64,64")
@@ -163,7 +166,9 @@ def main():
     launches = [
         {"role": "input projection" + (" + forward scan in the tile" if fwd_fused else ""),
          "kernel": kern(in_tile, 31 if fwd_fused else 3, -1), "gemms": 1, "ms": fs[1]},
-        {"role": "output projection + D u", "kernel": kern(out_tile, 7, -1), "gemms": 1, "ms": fs[3]},
+        ({"role": "output projection as two K halves, then the sum of the halves + D u (two kernels)",
+          "kernel": kern("128,128,32", 3, -1) + " + sum_halves_kernel", "gemms": 1, "ms": fs[3]} if out_split else
+         {"role": "output projection + D u", "kernel": kern(out_tile, 7, -1), "gemms": 1, "ms": fs[3]}),
         {"role": "C^H dy" + (" + reverse scan in the tile" if rev_fused else "") + " and the dC slabs, one launch",
          "kernel": kern("128,128,32", 33 if rev_fused else 1, 0), "gemms": 2, "ms": bs[1]},
         {"role": "Re(Bbar^H chi) + D dy and the dBbar slabs, one launch",

@@ -27,7 +27,7 @@
  *     and need not be initialised or preserved between calls.
  *   - Gradient of the real loss l w.r.t. a complex quantity q is returned as
  *     dl/dRe(q) + i dl/dIm(q).
- *   - Four environment variables are read at call time: SSM_GEMM_F32=1 runs the projections on
+ *   - Five environment variables are read at call time: SSM_GEMM_F32=1 runs the projections on
  *     the fp32 matrix instruction instead of the (equally accurate, faster) three-way bf16 split;
  *     SSM_GEMM_SPLIT=2 is an opt-in reduced-precision mode of the projections (two bf16 planes per
  *     operand, three partial products: a product is good to 2^-16 instead of 2^-23; results stay
@@ -38,7 +38,10 @@
  *     Bt * L a multiple of 128), and the batch fills the chip: by default the input projection
  *     and C^H dy scan their own output tiles (no scan kernel, no round trip of Bbar u and C^H dy
  *     through memory); =1 does so only in the forward pass, =0 keeps projections and scans as
- *     separate kernels.  All three settings meet the same tolerances; results differ by rounding.
+ *     separate kernels.  All three settings meet the same tolerances; results differ by rounding;
+ *     SSM_SPLIT_OUT=0 keeps the output projection in one kernel where by default it runs as two
+ *     halves of the state dimension plus a streaming sum (shapes with 100-199 tiles of 128 x 128
+ *     outputs, e.g. 4096 tokens and H = 512).
  */
 #ifndef SSM_H_
 #define SSM_H_

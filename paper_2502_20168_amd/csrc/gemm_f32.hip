@@ -137,6 +137,59 @@ size_t gemm_scan_desc_bytes(int64_t Bt, int64_t L, int64_t P)
     return (size_t)tiles * 64 * 2 * sizeof(unsigned long long);
 }
 
+// The output projection y = x Cc^T + D u has only M/128 * H/128 tiles of 128x128.  When they would
+// fill less than the chip but twice as many would, the product runs as two halves of K (256
+// workgroups of the efficient 128x128 tile instead of 64x128 tiles) into two slabs, and a streaming
+// kernel adds them and applies the store function.  SSM_SPLIT_OUT=0 switches this off (for comparison).
+bool gemm_out_split_shape(int64_t T, int64_t H, int64_t P)
+{
+    const int64_t tiles = ((T + 127) / 128) * ((H + 127) / 128);
+    return tiles < 200 && 2 * tiles >= 200 && P >= 64 && (2 * P) % 64 == 0;
+}
+
+bool gemm_out_split(int64_t T, int64_t H, int64_t P)
+{
+    const char *e = std::getenv("SSM_SPLIT_OUT");
+    if (e && e[0] == '0') return false;
+    return !use_f32_mfma() && gemm_out_split_shape(T, H, P);
+}
+
+// y = s0 + s1 + D (.) u (and GELU(y) next to it when gelu_y is given); n = T * H elements
+__global__ void __launch_bounds__(256) sum_halves_kernel(const float *__restrict__ s0, const float *__restrict__ s1,
+                                                         const float *__restrict__ D, const float *__restrict__ u,
+                                                         float *__restrict__ y, float *__restrict__ gelu_y, long n, int H,
+                                                         int vec)
+{
+    const long i = ((long)blockIdx.x * 256 + threadIdx.x) * (vec ? 4 : 1);
+    if (i >= n) return;
+    if (vec) {
+        const float4 a = *reinterpret_cast<const float4 *>(s0 + i), b = *reinterpret_cast<const float4 *>(s1 + i);
+        const float4 uu = *reinterpret_cast<const float4 *>(u + i);
+        const float4 d = *reinterpret_cast<const float4 *>(D + i % H);
+        const float4 r = make_float4(fmaf(d.x, uu.x, a.x + b.x), fmaf(d.y, uu.y, a.y + b.y), fmaf(d.z, uu.z, a.z + b.z),
+                                     fmaf(d.w, uu.w, a.w + b.w));
+        *reinterpret_cast<float4 *>(y + i) = r;
+        if (gelu_y)
+            *reinterpret_cast<float4 *>(gelu_y + i) = make_float4(gelu_value(r.x), gelu_value(r.y), gelu_value(r.z), gelu_value(r.w));
+    } else {
+        const float r = fmaf(D[i % H], u[i], s0[i] + s1[i]);
+        y[i] = r;
+        if (gelu_y) gelu_y[i] = gelu_value(r);
+    }
+}
+
+hipError_t launch_sum_halves(const float *s0, const float *s1, const float *D, const float *u, float *y, float *gelu_y,
+                             int64_t T, int64_t H, hipStream_t s)
+{
+    const long n = (long)T * H;
+    auto al16 = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+    const int vec = H % 4 == 0 && al16(s0) && al16(s1) && al16(D) && al16(u) && al16(y) && (!gelu_y || al16(gelu_y));
+    const long threads = vec ? n / 4 : n;
+    hipLaunchKernelGGL(sum_halves_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, s0, s1, D, u, y, gelu_y, n,
+                       (int)H, vec);
+    return hipGetLastError();
+}
+
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
 {
     if (a.M <= 0 || a.N <= 0 || a.K <= 0) return hipErrorInvalidValue;

@@ -16,7 +16,7 @@ inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 struct Layout {
     ScanPlan plan;
     int splitC, splitB, nslab;
-    size_t hdr, lam, Bri, Cc, xbuf, chi, ticket, desc, dCpart, dBpart, dApart, dDpart, fdesc, fdesc_bytes, total;
+    size_t hdr, lam, Bri, Cc, xbuf, chi, ticket, desc, dCpart, dBpart, dApart, dDpart, fdesc, fdesc_bytes, yhalves, total;
 };
 
 ssm_status check_dims(int64_t Bt, int64_t L, int64_t H, int64_t P)
@@ -55,7 +55,9 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
         const size_t per_tile = (size_t)(Bt * L / 128) * P;        // one dAbar row per 128-row tile
         if (per_tile > dA_elems) dA_elems = per_tile;
     }
+    o.yhalves = 0;
     if (!bwd) {
+        if (gemm_out_split_shape((int64_t)T, H, P)) { o.yhalves = off; off += up(2 * T * H * 4); }   // two K halves of y
         o.xbuf = off; off += up(T * P * 8);
     } else {
         o.chi = off; off += up(T * P * 8);
@@ -177,10 +179,19 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     GemmArgs g2{};
     g2.A = reinterpret_cast<const float *>(xs); g2.lda = 2 * P; g2.a_kcontig = 1;
     g2.B = Cc; g2.ldb = 2 * P; g2.b_kcontig = 1;
-    g2.C = y; g2.ldc = H; g2.diag = D; g2.E = u; g2.lde = H; g2.epilogue = 1;
-    if (gelu_y) { g2.epilogue = 6; g2.C2 = gelu_y; }       // the S5 block: GELU(y) for the gate, same store
-    g2.M = T; g2.N = (int)H; g2.K = (int)(2 * P); g2.splits = 1;
-    HIP_TRY(launch_gemm(g2, s));
+    g2.M = T; g2.N = (int)H; g2.K = (int)(2 * P);
+    if (lo.yhalves && gemm_out_split(T, H, P)) {
+        // too few 128x128 tiles for the chip: two K halves into two slabs, then one streaming pass
+        float *halves = reinterpret_cast<float *>(ws + lo.yhalves);
+        g2.C = halves; g2.ldc = H; g2.splits = 2;
+        HIP_TRY(launch_gemm(g2, s));
+        HIP_TRY(launch_sum_halves(halves, halves + (size_t)T * H, D, u, y, gelu_y, T, H, s));
+    } else {
+        g2.C = y; g2.ldc = H; g2.diag = D; g2.E = u; g2.lde = H; g2.epilogue = 1;
+        if (gelu_y) { g2.epilogue = 6; g2.C2 = gelu_y; }   // the S5 block: GELU(y) for the gate, same store
+        g2.splits = 1;
+        HIP_TRY(launch_gemm(g2, s));
+    }
     MARK();
     return SSM_OK;
 }

@@ -60,6 +60,13 @@ bool gemm_can_scan_reverse(int64_t Bt, int64_t L, int64_t P);
 // bytes of tagged words epilogues 7 and 8 need (zeroed before the launch)
 size_t gemm_scan_desc_bytes(int64_t Bt, int64_t L, int64_t P);
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t s);
+// the output projection as two K halves into two slabs plus a streaming sum: possible for this
+// shape (shape only), and taken on this call (shape and environment)
+bool gemm_out_split_shape(int64_t T, int64_t H, int64_t P);
+bool gemm_out_split(int64_t T, int64_t H, int64_t P);
+// y = s0 + s1 + D (.) u, and GELU(y) to gelu_y when it is not null
+hipError_t launch_sum_halves(const float *s0, const float *s1, const float *D, const float *u, float *y, float *gelu_y,
+                             int64_t T, int64_t H, hipStream_t s);
 // two independent problems in one launch (falls back to two launches for layouts without a
 // paired instantiation)
 hipError_t launch_gemm_pair(const GemmArgs &a, const GemmArgs &b, hipStream_t s);
