@@ -80,18 +80,18 @@ template <int NPL>
 __device__ __forceinline__ Split4 split_planes(float4 v) { return NPL == 3 ? split3(v) : split2(v); }
 
 // Stages one R x BK fp32 operand tile: global -> registers (fp32) -> split -> NPL LDS planes.
-// k-contiguous source: a thread handles units of 1 row x 4 k.  Row-contiguous source: units of
-// 4 rows x KU k (KU float4 loads, transposed in registers), KU = 4, 2 or 1; neighbouring lanes take
-// neighbouring k blocks of the same rows, so that their LDS writes fall into distinct banks while
-// the lanes that share a k row still read one contiguous 128-byte line.
+// A thread handles float4 units along the contiguous index of the source and writes the four
+// bf16 values of every plane with one 8-byte store, whatever the layout:
+//   k-contiguous source (KC):  unit = 1 row x 4 k;   planes are [row][k], row stride BK+8 halves;
+//   row-contiguous source:     unit = 1 k x 4 rows;  planes are [k][row], k stride R+16 halves --
+//       the same orientation as in memory, so global loads are whole 512-byte lines and nothing is
+//       transposed here; the consumers fetch their fragments with the transposing LDS read.
 template <int R, int BK, bool KC, int NT, int NPL>
 struct SplitLoader {
     static constexpr int NV = R * BK / 4 / NT;
     static_assert(NV >= 1 && NV * NT * 4 == R * BK, "tile must be a multiple of the workgroup's float4 loads");
-    static constexpr int KU = (NV % 4 == 0) ? 4 : (NV % 2 == 0) ? 2 : 1;
-    static_assert(KC || NV % KU == 0, "row-contiguous operands are staged in 4 x KU blocks");
-    static constexpr int S = BK + 8;              // plane row stride in halves
-    static constexpr int PLANE = R * S;           // halves per plane
+    static constexpr int S = KC ? BK + 8 : R + 16;        // stride of the slow index in halves
+    static constexpr int PLANE = KC ? R * S : BK * S;     // halves per plane
     float4 r[NV];
 
     // k-contiguous source: row handled by the g-th group of BK/4 lanes.  With BK = 32 a group
@@ -107,10 +107,10 @@ struct SplitLoader {
     __device__ __forceinline__ void load(const float *__restrict__ X, long ld, int row0, int rows, int k0,
                                          int kend, int tid)
     {
-        if (KC) {
 #pragma unroll
-            for (int i = 0; i < NV; ++i) {
-                const int idx = tid + i * NT;
+        for (int i = 0; i < NV; ++i) {
+            const int idx = tid + i * NT;
+            if (KC) {
                 const int row = kc_row(idx / (BK / 4)), kq = idx % (BK / 4);
                 const long gr = row0 + row;
                 const int k = k0 + 4 * kq;
@@ -122,24 +122,16 @@ struct SplitLoader {
                     for (int j = 0; j < 4; ++j) t[j] = (gr < rows && k + j < kend) ? X[gr * ld + k + j] : 0.f;
                     r[i] = make_float4(t[0], t[1], t[2], t[3]);
                 }
-            }
-        } else {
+            } else {
+                const int kk = idx / (R / 4), rq = idx % (R / 4);
+                const long k = k0 + kk, gr = row0 + 4 * rq;
+                if (FAST) {
+                    r[i] = *reinterpret_cast<const float4 *>(X + k * ld + gr);
+                } else {
+                    float t[4];
 #pragma unroll
-            for (int u = 0; u < NV / KU; ++u) {
-                const int idx = tid + u * NT;
-                const int kq = idx % (BK / KU), rq = idx / (BK / KU);
-                const long gr = row0 + 4 * rq;
-#pragma unroll
-                for (int j = 0; j < KU; ++j) {
-                    const long k = k0 + KU * kq + j;
-                    if (FAST) {
-                        r[KU * u + j] = *reinterpret_cast<const float4 *>(X + k * ld + gr);
-                    } else {
-                        float t[4];
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) t[q] = (gr + q < rows && k < kend) ? X[k * ld + gr + q] : 0.f;
-                        r[KU * u + j] = make_float4(t[0], t[1], t[2], t[3]);
-                    }
+                    for (int q = 0; q < 4; ++q) t[q] = (gr + q < rows && k < kend) ? X[k * ld + gr + q] : 0.f;
+                    r[i] = make_float4(t[0], t[1], t[2], t[3]);
                 }
             }
         }
@@ -147,46 +139,36 @@ struct SplitLoader {
 
     __device__ __forceinline__ void store(__bf16 *lds, int tid) const
     {
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int idx = tid + i * NT;
+            const int off = KC ? kc_row(idx / (BK / 4)) * S + 4 * (idx % (BK / 4))
+                               : (idx / (R / 4)) * S + 4 * (idx % (R / 4));
+            const Split4 sp = split_planes<NPL>(r[i]);
+#pragma unroll
+            for (int s = 0; s < NPL; ++s) *reinterpret_cast<bf16x4 *>(lds + s * PLANE + off) = sp.p[s];
+        }
+    }
+
+    // Fragment of a 32-row block for one 16-wide k step: lane (li = l % 32, hh = l / 32) gets the
+    // 8 values row0 + li, k = kbase + 8 hh .. 8 hh + 7 of a plane.
+    //   KC: one 16-byte read.
+    //   row-contiguous: two transposing 8-byte reads.  ds_read_b64_tr_b16 works on groups of 16
+    //   lanes: lane i of a group receives element i % 4 of the 8-byte chunks addressed by lanes
+    //   i / 4, i / 4 + 4, i / 4 + 8, i / 4 + 12 of the group.  With lane sl of a group pointing at
+    //   [k0 + sl / 4][m0 + 4 (sl % 4)], lane i receives rows m0 + i at k0 .. k0 + 3.
+    static __device__ __forceinline__ bf16x8 fragment(const __bf16 *plane, int row0, int kbase, int l)
+    {
         if (KC) {
-#pragma unroll
-            for (int i = 0; i < NV; ++i) {
-                const int idx = tid + i * NT;
-                const int row = kc_row(idx / (BK / 4)), kq = idx % (BK / 4);
-                const Split4 sp = split_planes<NPL>(r[i]);
-#pragma unroll
-                for (int s = 0; s < NPL; ++s)
-                    *reinterpret_cast<bf16x4 *>(lds + s * PLANE + row * S + 4 * kq) = sp.p[s];
-            }
+            return *reinterpret_cast<const bf16x8 *>(plane + (row0 + (l & 31)) * S + kbase + 8 * (l >> 5));
         } else {
-#pragma unroll
-            for (int u = 0; u < NV / KU; ++u) {
-                const int idx = tid + u * NT;
-                const int kq = idx % (BK / KU), rq = idx / (BK / KU);
-                // r[KU*u + j] holds rows 4rq..4rq+3 at k = KU*kq + j: transpose the block in registers
-                float blk[4][4];
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float4 c = (j < KU) ? r[KU * u + (j < KU ? j : 0)] : make_float4(0.f, 0.f, 0.f, 0.f);
-                    blk[0][j] = c.x; blk[1][j] = c.y; blk[2][j] = c.z; blk[3][j] = c.w;
-                }
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const Split4 sp = split_planes<NPL>(make_float4(blk[q][0], blk[q][1], blk[q][2], blk[q][3]));
-#pragma unroll
-                    for (int s = 0; s < NPL; ++s) {
-                        __bf16 *dst = lds + s * PLANE + (4 * rq + q) * S + KU * kq;
-                        if (KU == 4) {
-                            *reinterpret_cast<bf16x4 *>(dst) = sp.p[s];
-                        } else if (KU == 2) {
-                            bf16x2 two;
-                            two[0] = sp.p[s][0]; two[1] = sp.p[s][1];
-                            *reinterpret_cast<bf16x2 *>(dst) = two;
-                        } else {
-                            *dst = sp.p[s][0];
-                        }
-                    }
-                }
-            }
+            typedef short v4s __attribute__((ext_vector_type(4)));
+            const int sl = l & 15, grp = l >> 4;
+            const __bf16 *p0 = plane + (kbase + 8 * (grp >> 1) + (sl >> 2)) * S + row0 + 16 * (grp & 1) + 4 * (sl & 3);
+            union { v4s h[2]; bf16x8 v; } u;
+            u.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4s __attribute__((address_space(3))) *)(p0));
+            u.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((v4s __attribute__((address_space(3))) *)(p0 + 4 * S));
+            return u.v;
         }
     }
 };
@@ -444,7 +426,6 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
     using LA = SplitLoader<BM, BK, AKC, PT, NPL>;
     using LB = SplitLoader<BN, BK, BKC, PT, NPL>;
     static_assert(NPL == 2 || NPL == 3, "two or three bf16 planes per operand");
-    constexpr int S = BK + 8;
     constexpr int STAGE_A = NPL * LA::PLANE, STAGE_B = NPL * LB::PLANE, STAGE = STAGE_A + STAGE_B;
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int MI = WM / 32, NI = WN / 32;
@@ -533,18 +514,16 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
     bf16x8 fa[2][MI][NPL], fb[2][NI][NPL];
     auto fetch_frags = [&](int set, int kt, int ks) {
         const __bf16 *st = smem + (kt % NS) * STAGE;
-        const __bf16 *as = st + (wm * WM + li) * S + 8 * hh + ks * 16;
-        const __bf16 *bs = st + STAGE_A + (wn * WN + li) * S + 8 * hh + ks * 16;
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int s = 0; s < NPL; ++s)
-                fa[set][i][s] = *reinterpret_cast<const bf16x8 *>(as + s * LA::PLANE + i * 32 * S);
+                fa[set][i][s] = LA::fragment(st + s * LA::PLANE, wm * WM + i * 32, ks * 16, l);
 #pragma unroll
         for (int j = 0; j < NI; ++j)
 #pragma unroll
             for (int s = 0; s < NPL; ++s)
-                fb[set][j][s] = *reinterpret_cast<const bf16x8 *>(bs + s * LB::PLANE + j * 32 * S);
+                fb[set][j][s] = LB::fragment(st + STAGE_A + s * LB::PLANE, wn * WN + j * 32, ks * 16, l);
     };
     // the six products of one accumulator keep their order (smallest first); the MI*NI
     // accumulators alternate so that consecutive matrix instructions are independent
@@ -567,7 +546,7 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
     // issue order of one k step: a fragment read in the shadow of every second matrix
     // instruction (a burst of reads would keep the wavefront from issuing matrix work)
     auto interleave = [&]() {
-        constexpr int NREAD = NPL * (MI + NI), NMFMA = (NPL == 3 ? 6 : 3) * MI * NI;
+        constexpr int NREAD = NPL * (MI * (AKC ? 1 : 2) + NI * (BKC ? 1 : 2)), NMFMA = (NPL == 3 ? 6 : 3) * MI * NI;
 #pragma unroll
         for (int q = 0; q < NREAD; ++q) {
             __builtin_amdgcn_sched_group_barrier(0x008, NMFMA / NREAD > 0 ? NMFMA / NREAD : 1, 0);
@@ -655,6 +634,14 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
 
 // Operand layouts and epilogue of one problem, packed into one template argument.
 constexpr int gemm_layout(bool akc, bool bkc, int epi) { return (akc ? 1 : 0) | (bkc ? 2 : 0) | (epi << 2); }
+
+// Halves of LDS one stage of a problem needs (the planes of both operands; see SplitLoader).
+constexpr size_t gemm_stage_halves(int BM, int BN, int BK, int NPL, int lay)
+{
+    const size_t pa = (lay & 1) ? (size_t)BM * (BK + 8) : (size_t)BK * (BM + 16);
+    const size_t pb = (lay & 2) ? (size_t)BN * (BK + 8) : (size_t)BK * (BN + 16);
+    return (size_t)NPL * (pa + pb);
+}
 
 // Work item (tile, split) of the workgroup in slot q of XCD x.  Workgroup ids are dealt
 // round-robin to the 8 XCDs (id % 8), each with its own L2:
@@ -767,7 +754,8 @@ hipError_t launch_gemm_bf16x3_ws_variant(const GemmArgs &a, hipStream_t s, const
     GemmDev g1 = b ? make_gemm_dev<BM, BN, BK>(*b) : g0;
     if ((LAY1 >= 0) != (b != nullptr)) return hipErrorInvalidValue;
     g1.slot0 = g0.nx;
-    constexpr size_t stage_bytes = (size_t)NS * NPL * (BM + BN) * (BK + 8) * sizeof(__bf16);
+    constexpr size_t stage0 = gemm_stage_halves(BM, BN, BK, NPL, LAY0), stage1 = LAY1 >= 0 ? gemm_stage_halves(BM, BN, BK, NPL, LAY1) : 0;
+    constexpr size_t stage_bytes = (size_t)NS * (stage0 > stage1 ? stage0 : stage1) * sizeof(__bf16);
     constexpr bool scans = ((LAY0 >> 2) >= 7) || (LAY1 >= 0 && (LAY1 >> 2) >= 7);
     constexpr size_t smem = (scans && SCAN_LDS_BYTES > stage_bytes) ? SCAN_LDS_BYTES : stage_bytes;
     static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS of a gfx950 CU");
