@@ -171,8 +171,10 @@ def main():
          {"role": "output projection + D u", "kernel": kern(out_tile, 7, -1), "gemms": 1, "ms": fs[3]}),
         {"role": "C^H dy" + (" + reverse scan in the tile" if rev_fused else "") + " and the dC slabs, one launch",
          "kernel": kern("128,128,32", 33 if rev_fused else 1, 0), "gemms": 2, "ms": bs[1]},
-        {"role": "Re(Bbar^H chi) + D dy and the dBbar slabs, one launch",
-         "kernel": kern("128,128,32", 5, 0), "gemms": 2, "ms": bs[3]},
+        ({"role": "Re(Bbar^H chi) as two K halves and the dBbar slabs in one launch, then the sum of the halves + D dy",
+          "kernel": kern("128,128,32", 1, 0) + " + sum_halves_kernel", "gemms": 2, "ms": bs[3]} if out_split else
+         {"role": "Re(Bbar^H chi) + D dy and the dBbar slabs, one launch",
+          "kernel": kern("128,128,32", 5, 0), "gemms": 2, "ms": bs[3]}),
     ]
     for l in launches:
         l["fp32_flops"] = l["gemms"] * gemm_flops
@@ -190,7 +192,7 @@ def main():
     else:
         products = 3 if npl == 2 else BF16_PRODUCTS
         ach = products * dom_fp32_tflops
-        is_du = dom["kernel"] == kern("128,128,32", 5, 0) and npl == 3 and args.config == 2
+        is_du = dom["kernel"].startswith(kern("128,128,32", 1, 0)) and out_split and npl == 3 and args.config == 2
         roofline = {"kernel": "%s (%s)" % (dom["kernel"], dom["role"]),
                     "bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(ach / PEAK_BF16_MFMA_TFLOPS, 4),

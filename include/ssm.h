@@ -39,9 +39,9 @@
  *     and C^H dy scan their own output tiles (no scan kernel, no round trip of Bbar u and C^H dy
  *     through memory); =1 does so only in the forward pass, =0 keeps projections and scans as
  *     separate kernels.  All three settings meet the same tolerances; results differ by rounding;
- *     SSM_SPLIT_OUT=0 keeps the output projection in one kernel where by default it runs as two
- *     halves of the state dimension plus a streaming sum (shapes with 100-199 tiles of 128 x 128
- *     outputs, e.g. 4096 tokens and H = 512).
+ *     SSM_SPLIT_OUT=0 keeps the output projection and its adjoint for du in one kernel each where
+ *     by default they run as two halves of the state dimension plus a streaming sum (shapes with
+ *     100-199 tiles of 128 x 128 outputs, e.g. 4096 tokens and H = 512).
  */
 #ifndef SSM_H_
 #define SSM_H_

@@ -694,17 +694,21 @@ __device__ __forceinline__ void gemm_bf16x3_ws_problem(const GemmDev &g, __bf16 
 
 // One launch carries one problem (LAY1 < 0) or two independent ones (used for the gradient
 // pass, where pairs of products have the same inputs ready at the same time and one of them
-// alone would leave compute units idle).  The slots of the first problem come first in every XCD.
+// alone would leave compute units idle).  The slots of the first problem come first in every XCD
+// unless the launch asks for the second one first (the longer work items should start first).
 template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL, int LAY0, int LAY1>
 __global__ void __launch_bounds__(64 * (WGM * WGN + NP)) gemm_bf16x3_ws_kernel(GemmDev g0, GemmDev g1)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);
     const int x = blockIdx.x % 8, q = blockIdx.x / 8;
-    if (LAY1 < 0 || q < g1.slot0)
-        gemm_bf16x3_ws_problem<BM, BN, BK, WGM, WGN, NP, NS, NPL, LAY0>(g0, smem, x, q);
+    // slots of an XCD: the first problem's, then the second's -- or the other way round when asked
+    const bool first = LAY1 < 0 || (g1.second_first ? q >= g1.nx : q < g1.slot0);
+    if (first)
+        gemm_bf16x3_ws_problem<BM, BN, BK, WGM, WGN, NP, NS, NPL, LAY0>(g0, smem, x, g1.second_first && LAY1 >= 0 ? q - g1.nx : q);
     else
-        gemm_bf16x3_ws_problem<BM, BN, BK, WGM, WGN, NP, NS, NPL, (LAY1 < 0 ? LAY0 : LAY1)>(g1, smem, x, q - g1.slot0);
+        gemm_bf16x3_ws_problem<BM, BN, BK, WGM, WGN, NP, NS, NPL, (LAY1 < 0 ? LAY0 : LAY1)>(g1, smem, x,
+                                                                                             g1.second_first ? q : q - g1.slot0);
 }
 
 template <int BM, int BN, int BK>
@@ -724,7 +728,7 @@ inline GemmDev make_gemm_dev(const GemmArgs &a)
     const long ntiles = (long)g.ntm * g.ntn;
     g.per_xcd = (int)((ntiles + 7) / 8);
     g.splits = splits;
-    g.slot0 = 0;
+    g.slot0 = 0; g.second_first = 0;
     if (splits == 1) { g.mode = 0; g.mpar = 0; g.nx = g.per_xcd; }
     else if (splits % 8 == 0) { g.mode = 1; g.mpar = splits / 8; g.nx = (int)(ntiles * g.mpar); }
     else if (8 % splits == 0) { g.mode = 2; g.mpar = 8 / splits; g.nx = (int)((ntiles + g.mpar - 1) / g.mpar); }
@@ -748,12 +752,14 @@ inline GemmDev make_gemm_dev(const GemmArgs &a)
 
 // b == nullptr: one problem (LAY1 is ignored and must be -1).
 template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL, int LAY0, int LAY1 = -1>
-hipError_t launch_gemm_bf16x3_ws_variant(const GemmArgs &a, hipStream_t s, const GemmArgs *b = nullptr)
+hipError_t launch_gemm_bf16x3_ws_variant(const GemmArgs &a, hipStream_t s, const GemmArgs *b = nullptr,
+                                        bool second_first = false)
 {
     GemmDev g0 = make_gemm_dev<BM, BN, BK>(a);
     GemmDev g1 = b ? make_gemm_dev<BM, BN, BK>(*b) : g0;
     if ((LAY1 >= 0) != (b != nullptr)) return hipErrorInvalidValue;
     g1.slot0 = g0.nx;
+    g1.second_first = (b && second_first) ? 1 : 0;
     constexpr size_t stage0 = gemm_stage_halves(BM, BN, BK, NPL, LAY0), stage1 = LAY1 >= 0 ? gemm_stage_halves(BM, BN, BK, NPL, LAY1) : 0;
     constexpr size_t stage_bytes = (size_t)NS * (stage0 > stage1 ? stage0 : stage1) * sizeof(__bf16);
     constexpr bool scans = ((LAY0 >> 2) >= 7) || (LAY1 >= 0 && (LAY1 >> 2) >= 7);

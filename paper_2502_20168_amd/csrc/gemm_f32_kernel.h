@@ -31,7 +31,7 @@ struct GemmDev {
     int ntm, ntn, per_xcd;
     // placement of the (tile, split) work items on the 8 XCDs (bf16x3 kernel): slots per XCD,
     // mapping mode and its parameter, first slot of this problem in a shared launch
-    int splits, nx, mode, mpar, slot0;
+    int splits, nx, mode, mpar, slot0, second_first;
     // epilogue 7 (scan over the tile's rows): tiles per sequence, column tiles per unit, column
     // groups per sequence, number of units (a unit = the chains of one sequence and column group)
     ScanEpilogue scan;

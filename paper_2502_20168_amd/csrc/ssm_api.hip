@@ -65,6 +65,7 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
         o.dBpart = off; off += up((size_t)o.splitB * 2 * P * H * 4);
         o.dApart = off; off += up(dA_elems * 8);
         o.dDpart = off; off += up((size_t)o.nslab * H * 4);
+        if (gemm_out_split_shape((int64_t)T, H, P)) { o.yhalves = off; off += up(2 * T * H * 4); }   // two K halves of du
     }
     o.total = off;
     return SSM_OK;
@@ -288,15 +289,25 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     GemmArgs g5{};
     g5.A = reinterpret_cast<const float *>(chi); g5.lda = 2 * P; g5.a_kcontig = 1;
     g5.B = Bri; g5.ldb = H; g5.b_kcontig = 0;
-    g5.C = du; g5.ldc = H; g5.diag = D; g5.E = dy; g5.lde = H; g5.epilogue = 1;
-    g5.M = T; g5.N = (int)H; g5.K = (int)(2 * P); g5.splits = 1;
+    g5.M = T; g5.N = (int)H; g5.K = (int)(2 * P);
     // dBbar slabs: [2p+c, h] = sum_t chi[t, 2p+c] * u[t,h]   (same launch)
     GemmArgs g6{};
     g6.A = reinterpret_cast<const float *>(chi); g6.lda = 2 * P; g6.a_kcontig = 0;
     g6.B = u; g6.ldb = H; g6.b_kcontig = 0;
     g6.C = dBpart; g6.ldc = H;
     g6.M = (int)(2 * P); g6.N = (int)H; g6.K = T; g6.splits = lo.splitB;
-    HIP_TRY(launch_gemm_pair(g5, g6, s));
+    if (lo.yhalves && gemm_out_split(T, H, P)) {
+        // du has too few 128x128 tiles for half a chip's worth of time: it runs as two K halves (twice
+        // the workgroups, half as long) next to the long work items of the dBbar slabs, which start first;
+        // a streaming pass adds the halves and D dy
+        float *halves = reinterpret_cast<float *>(ws + lo.yhalves);
+        g5.C = halves; g5.ldc = H; g5.splits = 2;
+        HIP_TRY(launch_gemm_pair(g5, g6, s, true));
+        HIP_TRY(launch_sum_halves(halves, halves + (size_t)T * H, D, dy, du, nullptr, T, H, s));
+    } else {
+        g5.C = du; g5.ldc = H; g5.diag = D; g5.E = dy; g5.lde = H; g5.epilogue = 1; g5.splits = 1;
+        HIP_TRY(launch_gemm_pair(g5, g6, s));
+    }
     MARK();
 
     EpilogueArgs ea{};

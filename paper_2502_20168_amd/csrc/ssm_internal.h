@@ -69,7 +69,7 @@ hipError_t launch_sum_halves(const float *s0, const float *s1, const float *D, c
                              int64_t T, int64_t H, hipStream_t s);
 // two independent problems in one launch (falls back to two launches for layouts without a
 // paired instantiation)
-hipError_t launch_gemm_pair(const GemmArgs &a, const GemmArgs &b, hipStream_t s);
+hipError_t launch_gemm_pair(const GemmArgs &a, const GemmArgs &b, hipStream_t s, bool second_first = false);
 // number of K splits for a reduction over K rows with an M x N result that shares its launch
 // with a product of partner_tiles 128x128 tiles
 int gemm_pick_splits(int64_t M, int64_t N, int64_t K, int64_t partner_tiles);
