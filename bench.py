@@ -166,13 +166,13 @@ def main():
     launches = [
         {"role": "input projection" + (" + forward scan in the tile" if fwd_fused else ""),
          "kernel": kern(in_tile, 31 if fwd_fused else 3, -1), "gemms": 1, "ms": fs[1]},
-        ({"role": "output projection as two K halves, then the sum of the halves + D u (two kernels)",
-          "kernel": kern("128,128,32", 3, -1) + " + sum_halves_kernel", "gemms": 1, "ms": fs[3]} if out_split else
+        ({"role": "output projection as two K halves into two slabs (a streaming kernel adds them and D u)",
+          "kernel": kern("128,128,32", 3, -1), "gemms": 1, "ms": fs[3]} if out_split else
          {"role": "output projection + D u", "kernel": kern(out_tile, 7, -1), "gemms": 1, "ms": fs[3]}),
         {"role": "C^H dy" + (" + reverse scan in the tile" if rev_fused else "") + " and the dC slabs, one launch",
          "kernel": kern("128,128,32", 33 if rev_fused else 1, 0), "gemms": 2, "ms": bs[1]},
-        ({"role": "Re(Bbar^H chi) as two K halves and the dBbar slabs in one launch, then the sum of the halves + D dy",
-          "kernel": kern("128,128,32", 1, 0) + " + sum_halves_kernel", "gemms": 2, "ms": bs[3]} if out_split else
+        ({"role": "Re(Bbar^H chi) as two K halves and the dBbar slabs, one launch (a streaming kernel adds the halves and D dy)",
+          "kernel": kern("128,128,32", 1, 0), "gemms": 2, "ms": bs[3]} if out_split else
          {"role": "Re(Bbar^H chi) + D dy and the dBbar slabs, one launch",
           "kernel": kern("128,128,32", 5, 0), "gemms": 2, "ms": bs[3]}),
     ]

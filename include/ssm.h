@@ -69,8 +69,8 @@ typedef enum {
 #define SSM_MAX_ELEMS (1LL << 40)    /* largest Bt * L * max(H, 2P)                    */
 
 /* Number of per-stage timings written by the *_profiled calls (see below). */
-#define SSM_FWD_STAGES 4
-#define SSM_BWD_STAGES 5
+#define SSM_FWD_STAGES 5
+#define SSM_BWD_STAGES 6
 
 /* Static description of an error code. Never NULL. */
 const char *ssm_strerror(int status);
@@ -246,12 +246,14 @@ ssm_status ssm_mfma_probe(int64_t workgroups, int64_t iters, float *out, void *s
 /* Measurement aids: the same code path as ssm_scan_fwd / ssm_scan_bwd, with a HIP event recorded
  * on `stream` around every kernel.  They wait for the stream before returning and write the
  * milliseconds of each stage to the HOST array stage_ms:
- *   forward : [0] discretise+pack, [1] input projection, [2] scan, [3] output projection
+ *   forward : [0] discretise+pack, [1] input projection, [2] scan, [3] output projection,
+ *             [4] sum of the two halves of the output projection
  *   backward: [0] discretise+pack and dD partials, [1] gx = C^H dy with the dC partials (one
  *             launch), [2] reverse scan, [3] du with the dBbar partials (one launch),
- *             [4] parameter epilogue
- * Where a projection scans its own output tiles (see SSM_FUSED_SCAN above) stage [2] holds no kernel
- * and reads as the few microseconds between two events; the scan's time is inside stage [1].     */
+ *             [4] sum of the two halves of du, [5] parameter epilogue
+ * A stage that holds no kernel on this call (a scan that runs inside its projection, see
+ * SSM_FUSED_SCAN above; a product that is not run as two halves, see SSM_SPLIT_OUT) reads as the
+ * few microseconds between two events.                                                          */
 ssm_status ssm_scan_fwd_profiled(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C,
                                  const float *D, const float *log_delta, const float *u,
                                  const uint8_t *is_first, const ssm_c64 *x0,

@@ -20,10 +20,11 @@ SSM_ERR_WORKSPACE = 2
 SSM_ERR_UNSUPPORTED = 3
 SSM_ERR_HIP = 4
 SSM_ERR_SCAN_TIMEOUT = 5
-SSM_FWD_STAGES = 4
-SSM_BWD_STAGES = 5
-FWD_STAGE_NAMES = ("discretize_pack", "project_in", "scan", "project_out")
-BWD_STAGE_NAMES = ("discretize_pack_dD", "gx_dC_partials", "reverse_scan", "du_dBbar_partials", "param_epilogue")
+SSM_FWD_STAGES = 5
+SSM_BWD_STAGES = 6
+FWD_STAGE_NAMES = ("discretize_pack", "project_in", "scan", "project_out", "sum_out_halves")
+BWD_STAGE_NAMES = ("discretize_pack_dD", "gx_dC_partials", "reverse_scan", "du_dBbar_partials", "sum_du_halves",
+                   "param_epilogue")
 
 EXPORTS = ("ssm_strerror", "ssm_version", "ssm_workspace_bytes", "ssm_discretize", "ssm_scan_fwd",
            "ssm_scan_bwd", "ssm_scan_states", "ssm_scan_states_reverse", "ssm_scan_fwd_profiled",

@@ -647,14 +647,15 @@ constexpr size_t gemm_stage_halves(int BM, int BN, int BK, int NPL, int lay)
 // round-robin to the 8 XCDs (id % 8), each with its own L2:
 //   mode 0 (no K splits): XCD x owns the contiguous band of tiles [x*nx, (x+1)*nx), so it re-reads
 //          only its band of A from its own L2;
-//   modes 1-3 (K splits): every XCD owns whole K slabs (or a contiguous run of tiles inside
-//          one), so each operand element is fetched from memory once instead of once per tile band;
+//   modes 1-3 (K splits): every XCD owns whole K slabs (or, with fewer than 8 splits, one
+//          contiguous band of the tiles of one slab), so each operand element is fetched from
+//          memory once instead of once per tile band;
 //   mode 5: see below.
 __device__ __forceinline__ void gemm_place(const GemmDev &g, int x, int q, int &z, int &tile)
 {
     if (g.mode == 0) { z = 0; tile = x * g.nx + q; }
     else if (g.mode == 1) { z = x + 8 * (q % g.mpar); tile = q / g.mpar; }        // splits = 8 * mpar
-    else if (g.mode == 2) { z = x % g.splits; tile = q * g.mpar + x / g.splits; } // 8 = splits * mpar
+    else if (g.mode == 2) { z = x % g.splits; tile = (x / g.splits) * g.nx + q; } // 8 = splits * mpar: bands of nx tiles
     else if (g.mode == 3) { const int item = x * g.nx + q; z = item / (g.ntm * g.ntn); tile = item % (g.ntm * g.ntn); }
     else {
         // mode 5 (scan epilogue): a unit = the tiles of one sequence and column group, time-major;

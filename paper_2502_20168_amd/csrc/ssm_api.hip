@@ -186,12 +186,14 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
         float *halves = reinterpret_cast<float *>(ws + lo.yhalves);
         g2.C = halves; g2.ldc = H; g2.splits = 2;
         HIP_TRY(launch_gemm(g2, s));
+        MARK();
         HIP_TRY(launch_sum_halves(halves, halves + (size_t)T * H, D, u, y, gelu_y, T, H, s));
     } else {
         g2.C = y; g2.ldc = H; g2.diag = D; g2.E = u; g2.lde = H; g2.epilogue = 1;
         if (gelu_y) { g2.epilogue = 6; g2.C2 = gelu_y; }   // the S5 block: GELU(y) for the gate, same store
         g2.splits = 1;
         HIP_TRY(launch_gemm(g2, s));
+        MARK();
     }
     MARK();
     return SSM_OK;
@@ -303,10 +305,12 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
         float *halves = reinterpret_cast<float *>(ws + lo.yhalves);
         g5.C = halves; g5.ldc = H; g5.splits = 2;
         HIP_TRY(launch_gemm_pair(g5, g6, s, true));
+        MARK();
         HIP_TRY(launch_sum_halves(halves, halves + (size_t)T * H, D, dy, du, nullptr, T, H, s));
     } else {
         g5.C = du; g5.ldc = H; g5.diag = D; g5.E = dy; g5.lde = H; g5.epilogue = 1; g5.splits = 1;
         HIP_TRY(launch_gemm_pair(g5, g6, s));
+        MARK();
     }
     MARK();
 
