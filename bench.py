@@ -31,13 +31,19 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix
 PEAK_BF16_MFMA_TFLOPS = 2500.0 # MI355X dense bf16 matrix
 BF16_PRODUCTS = 6              # bf16 MFMA products the GEMM issues per fp32 multiply-add
-# HBM bytes per launch of the dominant kernel at config 2 (the launch that computes Re(Bbar^H chi) + D dy
-# and the dBbar slabs) from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same counters
-# read for a copy-like kernel of known size (profiles/gemm_bf16x3_scan_cfg2_fwd_bwd.md): 78.2 MiB read +
-# 16.2 MiB written; algorithmic 50 MiB (chi 16 + Bbar 2 + dy 8 for du; chi 16 + u 8 for the slabs) + 16 MiB
-# (du 8 + the dBbar slabs 8)
-TRAFFIC_DU_DBBAR = {"read_bytes": 82.0e6, "write_bytes": 17.0e6, "algorithmic_read_bytes": 52.4e6,
-                    "algorithmic_write_bytes": 16.8e6, "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, see profiles/"}
+# HBM bytes per launch of the two largest launches at config 2 from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+# scaled by what the same counters read for a copy-like kernel of known size
+# (profiles/gemm_bf16x3_scan_cfg2_fwd_bwd.md), next to the algorithmic bytes:
+#   C^H dy with the reverse scan in its tiles + the dC slabs: 64.3 MiB read (dy 8 + C 2 per XCD + x 16 for the
+#     scan; dy 8 + x 16 for the slabs), 32.9 MiB written (chi 16 + eight dC slabs 16)
+#   Re(Bbar^H chi) as two K halves + the dBbar slabs: 60.9 MiB read (chi 16 + Bbar 2 per XCD; chi 16 + u 8),
+#     24.3 MiB written (two du slabs 16 + four dBbar slabs 8)
+TRAFFIC = {
+    "33,0": {"read_bytes": 67.4e6, "write_bytes": 34.5e6, "algorithmic_read_bytes": 52.4e6,
+             "algorithmic_write_bytes": 33.6e6, "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, see profiles/"},
+    "1,0": {"read_bytes": 63.9e6, "write_bytes": 25.5e6, "algorithmic_read_bytes": 44.0e6,
+            "algorithmic_write_bytes": 25.2e6, "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, see profiles/"},
+}
 
 
 def main():
@@ -192,12 +198,14 @@ def main():
     else:
         products = 3 if npl == 2 else BF16_PRODUCTS
         ach = products * dom_fp32_tflops
-        is_du = dom["kernel"].startswith(kern("128,128,32", 1, 0)) and out_split and npl == 3 and args.config == 2
+        lay = dom["kernel"].rstrip(">").split(",")[-2] + "," + dom["kernel"].rstrip(">").split(",")[-1]
+        known = TRAFFIC.get(lay) if (npl == 3 and args.config == 2 and fused_env == "" and out_split and
+                                     dom["kernel"].startswith("gemm_bf16x3_ws_kernel<128,128,32")) else None
         roofline = {"kernel": "%s (%s)" % (dom["kernel"], dom["role"]),
                     "bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(ach / PEAK_BF16_MFMA_TFLOPS, 4),
-                    "traffic": (TRAFFIC_DU_DBBAR["read_bytes"] + TRAFFIC_DU_DBBAR["write_bytes"]) if is_du else None,
-                    "traffic_detail": TRAFFIC_DU_DBBAR if is_du else None,
+                    "traffic": (known["read_bytes"] + known["write_bytes"]) if known else None,
+                    "traffic_detail": known,
                     "note": "achieved counts the %d bf16 MFMA products per fp32 multiply-add that the kernel "
                             "executes by design; fp32-equivalent rate and its ratio to the fp32 matrix peak below" % products,
                     "fp32_equivalent_tflops": round(dom_fp32_tflops, 2),
