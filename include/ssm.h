@@ -250,7 +250,8 @@ ssm_status ssm_mfma_probe(int64_t workgroups, int64_t iters, float *out, void *s
  *             [4] sum of the two halves of the output projection
  *   backward: [0] discretise+pack and dD partials, [1] gx = C^H dy with the dC partials (one
  *             launch), [2] reverse scan, [3] du with the dBbar partials (one launch),
- *             [4] sum of the two halves of du, [5] parameter epilogue
+ *             [4] empty (the sum of the two halves of du shares the next launch),
+ *             [5] parameter epilogue
  * A stage that holds no kernel on this call (a scan that runs inside its projection, see
  * SSM_FUSED_SCAN above; a product that is not run as two halves, see SSM_SPLIT_OUT) reads as the
  * few microseconds between two events.                                                          */

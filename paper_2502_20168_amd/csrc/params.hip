@@ -216,10 +216,39 @@ __device__ __forceinline__ void block_sum2(double *red_r, double *red_i, double 
     r = red_r[0]; i = red_i[0];
 }
 
+// 2048 elements per workgroup (eight per thread, as two float4 where alignment allows)
+__device__ __forceinline__ void sum_halves_block(const SumHalvesArgs &a, int blk, int tid)
+{
+    const long base = (long)blk * 2048;
+    if (a.vec) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const long i = base + 4L * (tid + 256 * j);
+            if (i < a.n) {
+                const float4 x = *reinterpret_cast<const float4 *>(a.s0 + i), y = *reinterpret_cast<const float4 *>(a.s1 + i);
+                const float4 e = *reinterpret_cast<const float4 *>(a.e + i);
+                const float4 d = *reinterpret_cast<const float4 *>(a.D + i % a.H);
+                *reinterpret_cast<float4 *>(a.out + i) = make_float4(fmaf(d.x, e.x, x.x + y.x), fmaf(d.y, e.y, x.y + y.y),
+                                                                     fmaf(d.z, e.z, x.z + y.z), fmaf(d.w, e.w, x.w + y.w));
+            }
+        }
+    } else {
+        for (int j = 0; j < 8; ++j) {
+            const long i = base + tid + 256L * j;
+            if (i < a.n) a.out[i] = fmaf(a.D[i % a.H], a.e[i], a.s0[i] + a.s1[i]);
+        }
+    }
+}
+
 __global__ void __launch_bounds__(256) epilogue_kernel(EpilogueArgs a)
 {
     __shared__ double red_r[256], red_i[256];
-    const int blk = blockIdx.x, tid = threadIdx.x;
+    const int tid = threadIdx.x;
+    if ((int)blockIdx.x < a.sum.nblocks) {        // the streaming sum of the two halves of du comes first
+        sum_halves_block(a.sum, blockIdx.x, tid);
+        return;
+    }
+    const int blk = blockIdx.x - a.sum.nblocks;
     const long PH2 = 2L * a.P * a.H;
     if (blk < a.P) {
         const int p = blk;
@@ -270,9 +299,18 @@ __global__ void __launch_bounds__(256) epilogue_kernel(EpilogueArgs a)
     }
 }
 
-hipError_t launch_epilogue(const EpilogueArgs &a, hipStream_t s)
+hipError_t launch_epilogue(const EpilogueArgs &a_in, hipStream_t s)
 {
-    hipLaunchKernelGGL(epilogue_kernel, dim3((unsigned)(a.P + a.H)), dim3(256), 0, s, a);
+    EpilogueArgs a = a_in;
+    a.sum.nblocks = 0; a.sum.vec = 0;
+    if (a.sum.s0) {
+        auto al16 = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+        a.sum.vec = a.sum.H % 4 == 0 && al16(a.sum.s0) && al16(a.sum.s1) && al16(a.sum.D) && al16(a.sum.e) && al16(a.sum.out);
+        const long nb = (a.sum.n + 2047) / 2048;
+        if (nb > 0x7fff0000L) return hipErrorInvalidValue;
+        a.sum.nblocks = (int)nb;
+    }
+    hipLaunchKernelGGL(epilogue_kernel, dim3((unsigned)(a.sum.nblocks + a.P + a.H)), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 

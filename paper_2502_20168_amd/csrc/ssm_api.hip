@@ -288,6 +288,7 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     MARK();
 
     // du[t,h] = sum_{p,c} chi[t, 2p+c] * Bbar_ri[2p+c, h] + D[h] dy[t,h]      (Re(Bbar^H chi) + D dy)
+    const float *du_halves = nullptr;
     GemmArgs g5{};
     g5.A = reinterpret_cast<const float *>(chi); g5.lda = 2 * P; g5.a_kcontig = 1;
     g5.B = Bri; g5.ldb = H; g5.b_kcontig = 0;
@@ -306,7 +307,7 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
         g5.C = halves; g5.ldc = H; g5.splits = 2;
         HIP_TRY(launch_gemm_pair(g5, g6, s, true));
         MARK();
-        HIP_TRY(launch_sum_halves(halves, halves + (size_t)T * H, D, dy, du, nullptr, T, H, s));
+        du_halves = halves;                  // added by extra workgroups of the parameter epilogue's launch
     } else {
         g5.C = du; g5.ldc = H; g5.diag = D; g5.E = dy; g5.lde = H; g5.epilogue = 1; g5.splits = 1;
         HIP_TRY(launch_gemm_pair(g5, g6, s));
@@ -315,6 +316,10 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     MARK();
 
     EpilogueArgs ea{};
+    if (du_halves) {
+        ea.sum.s0 = du_halves; ea.sum.s1 = du_halves + (size_t)T * H; ea.sum.D = D; ea.sum.e = dy; ea.sum.out = du;
+        ea.sum.n = (long)T * H; ea.sum.H = (int)H;
+    }
     ea.Lambda = reinterpret_cast<const float2 *>(Lambda); ea.B = reinterpret_cast<const float2 *>(B);
     ea.log_delta = log_delta; ea.P = (int)P; ea.H = (int)H;
     ea.dBbar_part = dBpart; ea.nsplit_B = lo.splitB;

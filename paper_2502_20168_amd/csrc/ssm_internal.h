@@ -152,7 +152,15 @@ hipError_t launch_prep(const PrepArgs &a, hipStream_t s);
 
 
 
+// out = s0 + s1 + D (.) e over n = rows * H elements: the two K halves of du and D dy, added by extra
+// workgroups of the parameter epilogue's launch (both only wait for the products before them)
+struct SumHalvesArgs {
+    const float *s0, *s1, *D, *e; float *out; long n; int H;
+    int vec, nblocks;                        // set by launch_epilogue
+};
+
 struct EpilogueArgs {
+    SumHalvesArgs sum;                       // s0 == nullptr: nothing to add
     const float2 *Lambda; const float2 *B; const float *log_delta; int P, H;
     const float *dBbar_part; int nsplit_B;   // [nsplit_B][2P][H]
     const float *dC_part; int nsplit_C;      // [nsplit_C][H][2P]  (sum_t dy x_re, sum_t dy x_im)
