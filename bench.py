@@ -389,7 +389,7 @@ def s5_block(ssm, torch, wl, d, Bt, L, H, P, iters=10):
     return {"shape": "Bt=%d L=%d H=%d P=%d" % (Bt, L, H, P), "fwd_us": round(f_ms * 1e3, 1), "bwd_us": round(b_ms * 1e3, 1),
             "Mtokens_per_s": round(T / ((f_ms + b_ms) * 1e-3) / 1e6, 2),
             "note": "layer + gate, forward and gradient pass, replayed as HIP graphs (includes the binding's output "
-                    "allocations inside the graph); GELU of the layer output is formed in the output projection's store"}
+                    "allocations inside the graph); GELU of the layer output is formed where the output projection's result is stored (in the sum of its two K halves at this shape)"}
 
 
 def block_ops(ssm, torch, wl, T, H, iters=20):
