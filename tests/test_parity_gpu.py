@@ -145,6 +145,20 @@ def test_resets_on_the_edges_of_tiles_and_chunks():
     check_workload(w, backward=True, inp=inp)
 
 
+@pytest.mark.parametrize("split", ["default", "single_kernel"])
+@pytest.mark.parametrize("Bt,L,H,P", [(16, 256, 512, 128), (34, 128, 384, 96), (16, 256, 500, 64)])
+def test_products_with_too_few_tiles_as_two_k_halves(Bt, L, H, P, split, monkeypatch):
+    """y and du have 100-199 tiles of 128 x 128 at these shapes: by default each runs as two halves of
+    the state dimension plus a streaming sum (vector path, and the scalar path for a width that is no
+    multiple of 4); SSM_SPLIT_OUT=0 keeps the single kernels.  Both against the oracle."""
+    if split == "default":
+        monkeypatch.delenv("SSM_SPLIT_OUT", raising=False)
+    else:
+        monkeypatch.setenv("SSM_SPLIT_OUT", "0")
+    print("two K halves", Bt, L, H, P, split, flush=True)
+    check_workload(wl.custom("halves", Bt, L, H, P, p_reset=0.02, with_x0=True, seed=53), backward=True)
+
+
 def test_flag_array_at_an_odd_address():
     """is_first only needs byte alignment: the 16-byte flag loads of the scanning tiles and of the
     scan kernel must fall back to byte loads for a buffer that starts at an odd address."""
