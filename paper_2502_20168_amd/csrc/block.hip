@@ -133,14 +133,17 @@ __global__ void __launch_bounds__(256) sum_slabs_kernel(const float *__restrict_
     out[i] = acc;
 }
 
-struct GluLayout { size_t x1, dz, dWpart, total; int splits; };
+struct GluLayout { size_t x1, dz, dWpart, halves, total; int splits; };
 
 bool make_glu_layout(int64_t T, int64_t H, bool bwd, GluLayout &o)
 {
     if (T <= 0 || H <= 0 || H > SSM_MAX_WIDTH || T > SSM_MAX_TOKENS || T > SSM_MAX_ELEMS / H) return false;
     size_t off = 0;
     o.x1 = off; off += up((size_t)T * H * 4);
-    o.dz = o.dWpart = 0; o.splits = 1;
+    o.dz = o.dWpart = o.halves = 0; o.splits = 1;
+    if (gemm_out_split_shape(T, H, H / 2) && H % 2 == 0) {      // the gate products as two K halves
+        o.halves = off; off += up((size_t)2 * T * H * 4);
+    }
     if (bwd) {
         o.dz = off; off += up((size_t)T * H * 4);
         o.splits = gemm_pick_splits(H, H, T, 0);
@@ -217,7 +220,8 @@ ssm_status ssm_half_glu_fwd(const float *u, const float *W, int64_t T, int64_t H
     g.B = W; g.ldb = H; g.b_kcontig = 0;
     g.C = y; g.ldc = H; g.E = u; g.lde = H; g.C2 = gate; g.epilogue = 3;
     g.M = (int)T; g.N = (int)H; g.K = (int)H; g.splits = 1;
-    HIP_TRY(launch_gemm(g, s));
+    float *halves = lo.halves ? reinterpret_cast<float *>(static_cast<char *>(workspace) + lo.halves) : nullptr;
+    HIP_TRY(launch_gemm_halved(g, halves, s));
     return SSM_OK;
 }
 
@@ -248,7 +252,7 @@ ssm_status ssm_half_glu_bwd(const float *u, const float *W, const float *gate, c
     g.B = W; g.ldb = H; g.b_kcontig = 1;
     g.C = du; g.ldc = H; g.E = dy; g.E2 = gate; g.E3 = u; g.lde = H; g.epilogue = 4;
     g.M = (int)T; g.N = (int)H; g.K = (int)H; g.splits = 1;
-    HIP_TRY(launch_gemm(g, s));
+    HIP_TRY(launch_gemm_halved(g, lo.halves ? reinterpret_cast<float *>(ws + lo.halves) : nullptr, s));
     // dW[i, j] = sum_t x1[t, i] dz[t, j]: reduction over tokens in K slabs, then a fixed-order sum
     GemmArgs h{};
     h.A = x1; h.lda = H; h.a_kcontig = 0;

@@ -154,40 +154,86 @@ bool gemm_out_split(int64_t T, int64_t H, int64_t P)
     return !use_f32_mfma() && gemm_out_split_shape(T, H, P);
 }
 
-// y = s0 + s1 + D (.) u (and GELU(y) next to it when gelu_y is given); n = T * H elements
-__global__ void __launch_bounds__(256) sum_halves_kernel(const float *__restrict__ s0, const float *__restrict__ s1,
-                                                         const float *__restrict__ D, const float *__restrict__ u,
-                                                         float *__restrict__ y, float *__restrict__ gelu_y, long n, int H,
-                                                         int vec)
+// The store function of a product that ran as two K halves, applied to v = s0 + s1 (n = rows * H elements):
+//   mode 1: out = v + D (.) e                      (epilogue 1; out2 = GELU(out) when given: epilogue 6)
+//   mode 3: out = e (.) sigmoid(v), out2 = sigmoid(v) when given                       (epilogue 3)
+//   mode 4: out = e (.) e2 + v (.) GELU'(e3)                                            (epilogue 4)
+__device__ __forceinline__ float sum_halves_apply(int mode, float v, float d, float e, float e2, float e3, float &second)
 {
-    const long i = ((long)blockIdx.x * 256 + threadIdx.x) * (vec ? 4 : 1);
-    if (i >= n) return;
-    if (vec) {
-        const float4 a = *reinterpret_cast<const float4 *>(s0 + i), b = *reinterpret_cast<const float4 *>(s1 + i);
-        const float4 uu = *reinterpret_cast<const float4 *>(u + i);
-        const float4 d = *reinterpret_cast<const float4 *>(D + i % H);
-        const float4 r = make_float4(fmaf(d.x, uu.x, a.x + b.x), fmaf(d.y, uu.y, a.y + b.y), fmaf(d.z, uu.z, a.z + b.z),
-                                     fmaf(d.w, uu.w, a.w + b.w));
-        *reinterpret_cast<float4 *>(y + i) = r;
-        if (gelu_y)
-            *reinterpret_cast<float4 *>(gelu_y + i) = make_float4(gelu_value(r.x), gelu_value(r.y), gelu_value(r.z), gelu_value(r.w));
+    if (mode == 1) { const float r = fmaf(d, e, v); second = gelu_value(r); return r; }
+    if (mode == 3) { const float sg = sigmoidf(v); second = sg; return e * sg; }
+    second = 0.f;
+    return fmaf(v, gelu_derivative(e3), e * e2);
+}
+
+struct SumHalves {
+    const float *s0, *s1, *D, *e, *e2, *e3; float *out, *out2; long n; int H, mode, vec;
+};
+
+__global__ void __launch_bounds__(256) sum_halves_kernel(SumHalves a)
+{
+    const long i = ((long)blockIdx.x * 256 + threadIdx.x) * (a.vec ? 4 : 1);
+    if (i >= a.n) return;
+    if (a.vec) {
+        const float4 x = *reinterpret_cast<const float4 *>(a.s0 + i), y = *reinterpret_cast<const float4 *>(a.s1 + i);
+        const float4 e = *reinterpret_cast<const float4 *>(a.e + i);
+        const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
+        const float4 d = a.mode == 1 ? *reinterpret_cast<const float4 *>(a.D + i % a.H) : zero;
+        const float4 e2 = a.mode == 4 ? *reinterpret_cast<const float4 *>(a.e2 + i) : zero;
+        const float4 e3 = a.mode == 4 ? *reinterpret_cast<const float4 *>(a.e3 + i) : zero;
+        float4 r, q;
+        r.x = sum_halves_apply(a.mode, x.x + y.x, d.x, e.x, e2.x, e3.x, q.x);
+        r.y = sum_halves_apply(a.mode, x.y + y.y, d.y, e.y, e2.y, e3.y, q.y);
+        r.z = sum_halves_apply(a.mode, x.z + y.z, d.z, e.z, e2.z, e3.z, q.z);
+        r.w = sum_halves_apply(a.mode, x.w + y.w, d.w, e.w, e2.w, e3.w, q.w);
+        *reinterpret_cast<float4 *>(a.out + i) = r;
+        if (a.out2) *reinterpret_cast<float4 *>(a.out2 + i) = q;
     } else {
-        const float r = fmaf(D[i % H], u[i], s0[i] + s1[i]);
-        y[i] = r;
-        if (gelu_y) gelu_y[i] = gelu_value(r);
+        float q;
+        const float r = sum_halves_apply(a.mode, a.s0[i] + a.s1[i], a.mode == 1 ? a.D[i % a.H] : 0.f, a.e[i],
+                                         a.mode == 4 ? a.e2[i] : 0.f, a.mode == 4 ? a.e3[i] : 0.f, q);
+        a.out[i] = r;
+        if (a.out2) a.out2[i] = q;
     }
+}
+
+static hipError_t launch_sum(SumHalves a, hipStream_t s)
+{
+    auto al16 = [](const void *p) { return !p || (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+    a.vec = a.H % 4 == 0 && al16(a.s0) && al16(a.s1) && al16(a.D) && al16(a.e) && al16(a.e2) && al16(a.e3) && al16(a.out) &&
+            al16(a.out2);
+    const long threads = a.vec ? a.n / 4 : a.n;
+    hipLaunchKernelGGL(sum_halves_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, a);
+    return hipGetLastError();
 }
 
 hipError_t launch_sum_halves(const float *s0, const float *s1, const float *D, const float *u, float *y, float *gelu_y,
                              int64_t T, int64_t H, hipStream_t s)
 {
-    const long n = (long)T * H;
-    auto al16 = [](const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
-    const int vec = H % 4 == 0 && al16(s0) && al16(s1) && al16(D) && al16(u) && al16(y) && (!gelu_y || al16(gelu_y));
-    const long threads = vec ? n / 4 : n;
-    hipLaunchKernelGGL(sum_halves_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, s0, s1, D, u, y, gelu_y, n,
-                       (int)H, vec);
-    return hipGetLastError();
+    SumHalves a{};
+    a.s0 = s0; a.s1 = s1; a.D = D; a.e = u; a.out = y; a.out2 = gelu_y; a.n = (long)T * H; a.H = (int)H; a.mode = 1;
+    return launch_sum(a, s);
+}
+
+// A product with a store function (epilogue 1, 3, 4 or 6) that runs as two K halves into `halves`
+// ([2][M][N] floats) plus the streaming pass above when its shape calls for it and `halves` is given;
+// otherwise the plain launch.
+hipError_t launch_gemm_halved(const GemmArgs &a, float *halves, hipStream_t s)
+{
+    const bool store_fn = a.epilogue == 1 || a.epilogue == 3 || a.epilogue == 4 || a.epilogue == 6;
+    if (!halves || !store_fn || a.splits > 1 || a.ldc != a.N || (a.E && a.lde != a.N) || !gemm_out_split(a.M, a.N, a.K / 2) ||
+        a.K % 2 != 0)
+        return launch_gemm(a, s);
+    GemmArgs g = a;
+    g.C = halves; g.ldc = a.N; g.splits = 2; g.epilogue = 0; g.diag = nullptr; g.E = nullptr; g.E2 = g.E3 = nullptr; g.C2 = nullptr;
+    hipError_t e = launch_gemm(g, s);
+    if (e != hipSuccess) return e;
+    SumHalves q{};
+    q.s0 = halves; q.s1 = halves + (size_t)a.M * a.N; q.D = a.diag; q.e = a.E; q.e2 = a.E2; q.e3 = a.E3;
+    q.out = a.C; q.out2 = a.C2; q.n = (long)a.M * a.N; q.H = a.N;
+    q.mode = (a.epilogue == 6) ? 1 : a.epilogue;
+    if (a.epilogue == 1) q.out2 = nullptr;
+    return launch_sum(q, s);
 }
 
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)

@@ -632,7 +632,7 @@ ssm_status ssm_step_bwd(const void *plan, size_t plan_bytes, const float *D, con
 }
 
 namespace {
-struct BlockLayout { size_t ssm, x1, glu, dypre, total; };
+struct BlockLayout { size_t ssm, x1, glu, dypre, gate_halves, total; };
 bool make_block_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, BlockLayout &o)
 {
     Layout lo;
@@ -640,9 +640,10 @@ bool make_block_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, Bl
     const size_t TH = up((size_t)Bt * L * H * 4);
     size_t off = 0;
     o.ssm = off; off += up(lo.total);
-    o.x1 = o.glu = o.dypre = 0;
+    o.x1 = o.glu = o.dypre = o.gate_halves = 0;
     if (!bwd) {
         o.x1 = off; off += TH;
+        if (H % 2 == 0 && gemm_out_split_shape(Bt * L, H, H / 2)) { o.gate_halves = off; off += 2 * TH; }   // gate product as two K halves
     } else {
         const size_t g = ssm_half_glu_workspace_bytes(Bt * L, H, 1);
         if (g == 0) return false;
@@ -686,7 +687,7 @@ ssm_status ssm_block_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 
     g.B = W; g.ldb = H; g.b_kcontig = 0;
     g.C = out; g.ldc = H; g.E = y; g.lde = H; g.C2 = gate; g.epilogue = 3;
     g.M = (int)(Bt * L); g.N = (int)H; g.K = (int)H; g.splits = 1;
-    HIP_TRY(launch_gemm(g, s));
+    HIP_TRY(launch_gemm_halved(g, bl.gate_halves ? reinterpret_cast<float *>(ws + bl.gate_halves) : nullptr, s));
     return SSM_OK;
 }
 

@@ -67,6 +67,9 @@ bool gemm_out_split(int64_t T, int64_t H, int64_t P);
 // y = s0 + s1 + D (.) u, and GELU(y) to gelu_y when it is not null
 hipError_t launch_sum_halves(const float *s0, const float *s1, const float *D, const float *u, float *y, float *gelu_y,
                              int64_t T, int64_t H, hipStream_t s);
+// a product with a store function (epilogue 1, 3, 4, 6): as two K halves into halves[2][M][N] plus a
+// streaming pass when gemm_out_split(M, N, K/2) says so and halves is not null; else launch_gemm
+hipError_t launch_gemm_halved(const GemmArgs &g, float *halves, hipStream_t s);
 // two independent problems in one launch (falls back to two launches for layouts without a
 // paired instantiation)
 hipError_t launch_gemm_pair(const GemmArgs &a, const GemmArgs &b, hipStream_t s, bool second_first = false);
