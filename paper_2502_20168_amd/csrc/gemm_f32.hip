@@ -158,9 +158,10 @@ bool gemm_out_split(int64_t T, int64_t H, int64_t P)
 //   mode 1: out = v + D (.) e                      (epilogue 1; out2 = GELU(out) when given: epilogue 6)
 //   mode 3: out = e (.) sigmoid(v), out2 = sigmoid(v) when given                       (epilogue 3)
 //   mode 4: out = e (.) e2 + v (.) GELU'(e3)                                            (epilogue 4)
-__device__ __forceinline__ float sum_halves_apply(int mode, float v, float d, float e, float e2, float e3, float &second)
+__device__ __forceinline__ float sum_halves_apply(int mode, bool want2, float v, float d, float e, float e2, float e3,
+                                                  float &second)
 {
-    if (mode == 1) { const float r = fmaf(d, e, v); second = gelu_value(r); return r; }
+    if (mode == 1) { const float r = fmaf(d, e, v); second = want2 ? gelu_value(r) : 0.f; return r; }
     if (mode == 3) { const float sg = sigmoidf(v); second = sg; return e * sg; }
     second = 0.f;
     return fmaf(v, gelu_derivative(e3), e * e2);
@@ -182,15 +183,15 @@ __global__ void __launch_bounds__(256) sum_halves_kernel(SumHalves a)
         const float4 e2 = a.mode == 4 ? *reinterpret_cast<const float4 *>(a.e2 + i) : zero;
         const float4 e3 = a.mode == 4 ? *reinterpret_cast<const float4 *>(a.e3 + i) : zero;
         float4 r, q;
-        r.x = sum_halves_apply(a.mode, x.x + y.x, d.x, e.x, e2.x, e3.x, q.x);
-        r.y = sum_halves_apply(a.mode, x.y + y.y, d.y, e.y, e2.y, e3.y, q.y);
-        r.z = sum_halves_apply(a.mode, x.z + y.z, d.z, e.z, e2.z, e3.z, q.z);
-        r.w = sum_halves_apply(a.mode, x.w + y.w, d.w, e.w, e2.w, e3.w, q.w);
+        r.x = sum_halves_apply(a.mode, a.out2 != nullptr, x.x + y.x, d.x, e.x, e2.x, e3.x, q.x);
+        r.y = sum_halves_apply(a.mode, a.out2 != nullptr, x.y + y.y, d.y, e.y, e2.y, e3.y, q.y);
+        r.z = sum_halves_apply(a.mode, a.out2 != nullptr, x.z + y.z, d.z, e.z, e2.z, e3.z, q.z);
+        r.w = sum_halves_apply(a.mode, a.out2 != nullptr, x.w + y.w, d.w, e.w, e2.w, e3.w, q.w);
         *reinterpret_cast<float4 *>(a.out + i) = r;
         if (a.out2) *reinterpret_cast<float4 *>(a.out2 + i) = q;
     } else {
         float q;
-        const float r = sum_halves_apply(a.mode, a.s0[i] + a.s1[i], a.mode == 1 ? a.D[i % a.H] : 0.f, a.e[i],
+        const float r = sum_halves_apply(a.mode, a.out2 != nullptr, a.s0[i] + a.s1[i], a.mode == 1 ? a.D[i % a.H] : 0.f, a.e[i],
                                          a.mode == 4 ? a.e2[i] : 0.f, a.mode == 4 ? a.e3[i] : 0.f, q);
         a.out[i] = r;
         if (a.out2) a.out2[i] = q;
