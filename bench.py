@@ -163,7 +163,7 @@ def main():
     kern = lambda tile, lay0, lay1: "gemm_bf16x3_ws_kernel<%s,2,2,8,2,%d,%d,%d>" % (tile, npl, lay0, lay1)
     big = (T // 128) * ((2 * P + 127) // 128) >= 200
     t128 = ((T + 127) // 128) * ((H + 127) // 128)
-    out_split = (not f32_path and t128 < 200 and 2 * t128 >= 200 and P >= 64 and (2 * P) % 64 == 0
+    out_split = (not f32_path and t128 < 200 and 2 * t128 >= 200 and P >= 256 and (2 * P) % 64 == 0
                  and os.environ.get("SSM_SPLIT_OUT", "") != "0")
     out_tile = "128,128,32" if ((T + 127) // 128) * ((H + 127) // 128) >= 200 else \
                ("64,128,32" if ((T + 63) // 64) * ((H + 127) // 128) >= 200 else "64,64,64")

@@ -143,8 +143,9 @@ size_t gemm_scan_desc_bytes(int64_t Bt, int64_t L, int64_t P)
 // kernel adds them and applies the store function.  SSM_SPLIT_OUT=0 switches this off (for comparison).
 bool gemm_out_split_shape(int64_t T, int64_t H, int64_t P)
 {
+    // a half must still be long enough (8 K tiles) to pay for the streaming pass
     const int64_t tiles = ((T + 127) / 128) * ((H + 127) / 128);
-    return tiles < 200 && 2 * tiles >= 200 && P >= 64 && (2 * P) % 64 == 0;
+    return tiles < 200 && 2 * tiles >= 200 && P >= 256 && (2 * P) % 64 == 0;
 }
 
 bool gemm_out_split(int64_t T, int64_t H, int64_t P)

@@ -146,7 +146,7 @@ def test_resets_on_the_edges_of_tiles_and_chunks():
 
 
 @pytest.mark.parametrize("split", ["default", "single_kernel"])
-@pytest.mark.parametrize("Bt,L,H,P", [(16, 256, 512, 128), (34, 128, 384, 96), (16, 256, 500, 64)])
+@pytest.mark.parametrize("Bt,L,H,P", [(16, 256, 512, 256), (34, 128, 384, 288), (16, 256, 500, 256)])
 def test_products_with_too_few_tiles_as_two_k_halves(Bt, L, H, P, split, monkeypatch):
     """y and du have 100-199 tiles of 128 x 128 at these shapes: by default each runs as two halves of
     the state dimension plus a streaming sum (vector path, and the scalar path for a width that is no
