@@ -55,29 +55,71 @@ __device__ __forceinline__ Split4 split3(float4 v)
     return o;
 }
 
-// Two-plane split with round-to-nearest (v_cvt_pk_bf16_f32): a1 = rn_bf16(a), a2 = rn_bf16(a - a1);
-// |a - a1 - a2| <= 2^-18 |a|.  Used by the reduced-precision mode (three products a1b1, a1b2, a2b1:
-// relative error of a product below 2^-16), never by the default path.
+// Two-plane split into fp16: with the operand scaled by a power of two so that its largest
+// magnitude lies in [2^14, 2^15), a1 = rn_fp16(s a) and a2 = rn_fp16(s a - a1) (the residual is
+// formed exactly by one fused multiply-add).  fp16 keeps 11 significant bits, so
+// |s a - a1 - a2| <= 2^-22 |s a| as long as a2 is a normal fp16 number, i.e. for |a| down to 2^-17
+// of the largest magnitude; below that the planes act as a fixed-point pair with an absolute error
+// of at most 2^-25 (half the spacing of the fp16 subnormals) in scaled units, i.e. 2^-39 of the
+// largest magnitude.  The three products a1b1, a1b2, a2b1 (each exact in fp32) then leave a
+// relative error of about 3 * 2^-22 per product term at worst -- the level of fp32 rounding -- for
+// half the matrix instructions of the three-way bf16 split.  The scale is taken off the
+// accumulators before anything is stored.
 typedef float f32x2 __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ Split4 split2(float4 v)
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ Split4 split2_f16(float4 v, float s)
 {
+    const f32x2 a = {v.x * s, v.y * s}, b = {v.z * s, v.w * s};
+    union { f16x2 h; unsigned u; } ha, hb, la, lb;
+    ha.h = __builtin_convertvector(a, f16x2);
+    hb.h = __builtin_convertvector(b, f16x2);
+    const f32x2 ra = {__builtin_fmaf(v.x, s, -(float)ha.h.x), __builtin_fmaf(v.y, s, -(float)ha.h.y)};
+    const f32x2 rb = {__builtin_fmaf(v.z, s, -(float)hb.h.x), __builtin_fmaf(v.w, s, -(float)hb.h.y)};
+    la.h = __builtin_convertvector(ra, f16x2);
+    lb.h = __builtin_convertvector(rb, f16x2);
+    union { unsigned u[2]; bf16x4 b; } p0, p1;       // bf16x4 is only the 8-byte container of the LDS store
+    p0.u[0] = ha.u; p0.u[1] = hb.u;
+    p1.u[0] = la.u; p1.u[1] = lb.u;
     Split4 o;
-    const f32x2 lo = {v.x, v.y}, hi = {v.z, v.w};
-    union { bf16x2 b; unsigned u; } a0, a1, b0, b1;
-    a0.b = __builtin_convertvector(lo, bf16x2);
-    a1.b = __builtin_convertvector(hi, bf16x2);
-    const f32x2 rlo = {v.x - __uint_as_float(a0.u << 16), v.y - __uint_as_float(a0.u & 0xffff0000u)};
-    const f32x2 rhi = {v.z - __uint_as_float(a1.u << 16), v.w - __uint_as_float(a1.u & 0xffff0000u)};
-    b0.b = __builtin_convertvector(rlo, bf16x2);
-    b1.b = __builtin_convertvector(rhi, bf16x2);
-    union { unsigned u[2]; bf16x4 b; } p0, p1;
-    p0.u[0] = a0.u; p0.u[1] = a1.u;
-    p1.u[0] = b0.u; p1.u[1] = b1.u;
     o.p[0] = p0.b; o.p[1] = p1.b; o.p[2] = p1.b;
     return o;
 }
 template <int NPL>
-__device__ __forceinline__ Split4 split_planes(float4 v) { return NPL == 3 ? split3(v) : split2(v); }
+__device__ __forceinline__ Split4 split_planes(float4 v, float s) { return NPL == 3 ? split3(v) : split2_f16(v, s); }
+
+// log2 of the power-of-two scale that brings the largest magnitude of an operand into [2^14, 2^15):
+// every lane of the wavefront gets the same value.  The slots hold bit patterns of non-negative
+// floats, which order like unsigned integers.  An operand of zeros gets the largest scale (its
+// planes are zeros whatever the scale).  Two steps, so that the loads can be issued ahead of other
+// memory traffic and waited for behind it: absmax_issue starts eight independent loads per lane (the
+// first 512 slots), absmax_log2_scale reduces them (and walks the slots beyond 512, if any).
+struct AbsMaxLoads { unsigned w[8]; };
+__device__ __forceinline__ AbsMaxLoads absmax_issue(const AbsMax &m, int lane)
+{
+    AbsMaxLoads r;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const int i = lane + 64 * j;
+        const unsigned t = m.slots[i < m.n ? i : 0];         // unconditional, so that the loads overlap
+        r.w[j] = i < m.n ? t : 0u;
+    }
+    return r;
+}
+__device__ __forceinline__ int absmax_log2_scale(const AbsMax &m, const AbsMaxLoads &r, int lane)
+{
+    unsigned v = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v = max(v, r.w[j]);
+    for (int i = 512 + lane; i < m.n; i += 64) v = max(v, m.slots[i]);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = max(v, (unsigned)__shfl_xor((int)v, o));
+    const int e = (int)((v >> 23) & 0xffu);          // biased exponent of the maximum
+    int f = 268 - e;                                 // biased exponent of 2^(14 - (e - 127))
+    f = f < 1 ? 1 : (f > 254 ? 254 : f);
+    return f - 127;
+}
+__device__ __forceinline__ float pow2f(int e) { return __uint_as_float((unsigned)(e + 127) << 23); }   // e in [-127, 127]
 
 // Stages one R x BK fp32 operand tile: global -> registers (fp32) -> split -> NPL LDS planes.
 // A thread handles float4 units along the contiguous index of the source and writes the four
@@ -137,14 +179,15 @@ struct SplitLoader {
         }
     }
 
-    __device__ __forceinline__ void store(__bf16 *lds, int tid) const
+    // scale: two-plane staging only (a power of two, see split2_f16)
+    __device__ __forceinline__ void store(__bf16 *lds, int tid, float scale) const
     {
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             const int idx = tid + i * NT;
             const int off = KC ? kc_row(idx / (BK / 4)) * S + 4 * (idx % (BK / 4))
                                : (idx / (R / 4)) * S + 4 * (idx % (R / 4));
-            const Split4 sp = split_planes<NPL>(r[i]);
+            const Split4 sp = split_planes<NPL>(r[i], scale);
 #pragma unroll
             for (int s = 0; s < NPL; ++s) *reinterpret_cast<bf16x4 *>(lds + s * PLANE + off) = sp.p[s];
         }
@@ -227,6 +270,7 @@ __device__ __forceinline__ void scan_epilogue_barriers(const GemmDev &g, int m0)
     if (has_pred) __syncthreads();
     __syncthreads();
     if (REV) __syncthreads();
+    if (g.scan.amax_out) __syncthreads();
 }
 
 // tid: 0 .. 64*SCAN_WAVES-1 (the consumers and the first producer wavefronts: the scan is bound by
@@ -357,6 +401,7 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
     if (whole_seqs) Xin = (!REV && a.x0 && active) ? a.x0[(long)b * a.P + p] : make_float2(0.f, 0.f);
     float2 xs = cfma(Aex, Xin, Sex);
     float2 *dst = reinterpret_cast<float2 *>(g.C) + (long)row0 * a.P + p;
+    float amax = 0.f;                                        // largest magnitude this thread stores
     if (!REV) {
 #pragma unroll
         for (int e = 0; e < RC; ++e) {
@@ -364,6 +409,7 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
             const float2 le = make_float2(r ? 0.f : lam.x, r ? 0.f : lam.y);
             xs = cfma(le, xs, val[e]);
             if (active) dst[(long)e * a.P] = xs;
+            amax = fmaxf(amax, fmaxf(fabsf(xs.x), fabsf(xs.y)));
         }
         if (active && a.x_last && t0 + RC == a.L) a.x_last[(long)b * a.P + p] = xs;
     } else {
@@ -389,6 +435,7 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
                 const float2 le = make_float2(r ? 0.f : lam.x, r ? 0.f : lam.y);
                 xs = cfma(le, xs, val[e]);
                 if (active) dst[(long)e * a.P] = xs;
+                amax = fmaxf(amax, fmaxf(fabsf(xs.x), fabsf(xs.y)));
                 const bool m = (fmask >> e) & 1u;
                 const float2 qv = make_float2(m ? 0.f : xp[j].x, m ? 0.f : xp[j].y);
                 acc.x = fmaf(qv.x, xs.x, fmaf(qv.y, xs.y, acc.x));
@@ -403,6 +450,19 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
             float2 sum = make_float2(0.f, 0.f);
             for (int j = 0; j < NCH; ++j) { sum.x += lds.cS[j * 64 + c].x; sum.y += lds.cS[j * 64 + c].y; }
             a.partial[(size_t)(m0 / SCAN_TILE) * a.P + p] = sum;
+        }
+    }
+    if (a.amax_out) {
+        // one atomic per workgroup, spread over ABSMAX_SLOTS addresses (the bit patterns of non-negative
+        // floats order like unsigned integers); cAny is free since barrier 5
+        unsigned v = active ? __float_as_uint(amax) : 0u;
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) v = max(v, (unsigned)__shfl_xor((int)v, o));
+        if (c == 0) lds.cAny[q] = v;
+        __syncthreads();                                                                   // barrier 7 (with amax_out only)
+        if (tid == 0) {
+            for (int j = 1; j < NCH; ++j) v = max(v, lds.cAny[j]);
+            atomicMax(a.amax_out + (unsigned)tile % ABSMAX_SLOTS, v);
         }
     }
 }
@@ -425,7 +485,7 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
     constexpr int PT = 64 * NP;                   // producer threads
     using LA = SplitLoader<BM, BK, AKC, PT, NPL>;
     using LB = SplitLoader<BN, BK, BKC, PT, NPL>;
-    static_assert(NPL == 2 || NPL == 3, "two or three bf16 planes per operand");
+    static_assert(NPL == 2 || NPL == 3, "three bf16 planes or two scaled fp16 planes per operand");
     constexpr int STAGE_A = NPL * LA::PLANE, STAGE_B = NPL * LB::PLANE, STAGE = STAGE_A + STAGE_B;
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int MI = WM / 32, NI = WN / 32;
@@ -446,14 +506,24 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
             la[set].template load<FAST>(g.A, g.lda, m0, g.M, kbeg + t * BK, kend, ptid);
             lb[set].template load<FAST>(g.B, g.ldb, n0, g.N, kbeg + t * BK, kend, ptid);
         };
+        float sca = 1.f, scb = 1.f;
+        AbsMaxLoads ma, mb;
+        if constexpr (NPL == 2) {                 // ahead of the tile loads: returned first, waited for with tile 0
+            ma = absmax_issue(g.amaxA, tid & 63);
+            mb = absmax_issue(g.amaxB, tid & 63);
+        }
         auto stash = [&](int set, int t) {
             __bf16 *st = smem + (t % NS) * STAGE;
-            la[set].store(st, ptid);
-            lb[set].store(st + STAGE_A, ptid);
+            la[set].store(st, ptid, sca);
+            lb[set].store(st + STAGE_A, ptid, scb);
         };
 #pragma unroll
         for (int j = 0; j < PF; ++j)
             if (j < nk) fetch(j, j);
+        if constexpr (NPL == 2) {
+            sca = pow2f(absmax_log2_scale(g.amaxA, ma, tid & 63));
+            scb = pow2f(absmax_log2_scale(g.amaxB, mb, tid & 63));
+        }
         // prologue: tiles 0 .. NS-2 into their stages
 #pragma unroll
         for (int t = 0; t < NS - 1; ++t) {
@@ -539,7 +609,11 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
 #pragma unroll
                 for (int j = 0; j < NI; ++j) {
                     const int pa = NPL == 3 ? PA3[p] : PA2[p % 3], pb = NPL == 3 ? PB3[p] : PB2[p % 3];
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i][pa], fb[set][j][pb], acc[i][j], 0, 0, 0);
+                    if constexpr (NPL == 3)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i][pa], fb[set][j][pb], acc[i][j], 0, 0, 0);
+                    else
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, fa[set][i][pa]),
+                                                                           __builtin_bit_cast(f16x8, fb[set][j][pb]), acc[i][j], 0, 0, 0);
                 }
     };
     static_assert(KS % 2 == 0 || KS == 1, "k steps per tile: 1 or even");
@@ -554,6 +628,15 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
         }
     };
 
+    // two-plane staging: the power of two that takes both operand scales off again, in two factors
+    // (either alone stays a normal number whenever the result does)
+    float unscale1 = 1.f, unscale2 = 1.f;
+    if constexpr (NPL == 2) {
+        const AbsMaxLoads ma = absmax_issue(g.amaxA, l), mb = absmax_issue(g.amaxB, l);
+        const int st = absmax_log2_scale(g.amaxA, ma, l) + absmax_log2_scale(g.amaxB, mb, l);
+        const int s1 = st >> 1;
+        unscale1 = pow2f(-s1); unscale2 = pow2f(s1 - st);
+    }
     __syncthreads();
     if (nk > 0) fetch_frags(0, 0, 0);
     if (KS == 1) {
@@ -591,6 +674,14 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
         }
     }
 
+    if constexpr (NPL == 2) {
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = (acc[i][j][r] * unscale1) * unscale2;
+    }
     if constexpr (EPI == 7 || EPI == 8) {
         static_assert(BM == SCAN_TILE && BN == SCAN_TILE && NC == 4, "scan epilogue: 128x128 tile, 4 consumers");
         const ScanLds lds(smem);
@@ -735,6 +826,7 @@ inline GemmDev make_gemm_dev(const GemmArgs &a)
     else if (8 % splits == 0) { g.mode = 2; g.mpar = 8 / splits; g.nx = (int)((ntiles + g.mpar - 1) / g.mpar); }
     else { g.mode = 3; g.mpar = 0; g.nx = (int)((ntiles * splits + 7) / 8); }
     g.scan = a.scan;
+    g.amaxA = a.amaxA; g.amaxB = a.amaxB;
     g.sc_nt = g.sc_cpu = g.sc_ncg = g.sc_units = g.sc_rev = 0;
     if ((a.epilogue == 7 || a.epilogue == 8) && a.scan.L >= BM) {
         g.sc_rev = a.epilogue == 8;

@@ -81,12 +81,17 @@ static bool use_f32_mfma()
     return e && e[0] == '1';
 }
 
-// SSM_GEMM_SPLIT=2 selects the reduced-precision mode: two bf16 planes per operand and three
-// products (relative error of a product below 2^-16 instead of 2^-23).  Default: three planes.
-static bool use_two_planes()
+// A product whose operands both come with their largest magnitude is staged as two scaled fp16
+// planes per operand (three matrix instructions per k block instead of six, same accuracy class);
+// SSM_GEMM_SPLIT=3 keeps the three-way bf16 split everywhere (for comparison).
+bool gemm_two_planes_enabled()
 {
     const char *e = std::getenv("SSM_GEMM_SPLIT");
-    return e && e[0] == '2';
+    return !(e && e[0] == '3') && !use_f32_mfma();
+}
+static bool use_two_planes(const GemmArgs &a)
+{
+    return a.amaxA.slots && a.amaxB.slots && a.amaxA.n > 0 && a.amaxB.n > 0 && gemm_two_planes_enabled();
 }
 
 bool gemm_scan_shape_ok(int64_t Bt, int64_t L, int64_t P)
@@ -244,14 +249,14 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
     if (a.epilogue == 7) {
         // the input projection that scans its own output: 128x128 tiles only
         if (!scan_args_ok(a)) return hipErrorInvalidValue;
-        if (use_two_planes())
+        if (use_two_planes(a))
             return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, gemm_layout(true, true, 7)>(a, s);
         return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 3, gemm_layout(true, true, 7)>(a, s);
     }
     if (a.epilogue == 8) {
         // C^H dy that runs the reverse scan on its own output
         if (!scan_args_ok(a)) return hipErrorInvalidValue;
-        if (use_two_planes())
+        if (use_two_planes(a))
             return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, gemm_layout(true, false, 8)>(a, s);
         return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 3, gemm_layout(true, false, 8)>(a, s);
     }
@@ -277,7 +282,7 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
     // (nearly) every CU a workgroup; else 64x128x32 tiles (staging per multiply-add is 1.5x there);
     // else, for the small products of step mode, 64x64x64 tiles (fewer, longer K steps)
     const long tiles64x128 = (long)((a.M + 63) / 64) * ((a.N + 127) / 128) * splits;
-    if (use_two_planes()) {
+    if (use_two_planes(a)) {
         if (tiles128 >= 200) return dispatch_bf16x3<128, 128, 32, 2, 2, 8, 2, 2>(a, s);
         if (tiles64x128 >= 200) return dispatch_bf16x3<64, 128, 32, 2, 2, 8, 2, 2>(a, s);
         return dispatch_bf16x3<64, 64, 64, 2, 2, 8, 2, 2>(a, s);
@@ -300,7 +305,7 @@ hipError_t launch_gemm_pair(const GemmArgs &a, const GemmArgs &b, hipStream_t s,
                       NN8 = gemm_layout(true, false, 8), TN0 = gemm_layout(false, false, 0);
         const int la = layout_of(a), lb = layout_of(b);
         if (la == NN8 && !scan_args_ok(a)) return hipErrorInvalidValue;
-        if (use_two_planes()) {
+        if (use_two_planes(a) && use_two_planes(b)) {
             if (la == NN8 && lb == TN0) return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, NN8, TN0>(a, s, &b, second_first);
             if (la == NN0 && lb == TN0) return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, NN0, TN0>(a, s, &b, second_first);
             if (la == NN1 && lb == TN0) return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, NN1, TN0>(a, s, &b, second_first);

@@ -36,6 +36,7 @@ struct GemmDev {
     // groups per sequence, number of units (a unit = the chains of one sequence and column group)
     ScanEpilogue scan;
     int sc_nt, sc_cpu, sc_ncg, sc_units, sc_rev;
+    AbsMax amaxA, amaxB;    // two-plane fp16 staging only
 };
 
 // Value stored for an output element whose accumulated product is v.

@@ -46,14 +46,26 @@ __device__ Zoh zoh_discretize(float2 Lambda, float log_delta)
 // partial[s][h] = sum_{t in slab s} a[t,h] * b[t,h]      (dD = sum_t dy_t (.) u_t)
 // workgroup = 64 columns x 4 row phases
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ void coldot_block(const ColDotArgs &a, int colblock, int slab)
+// largest bit pattern of the non-negative floats v of a 256-thread workgroup, valid in thread 0
+__device__ __forceinline__ unsigned block_absmax(float v)
+{
+    __shared__ unsigned wmax[4];
+    unsigned u = __float_as_uint(v);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) u = max(u, (unsigned)__shfl_xor((int)u, o));
+    if ((threadIdx.x & 63) == 0) wmax[threadIdx.x >> 6] = u;
+    __syncthreads();
+    return max(max(wmax[0], wmax[1]), max(wmax[2], wmax[3]));
+}
+
+__device__ __forceinline__ void coldot_block(const ColDotArgs &a, int colblock, int slab, unsigned *amax, unsigned *bmax, int slot)
 {
     __shared__ float red[256];
     const int tid = threadIdx.x;
     const int col = colblock * 64 + (tid & 63), ph = tid >> 6;
     const long rows_per = (a.T + a.nslab - 1) / a.nslab;
     const long r0 = slab * rows_per, r1 = min((long)a.T, r0 + rows_per);
-    float s = 0.f;
+    float s = 0.f, ma = 0.f, mb = 0.f;
     if (col < a.H) {
         long t = r0 + ph;
         for (; t + 12 < r1; t += 16) {           // four independent row pairs in flight
@@ -62,13 +74,53 @@ __device__ __forceinline__ void coldot_block(const ColDotArgs &a, int colblock, 
             const float a2 = a.a[(t + 8) * a.H + col], b2 = a.b[(t + 8) * a.H + col];
             const float a3 = a.a[(t + 12) * a.H + col], b3 = a.b[(t + 12) * a.H + col];
             s = fmaf(a0, b0, s); s = fmaf(a1, b1, s); s = fmaf(a2, b2, s); s = fmaf(a3, b3, s);
+            ma = fmaxf(fmaxf(ma, fmaxf(fabsf(a0), fabsf(a1))), fmaxf(fabsf(a2), fabsf(a3)));
+            mb = fmaxf(fmaxf(mb, fmaxf(fabsf(b0), fabsf(b1))), fmaxf(fabsf(b2), fabsf(b3)));
         }
-        for (; t < r1; t += 4) s = fmaf(a.a[t * a.H + col], a.b[t * a.H + col], s);
+        for (; t < r1; t += 4) {
+            const float a0 = a.a[t * a.H + col], b0 = a.b[t * a.H + col];
+            s = fmaf(a0, b0, s);
+            ma = fmaxf(ma, fabsf(a0)); mb = fmaxf(mb, fabsf(b0));
+        }
     }
     red[tid] = s;
     __syncthreads();
     if (ph == 0 && col < a.H)
         a.partial[(long)slab * a.H + col] = (red[tid] + red[tid + 64]) + (red[tid + 128] + red[tid + 192]);
+    if (amax) {
+        const unsigned ua = block_absmax(ma);
+        __syncthreads();
+        const unsigned ub = block_absmax(mb);
+        if (tid == 0) { amax[slot] = ua; bmax[slot] = ub; }
+    }
+}
+
+// slots[piece] = largest magnitude of piece `piece` of x[n] (pieces of whole float4 units when vec)
+__device__ __forceinline__ void absmax_pass_block(const PrepArgs::Pass &q, int piece)
+{
+    const int tid = threadIdx.x;
+    float m = 0.f;
+    if (q.vec) {
+        const size_t n4 = q.n / 4;
+        const float4 *x4 = reinterpret_cast<const float4 *>(q.x);
+        size_t i = (size_t)piece * 256 + tid;
+        const size_t stride = (size_t)q.nblocks * 256;
+        for (; i + 3 * stride < n4; i += 4 * stride) {          // four loads in flight
+            const float4 a = x4[i], b = x4[i + stride], c = x4[i + 2 * stride], d = x4[i + 3 * stride];
+            m = fmaxf(m, fmaxf(fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))),
+                               fmaxf(fmaxf(fabsf(b.x), fabsf(b.y)), fmaxf(fabsf(b.z), fabsf(b.w)))));
+            m = fmaxf(m, fmaxf(fmaxf(fmaxf(fabsf(c.x), fabsf(c.y)), fmaxf(fabsf(c.z), fabsf(c.w))),
+                               fmaxf(fmaxf(fabsf(d.x), fabsf(d.y)), fmaxf(fabsf(d.z), fabsf(d.w)))));
+        }
+        for (; i < n4; i += stride) {
+            const float4 a = x4[i];
+            m = fmaxf(m, fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))));
+        }
+    } else {
+        for (size_t i = (size_t)piece * 256 + tid; i < q.n; i += (size_t)q.nblocks * 256) m = fmaxf(m, fabsf(q.x[i]));
+    }
+    const unsigned u = block_absmax(m);
+    if (tid == 0) q.slots[piece] = u;
 }
 
 // Workgroups [0, P): state p -> Abar_p, packed Bbar rows 2p, 2p+1 (and the interleaved complex
@@ -80,11 +132,16 @@ __global__ void __launch_bounds__(256) prep_kernel(PrepArgs a)
     if (blk == 0 && tid == 0 && a.hdr) {
         a.hdr->err = 0; a.hdr->magic = 0x53534d31u;
     }
-    if (blk < a.P) {
+    if (a.pass[0].nblocks > 0 && blk >= a.pass[0].block0) {
+        // passes over the activations whose largest magnitude no earlier kernel could record
+        const int second = (a.pass[1].nblocks > 0 && blk >= a.pass[1].block0) ? 1 : 0;
+        absmax_pass_block(a.pass[second], blk - a.pass[second].block0);
+    } else if (blk < a.P) {
         const int p = blk;
         const Zoh z = zoh_discretize(a.Lambda[p], a.log_delta[p]);
         const float gr = (float)z.gr, gi = (float)z.gi;
         if (tid == 0 && a.lam_bar) a.lam_bar[p] = make_float2((float)z.lr, (float)z.li);
+        float m = 0.f;
         if (a.B) {
             for (int h = tid; h < a.H; h += 256) {
                 const float2 bv = a.B[(long)p * a.H + h];
@@ -94,15 +151,26 @@ __global__ void __launch_bounds__(256) prep_kernel(PrepArgs a)
                     a.Bbar_ri[(long)(2 * p + 1) * a.H + h] = im;
                 }
                 if (a.Bbar_c64) a.Bbar_c64[(long)p * a.H + h] = make_float2(re, im);
+                m = fmaxf(m, fmaxf(fabsf(re), fabsf(im)));
             }
+        }
+        if (a.bbar_max) {
+            const unsigned u = block_absmax(m);
+            if (tid == 0) a.bbar_max[p] = u;
         }
     } else if (blk < a.P + a.H) {
         const int h = blk - a.P;
         const float2 *src = a.C + (long)h * a.P;
         float2 *dst = reinterpret_cast<float2 *>(a.Cc) + (long)h * a.P;
+        float m = 0.f;
         for (int p = tid; p < a.P; p += 256) {
             const float2 c = src[p];
             dst[p] = make_float2(c.x, -c.y);
+            m = fmaxf(m, fmaxf(fabsf(c.x), fabsf(c.y)));
+        }
+        if (a.cc_max) {
+            const unsigned u = block_absmax(m);
+            if (tid == 0) a.cc_max[h] = u;
         }
     } else if (a.zero16 && blk >= a.zero_block0) {
         // clears the tagged words that the scanning input projection will publish into
@@ -116,7 +184,7 @@ __global__ void __launch_bounds__(256) prep_kernel(PrepArgs a)
     } else {
         // column-dot slabs of the gradient pass share this launch (they depend on nothing here)
         const int cb = blk - (a.P + a.H);
-        coldot_block(a.cd, cb % a.cd_colblocks, cb / a.cd_colblocks);
+        coldot_block(a.cd, cb % a.cd_colblocks, cb / a.cd_colblocks, a.cd_amax, a.cd_bmax, cb);
     }
 }
 
@@ -137,6 +205,16 @@ hipError_t launch_prep(const PrepArgs &a_in, hipStream_t s)
         blocks += (unsigned)((a.n16 + 256 * 8 - 1) / (256 * 8));
     } else {
         a.zero16 = nullptr;
+    }
+    // the passes come last; pass[1] without pass[0] moves up
+    if (a.pass[0].nblocks <= 0 && a.pass[1].nblocks > 0) { a.pass[0] = a.pass[1]; a.pass[1].nblocks = 0; }
+    for (int i = 0; i < 2; ++i) {
+        PrepArgs::Pass &q = a.pass[i];
+        if (q.nblocks <= 0) { q.nblocks = 0; continue; }
+        if (!a.Cc || !q.x || !q.slots) return hipErrorInvalidValue;
+        q.vec = (reinterpret_cast<uintptr_t>(q.x) & 15) == 0 && q.n % 4 == 0;
+        q.block0 = (int)blocks;
+        blocks += (unsigned)q.nblocks;
     }
     hipLaunchKernelGGL(prep_kernel, dim3(blocks), dim3(256), 0, s, a);
     return hipGetLastError();

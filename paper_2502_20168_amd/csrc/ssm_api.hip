@@ -17,6 +17,10 @@ struct Layout {
     ScanPlan plan;
     int splitC, splitB, nslab;
     size_t hdr, lam, Bri, Cc, xbuf, chi, ticket, desc, dCpart, dBpart, dApart, dDpart, fdesc, fdesc_bytes, yhalves, total;
+    // largest magnitudes of the operands of the products (shapes whose projections scan their own tiles):
+    // amax_atomic: ABSMAX_SLOTS words gathered with atomics, directly before fdesc so that one range is
+    // cleared; amax_slots: [P] Bbar, [H] Cc, then 2 x PREP_PASS_BLOCKS and 2 x amax_cd words of the passes
+    size_t amax_atomic, amax_slots; int amax_cd;
 };
 
 ssm_status check_dims(int64_t Bt, int64_t L, int64_t H, int64_t P)
@@ -49,9 +53,14 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
     o.desc = off; off += up(o.plan.desc_bytes);
     o.xbuf = o.chi = o.dCpart = o.dBpart = o.dApart = o.dDpart = o.fdesc = o.fdesc_bytes = 0;
     size_t dA_elems = o.plan.partial_elems;
+    o.amax_atomic = o.amax_slots = 0; o.amax_cd = 0;
     if (gemm_scan_shape_ok(Bt, L, P)) {              // tagged words of a projection that scans its own output
+        static_assert(ABSMAX_SLOTS * 4 % ALIGN == 0, "the atomic slots and the tagged words are cleared as one range");
+        o.amax_atomic = off; off += ABSMAX_SLOTS * 4;
         o.fdesc_bytes = gemm_scan_desc_bytes(Bt, L, P);
         o.fdesc = off; off += up(o.fdesc_bytes);
+        o.amax_cd = o.nslab * (int)((H + 63) / 64);
+        o.amax_slots = off; off += up((size_t)(P + H + 2 * PREP_PASS_BLOCKS + 2 * o.amax_cd) * 4);
         const size_t per_tile = (size_t)(Bt * L / 128) * P;        // one dAbar row per 128-row tile
         if (per_tile > dA_elems) dA_elems = per_tile;
     }
@@ -69,6 +78,14 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
     }
     o.total = off;
     return SSM_OK;
+}
+
+// pieces of the pass that measures the largest magnitude of n floats (each workgroup takes whole
+// rounds of 256 float4 units)
+inline int pass_pieces(size_t n)
+{
+    const size_t rounds = (n / 4 + 256 * 4 - 1) / (256 * 4);
+    return (int)(rounds < 1 ? 1 : (rounds > (size_t)PREP_PASS_BLOCKS ? (size_t)PREP_PASS_BLOCKS : rounds));
 }
 
 inline bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
@@ -144,7 +161,17 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     pa.C = reinterpret_cast<const float2 *>(C); pa.log_delta = log_delta;
     pa.P = (int)P; pa.H = (int)H; pa.lam_bar = lam; pa.Bbar_ri = Bri; pa.Cc = Cc; pa.Bbar_c64 = nullptr;
     pa.hdr = (fused || lo.plan.nTB == 1) ? hdr : nullptr;
-    if (fused && lo.fdesc_bytes) { pa.zero16 = reinterpret_cast<uint4 *>(ws + lo.fdesc); pa.n16 = lo.fdesc_bytes / 16; }
+    // the atomic slots and the tagged words behind them are cleared in the same launch
+    if (fused) { pa.zero16 = reinterpret_cast<uint4 *>(ws + lo.amax_atomic); pa.n16 = (ABSMAX_SLOTS * 4 + lo.fdesc_bytes) / 16; }
+    // two scaled fp16 planes per operand: every operand of the two products brings its largest magnitude
+    const bool two_planes = fused && gemm_two_planes_enabled();
+    unsigned *am_atomic = reinterpret_cast<unsigned *>(ws + lo.amax_atomic);
+    unsigned *am_bbar = reinterpret_cast<unsigned *>(ws + lo.amax_slots), *am_cc = am_bbar + P, *am_pass = am_cc + H;
+    const int u_pieces = pass_pieces((size_t)T * H);
+    if (two_planes) {
+        pa.bbar_max = am_bbar; pa.cc_max = am_cc;
+        pa.pass[0].x = u; pa.pass[0].n = (size_t)T * H; pa.pass[0].slots = am_pass; pa.pass[0].nblocks = u_pieces;
+    }
     HIP_TRY(launch_prep(pa, s));
     MARK();
 
@@ -160,6 +187,10 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
         g1.scan.x0 = reinterpret_cast<const float2 *>(x0); g1.scan.x_last = reinterpret_cast<float2 *>(x_last);
         g1.scan.desc = reinterpret_cast<unsigned long long *>(ws + lo.fdesc); g1.scan.err = &hdr->err;
         g1.scan.L = (int)L; g1.scan.P = (int)P; g1.scan.spin_limit = spin_limit();
+        if (two_planes) {
+            g1.amaxA = AbsMax{am_pass, u_pieces}; g1.amaxB = AbsMax{am_bbar, (int)P};
+            g1.scan.amax_out = am_atomic;                    // of the states, for the output projection
+        }
     }
     HIP_TRY(launch_gemm(g1, s));
     MARK();
@@ -181,6 +212,7 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     g2.A = reinterpret_cast<const float *>(xs); g2.lda = 2 * P; g2.a_kcontig = 1;
     g2.B = Cc; g2.ldb = 2 * P; g2.b_kcontig = 1;
     g2.M = T; g2.N = (int)H; g2.K = (int)(2 * P);
+    if (two_planes) { g2.amaxA = AbsMax{am_atomic, ABSMAX_SLOTS}; g2.amaxB = AbsMax{am_cc, (int)H}; }
     if (lo.yhalves && gemm_out_split(T, H, P)) {
         // too few 128x128 tiles for the chip: two K halves into two slabs, then one streaming pass
         float *halves = reinterpret_cast<float *>(ws + lo.yhalves);
@@ -243,9 +275,22 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     pa.C = reinterpret_cast<const float2 *>(C); pa.log_delta = log_delta;
     pa.P = (int)P; pa.H = (int)H; pa.lam_bar = lam; pa.Bbar_ri = Bri; pa.Cc = Cc; pa.Bbar_c64 = nullptr;
     pa.hdr = (fused || lo.plan.nTB == 1) ? hdr : nullptr;
-    if (fused && lo.fdesc_bytes) { pa.zero16 = reinterpret_cast<uint4 *>(ws + lo.fdesc); pa.n16 = lo.fdesc_bytes / 16; }
+    if (fused) { pa.zero16 = reinterpret_cast<uint4 *>(ws + lo.amax_atomic); pa.n16 = (ABSMAX_SLOTS * 4 + lo.fdesc_bytes) / 16; }
     // dD slabs: sum_t dy[t,h] u[t,h] over row slabs, in the same launch
     pa.cd.a = dy; pa.cd.b = u; pa.cd.T = T; pa.cd.H = (int)H; pa.cd.nslab = lo.nslab; pa.cd.partial = dDpart;
+    // two scaled fp16 planes per operand: dy and u are measured where dD reads them, the saved states
+    // by a pass of their own, chi where the reverse scan stores it
+    const bool two_planes = fused && gemm_two_planes_enabled();
+    unsigned *am_atomic = reinterpret_cast<unsigned *>(ws + lo.amax_atomic);
+    unsigned *am_bbar = reinterpret_cast<unsigned *>(ws + lo.amax_slots), *am_cc = am_bbar + P, *am_pass = am_cc + H;
+    unsigned *am_dy = am_pass + 2 * PREP_PASS_BLOCKS, *am_u = am_dy + lo.amax_cd;
+    const int x_pieces = pass_pieces((size_t)T * 2 * P);
+    if (two_planes) {
+        pa.bbar_max = am_bbar; pa.cc_max = am_cc; pa.cd_amax = am_dy; pa.cd_bmax = am_u;
+        pa.pass[0].x = xf; pa.pass[0].n = (size_t)T * 2 * P; pa.pass[0].slots = am_pass; pa.pass[0].nblocks = x_pieces;
+    }
+    const AbsMax mx_dy{am_dy, lo.amax_cd}, mx_u{am_u, lo.amax_cd}, mx_x{am_pass, x_pieces}, mx_chi{am_atomic, ABSMAX_SLOTS},
+                 mx_bbar{am_bbar, (int)P}, mx_cc{am_cc, (int)H};
     HIP_TRY(launch_prep(pa, s));
     MARK();
 
@@ -263,6 +308,7 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
         g3.scan.dx0 = reinterpret_cast<float2 *>(dx0);
         g3.scan.desc = reinterpret_cast<unsigned long long *>(ws + lo.fdesc); g3.scan.err = &hdr->err;
         g3.scan.L = (int)L; g3.scan.P = (int)P; g3.scan.spin_limit = spin_limit();
+        if (two_planes) { g3.amaxA = mx_dy; g3.amaxB = mx_cc; g3.scan.amax_out = am_atomic; }
     }
     // dC slabs: [h, 2p+c] = sum_t dy[t,h] * x[t, 2p+c]    (needs only saved states: same launch)
     GemmArgs g4{};
@@ -270,6 +316,7 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     g4.B = xf; g4.ldb = 2 * P; g4.b_kcontig = 0;
     g4.C = dCpart; g4.ldc = 2 * P;
     g4.M = (int)H; g4.N = (int)(2 * P); g4.K = T; g4.splits = lo.splitC;
+    if (two_planes) { g4.amaxA = mx_dy; g4.amaxB = mx_x; }
     HIP_TRY(launch_gemm_pair(g3, g4, s));
     MARK();
 
@@ -299,6 +346,7 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     g6.B = u; g6.ldb = H; g6.b_kcontig = 0;
     g6.C = dBpart; g6.ldc = H;
     g6.M = (int)(2 * P); g6.N = (int)H; g6.K = T; g6.splits = lo.splitB;
+    if (two_planes) { g5.amaxA = mx_chi; g5.amaxB = mx_bbar; g6.amaxA = mx_chi; g6.amaxB = mx_u; }
     if (lo.yhalves && gemm_out_split(T, H, P)) {
         // du has too few 128x128 tiles for half a chip's worth of time: it runs as two K halves (twice
         // the workgroups, half as long) next to the long work items of the dBbar slabs, which start first;

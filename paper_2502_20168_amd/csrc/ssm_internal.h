@@ -27,6 +27,14 @@ namespace ssm {
 // operator of Eq. 10) over the rows of the output tile itself, so that the input projection stores
 // the states x directly and Bbar u never goes to memory.  Rows are tokens (Bt sequences of L steps,
 // L a multiple of the 128-row tile), columns (re, im) pairs of P states.
+// Largest magnitude of a matrix, kept as n bit patterns of non-negative floats whose maximum it is
+// (written by the kernel that produced the matrix, or by a pass over it).  A product whose two
+// operands both carry one may stage them as two scaled fp16 planes (see gemm_bf16x3_kernel.h).
+constexpr int ABSMAX_SLOTS = 512;            // slots of a maximum that is gathered with atomics
+struct AbsMax {
+    const unsigned *slots; int n;            // slots == nullptr: not known
+};
+
 struct ScanEpilogue {
     const float2 *lam;            // [P] Abar
     const uint8_t *is_first;      // [Bt*L] or null
@@ -37,6 +45,7 @@ struct ScanEpilogue {
     float2 *dx0;                  // [Bt, P] or null (reverse)
     unsigned long long *desc;     // [M/128 * ceil(N/128) * 64][2] tagged aggregate words, zero on entry
     unsigned *err;                // set when a bounded wait gives up
+    unsigned *amax_out;           // [ABSMAX_SLOTS] or null: atomic maximum of the magnitudes stored to C, zero on entry
     int L, P;
     unsigned spin_limit;
 };
@@ -50,6 +59,7 @@ struct GemmArgs {
     const float *E2; const float *E3; float *C2;     // epilogues 3 and 4 (gate), pitch lde / ldc
     int M, N, K, splits;
     ScanEpilogue scan;                               // epilogues 7 and 8
+    AbsMax amaxA, amaxB;                             // largest magnitudes of A and B when known
 };
 // the input projection can scan its own output (epilogue 7) for this shape (shape only), and
 // whether it will on this call (shape and environment)
@@ -59,6 +69,8 @@ bool gemm_can_scan(int64_t Bt, int64_t L, int64_t P);
 bool gemm_can_scan_reverse(int64_t Bt, int64_t L, int64_t P);
 // bytes of tagged words epilogues 7 and 8 need (zeroed before the launch)
 size_t gemm_scan_desc_bytes(int64_t Bt, int64_t L, int64_t P);
+// products may use the two-plane fp16 staging when their operands carry their largest magnitude
+bool gemm_two_planes_enabled();
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t s);
 // the output projection as two K halves into two slabs plus a streaming sum: possible for this
 // shape (shape only), and taken on this call (shape and environment)
@@ -150,7 +162,14 @@ struct PrepArgs {
     int cd_colblocks;        // set by launch_prep
     uint4 *zero16; size_t n16;   // region to clear in the same launch (tagged words of epilogue 7), may be null
     int zero_block0;         // set by launch_prep: first workgroup of the clearing range
+    // largest magnitudes for the two-plane fp16 staging of the products (all may be null):
+    unsigned *bbar_max;      // [P]: of the rows 2p, 2p+1 of Bbar_ri
+    unsigned *cc_max;        // [H]: of row h of Cc
+    unsigned *cd_amax, *cd_bmax;   // [cd.nslab * ceil(cd.H/64)]: of the pieces of cd.a and cd.b
+    struct Pass { const float *x; size_t n; unsigned *slots; int nblocks, block0, vec; } pass[2];
+                             // slots[nblocks]: of nblocks pieces of x[n]; block0 and vec set by launch_prep
 };
+constexpr int PREP_PASS_BLOCKS = 256;
 hipError_t launch_prep(const PrepArgs &a, hipStream_t s);
 
 
