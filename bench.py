@@ -39,9 +39,9 @@ BF16_PRODUCTS = 6              # bf16 MFMA products the GEMM issues per fp32 mul
 #   Re(Bbar^H chi) as two K halves + the dBbar slabs: 60.9 MiB read (chi 16 + Bbar 2 per XCD; chi 16 + u 8),
 #     24.3 MiB written (two du slabs 16 + four dBbar slabs 8)
 TRAFFIC = {
-    "33,0": {"read_bytes": 67.4e6, "write_bytes": 34.5e6, "algorithmic_read_bytes": 52.4e6,
+    "33,0": {"read_bytes": 67.6e6, "write_bytes": 34.5e6, "algorithmic_read_bytes": 52.4e6,
              "algorithmic_write_bytes": 33.6e6, "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, see profiles/"},
-    "1,0": {"read_bytes": 63.9e6, "write_bytes": 25.5e6, "algorithmic_read_bytes": 44.0e6,
+    "1,0": {"read_bytes": 64.2e6, "write_bytes": 25.5e6, "algorithmic_read_bytes": 44.0e6,
             "algorithmic_write_bytes": 25.2e6, "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, see profiles/"},
 }
 
@@ -119,10 +119,11 @@ def main():
                  "p90_us": round(float(per_step[int(0.9 * (len(per_step) - 1))]), 1),
                  "note": "HIP events around every single step (forward + gradient pass)"}
 
-    # ---- the opt-in reduced-precision mode of the projections, timed the same way (never `value`)
-    two_plane = None
-    if not args.path_only and os.environ.get("SSM_GEMM_F32", "") != "1" and os.environ.get("SSM_GEMM_SPLIT", "") != "2":
-        os.environ["SSM_GEMM_SPLIT"] = "2"
+    # ---- the same step with the three-way bf16 split in every product (SSM_GEMM_SPLIT=3), timed the same
+    # way, for comparison with the default (two scaled fp16 planes where the projections scan their tiles)
+    three_plane = None
+    if not args.path_only and os.environ.get("SSM_GEMM_F32", "") != "1" and os.environ.get("SSM_GEMM_SPLIT", "") != "3":
+        os.environ["SSM_GEMM_SPLIT"] = "3"
         try:
             for _ in range(args.warmup):
                 step()
@@ -131,12 +132,12 @@ def main():
             for _ in range(args.steps):
                 step()
             torch.cuda.synchronize()
-            ms2 = (time.perf_counter() - t0) / args.steps * 1e3
+            ms3 = (time.perf_counter() - t0) / args.steps * 1e3
         finally:
             os.environ.pop("SSM_GEMM_SPLIT", None)
-        two_plane = {"ms_per_step": round(ms2, 4), "Mtokens_per_s": round(T / (ms2 * 1e-3) / 1e6, 3),
-                     "note": "SSM_GEMM_SPLIT=2: two bf16 planes per operand, three products (a product good to 2^-16 "
-                             "instead of 2^-23); opt-in, inside the 1e-4 / 1e-3 tolerances, not the headline value"}
+        three_plane = {"ms_per_step": round(ms3, 4), "Mtokens_per_s": round(T / (ms3 * 1e-3) / 1e6, 3),
+                       "note": "SSM_GEMM_SPLIT=3: three bf16 planes per operand and six products in every projection "
+                               "(the default uses them only where an operand's largest magnitude is not known)"}
         step()                                              # leave the default-mode results in the output buffers
         torch.cuda.synchronize()
 
@@ -159,8 +160,12 @@ def main():
                    and (T // 128) * ((2 * P + 127) // 128) >= 200 and not f32_path)
     fwd_fused = shape_scans and fused_env != "0"
     rev_fused = shape_scans and fused_env not in ("0", "1")
-    npl = 2 if os.environ.get("SSM_GEMM_SPLIT", "") == "2" else 3
-    kern = lambda tile, lay0, lay1: "gemm_bf16x3_ws_kernel<%s,2,2,8,2,%d,%d,%d>" % (tile, npl, lay0, lay1)
+    # two scaled fp16 planes where the pass's projection scans its own tiles (every operand then comes
+    # with its largest magnitude), three bf16 planes otherwise
+    split3 = os.environ.get("SSM_GEMM_SPLIT", "") == "3"
+    npl_f = 2 if (fwd_fused and not split3) else 3
+    npl_b = 2 if (rev_fused and not split3) else 3
+    kern = lambda tile, lay0, lay1, npl: "gemm_bf16x3_ws_kernel<%s,2,2,8,2,%d,%d,%d>" % (tile, npl, lay0, lay1)
     big = (T // 128) * ((2 * P + 127) // 128) >= 200
     t128 = ((T + 127) // 128) * ((H + 127) // 128)
     out_split = (not f32_path and t128 < 200 and 2 * t128 >= 200 and P >= 256 and (2 * P) % 64 == 0
@@ -171,24 +176,24 @@ def main():
     # every launch of the projection kernel in one step: role, instantiation, fp32 flops, duration
     launches = [
         {"role": "input projection" + (" + forward scan in the tile" if fwd_fused else ""),
-         "kernel": kern(in_tile, 31 if fwd_fused else 3, -1), "gemms": 1, "ms": fs[1]},
+         "kernel": kern(in_tile, 31 if fwd_fused else 3, -1, npl_f), "npl": npl_f, "gemms": 1, "ms": fs[1]},
         ({"role": "output projection as two K halves into two slabs (a streaming kernel adds them and D u)",
-          "kernel": kern("128,128,32", 3, -1), "gemms": 1, "ms": fs[3]} if out_split else
-         {"role": "output projection + D u", "kernel": kern(out_tile, 7, -1), "gemms": 1, "ms": fs[3]}),
+          "kernel": kern("128,128,32", 3, -1, npl_f), "npl": npl_f, "gemms": 1, "ms": fs[3]} if out_split else
+         {"role": "output projection + D u", "kernel": kern(out_tile, 7, -1, npl_f), "npl": npl_f, "gemms": 1, "ms": fs[3]}),
         {"role": "C^H dy" + (" + reverse scan in the tile" if rev_fused else "") + " and the dC slabs, one launch",
-         "kernel": kern("128,128,32", 33 if rev_fused else 1, 0), "gemms": 2, "ms": bs[1]},
+         "kernel": kern("128,128,32", 33 if rev_fused else 1, 0, npl_b), "npl": npl_b, "gemms": 2, "ms": bs[1]},
         ({"role": "Re(Bbar^H chi) as two K halves and the dBbar slabs, one launch (a streaming kernel adds the halves and D dy)",
-          "kernel": kern("128,128,32", 1, 0), "gemms": 2, "ms": bs[3]} if out_split else
+          "kernel": kern("128,128,32", 1, 0, npl_b), "npl": npl_b, "gemms": 2, "ms": bs[3]} if out_split else
          {"role": "Re(Bbar^H chi) + D dy and the dBbar slabs, one launch",
-          "kernel": kern("128,128,32", 5, 0), "gemms": 2, "ms": bs[3]}),
+          "kernel": kern("128,128,32", 5, 0, npl_b), "npl": npl_b, "gemms": 2, "ms": bs[3]}),
     ]
     for l in launches:
         l["fp32_flops"] = l["gemms"] * gemm_flops
         l["fp32_equivalent_tflops"] = round(l["fp32_flops"] / (l["ms"] * 1e-3) / 1e12, 2)
         l["us"] = round(float(l.pop("ms")) * 1e3, 2)
     # Dominant kernel = the launch of gemm_bf16x3_ws_kernel with the largest share of the step.  Its
-    # algorithmic work: the six bf16 partial products per multiply-add that the exact three-way
-    # split needs (three in the opt-in two-plane mode).
+    # algorithmic work: the partial products per multiply-add that its operand split needs (three
+    # fp16 ones with two scaled planes, six bf16 ones with three planes).
     dom = max(launches, key=lambda l: l["us"])
     dom_fp32_tflops = dom["fp32_flops"] / (dom["us"] * 1e-6) / 1e12
     if f32_path:
@@ -196,24 +201,26 @@ def main():
                     "bound": "mfma", "achieved": round(dom_fp32_tflops, 2), "peak": PEAK_FP32_MFMA_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(dom_fp32_tflops / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": None}
     else:
+        npl = dom["npl"]
         products = 3 if npl == 2 else BF16_PRODUCTS
         ach = products * dom_fp32_tflops
         lay = dom["kernel"].rstrip(">").split(",")[-2] + "," + dom["kernel"].rstrip(">").split(",")[-1]
-        known = TRAFFIC.get(lay) if (npl == 3 and args.config == 2 and fused_env == "" and out_split and
+        known = TRAFFIC.get(lay) if (npl == 2 and args.config == 2 and fused_env == "" and out_split and
                                      dom["kernel"].startswith("gemm_bf16x3_ws_kernel<128,128,32")) else None
         roofline = {"kernel": "%s (%s)" % (dom["kernel"], dom["role"]),
                     "bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(ach / PEAK_BF16_MFMA_TFLOPS, 4),
                     "traffic": (known["read_bytes"] + known["write_bytes"]) if known else None,
                     "traffic_detail": known,
-                    "note": "achieved counts the %d bf16 MFMA products per fp32 multiply-add that the kernel "
-                            "executes by design; fp32-equivalent rate and its ratio to the fp32 matrix peak below" % products,
+                    "note": "achieved counts the %d %s MFMA products per fp32 multiply-add that the kernel executes by "
+                            "design (peak: the dense fp16 / bf16 matrix rate, the same for both); fp32-equivalent rate "
+                            "and its ratio to the fp32 matrix peak below" % (products, "fp16" if npl == 2 else "bf16"),
                     "fp32_equivalent_tflops": round(dom_fp32_tflops, 2),
                     "fp32_equivalent_over_fp32_matrix_peak": round(dom_fp32_tflops / PEAK_FP32_MFMA_TFLOPS, 4)}
     roofline.update({"flops_per_launch_fp32": dom["fp32_flops"], "avg_launch_us": dom["us"],
                      "all_launches": launches})
     if not f32_path:
-        roofline["measured_matrix_only"] = mfma_only_rate(ssm, torch, dom["us"])
+        roofline["measured_matrix_only"] = mfma_only_rate(ssm, torch, dom["us"], dom["npl"] == 2)
         roofline["frac_of_measured_matrix_only"] = round(
             roofline["achieved"] / roofline["measured_matrix_only"]["launch_like_the_dominant_one"]["TFLOPs"], 4)
 
@@ -241,7 +248,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32",
         "arith": "fp32 I/O and accumulation; projections on " + ("fp32 MFMA" if f32_path else
-                 "bf16 MFMA with an exact 3-way bf16 split of both operands (fp32-class accuracy)"),
+                 ("fp16 MFMA on two scaled fp16 planes per operand (three products, fp32-class accuracy)"
+                  if (npl_f == 2 and npl_b == 2) else
+                  "bf16 MFMA with an exact 3-way bf16 split of both operands (fp32-class accuracy)")),
         "data": "synthetic",
         "config": {"workload": "%s: Bt=%d L=%d H=%d P=%d fwd+bwd, fp32 I/O, complex64 state, seed %d"
                                % (w.name, Bt, L, H, P, w.seed), "tokens_per_step": T},
@@ -251,7 +260,7 @@ def main():
                           "frac_of_hbm_peak": round(compulsory_bytes(Bt, L, H, P) / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                           "note": "whole forward + gradient pass against the HBM peak, for reference only: the path "
                                   "is matrix-core bound (about 290 flop per compulsory byte at this shape)"},
-        "reduced_precision_mode": two_plane,
+        "three_plane_mode": three_plane,
     }
     if not args.path_only:
         result["block_ops"] = block_ops(ssm, torch, wl, T, H)
@@ -262,7 +271,7 @@ def main():
     print(json.dumps(result))
 
 
-def mfma_only_rate(ssm, torch, dom_us):
+def mfma_only_rate(ssm, torch, dom_us, fp16):
     """The projection kernel's matrix-instruction stream alone (ssm_mfma_probe: one wavefront per SIMD
     on all 256 CUs, register operands with changing bits): what the matrix cores sustain on this
     device, at the clock they hold under that load, for a launch as long as the dominant one and for
@@ -273,19 +282,19 @@ def mfma_only_rate(ssm, torch, dom_us):
     # 24 matrix instructions of 8 passes take 768 cycles: about 0.4 us per iteration
     for label, iters in (("launch_like_the_dominant_one", max(8, int(dom_us / 0.42))), ("long_launch", 4000)):
         for _ in range(3):
-            ssm.ssm_mfma_probe(256, iters, out=out)
+            ssm.ssm_mfma_probe(256, iters, fp16=fp16, out=out)
         torch.cuda.synchronize()
         reps = 10
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(reps):
-            ssm.ssm_mfma_probe(256, iters, out=out)
+            ssm.ssm_mfma_probe(256, iters, fp16=fp16, out=out)
         e1.record()
         torch.cuda.synchronize()
         us = e0.elapsed_time(e1) * 1e3 / reps
         res[label] = {"iters": iters, "us": round(us, 2), "TFLOPs": round(flops_per_iter * iters / (us * 1e-6) / 1e12, 1)}
-    res["note"] = ("bf16 32x32x16 matrix instructions only, 256 workgroups x 4 wavefronts; includes the launch; "
-                   "the published peak assumes 2.4 GHz")
+    res["note"] = ("%s 32x32x16 matrix instructions only, 256 workgroups x 4 wavefronts; includes the launch; "
+                   "the published peak assumes 2.4 GHz" % ("fp16" if fp16 else "bf16"))
     return res
 
 

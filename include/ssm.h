@@ -28,10 +28,13 @@
  *   - Gradient of the real loss l w.r.t. a complex quantity q is returned as
  *     dl/dRe(q) + i dl/dIm(q).
  *   - Five environment variables are read at call time: SSM_GEMM_F32=1 runs the projections on
- *     the fp32 matrix instruction instead of the (equally accurate, faster) three-way bf16 split;
- *     SSM_GEMM_SPLIT=2 is an opt-in reduced-precision mode of the projections (two bf16 planes per
- *     operand, three partial products: a product is good to 2^-16 instead of 2^-23; results stay
- *     inside the 1e-4 / 1e-3 tolerances of the benchmark configurations, the default is 3);
+ *     the fp32 matrix instruction instead of the (equally accurate, faster) split operands;
+ *     SSM_GEMM_SPLIT=3 stages every operand of every projection as three bf16 planes (six partial
+ *     products) -- by default the products of ssm_scan_fwd / ssm_scan_bwd at the shapes named under
+ *     SSM_FUSED_SCAN below, where the largest magnitude of every operand is measured on the device,
+ *     stage two fp16 planes of the operand scaled into the fp16 range by a power of two (three
+ *     partial products, errors at the level of fp32 products; an element more than 2^17 below the
+ *     largest magnitude of its matrix is held with an absolute error of 2^-39 of that magnitude);
  *     SSM_SPIN_LIMIT=<n> bounds the polls of a cross-workgroup wait in the scan (default 2^20);
  *     SSM_FUSED_SCAN selects where the scans run when every sequence is a whole number of 128-step
  *     tiles (L % 128 == 0, L <= 4096) or every 128 tokens are whole sequences (L = 16, 32, 64 with
@@ -236,12 +239,14 @@ ssm_status ssm_block_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 
                          ssm_c64 *dx0, float *dW, void *workspace, size_t ws_bytes, void *stream);
 
 /* Measurement aid for the roofline of the projection kernel (no operation of the paper): launches
- * `workgroups` workgroups of four wavefronts that issue nothing but the bf16 matrix instructions of
- * the projection kernel's inner loop (24 v_mfma_f32_32x32x16_bf16 per iteration and wavefront, on
- * register operands whose bits change every iteration) for `iters` iterations.  The caller times
- * the launch; the work is workgroups * 4 * iters * 24 * 2*32*32*16 flops.  out: device, at least
- * workgroups * 256 floats (receives checksums).  workgroups <= 65536, iters <= 2^24.              */
-ssm_status ssm_mfma_probe(int64_t workgroups, int64_t iters, float *out, void *stream);
+ * `workgroups` workgroups of four wavefronts that issue nothing but the matrix instructions of the
+ * projection kernel's inner loop (24 per iteration and wavefront, on register operands whose bits
+ * change every iteration) for `iters` iterations: v_mfma_f32_32x32x16_bf16 in the order of the
+ * three-plane split (fp16 == 0) or v_mfma_f32_32x32x16_f16 in the order of the two-plane one
+ * (fp16 != 0).  The caller times the launch; the work is workgroups * 4 * iters * 24 * 2*32*32*16
+ * flops.  out: device, at least workgroups * 256 floats (receives checksums).
+ * workgroups <= 65536, iters <= 2^24.                                                             */
+ssm_status ssm_mfma_probe(int64_t workgroups, int64_t iters, int fp16, float *out, void *stream);
 
 /* Measurement aids: the same code path as ssm_scan_fwd / ssm_scan_bwd, with a HIP event recorded
  * on `stream` around every kernel.  They wait for the stream before returning and write the

@@ -93,7 +93,7 @@ def lib():
         L.ssm_half_glu_bwd.restype = ctypes.c_int
         L.ssm_half_glu_bwd.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _vp, _vp, _vp, _sz, _vp]
         L.ssm_mfma_probe.restype = ctypes.c_int
-        L.ssm_mfma_probe.argtypes = [_i64, _i64, _vp, _vp]
+        L.ssm_mfma_probe.argtypes = [_i64, _i64, ctypes.c_int, _vp, _vp]
         L.ssm_block_workspace_bytes.restype = _sz
         L.ssm_block_workspace_bytes.argtypes = [_i64, _i64, _i64, _i64, ctypes.c_int]
         L.ssm_block_fwd.restype = ctypes.c_int
@@ -366,14 +366,15 @@ def ssm_lambda_return_bwd(cont, value, ret, dret, gamma: float, lam: float, *, s
     return dr, dc, dv
 
 
-def ssm_mfma_probe(workgroups: int, iters: int, *, out=None, stream=None):
-    """Launches the matrix-instruction-only probe; returns the checksum tensor [workgroups * 256]."""
+def ssm_mfma_probe(workgroups: int, iters: int, *, fp16: bool = False, out=None, stream=None):
+    """Launches the matrix-instruction-only probe (bf16 instructions, or fp16 ones); returns the checksum
+    tensor [workgroups * 256]."""
     torch = _torch()
     if out is None:
         out = torch.empty(max(int(workgroups), 1) * 256, dtype=torch.float32, device="cuda")
     if not out.is_cuda or out.dtype != torch.float32 or not out.is_contiguous() or out.numel() < int(workgroups) * 256:
         raise ValueError("out must be a contiguous cuda float32 tensor of at least workgroups * 256 elements")
-    rc = lib().ssm_mfma_probe(int(workgroups), int(iters), _ptr(out), _stream(stream))
+    rc = lib().ssm_mfma_probe(int(workgroups), int(iters), 1 if fp16 else 0, _ptr(out), _stream(stream))
     if rc != SSM_OK:
         raise SsmError(rc, "ssm_mfma_probe")
     return out
@@ -423,7 +424,7 @@ def ssm_half_glu_bwd(u, W, gate, dy, *, workspace=None, du=None, dW=None, stream
     rc = lib().ssm_half_glu_bwd(_ptr(u), _ptr(W), _ptr(gate), _ptr(dy), T, H, _ptr(du), _ptr(dW), _ptr(ws), ws.numel(),
                                 _stream(stream))
     if rc != SSM_OK:
-        raise SsmError(rc, "ssm_half_glu_bwd", "ssm_block_workspace_bytes", "ssm_block_fwd", "ssm_block_bwd", "ssm_mfma_probe")
+        raise SsmError(rc, "ssm_half_glu_bwd")
     return du, dW
 
 

@@ -1,4 +1,5 @@
-// fp32-accurate GEMM on the bf16 matrix cores of gfx950 (three-way operand split).
+// fp32-accurate GEMM on the 16-bit matrix cores of gfx950: three-way bf16 operand split, or two
+// scaled fp16 planes where the largest magnitude of both operands is known (see split2_f16).
 //
 //   C[m,n] = sum_k A(m,k) * B(n,k)  (+ diag[n] * E[m,n]),   A, B, C fp32
 //

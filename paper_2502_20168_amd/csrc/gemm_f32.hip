@@ -1,8 +1,11 @@
 // Tile selection and launch of the projection GEMMs.
 //
 // Two kernels compute the same fp32-in / fp32-out product:
-//   * gemm_bf16x3_ws_kernel (default): exact three-way bf16 split of both operands, six bf16
-//     MFMAs per k block accumulated in fp32 -- fp32-class accuracy at 2.7x the fp32 matrix rate;
+//   * gemm_bf16x3_ws_kernel (default): both operands split while they are staged -- exactly into
+//     three bf16 planes (six bf16 MFMAs per k block), or, when the largest magnitude of both operands
+//     is known, into two fp16 planes of the operand scaled by a power of two (three fp16 MFMAs per
+//     k block); fp32 accumulation and fp32-class accuracy either way, at several times the fp32
+//     matrix rate;
 //   * gemm_f32_kernel: plain fp32 MFMA, selected with the environment variable SSM_GEMM_F32=1
 //     (kept as the reference point for the measurement of the default kernel).
 #include "gemm_bf16x3_kernel.h"

@@ -169,11 +169,11 @@ def test_s5_block_argument_errors(lib):
 
 
 def test_mfma_probe_argument_errors(lib):
-    assert lib.ssm_mfma_probe(256, 10, None, None) == ssm.SSM_ERR_INVALID_ARG
-    assert lib.ssm_mfma_probe(0, 10, FAKE, None) == ssm.SSM_ERR_INVALID_ARG
-    assert lib.ssm_mfma_probe(256, 0, FAKE, None) == ssm.SSM_ERR_INVALID_ARG
-    assert lib.ssm_mfma_probe(65537, 10, FAKE, None) == ssm.SSM_ERR_UNSUPPORTED
-    assert lib.ssm_mfma_probe(256, (1 << 24) + 1, FAKE, None) == ssm.SSM_ERR_UNSUPPORTED
+    assert lib.ssm_mfma_probe(256, 10, 0, None, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_mfma_probe(0, 10, 0, FAKE, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_mfma_probe(256, 0, 0, FAKE, None) == ssm.SSM_ERR_INVALID_ARG
+    assert lib.ssm_mfma_probe(65537, 10, 0, FAKE, None) == ssm.SSM_ERR_UNSUPPORTED
+    assert lib.ssm_mfma_probe(256, (1 << 24) + 1, 0, FAKE, None) == ssm.SSM_ERR_UNSUPPORTED
 
 
 def test_binding_refuses_cpu_tensors(lib):

@@ -513,11 +513,12 @@ def test_matrix_instruction_probe_runs_and_is_repeatable():
     """The measurement aid behind the benchmark's matrix-core ceiling: finite checksums, the same on
     every run (its operands come from a counter-based hash, not from memory)."""
     import torch
-    a = ssm.ssm_mfma_probe(64, 50).clone()
-    b = ssm.ssm_mfma_probe(64, 50)
-    torch.cuda.synchronize()
-    assert a.shape == (64 * 256,) and bool(torch.isfinite(a).all()) and bool(a.abs().max() > 0)
-    assert torch.equal(a, b)
+    for fp16 in (False, True):
+        a = ssm.ssm_mfma_probe(64, 50, fp16=fp16).clone()
+        b = ssm.ssm_mfma_probe(64, 50, fp16=fp16)
+        torch.cuda.synchronize()
+        assert a.shape == (64 * 256,) and bool(torch.isfinite(a).all()) and bool(a.abs().max() > 0)
+        assert torch.equal(a, b)
 
 
 def test_two_stacked_layers_at_the_vision_shape():
