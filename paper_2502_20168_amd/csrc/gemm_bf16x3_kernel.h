@@ -95,6 +95,7 @@ __device__ __forceinline__ Split4 split_planes(float4 v, float s) { return NPL =
 // planes are zeros whatever the scale).  Two steps, so that the loads can be issued ahead of other
 // memory traffic and waited for behind it: absmax_issue starts eight independent loads per lane (the
 // first 512 slots), absmax_log2_scale reduces them (and walks the slots beyond 512, if any).
+__device__ __forceinline__ int log2_scale_of(unsigned maxbits);
 struct AbsMaxLoads { unsigned w[8]; };
 __device__ __forceinline__ AbsMaxLoads absmax_issue(const AbsMax &m, int lane)
 {
@@ -115,12 +116,36 @@ __device__ __forceinline__ int absmax_log2_scale(const AbsMax &m, const AbsMaxLo
     for (int i = 512 + lane; i < m.n; i += 64) v = max(v, m.slots[i]);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v = max(v, (unsigned)__shfl_xor((int)v, o));
-    const int e = (int)((v >> 23) & 0xffu);          // biased exponent of the maximum
-    int f = 268 - e;                                 // biased exponent of 2^(14 - (e - 127))
+    return log2_scale_of(v);     // (defined below) 14 - floor(log2(maximum)), kept inside the exponent range
+}
+__device__ __forceinline__ float pow2f(int e) { return __uint_as_float((unsigned)(e + 127) << 23); }   // e in [-127, 127]
+__device__ __forceinline__ int log2_scale_of(unsigned maxbits)
+{
+    const int e = (int)((maxbits >> 23) & 0xffu);
+    int f = 268 - e;
     f = f < 1 ? 1 : (f > 254 ? 254 : f);
     return f - 127;
 }
-__device__ __forceinline__ float pow2f(int e) { return __uint_as_float((unsigned)(e + 127) << 23); }   // e in [-127, 127]
+// The same for one row of an operand with per-row maxima (the first eight parts by independent loads).
+__device__ __forceinline__ AbsMaxLoads absmax_row_issue(const AbsMax &m, long row)
+{
+    AbsMaxLoads r;
+    const unsigned *p = m.rows + row;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const unsigned t = p[j < m.row_parts ? (size_t)j * m.row_stride : 0];
+        r.w[j] = j < m.row_parts ? t : 0u;
+    }
+    return r;
+}
+__device__ __forceinline__ int absmax_row_log2_scale(const AbsMax &m, const AbsMaxLoads &r, long row)
+{
+    unsigned v = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v = max(v, r.w[j]);
+    for (int j = 8; j < m.row_parts; ++j) v = max(v, m.rows[(size_t)j * m.row_stride + row]);
+    return log2_scale_of(v);
+}
 
 // Stages one R x BK fp32 operand tile: global -> registers (fp32) -> split -> NPL LDS planes.
 // A thread handles float4 units along the contiguous index of the source and writes the four
@@ -145,6 +170,9 @@ struct SplitLoader {
     {
         return (BK == 32 && R % 4 == 0) ? (g % (R / 4)) * 4 + g / (R / 4) : g;
     }
+
+    // k-contiguous source: the tile row that unit i of this thread belongs to
+    static __device__ __forceinline__ int unit_row(int tid, int i) { return kc_row((tid + i * NT) / (BK / 4)); }
 
     template <bool FAST>
     __device__ __forceinline__ void load(const float *__restrict__ X, long ld, int row0, int rows, int k0,
@@ -180,15 +208,15 @@ struct SplitLoader {
         }
     }
 
-    // scale: two-plane staging only (a power of two, see split2_f16)
-    __device__ __forceinline__ void store(__bf16 *lds, int tid, float scale) const
+    // scale[i]: two-plane staging only (a power of two for the i-th unit of the thread, see split2_f16)
+    __device__ __forceinline__ void store(__bf16 *lds, int tid, const float (&scale)[NV]) const
     {
 #pragma unroll
         for (int i = 0; i < NV; ++i) {
             const int idx = tid + i * NT;
             const int off = KC ? kc_row(idx / (BK / 4)) * S + 4 * (idx % (BK / 4))
                                : (idx / (R / 4)) * S + 4 * (idx % (R / 4));
-            const Split4 sp = split_planes<NPL>(r[i], scale);
+            const Split4 sp = split_planes<NPL>(r[i], scale[i]);
 #pragma unroll
             for (int s = 0; s < NPL; ++s) *reinterpret_cast<bf16x4 *>(lds + s * PLANE + off) = sp.p[s];
         }
@@ -244,6 +272,63 @@ constexpr size_t SCAN_LDS_BYTES = (size_t)SCAN_TILE * SCAN_TS * 4   // staged ti
                                   + SCAN_WAVES * 64 * 8 + SCAN_WAVES * 64 * 4   // chunk states and reset tags
                                   + SCAN_MAX_CHAIN * 64 * 8 + SCAN_MAX_CHAIN * 64 * 4   // predecessors
                                   + 64 * 8;                          // incoming state per lane
+
+// v[e], e < 16, per lane -> the maximum over the 64 lanes of v[rows16_index(lane)].  Two halving steps
+// inside every quad (lanes that differ in bit 0, then bit 1, swap the half of the remaining values
+// the other one keeps; data-parallel-primitive moves, no LDS), then the four values left per lane are
+// combined over the lanes with the same two low bits: rotations by 4 and 8 inside a row of 16, then
+// the two exchanges across rows (lane swaps).
+template <int CTRL>
+__device__ __forceinline__ unsigned dpp_move(unsigned v)
+{
+    return (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, CTRL, 0xf, 0xf, false);
+}
+// max(v, v of lane ^ 16) or max(v, v of lane ^ 32) with the lane-swap instructions of gfx950 (given the
+// same register twice, v_permlane16_swap / v_permlane32_swap return it and its copy from the partner row
+// or half): no LDS involved
+template <int X>
+__device__ __forceinline__ unsigned lane_xor_max(unsigned v)
+{
+    static_assert(X == 16 || X == 32, "rows of 16 lanes or halves of 32");
+    if constexpr (X == 16) {
+        const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+        return max((unsigned)r[0], (unsigned)r[1]);
+    } else {
+        const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+        return max((unsigned)r[0], (unsigned)r[1]);
+    }
+}
+__device__ __forceinline__ unsigned rows16_wave_max(unsigned (&v)[16], int lane)
+{
+    {
+        const bool up = lane & 1;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const unsigned keep = up ? v[k + 8] : v[k], send = up ? v[k] : v[k + 8];
+            v[k] = max(keep, dpp_move<0xb1>(send));                   // quad_perm [1,0,3,2]: lane ^ 1
+        }
+    }
+    {
+        const bool up = (lane >> 1) & 1;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const unsigned keep = up ? v[k + 4] : v[k], send = up ? v[k] : v[k + 4];
+            v[k] = max(keep, dpp_move<0x4e>(send));                   // quad_perm [2,3,0,1]: lane ^ 2
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        v[k] = max(v[k], dpp_move<0x124>(v[k]));                      // row_ror:4
+        v[k] = max(v[k], dpp_move<0x128>(v[k]));                      // row_ror:8
+        v[k] = lane_xor_max<16>(v[k]);
+        v[k] = lane_xor_max<32>(v[k]);
+    }
+    // lanes 4j .. 4j+3 (j < 4) hand out value j
+    const int j = (lane >> 2) & 3;
+    return j == 0 ? v[0] : (j == 1 ? v[1] : (j == 2 ? v[2] : v[3]));
+}
+// the row whose maximum lane `lane` (< 16) holds after rows16_wave_max
+__device__ __forceinline__ int rows16_index(int lane) { return ((lane >> 2) & 3) + 4 * ((lane >> 1) & 1) + 8 * (lane & 1); }
 
 struct ScanLds {
     float *tile; float2 *cS; unsigned *cAny; float2 *pS; unsigned *pAny; float2 *sX;
@@ -403,6 +488,7 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
     float2 xs = cfma(Aex, Xin, Sex);
     float2 *dst = reinterpret_cast<float2 *>(g.C) + (long)row0 * a.P + p;
     float amax = 0.f;                                        // largest magnitude this thread stores
+    unsigned rm[RC];                                         // and per step (row of the tile), for rowmax_out
     if (!REV) {
 #pragma unroll
         for (int e = 0; e < RC; ++e) {
@@ -410,7 +496,9 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
             const float2 le = make_float2(r ? 0.f : lam.x, r ? 0.f : lam.y);
             xs = cfma(le, xs, val[e]);
             if (active) dst[(long)e * a.P] = xs;
-            amax = fmaxf(amax, fmaxf(fabsf(xs.x), fabsf(xs.y)));
+            const float me = fmaxf(fabsf(xs.x), fabsf(xs.y));
+            rm[e] = active ? __float_as_uint(me) : 0u;
+            amax = fmaxf(amax, me);
         }
         if (active && a.x_last && t0 + RC == a.L) a.x_last[(long)b * a.P + p] = xs;
     } else {
@@ -436,7 +524,9 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
                 const float2 le = make_float2(r ? 0.f : lam.x, r ? 0.f : lam.y);
                 xs = cfma(le, xs, val[e]);
                 if (active) dst[(long)e * a.P] = xs;
-                amax = fmaxf(amax, fmaxf(fabsf(xs.x), fabsf(xs.y)));
+                const float me = fmaxf(fabsf(xs.x), fabsf(xs.y));
+                rm[e] = active ? __float_as_uint(me) : 0u;
+                amax = fmaxf(amax, me);
                 const bool m = (fmask >> e) & 1u;
                 const float2 qv = make_float2(m ? 0.f : xp[j].x, m ? 0.f : xp[j].y);
                 acc.x = fmaf(qv.x, xs.x, fmaf(qv.y, xs.y, acc.x));
@@ -452,6 +542,13 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
             for (int j = 0; j < NCH; ++j) { sum.x += lds.cS[j * 64 + c].x; sum.y += lds.cS[j * 64 + c].y; }
             a.partial[(size_t)(m0 / SCAN_TILE) * a.P + p] = sum;
         }
+    }
+    if (a.rowmax_out) {
+        // largest magnitude of every row within this column tile, stored as [column tile][row] (the consumer
+        // of C takes the maximum over the column tiles): lane l < 16 ends up with the row rows16_index(l) of
+        // the thread's 16
+        const unsigned r = rows16_wave_max(rm, c);
+        if (c < RC) a.rowmax_out[(size_t)tn * g.M + row0 + rows16_index(c)] = r;
     }
     if (a.amax_out) {
         // one atomic per workgroup, spread over ABSMAX_SLOTS addresses (the bit patterns of non-negative
@@ -476,6 +573,9 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
 // LDS holds NS stages; in iteration kt the producers fill the stage of tile kt+NS-1 while the
 // consumers work on tile kt, with one workgroup barrier per K tile.
 // ---------------------------------------------------------------------------------------------
+// Halves of LDS ahead of the stages: log2 of the scale of every row of the A tile (two-plane staging)
+constexpr int gemm_rowexp_halves(int BM, int NPL) { return NPL == 2 ? 2 * BM + 8 : 0; }   // BM + 1 ints, 16-byte multiple
+
 template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL, bool AKC, bool BKC, int EPI, bool FAST>
 __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *smem, int m0, int n0, int z,
                                                     int kbeg, int kend, int scan_tile)
@@ -488,6 +588,11 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
     using LB = SplitLoader<BN, BK, BKC, PT, NPL>;
     static_assert(NPL == 2 || NPL == 3, "three bf16 planes or two scaled fp16 planes per operand");
     constexpr int STAGE_A = NPL * LA::PLANE, STAGE_B = NPL * LB::PLANE, STAGE = STAGE_A + STAGE_B;
+    // two-plane staging: LDS starts with log2 of the scale of every row of the A tile and of B (BM + 1 ints),
+    // written by the producers before the first barrier and read by the consumers after the K loop
+    constexpr int ROWEXP_HALVES = gemm_rowexp_halves(BM, NPL);
+    __bf16 *stages = smem + ROWEXP_HALVES;
+    int *rowexp = reinterpret_cast<int *>(smem);
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int MI = WM / 32, NI = WN / 32;
     static_assert(MI >= 1 && NI >= 1 && WM % 32 == 0 && WN % 32 == 0 && BK % 16 == 0 && NS >= 2, "bad tile");
@@ -507,14 +612,26 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
             la[set].template load<FAST>(g.A, g.lda, m0, g.M, kbeg + t * BK, kend, ptid);
             lb[set].template load<FAST>(g.B, g.ldb, n0, g.N, kbeg + t * BK, kend, ptid);
         };
-        float sca = 1.f, scb = 1.f;
-        AbsMaxLoads ma, mb;
-        if constexpr (NPL == 2) {                 // ahead of the tile loads: returned first, waited for with tile 0
-            ma = absmax_issue(g.amaxA, tid & 63);
-            mb = absmax_issue(g.amaxB, tid & 63);
+        float sca[LA::NV], scb[LB::NV];
+#pragma unroll
+        for (int i = 0; i < LA::NV; ++i) sca[i] = 1.f;
+#pragma unroll
+        for (int i = 0; i < LB::NV; ++i) scb[i] = 1.f;
+        // Two-plane staging: log2 of the scales goes through LDS (rowexp[r], r < BM: row r of the A tile;
+        // rowexp[BM]: B).  The first producer wavefront reduces the one-per-matrix maxima, the first BM
+        // producer threads the per-row ones of A; their loads are issued ahead of the tile loads, so they
+        // return first and are waited for with tile 0.
+        AbsMaxLoads ma, mb, mr;
+        const bool arows = NPL == 2 && AKC && g.amaxA.rows != nullptr;      // every row of A has its own scale
+        if constexpr (NPL == 2) {
+            if (wave == NC) {
+                mb = absmax_issue(g.amaxB, tid & 63);
+                if (!arows) ma = absmax_issue(g.amaxA, tid & 63);
+            }
+            if (arows && ptid < BM) mr = absmax_row_issue(g.amaxA, min(m0 + ptid, g.M - 1));
         }
         auto stash = [&](int set, int t) {
-            __bf16 *st = smem + (t % NS) * STAGE;
+            __bf16 *st = stages + (t % NS) * STAGE;
             la[set].store(st, ptid, sca);
             lb[set].store(st + STAGE_A, ptid, scb);
         };
@@ -522,8 +639,21 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
         for (int j = 0; j < PF; ++j)
             if (j < nk) fetch(j, j);
         if constexpr (NPL == 2) {
-            sca = pow2f(absmax_log2_scale(g.amaxA, ma, tid & 63));
-            scb = pow2f(absmax_log2_scale(g.amaxB, mb, tid & 63));
+            if (wave == NC) {
+                const int e = absmax_log2_scale(g.amaxB, mb, tid & 63);
+                if ((tid & 63) == 0) rowexp[BM] = e;
+                if (!arows) {
+                    const int ea = absmax_log2_scale(g.amaxA, ma, tid & 63);
+                    for (int r = tid & 63; r < BM; r += 64) rowexp[r] = ea;
+                }
+            }
+            if (arows && ptid < BM) rowexp[ptid] = absmax_row_log2_scale(g.amaxA, mr, min(m0 + ptid, g.M - 1));
+            __syncthreads();                      // (the consumers wait here as well)
+            const float sb = pow2f(rowexp[BM]);
+#pragma unroll
+            for (int i = 0; i < LB::NV; ++i) scb[i] = sb;
+#pragma unroll
+            for (int i = 0; i < LA::NV; ++i) sca[i] = pow2f(rowexp[AKC ? LA::unit_row(ptid, i) : 0]);
         }
         // prologue: tiles 0 .. NS-2 into their stages
 #pragma unroll
@@ -584,7 +714,7 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
     constexpr int KS = BK / 16;
     bf16x8 fa[2][MI][NPL], fb[2][NI][NPL];
     auto fetch_frags = [&](int set, int kt, int ks) {
-        const __bf16 *st = smem + (kt % NS) * STAGE;
+        const __bf16 *st = stages + (kt % NS) * STAGE;
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -629,15 +759,7 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
         }
     };
 
-    // two-plane staging: the power of two that takes both operand scales off again, in two factors
-    // (either alone stays a normal number whenever the result does)
-    float unscale1 = 1.f, unscale2 = 1.f;
-    if constexpr (NPL == 2) {
-        const AbsMaxLoads ma = absmax_issue(g.amaxA, l), mb = absmax_issue(g.amaxB, l);
-        const int st = absmax_log2_scale(g.amaxA, ma, l) + absmax_log2_scale(g.amaxB, mb, l);
-        const int s1 = st >> 1;
-        unscale1 = pow2f(-s1); unscale2 = pow2f(s1 - st);
-    }
+    if constexpr (NPL == 2) __syncthreads();      // the producers have put log2 of the scales into rowexp
     __syncthreads();
     if (nk > 0) fetch_frags(0, 0, 0);
     if (KS == 1) {
@@ -676,12 +798,18 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
     }
 
     if constexpr (NPL == 2) {
+        // the power of two that takes both operand scales off again, in two factors (either alone stays a
+        // normal number whenever the result does)
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int j = 0; j < NI; ++j)
+            for (int r = 0; r < 16; ++r) {
+                const int st = rowexp[wm * WM + i * 32 + 8 * (r / 4) + 4 * hh + (r % 4)] + rowexp[BM];
+                const int s1 = st >> 1;
+                const float f1 = pow2f(-s1), f2 = pow2f(s1 - st);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[i][j][r] = (acc[i][j][r] * unscale1) * unscale2;
+                for (int j = 0; j < NI; ++j) acc[i][j][r] = (acc[i][j][r] * f1) * f2;
+            }
     }
     if constexpr (EPI == 7 || EPI == 8) {
         static_assert(BM == SCAN_TILE && BN == SCAN_TILE && NC == 4, "scan epilogue: 128x128 tile, 4 consumers");
@@ -855,7 +983,7 @@ hipError_t launch_gemm_bf16x3_ws_variant(const GemmArgs &a, hipStream_t s, const
     g1.slot0 = g0.nx;
     g1.second_first = (b && second_first) ? 1 : 0;
     constexpr size_t stage0 = gemm_stage_halves(BM, BN, BK, NPL, LAY0), stage1 = LAY1 >= 0 ? gemm_stage_halves(BM, BN, BK, NPL, LAY1) : 0;
-    constexpr size_t stage_bytes = (size_t)NS * (stage0 > stage1 ? stage0 : stage1) * sizeof(__bf16);
+    constexpr size_t stage_bytes = ((size_t)NS * (stage0 > stage1 ? stage0 : stage1) + gemm_rowexp_halves(BM, NPL)) * sizeof(__bf16);
     constexpr bool scans = ((LAY0 >> 2) >= 7) || (LAY1 >= 0 && (LAY1 >> 2) >= 7);
     constexpr size_t smem = (scans && SCAN_LDS_BYTES > stage_bytes) ? SCAN_LDS_BYTES : stage_bytes;
     static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS of a gfx950 CU");

@@ -94,7 +94,9 @@ bool gemm_two_planes_enabled()
 }
 static bool use_two_planes(const GemmArgs &a)
 {
-    return a.amaxA.slots && a.amaxB.slots && a.amaxA.n > 0 && a.amaxB.n > 0 && gemm_two_planes_enabled();
+    // A: one maximum, or one per row when its rows are contiguous along k; B: one maximum
+    const bool a_ok = (a.amaxA.rows && a.amaxA.row_parts > 0 && a.a_kcontig) || (!a.amaxA.rows && a.amaxA.slots && a.amaxA.n > 0);
+    return a_ok && a.amaxB.slots && a.amaxB.n > 0 && gemm_two_planes_enabled();
 }
 
 bool gemm_scan_shape_ok(int64_t Bt, int64_t L, int64_t P)

@@ -46,6 +46,38 @@ __device__ Zoh zoh_discretize(float2 Lambda, float log_delta)
 // partial[s][h] = sum_{t in slab s} a[t,h] * b[t,h]      (dD = sum_t dy_t (.) u_t)
 // workgroup = 64 columns x 4 row phases
 // ---------------------------------------------------------------------------------------------
+// maximum of v over the wavefront, valid in lane 63 (data-parallel-primitive moves only: inside quads,
+// inside rows of 16 lanes, then the last lane of a row broadcast to the following rows)
+__device__ __forceinline__ unsigned wave_max_lane63(unsigned v)
+{
+    v = max(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xb1, 0xf, 0xf, false));    // quad_perm [1,0,3,2]
+    v = max(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4e, 0xf, 0xf, false));    // quad_perm [2,3,0,1]
+    v = max(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x124, 0xf, 0xf, false));   // row_ror:4
+    v = max(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x128, 0xf, 0xf, false));   // row_ror:8
+    v = max(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x142, 0xa, 0xf, false));   // row_bcast:15 into rows 1, 3
+    v = max(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x143, 0xc, 0xf, false));   // row_bcast:31 into rows 2, 3
+    return v;
+}
+
+// Four values per lane -> lane l < 4 gets the maximum over the wavefront of value 2 (l & 1) + (l >> 1):
+// two halving steps inside the quads (lanes that differ in bit 0, then bit 1, swap the half the other
+// keeps), rotations inside the rows of 16 lanes, lane swaps across rows: seven moves for four reductions.
+__device__ __forceinline__ unsigned wave_max4(unsigned v0, unsigned v1, unsigned v2, unsigned v3, int lane)
+{
+    const bool up0 = lane & 1, up1 = (lane >> 1) & 1;
+    const unsigned k0 = up0 ? v2 : v0, s0 = up0 ? v0 : v2, k1 = up0 ? v3 : v1, s1 = up0 ? v1 : v3;
+    const unsigned w0 = max(k0, (unsigned)__builtin_amdgcn_update_dpp((int)s0, (int)s0, 0xb1, 0xf, 0xf, false));
+    const unsigned w1 = max(k1, (unsigned)__builtin_amdgcn_update_dpp((int)s1, (int)s1, 0xb1, 0xf, 0xf, false));
+    const unsigned k = up1 ? w1 : w0, sd = up1 ? w0 : w1;
+    unsigned v = max(k, (unsigned)__builtin_amdgcn_update_dpp((int)sd, (int)sd, 0x4e, 0xf, 0xf, false));
+    v = max(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x124, 0xf, 0xf, false));   // row_ror:4
+    v = max(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x128, 0xf, 0xf, false));   // row_ror:8
+    const auto r16 = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    v = max((unsigned)r16[0], (unsigned)r16[1]);
+    const auto r32 = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return max((unsigned)r32[0], (unsigned)r32[1]);
+}
+
 // largest bit pattern of the non-negative floats v of a 256-thread workgroup, valid in thread 0
 __device__ __forceinline__ unsigned block_absmax(float v)
 {
@@ -58,7 +90,9 @@ __device__ __forceinline__ unsigned block_absmax(float v)
     return max(max(wmax[0], wmax[1]), max(wmax[2], wmax[3]));
 }
 
-__device__ __forceinline__ void coldot_block(const ColDotArgs &a, int colblock, int slab, unsigned *amax, unsigned *bmax, int slot)
+// arow (may be null): [colblocks][T], the largest magnitude of a[t, 64 columns of the block] per row t
+__device__ __forceinline__ void coldot_block(const ColDotArgs &a, int colblock, int slab, unsigned *amax, unsigned *bmax, int slot,
+                                             unsigned *arow)
 {
     __shared__ float red[256];
     const int tid = threadIdx.x;
@@ -66,21 +100,36 @@ __device__ __forceinline__ void coldot_block(const ColDotArgs &a, int colblock, 
     const long rows_per = (a.T + a.nslab - 1) / a.nslab;
     const long r0 = slab * rows_per, r1 = min((long)a.T, r0 + rows_per);
     float s = 0.f, ma = 0.f, mb = 0.f;
-    if (col < a.H) {
-        long t = r0 + ph;
-        for (; t + 12 < r1; t += 16) {           // four independent row pairs in flight
-            const float a0 = a.a[t * a.H + col], b0 = a.b[t * a.H + col];
-            const float a1 = a.a[(t + 4) * a.H + col], b1 = a.b[(t + 4) * a.H + col];
-            const float a2 = a.a[(t + 8) * a.H + col], b2 = a.b[(t + 8) * a.H + col];
-            const float a3 = a.a[(t + 12) * a.H + col], b3 = a.b[(t + 12) * a.H + col];
-            s = fmaf(a0, b0, s); s = fmaf(a1, b1, s); s = fmaf(a2, b2, s); s = fmaf(a3, b3, s);
-            ma = fmaxf(fmaxf(ma, fmaxf(fabsf(a0), fabsf(a1))), fmaxf(fabsf(a2), fabsf(a3)));
-            mb = fmaxf(fmaxf(mb, fmaxf(fabsf(b0), fabsf(b1))), fmaxf(fabsf(b2), fabsf(b3)));
+    // every lane walks the rows (a wavefront = 64 columns of the rows r0 + ph, + 4, ...); columns past H read
+    // column 0 and count as zero, so that the per-row maxima can be formed across the whole wavefront
+    const bool okc = col < a.H;
+    const int cc = okc ? col : 0;
+    unsigned *arow_cb = arow ? arow + (size_t)colblock * a.T : nullptr;
+    long t = r0 + ph;
+    for (; t + 12 < r1; t += 16) {           // four independent row pairs in flight
+        float a0 = a.a[t * a.H + cc], b0 = a.b[t * a.H + cc];
+        float a1 = a.a[(t + 4) * a.H + cc], b1 = a.b[(t + 4) * a.H + cc];
+        float a2 = a.a[(t + 8) * a.H + cc], b2 = a.b[(t + 8) * a.H + cc];
+        float a3 = a.a[(t + 12) * a.H + cc], b3 = a.b[(t + 12) * a.H + cc];
+        if (!okc) { a0 = a1 = a2 = a3 = 0.f; b0 = b1 = b2 = b3 = 0.f; }
+        s = fmaf(a0, b0, s); s = fmaf(a1, b1, s); s = fmaf(a2, b2, s); s = fmaf(a3, b3, s);
+        ma = fmaxf(fmaxf(ma, fmaxf(fabsf(a0), fabsf(a1))), fmaxf(fabsf(a2), fabsf(a3)));
+        mb = fmaxf(fmaxf(mb, fmaxf(fabsf(b0), fabsf(b1))), fmaxf(fabsf(b2), fabsf(b3)));
+        if (arow_cb) {
+            const int l = tid & 63;
+            const unsigned m = wave_max4(__float_as_uint(fabsf(a0)), __float_as_uint(fabsf(a1)), __float_as_uint(fabsf(a2)),
+                                         __float_as_uint(fabsf(a3)), l);
+            if (l < 4) arow_cb[t + 4 * (2 * (l & 1) + (l >> 1))] = m;
         }
-        for (; t < r1; t += 4) {
-            const float a0 = a.a[t * a.H + col], b0 = a.b[t * a.H + col];
-            s = fmaf(a0, b0, s);
-            ma = fmaxf(ma, fabsf(a0)); mb = fmaxf(mb, fabsf(b0));
+    }
+    for (; t < r1; t += 4) {
+        float a0 = a.a[t * a.H + cc], b0 = a.b[t * a.H + cc];
+        if (!okc) { a0 = 0.f; b0 = 0.f; }
+        s = fmaf(a0, b0, s);
+        ma = fmaxf(ma, fabsf(a0)); mb = fmaxf(mb, fabsf(b0));
+        if (arow_cb) {
+            const unsigned u0 = wave_max_lane63(__float_as_uint(fabsf(a0)));
+            if ((tid & 63) == 63) arow_cb[t] = u0;
         }
     }
     red[tid] = s;
@@ -95,9 +144,61 @@ __device__ __forceinline__ void coldot_block(const ColDotArgs &a, int colblock, 
     }
 }
 
+// slots[row] = largest magnitude of row `row` of x[n / rowlen][rowlen]: a wavefront takes four rows at a
+// time (all loads of the four rows in flight before the first reduction)
+__device__ __forceinline__ void absmax_rows_block(const PrepArgs::Pass &q, int piece)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const size_t rows = q.n / (size_t)q.rowlen;
+    const size_t wid = (size_t)piece * 4 + wave, nw = (size_t)q.nblocks * 4;
+    for (size_t row0 = wid * 4; row0 < rows; row0 += nw * 4) {
+        float m[4] = {0.f, 0.f, 0.f, 0.f};
+        if (q.vec && q.rowlen <= 512) {
+            // up to two float4 per lane and row: eight independent loads
+            float4 a[4][2];
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int i = lane + 64 * h;
+                    const bool ok = row0 + r < rows && i < q.rowlen / 4;
+                    const float4 *x4 = reinterpret_cast<const float4 *>(q.x + (ok ? row0 + r : 0) * (size_t)q.rowlen);
+                    const float4 t = x4[ok ? i : 0];
+                    a[r][h] = ok ? t : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+#pragma unroll
+                for (int h = 0; h < 2; ++h)
+                    m[r] = fmaxf(m[r], fmaxf(fmaxf(fabsf(a[r][h].x), fabsf(a[r][h].y)), fmaxf(fabsf(a[r][h].z), fabsf(a[r][h].w))));
+        } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                if (row0 + r >= rows) break;
+                const float *x = q.x + (row0 + r) * (size_t)q.rowlen;
+                if (q.vec) {
+                    const float4 *x4 = reinterpret_cast<const float4 *>(x);
+                    for (int i = lane; i < q.rowlen / 4; i += 64) {
+                        const float4 t = x4[i];
+                        m[r] = fmaxf(m[r], fmaxf(fmaxf(fabsf(t.x), fabsf(t.y)), fmaxf(fabsf(t.z), fabsf(t.w))));
+                    }
+                } else {
+                    for (int i = lane; i < q.rowlen; i += 64) m[r] = fmaxf(m[r], fabsf(x[i]));
+                }
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const unsigned u = wave_max_lane63(__float_as_uint(m[r]));
+            if (lane == 63 && row0 + r < rows) q.slots[row0 + r] = u;
+        }
+    }
+}
+
 // slots[piece] = largest magnitude of piece `piece` of x[n] (pieces of whole float4 units when vec)
 __device__ __forceinline__ void absmax_pass_block(const PrepArgs::Pass &q, int piece)
 {
+    if (q.rowlen > 0) { absmax_rows_block(q, piece); return; }
     const int tid = threadIdx.x;
     float m = 0.f;
     if (q.vec) {
@@ -184,7 +285,7 @@ __global__ void __launch_bounds__(256) prep_kernel(PrepArgs a)
     } else {
         // column-dot slabs of the gradient pass share this launch (they depend on nothing here)
         const int cb = blk - (a.P + a.H);
-        coldot_block(a.cd, cb % a.cd_colblocks, cb / a.cd_colblocks, a.cd_amax, a.cd_bmax, cb);
+        coldot_block(a.cd, cb % a.cd_colblocks, cb / a.cd_colblocks, a.cd_amax, a.cd_bmax, cb, a.cd_arow);
     }
 }
 
@@ -212,7 +313,8 @@ hipError_t launch_prep(const PrepArgs &a_in, hipStream_t s)
         PrepArgs::Pass &q = a.pass[i];
         if (q.nblocks <= 0) { q.nblocks = 0; continue; }
         if (!a.Cc || !q.x || !q.slots) return hipErrorInvalidValue;
-        q.vec = (reinterpret_cast<uintptr_t>(q.x) & 15) == 0 && q.n % 4 == 0;
+        q.vec = (reinterpret_cast<uintptr_t>(q.x) & 15) == 0 && q.n % 4 == 0 && q.rowlen % 4 == 0;
+        if (q.rowlen < 0 || (q.rowlen > 0 && q.n % (size_t)q.rowlen != 0)) return hipErrorInvalidValue;
         q.block0 = (int)blocks;
         blocks += (unsigned)q.nblocks;
     }

@@ -21,6 +21,9 @@ struct Layout {
     // amax_atomic: ABSMAX_SLOTS words gathered with atomics, directly before fdesc so that one range is
     // cleared; amax_slots: [P] Bbar, [H] Cc, then 2 x PREP_PASS_BLOCKS and 2 x amax_cd words of the passes
     size_t amax_atomic, amax_slots; int amax_cd;
+    // per-row maxima of the operands whose rows are tokens: rowmax (u forward: [T]; dy gradient pass: [ceil(H/64), T]) and
+    // rowpart [ceil(2P/128), T] (x forward, chi gradient pass: one word per column tile of the scanning projection)
+    size_t rowmax, rowpart; int row_parts;
 };
 
 ssm_status check_dims(int64_t Bt, int64_t L, int64_t H, int64_t P)
@@ -53,7 +56,7 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
     o.desc = off; off += up(o.plan.desc_bytes);
     o.xbuf = o.chi = o.dCpart = o.dBpart = o.dApart = o.dDpart = o.fdesc = o.fdesc_bytes = 0;
     size_t dA_elems = o.plan.partial_elems;
-    o.amax_atomic = o.amax_slots = 0; o.amax_cd = 0;
+    o.amax_atomic = o.amax_slots = o.rowmax = o.rowpart = 0; o.amax_cd = o.row_parts = 0;
     if (gemm_scan_shape_ok(Bt, L, P)) {              // tagged words of a projection that scans its own output
         static_assert(ABSMAX_SLOTS * 4 % ALIGN == 0, "the atomic slots and the tagged words are cleared as one range");
         o.amax_atomic = off; off += ABSMAX_SLOTS * 4;
@@ -61,6 +64,9 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
         o.fdesc = off; off += up(o.fdesc_bytes);
         o.amax_cd = o.nslab * (int)((H + 63) / 64);
         o.amax_slots = off; off += up((size_t)(P + H + 2 * PREP_PASS_BLOCKS + 2 * o.amax_cd) * 4);
+        o.row_parts = (int)((2 * P + 127) / 128);
+        o.rowmax = off; off += up(T * (size_t)((H + 63) / 64) * 4);
+        o.rowpart = off; off += up(T * (size_t)o.row_parts * 4);
         const size_t per_tile = (size_t)(Bt * L / 128) * P;        // one dAbar row per 128-row tile
         if (per_tile > dA_elems) dA_elems = per_tile;
     }
@@ -167,10 +173,12 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     const bool two_planes = fused && gemm_two_planes_enabled();
     unsigned *am_atomic = reinterpret_cast<unsigned *>(ws + lo.amax_atomic);
     unsigned *am_bbar = reinterpret_cast<unsigned *>(ws + lo.amax_slots), *am_cc = am_bbar + P, *am_pass = am_cc + H;
-    const int u_pieces = pass_pieces((size_t)T * H);
+    unsigned *rowmax = reinterpret_cast<unsigned *>(ws + lo.rowmax), *rowpart = reinterpret_cast<unsigned *>(ws + lo.rowpart);
     if (two_planes) {
+        // u and x enter their products with tokens as rows: every token gets its own scale
         pa.bbar_max = am_bbar; pa.cc_max = am_cc;
-        pa.pass[0].x = u; pa.pass[0].n = (size_t)T * H; pa.pass[0].slots = am_pass; pa.pass[0].nblocks = u_pieces;
+        pa.pass[0].x = u; pa.pass[0].n = (size_t)T * H; pa.pass[0].slots = rowmax; pa.pass[0].rowlen = (int)H;
+        pa.pass[0].nblocks = pass_pieces((size_t)T * H);
     }
     HIP_TRY(launch_prep(pa, s));
     MARK();
@@ -188,8 +196,8 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
         g1.scan.desc = reinterpret_cast<unsigned long long *>(ws + lo.fdesc); g1.scan.err = &hdr->err;
         g1.scan.L = (int)L; g1.scan.P = (int)P; g1.scan.spin_limit = spin_limit();
         if (two_planes) {
-            g1.amaxA = AbsMax{am_pass, u_pieces}; g1.amaxB = AbsMax{am_bbar, (int)P};
-            g1.scan.amax_out = am_atomic;                    // of the states, for the output projection
+            g1.amaxA = AbsMax{nullptr, 0, rowmax, 1, T}; g1.amaxB = AbsMax{am_bbar, (int)P, nullptr, 0, 0};
+            g1.scan.rowmax_out = rowpart;                    // of the states, for the output projection
         }
     }
     HIP_TRY(launch_gemm(g1, s));
@@ -212,7 +220,7 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     g2.A = reinterpret_cast<const float *>(xs); g2.lda = 2 * P; g2.a_kcontig = 1;
     g2.B = Cc; g2.ldb = 2 * P; g2.b_kcontig = 1;
     g2.M = T; g2.N = (int)H; g2.K = (int)(2 * P);
-    if (two_planes) { g2.amaxA = AbsMax{am_atomic, ABSMAX_SLOTS}; g2.amaxB = AbsMax{am_cc, (int)H}; }
+    if (two_planes) { g2.amaxA = AbsMax{nullptr, 0, rowpart, lo.row_parts, T}; g2.amaxB = AbsMax{am_cc, (int)H, nullptr, 0, 0}; }
     if (lo.yhalves && gemm_out_split(T, H, P)) {
         // too few 128x128 tiles for the chip: two K halves into two slabs, then one streaming pass
         float *halves = reinterpret_cast<float *>(ws + lo.yhalves);
@@ -284,13 +292,18 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     unsigned *am_atomic = reinterpret_cast<unsigned *>(ws + lo.amax_atomic);
     unsigned *am_bbar = reinterpret_cast<unsigned *>(ws + lo.amax_slots), *am_cc = am_bbar + P, *am_pass = am_cc + H;
     unsigned *am_dy = am_pass + 2 * PREP_PASS_BLOCKS, *am_u = am_dy + lo.amax_cd;
+    unsigned *rowmax = reinterpret_cast<unsigned *>(ws + lo.rowmax), *rowpart = reinterpret_cast<unsigned *>(ws + lo.rowpart);
     const int x_pieces = pass_pieces((size_t)T * 2 * P);
     if (two_planes) {
         pa.bbar_max = am_bbar; pa.cc_max = am_cc; pa.cd_amax = am_dy; pa.cd_bmax = am_u;
         pa.pass[0].x = xf; pa.pass[0].n = (size_t)T * 2 * P; pa.pass[0].slots = am_pass; pa.pass[0].nblocks = x_pieces;
+        pa.cd_arow = rowmax;                 // [ceil(H/64)][T]: rows of dy, measured where the dD column dots read it
     }
-    const AbsMax mx_dy{am_dy, lo.amax_cd}, mx_u{am_u, lo.amax_cd}, mx_x{am_pass, x_pieces}, mx_chi{am_atomic, ABSMAX_SLOTS},
-                 mx_bbar{am_bbar, (int)P}, mx_cc{am_cc, (int)H};
+    // dy and chi enter C^H dy and Bbar^H chi with tokens as rows (a scale per token); the sums over tokens
+    // (dC, dBbar) take one scale per matrix
+    const AbsMax mx_dy{am_dy, lo.amax_cd, nullptr, 0, 0}, mx_u{am_u, lo.amax_cd, nullptr, 0, 0}, mx_x{am_pass, x_pieces, nullptr, 0, 0},
+                 mx_chi{am_atomic, ABSMAX_SLOTS, nullptr, 0, 0}, mx_bbar{am_bbar, (int)P, nullptr, 0, 0},
+                 mx_cc{am_cc, (int)H, nullptr, 0, 0}, mx_dy_rows{nullptr, 0, rowmax, (int)((H + 63) / 64), T}, mx_chi_rows{nullptr, 0, rowpart, lo.row_parts, T};
     HIP_TRY(launch_prep(pa, s));
     MARK();
 
@@ -308,7 +321,7 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
         g3.scan.dx0 = reinterpret_cast<float2 *>(dx0);
         g3.scan.desc = reinterpret_cast<unsigned long long *>(ws + lo.fdesc); g3.scan.err = &hdr->err;
         g3.scan.L = (int)L; g3.scan.P = (int)P; g3.scan.spin_limit = spin_limit();
-        if (two_planes) { g3.amaxA = mx_dy; g3.amaxB = mx_cc; g3.scan.amax_out = am_atomic; }
+        if (two_planes) { g3.amaxA = mx_dy_rows; g3.amaxB = mx_cc; g3.scan.amax_out = am_atomic; g3.scan.rowmax_out = rowpart; }
     }
     // dC slabs: [h, 2p+c] = sum_t dy[t,h] * x[t, 2p+c]    (needs only saved states: same launch)
     GemmArgs g4{};
@@ -346,7 +359,7 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     g6.B = u; g6.ldb = H; g6.b_kcontig = 0;
     g6.C = dBpart; g6.ldc = H;
     g6.M = (int)(2 * P); g6.N = (int)H; g6.K = T; g6.splits = lo.splitB;
-    if (two_planes) { g5.amaxA = mx_chi; g5.amaxB = mx_bbar; g6.amaxA = mx_chi; g6.amaxB = mx_u; }
+    if (two_planes) { g5.amaxA = mx_chi_rows; g5.amaxB = mx_bbar; g6.amaxA = mx_chi; g6.amaxB = mx_u; }
     if (lo.yhalves && gemm_out_split(T, H, P)) {
         // du has too few 128x128 tiles for half a chip's worth of time: it runs as two K halves (twice
         // the workgroups, half as long) next to the long work items of the dBbar slabs, which start first;

@@ -28,11 +28,15 @@ namespace ssm {
 // the states x directly and Bbar u never goes to memory.  Rows are tokens (Bt sequences of L steps,
 // L a multiple of the 128-row tile), columns (re, im) pairs of P states.
 // Largest magnitude of a matrix, kept as n bit patterns of non-negative floats whose maximum it is
-// (written by the kernel that produced the matrix, or by a pass over it).  A product whose two
-// operands both carry one may stage them as two scaled fp16 planes (see gemm_bf16x3_kernel.h).
+// (written by the kernel that produced the matrix, or by a pass over it), or, for a matrix whose
+// rows are tokens, per row: rows[j * row_stride + r], j < row_parts, are patterns whose maximum is the
+// largest magnitude of row r.  A product whose two operands both carry one may stage them as two
+// scaled fp16 planes (see gemm_bf16x3_kernel.h); per-row maxima (k-contiguous A operand only) give
+// every row its own scale.
 constexpr int ABSMAX_SLOTS = 512;            // slots of a maximum that is gathered with atomics
 struct AbsMax {
-    const unsigned *slots; int n;            // slots == nullptr: not known
+    const unsigned *slots; int n;            // slots == nullptr and rows == nullptr: not known
+    const unsigned *rows; int row_parts; long row_stride;
 };
 
 struct ScanEpilogue {
@@ -46,6 +50,7 @@ struct ScanEpilogue {
     unsigned long long *desc;     // [M/128 * ceil(N/128) * 64][2] tagged aggregate words, zero on entry
     unsigned *err;                // set when a bounded wait gives up
     unsigned *amax_out;           // [ABSMAX_SLOTS] or null: atomic maximum of the magnitudes stored to C, zero on entry
+    unsigned *rowmax_out;         // [ceil(N/128), M] or null: per column tile and row, the largest magnitude stored to C
     int L, P;
     unsigned spin_limit;
 };
@@ -166,8 +171,10 @@ struct PrepArgs {
     unsigned *bbar_max;      // [P]: of the rows 2p, 2p+1 of Bbar_ri
     unsigned *cc_max;        // [H]: of row h of Cc
     unsigned *cd_amax, *cd_bmax;   // [cd.nslab * ceil(cd.H/64)]: of the pieces of cd.a and cd.b
-    struct Pass { const float *x; size_t n; unsigned *slots; int nblocks, block0, vec; } pass[2];
-                             // slots[nblocks]: of nblocks pieces of x[n]; block0 and vec set by launch_prep
+    unsigned *cd_arow;       // [ceil(cd.H/64)][cd.T]: of every row of cd.a within a block of 64 columns
+    struct Pass { const float *x; size_t n; unsigned *slots; int nblocks, block0, vec, rowlen; } pass[2];
+                             // rowlen == 0: slots[nblocks] of nblocks pieces of x[n]; rowlen > 0: slots[n / rowlen],
+                             // one per row of rowlen values; block0 and vec set by launch_prep
 };
 constexpr int PREP_PASS_BLOCKS = 256;
 hipError_t launch_prep(const PrepArgs &a, hipStream_t s);

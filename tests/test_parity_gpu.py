@@ -426,15 +426,14 @@ def test_scaled_fp16_planes_follow_the_magnitude_of_the_operands(scale_u, scale_
 
 
 def test_scaled_fp16_planes_with_a_wide_range_inside_one_operand():
-    """One scale per operand makes the two planes a fixed-point pair below 2^-17 of the operand's
-    largest magnitude: the error of every element stays below 2^-36 of that maximum times the
-    magnitudes it meets (far inside the tolerances measured against the tensor), while parts of a
-    tensor that are many orders of magnitude smaller than its largest element lose relative accuracy
-    of their own.  Pinned here: a sequence 1e-4 of the others and an outlier element of 1e3 keep the
-    stated tolerances even when the small sequence is looked at alone."""
+    """u, x, dy and chi enter their products with tokens as rows, and every token row gets its own
+    power-of-two scale (a single scale per matrix would hold a token ten orders of magnitude below
+    the largest element of the batch as a fixed-point number).  Pinned here: a sequence scaled by
+    1e-10 next to an outlier element of 1e4 keeps the stated tolerances when its own y, x and du are
+    looked at alone, and the whole tensors keep them as well."""
     inp = dict(wl.gen_inputs(wl.CONFIGS[2]))
-    u = inp["u"].copy(); u[3] *= 1e-4; u[5, 7, 11] = 1e3; inp["u"] = u
-    dy = inp["dy"].copy(); dy[2] *= 1e-4; dy[9, 100, 3] = -1e3; inp["dy"] = dy
+    u = inp["u"].copy(); u[3] *= 1e-10; u[5, 7, 11] = 1e4; inp["u"] = u
+    dy = inp["dy"].copy(); dy[2] *= 1e-10; dy[9, 100, 3] = -1e4; inp["dy"] = dy
     ref = orc.run_workload(inp, True)
     got = run_gpu(inp, True)
     for k in ("y", "x", "x_last"):
@@ -444,7 +443,7 @@ def test_scaled_fp16_planes_with_a_wide_range_inside_one_operand():
     rel = lambda a, b: float(np.linalg.norm((a - b).ravel()) / np.linalg.norm(b.ravel()))
     small = {"y[3]": rel(got["y"][3], ref["y"][3]), "x[3]": rel(got["x"][3], ref["x"][3]), "du[2]": rel(got["du"][2], ref["du"][2])}
     print(small, flush=True)
-    assert small["y[3]"] <= TOL_FWD and small["x[3]"] <= TOL_FWD and small["du[2]"] <= TOL_GRAD, small
+    assert small["y[3]"] <= 1e-5 and small["x[3]"] <= 1e-5 and small["du[2]"] <= 1e-5, small
 
 
 def test_bounded_wait_reports_instead_of_hanging():
