@@ -33,8 +33,10 @@
  *     products) -- by default the products of ssm_scan_fwd / ssm_scan_bwd at the shapes named under
  *     SSM_FUSED_SCAN below, where the largest magnitude of every operand is measured on the device,
  *     stage two fp16 planes of the operand scaled into the fp16 range by a power of two (three
- *     partial products, errors at the level of fp32 products; an element more than 2^17 below the
- *     largest magnitude of its matrix is held with an absolute error of 2^-39 of that magnitude);
+ *     partial products, errors at the level of fp32 products).  u, x, dy and chi get a scale per
+ *     token where tokens are the rows of the product, the weights and the operands of the sums
+ *     over tokens one per matrix; an element more than 2^17 below the largest magnitude under
+ *     its scale is held with an absolute error of 2^-39 of that magnitude;
  *     SSM_SPIN_LIMIT=<n> bounds the polls of a cross-workgroup wait in the scan (default 2^20);
  *     SSM_FUSED_SCAN selects where the scans run when every sequence is a whole number of 128-step
  *     tiles (L % 128 == 0, L <= 4096) or every 128 tokens are whole sequences (L = 16, 32, 64 with
