@@ -112,6 +112,10 @@ SCANNING_TILES = [
     ("four_sequences_per_tile", 128, 32, 24, 520, 0.05, True, True),
     ("two_sequences_per_tile", 64, 64, 16, 1024, 0.03, False, False),
     ("one_sequence_per_tile", 32, 128, 16, 1024, 0.02, False, True),
+    # layer widths that take the other paths of the row-maximum pass: rows longer than 512 values, and a
+    # width that is no multiple of 4 (scalar loads)
+    ("wide_layer", 16, 256, 1024, 512, 0.02, True, True),
+    ("layer_width_50", 16, 256, 50, 512, 0.02, False, True),
 ]
 
 
