@@ -171,8 +171,7 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     if (fused) { pa.zero16 = reinterpret_cast<uint4 *>(ws + lo.amax_atomic); pa.n16 = (ABSMAX_SLOTS * 4 + lo.fdesc_bytes) / 16; }
     // two scaled fp16 planes per operand: every operand of the two products brings its largest magnitude
     const bool two_planes = fused && gemm_two_planes_enabled();
-    unsigned *am_atomic = reinterpret_cast<unsigned *>(ws + lo.amax_atomic);
-    unsigned *am_bbar = reinterpret_cast<unsigned *>(ws + lo.amax_slots), *am_cc = am_bbar + P, *am_pass = am_cc + H;
+    unsigned *am_bbar = reinterpret_cast<unsigned *>(ws + lo.amax_slots), *am_cc = am_bbar + P;
     unsigned *rowmax = reinterpret_cast<unsigned *>(ws + lo.rowmax), *rowpart = reinterpret_cast<unsigned *>(ws + lo.rowpart);
     if (two_planes) {
         // u and x enter their products with tokens as rows: every token gets its own scale
