@@ -56,8 +56,8 @@ __device__ __forceinline__ Split4 split3(float4 v)
     return o;
 }
 
-// Two-plane split into fp16: with the operand scaled by a power of two so that its largest
-// magnitude lies in [2^14, 2^15), a1 = rn_fp16(s a) and a2 = rn_fp16(s a - a1) (the residual is
+// Two-plane split into fp16: with the operand (the whole matrix, or one row of it) scaled by a power
+// of two so that its largest magnitude lies in [2^14, 2^15), a1 = rn_fp16(s a) and a2 = rn_fp16(s a - a1) (the residual is
 // formed exactly by one fused multiply-add).  fp16 keeps 11 significant bits, so
 // |s a - a1 - a2| <= 2^-22 |s a| as long as a2 is a normal fp16 number, i.e. for |a| down to 2^-17
 // of the largest magnitude; below that the planes act as a fixed-point pair with an absolute error
