@@ -827,6 +827,81 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
         return;
     }
     float *Cz = g.C + (long)z * g.M * g.ldc;
+    if constexpr (EPI == 1 || EPI == 6) {
+        // sum + diag (.) E: the 16 values of E that a 32x32 block needs are loaded before its first store
+        // (the compiler may not move a load of E above an earlier store to C, so a load-compute-store loop
+        // would pay one memory latency per element); the scheduling barrier keeps the loads of the next
+        // block from being hoisted as well, which would not fit the register budget
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                const int col = n0 + wn * WN + j * 32 + li;
+                const long rbase = m0 + wm * WM + i * 32 + 4 * hh;
+                float e[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const long row = rbase + 8 * (r / 4) + (r % 4);
+                    e[r] = (FAST || (row < g.M && col < g.N)) ? g.E[row * g.lde + col] : 0.f;
+                }
+                const float dcol = (FAST || col < g.N) ? g.diag[col] : 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const long row = rbase + 8 * (r / 4) + (r % 4);
+                    if (FAST || (row < g.M && col < g.N)) {
+                        const float y = fmaf(dcol, e[r], acc[i][j][r]);
+                        Cz[row * g.ldc + col] = y;
+                        if constexpr (EPI == 6) g.C2[row * g.ldc + col] = gelu_value(y);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        return;
+    }
+    if constexpr (EPI == 2 || EPI == 5) {
+        // one recurrence step and its adjoint (columns are (re, im) pairs, the partner column lives in the
+        // neighbouring lane): the same block-wise order, inputs of a block first
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                const int col = n0 + wn * WN + j * 32 + li;
+                const long rbase = m0 + wm * WM + i * 32 + 4 * hh;
+                const bool colok = FAST || col < g.N;
+                float e[16];
+                bool dropped[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const long row = rbase + 8 * (r / 4) + (r % 4);
+                    const bool inb = colok && (FAST || row < g.M);
+                    e[r] = (inb && (EPI == 2 || g.E)) ? g.E[row * g.lde + col] : 0.f;
+                    dropped[r] = inb && g.rowflag && g.rowflag[row];
+                }
+                const bool has_diag = EPI == 2 || g.C2;
+                const float lr = (colok && has_diag) ? g.diag[col & ~1] : 0.f, li_ = (colok && has_diag) ? g.diag[col | 1] : 0.f;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const long row = rbase + 8 * (r / 4) + (r % 4);
+                    const bool inb = colok && (FAST || row < g.M);
+                    if constexpr (EPI == 2) {
+                        // the carried state Abar x_{t-1} of the step, unless the step resets
+                        const float own = e[r], other = __shfl_xor(own, 1);
+                        const float carried = (col & 1) ? fmaf(lr, own, li_ * other) : fmaf(lr, own, -li_ * other);
+                        if (inb) Cz[row * g.ldc + col] = dropped[r] ? acc[i][j][r] : acc[i][j][r] + carried;
+                    } else {
+                        const float v = acc[i][j][r] + e[r];
+                        const float other = __shfl_xor(v, 1);
+                        if (inb) {
+                            Cz[row * g.ldc + col] = v;
+                            if (g.C2)
+                                g.C2[row * g.ldc + col] = dropped[r] ? 0.f : ((col & 1) ? fmaf(lr, v, -li_ * other) : fmaf(lr, v, li_ * other));
+                        }
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < MI; ++i)
 #pragma unroll

@@ -77,7 +77,9 @@ __device__ __forceinline__ float sigmoidf(float z)
 template <int EPI>
 __device__ __forceinline__ float gemm_epilogue_apply(const GemmDev &g, long row, int col, float v)
 {
-    if (EPI == 1) return v + g.diag[col] * g.E[row * g.lde + col];
+    // (explicitly fused: v may itself be a product that the compiler could fuse with this sum instead,
+    // and every instantiation must round the same way)
+    if (EPI == 1) return fmaf(g.diag[col], g.E[row * g.lde + col], v);
     if (EPI == 2) {
         if (g.rowflag && g.rowflag[row]) return v;
         const float lr = g.diag[col & ~1], li = g.diag[col | 1];
@@ -94,7 +96,7 @@ __device__ __forceinline__ float gemm_epilogue_apply(const GemmDev &g, long row,
         return fmaf(v, gelu_derivative(g.E3[i]), g.E[i] * g.E2[i]);
     }
     if (EPI == 6) {
-        const float y = v + g.diag[col] * g.E[row * g.lde + col];
+        const float y = fmaf(g.diag[col], g.E[row * g.lde + col], v);
         g.C2[row * g.ldc + col] = gelu_value(y);
         return y;
     }
