@@ -858,6 +858,34 @@ __device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *sm
             }
         return;
     }
+    if constexpr (EPI == 3) {
+        // half-GLU gate: the same order (the adjoint of the gate, three inputs per value and the error
+        // function in its store, stays with the plain loop: it has no registers to spare)
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                const int col = n0 + wn * WN + j * 32 + li;
+                const long rbase = m0 + wm * WM + i * 32 + 4 * hh;
+                float e[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const long row = rbase + 8 * (r / 4) + (r % 4);
+                    e[r] = (FAST || (row < g.M && col < g.N)) ? g.E[row * g.lde + col] : 0.f;
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const long row = rbase + 8 * (r / 4) + (r % 4);
+                    if (FAST || (row < g.M && col < g.N)) {
+                        const float sg = sigmoidf(acc[i][j][r]);
+                        if (g.C2) g.C2[row * g.ldc + col] = sg;
+                        Cz[row * g.ldc + col] = e[r] * sg;
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        return;
+    }
     if constexpr (EPI == 2 || EPI == 5) {
         // one recurrence step and its adjoint (columns are (re, im) pairs, the partner column lives in the
         // neighbouring lane): the same block-wise order, inputs of a block first
