@@ -113,7 +113,17 @@ __device__ __forceinline__ int absmax_log2_scale(const AbsMax &m, const AbsMaxLo
     unsigned v = 0;
 #pragma unroll
     for (int j = 0; j < 8; ++j) v = max(v, r.w[j]);
-    for (int i = 512 + lane; i < m.n; i += 64) v = max(v, m.slots[i]);
+    for (int base = 512; base < m.n; base += 512) {          // more than 512 slots: eight more per lane at a time
+        unsigned w[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int i = base + lane + 64 * j;
+            const unsigned t = m.slots[i < m.n ? i : 0];
+            w[j] = i < m.n ? t : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v = max(v, w[j]);
+    }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v = max(v, (unsigned)__shfl_xor((int)v, o));
     return log2_scale_of(v);     // (defined below) 14 - floor(log2(maximum)), kept inside the exponent range
@@ -143,7 +153,16 @@ __device__ __forceinline__ int absmax_row_log2_scale(const AbsMax &m, const AbsM
     unsigned v = 0;
 #pragma unroll
     for (int j = 0; j < 8; ++j) v = max(v, r.w[j]);
-    for (int j = 8; j < m.row_parts; ++j) v = max(v, m.rows[(size_t)j * m.row_stride + row]);
+    for (int j0 = 8; j0 < m.row_parts; j0 += 8) {            // wide states or layers: eight more at a time
+        unsigned w[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const unsigned t = m.rows[(j0 + j < m.row_parts ? (size_t)(j0 + j) * m.row_stride : 0) + row];
+            w[j] = j0 + j < m.row_parts ? t : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v = max(v, w[j]);
+    }
     return log2_scale_of(v);
 }
 

@@ -116,6 +116,8 @@ SCANNING_TILES = [
     # width that is no multiple of 4 (scalar loads)
     ("wide_layer", 16, 256, 1024, 512, 0.02, True, True),
     ("layer_width_50", 16, 256, 50, 512, 0.02, False, True),
+    # more than eight row-maximum words per token (16 column tiles of x and chi, 9 column blocks of dy)
+    ("wide_state_many_row_parts", 4, 256, 576, 1024, 0.02, True, True),
 ]
 
 
