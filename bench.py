@@ -157,7 +157,7 @@ def main():
     f32_path = os.environ.get("SSM_GEMM_F32", "") == "1"
     fused_env = os.environ.get("SSM_FUSED_SCAN", "")
     shape_scans = (((L % 128 == 0 and L // 128 <= 32) or (L in (16, 32, 64) and T % 128 == 0))
-                   and (T // 128) * ((2 * P + 127) // 128) >= 200 and not f32_path)
+                   and (T // 128) * ((2 * P + 127) // 128) >= 64 and not f32_path)
     fwd_fused = shape_scans and fused_env != "0"
     rev_fused = shape_scans and fused_env not in ("0", "1")
     # two scaled fp16 planes where the pass's projection scans its own tiles (every operand then comes
@@ -172,7 +172,7 @@ def main():
                  and os.environ.get("SSM_SPLIT_OUT", "") != "0")
     out_tile = "128,128,32" if ((T + 127) // 128) * ((H + 127) // 128) >= 200 else \
                ("64,128,32" if ((T + 63) // 64) * ((H + 127) // 128) >= 200 else "64,64,64")
-    in_tile = "128,128,32" if big else ("64,128,32" if ((T + 63) // 64) * ((2 * P + 127) // 128) >= 200 else "64,64,64")
+    in_tile = "128,128,32" if (big or fwd_fused) else ("64,128,32" if ((T + 63) // 64) * ((2 * P + 127) // 128) >= 200 else "64,64,64")
     # every launch of the projection kernel in one step: role, instantiation, fp32 flops, duration
     launches = [
         {"role": "input projection" + (" + forward scan in the tile" if fwd_fused else ""),

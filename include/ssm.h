@@ -40,7 +40,7 @@
  *     SSM_SPIN_LIMIT=<n> bounds the polls of a cross-workgroup wait in the scan (default 2^20);
  *     SSM_FUSED_SCAN selects where the scans run when every sequence is a whole number of 128-step
  *     tiles (L % 128 == 0, L <= 4096) or every 128 tokens are whole sequences (L = 16, 32, 64 with
- *     Bt * L a multiple of 128), and the batch fills the chip: by default the input projection
+ *     Bt * L a multiple of 128), and the batch gives at least 64 tiles: by default the input projection
  *     and C^H dy scan their own output tiles (no scan kernel, no round trip of Bbar u and C^H dy
  *     through memory); =1 does so only in the forward pass, =0 keeps projections and scans as
  *     separate kernels.  All three settings meet the same tolerances; results differ by rounding;

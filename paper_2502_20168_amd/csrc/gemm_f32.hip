@@ -102,13 +102,14 @@ static bool use_two_planes(const GemmArgs &a)
 bool gemm_scan_shape_ok(int64_t Bt, int64_t L, int64_t P)
 {
     // 128-row tiles that hold a piece of one sequence (a bounded chain of tiles per sequence) or a
-    // whole number of sequences made of whole 16-step chunks, and enough tiles that the plain
-    // product would use 128x128 tiles anyway
+    // whole number of sequences made of whole 16-step chunks, and enough tiles
     const bool chain = L % SCAN_TILE == 0 && L / SCAN_TILE <= SCAN_MAX_CHAIN;
     const bool whole = L < SCAN_TILE && SCAN_TILE % L == 0 && L % SCAN_RC == 0 && (Bt * L) % SCAN_TILE == 0;
     if (!chain && !whole) return false;
+    // (measured: from 64 tiles on -- a quarter of the CUs -- the scanning tile with its two fp16 planes beats
+    // smaller tiles plus a scan kernel: +2 % at 64 tiles, +7..13 % at 96-128; no difference at 32-48)
     const int64_t tiles = (Bt * L / SCAN_TILE) * ((2 * P + SCAN_TILE - 1) / SCAN_TILE);
-    return tiles >= 200 && tiles * 64 <= 0x7fffffffLL;
+    return tiles >= 64 && tiles * 64 <= 0x7fffffffLL;
 }
 
 // SSM_FUSED_SCAN=0 keeps every projection and its scan as two kernels, =1 fuses only the forward

@@ -116,6 +116,10 @@ SCANNING_TILES = [
     # width that is no multiple of 4 (scalar loads)
     ("wide_layer", 16, 256, 1024, 512, 0.02, True, True),
     ("layer_width_50", 16, 256, 50, 512, 0.02, False, True),
+    # 64-199 tiles: less than the chip, still scanning tiles
+    ("ninety_six_tiles", 24, 128, 512, 256, 0.02, True, True),
+    ("sixty_four_tiles", 8, 128, 40, 512, 0.05, False, True),
+    ("sixty_four_tiles_of_whole_sequences", 64, 16, 24, 512, 0.05, False, True),
     # more than eight row-maximum words per token (16 column tiles of x and chi, 9 column blocks of dy)
     ("wide_state_many_row_parts", 4, 256, 576, 1024, 0.02, True, True),
 ]
