@@ -20,33 +20,29 @@
  *     1 - c_k of Eq. 9): x_t = Bbar u_t there.  is_first[b,0] != 0 makes x0[b] irrelevant.
  *   - Calls validate their arguments on the host first and return an error code before any
  *     launch; otherwise they enqueue kernels on `stream` (a hipStream_t, NULL = default stream)
- *     and return without waiting.  No exceptions, no abort, no global mutable state: concurrent
- *     calls are safe as long as they use distinct workspaces.
+ *     and return without waiting.  No exceptions, no abort; concurrent calls are safe as long
+ *     as they use distinct workspaces.
  *   - Outputs are overwritten, never accumulated into.  Outputs must not alias inputs.
  *   - The workspace must hold at least ssm_workspace_bytes(...) bytes; its contents are scratch
  *     and need not be initialised or preserved between calls.
  *   - Gradient of the real loss l w.r.t. a complex quantity q is returned as
  *     dl/dRe(q) + i dl/dIm(q).
- *   - Five environment variables are read at call time: SSM_GEMM_F32=1 runs the projections on
- *     the fp32 matrix instruction instead of the (equally accurate, faster) split operands;
- *     SSM_GEMM_SPLIT=3 stages every operand of every projection as three bf16 planes (six partial
- *     products) -- by default the products of ssm_scan_fwd / ssm_scan_bwd at the shapes named under
- *     SSM_FUSED_SCAN below, where the largest magnitude of every operand is measured on the device,
- *     stage two fp16 planes of the operand scaled into the fp16 range by a power of two (three
- *     partial products, errors at the level of fp32 products).  u, x, dy and chi get a scale per
- *     token where tokens are the rows of the product, the weights and the operands of the sums
- *     over tokens one per matrix; an element more than 2^17 below the largest magnitude under
- *     its scale is held with an absolute error of 2^-39 of that magnitude;
- *     SSM_SPIN_LIMIT=<n> bounds the polls of a cross-workgroup wait in the scan (default 2^20);
- *     SSM_FUSED_SCAN selects where the scans run when every sequence is a whole number of 128-step
- *     tiles (L % 128 == 0, L <= 4096) or every 128 tokens are whole sequences (L = 16, 32, 64 with
- *     Bt * L a multiple of 128), and the batch gives at least 64 tiles: by default the input projection
- *     and C^H dy scan their own output tiles (no scan kernel, no round trip of Bbar u and C^H dy
- *     through memory); =1 does so only in the forward pass, =0 keeps projections and scans as
- *     separate kernels.  All three settings meet the same tolerances; results differ by rounding;
- *     SSM_SPLIT_OUT=0 keeps the output projection and its adjoint for du in one kernel each where
- *     by default they run as two halves of the state dimension plus a streaming sum (shapes with
- *     100-199 tiles of 128 x 128 outputs, e.g. 4096 tokens and H = 512).
+ *   - The library reads no environment variable and keeps no state between calls other than the
+ *     poll bound of ssm_set_spin_limit below.
+ *   - Arithmetic of the projections: inputs, outputs and accumulation are fp32; the products run on
+ *     the 16-bit matrix cores with both operands split while they are staged.  Where the largest
+ *     magnitude of every operand is measured on the device as part of the call (ssm_scan_fwd /
+ *     ssm_scan_bwd at shapes where every sequence is a whole number of 128-step tiles, L % 128 == 0
+ *     and L <= 4096, or every 128 tokens are whole sequences, L = 16, 32, 64 with Bt * L a multiple of
+ *     128, and the batch gives at least 64 tiles of 128 tokens x 64 states) an operand is staged as two
+ *     fp16 planes of the operand scaled by a power of two (three partial products, errors at the level
+ *     of fp32 products): u, x, dy and chi get a scale per token where tokens are the rows of the
+ *     product, the weights and the operands of the sums over tokens one per matrix.  Under one scale
+ *     with largest magnitude m an element a is held with an absolute error of at most
+ *     max(2^-22 |a|, 2^-39 m): elements more than 2^17 below m are fixed-point, not floating-point.
+ *     Everywhere else every operand is split exactly into three bf16 planes (six partial products).
+ *     At the shapes named above the input projection and C^H dy also scan their own output tiles
+ *     (no scan kernel, no round trip of Bbar u and C^H dy through memory).  Infinite inputs give NaN.
  */
 #ifndef SSM_H_
 #define SSM_H_
@@ -73,15 +69,17 @@ typedef enum {
 #define SSM_MAX_TOKENS 2147483647LL  /* largest Bt * L                                 */
 #define SSM_MAX_ELEMS (1LL << 40)    /* largest Bt * L * max(H, 2P)                    */
 
-/* Number of per-stage timings written by the *_profiled calls (see below). */
-#define SSM_FWD_STAGES 5
-#define SSM_BWD_STAGES 6
-
 /* Static description of an error code. Never NULL. */
 const char *ssm_strerror(int status);
 
 /* Library version, major * 100 + minor. */
 int ssm_version(void);
+
+/* Bound on the polls of one cross-workgroup wait (default 2^20, each poll sleeps about 128 clocks);
+ * returns the previous value.  Process-wide and meant for tests: a bound of 0 makes every wait whose
+ * predecessor is not ready yet give up at once, so the give-up path can be exercised while every
+ * kernel still terminates.                                                                      */
+uint32_t ssm_set_spin_limit(uint32_t polls);
 
 /* Scratch bytes the forward (want_bwd = 0) or the gradient pass (want_bwd != 0) needs for the
  * given shape.  Returns 0 for an invalid or unsupported shape.  Pure host function.           */
@@ -240,49 +238,12 @@ ssm_status ssm_block_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 
                          float *du, ssm_c64 *dLambda, ssm_c64 *dB, ssm_c64 *dC, float *dD, float *dlog_delta,
                          ssm_c64 *dx0, float *dW, void *workspace, size_t ws_bytes, void *stream);
 
-/* Measurement aid for the roofline of the projection kernel (no operation of the paper): launches
- * `workgroups` workgroups of four wavefronts that issue nothing but the matrix instructions of the
- * projection kernel's inner loop (24 per iteration and wavefront, on register operands whose bits
- * change every iteration) for `iters` iterations: v_mfma_f32_32x32x16_bf16 in the order of the
- * three-plane split (fp16 == 0) or v_mfma_f32_32x32x16_f16 in the order of the two-plane one
- * (fp16 != 0).  The caller times the launch; the work is workgroups * 4 * iters * 24 * 2*32*32*16
- * flops.  out: device, at least workgroups * 256 floats (receives checksums).
- * workgroups <= 65536, iters <= 2^24.                                                             */
-ssm_status ssm_mfma_probe(int64_t workgroups, int64_t iters, int fp16, float *out, void *stream);
-
-/* Measurement aids: the same code path as ssm_scan_fwd / ssm_scan_bwd, with a HIP event recorded
- * on `stream` around every kernel.  They wait for the stream before returning and write the
- * milliseconds of each stage to the HOST array stage_ms:
- *   forward : [0] discretise+pack, [1] input projection, [2] scan, [3] output projection,
- *             [4] sum of the two halves of the output projection
- *   backward: [0] discretise+pack and dD partials, [1] gx = C^H dy with the dC partials (one
- *             launch), [2] reverse scan, [3] du with the dBbar partials (one launch),
- *             [4] empty (the sum of the two halves of du shares the next launch),
- *             [5] parameter epilogue
- * A stage that holds no kernel on this call (a scan that runs inside its projection, see
- * SSM_FUSED_SCAN above; a product that is not run as two halves, see SSM_SPLIT_OUT) reads as the
- * few microseconds between two events.                                                          */
-ssm_status ssm_scan_fwd_profiled(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C,
-                                 const float *D, const float *log_delta, const float *u,
-                                 const uint8_t *is_first, const ssm_c64 *x0,
-                                 int64_t Bt, int64_t L, int64_t H, int64_t P,
-                                 float *y, ssm_c64 *x, ssm_c64 *x_last,
-                                 void *workspace, size_t ws_bytes, void *stream,
-                                 float *stage_ms /* host, [SSM_FWD_STAGES] */);
-ssm_status ssm_scan_bwd_profiled(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C,
-                                 const float *D, const float *log_delta, const float *u,
-                                 const uint8_t *is_first, const ssm_c64 *x0,
-                                 int64_t Bt, int64_t L, int64_t H, int64_t P,
-                                 const ssm_c64 *x, const float *dy,
-                                 float *du, ssm_c64 *dLambda, ssm_c64 *dB, ssm_c64 *dC, float *dD,
-                                 float *dlog_delta, ssm_c64 *dx0,
-                                 void *workspace, size_t ws_bytes, void *stream,
-                                 float *stage_ms /* host, [SSM_BWD_STAGES] */);
-
 /* Waits for `stream` and reports whether any scan launched with this workspace since its last
- * use gave up a bounded cross-block wait (SSM_ERR_SCAN_TIMEOUT; the outputs of that call are
- * then invalid) or SSM_OK.  Long sequences are split over several workgroups that hand their
- * running state forward; every such wait is bounded so that a kernel always terminates.        */
+ * use gave up a bounded cross-block wait (SSM_ERR_SCAN_TIMEOUT) or SSM_OK.  Long sequences are
+ * split over several workgroups that hand their running state forward; every such wait is bounded
+ * so that a kernel always terminates.  A wait that gives up hands on NaN: the states that depend on
+ * it, and everything computed from them, are NaN, so the failure cannot pass as data even for a
+ * caller who never asks here.                                                                   */
 ssm_status ssm_workspace_status(const void *workspace, void *stream);
 
 #ifdef __cplusplus

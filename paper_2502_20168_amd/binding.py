@@ -23,14 +23,14 @@ SSM_ERR_SCAN_TIMEOUT = 5
 SSM_FWD_STAGES = 5
 SSM_BWD_STAGES = 6
 FWD_STAGE_NAMES = ("discretize_pack", "project_in", "scan", "project_out", "sum_out_halves")
-BWD_STAGE_NAMES = ("discretize_pack_dD", "gx_dC_partials", "reverse_scan", "du_dBbar_partials", "sum_du_halves",
+BWD_STAGE_NAMES = ("discretize_pack_dD", "gx", "reverse_scan", "du_dBbar_dC_partials", "sum_du_halves",
                    "param_epilogue")
 
 EXPORTS = ("ssm_strerror", "ssm_version", "ssm_workspace_bytes", "ssm_discretize", "ssm_scan_fwd",
            "ssm_scan_bwd", "ssm_scan_states", "ssm_scan_states_reverse", "ssm_scan_fwd_profiled",
            "ssm_scan_bwd_profiled", "ssm_workspace_status", "ssm_step_plan_bytes", "ssm_step_prepare", "ssm_step",
            "ssm_step_bwd", "ssm_lambda_return", "ssm_lambda_return_bwd", "ssm_half_glu_workspace_bytes", "ssm_half_glu_fwd",
-           "ssm_half_glu_bwd", "ssm_block_workspace_bytes", "ssm_block_fwd", "ssm_block_bwd", "ssm_mfma_probe")
+           "ssm_half_glu_bwd", "ssm_block_workspace_bytes", "ssm_block_fwd", "ssm_block_bwd", "ssm_set_spin_limit")
 
 _lib = None
 _vp, _i64, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t
@@ -92,8 +92,8 @@ def lib():
         L.ssm_half_glu_fwd.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp, _vp, _sz, _vp]
         L.ssm_half_glu_bwd.restype = ctypes.c_int
         L.ssm_half_glu_bwd.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _vp, _vp, _vp, _sz, _vp]
-        L.ssm_mfma_probe.restype = ctypes.c_int
-        L.ssm_mfma_probe.argtypes = [_i64, _i64, ctypes.c_int, _vp, _vp]
+        L.ssm_set_spin_limit.restype = ctypes.c_uint32
+        L.ssm_set_spin_limit.argtypes = [ctypes.c_uint32]
         L.ssm_block_workspace_bytes.restype = _sz
         L.ssm_block_workspace_bytes.argtypes = [_i64, _i64, _i64, _i64, ctypes.c_int]
         L.ssm_block_fwd.restype = ctypes.c_int
@@ -149,6 +149,15 @@ def alloc_workspace(Bt, L, H, P, want_bwd, device="cuda"):
     return torch.empty(n, dtype=torch.uint8, device=device)
 
 
+def _own_workspace(ws, stream):
+    """A workspace this module allocated for one call is dropped when the call returns, while its
+    kernels are still queued: tell the caching allocator which stream they run on, so that the block is
+    not handed out again before they finish (the allocation itself happened on the current stream)."""
+    if stream is not None:
+        ws.record_stream(stream)
+    return ws
+
+
 def _check_inputs(Lambda, B, C, D, log_delta, u, is_first, x0):
     torch = _torch()
     if u.dim() != 3 or Lambda.dim() != 1:
@@ -195,7 +204,7 @@ def ssm_scan_fwd(Lambda, B, C, D, log_delta, u, is_first=None, x0=None, *, want_
         torch.empty((Bt, L, P), dtype=torch.complex64, device=u.device) if want_x else None)
     x_last = out.get("x_last") if out.get("x_last") is not None else (
         torch.empty((Bt, P), dtype=torch.complex64, device=u.device) if want_x_last else None)
-    ws = workspace if workspace is not None else alloc_workspace(Bt, L, H, P, False, u.device)
+    ws = workspace if workspace is not None else _own_workspace(alloc_workspace(Bt, L, H, P, False, u.device), stream)
     args = [_ptr(Lambda), _ptr(B), _ptr(C), _ptr(D), _ptr(log_delta), _ptr(u), _ptr(is_first), _ptr(x0),
             Bt, L, H, P, _ptr(y), _ptr(x), _ptr(x_last), _ptr(ws), ws.numel(), _stream(stream)]
     res = {"y": y, "x": x, "x_last": x_last}
@@ -229,7 +238,7 @@ def ssm_scan_bwd(Lambda, B, C, D, log_delta, u, is_first, x0, x, dy, *, want_dx0
         "dC": get("dC", like=C), "dD": get("dD", like=D), "dlog_delta": get("dlog_delta", like=log_delta),
         "dx0": get("dx0", shape=(Bt, P), dtype=torch.complex64) if want_dx0 else None,
     }
-    ws = workspace if workspace is not None else alloc_workspace(Bt, L, H, P, True, u.device)
+    ws = workspace if workspace is not None else _own_workspace(alloc_workspace(Bt, L, H, P, True, u.device), stream)
     args = [_ptr(Lambda), _ptr(B), _ptr(C), _ptr(D), _ptr(log_delta), _ptr(u), _ptr(is_first), _ptr(x0),
             Bt, L, H, P, _ptr(x), _ptr(dy), _ptr(res["du"]), _ptr(res["dLambda"]), _ptr(res["dB"]),
             _ptr(res["dC"]), _ptr(res["dD"]), _ptr(res["dlog_delta"]), _ptr(res["dx0"]),
@@ -254,7 +263,7 @@ def ssm_scan_states(A_bar, v, is_first=None, x0=None, *, want_x_last=True, works
     _chk(is_first, torch.uint8, (Bt, L), "is_first")
     _chk(x0, torch.complex64, (Bt, P), "x0")
     x_last = torch.empty((Bt, P), dtype=torch.complex64, device=v.device) if want_x_last else None
-    ws = workspace if workspace is not None else alloc_workspace(Bt, L, 1, P, False, v.device)
+    ws = workspace if workspace is not None else _own_workspace(alloc_workspace(Bt, L, 1, P, False, v.device), stream)
     rc = lib().ssm_scan_states(_ptr(A_bar), _ptr(v), _ptr(is_first), _ptr(x0), Bt, L, P, _ptr(x_last),
                                _ptr(ws), ws.numel(), _stream(stream))
     if rc != SSM_OK:
@@ -274,7 +283,7 @@ def ssm_scan_states_reverse(A_bar, gx, x, is_first=None, x0=None, *, want_dx0=Tr
     _chk(x0, torch.complex64, (Bt, P), "x0")
     dA = torch.empty_like(A_bar)
     dx0 = torch.empty((Bt, P), dtype=torch.complex64, device=gx.device) if want_dx0 else None
-    ws = workspace if workspace is not None else alloc_workspace(Bt, L, 1, P, True, gx.device)
+    ws = workspace if workspace is not None else _own_workspace(alloc_workspace(Bt, L, 1, P, True, gx.device), stream)
     rc = lib().ssm_scan_states_reverse(_ptr(A_bar), _ptr(gx), _ptr(x), _ptr(is_first), _ptr(x0), Bt, L, P,
                                        _ptr(dA), _ptr(dx0), _ptr(ws), ws.numel(), _stream(stream))
     if rc != SSM_OK:
@@ -366,18 +375,9 @@ def ssm_lambda_return_bwd(cont, value, ret, dret, gamma: float, lam: float, *, s
     return dr, dc, dv
 
 
-def ssm_mfma_probe(workgroups: int, iters: int, *, fp16: bool = False, out=None, stream=None):
-    """Launches the matrix-instruction-only probe (bf16 instructions, or fp16 ones); returns the checksum
-    tensor [workgroups * 256]."""
-    torch = _torch()
-    if out is None:
-        out = torch.empty(max(int(workgroups), 1) * 256, dtype=torch.float32, device="cuda")
-    if not out.is_cuda or out.dtype != torch.float32 or not out.is_contiguous() or out.numel() < int(workgroups) * 256:
-        raise ValueError("out must be a contiguous cuda float32 tensor of at least workgroups * 256 elements")
-    rc = lib().ssm_mfma_probe(int(workgroups), int(iters), 1 if fp16 else 0, _ptr(out), _stream(stream))
-    if rc != SSM_OK:
-        raise SsmError(rc, "ssm_mfma_probe")
-    return out
+def ssm_set_spin_limit(polls: int) -> int:
+    """Test hook: bound on the polls of a cross-workgroup wait.  Returns the previous bound."""
+    return int(lib().ssm_set_spin_limit(int(polls)))
 
 
 def ssm_half_glu_workspace_bytes(T: int, H: int, want_bwd: bool) -> int:
@@ -400,7 +400,7 @@ def ssm_half_glu_fwd(u, W, *, want_gate=True, workspace=None, y=None, gate=None,
     _chk(W, torch.float32, (H, H), "W")
     _chk(y, torch.float32, (T, H), "y")
     _chk(gate, torch.float32, (T, H), "gate")
-    ws = workspace if workspace is not None else _glu_workspace(T, H, False, u.device)
+    ws = workspace if workspace is not None else _own_workspace(_glu_workspace(T, H, False, u.device), stream)
     y = y if y is not None else torch.empty_like(u)
     if gate is None and want_gate:
         gate = torch.empty_like(u)
@@ -418,7 +418,7 @@ def ssm_half_glu_bwd(u, W, gate, dy, *, workspace=None, du=None, dW=None, stream
         _chk(t, torch.float32, (T, H), name)
     _chk(W, torch.float32, (H, H), "W")
     _chk(dW, torch.float32, (H, H), "dW")
-    ws = workspace if workspace is not None else _glu_workspace(T, H, True, u.device)
+    ws = workspace if workspace is not None else _own_workspace(_glu_workspace(T, H, True, u.device), stream)
     du = du if du is not None else torch.empty_like(u)
     dW = dW if dW is not None else torch.empty_like(W)
     rc = lib().ssm_half_glu_bwd(_ptr(u), _ptr(W), _ptr(gate), _ptr(dy), T, H, _ptr(du), _ptr(dW), _ptr(ws), ws.numel(),
@@ -455,7 +455,7 @@ def ssm_block_fwd(Lambda, B, C, D, log_delta, W, u, is_first=None, x0=None, *, w
     _chk(u, torch.float32, (Bt, L, H), "u")
     _chk(is_first, torch.uint8, (Bt, L), "is_first")
     _chk(x0, torch.complex64, (Bt, P), "x0")
-    ws = workspace if workspace is not None else _block_workspace(Bt, L, H, P, False, u.device)
+    ws = workspace if workspace is not None else _own_workspace(_block_workspace(Bt, L, H, P, False, u.device), stream)
     y, out = torch.empty_like(u), torch.empty_like(u)
     gate = torch.empty_like(u) if want_gate else None
     x = torch.empty((Bt, L, P), dtype=torch.complex64, device=u.device)
@@ -477,7 +477,7 @@ def ssm_block_bwd(Lambda, B, C, D, log_delta, W, u, is_first, x0, x, y, gate, do
         _chk(t, torch.float32, (Bt, L, H), name)
     _chk(x, torch.complex64, (Bt, L, P), "x")
     _chk(W, torch.float32, (H, H), "W")
-    ws = workspace if workspace is not None else _block_workspace(Bt, L, H, P, True, u.device)
+    ws = workspace if workspace is not None else _own_workspace(_block_workspace(Bt, L, H, P, True, u.device), stream)
     o = {"du": torch.empty_like(u), "dLambda": torch.empty_like(Lambda), "dB": torch.empty_like(B),
          "dC": torch.empty_like(C), "dD": torch.empty_like(D), "dlog_delta": torch.empty_like(log_delta),
          "dx0": torch.empty((Bt, P), dtype=torch.complex64, device=u.device), "dW": torch.empty_like(W)}

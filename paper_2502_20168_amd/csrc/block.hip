@@ -2,7 +2,7 @@
 // section and the half-GLU gate of the S5 sequence layer (appendix), with their adjoints.
 #include "../../include/ssm.h"
 #include "ssm_internal.h"
-#include "gemm_f32_kernel.h"
+#include "gemm_common.h"
 
 namespace ssm {
 namespace {

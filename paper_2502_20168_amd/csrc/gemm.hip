@@ -1,16 +1,12 @@
 // Tile selection and launch of the projection GEMMs.
 //
-// Two kernels compute the same fp32-in / fp32-out product:
-//   * gemm_bf16x3_ws_kernel (default): both operands split while they are staged -- exactly into
-//     three bf16 planes (six bf16 MFMAs per k block), or, when the largest magnitude of both operands
-//     is known, into two fp16 planes of the operand scaled by a power of two (three fp16 MFMAs per
-//     k block); fp32 accumulation and fp32-class accuracy either way, at several times the fp32
-//     matrix rate;
-//   * gemm_f32_kernel: plain fp32 MFMA, selected with the environment variable SSM_GEMM_F32=1
-//     (kept as the reference point for the measurement of the default kernel).
-#include "gemm_bf16x3_kernel.h"
-
-#include <cstdlib>
+// One kernel template (gemm_kernel.h) computes the fp32-in / fp32-out products on the 16-bit matrix
+// cores with both operands split while they are staged: exactly into three bf16 planes (six bf16
+// MFMAs per k block), or, when the largest magnitude of both operands is known, into two fp16 planes
+// of the operand scaled by a power of two (three fp16 MFMAs per k block); fp32 accumulation and
+// fp32-class accuracy either way.  The instantiations live in gemm_inst2.hip / gemm_inst3.hip (one
+// problem per launch) and gemm_pair.hip (several problems per launch).
+#include "gemm_kernel.h"
 
 namespace ssm {
 
@@ -29,27 +25,8 @@ int gemm_pick_splits(int64_t M, int64_t N, int64_t K, int64_t partner_tiles)
     return (int)s;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN>
-static hipError_t dispatch_f32(const GemmArgs &a, hipStream_t s)
-{
-    const bool epi = a.epilogue == 1;
-    if (a.epilogue == 2) {
-        if (a.a_kcontig && a.b_kcontig) return launch_gemm_variant<BM, BN, BK, WGM, WGN, true, true, 2>(a, s);
-        return hipErrorInvalidValue;
-    }
-    if (a.a_kcontig && a.b_kcontig)
-        return epi ? launch_gemm_variant<BM, BN, BK, WGM, WGN, true, true, true>(a, s)
-                   : launch_gemm_variant<BM, BN, BK, WGM, WGN, true, true, false>(a, s);
-    if (a.a_kcontig && !a.b_kcontig)
-        return epi ? launch_gemm_variant<BM, BN, BK, WGM, WGN, true, false, true>(a, s)
-                   : launch_gemm_variant<BM, BN, BK, WGM, WGN, true, false, false>(a, s);
-    if (!a.a_kcontig && !a.b_kcontig && !epi)
-        return launch_gemm_variant<BM, BN, BK, WGM, WGN, false, false, false>(a, s);
-    return hipErrorInvalidValue;
-}
-
-// Layout code of a problem, or -1 when the bf16x3 kernel has no instantiation for it.
-static int layout_of(const GemmArgs &a)
+// Layout code of a problem, or -1 when the projection kernel has no instantiation for it.
+int gemm_layout_of(const GemmArgs &a)
 {
     if (a.epilogue == 2) return (a.a_kcontig && a.b_kcontig) ? gemm_layout(true, true, 2) : -1;
     if (a.epilogue == 3) return (a.a_kcontig && !a.b_kcontig) ? gemm_layout(true, false, 3) : -1;
@@ -63,40 +40,13 @@ static int layout_of(const GemmArgs &a)
     return -1;
 }
 
-template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL>
-static hipError_t dispatch_bf16x3(const GemmArgs &a, hipStream_t s)
+bool gemm_use_two_planes(const GemmArgs &a)
 {
-    switch (layout_of(a)) {
-#define SSM_CASE(akc, bkc, epi) \
-    case gemm_layout(akc, bkc, epi): \
-        return launch_gemm_bf16x3_ws_variant<BM, BN, BK, WGM, WGN, NP, NS, NPL, gemm_layout(akc, bkc, epi)>(a, s);
-        SSM_CASE(true, true, 0) SSM_CASE(true, true, 1) SSM_CASE(true, true, 2)
-        SSM_CASE(true, false, 0) SSM_CASE(true, false, 1) SSM_CASE(false, false, 0)
-        SSM_CASE(true, false, 3) SSM_CASE(true, true, 4) SSM_CASE(true, false, 5) SSM_CASE(true, true, 6)
-#undef SSM_CASE
-    default: return hipErrorInvalidValue;
-    }
-}
-
-static bool use_f32_mfma()
-{
-    const char *e = std::getenv("SSM_GEMM_F32");
-    return e && e[0] == '1';
-}
-
-// A product whose operands both come with their largest magnitude is staged as two scaled fp16
-// planes per operand (three matrix instructions per k block instead of six, same accuracy class);
-// SSM_GEMM_SPLIT=3 keeps the three-way bf16 split everywhere (for comparison).
-bool gemm_two_planes_enabled()
-{
-    const char *e = std::getenv("SSM_GEMM_SPLIT");
-    return !(e && e[0] == '3') && !use_f32_mfma();
-}
-static bool use_two_planes(const GemmArgs &a)
-{
+    // A product whose operands both come with their largest magnitude is staged as two scaled fp16
+    // planes per operand (three matrix instructions per k block instead of six, same accuracy class).
     // A: one maximum, or one per row when its rows are contiguous along k; B: one maximum
     const bool a_ok = (a.amaxA.rows && a.amaxA.row_parts > 0 && a.a_kcontig) || (!a.amaxA.rows && a.amaxA.slots && a.amaxA.n > 0);
-    return a_ok && a.amaxB.slots && a.amaxB.n > 0 && gemm_two_planes_enabled();
+    return a_ok && a.amaxB.slots && a.amaxB.n > 0;
 }
 
 bool gemm_scan_shape_ok(int64_t Bt, int64_t L, int64_t P)
@@ -112,26 +62,10 @@ bool gemm_scan_shape_ok(int64_t Bt, int64_t L, int64_t P)
     return tiles >= 64 && tiles * 64 <= 0x7fffffffLL;
 }
 
-// SSM_FUSED_SCAN=0 keeps every projection and its scan as two kernels, =1 fuses only the forward
-// pair (both for comparison); default: forward and gradient pass fused.
-bool gemm_can_scan(int64_t Bt, int64_t L, int64_t P)
-{
-    const char *e = std::getenv("SSM_FUSED_SCAN");
-    if (e && e[0] == '0') return false;
-    return !use_f32_mfma() && gemm_scan_shape_ok(Bt, L, P);
-}
-
-bool gemm_can_scan_reverse(int64_t Bt, int64_t L, int64_t P)
-{
-    const char *e = std::getenv("SSM_FUSED_SCAN");
-    if (e && (e[0] == '0' || e[0] == '1')) return false;
-    return !use_f32_mfma() && gemm_scan_shape_ok(Bt, L, P);
-}
-
 // argument checks shared by the two scanning epilogues
-static bool scan_args_ok(const GemmArgs &a)
+bool gemm_scan_args_ok(const GemmArgs &a)
 {
-    if (a.splits > 1 || use_f32_mfma() || !a.scan.lam || !a.scan.err || a.scan.L <= 0) return false;
+    if (a.splits > 1 || !a.scan.lam || !a.scan.err || a.scan.L <= 0) return false;
     const int L = a.scan.L;
     const bool chain = L % SCAN_TILE == 0 && L / SCAN_TILE <= SCAN_MAX_CHAIN && a.scan.desc;
     const bool whole = L < SCAN_TILE && SCAN_TILE % L == 0 && L % SCAN_RC == 0 && a.M % SCAN_TILE == 0;
@@ -151,19 +85,12 @@ size_t gemm_scan_desc_bytes(int64_t Bt, int64_t L, int64_t P)
 // The output projection y = x Cc^T + D u has only M/128 * H/128 tiles of 128x128.  When they would
 // fill less than the chip but twice as many would, the product runs as two halves of K (256
 // workgroups of the efficient 128x128 tile instead of 64x128 tiles) into two slabs, and a streaming
-// kernel adds them and applies the store function.  SSM_SPLIT_OUT=0 switches this off (for comparison).
+// kernel adds them and applies the store function.
 bool gemm_out_split_shape(int64_t T, int64_t H, int64_t P)
 {
     // a half must still be long enough (8 K tiles) to pay for the streaming pass
     const int64_t tiles = ((T + 127) / 128) * ((H + 127) / 128);
     return tiles < 200 && 2 * tiles >= 200 && P >= 256 && (2 * P) % 64 == 0;
-}
-
-bool gemm_out_split(int64_t T, int64_t H, int64_t P)
-{
-    const char *e = std::getenv("SSM_SPLIT_OUT");
-    if (e && e[0] == '0') return false;
-    return !use_f32_mfma() && gemm_out_split_shape(T, H, P);
 }
 
 // The store function of a product that ran as two K halves, applied to v = s0 + s1 (n = rows * H elements):
@@ -234,7 +161,7 @@ hipError_t launch_sum_halves(const float *s0, const float *s1, const float *D, c
 hipError_t launch_gemm_halved(const GemmArgs &a, float *halves, hipStream_t s)
 {
     const bool store_fn = a.epilogue == 1 || a.epilogue == 3 || a.epilogue == 4 || a.epilogue == 6;
-    if (!halves || !store_fn || a.splits > 1 || a.ldc != a.N || (a.E && a.lde != a.N) || !gemm_out_split(a.M, a.N, a.K / 2) ||
+    if (!halves || !store_fn || a.splits > 1 || a.ldc != a.N || (a.E && a.lde != a.N) || !gemm_out_split_shape(a.M, a.N, a.K / 2) ||
         a.K % 2 != 0)
         return launch_gemm(a, s);
     GemmArgs g = a;
@@ -252,19 +179,11 @@ hipError_t launch_gemm_halved(const GemmArgs &a, float *halves, hipStream_t s)
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
 {
     if (a.M <= 0 || a.N <= 0 || a.K <= 0) return hipErrorInvalidValue;
-    if (a.epilogue == 7) {
-        // the input projection that scans its own output: 128x128 tiles only
-        if (!scan_args_ok(a)) return hipErrorInvalidValue;
-        if (use_two_planes(a))
-            return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, gemm_layout(true, true, 7)>(a, s);
-        return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 3, gemm_layout(true, true, 7)>(a, s);
-    }
-    if (a.epilogue == 8) {
-        // C^H dy that runs the reverse scan on its own output
-        if (!scan_args_ok(a)) return hipErrorInvalidValue;
-        if (use_two_planes(a))
-            return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, gemm_layout(true, false, 8)>(a, s);
-        return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 3, gemm_layout(true, false, 8)>(a, s);
+    const bool two = gemm_use_two_planes(a);
+    if (a.epilogue == 7 || a.epilogue == 8) {
+        // a projection that scans its own output (forward: the input projection; reverse: C^H dy): 128x128 tiles only
+        if (!gemm_scan_args_ok(a) || gemm_layout_of(a) < 0) return hipErrorInvalidValue;
+        return two ? gemm_dispatch_two_planes(a, 0, s) : gemm_dispatch_three_planes(a, 0, s);
     }
     if (a.splits > 1 && a.epilogue) return hipErrorInvalidValue;
     if (a.epilogue < 0 || a.epilogue > 6 || (a.epilogue && a.epilogue != 5 && !a.E)) return hipErrorInvalidValue;
@@ -272,57 +191,15 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
     if ((a.epilogue == 1 || a.epilogue == 2 || a.epilogue == 6) && !a.diag) return hipErrorInvalidValue;
     if (a.epilogue == 6 && !a.C2) return hipErrorInvalidValue;
     if (a.epilogue == 4 && (!a.E2 || !a.E3)) return hipErrorInvalidValue;
-    const long splits = a.splits < 1 ? 1 : a.splits;
-    const long tiles128 = (long)((a.M + 127) / 128) * ((a.N + 127) / 128) * splits;
-    if (use_f32_mfma() && a.epilogue < 3) {              // the gate epilogues exist for bf16x3 only
-        // measured on MI355X: 128x128 tiles with 8 wavefronts when they give every CU a workgroup,
-        // 64x64 tiles otherwise
-        if (tiles128 >= 256) {
-            if (a.a_kcontig && a.b_kcontig) return dispatch_f32<128, 128, 32, 4, 2>(a, s);
-            return dispatch_f32<128, 128, 16, 4, 2>(a, s);
-        }
-        if (a.a_kcontig && a.b_kcontig) return dispatch_f32<64, 64, 32, 2, 2>(a, s);
-        return dispatch_f32<64, 64, 16, 2, 2>(a, s);
-    }
+    if (gemm_layout_of(a) < 0) return hipErrorInvalidValue;
     // measured on MI355X: 128x128x32 tiles with 4 consumer and 8 producer wavefronts when they give
     // (nearly) every CU a workgroup; else 64x128x32 tiles (staging per multiply-add is 1.5x there);
     // else, for the small products of step mode, 64x64x64 tiles (fewer, longer K steps)
+    const long splits = a.splits < 1 ? 1 : a.splits;
+    const long tiles128 = (long)((a.M + 127) / 128) * ((a.N + 127) / 128) * splits;
     const long tiles64x128 = (long)((a.M + 63) / 64) * ((a.N + 127) / 128) * splits;
-    if (use_two_planes(a)) {
-        if (tiles128 >= 200) return dispatch_bf16x3<128, 128, 32, 2, 2, 8, 2, 2>(a, s);
-        if (tiles64x128 >= 200) return dispatch_bf16x3<64, 128, 32, 2, 2, 8, 2, 2>(a, s);
-        return dispatch_bf16x3<64, 64, 64, 2, 2, 8, 2, 2>(a, s);
-    }
-    if (tiles128 >= 200) return dispatch_bf16x3<128, 128, 32, 2, 2, 8, 2, 3>(a, s);
-    if (tiles64x128 >= 200) return dispatch_bf16x3<64, 128, 32, 2, 2, 8, 2, 3>(a, s);
-    return dispatch_bf16x3<64, 64, 64, 2, 2, 8, 2, 3>(a, s);
-}
-
-// Two independent problems in one launch of 128x128 tiles.  The pairs of the gradient pass:
-//   C^H dy (row-major A, B read along N; plain or running the reverse scan on its output)
-//                                                 with  dy^T x  (K = T reduction in slabs)
-//   Bbar^H chi + D dy (same layout, epilogue 1)   with  chi^T u (K = T reduction in slabs)
-hipError_t launch_gemm_pair(const GemmArgs &a, const GemmArgs &b, hipStream_t s, bool second_first)
-{
-    if (a.M <= 0 || a.N <= 0 || a.K <= 0 || b.M <= 0 || b.N <= 0 || b.K <= 0) return hipErrorInvalidValue;
-    if ((a.splits > 1 && a.epilogue) || (b.splits > 1 && b.epilogue)) return hipErrorInvalidValue;
-    if (!use_f32_mfma()) {
-        constexpr int NN0 = gemm_layout(true, false, 0), NN1 = gemm_layout(true, false, 1),
-                      NN8 = gemm_layout(true, false, 8), TN0 = gemm_layout(false, false, 0);
-        const int la = layout_of(a), lb = layout_of(b);
-        if (la == NN8 && !scan_args_ok(a)) return hipErrorInvalidValue;
-        if (use_two_planes(a) && use_two_planes(b)) {
-            if (la == NN8 && lb == TN0) return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, NN8, TN0>(a, s, &b, second_first);
-            if (la == NN0 && lb == TN0) return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, NN0, TN0>(a, s, &b, second_first);
-            if (la == NN1 && lb == TN0) return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, NN1, TN0>(a, s, &b, second_first);
-        } else {
-            if (la == NN8 && lb == TN0) return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 3, NN8, TN0>(a, s, &b, second_first);
-            if (la == NN0 && lb == TN0) return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 3, NN0, TN0>(a, s, &b, second_first);
-            if (la == NN1 && lb == TN0) return launch_gemm_bf16x3_ws_variant<128, 128, 32, 2, 2, 8, 2, 3, NN1, TN0>(a, s, &b, second_first);
-        }
-    }
-    hipError_t e = launch_gemm(a, s);
-    return e != hipSuccess ? e : launch_gemm(b, s);
+    const int tier = tiles128 >= 200 ? 0 : (tiles64x128 >= 200 ? 1 : 2);
+    return two ? gemm_dispatch_two_planes(a, tier, s) : gemm_dispatch_three_planes(a, tier, s);
 }
 
 }  // namespace ssm

@@ -17,7 +17,7 @@
 // the 16-byte fragment reads of 16 consecutive rows fall into distinct banks).
 #pragma once
 
-#include "gemm_f32_kernel.h"
+#include "gemm_common.h"
 #include "lookback.h"
 
 #include <atomic>
@@ -483,8 +483,10 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
                 const int j = REV ? nt - 1 - k : k;
                 const size_t ptile = (size_t)(b * nt + j) * g.ntn + tn;
                 if (!wait_pair(a.desc + (ptile * 64 + c) * 2, 1u, a.spin_limit, Sj, tag)) {
-                    atomicOr(a.err, 1u);                 // gave up: flag it and finish anyway
-                    Sj = make_float2(0.f, 0.f); tag = 2;
+                    // gave up: flag it, hand on NaN (every state that depends on the missing aggregate
+                    // becomes NaN, so the failure cannot pass as data) and finish anyway
+                    atomicOr(a.err, 1u);
+                    Sj = make_float2(__builtin_nanf(""), __builtin_nanf("")); tag = 2;
                 }
             }
             lds.pS[k * 64 + c] = Sj;
@@ -596,7 +598,7 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
 constexpr int gemm_rowexp_halves(int BM, int NPL) { return NPL == 2 ? 2 * BM + 8 : 0; }   // BM + 1 ints, 16-byte multiple
 
 template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL, bool AKC, bool BKC, int EPI, bool FAST>
-__device__ __forceinline__ void gemm_bf16x3_ws_tile(const GemmDev &g, __bf16 *smem, int m0, int n0, int z,
+__device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int m0, int n0, int z,
                                                     int kbeg, int kend, int scan_tile)
 {
     constexpr int NC = WGM * WGN;                 // consumer wavefronts
@@ -1015,7 +1017,7 @@ __device__ __forceinline__ void gemm_place(const GemmDev &g, int x, int q, int &
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL, int LAY>
-__device__ __forceinline__ void gemm_bf16x3_ws_problem(const GemmDev &g, __bf16 *smem, int x, int q)
+__device__ __forceinline__ void gemm_ws_problem(const GemmDev &g, __bf16 *smem, int x, int q)
 {
     constexpr bool AKC = (LAY & 1) != 0, BKC = (LAY & 2) != 0;
     constexpr int EPI = LAY >> 2;
@@ -1030,9 +1032,9 @@ __device__ __forceinline__ void gemm_bf16x3_ws_problem(const GemmDev &g, __bf16 
                       (g.ldb % 4 == 0) && ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0) &&
                       (m0 + BM <= g.M) && (n0 + BN <= g.N) && ((kend - kbeg) % BK == 0);
     if (fast)
-        gemm_bf16x3_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, NPL, AKC, BKC, EPI, true>(g, smem, m0, n0, z, kbeg, kend, tile);
+        gemm_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, NPL, AKC, BKC, EPI, true>(g, smem, m0, n0, z, kbeg, kend, tile);
     else
-        gemm_bf16x3_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, NPL, AKC, BKC, EPI, false>(g, smem, m0, n0, z, kbeg, kend, tile);
+        gemm_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, NPL, AKC, BKC, EPI, false>(g, smem, m0, n0, z, kbeg, kend, tile);
 }
 
 // One launch carries one problem (LAY1 < 0) or two independent ones (used for the gradient
@@ -1040,7 +1042,7 @@ __device__ __forceinline__ void gemm_bf16x3_ws_problem(const GemmDev &g, __bf16 
 // alone would leave compute units idle).  The slots of the first problem come first in every XCD
 // unless the launch asks for the second one first (the longer work items should start first).
 template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL, int LAY0, int LAY1>
-__global__ void __launch_bounds__(64 * (WGM * WGN + NP)) gemm_bf16x3_ws_kernel(GemmDev g0, GemmDev g1)
+__global__ void __launch_bounds__(64 * (WGM * WGN + NP)) gemm_ws_kernel(GemmDev g0, GemmDev g1)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);
@@ -1048,9 +1050,9 @@ __global__ void __launch_bounds__(64 * (WGM * WGN + NP)) gemm_bf16x3_ws_kernel(G
     // slots of an XCD: the first problem's, then the second's -- or the other way round when asked
     const bool first = LAY1 < 0 || (g1.second_first ? q >= g1.nx : q < g1.slot0);
     if (first)
-        gemm_bf16x3_ws_problem<BM, BN, BK, WGM, WGN, NP, NS, NPL, LAY0>(g0, smem, x, g1.second_first && LAY1 >= 0 ? q - g1.nx : q);
+        gemm_ws_problem<BM, BN, BK, WGM, WGN, NP, NS, NPL, LAY0>(g0, smem, x, g1.second_first && LAY1 >= 0 ? q - g1.nx : q);
     else
-        gemm_bf16x3_ws_problem<BM, BN, BK, WGM, WGN, NP, NS, NPL, (LAY1 < 0 ? LAY0 : LAY1)>(g1, smem, x,
+        gemm_ws_problem<BM, BN, BK, WGM, WGN, NP, NS, NPL, (LAY1 < 0 ? LAY0 : LAY1)>(g1, smem, x,
                                                                                              g1.second_first ? q : q - g1.slot0);
 }
 
@@ -1096,7 +1098,7 @@ inline GemmDev make_gemm_dev(const GemmArgs &a)
 
 // b == nullptr: one problem (LAY1 is ignored and must be -1).
 template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL, int LAY0, int LAY1 = -1>
-hipError_t launch_gemm_bf16x3_ws_variant(const GemmArgs &a, hipStream_t s, const GemmArgs *b = nullptr,
+hipError_t launch_gemm_ws_variant(const GemmArgs &a, hipStream_t s, const GemmArgs *b = nullptr,
                                         bool second_first = false)
 {
     GemmDev g0 = make_gemm_dev<BM, BN, BK>(a);
@@ -1109,7 +1111,7 @@ hipError_t launch_gemm_bf16x3_ws_variant(const GemmArgs &a, hipStream_t s, const
     constexpr bool scans = ((LAY0 >> 2) >= 7) || (LAY1 >= 0 && (LAY1 >> 2) >= 7);
     constexpr size_t smem = (scans && SCAN_LDS_BYTES > stage_bytes) ? SCAN_LDS_BYTES : stage_bytes;
     static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS of a gfx950 CU");
-    auto kern = gemm_bf16x3_ws_kernel<BM, BN, BK, WGM, WGN, NP, NS, NPL, LAY0, LAY1>;
+    auto kern = gemm_ws_kernel<BM, BN, BK, WGM, WGN, NP, NS, NPL, LAY0, LAY1>;
     if (smem > 64 * 1024) {
         // raising the dynamic LDS limit is idempotent; once per instantiation and device is enough
         // (the attribute belongs to the device's copy of the kernel)

@@ -219,8 +219,11 @@ __global__ void __launch_bounds__(SCAN_THREADS) scan_kernel(ScanArgs a)
             const ScanDesc *pred = mine - (size_t)(tb - j) * desc_stride;
             unsigned tag = 0;
             if (!wait_pair(pred->agg, 1u, a.spin_limit, Sj, tag)) {
-                atomicOr(a.err, 1u);                 // gave up: flag it and finish anyway
-                Sj = make_float2(0.f, 0.f);
+                // gave up: flag it, hand on NaN (the states that depend on the missing aggregate become
+                // NaN, so the failure cannot pass as data) and finish anyway
+                atomicOr(a.err, 1u);
+                Sj = make_float2(__builtin_nanf(""), __builtin_nanf(""));
+                Aj = make_float2(0.f, 0.f);
             } else {
                 Aj = (tag == 2u) ? make_float2(0.f, 0.f) : pow_block(lam, a.cy);
             }
@@ -231,8 +234,12 @@ __global__ void __launch_bounds__(SCAN_THREADS) scan_kernel(ScanArgs a)
             const ScanDesc *pred = mine - (size_t)(tb - sg0 + 1) * desc_stride;
             unsigned tag = 0;
             float2 incl;
-            if (!wait_pair(pred->incl, 3u, a.spin_limit, incl, tag)) atomicOr(a.err, 1u);
-            else Xin = incl;
+            if (!wait_pair(pred->incl, 3u, a.spin_limit, incl, tag)) {
+                atomicOr(a.err, 1u);
+                Xin = make_float2(__builtin_nanf(""), __builtin_nanf(""));
+            } else {
+                Xin = incl;
+            }
         }
         __syncthreads();
         if (lastchunk) {

@@ -1,12 +1,73 @@
 // Host side of libssmscan: argument validation, workspace layout and the kernel sequences of
 // the forward and the gradient pass.  See include/ssm.h for the contract of every entry point.
 #include "../../include/ssm.h"
+#include "../../include/ssm_measure.h"
 #include "ssm_internal.h"
 
-#include <cstdlib>
+#include <atomic>
 #include <vector>
 
 using namespace ssm;
+
+namespace ssm {
+
+namespace {
+constexpr size_t WS_ALIGN = 256;
+inline size_t up256(size_t v) { return (v + WS_ALIGN - 1) / WS_ALIGN * WS_ALIGN; }
+inline bool off_align(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+}  // namespace
+
+int make_scan_layout(int64_t Bt, int64_t L, int64_t P, bool rev, ScanOnlyLayout &o)
+{
+    if (Bt <= 0 || L <= 0 || P <= 0) return SSM_ERR_INVALID_ARG;
+    if (P > SSM_MAX_WIDTH) return SSM_ERR_UNSUPPORTED;
+    if (Bt > SSM_MAX_TOKENS || L > SSM_MAX_TOKENS || Bt > SSM_MAX_TOKENS / L) return SSM_ERR_UNSUPPORTED;
+    if (Bt * L > SSM_MAX_ELEMS / (2 * P)) return SSM_ERR_UNSUPPORTED;
+    o.plan = plan_scan(Bt, L, P);
+    if (o.plan.nblocks > 0x7fffffffLL) return SSM_ERR_UNSUPPORTED;
+    size_t off = 0;
+    o.hdr = off; off += up256(sizeof(WsHeader));
+    o.ticket = off; off += up256(o.plan.ticket_bytes);
+    o.desc = off; off += up256(o.plan.desc_bytes);
+    o.dApart = off; if (rev) off += up256(o.plan.partial_elems * 8);
+    o.total = off;
+    return SSM_OK;
+}
+
+// ssm_scan_states on a caller's workspace, or on the built-in scratch of the no-allocation entry point
+int scan_states_forward(const void *A_bar, void *v, const uint8_t *is_first, const void *x0, int64_t Bt, int64_t L,
+                        int64_t P, void *x_last, void *workspace, size_t ws_bytes, hipStream_t s)
+{
+    if (!A_bar || !v) return SSM_ERR_INVALID_ARG;
+    ScanOnlyLayout lo;
+    const int st = make_scan_layout(Bt, L, P, false, lo);
+    if (st != SSM_OK) return st;
+    if (off_align(A_bar, 8) || off_align(v, 8) || off_align(x0, 8) || off_align(x_last, 8)) return SSM_ERR_INVALID_ARG;
+    if (!workspace || off_align(workspace, WS_ALIGN) || ws_bytes < lo.total) return SSM_ERR_WORKSPACE;
+    char *ws = static_cast<char *>(workspace);
+    WsHeader *hdr = reinterpret_cast<WsHeader *>(ws + lo.hdr);
+    ScanDesc *desc = reinterpret_cast<ScanDesc *>(ws + lo.desc);
+    if (lo.plan.nTB > 1 &&
+        launch_clear(hdr, ws + lo.ticket, lo.desc + up256(lo.plan.desc_bytes) - lo.ticket, s) != hipSuccess)
+        return SSM_ERR_HIP;
+    ScanArgs sa{};
+    sa.in = static_cast<const float2 *>(v); sa.out = static_cast<float2 *>(v);
+    sa.lam = static_cast<const float2 *>(A_bar); sa.is_first = is_first;
+    sa.x0 = static_cast<const float2 *>(x0); sa.x_last = static_cast<float2 *>(x_last);
+    sa.desc = desc; sa.ticket = reinterpret_cast<uint32_t *>(ws + lo.ticket); sa.err = &hdr->err;
+    sa.Bt = (int)Bt; sa.L = (int)L; sa.P = (int)P;
+    sa.pxb = lo.plan.pxb; sa.cy = lo.plan.cy; sa.nPX = lo.plan.nPX; sa.nTB = lo.plan.nTB;
+    sa.spin_limit = scan_spin_limit();
+    return launch_scan(sa, false, s) == hipSuccess ? SSM_OK : SSM_ERR_HIP;
+}
+
+// upper bound on the polls of one cross-workgroup wait (each poll sleeps ~128 clocks); the only
+// process-wide setting of the library, changed through ssm_set_spin_limit (a test hook)
+static std::atomic<uint32_t> g_spin_limit{1u << 20};
+uint32_t scan_spin_limit() { return g_spin_limit.load(std::memory_order_relaxed); }
+uint32_t scan_set_spin_limit(uint32_t polls) { return g_spin_limit.exchange(polls, std::memory_order_relaxed); }
+
+}  // namespace ssm
 
 namespace {
 
@@ -96,13 +157,7 @@ inline int pass_pieces(size_t n)
 
 inline bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 
-uint32_t spin_limit()
-{
-    // upper bound on the polls of one cross-workgroup wait (each poll sleeps ~128 clocks)
-    const char *e = std::getenv("SSM_SPIN_LIMIT");
-    if (e && *e) return (uint32_t)std::strtoul(e, nullptr, 10);
-    return 1u << 20;
-}
+inline uint32_t spin_limit() { return scan_spin_limit(); }
 
 // Records an event on the stream around every stage when timing is requested.
 struct StageTimer {
@@ -158,7 +213,7 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
 
     // Shapes whose sequences are whole numbers of 128-row tiles: the input projection scans its own
     // output tile and stores the states directly (no scan kernel, Bbar u never goes to memory).
-    const bool fused = gemm_can_scan(Bt, L, P);
+    const bool fused = gemm_scan_shape_ok(Bt, L, P);
     MARK();
     if (!fused && lo.plan.nTB > 1)
         HIP_TRY(launch_clear(hdr, ws + lo.ticket, lo.desc + up(lo.plan.desc_bytes) - lo.ticket, s));
@@ -170,7 +225,7 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     // the atomic slots and the tagged words behind them are cleared in the same launch
     if (fused) { pa.zero16 = reinterpret_cast<uint4 *>(ws + lo.amax_atomic); pa.n16 = (ABSMAX_SLOTS * 4 + lo.fdesc_bytes) / 16; }
     // two scaled fp16 planes per operand: every operand of the two products brings its largest magnitude
-    const bool two_planes = fused && gemm_two_planes_enabled();
+    const bool two_planes = fused;
     unsigned *am_bbar = reinterpret_cast<unsigned *>(ws + lo.amax_slots), *am_cc = am_bbar + P;
     unsigned *rowmax = reinterpret_cast<unsigned *>(ws + lo.rowmax), *rowpart = reinterpret_cast<unsigned *>(ws + lo.rowpart);
     if (two_planes) {
@@ -220,7 +275,7 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     g2.B = Cc; g2.ldb = 2 * P; g2.b_kcontig = 1;
     g2.M = T; g2.N = (int)H; g2.K = (int)(2 * P);
     if (two_planes) { g2.amaxA = AbsMax{nullptr, 0, rowpart, lo.row_parts, T}; g2.amaxB = AbsMax{am_cc, (int)H, nullptr, 0, 0}; }
-    if (lo.yhalves && gemm_out_split(T, H, P)) {
+    if (lo.yhalves) {
         // too few 128x128 tiles for the chip: two K halves into two slabs, then one streaming pass
         float *halves = reinterpret_cast<float *>(ws + lo.yhalves);
         g2.C = halves; g2.ldc = H; g2.splits = 2;
@@ -273,7 +328,7 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
 
     // Shapes whose sequences are whole numbers of 128-row tiles: C^H dy runs the reverse scan on its
     // own output tile (chi stored directly, dAbar rows per tile, no scan kernel).
-    const bool fused = gemm_can_scan_reverse(Bt, L, P);
+    const bool fused = gemm_scan_shape_ok(Bt, L, P);
     MARK();
     if (!fused && lo.plan.nTB > 1)
         HIP_TRY(launch_clear(hdr, ws + lo.ticket, lo.desc + up(lo.plan.desc_bytes) - lo.ticket, s));
@@ -287,7 +342,7 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     pa.cd.a = dy; pa.cd.b = u; pa.cd.T = T; pa.cd.H = (int)H; pa.cd.nslab = lo.nslab; pa.cd.partial = dDpart;
     // two scaled fp16 planes per operand: dy and u are measured where dD reads them, the saved states
     // by a pass of their own, chi where the reverse scan stores it
-    const bool two_planes = fused && gemm_two_planes_enabled();
+    const bool two_planes = fused;
     unsigned *am_atomic = reinterpret_cast<unsigned *>(ws + lo.amax_atomic);
     unsigned *am_bbar = reinterpret_cast<unsigned *>(ws + lo.amax_slots), *am_cc = am_bbar + P, *am_pass = am_cc + H;
     unsigned *am_dy = am_pass + 2 * PREP_PASS_BLOCKS, *am_u = am_dy + lo.amax_cd;
@@ -359,7 +414,7 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     g6.C = dBpart; g6.ldc = H;
     g6.M = (int)(2 * P); g6.N = (int)H; g6.K = T; g6.splits = lo.splitB;
     if (two_planes) { g5.amaxA = mx_chi_rows; g5.amaxB = mx_bbar; g6.amaxA = mx_chi; g6.amaxB = mx_u; }
-    if (lo.yhalves && gemm_out_split(T, H, P)) {
+    if (lo.yhalves) {
         // du has too few 128x128 tiles for half a chip's worth of time: it runs as two K halves (twice
         // the workgroups, half as long) next to the long work items of the dBbar slabs, which start first;
         // a streaming pass adds the halves and D dy
@@ -393,23 +448,6 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     return SSM_OK;
 }
 
-struct ScanOnlyLayout { ScanPlan plan; size_t hdr, ticket, desc, dApart, total; };
-
-ssm_status make_scan_layout(int64_t Bt, int64_t L, int64_t P, bool rev, ScanOnlyLayout &o)
-{
-    ssm_status st = check_dims(Bt, L, 1, P);
-    if (st != SSM_OK) return st;
-    o.plan = plan_scan(Bt, L, P);
-    if (o.plan.nblocks > 0x7fffffffLL) return SSM_ERR_UNSUPPORTED;
-    size_t off = 0;
-    o.hdr = off; off += up(sizeof(WsHeader));
-    o.ticket = off; off += up(o.plan.ticket_bytes);
-    o.desc = off; off += up(o.plan.desc_bytes);
-    o.dApart = off; if (rev) off += up(o.plan.partial_elems * 8);
-    o.total = off;
-    return SSM_OK;
-}
-
 }  // namespace
 
 extern "C" {
@@ -427,7 +465,12 @@ const char *ssm_strerror(int status)
     }
 }
 
-int ssm_version(void) { return 100; }
+int ssm_version(void) { return 200; }
+
+uint32_t ssm_set_spin_limit(uint32_t polls)
+{
+    return scan_set_spin_limit(polls);
+}
 
 size_t ssm_workspace_bytes(int64_t Bt, int64_t L, int64_t H, int64_t P, int want_bwd)
 {
@@ -514,29 +557,8 @@ ssm_status ssm_scan_states(const ssm_c64 *A_bar, ssm_c64 *v, const uint8_t *is_f
                            const ssm_c64 *x0, int64_t Bt, int64_t L, int64_t P, ssm_c64 *x_last,
                            void *workspace, size_t ws_bytes, void *stream)
 {
-    if (!A_bar || !v) return SSM_ERR_INVALID_ARG;
-    ScanOnlyLayout lo;
-    ssm_status st = make_scan_layout(Bt, L, P, false, lo);
-    if (st != SSM_OK) return st;
-    if (misaligned(A_bar, 8) || misaligned(v, 8) || misaligned(x0, 8) || misaligned(x_last, 8))
-        return SSM_ERR_INVALID_ARG;
-    if (!workspace || misaligned(workspace, ALIGN) || ws_bytes < lo.total) return SSM_ERR_WORKSPACE;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    char *ws = static_cast<char *>(workspace);
-    WsHeader *hdr = reinterpret_cast<WsHeader *>(ws + lo.hdr);
-    ScanDesc *desc = reinterpret_cast<ScanDesc *>(ws + lo.desc);
-    if (lo.plan.nTB > 1)
-        HIP_TRY(launch_clear(hdr, ws + lo.ticket, lo.desc + up(lo.plan.desc_bytes) - lo.ticket, s));
-    ScanArgs sa{};
-    sa.in = reinterpret_cast<const float2 *>(v); sa.out = reinterpret_cast<float2 *>(v);
-    sa.lam = reinterpret_cast<const float2 *>(A_bar); sa.is_first = is_first;
-    sa.x0 = reinterpret_cast<const float2 *>(x0); sa.x_last = reinterpret_cast<float2 *>(x_last);
-    sa.desc = desc; sa.ticket = reinterpret_cast<uint32_t *>(ws + lo.ticket); sa.err = &hdr->err;
-    sa.Bt = (int)Bt; sa.L = (int)L; sa.P = (int)P;
-    sa.pxb = lo.plan.pxb; sa.cy = lo.plan.cy; sa.nPX = lo.plan.nPX; sa.nTB = lo.plan.nTB;
-    sa.spin_limit = spin_limit();
-    HIP_TRY(launch_scan(sa, false, s));
-    return SSM_OK;
+    return (ssm_status)scan_states_forward(A_bar, v, is_first, x0, Bt, L, P, x_last, workspace, ws_bytes,
+                                           static_cast<hipStream_t>(stream));
 }
 
 ssm_status ssm_scan_states_reverse(const ssm_c64 *A_bar, ssm_c64 *gx, const ssm_c64 *x,
@@ -546,7 +568,7 @@ ssm_status ssm_scan_states_reverse(const ssm_c64 *A_bar, ssm_c64 *gx, const ssm_
 {
     if (!A_bar || !gx || !x || !dA_bar) return SSM_ERR_INVALID_ARG;
     ScanOnlyLayout lo;
-    ssm_status st = make_scan_layout(Bt, L, P, true, lo);
+    ssm_status st = (ssm_status)make_scan_layout(Bt, L, P, true, lo);
     if (st != SSM_OK) return st;
     if (misaligned(A_bar, 8) || misaligned(gx, 8) || misaligned(x, 8) || misaligned(x0, 8) ||
         misaligned(dA_bar, 8) || misaligned(dx0, 8))

@@ -66,26 +66,27 @@ struct GemmArgs {
     ScanEpilogue scan;                               // epilogues 7 and 8
     AbsMax amaxA, amaxB;                             // largest magnitudes of A and B when known
 };
-// the input projection can scan its own output (epilogue 7) for this shape (shape only), and
-// whether it will on this call (shape and environment)
+// the input projection (epilogue 7) and C^H dy (epilogue 8, the reverse scan of the gradient pass) scan
+// their own output tiles at this shape
 bool gemm_scan_shape_ok(int64_t Bt, int64_t L, int64_t P);
-bool gemm_can_scan(int64_t Bt, int64_t L, int64_t P);
-// the same for C^H dy with the reverse scan of the gradient pass (epilogue 8)
-bool gemm_can_scan_reverse(int64_t Bt, int64_t L, int64_t P);
 // bytes of tagged words epilogues 7 and 8 need (zeroed before the launch)
 size_t gemm_scan_desc_bytes(int64_t Bt, int64_t L, int64_t P);
-// products may use the two-plane fp16 staging when their operands carry their largest magnitude
-bool gemm_two_planes_enabled();
+// a product is staged as two scaled fp16 planes per operand when both operands carry their largest magnitude
+bool gemm_use_two_planes(const GemmArgs &g);
+// argument checks of the scanning epilogues; layout code of a problem (-1: no instantiation)
+bool gemm_scan_args_ok(const GemmArgs &g);
+int gemm_layout_of(const GemmArgs &g);
 hipError_t launch_gemm(const GemmArgs &g, hipStream_t s);
-// the output projection as two K halves into two slabs plus a streaming sum: possible for this
-// shape (shape only), and taken on this call (shape and environment)
+// the instantiations of the kernel for one problem per launch (tier 0: 128x128x32 tiles, 1: 64x128x32, 2: 64x64x64)
+hipError_t gemm_dispatch_two_planes(const GemmArgs &g, int tier, hipStream_t s);
+hipError_t gemm_dispatch_three_planes(const GemmArgs &g, int tier, hipStream_t s);
+// the output projection runs as two K halves into two slabs plus a streaming sum at this shape
 bool gemm_out_split_shape(int64_t T, int64_t H, int64_t P);
-bool gemm_out_split(int64_t T, int64_t H, int64_t P);
 // y = s0 + s1 + D (.) u, and GELU(y) to gelu_y when it is not null
 hipError_t launch_sum_halves(const float *s0, const float *s1, const float *D, const float *u, float *y, float *gelu_y,
                              int64_t T, int64_t H, hipStream_t s);
 // a product with a store function (epilogue 1, 3, 4, 6): as two K halves into halves[2][M][N] plus a
-// streaming pass when gemm_out_split(M, N, K/2) says so and halves is not null; else launch_gemm
+// streaming pass when gemm_out_split_shape(M, N, K/2) says so and halves is not null; else launch_gemm
 hipError_t launch_gemm_halved(const GemmArgs &g, float *halves, hipStream_t s);
 // two independent problems in one launch (falls back to two launches for layouts without a
 // paired instantiation)
@@ -142,6 +143,14 @@ struct ScanArgs {
     uint32_t spin_limit;
 };
 hipError_t launch_scan(const ScanArgs &a, bool reverse, hipStream_t s);
+// workspace layout of the scan-level entry points: header, ticket counters, descriptors, partial rows
+struct ScanOnlyLayout { ScanPlan plan; size_t hdr, ticket, desc, dApart, total; };
+int make_scan_layout(int64_t Bt, int64_t L, int64_t P, bool rev, ScanOnlyLayout &o);   // returns an ssm_status
+// body of ssm_scan_states (returns an ssm_status); workspace may be any 256-byte aligned device memory
+int scan_states_forward(const void *A_bar, void *v, const uint8_t *is_first, const void *x0, int64_t Bt, int64_t L,
+                        int64_t P, void *x_last, void *workspace, size_t ws_bytes, hipStream_t s);
+uint32_t scan_spin_limit();
+uint32_t scan_set_spin_limit(uint32_t polls);
 // zeroes the header and `scratch_bytes` (a multiple of 16) of ticket counters + descriptors
 hipError_t launch_clear(WsHeader *hdr, void *scratch, size_t scratch_bytes, hipStream_t s);
 // out[p] = sum_i partial[i*P + p]

@@ -11,10 +11,18 @@ from paper_2502_20168_amd import workloads as wl
 # spec tolerances: relative 1e-4 for fp32 forward outputs, 1e-3 for gradients.  Each tensor
 # must pass BOTH a normwise test ||g - o||_2 <= tol ||o||_2 and a max-abs test
 # max|g - o| <= tol max|o| (element-wise relative error is undefined at zero crossings).
+# The gradients that are vectors of separate per-state (or per-feature, per-sequence) quantities --
+# dLambda, dlog_delta, dD, dx0 -- are additionally compared element by element:
+#   |g_i - o_i| <= tol |o_i| + FLOOR_FRAC * tol * rms(o)
+# Every such element is a sum of T (or T*H) fp32 products whose terms cancel, so its absolute error
+# follows the size of the terms, not the size of the element: the floor is that accumulation error,
+# taken as a fifth of the tolerance on an element of typical (rms) size.
 TOL_FWD = 1e-4
 TOL_GRAD = 1e-3
+FLOOR_FRAC = 0.2
 FWD_KEYS = ("y", "x", "x_last")
 GRAD_KEYS = ("du", "dLambda", "dB", "dC", "dD", "dlog_delta", "dx0")
+ELEMENTWISE_KEYS = ("dLambda", "dlog_delta", "dD", "dx0")
 NTHREADS = max(1, min(16, len(os.sched_getaffinity(0))))
 
 
@@ -37,6 +45,28 @@ def assert_close(got, ref, tol, name):
     return ne, me
 
 
+def assert_close_elementwise(got, ref, tol, name, floor_frac=FLOOR_FRAC):
+    """Every element within tol of its own reference value, plus a floor of floor_frac * tol * rms(ref).
+    Returns the largest ratio error / allowance over the elements (<= 1 passes)."""
+    got = np.asarray(got)
+    ref = np.asarray(ref)
+    assert got.shape == ref.shape, (got.shape, ref.shape)
+    if ref.size == 0:
+        return 0.0
+    err = np.abs(got.astype(ref.dtype) - ref)
+    rms = float(np.sqrt(np.mean(np.abs(ref) ** 2)))
+    allow = tol * np.abs(ref) + floor_frac * tol * rms
+    if rms == 0.0:
+        assert not np.any(err), name + ": reference is all zero, result is not"
+        return 0.0
+    ratio = err / allow
+    i = int(np.argmax(ratio))
+    worst = float(ratio.ravel()[i])
+    assert worst <= 1.0, "%s: element %s is off by %.3e (reference %.3e, rms %.3e): %.2f times the allowance" % (
+        name, np.unravel_index(i, ref.shape), float(err.ravel()[i]), float(np.abs(ref).ravel()[i]), rms, worst)
+    return worst
+
+
 def run_gpu(inp, backward, want_x=True):
     import torch
     d = ssm.to_device(inp)
@@ -51,7 +81,8 @@ def run_gpu(inp, backward, want_x=True):
 
 
 def check_workload(w, backward=None, inp=None, tol_fwd=TOL_FWD, tol_grad=TOL_GRAD):
-    """Element-by-element comparison of every output of the HIP path with the oracle."""
+    """Every output of the HIP path against the oracle: per tensor in the 2-norm and in max-abs error
+    over max-abs reference; the per-state gradient vectors also element by element."""
     backward = w.backward if backward is None else backward
     inp = wl.gen_inputs(w) if inp is None else inp
     ref = orc.run_workload(inp, backward, nthreads=NTHREADS)
@@ -61,8 +92,7 @@ def check_workload(w, backward=None, inp=None, tol_fwd=TOL_FWD, tol_grad=TOL_GRA
         report[k] = assert_close(got[k], ref[k], tol_fwd, "%s %s" % (w.name, k))
     if backward:
         for k in GRAD_KEYS:
-            if k == "dx0" and inp["x0"] is None:
-                # without x0 the adjoint of the (zero) initial state is still defined
-                pass
             report[k] = assert_close(got[k], ref[k], tol_grad, "%s %s" % (w.name, k))
+        for k in ELEMENTWISE_KEYS:
+            report[k + "_elementwise"] = (assert_close_elementwise(got[k], ref[k], tol_grad, "%s %s" % (w.name, k)),)
     return report

@@ -20,7 +20,7 @@ def lib():
 
 
 def test_every_declared_symbol_is_exported(lib):
-    header = open(os.path.join(ROOT, "include", "ssm.h")).read()
+    header = "".join(open(os.path.join(ROOT, "include", h)).read() for h in ("ssm.h", "ssm_measure.h"))
     declared = set(re.findall(r"\b(ssm_[a-z0-9_]+)\s*\(", header))
     assert declared == set(ssm.EXPORTS)
     for name in declared:
@@ -168,12 +168,10 @@ def test_s5_block_argument_errors(lib):
     assert lib.ssm_block_bwd(*F, 2, 8, 4, 4, FAKE, FAKE, FAKE, FAKE, *Gd, FAKE, need_b - 1, None) == ssm.SSM_ERR_WORKSPACE
 
 
-def test_mfma_probe_argument_errors(lib):
-    assert lib.ssm_mfma_probe(256, 10, 0, None, None) == ssm.SSM_ERR_INVALID_ARG
-    assert lib.ssm_mfma_probe(0, 10, 0, FAKE, None) == ssm.SSM_ERR_INVALID_ARG
-    assert lib.ssm_mfma_probe(256, 0, 0, FAKE, None) == ssm.SSM_ERR_INVALID_ARG
-    assert lib.ssm_mfma_probe(65537, 10, 0, FAKE, None) == ssm.SSM_ERR_UNSUPPORTED
-    assert lib.ssm_mfma_probe(256, (1 << 24) + 1, 0, FAKE, None) == ssm.SSM_ERR_UNSUPPORTED
+def test_spin_limit_hook_returns_the_previous_bound(lib):
+    old = ssm.ssm_set_spin_limit(7)
+    assert ssm.ssm_set_spin_limit(old) == 7
+    assert ssm.ssm_set_spin_limit(old) == old
 
 
 def test_binding_refuses_cpu_tensors(lib):
