@@ -6,15 +6,20 @@ scan, output projection) plus the gradient pass (C^H dy, reverse scan, du, param
 -- over one synthetic world-model-shaped batch (Bt=16, L=256, H=P=512) that is already resident
 in HBM.  Prints ONE JSON line:
   metric/value : whole-job throughput in Mtokens/s (token = one (sequence, step) pair)
-  roofline     : the dominant kernel (the projection GEMM: fp32 in/out, three-way bf16 operand
-                 split, six bf16 MFMAs per k block; the launch with the largest share of the
-                 step) against the bf16 matrix peak, its duration measured with HIP events on
-                 the launch stream inside the library's *_profiled entry points; the
-                 fp32-equivalent rate is given next to it, and every launch of the kernel below
-  scan_roofline: the two scan kernels against the HBM peak (algorithmic bytes / event time),
-                 warm (buffers resident in the 256 MB last-level cache) and cold (rotating over
-                 more than 1 GiB of distinct buffers); at shapes where the projections scan
-                 their own output tiles these kernels are not in the path and are timed alone
+  parity       : the outputs of the timed steps against the float64 oracle on the same batch, with the
+                 tolerances of the parity tests; the run fails on a mismatch
+  roofline     : the dominant kernel (the launch of the projection GEMM with the largest share of the
+                 step: fp32 in/out, operands staged as two scaled fp16 planes, three fp16 MFMA products
+                 per multiply-add) against the fp16 matrix peak, its duration measured with HIP events on
+                 the launch stream inside the library's *_profiled entry points; the fp32-equivalent rate
+                 is given next to it, and every launch of the kernel below
+  scan_roofline: the two scan kernels against the HBM peak (algorithmic bytes / event time): at the
+                 benchmark shape warm (buffers resident in the 256 MB last-level cache) and cold (rotating
+                 over more than 1 GiB of distinct buffers), and cold at working sets well past that cache
+                 (the long-sequence configuration, and the benchmark shape with eight times the batch);
+                 at shapes where the projections scan their own output tiles these kernels are not in the
+                 path and are timed through the scan-level entry points
+  whole_step_traffic: HBM bytes of all launches of one step (rocprofv3 counters, from profiles/)
   cpu_baseline : the float64 CPU oracle timed on the host cores on a bounded sample
 """
 import argparse
@@ -29,21 +34,12 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 PEAK_FP32_MFMA_TFLOPS = 157.3  # MI355X dense fp32 matrix
-PEAK_BF16_MFMA_TFLOPS = 2500.0 # MI355X dense bf16 matrix
-BF16_PRODUCTS = 6              # bf16 MFMA products the GEMM issues per fp32 multiply-add
-# HBM bytes per launch of the two largest launches at config 2 from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
-# scaled by what the same counters read for a copy-like kernel of known size
-# (profiles/gemm_bf16x3_scan_cfg2_fwd_bwd.md), next to the algorithmic bytes:
-#   C^H dy with the reverse scan in its tiles + the dC slabs: 64.3 MiB read (dy 8 + C 2 per XCD + x 16 for the
-#     scan; dy 8 + x 16 for the slabs), 32.9 MiB written (chi 16 + eight dC slabs 16)
-#   Re(Bbar^H chi) as two K halves + the dBbar slabs: 60.9 MiB read (chi 16 + Bbar 2 per XCD; chi 16 + u 8),
-#     24.3 MiB written (two du slabs 16 + four dBbar slabs 8)
-TRAFFIC = {
-    "33,0": {"read_bytes": 67.6e6, "write_bytes": 34.5e6, "algorithmic_read_bytes": 52.4e6,
-             "algorithmic_write_bytes": 33.6e6, "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, see profiles/"},
-    "1,0": {"read_bytes": 64.2e6, "write_bytes": 25.5e6, "algorithmic_read_bytes": 44.0e6,
-            "algorithmic_write_bytes": 25.2e6, "source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, see profiles/"},
-}
+PEAK_F16_MFMA_TFLOPS = 2500.0  # MI355X dense fp16 / bf16 matrix
+# HBM bytes per launch at config 2 from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
+# counters read for a copy-like kernel of known size (profiles/gemm_scan_cfg2_fwd_bwd.md, which names the
+# commit it was taken at).  Counters cannot be read from inside this process: these are constants of that
+# profile, not measurements of this run.
+PROFILE_TRAFFIC = None         # filled in from profiles/ once the profile of this build exists
 
 
 def main():
@@ -55,7 +51,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-iters", type=int, default=30)
     ap.add_argument("--path-only", action="store_true",
-                    help="skip the sections beside the hot path (reduced-precision mode, block_ops, step_mode): "
+                    help="skip the sections beside the hot path (scan kernels alone, block_ops, step_mode, s5_block): "
                          "used for the rocprofv3 runs so that every kernel in the trace belongs to one role")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -104,7 +100,12 @@ def main():
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
     mtok = T / (ms_per_step * 1e-3) / 1e6
-    assert ssm.ssm_workspace_status(ws_f) == ssm.SSM_OK and ssm.ssm_workspace_status(ws_b) == ssm.SSM_OK
+    # a cross-workgroup wait that gave up would have been flagged in the workspace (and its outputs are NaN)
+    for ws, name in ((ws_f, "forward"), (ws_b, "gradient pass")):
+        st = ssm.ssm_workspace_status(ws)
+        if st != ssm.SSM_OK:
+            raise ssm.SsmError(st, "timed loop, %s" % name)
+    timed_out = {k: v.cpu().numpy() for k, v in list(out_f.items()) + list(out_b.items())}
 
     # ---- distribution of single steps: one event pair per step (adds a little per-step overhead)
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
@@ -119,28 +120,6 @@ def main():
                  "p90_us": round(float(per_step[int(0.9 * (len(per_step) - 1))]), 1),
                  "note": "HIP events around every single step (forward + gradient pass)"}
 
-    # ---- the same step with the three-way bf16 split in every product (SSM_GEMM_SPLIT=3), timed the same
-    # way, for comparison with the default (two scaled fp16 planes where the projections scan their tiles)
-    three_plane = None
-    if not args.path_only and os.environ.get("SSM_GEMM_F32", "") != "1" and os.environ.get("SSM_GEMM_SPLIT", "") != "3":
-        os.environ["SSM_GEMM_SPLIT"] = "3"
-        try:
-            for _ in range(args.warmup):
-                step()
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(args.steps):
-                step()
-            torch.cuda.synchronize()
-            ms3 = (time.perf_counter() - t0) / args.steps * 1e3
-        finally:
-            os.environ.pop("SSM_GEMM_SPLIT", None)
-        three_plane = {"ms_per_step": round(ms3, 4), "Mtokens_per_s": round(T / (ms3 * 1e-3) / 1e6, 3),
-                       "note": "SSM_GEMM_SPLIT=3: three bf16 planes per operand and six products in every projection "
-                               "(the default uses them only where an operand's largest magnitude is not known)"}
-        step()                                              # leave the default-mode results in the output buffers
-        torch.cuda.synchronize()
-
     # ---- per-kernel durations from HIP events recorded on the launch stream (library side)
     fs = np.zeros(ssm.SSM_FWD_STAGES)
     bs = np.zeros(ssm.SSM_BWD_STAGES)
@@ -154,75 +133,55 @@ def main():
     stages.update({"bwd_" + n: round(float(v) * 1e3, 2) for n, v in zip(ssm.BWD_STAGE_NAMES, bs)})
 
     gemm_flops = 2.0 * T * (2 * P) * H                    # fp32 flops of every one of the six projections
-    f32_path = os.environ.get("SSM_GEMM_F32", "") == "1"
-    fused_env = os.environ.get("SSM_FUSED_SCAN", "")
-    shape_scans = (((L % 128 == 0 and L // 128 <= 32) or (L in (16, 32, 64) and T % 128 == 0))
-                   and (T // 128) * ((2 * P + 127) // 128) >= 64 and not f32_path)
-    fwd_fused = shape_scans and fused_env != "0"
-    rev_fused = shape_scans and fused_env not in ("0", "1")
-    # two scaled fp16 planes where the pass's projection scans its own tiles (every operand then comes
-    # with its largest magnitude), three bf16 planes otherwise
-    split3 = os.environ.get("SSM_GEMM_SPLIT", "") == "3"
-    npl_f = 2 if (fwd_fused and not split3) else 3
-    npl_b = 2 if (rev_fused and not split3) else 3
-    kern = lambda tile, lay0, lay1, npl: "gemm_bf16x3_ws_kernel<%s,2,2,8,2,%d,%d,%d>" % (tile, npl, lay0, lay1)
-    big = (T // 128) * ((2 * P + 127) // 128) >= 200
+    # where the projections scan their own tiles every operand comes with its largest magnitude and is staged
+    # as two scaled fp16 planes (three products per multiply-add); elsewhere as three bf16 planes (six)
+    scans = (((L % 128 == 0 and L // 128 <= 32) or (L in (16, 32, 64) and T % 128 == 0))
+             and (T // 128) * ((2 * P + 127) // 128) >= 64)
+    products = 3 if scans else 6
     t128 = ((T + 127) // 128) * ((H + 127) // 128)
-    out_split = (not f32_path and t128 < 200 and 2 * t128 >= 200 and P >= 256 and (2 * P) % 64 == 0
-                 and os.environ.get("SSM_SPLIT_OUT", "") != "0")
-    out_tile = "128,128,32" if ((T + 127) // 128) * ((H + 127) // 128) >= 200 else \
-               ("64,128,32" if ((T + 63) // 64) * ((H + 127) // 128) >= 200 else "64,64,64")
-    in_tile = "128,128,32" if (big or fwd_fused) else ("64,128,32" if ((T + 63) // 64) * ((2 * P + 127) // 128) >= 200 else "64,64,64")
-    # every launch of the projection kernel in one step: role, instantiation, fp32 flops, duration
-    launches = [
-        {"role": "input projection" + (" + forward scan in the tile" if fwd_fused else ""),
-         "kernel": kern(in_tile, 31 if fwd_fused else 3, -1, npl_f), "npl": npl_f, "gemms": 1, "ms": fs[1]},
-        ({"role": "output projection as two K halves into two slabs (a streaming kernel adds them and D u)",
-          "kernel": kern("128,128,32", 3, -1, npl_f), "npl": npl_f, "gemms": 1, "ms": fs[3]} if out_split else
-         {"role": "output projection + D u", "kernel": kern(out_tile, 7, -1, npl_f), "npl": npl_f, "gemms": 1, "ms": fs[3]}),
-        {"role": "C^H dy" + (" + reverse scan in the tile" if rev_fused else "") + " and the dC slabs, one launch",
-         "kernel": kern("128,128,32", 33 if rev_fused else 1, 0, npl_b), "npl": npl_b, "gemms": 2, "ms": bs[1]},
-        ({"role": "Re(Bbar^H chi) as two K halves and the dBbar slabs, one launch (a streaming kernel adds the halves and D dy)",
-          "kernel": kern("128,128,32", 1, 0, npl_b), "npl": npl_b, "gemms": 2, "ms": bs[3]} if out_split else
-         {"role": "Re(Bbar^H chi) + D dy and the dBbar slabs, one launch",
-          "kernel": kern("128,128,32", 5, 0, npl_b), "npl": npl_b, "gemms": 2, "ms": bs[3]}),
-    ]
+    out_split = t128 < 200 and 2 * t128 >= 200 and P >= 256 and (2 * P) % 64 == 0
+    # every launch of the projection kernel in one step: role, fp32 flops, duration
+    if scans:
+        launches = [
+            {"role": "input projection + forward scan in the tile (S2 + S3)", "gemms": 1, "ms": fs[1]},
+            {"role": "output projection" + (" as two K halves (a streaming kernel adds them and D u)" if out_split else " + D u")
+                     + " (S4)", "gemms": 1, "ms": fs[3]},
+            {"role": "C^H dy + reverse scan in the tile (S5 + S6)", "gemms": 1, "ms": bs[1]},
+            {"role": "Re(Bbar^H chi)" + (" as two K halves" if out_split else " + D dy")
+                     + ", the dBbar slabs and the dC slabs, one launch (S7 + S5)", "gemms": 3, "ms": bs[3]},
+        ]
+    else:
+        launches = [
+            {"role": "input projection (S2)", "gemms": 1, "ms": fs[1]},
+            {"role": "output projection + D u (S4)", "gemms": 1, "ms": fs[3]},
+            {"role": "C^H dy and the dC slabs, one launch (S5)", "gemms": 2, "ms": bs[1]},
+            {"role": "Re(Bbar^H chi) + D dy and the dBbar slabs, one launch (S7)", "gemms": 2, "ms": bs[3]},
+        ]
     for l in launches:
         l["fp32_flops"] = l["gemms"] * gemm_flops
         l["fp32_equivalent_tflops"] = round(l["fp32_flops"] / (l["ms"] * 1e-3) / 1e12, 2)
+        l["executed_tflops"] = round(products * l["fp32_flops"] / (l["ms"] * 1e-3) / 1e12, 1)
+        l["frac_of_f16_matrix_peak"] = round(l["executed_tflops"] / PEAK_F16_MFMA_TFLOPS, 4)
         l["us"] = round(float(l.pop("ms")) * 1e3, 2)
-    # Dominant kernel = the launch of gemm_bf16x3_ws_kernel with the largest share of the step.  Its
-    # algorithmic work: the partial products per multiply-add that its operand split needs (three
-    # fp16 ones with two scaled planes, six bf16 ones with three planes).
+    # Dominant kernel = the launch of gemm_ws_kernel with the largest share of the step.  Its algorithmic
+    # work: the partial products per multiply-add that its operand split needs.
     dom = max(launches, key=lambda l: l["us"])
     dom_fp32_tflops = dom["fp32_flops"] / (dom["us"] * 1e-6) / 1e12
-    if f32_path:
-        roofline = {"kernel": "gemm_f32_kernel (%s)" % dom["role"],
-                    "bound": "mfma", "achieved": round(dom_fp32_tflops, 2), "peak": PEAK_FP32_MFMA_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(dom_fp32_tflops / PEAK_FP32_MFMA_TFLOPS, 4), "traffic": None}
-    else:
-        npl = dom["npl"]
-        products = 3 if npl == 2 else BF16_PRODUCTS
-        ach = products * dom_fp32_tflops
-        lay = dom["kernel"].rstrip(">").split(",")[-2] + "," + dom["kernel"].rstrip(">").split(",")[-1]
-        known = TRAFFIC.get(lay) if (npl == 2 and args.config == 2 and fused_env == "" and out_split and
-                                     dom["kernel"].startswith("gemm_bf16x3_ws_kernel<128,128,32")) else None
-        roofline = {"kernel": "%s (%s)" % (dom["kernel"], dom["role"]),
-                    "bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(ach / PEAK_BF16_MFMA_TFLOPS, 4),
-                    "traffic": (known["read_bytes"] + known["write_bytes"]) if known else None,
-                    "traffic_detail": known,
-                    "note": "achieved counts the %d %s MFMA products per fp32 multiply-add that the kernel executes by "
-                            "design (peak: the dense fp16 / bf16 matrix rate, the same for both); fp32-equivalent rate "
-                            "and its ratio to the fp32 matrix peak below" % (products, "fp16" if npl == 2 else "bf16"),
-                    "fp32_equivalent_tflops": round(dom_fp32_tflops, 2),
-                    "fp32_equivalent_over_fp32_matrix_peak": round(dom_fp32_tflops / PEAK_FP32_MFMA_TFLOPS, 4)}
-    roofline.update({"flops_per_launch_fp32": dom["fp32_flops"], "avg_launch_us": dom["us"],
-                     "all_launches": launches})
-    if not f32_path:
-        roofline["measured_matrix_only"] = mfma_only_rate(ssm, torch, dom["us"], dom["npl"] == 2)
-        roofline["frac_of_measured_matrix_only"] = round(
-            roofline["achieved"] / roofline["measured_matrix_only"]["launch_like_the_dominant_one"]["TFLOPs"], 4)
+    ach = products * dom_fp32_tflops
+    roofline = {"kernel": "gemm_ws_kernel (%s)" % dom["role"],
+                "bound": "mfma", "achieved": round(ach, 1), "peak": PEAK_F16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(ach / PEAK_F16_MFMA_TFLOPS, 4),
+                "traffic": None,
+                "note": "achieved counts the %d %s MFMA products per fp32 multiply-add that the kernel executes by "
+                        "design (peak: the dense fp16 / bf16 matrix rate, the same for both); fp32-equivalent rate "
+                        "and its ratio to the fp32 matrix peak below" % (products, "fp16" if scans else "bf16"),
+                "fp32_equivalent_tflops": round(dom_fp32_tflops, 2),
+                "fp32_equivalent_over_fp32_matrix_peak": round(dom_fp32_tflops / PEAK_FP32_MFMA_TFLOPS, 4),
+                "flops_per_launch_fp32": dom["fp32_flops"], "avg_launch_us": dom["us"], "all_launches": launches}
+    whole = None
+    if PROFILE_TRAFFIC and args.config == 2:
+        whole = dict(PROFILE_TRAFFIC)
+        roofline["traffic"] = PROFILE_TRAFFIC.get("dominant_launch_bytes")
 
     # ---- scans against the HBM roofline: algorithmic bytes = 16 B (forward: read v, write x) and
     # 24 B (reverse: read gx, read x, write chi) per (token, state).  Where the projections scan their
@@ -230,27 +189,27 @@ def main():
     fwd_bytes, rev_bytes = 16.0 * T * P, 24.0 * T * P
     scan = {"bound": "hbm", "peak": PEAK_HBM_GBS, "unit": "GB/s",
             "fwd_bytes_per_launch": fwd_bytes, "rev_bytes_per_launch": rev_bytes,
-            "in_path": {"fwd": "inside the input projection" if fwd_fused else "scan_kernel<false>",
-                        "rev": "inside the C^H dy launch" if rev_fused else "scan_kernel<true>"},
-            "in_path_fwd_us": None if fwd_fused else round(float(fs[2]) * 1e3, 2),
-            "in_path_rev_us": None if rev_fused else round(float(bs[2]) * 1e3, 2),
-            "in_path_fwd_GBs": None if fwd_fused else round(fwd_bytes / (fs[2] * 1e-3) / 1e9, 1),
-            "in_path_rev_GBs": None if rev_fused else round(rev_bytes / (bs[2] * 1e-3) / 1e9, 1)}
-    scan.update(scan_cold_warm(ssm, torch, d, Bt, L, P, fwd_bytes, rev_bytes))
-    scan["frac"] = round(scan["cold_fwd_GBs"] / PEAK_HBM_GBS, 4)
-    scan["frac_of_copy_kernel_cold"] = round(scan["cold_fwd_GBs"] / scan["copy_cold_GBs"], 4)
-    if (fwd_fused or rev_fused) and not args.path_only:
-        scan["separate_kernels"] = separate_scan_kernels(step, args.warmup, args.steps, T, torch, time)
+            "in_path": {"fwd": "inside the input projection" if scans else "scan_kernel<false>",
+                        "rev": "inside the C^H dy launch" if scans else "scan_kernel<true>"},
+            "in_path_fwd_us": None if scans else round(float(fs[2]) * 1e3, 2),
+            "in_path_rev_us": None if scans else round(float(bs[2]) * 1e3, 2),
+            "in_path_fwd_GBs": None if scans else round(fwd_bytes / (fs[2] * 1e-3) / 1e9, 1),
+            "in_path_rev_GBs": None if scans else round(rev_bytes / (bs[2] * 1e-3) / 1e9, 1)}
+    if not args.path_only:
+        scan.update(scan_cold_warm(ssm, torch, d, Bt, L, P, fwd_bytes, rev_bytes))
+        scan["frac"] = round(scan["cold_fwd_GBs"] / PEAK_HBM_GBS, 4)
+        scan["frac_of_copy_kernel_cold"] = round(scan["cold_fwd_GBs"] / scan["copy_cold_GBs"], 4)
+        scan["large_working_sets"] = scan_large(ssm, torch, wl)
 
     result = {
         "metric": "SSM scan fwd+bwd Mtokens/s (B=16, L=256, H=P=512); achieved HBM GB/s in scan_roofline and composite_hbm", "value": round(mtok, 3), "unit": "Mtokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32",
-        "arith": "fp32 I/O and accumulation; projections on " + ("fp32 MFMA" if f32_path else
-                 ("fp16 MFMA on two scaled fp16 planes per operand (three products, fp32-class accuracy)"
-                  if (npl_f == 2 and npl_b == 2) else
-                  "bf16 MFMA with an exact 3-way bf16 split of both operands (fp32-class accuracy)")),
+        "arith": "fp32 I/O and accumulation; projections on " +
+                 ("fp16 MFMA on two scaled fp16 planes per operand (three products, fp32-class accuracy; an element more "
+                  "than 2^17 below the largest magnitude under its scale is fixed-point)" if scans else
+                  "bf16 MFMA with an exact 3-way bf16 split of both operands (fp32-class accuracy)"),
         "data": "synthetic",
         "config": {"workload": "%s: Bt=%d L=%d H=%d P=%d fwd+bwd, fp32 I/O, complex64 state, seed %d"
                                % (w.name, Bt, L, H, P, w.seed), "tokens_per_step": T},
@@ -260,66 +219,70 @@ def main():
                           "frac_of_hbm_peak": round(compulsory_bytes(Bt, L, H, P) / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                           "note": "whole forward + gradient pass against the HBM peak, for reference only: the path "
                                   "is matrix-core bound (about 290 flop per compulsory byte at this shape)"},
-        "three_plane_mode": three_plane,
+        "whole_step_traffic": whole,
     }
     if not args.path_only:
         result["block_ops"] = block_ops(ssm, torch, wl, T, H)
         result["step_mode"] = step_mode(ssm, torch, d, H, P)
         result["s5_block"] = s5_block(ssm, torch, wl, d, Bt, L, H, P)
+    # the oracle on the same batch: checks what the timed steps produced, and is the CPU baseline
+    oracle = oracle_check_and_time(w, inp, timed_out, want_timing=not args.no_cpu_baseline)
+    result["parity"] = oracle["parity"]
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(w, inp)
+        result["cpu_baseline"] = oracle["cpu_baseline"]
     print(json.dumps(result))
+    if not oracle["parity"]["ok"]:
+        print("bench.py: the timed outputs do not match the oracle: %s" % oracle["parity"]["failed"], file=sys.stderr)
+        sys.exit(1)
 
 
-def mfma_only_rate(ssm, torch, dom_us, fp16):
-    """The projection kernel's matrix-instruction stream alone (ssm_mfma_probe: one wavefront per SIMD
-    on all 256 CUs, register operands with changing bits): what the matrix cores sustain on this
-    device, at the clock they hold under that load, for a launch as long as the dominant one and for
-    a long one.  Context for roofline.frac, whose peak is the published 2.4 GHz figure."""
-    flops_per_iter = 256 * 4 * 24 * 2.0 * 32 * 32 * 16
-    out = torch.empty(256 * 256, dtype=torch.float32, device="cuda")
-    res = {}
-    # 24 matrix instructions of 8 passes take 768 cycles: about 0.4 us per iteration
-    for label, iters in (("launch_like_the_dominant_one", max(8, int(dom_us / 0.42))), ("long_launch", 4000)):
-        for _ in range(3):
-            ssm.ssm_mfma_probe(256, iters, fp16=fp16, out=out)
-        torch.cuda.synchronize()
-        reps = 10
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            ssm.ssm_mfma_probe(256, iters, fp16=fp16, out=out)
-        e1.record()
-        torch.cuda.synchronize()
-        us = e0.elapsed_time(e1) * 1e3 / reps
-        res[label] = {"iters": iters, "us": round(us, 2), "TFLOPs": round(flops_per_iter * iters / (us * 1e-6) / 1e12, 1)}
-    res["note"] = ("%s 32x32x16 matrix instructions only, 256 workgroups x 4 wavefronts; includes the launch; "
-                   "the published peak assumes 2.4 GHz" % ("fp16" if fp16 else "bf16"))
-    return res
-
-
-def separate_scan_kernels(step, warmup, steps, T, torch, time):
-    """The same step with SSM_FUSED_SCAN=0 (projections and scans as separate kernels), for comparison."""
-    old = os.environ.get("SSM_FUSED_SCAN")
-    os.environ["SSM_FUSED_SCAN"] = "0"
-    try:
-        for _ in range(warmup):
-            step()
-        torch.cuda.synchronize()
+def oracle_check_and_time(w, inp, got, want_timing, budget_s=12.0):
+    """Runs the float64 oracle (plain C, OpenMP over sequences) on the whole batch of the timed steps:
+    every output of the last timed step is compared with it (normwise and max-abs, 1e-4 forward / 1e-3
+    gradients, as in the parity tests), and the same calls, repeated for about `budget_s` seconds, are
+    the CPU baseline."""
+    import numpy as np
+    from oracle import ssm_oracle as orc
+    cores = max(1, min(len(os.sched_getaffinity(0)), orc.max_threads()))
+    threads = min(cores, w.Bt)
+    t0 = time.perf_counter()
+    ref = orc.run_workload(inp, True, nthreads=threads)
+    first = time.perf_counter() - t0
+    worst, failed = {}, []
+    for k, tol in (("y", 1e-4), ("x", 1e-4), ("x_last", 1e-4), ("du", 1e-3), ("dLambda", 1e-3), ("dB", 1e-3),
+                   ("dC", 1e-3), ("dD", 1e-3), ("dlog_delta", 1e-3), ("dx0", 1e-3)):
+        g, r = got[k], ref[k]
+        diff = g.astype(r.dtype) - r
+        nr, mr = float(np.linalg.norm(r.ravel())), float(np.max(np.abs(r)))
+        # (an all-zero reference, e.g. dx0 when every sequence starts with a reset, must be met exactly)
+        ne = float(np.linalg.norm(diff.ravel())) / (nr if nr > 0 else 1.0)
+        me = float(np.max(np.abs(diff))) / (mr if mr > 0 else 1.0)
+        worst[k] = round(max(ne, me) / tol, 4)
+        if not (np.all(np.isfinite(g)) and ne <= tol and me <= tol):
+            failed.append(k)
+    res = {"parity": {"ok": not failed, "failed": failed, "worst_error_over_tolerance": worst,
+                      "what": "outputs of the last timed step against the float64 oracle on the same batch, per tensor "
+                              "normwise and max-abs (1e-4 forward, 1e-3 gradients)"}}
+    if want_timing:
+        reps, spent = 1, first
+        while spent < budget_s and reps < 64:
+            t0 = time.perf_counter()
+            orc.run_workload(inp, True, nthreads=threads)
+            spent += time.perf_counter() - t0
+            reps += 1
+        # single-threaded leg on a smaller sample
+        n1 = min(w.Bt, 2)
+        sub1 = {k: (v[:n1] if (v is not None and k in ("u", "is_first", "dy", "x0")) else v) for k, v in inp.items()}
         t0 = time.perf_counter()
-        for _ in range(steps):
-            step()
-        torch.cuda.synchronize()
-        ms = (time.perf_counter() - t0) / steps * 1e3
-    finally:
-        if old is None:
-            os.environ.pop("SSM_FUSED_SCAN", None)
-        else:
-            os.environ["SSM_FUSED_SCAN"] = old
-    step()                                                  # leave the default path's results in the buffers
-    torch.cuda.synchronize()
-    return {"ms_per_step": round(ms, 4), "Mtokens_per_s": round(T / (ms * 1e-3) / 1e6, 3),
-            "note": "SSM_FUSED_SCAN=0: scan_kernel<false> / scan_kernel<true> between the projections"}
+        orc.run_workload(sub1, True, nthreads=1)
+        dt1 = time.perf_counter() - t0
+        res["cpu_baseline"] = {"value": round(reps * w.Bt * w.L / spent / 1e6, 5), "unit": "Mtokens/s", "cores": threads,
+                               "kind": "oracle", "seconds": round(spent, 2),
+                               "single_thread_value": round(n1 * w.L / dt1 / 1e6, 5), "single_thread_seconds": round(dt1, 2),
+                               "single_thread_sample": "first %d sequences" % n1,
+                               "sample": "float64 oracle forward + gradient pass on all %d sequences of the same batch, "
+                                         "%d times over" % (w.Bt, reps)}
+    return res
 
 
 def compulsory_bytes(Bt, L, H, P):
@@ -473,28 +436,46 @@ def scan_cold_warm(ssm, torch, d, Bt, L, P, fwd_bytes, rev_bytes, iters=40):
     return out
 
 
-def cpu_baseline(w, inp):
-    """The float64 oracle (plain C, OpenMP over sequences) on the first sequences of the same batch."""
-    from oracle import ssm_oracle as orc
-    cores = max(1, min(len(os.sched_getaffinity(0)), orc.max_threads()))
-    nseq = min(w.Bt, max(cores, 4))
-    sub = {k: (v[:nseq] if (v is not None and k in ("u", "is_first", "dy", "x0")) else v) for k, v in inp.items()}
-    threads = min(cores, nseq)
-    t0 = time.perf_counter()
-    orc.run_workload(sub, True, nthreads=threads)
-    dt = time.perf_counter() - t0
-    # single-threaded leg on a smaller sample
-    n1 = min(nseq, 2)
-    sub1 = {k: (v[:n1] if (v is not None and k in ("u", "is_first", "dy", "x0")) else v) for k, v in inp.items()}
-    t0 = time.perf_counter()
-    orc.run_workload(sub1, True, nthreads=1)
-    dt1 = time.perf_counter() - t0
-    return {"value": round(nseq * w.L / dt / 1e6, 5), "unit": "Mtokens/s", "cores": threads, "kind": "oracle",
-            "seconds": round(dt, 2),
-            "single_thread_value": round(n1 * w.L / dt1 / 1e6, 5), "single_thread_seconds": round(dt1, 2),
-            "single_thread_sample": "first %d sequences" % n1,
-            "sample": "float64 oracle forward + gradient pass on the first %d of %d sequences of the same batch"
-                      % (nseq, w.Bt)}
+def scan_large(ssm, torch, wl, iters=12):
+    """The two scan kernels cold (rotating over more than 1 GiB of distinct buffers) at working sets well
+    past the 256 MB last-level cache, where the launch and the first memory round trip no longer
+    dominate: the long-sequence configuration (4 x 4096 steps x 256 states) and the benchmark shape with
+    eight times the batch (128 x 256 steps x 512 states).  Algorithmic bytes over event time."""
+    import numpy as np
+    res = {}
+    for name, Bt, L, P, p_reset in (("cfg3_shape_4x4096x256", 4, 4096, 256, 0.001), ("cfg2_shape_x8_batch_128x256x512", 128, 256, 512, 0.01)):
+        rng = np.random.Generator(np.random.PCG64(11))
+        lam = (rng.uniform(0.5, 0.97, P) * np.exp(1j * rng.uniform(0, np.pi, P))).astype(np.complex64)
+        fl = (rng.random((Bt, L)) < p_reset).astype(np.uint8)
+        A_bar, flags = torch.from_numpy(lam).cuda(), torch.from_numpy(fl).cuda()
+        set_bytes = Bt * L * P * 8
+        nsets = max(3, int((5 << 28) // set_bytes) + 1)           # 1.25 GiB of v / gx buffers
+        vs = [torch.randn((Bt, L, P), dtype=torch.complex64, device="cuda") * 0.05 for _ in range(nsets)]
+        nx = max(2, min(nsets, int((1 << 29) // set_bytes) + 1))  # 0.5 GiB of saved-state buffers
+        xs = [torch.randn((Bt, L, P), dtype=torch.complex64, device="cuda") * 0.05 for _ in range(nx)]
+        ws_f = ssm.alloc_workspace(Bt, L, 1, P, False)
+        ws_r = ssm.alloc_workspace(Bt, L, 1, P, True)
+        fwd_bytes, rev_bytes = 16.0 * Bt * L * P, 24.0 * Bt * L * P
+        f = lambda i: ssm.ssm_scan_states(A_bar, vs[i % nsets], flags, None, want_x_last=False, workspace=ws_f)
+        r = lambda i: ssm.ssm_scan_states_reverse(A_bar, vs[i % nsets], xs[i % nx], flags, None, want_dx0=False, workspace=ws_r)
+        cp = lambda i: vs[(i + 1) % nsets].copy_(vs[i % nsets])
+        n = max(iters, nsets)
+        e = {"working_set_MB": round(2 * set_bytes / 1e6, 1), "buffers_rotated": nsets}
+        for key, fn, nbytes in (("copy", cp, fwd_bytes), ("fwd", f, fwd_bytes), ("rev", r, rev_bytes)):
+            ms = graph_time_ms(torch, fn, n)
+            e[key + "_us"] = round(ms * 1e3, 2)
+            e[key + "_GBs"] = round(nbytes / (ms * 1e-3) / 1e9, 1)
+            e[key + "_frac_of_hbm_peak"] = round(nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)
+        assert ssm.ssm_workspace_status(ws_f) == ssm.SSM_OK and ssm.ssm_workspace_status(ws_r) == ssm.SSM_OK
+        res[name] = e
+        del vs, xs
+        torch.cuda.empty_cache()
+    res["note"] = ("cold: every launch works on buffers that no earlier launch of the replayed graph has touched within "
+                   "the last 1 GiB of traffic; copy = torch's copy kernel on the same bytes as the forward scan (read 8 B + "
+                   "write 8 B per element); the reverse figure includes its small partial-sum reduction kernel")
+    return res
+
+
 
 
 if __name__ == "__main__":

@@ -23,9 +23,9 @@ struct GemmDev {
     const uint8_t *rowflag;
     int M, N, K, kper;      // kper: K range per split (multiple of the K tile)
     int ntm, ntn, per_xcd;
-    // placement of the (tile, split) work items on the 8 XCDs (bf16x3 kernel): slots per XCD,
-    // mapping mode and its parameter, first slot of this problem in a shared launch
-    int splits, nx, mode, mpar, slot0, second_first;
+    // placement of the (tile, split) work items on the 8 XCDs: slots per XCD, mapping mode and its
+    // parameter, first slot of this problem in a launch that carries several
+    int splits, nx, mode, mpar, slot0;
     // epilogue 7 (scan over the tile's rows): tiles per sequence, column tiles per unit, column
     // groups per sequence, number of units (a unit = the chains of one sequence and column group)
     ScanEpilogue scan;

@@ -509,6 +509,7 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
     float2 xs = cfma(Aex, Xin, Sex);
     float2 *dst = reinterpret_cast<float2 *>(g.C) + (long)row0 * a.P + p;
     float amax = 0.f;                                        // largest magnitude this thread stores
+    float xmax = 0.f;                                        // reverse: largest magnitude of the saved states it reads
     unsigned rm[RC];                                         // and per step (row of the tile), for rowmax_out
     if (!REV) {
 #pragma unroll
@@ -526,6 +527,13 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
         // also dAbar += [not is_first_t] conj(x_{t-1}) chi_t; x_{-1} = x0 (zero when absent)
         const float2 *xprev = a.xsaved + ((long)row0 - 1) * a.P + p;             // x_{t0-1}; valid for e >= 1 or t0 > 0
         float2 acc = make_float2(0.f, 0.f);
+        // the saved states pass through here once (x_{t-1} for every step; the last state of a sequence is
+        // fetched on top by the thread that owns its last steps), so their largest magnitude is recorded
+        // on the way: dy^T x, in the next launch, stages x under that scale
+        if (a.xmax_out && active && t0 + RC == a.L) {
+            const float2 xl = xprev[(long)RC * a.P];
+            xmax = fmaxf(fabsf(xl.x), fabsf(xl.y));
+        }
 #pragma unroll
         for (int blk = RC / 8 - 1; blk >= 0; --blk) {
             float2 xp[8];                                  // eight loads in flight
@@ -534,8 +542,12 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
                 const int e = blk * 8 + j;
                 xp[j] = make_float2(0.f, 0.f);
                 if (active) {
-                    if (t0 + e > 0) xp[j] = xprev[(long)e * a.P];
-                    else if (a.x0) xp[j] = a.x0[(long)b * a.P + p];
+                    if (t0 + e > 0) {
+                        xp[j] = xprev[(long)e * a.P];
+                        xmax = fmaxf(xmax, fmaxf(fabsf(xp[j].x), fabsf(xp[j].y)));
+                    } else if (a.x0) {
+                        xp[j] = a.x0[(long)b * a.P + p];
+                    }
                 }
             }
 #pragma unroll
@@ -574,14 +586,18 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
     if (a.amax_out) {
         // one atomic per workgroup, spread over ABSMAX_SLOTS addresses (the bit patterns of non-negative
         // floats order like unsigned integers); cAny is free since barrier 5
-        unsigned v = active ? __float_as_uint(amax) : 0u;
+        unsigned v = active ? __float_as_uint(amax) : 0u, vx = active ? __float_as_uint(xmax) : 0u;
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) v = max(v, (unsigned)__shfl_xor((int)v, o));
-        if (c == 0) lds.cAny[q] = v;
+        for (int o = 32; o > 0; o >>= 1) {
+            v = max(v, (unsigned)__shfl_xor((int)v, o));
+            if (REV) vx = max(vx, (unsigned)__shfl_xor((int)vx, o));
+        }
+        if (c == 0) { lds.cAny[q] = v; lds.cAny[NCH + q] = vx; }
         __syncthreads();                                                                   // barrier 7 (with amax_out only)
         if (tid == 0) {
-            for (int j = 1; j < NCH; ++j) v = max(v, lds.cAny[j]);
+            for (int j = 1; j < NCH; ++j) { v = max(v, lds.cAny[j]); vx = max(vx, lds.cAny[NCH + j]); }
             atomicMax(a.amax_out + (unsigned)tile % ABSMAX_SLOTS, v);
+            if (REV && a.xmax_out) atomicMax(a.xmax_out + (unsigned)tile % ABSMAX_SLOTS, vx);
         }
     }
 }
@@ -1037,23 +1053,25 @@ __device__ __forceinline__ void gemm_ws_problem(const GemmDev &g, __bf16 *smem, 
         gemm_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, NPL, AKC, BKC, EPI, false>(g, smem, m0, n0, z, kbeg, kend, tile);
 }
 
-// One launch carries one problem (LAY1 < 0) or two independent ones (used for the gradient
-// pass, where pairs of products have the same inputs ready at the same time and one of them
-// alone would leave compute units idle).  The slots of the first problem come first in every XCD
-// unless the launch asks for the second one first (the longer work items should start first).
+// One launch carries one problem (LAY1 < 0), two, or three independent ones (the third has the layout
+// of the second; it is absent when its slot count is zero).  Used for the gradient pass, where several
+// products have their inputs ready at the same time and one of them alone would leave compute units
+// idle.  Every problem owns a contiguous range of the slots of every XCD, [slot0, slot0 + nx); the host
+// decides the order (work items that should start first get the lowest slots).
 template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL, int LAY0, int LAY1>
-__global__ void __launch_bounds__(64 * (WGM * WGN + NP)) gemm_ws_kernel(GemmDev g0, GemmDev g1)
+__global__ void __launch_bounds__(64 * (WGM * WGN + NP)) gemm_ws_kernel(GemmDev g0, GemmDev g1, GemmDev g2)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);
     const int x = blockIdx.x % 8, q = blockIdx.x / 8;
-    // slots of an XCD: the first problem's, then the second's -- or the other way round when asked
-    const bool first = LAY1 < 0 || (g1.second_first ? q >= g1.nx : q < g1.slot0);
-    if (first)
-        gemm_ws_problem<BM, BN, BK, WGM, WGN, NP, NS, NPL, LAY0>(g0, smem, x, g1.second_first && LAY1 >= 0 ? q - g1.nx : q);
-    else
-        gemm_ws_problem<BM, BN, BK, WGM, WGN, NP, NS, NPL, (LAY1 < 0 ? LAY0 : LAY1)>(g1, smem, x,
-                                                                                             g1.second_first ? q : q - g1.slot0);
+    if (LAY1 < 0 || (q >= g0.slot0 && q < g0.slot0 + g0.nx)) {
+        gemm_ws_problem<BM, BN, BK, WGM, WGN, NP, NS, NPL, LAY0>(g0, smem, x, q - g0.slot0);
+    } else if (q >= g1.slot0 && q < g1.slot0 + g1.nx) {
+        gemm_ws_problem<BM, BN, BK, WGM, WGN, NP, NS, NPL, (LAY1 < 0 ? LAY0 : LAY1)>(g1, smem, x, q - g1.slot0);
+    } else {
+        // (a branch of its own: choosing between the two argument structs at run time would put them on the stack)
+        gemm_ws_problem<BM, BN, BK, WGM, WGN, NP, NS, NPL, (LAY1 < 0 ? LAY0 : LAY1)>(g2, smem, x, q - g2.slot0);
+    }
 }
 
 template <int BM, int BN, int BK>
@@ -1073,7 +1091,7 @@ inline GemmDev make_gemm_dev(const GemmArgs &a)
     const long ntiles = (long)g.ntm * g.ntn;
     g.per_xcd = (int)((ntiles + 7) / 8);
     g.splits = splits;
-    g.slot0 = 0; g.second_first = 0;
+    g.slot0 = 0;
     if (splits == 1) { g.mode = 0; g.mpar = 0; g.nx = g.per_xcd; }
     else if (splits % 8 == 0) { g.mode = 1; g.mpar = splits / 8; g.nx = (int)(ntiles * g.mpar); }
     else if (8 % splits == 0) { g.mode = 2; g.mpar = 8 / splits; g.nx = (int)((ntiles + g.mpar - 1) / g.mpar); }
@@ -1096,16 +1114,33 @@ inline GemmDev make_gemm_dev(const GemmArgs &a)
     return g;
 }
 
-// b == nullptr: one problem (LAY1 is ignored and must be -1).
+// b == nullptr: one problem (LAY1 must be -1).  c (optional, only with b): a third problem with the
+// layout of b.  order[i] = which problem (0 = a, 1 = b, 2 = c) takes the i-th range of slots in every
+// XCD; nullptr = a, b, c.
 template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL, int LAY0, int LAY1 = -1>
 hipError_t launch_gemm_ws_variant(const GemmArgs &a, hipStream_t s, const GemmArgs *b = nullptr,
-                                        bool second_first = false)
+                                  const GemmArgs *c = nullptr, const int *order = nullptr)
 {
-    GemmDev g0 = make_gemm_dev<BM, BN, BK>(a);
-    GemmDev g1 = b ? make_gemm_dev<BM, BN, BK>(*b) : g0;
-    if ((LAY1 >= 0) != (b != nullptr)) return hipErrorInvalidValue;
-    g1.slot0 = g0.nx;
-    g1.second_first = (b && second_first) ? 1 : 0;
+    if ((LAY1 >= 0) != (b != nullptr) || (c && !b)) return hipErrorInvalidValue;
+    GemmDev g[3];
+    g[0] = make_gemm_dev<BM, BN, BK>(a);
+    g[1] = b ? make_gemm_dev<BM, BN, BK>(*b) : g[0];
+    g[2] = c ? make_gemm_dev<BM, BN, BK>(*c) : g[0];
+    const int nprob = c ? 3 : (b ? 2 : 1);
+    if (!b) g[1].nx = 0;
+    if (!c) g[2].nx = 0;
+    static const int natural[3] = {0, 1, 2};
+    const int *ord = order ? order : natural;
+    long slots = 0;
+    int seen = 0;
+    for (int i = 0; i < nprob; ++i) {
+        const int k = ord[i];
+        if (k < 0 || k >= nprob || (seen & (1 << k))) return hipErrorInvalidValue;
+        seen |= 1 << k;
+        g[k].slot0 = (int)slots;
+        slots += g[k].nx;
+    }
+    for (int k = nprob; k < 3; ++k) g[k].slot0 = (int)slots;
     constexpr size_t stage0 = gemm_stage_halves(BM, BN, BK, NPL, LAY0), stage1 = LAY1 >= 0 ? gemm_stage_halves(BM, BN, BK, NPL, LAY1) : 0;
     constexpr size_t stage_bytes = ((size_t)NS * (stage0 > stage1 ? stage0 : stage1) + gemm_rowexp_halves(BM, NPL)) * sizeof(__bf16);
     constexpr bool scans = ((LAY0 >> 2) >= 7) || (LAY1 >= 0 && (LAY1 >> 2) >= 7);
@@ -1127,9 +1162,8 @@ hipError_t launch_gemm_ws_variant(const GemmArgs &a, hipStream_t s, const GemmAr
             if (dev >= 0 && dev < MAXDEV) raised[dev].store(true, std::memory_order_release);
         }
     }
-    const long slots = (long)g0.nx + (b ? g1.nx : 0);
     if (slots <= 0 || 8 * slots > 0x7fffffffL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(8 * slots)), dim3(64 * (WGM * WGN + NP)), smem, s, g0, g1);
+    hipLaunchKernelGGL(kern, dim3((unsigned)(8 * slots)), dim3(64 * (WGM * WGN + NP)), smem, s, g[0], g[1], g[2]);
     return hipGetLastError();
 }
 

@@ -79,7 +79,7 @@ struct Layout {
     int splitC, splitB, nslab;
     size_t hdr, lam, Bri, Cc, xbuf, chi, ticket, desc, dCpart, dBpart, dApart, dDpart, fdesc, fdesc_bytes, yhalves, total;
     // largest magnitudes of the operands of the products (shapes whose projections scan their own tiles):
-    // amax_atomic: ABSMAX_SLOTS words gathered with atomics, directly before fdesc so that one range is
+    // amax_atomic: 2 x ABSMAX_SLOTS words gathered with atomics, directly before fdesc so that one range is
     // cleared; amax_slots: [P] Bbar, [H] Cc, then 2 x PREP_PASS_BLOCKS and 2 x amax_cd words of the passes
     size_t amax_atomic, amax_slots; int amax_cd;
     // per-row maxima of the operands whose rows are tokens: rowmax (u forward: [T]; dy gradient pass: [ceil(H/64), T]) and
@@ -105,8 +105,19 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
     o.plan = plan_scan(Bt, L, P);
     if (o.plan.nblocks > 0x7fffffffLL) return SSM_ERR_UNSUPPORTED;
     const int64_t rows128 = ((int64_t)T + 127) / 128;
-    o.splitC = gemm_pick_splits(H, 2 * P, (int64_t)T, rows128 * ((2 * P + 127) / 128));   // shares C^H dy's launch
-    o.splitB = gemm_pick_splits(2 * P, H, (int64_t)T, rows128 * ((H + 127) / 128));       // shares Bbar^H chi's launch
+    if (gemm_scan_shape_ok(Bt, L, P)) {
+        // dy^T x and chi^T u share the launch of Re(Bbar^H chi): K splits that make their work items as
+        // long as that product's (its whole K = 2P, or one K half), at least 256 rows each
+        const int64_t k_du = gemm_out_split_shape((int64_t)T, H, P) ? P : 2 * P;
+        int64_t sp = ((int64_t)T + k_du / 2) / k_du;
+        const int64_t maxs = ((int64_t)T + 255) / 256;
+        sp = sp > maxs ? maxs : sp;
+        sp = sp > 64 ? 64 : (sp < 1 ? 1 : sp);
+        o.splitC = o.splitB = (int)sp;
+    } else {
+        o.splitC = gemm_pick_splits(H, 2 * P, (int64_t)T, rows128 * ((2 * P + 127) / 128));   // shares C^H dy's launch
+        o.splitB = gemm_pick_splits(2 * P, H, (int64_t)T, rows128 * ((H + 127) / 128));       // shares Bbar^H chi's launch
+    }
     o.nslab = coldot_slabs((int64_t)T);
     size_t off = 0;
     o.hdr = off; off += up(sizeof(WsHeader));
@@ -120,7 +131,7 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
     o.amax_atomic = o.amax_slots = o.rowmax = o.rowpart = 0; o.amax_cd = o.row_parts = 0;
     if (gemm_scan_shape_ok(Bt, L, P)) {              // tagged words of a projection that scans its own output
         static_assert(ABSMAX_SLOTS * 4 % ALIGN == 0, "the atomic slots and the tagged words are cleared as one range");
-        o.amax_atomic = off; off += ABSMAX_SLOTS * 4;
+        o.amax_atomic = off; off += 2 * ABSMAX_SLOTS * 4;            // chi, then the saved states (gradient pass)
         o.fdesc_bytes = gemm_scan_desc_bytes(Bt, L, P);
         o.fdesc = off; off += up(o.fdesc_bytes);
         o.amax_cd = o.nslab * (int)((H + 63) / 64);
@@ -223,7 +234,7 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     pa.P = (int)P; pa.H = (int)H; pa.lam_bar = lam; pa.Bbar_ri = Bri; pa.Cc = Cc; pa.Bbar_c64 = nullptr;
     pa.hdr = (fused || lo.plan.nTB == 1) ? hdr : nullptr;
     // the atomic slots and the tagged words behind them are cleared in the same launch
-    if (fused) { pa.zero16 = reinterpret_cast<uint4 *>(ws + lo.amax_atomic); pa.n16 = (ABSMAX_SLOTS * 4 + lo.fdesc_bytes) / 16; }
+    if (fused) { pa.zero16 = reinterpret_cast<uint4 *>(ws + lo.amax_atomic); pa.n16 = (2 * ABSMAX_SLOTS * 4 + lo.fdesc_bytes) / 16; }
     // two scaled fp16 planes per operand: every operand of the two products brings its largest magnitude
     const bool two_planes = fused;
     unsigned *am_bbar = reinterpret_cast<unsigned *>(ws + lo.amax_slots), *am_cc = am_bbar + P;
@@ -337,27 +348,26 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     pa.C = reinterpret_cast<const float2 *>(C); pa.log_delta = log_delta;
     pa.P = (int)P; pa.H = (int)H; pa.lam_bar = lam; pa.Bbar_ri = Bri; pa.Cc = Cc; pa.Bbar_c64 = nullptr;
     pa.hdr = (fused || lo.plan.nTB == 1) ? hdr : nullptr;
-    if (fused) { pa.zero16 = reinterpret_cast<uint4 *>(ws + lo.amax_atomic); pa.n16 = (ABSMAX_SLOTS * 4 + lo.fdesc_bytes) / 16; }
+    if (fused) { pa.zero16 = reinterpret_cast<uint4 *>(ws + lo.amax_atomic); pa.n16 = (2 * ABSMAX_SLOTS * 4 + lo.fdesc_bytes) / 16; }
     // dD slabs: sum_t dy[t,h] u[t,h] over row slabs, in the same launch
     pa.cd.a = dy; pa.cd.b = u; pa.cd.T = T; pa.cd.H = (int)H; pa.cd.nslab = lo.nslab; pa.cd.partial = dDpart;
-    // two scaled fp16 planes per operand: dy and u are measured where dD reads them, the saved states
-    // by a pass of their own, chi where the reverse scan stores it
+    // two scaled fp16 planes per operand: dy and u are measured where dD reads them, chi and the saved
+    // states where the reverse scan stores / reads them
     const bool two_planes = fused;
-    unsigned *am_atomic = reinterpret_cast<unsigned *>(ws + lo.amax_atomic);
+    unsigned *am_atomic = reinterpret_cast<unsigned *>(ws + lo.amax_atomic), *am_xsaved = am_atomic + ABSMAX_SLOTS;
     unsigned *am_bbar = reinterpret_cast<unsigned *>(ws + lo.amax_slots), *am_cc = am_bbar + P, *am_pass = am_cc + H;
     unsigned *am_dy = am_pass + 2 * PREP_PASS_BLOCKS, *am_u = am_dy + lo.amax_cd;
     unsigned *rowmax = reinterpret_cast<unsigned *>(ws + lo.rowmax), *rowpart = reinterpret_cast<unsigned *>(ws + lo.rowpart);
-    const int x_pieces = pass_pieces((size_t)T * 2 * P);
     if (two_planes) {
         pa.bbar_max = am_bbar; pa.cc_max = am_cc; pa.cd_amax = am_dy; pa.cd_bmax = am_u;
-        pa.pass[0].x = xf; pa.pass[0].n = (size_t)T * 2 * P; pa.pass[0].slots = am_pass; pa.pass[0].nblocks = x_pieces;
         pa.cd_arow = rowmax;                 // [ceil(H/64)][T]: rows of dy, measured where the dD column dots read it
     }
     // dy and chi enter C^H dy and Bbar^H chi with tokens as rows (a scale per token); the sums over tokens
     // (dC, dBbar) take one scale per matrix
-    const AbsMax mx_dy{am_dy, lo.amax_cd, nullptr, 0, 0}, mx_u{am_u, lo.amax_cd, nullptr, 0, 0}, mx_x{am_pass, x_pieces, nullptr, 0, 0},
-                 mx_chi{am_atomic, ABSMAX_SLOTS, nullptr, 0, 0}, mx_bbar{am_bbar, (int)P, nullptr, 0, 0},
-                 mx_cc{am_cc, (int)H, nullptr, 0, 0}, mx_dy_rows{nullptr, 0, rowmax, (int)((H + 63) / 64), T}, mx_chi_rows{nullptr, 0, rowpart, lo.row_parts, T};
+    const AbsMax mx_dy{am_dy, lo.amax_cd, nullptr, 0, 0}, mx_u{am_u, lo.amax_cd, nullptr, 0, 0},
+                 mx_x{am_xsaved, ABSMAX_SLOTS, nullptr, 0, 0}, mx_chi{am_atomic, ABSMAX_SLOTS, nullptr, 0, 0},
+                 mx_bbar{am_bbar, (int)P, nullptr, 0, 0}, mx_cc{am_cc, (int)H, nullptr, 0, 0},
+                 mx_dy_rows{nullptr, 0, rowmax, (int)((H + 63) / 64), T}, mx_chi_rows{nullptr, 0, rowpart, lo.row_parts, T};
     HIP_TRY(launch_prep(pa, s));
     MARK();
 
@@ -367,7 +377,15 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     g3.B = Cc; g3.ldb = 2 * P; g3.b_kcontig = 0;
     g3.C = reinterpret_cast<float *>(chi); g3.ldc = 2 * P;
     g3.M = T; g3.N = (int)(2 * P); g3.K = (int)H; g3.splits = 1;
+    // dC slabs: [h, 2p+c] = sum_t dy[t,h] * x[t, 2p+c]
+    GemmArgs g4{};
+    g4.A = dy; g4.lda = H; g4.a_kcontig = 0;
+    g4.B = xf; g4.ldb = 2 * P; g4.b_kcontig = 0;
+    g4.C = dCpart; g4.ldc = 2 * P;
+    g4.M = (int)H; g4.N = (int)(2 * P); g4.K = T; g4.splits = lo.splitC;
     if (fused) {
+        // the product scans its own tiles; the dC slabs wait for the next launch, where the largest
+        // magnitude of the saved states (recorded here, as the scan reads them) is known
         g3.epilogue = 8;
         g3.scan.lam = lam; g3.scan.is_first = is_first;
         g3.scan.x0 = reinterpret_cast<const float2 *>(x0);
@@ -375,16 +393,13 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
         g3.scan.dx0 = reinterpret_cast<float2 *>(dx0);
         g3.scan.desc = reinterpret_cast<unsigned long long *>(ws + lo.fdesc); g3.scan.err = &hdr->err;
         g3.scan.L = (int)L; g3.scan.P = (int)P; g3.scan.spin_limit = spin_limit();
-        if (two_planes) { g3.amaxA = mx_dy_rows; g3.amaxB = mx_cc; g3.scan.amax_out = am_atomic; g3.scan.rowmax_out = rowpart; }
+        g3.amaxA = mx_dy_rows; g3.amaxB = mx_cc;
+        g3.scan.amax_out = am_atomic; g3.scan.xmax_out = am_xsaved; g3.scan.rowmax_out = rowpart;
+        HIP_TRY(launch_gemm(g3, s));
+    } else {
+        // dC needs only dy and the saved states: it shares the launch
+        HIP_TRY(launch_gemm_pair(g3, g4, s));
     }
-    // dC slabs: [h, 2p+c] = sum_t dy[t,h] * x[t, 2p+c]    (needs only saved states: same launch)
-    GemmArgs g4{};
-    g4.A = dy; g4.lda = H; g4.a_kcontig = 0;
-    g4.B = xf; g4.ldb = 2 * P; g4.b_kcontig = 0;
-    g4.C = dCpart; g4.ldc = 2 * P;
-    g4.M = (int)H; g4.N = (int)(2 * P); g4.K = T; g4.splits = lo.splitC;
-    if (two_planes) { g4.amaxA = mx_dy; g4.amaxB = mx_x; }
-    HIP_TRY(launch_gemm_pair(g3, g4, s));
     MARK();
 
     if (!fused) {
@@ -413,21 +428,19 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     g6.B = u; g6.ldb = H; g6.b_kcontig = 0;
     g6.C = dBpart; g6.ldc = H;
     g6.M = (int)(2 * P); g6.N = (int)H; g6.K = T; g6.splits = lo.splitB;
-    if (two_planes) { g5.amaxA = mx_chi_rows; g5.amaxB = mx_bbar; g6.amaxA = mx_chi; g6.amaxB = mx_u; }
+    if (two_planes) { g4.amaxA = mx_dy; g4.amaxB = mx_x; g5.amaxA = mx_chi_rows; g5.amaxB = mx_bbar; g6.amaxA = mx_chi; g6.amaxB = mx_u; }
     if (lo.yhalves) {
         // du has too few 128x128 tiles for half a chip's worth of time: it runs as two K halves (twice
-        // the workgroups, half as long) next to the long work items of the dBbar slabs, which start first;
-        // a streaming pass adds the halves and D dy
+        // the workgroups, half as long); a streaming pass adds the halves and D dy
         float *halves = reinterpret_cast<float *>(ws + lo.yhalves);
         g5.C = halves; g5.ldc = H; g5.splits = 2;
-        HIP_TRY(launch_gemm_pair(g5, g6, s, true));
-        MARK();
         du_halves = halves;                  // added by extra workgroups of the parameter epilogue's launch
     } else {
         g5.C = du; g5.ldc = H; g5.diag = D; g5.E = dy; g5.lde = H; g5.epilogue = 1; g5.splits = 1;
-        HIP_TRY(launch_gemm_pair(g5, g6, s));
-        MARK();
     }
+    if (fused) HIP_TRY(launch_gemm_triple(g5, g6, g4, s));          // three products of equally long work items
+    else HIP_TRY(launch_gemm_pair(g5, g6, s, lo.yhalves != 0));    // the long work items of the slabs first
+    MARK();
     MARK();
 
     EpilogueArgs ea{};

@@ -50,6 +50,7 @@ struct ScanEpilogue {
     unsigned long long *desc;     // [M/128 * ceil(N/128) * 64][2] tagged aggregate words, zero on entry
     unsigned *err;                // set when a bounded wait gives up
     unsigned *amax_out;           // [ABSMAX_SLOTS] or null: atomic maximum of the magnitudes stored to C, zero on entry
+    unsigned *xmax_out;           // [ABSMAX_SLOTS] or null (reverse, with amax_out): atomic maximum of the magnitudes of xsaved
     unsigned *rowmax_out;         // [ceil(N/128), M] or null: per column tile and row, the largest magnitude stored to C
     int L, P;
     unsigned spin_limit;
@@ -91,6 +92,8 @@ hipError_t launch_gemm_halved(const GemmArgs &g, float *halves, hipStream_t s);
 // two independent problems in one launch (falls back to two launches for layouts without a
 // paired instantiation)
 hipError_t launch_gemm_pair(const GemmArgs &a, const GemmArgs &b, hipStream_t s, bool second_first = false);
+// three independent problems in one launch: a product over the state dimension and two K = T reductions
+hipError_t launch_gemm_triple(const GemmArgs &a, const GemmArgs &b, const GemmArgs &c, hipStream_t s);
 // number of K splits for a reduction over K rows with an M x N result that shares its launch
 // with a product of partner_tiles 128x128 tiles
 int gemm_pick_splits(int64_t M, int64_t N, int64_t K, int64_t partner_tiles);
