@@ -378,6 +378,34 @@ __device__ __forceinline__ void scan_epilogue_barriers(const GemmDev &g, int m0)
     if (g.scan.amax_out) __syncthreads();
 }
 
+// Reverse scan: the saved states x_{t-1} of a thread's 16 steps (x_{-1} = x0, zero when absent), plus the
+// last state of the sequence for the thread that owns its last steps.  They are requested before the K
+// loop of the product starts and used in the second pass of the scan, so that their way from memory
+// (16 bytes per token and state that nothing else in this launch reads) is hidden behind the matrix work.
+struct ScanSaved { float2 xp[SCAN_RC]; float2 xl; };
+__device__ __forceinline__ ScanSaved scan_request_saved(const ScanEpilogue &a, int tid, int m0, int n0)
+{
+    constexpr int RC = SCAN_RC;
+    const int c = tid & 63, q = tid >> 6;
+    const int p = n0 / 2 + c;
+    const bool active = p < a.P;
+    const int row0 = m0 + q * RC;
+    const int b = row0 / a.L, t0 = row0 % a.L;
+    const float2 *xprev = a.xsaved + ((long)row0 - 1) * a.P + p;                     // x_{t0-1}; valid for e >= 1 or t0 > 0
+    ScanSaved s;
+    s.xl = make_float2(0.f, 0.f);
+    if (a.xmax_out && active && t0 + RC == a.L) s.xl = xprev[(long)RC * a.P];
+#pragma unroll
+    for (int e = 0; e < RC; ++e) {
+        s.xp[e] = make_float2(0.f, 0.f);
+        if (active) {
+            if (t0 + e > 0) s.xp[e] = xprev[(long)e * a.P];
+            else if (a.x0) s.xp[e] = a.x0[(long)b * a.P + p];
+        }
+    }
+    return s;
+}
+
 // tid: 0 .. 64*SCAN_WAVES-1 (the consumers and the first producer wavefronts: the scan is bound by
 // the issue rate of dependent multiply-adds, so eight wavefronts with 16 steps per lane finish a pass
 // in about half the time of four with 32); the tile is staged in lds.tile on entry (after the first
@@ -386,7 +414,8 @@ __device__ __forceinline__ void scan_epilogue_barriers(const GemmDev &g, int m0)
 // walks time backwards (later chunks and later tiles are the predecessors) and also reduces
 // dAbar += [not is_first_t] conj(x_{t-1}) chi_t per tile and writes dx0.
 template <bool REV>
-__device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanLds &lds, int tid, int m0, int n0, int tile)
+__device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanLds &lds, int tid, int m0, int n0, int tile,
+                                                   const ScanSaved &saved)
 {
     constexpr int RC = SCAN_RC, NCH = SCAN_WAVES;
     static_assert(RC == 16, "flag loads and the powers of Abar below assume 16 steps per lane");
@@ -409,6 +438,15 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
     float2 val[RC];
 #pragma unroll
     for (int e = 0; e < RC; ++e) val[e] = *reinterpret_cast<const float2 *>(lds.tile + (q * RC + e) * SCAN_TS + 2 * c);
+    // Reverse: the saved states pass through this launch exactly once, so their largest magnitude is
+    // recorded on the way: dy^T x, in the next launch, stages x under that scale (x0 is not part of x)
+    float xmax = 0.f;
+    if constexpr (REV) {
+        xmax = fmaxf(fabsf(saved.xl.x), fabsf(saved.xl.y));
+#pragma unroll
+        for (int e = 0; e < RC; ++e)
+            if (t0 + e > 0) xmax = fmaxf(xmax, fmaxf(fabsf(saved.xp[e].x), fabsf(saved.xp[e].y)));
+    }
     // fmask bit e: is_first at time t0 + e
     unsigned fmask = 0;
     if (a.is_first) {
@@ -509,7 +547,6 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
     float2 xs = cfma(Aex, Xin, Sex);
     float2 *dst = reinterpret_cast<float2 *>(g.C) + (long)row0 * a.P + p;
     float amax = 0.f;                                        // largest magnitude this thread stores
-    float xmax = 0.f;                                        // reverse: largest magnitude of the saved states it reads
     unsigned rm[RC];                                         // and per step (row of the tile), for rowmax_out
     if (!REV) {
 #pragma unroll
@@ -524,47 +561,21 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
         }
         if (active && a.x_last && t0 + RC == a.L) a.x_last[(long)b * a.P + p] = xs;
     } else {
-        // also dAbar += [not is_first_t] conj(x_{t-1}) chi_t; x_{-1} = x0 (zero when absent)
-        const float2 *xprev = a.xsaved + ((long)row0 - 1) * a.P + p;             // x_{t0-1}; valid for e >= 1 or t0 > 0
+        // also dAbar += [not is_first_t] conj(x_{t-1}) chi_t
         float2 acc = make_float2(0.f, 0.f);
-        // the saved states pass through here once (x_{t-1} for every step; the last state of a sequence is
-        // fetched on top by the thread that owns its last steps), so their largest magnitude is recorded
-        // on the way: dy^T x, in the next launch, stages x under that scale
-        if (a.xmax_out && active && t0 + RC == a.L) {
-            const float2 xl = xprev[(long)RC * a.P];
-            xmax = fmaxf(fabsf(xl.x), fabsf(xl.y));
-        }
 #pragma unroll
-        for (int blk = RC / 8 - 1; blk >= 0; --blk) {
-            float2 xp[8];                                  // eight loads in flight
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int e = blk * 8 + j;
-                xp[j] = make_float2(0.f, 0.f);
-                if (active) {
-                    if (t0 + e > 0) {
-                        xp[j] = xprev[(long)e * a.P];
-                        xmax = fmaxf(xmax, fmaxf(fabsf(xp[j].x), fabsf(xp[j].y)));
-                    } else if (a.x0) {
-                        xp[j] = a.x0[(long)b * a.P + p];
-                    }
-                }
-            }
-#pragma unroll
-            for (int j = 7; j >= 0; --j) {
-                const int e = blk * 8 + j;
-                const bool r = (rmask >> e) & 1u;
-                const float2 le = make_float2(r ? 0.f : lam.x, r ? 0.f : lam.y);
-                xs = cfma(le, xs, val[e]);
-                if (active) dst[(long)e * a.P] = xs;
-                const float me = fmaxf(fabsf(xs.x), fabsf(xs.y));
-                rm[e] = active ? __float_as_uint(me) : 0u;
-                amax = fmaxf(amax, me);
-                const bool m = (fmask >> e) & 1u;
-                const float2 qv = make_float2(m ? 0.f : xp[j].x, m ? 0.f : xp[j].y);
-                acc.x = fmaf(qv.x, xs.x, fmaf(qv.y, xs.y, acc.x));
-                acc.y = fmaf(qv.x, xs.y, fmaf(-qv.y, xs.x, acc.y));
-            }
+        for (int e = RC - 1; e >= 0; --e) {
+            const bool r = (rmask >> e) & 1u;
+            const float2 le = make_float2(r ? 0.f : lam.x, r ? 0.f : lam.y);
+            xs = cfma(le, xs, val[e]);
+            if (active) dst[(long)e * a.P] = xs;
+            const float me = fmaxf(fabsf(xs.x), fabsf(xs.y));
+            rm[e] = active ? __float_as_uint(me) : 0u;
+            amax = fmaxf(amax, me);
+            const bool m = (fmask >> e) & 1u;
+            const float2 qv = make_float2(m ? 0.f : saved.xp[e].x, m ? 0.f : saved.xp[e].y);
+            acc.x = fmaf(qv.x, xs.x, fmaf(qv.y, xs.y, acc.x));
+            acc.y = fmaf(qv.x, xs.y, fmaf(-qv.y, xs.x, acc.y));
         }
         // lam holds conj(Abar) here: dx0 = [not is_first_0] conj(Abar) chi_0
         if (active && a.dx0 && t0 == 0) a.dx0[(long)b * a.P + p] = (fmask & 1u) ? make_float2(0.f, 0.f) : cmul(lam, xs);
@@ -610,9 +621,6 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
 // LDS holds NS stages; in iteration kt the producers fill the stage of tile kt+NS-1 while the
 // consumers work on tile kt, with one workgroup barrier per K tile.
 // ---------------------------------------------------------------------------------------------
-// Halves of LDS ahead of the stages: log2 of the scale of every row of the A tile (two-plane staging)
-constexpr int gemm_rowexp_halves(int BM, int NPL) { return NPL == 2 ? 2 * BM + 8 : 0; }   // BM + 1 ints, 16-byte multiple
-
 template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL, bool AKC, bool BKC, int EPI, bool FAST>
 __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int m0, int n0, int z,
                                                     int kbeg, int kend, int scan_tile)
@@ -625,11 +633,17 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
     using LB = SplitLoader<BN, BK, BKC, PT, NPL>;
     static_assert(NPL == 2 || NPL == 3, "three bf16 planes or two scaled fp16 planes per operand");
     constexpr int STAGE_A = NPL * LA::PLANE, STAGE_B = NPL * LB::PLANE, STAGE = STAGE_A + STAGE_B;
-    // two-plane staging: LDS starts with log2 of the scale of every row of the A tile and of B (BM + 1 ints),
-    // written by the producers before the first barrier and read by the consumers after the K loop
-    constexpr int ROWEXP_HALVES = gemm_rowexp_halves(BM, NPL);
-    __bf16 *stages = smem + ROWEXP_HALVES;
-    int *rowexp = reinterpret_cast<int *>(smem);
+    // two-plane staging: log2 of the scale of every row of the A tile (index r < BM) and of B (index BM),
+    // written by the producers before the first barrier and read by the consumers after the K loop.
+    // They live in the padding of the first A plane of stage 0 (the 16 or 32 bytes behind every row that
+    // no staging store and no fragment read touches), so that the stages alone are the LDS footprint
+    // (2 x 40 KB for a 128 x 128 x 32 tile with two planes: two workgroups fit the 160 KB of a CU).
+    __bf16 *stages = smem;
+    auto rowexp = [&](int i) -> int & {
+        if constexpr (AKC) return *reinterpret_cast<int *>(stages + (i < BM ? i : 0) * LA::S + BK + (i < BM ? 0 : 2));
+        else return *reinterpret_cast<int *>(stages + (i / 8) * LA::S + BM + 2 * (i % 8));
+    };
+    static_assert(AKC || BM / 8 < BK, "the k rows of a row-contiguous A plane must hold BM + 1 scale words in their padding");
     constexpr int WM = BM / WGM, WN = BN / WGN;
     constexpr int MI = WM / 32, NI = WN / 32;
     static_assert(MI >= 1 && NI >= 1 && WM % 32 == 0 && WN % 32 == 0 && BK % 16 == 0 && NS >= 2, "bad tile");
@@ -654,8 +668,8 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
         for (int i = 0; i < LA::NV; ++i) sca[i] = 1.f;
 #pragma unroll
         for (int i = 0; i < LB::NV; ++i) scb[i] = 1.f;
-        // Two-plane staging: log2 of the scales goes through LDS (rowexp[r], r < BM: row r of the A tile;
-        // rowexp[BM]: B).  The first producer wavefront reduces the one-per-matrix maxima, the first BM
+        // Two-plane staging: log2 of the scales goes through LDS (rowexp(r), r < BM: row r of the A tile;
+        // rowexp(BM): B).  The first producer wavefront reduces the one-per-matrix maxima, the first BM
         // producer threads the per-row ones of A; their loads are issued ahead of the tile loads, so they
         // return first and are waited for with tile 0.
         AbsMaxLoads ma, mb, mr;
@@ -678,19 +692,24 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
         if constexpr (NPL == 2) {
             if (wave == NC) {
                 const int e = absmax_log2_scale(g.amaxB, mb, tid & 63);
-                if ((tid & 63) == 0) rowexp[BM] = e;
+                if ((tid & 63) == 0) rowexp(BM) = e;
                 if (!arows) {
                     const int ea = absmax_log2_scale(g.amaxA, ma, tid & 63);
-                    for (int r = tid & 63; r < BM; r += 64) rowexp[r] = ea;
+                    for (int r = tid & 63; r < BM; r += 64) rowexp(r) = ea;
                 }
             }
-            if (arows && ptid < BM) rowexp[ptid] = absmax_row_log2_scale(g.amaxA, mr, min(m0 + ptid, g.M - 1));
+            if (arows && ptid < BM) rowexp(ptid) = absmax_row_log2_scale(g.amaxA, mr, min(m0 + ptid, g.M - 1));
             __syncthreads();                      // (the consumers wait here as well)
-            const float sb = pow2f(rowexp[BM]);
+            const float sb = pow2f(rowexp(BM));
 #pragma unroll
             for (int i = 0; i < LB::NV; ++i) scb[i] = sb;
 #pragma unroll
-            for (int i = 0; i < LA::NV; ++i) sca[i] = pow2f(rowexp[AKC ? LA::unit_row(ptid, i) : 0]);
+            for (int i = 0; i < LA::NV; ++i) sca[i] = pow2f(rowexp(AKC ? LA::unit_row(ptid, i) : 0));
+        }
+        // the scanning producers of the reverse scan ask for their saved states behind the first tile loads
+        ScanSaved saved;
+        if constexpr (EPI == 8) {
+            if (wave < SCAN_WAVES) saved = scan_request_saved(g.scan, tid, m0, n0);
         }
         // prologue: tiles 0 .. NS-2 into their stages
 #pragma unroll
@@ -722,7 +741,7 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
                 // the first producers scan with the consumers: barriers 1 and 2 frame the staging of the tile
                 __syncthreads();
                 __syncthreads();
-                scan_epilogue_body<EPI == 8>(g, ScanLds(smem), tid, m0, n0, scan_tile);
+                scan_epilogue_body<EPI == 8>(g, ScanLds(smem), tid, m0, n0, scan_tile, saved);
             } else {
                 scan_epilogue_barriers<EPI == 8>(g, m0);
             }
@@ -796,6 +815,8 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
         }
     };
 
+    ScanSaved saved;
+    if constexpr (EPI == 8) saved = scan_request_saved(g.scan, tid, m0, n0);     // (see the producers)
     if constexpr (NPL == 2) __syncthreads();      // the producers have put log2 of the scales into rowexp
     __syncthreads();
     if (nk > 0) fetch_frags(0, 0, 0);
@@ -841,7 +862,7 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
         for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int st = rowexp[wm * WM + i * 32 + 8 * (r / 4) + 4 * hh + (r % 4)] + rowexp[BM];
+                const int st = rowexp(wm * WM + i * 32 + 8 * (r / 4) + 4 * hh + (r % 4)) + rowexp(BM);
                 const int s1 = st >> 1;
                 const float f1 = pow2f(-s1), f2 = pow2f(s1 - st);
 #pragma unroll
@@ -860,7 +881,7 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
                 for (int r = 0; r < 16; ++r)
                     lds.tile[(wm * WM + i * 32 + 8 * (r / 4) + 4 * hh + (r % 4)) * SCAN_TS + wn * WN + j * 32 + li] = acc[i][j][r];
         __syncthreads();                             // barrier 2: the tile is staged
-        scan_epilogue_body<EPI == 8>(g, lds, tid, m0, n0, scan_tile);
+        scan_epilogue_body<EPI == 8>(g, lds, tid, m0, n0, scan_tile, saved);
         return;
     }
     float *Cz = g.C + (long)z * g.M * g.ldc;
@@ -1058,8 +1079,8 @@ __device__ __forceinline__ void gemm_ws_problem(const GemmDev &g, __bf16 *smem, 
 // products have their inputs ready at the same time and one of them alone would leave compute units
 // idle.  Every problem owns a contiguous range of the slots of every XCD, [slot0, slot0 + nx); the host
 // decides the order (work items that should start first get the lowest slots).
-template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL, int LAY0, int LAY1>
-__global__ void __launch_bounds__(64 * (WGM * WGN + NP)) gemm_ws_kernel(GemmDev g0, GemmDev g1, GemmDev g2)
+template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL, int LAY0, int LAY1, int WPE>
+__global__ void __launch_bounds__(64 * (WGM * WGN + NP), WPE) gemm_ws_kernel(GemmDev g0, GemmDev g1, GemmDev g2)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     __bf16 *smem = reinterpret_cast<__bf16 *>(smem_raw);
@@ -1116,8 +1137,10 @@ inline GemmDev make_gemm_dev(const GemmArgs &a)
 
 // b == nullptr: one problem (LAY1 must be -1).  c (optional, only with b): a third problem with the
 // layout of b.  order[i] = which problem (0 = a, 1 = b, 2 = c) takes the i-th range of slots in every
-// XCD; nullptr = a, b, c.
-template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL, int LAY0, int LAY1 = -1>
+// XCD; nullptr = a, b, c.  WPE: wavefronts per SIMD the register allocation must leave room for (with
+// 4 consumer + 4 producer wavefronts and WPE = 4, two workgroups share a CU: one's prologue and stores
+// overlap the other's K loop).
+template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL, int LAY0, int LAY1 = -1, int WPE = 1>
 hipError_t launch_gemm_ws_variant(const GemmArgs &a, hipStream_t s, const GemmArgs *b = nullptr,
                                   const GemmArgs *c = nullptr, const int *order = nullptr)
 {
@@ -1142,11 +1165,11 @@ hipError_t launch_gemm_ws_variant(const GemmArgs &a, hipStream_t s, const GemmAr
     }
     for (int k = nprob; k < 3; ++k) g[k].slot0 = (int)slots;
     constexpr size_t stage0 = gemm_stage_halves(BM, BN, BK, NPL, LAY0), stage1 = LAY1 >= 0 ? gemm_stage_halves(BM, BN, BK, NPL, LAY1) : 0;
-    constexpr size_t stage_bytes = ((size_t)NS * (stage0 > stage1 ? stage0 : stage1) + gemm_rowexp_halves(BM, NPL)) * sizeof(__bf16);
+    constexpr size_t stage_bytes = (size_t)NS * (stage0 > stage1 ? stage0 : stage1) * sizeof(__bf16);
     constexpr bool scans = ((LAY0 >> 2) >= 7) || (LAY1 >= 0 && (LAY1 >> 2) >= 7);
     constexpr size_t smem = (scans && SCAN_LDS_BYTES > stage_bytes) ? SCAN_LDS_BYTES : stage_bytes;
     static_assert(smem <= 160 * 1024, "tile does not fit the 160 KB LDS of a gfx950 CU");
-    auto kern = gemm_ws_kernel<BM, BN, BK, WGM, WGN, NP, NS, NPL, LAY0, LAY1>;
+    auto kern = gemm_ws_kernel<BM, BN, BK, WGM, WGN, NP, NS, NPL, LAY0, LAY1, WPE>;
     if (smem > 64 * 1024) {
         // raising the dynamic LDS limit is idempotent; once per instantiation and device is enough
         // (the attribute belongs to the device's copy of the kernel)

@@ -108,7 +108,7 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
     if (gemm_scan_shape_ok(Bt, L, P)) {
         // dy^T x and chi^T u share the launch of Re(Bbar^H chi): K splits that make their work items as
         // long as that product's (its whole K = 2P, or one K half), at least 256 rows each
-        const int64_t k_du = gemm_out_split_shape((int64_t)T, H, P) ? P : 2 * P;
+        const int64_t k_du = gemm_out_split_shape((int64_t)T, H, P) ? P : 2 * P;      // (half of K where the product has few tiles)
         int64_t sp = ((int64_t)T + k_du / 2) / k_du;
         const int64_t maxs = ((int64_t)T + 255) / 256;
         sp = sp > maxs ? maxs : sp;
@@ -152,7 +152,9 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
         o.dBpart = off; off += up((size_t)o.splitB * 2 * P * H * 4);
         o.dApart = off; off += up(dA_elems * 8);
         o.dDpart = off; off += up((size_t)o.nslab * H * 4);
-        if (gemm_out_split_shape((int64_t)T, H, P)) { o.yhalves = off; off += up(2 * T * H * 4); }   // two K halves of du
+        // two K halves of du, where it shares its launch with the dBbar slabs only (at the scanning shapes it
+        // runs whole, first in a launch of three problems with two workgroups per CU)
+        if (!gemm_scan_shape_ok(Bt, L, P) && gemm_out_split_shape((int64_t)T, H, P)) { o.yhalves = off; off += up(2 * T * H * 4); }
     }
     o.total = off;
     return SSM_OK;
@@ -438,7 +440,7 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     } else {
         g5.C = du; g5.ldc = H; g5.diag = D; g5.E = dy; g5.lde = H; g5.epilogue = 1; g5.splits = 1;
     }
-    if (fused) HIP_TRY(launch_gemm_triple(g5, g6, g4, s));          // three products of equally long work items
+    if (fused) HIP_TRY(launch_gemm_triple(g5, g6, g4, s));          // three products, two workgroups per CU
     else HIP_TRY(launch_gemm_pair(g5, g6, s, lo.yhalves != 0));    // the long work items of the slabs first
     MARK();
     MARK();
