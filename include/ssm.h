@@ -62,7 +62,8 @@ typedef enum {
     SSM_ERR_WORKSPACE = 2,    /* workspace NULL or smaller than ssm_workspace_bytes()        */
     SSM_ERR_UNSUPPORTED = 3,  /* dimension beyond SSM_MAX_*                                   */
     SSM_ERR_HIP = 4,          /* a HIP runtime call or kernel launch failed                   */
-    SSM_ERR_SCAN_TIMEOUT = 5  /* reported by ssm_workspace_status(): a cross-block wait gave up */
+    SSM_ERR_SCAN_TIMEOUT = 5, /* reported by ssm_workspace_status(): a cross-block wait gave up */
+    SSM_ERR_SCRATCH_LIMIT = 6 /* ssm_scan_states_noalloc: the shape needs more than the built-in scratch */
 } ssm_status;
 
 #define SSM_MAX_WIDTH 65536          /* largest H and largest P                        */
@@ -148,6 +149,23 @@ ssm_status ssm_scan_states_reverse(const ssm_c64 *A_bar, ssm_c64 *gx, const ssm_
                                    const uint8_t *is_first, const ssm_c64 *x0,
                                    int64_t Bt, int64_t L, int64_t P, ssm_c64 *dA_bar, ssm_c64 *dx0,
                                    void *workspace, size_t ws_bytes, void *stream);
+
+/* ssm_scan_states for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels
+ * and bit-identical results; the scratch (status header, ticket counters and look-back descriptors of
+ * sequences longer than 256 steps) lives in a device array that is part of the library image, one
+ * copy per GPU, SSM_NOALLOC_SCRATCH_BYTES long.  The call allocates nothing and frees nothing.
+ * A shape whose scratch (ssm_workspace_bytes(Bt, L, 1, P, 0), about Bt * L * P / 8 bytes for L > 256,
+ * 256 bytes otherwise) exceeds that size is refused with SSM_ERR_SCRATCH_LIMIT before any launch.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams,
+ * two host threads) race on it and must be serialised by the caller; consecutive calls on one stream
+ * are fine (what must start at zero is cleared by the call itself, with a kernel).
+ * ssm_scan_states_noalloc_status is ssm_workspace_status for that array on the current device.    */
+#define SSM_NOALLOC_SCRATCH_BYTES (8u << 20)
+ssm_status ssm_scan_states_noalloc(const ssm_c64 *A_bar, ssm_c64 *v, const uint8_t *is_first,
+                                   const ssm_c64 *x0, int64_t Bt, int64_t L, int64_t P, ssm_c64 *x_last,
+                                   void *stream);
+ssm_status ssm_scan_states_noalloc_status(void *stream);
 
 /* Step (recurrent) mode: one transition of the sequence model, x_t, y_t = SSM(u_t, is_first_t,
  * x_{t-1}) (the sequence-model line of Eq. 8), as the imagination roll-out of the actor-critic

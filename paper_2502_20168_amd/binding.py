@@ -20,6 +20,8 @@ SSM_ERR_WORKSPACE = 2
 SSM_ERR_UNSUPPORTED = 3
 SSM_ERR_HIP = 4
 SSM_ERR_SCAN_TIMEOUT = 5
+SSM_ERR_SCRATCH_LIMIT = 6
+SSM_NOALLOC_SCRATCH_BYTES = 8 << 20
 SSM_FWD_STAGES = 5
 SSM_BWD_STAGES = 6
 FWD_STAGE_NAMES = ("discretize_pack", "project_in", "scan", "project_out", "sum_out_halves")
@@ -30,7 +32,8 @@ EXPORTS = ("ssm_strerror", "ssm_version", "ssm_workspace_bytes", "ssm_discretize
            "ssm_scan_bwd", "ssm_scan_states", "ssm_scan_states_reverse", "ssm_scan_fwd_profiled",
            "ssm_scan_bwd_profiled", "ssm_workspace_status", "ssm_step_plan_bytes", "ssm_step_prepare", "ssm_step",
            "ssm_step_bwd", "ssm_lambda_return", "ssm_lambda_return_bwd", "ssm_half_glu_workspace_bytes", "ssm_half_glu_fwd",
-           "ssm_half_glu_bwd", "ssm_block_workspace_bytes", "ssm_block_fwd", "ssm_block_bwd", "ssm_set_spin_limit")
+           "ssm_half_glu_bwd", "ssm_block_workspace_bytes", "ssm_block_fwd", "ssm_block_bwd", "ssm_set_spin_limit",
+           "ssm_scan_states_noalloc", "ssm_scan_states_noalloc_status")
 
 _lib = None
 _vp, _i64, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t
@@ -92,6 +95,10 @@ def lib():
         L.ssm_half_glu_fwd.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp, _vp, _sz, _vp]
         L.ssm_half_glu_bwd.restype = ctypes.c_int
         L.ssm_half_glu_bwd.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _vp, _vp, _vp, _sz, _vp]
+        L.ssm_scan_states_noalloc.restype = ctypes.c_int
+        L.ssm_scan_states_noalloc.argtypes = [_vp, _vp, _vp, _vp, _i64, _i64, _i64, _vp, _vp]
+        L.ssm_scan_states_noalloc_status.restype = ctypes.c_int
+        L.ssm_scan_states_noalloc_status.argtypes = [_vp]
         L.ssm_set_spin_limit.restype = ctypes.c_uint32
         L.ssm_set_spin_limit.argtypes = [ctypes.c_uint32]
         L.ssm_block_workspace_bytes.restype = _sz
@@ -269,6 +276,27 @@ def ssm_scan_states(A_bar, v, is_first=None, x0=None, *, want_x_last=True, works
     if rc != SSM_OK:
         raise SsmError(rc, "ssm_scan_states")
     return v, x_last
+
+
+def ssm_scan_states_noalloc(A_bar, v, is_first=None, x0=None, *, x_last=None, stream=None):
+    """ssm_scan_states on the library's built-in scratch: no workspace, and nothing is allocated here
+    either (x_last, when wanted, is the caller's tensor).  Returns v."""
+    torch = _torch()
+    Bt, L, P = v.shape
+    _chk(A_bar, torch.complex64, (P,), "A_bar")
+    _chk(v, torch.complex64, (Bt, L, P), "v")
+    _chk(is_first, torch.uint8, (Bt, L), "is_first")
+    _chk(x0, torch.complex64, (Bt, P), "x0")
+    _chk(x_last, torch.complex64, (Bt, P), "x_last")
+    rc = lib().ssm_scan_states_noalloc(_ptr(A_bar), _ptr(v), _ptr(is_first), _ptr(x0), Bt, L, P, _ptr(x_last),
+                                       _stream(stream))
+    if rc != SSM_OK:
+        raise SsmError(rc, "ssm_scan_states_noalloc")
+    return v
+
+
+def ssm_scan_states_noalloc_status(stream=None) -> int:
+    return int(lib().ssm_scan_states_noalloc_status(_stream(stream)))
 
 
 def ssm_scan_states_reverse(A_bar, gx, x, is_first=None, x0=None, *, want_dx0=True, workspace=None,

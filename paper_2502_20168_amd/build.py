@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJDIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libssmscan.so")
 SOURCES = ["ssm_api.hip", "gemm.hip", "gemm_inst2.hip", "gemm_inst3.hip", "gemm_pair.hip", "scan.hip", "params.hip",
-           "block.hip"]
+           "block.hip", "noalloc.hip"]
 HEADERS = [os.path.join(CSRC, h) for h in ("ssm_internal.h", "gemm_common.h", "gemm_kernel.h", "lookback.h")] + \
           [os.path.join(os.path.dirname(HERE), "include", h) for h in ("ssm.h", "ssm_measure.h")]
 # packed-fp32 instructions are switched off on purpose (target feature removed for device code)

@@ -476,6 +476,7 @@ const char *ssm_strerror(int status)
     case SSM_ERR_UNSUPPORTED: return "dimension beyond the supported limits";
     case SSM_ERR_HIP: return "HIP runtime call or kernel launch failed";
     case SSM_ERR_SCAN_TIMEOUT: return "a bounded cross-workgroup wait in the scan gave up; outputs invalid";
+    case SSM_ERR_SCRATCH_LIMIT: return "shape needs more than the built-in scratch of the no-allocation entry point";
     default: return "unknown status";
     }
 }

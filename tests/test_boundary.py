@@ -28,8 +28,8 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_strerror_covers_every_code(lib):
-    texts = {ssm.strerror(c) for c in range(6)}
-    assert len(texts) == 6 and all(texts)
+    texts = {ssm.strerror(c) for c in range(7)}
+    assert len(texts) == 7 and all(texts)
     assert ssm.strerror(99) == "unknown status"
     assert ssm.ssm_version() >= 100
 
@@ -166,6 +166,19 @@ def test_s5_block_argument_errors(lib):
     Gd = [FAKE] * 8
     assert lib.ssm_block_bwd(*F, 2, 8, 4, 4, FAKE, FAKE, FAKE, None, *Gd, FAKE, need_b, None) == ssm.SSM_ERR_INVALID_ARG
     assert lib.ssm_block_bwd(*F, 2, 8, 4, 4, FAKE, FAKE, FAKE, FAKE, *Gd, FAKE, need_b - 1, None) == ssm.SSM_ERR_WORKSPACE
+
+
+def test_no_allocation_entry_point_argument_errors(lib):
+    """Errors of ssm_scan_states_noalloc come before any launch (and before the scratch is looked up)."""
+    f = lib.ssm_scan_states_noalloc
+    assert f(None, FAKE, None, None, 2, 8, 4, None, None) == ssm.SSM_ERR_INVALID_ARG
+    assert f(FAKE, None, None, None, 2, 8, 4, None, None) == ssm.SSM_ERR_INVALID_ARG
+    assert f(FAKE, FAKE, None, None, 2, 0, 4, None, None) == ssm.SSM_ERR_INVALID_ARG
+    assert f(FAKE, FAKE, None, None, 2, 8, 1 << 17, None, None) == ssm.SSM_ERR_UNSUPPORTED
+    # 64 sequences of 8192 steps with 256 states need 16 MiB of look-back descriptors: beyond the built-in 8 MiB
+    assert ssm.ssm_workspace_bytes(64, 8192, 1, 256, False) > ssm.SSM_NOALLOC_SCRATCH_BYTES
+    assert f(FAKE, FAKE, None, None, 64, 8192, 256, None, None) == ssm.SSM_ERR_SCRATCH_LIMIT
+    assert "scratch" in ssm.strerror(ssm.SSM_ERR_SCRATCH_LIMIT)
 
 
 def test_spin_limit_hook_returns_the_previous_bound(lib):
