@@ -58,8 +58,11 @@ bool gemm_scan_shape_ok(int64_t Bt, int64_t L, int64_t P)
     if (!chain && !whole) return false;
     // (measured: from 64 tiles on -- a quarter of the CUs -- the scanning tile with its two fp16 planes beats
     // smaller tiles plus a scan kernel: +2 % at 64 tiles, +7..13 % at 96-128; no difference at 32-48)
+#ifndef SSM_SCAN_MIN_TILES
+#define SSM_SCAN_MIN_TILES 64
+#endif
     const int64_t tiles = (Bt * L / SCAN_TILE) * ((2 * P + SCAN_TILE - 1) / SCAN_TILE);
-    return tiles >= 64 && tiles * 64 <= 0x7fffffffLL;
+    return tiles >= SSM_SCAN_MIN_TILES && tiles * 64 <= 0x7fffffffLL;
 }
 
 // argument checks shared by the two scanning epilogues

@@ -24,8 +24,19 @@ static hipError_t dispatch_tile(const GemmArgs &a, hipStream_t s)
 hipError_t gemm_dispatch_two_planes(const GemmArgs &a, int tier, hipStream_t s)
 {
     constexpr int NPL = 2;
-    if (a.epilogue == 7) return launch_gemm_ws_variant<128, 128, 32, 2, 2, 8, 2, NPL, gemm_layout(true, true, 7)>(a, s);
-    if (a.epilogue == 8) return launch_gemm_ws_variant<128, 128, 32, 2, 2, 8, 2, NPL, gemm_layout(true, false, 8)>(a, s);
+    if (a.epilogue == 7 || a.epilogue == 8) {
+        // More tiles than CUs: four producer wavefronts and at most 128 registers, so that two workgroups
+        // share a CU and the scan, the stores and the first loads of one overlap the K loop of the other
+        // (4 x 4096 tokens, H = P = 256: 37.7 instead of 44.7 us).  One round of tiles or less: eight
+        // producers, one workgroup per CU.
+        // (the reverse scan, whose second pass needs more registers, gains nothing from it: measured)
+        const long tiles = (long)((a.M + 127) / 128) * ((a.N + 127) / 128);
+        if (tiles > 256 && a.epilogue == 7)
+            return launch_gemm_ws_variant<128, 128, 32, 2, 2, 4, 2, NPL, gemm_layout(true, true, 7), -1, 4>(a, s);
+        if (a.epilogue == 7) return launch_gemm_ws_variant<128, 128, 32, 2, 2, 8, 2, NPL, gemm_layout(true, true, 7)>(a, s);
+        return launch_gemm_ws_variant<128, 128, 32, 2, 2, 8, 2, NPL, gemm_layout(true, false, 8)>(a, s);
+    }
+    // (a plain product with several rounds of long work items gains nothing from two workgroups per CU: measured)
     if (tier == 0) return dispatch_tile<128, 128, 32>(a, s);
     if (tier == 1) return dispatch_tile<64, 128, 32>(a, s);
     return dispatch_tile<64, 64, 64>(a, s);

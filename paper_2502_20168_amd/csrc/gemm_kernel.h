@@ -289,8 +289,9 @@ constexpr int SCAN_WAVES = 8;                        // wavefronts that scan: th
 constexpr int SCAN_RC = SCAN_TILE / SCAN_WAVES;      // consecutive steps per thread
 constexpr size_t SCAN_LDS_BYTES = (size_t)SCAN_TILE * SCAN_TS * 4   // staged tile
                                   + SCAN_WAVES * 64 * 8 + SCAN_WAVES * 64 * 4   // chunk states and reset tags
-                                  + SCAN_MAX_CHAIN * 64 * 8 + SCAN_MAX_CHAIN * 64 * 4   // predecessors
+                                  + SCAN_WAVES * 64 * 8 + SCAN_WAVES * 64 * 4   // predecessors, one batch (a wavefront each)
                                   + 64 * 8;                          // incoming state per lane
+static_assert(SCAN_LDS_BYTES <= 80 * 1024, "two scanning workgroups share the 160 KB LDS of a CU");
 
 // v[e], e < 16, per lane -> the maximum over the 64 lanes of v[rows16_index(lane)].  Two halving steps
 // inside every quad (lanes that differ in bit 0, then bit 1, swap the half of the remaining values
@@ -357,26 +358,11 @@ struct ScanLds {
         tile = reinterpret_cast<float *>(p); p += (size_t)SCAN_TILE * SCAN_TS * 4;
         cS = reinterpret_cast<float2 *>(p); p += SCAN_WAVES * 64 * 8;
         cAny = reinterpret_cast<unsigned *>(p); p += SCAN_WAVES * 64 * 4;
-        pS = reinterpret_cast<float2 *>(p); p += SCAN_MAX_CHAIN * 64 * 8;
-        pAny = reinterpret_cast<unsigned *>(p); p += SCAN_MAX_CHAIN * 64 * 4;
+        pS = reinterpret_cast<float2 *>(p); p += SCAN_WAVES * 64 * 8;
+        pAny = reinterpret_cast<unsigned *>(p); p += SCAN_WAVES * 64 * 4;
         sX = reinterpret_cast<float2 *>(p);
     }
 };
-
-// the wavefronts that do not scan only keep the others company at the workgroup barriers of the epilogue
-template <bool REV>
-__device__ __forceinline__ void scan_epilogue_barriers(const GemmDev &g, int m0)
-{
-    const int tmL = (m0 % g.scan.L) / SCAN_TILE, nt = g.scan.L / SCAN_TILE;
-    const bool has_pred = g.scan.L >= SCAN_TILE && (REV ? (tmL + 1 < nt) : (tmL > 0));
-    __syncthreads();
-    __syncthreads();
-    __syncthreads();
-    if (has_pred) __syncthreads();
-    __syncthreads();
-    if (REV) __syncthreads();
-    if (g.scan.amax_out) __syncthreads();
-}
 
 // Reverse scan: the saved states x_{t-1} of a thread's 16 steps (x_{-1} = x0, zero when absent), plus the
 // last state of the sequence for the thread that owns its last steps.  They are requested before the K
@@ -406,48 +392,15 @@ __device__ __forceinline__ ScanSaved scan_request_saved(const ScanEpilogue &a, i
     return s;
 }
 
-// tid: 0 .. 64*SCAN_WAVES-1 (the consumers and the first producer wavefronts: the scan is bound by
-// the issue rate of dependent multiply-adds, so eight wavefronts with 16 steps per lane finish a pass
-// in about half the time of four with 32); the tile is staged in lds.tile on entry (after the first
-// two barriers).
-// REV: the scan of the gradient pass, chi_t = gx_t + [not is_first_{t+1}] conj(Abar) chi_{t+1}, which
-// walks time backwards (later chunks and later tiles are the predecessors) and also reduces
-// dAbar += [not is_first_t] conj(x_{t-1}) chi_t per tile and writes dx0.
+// The flags of a thread's 16 steps as bit masks, formed before the K loop of the product so that the
+// scan does not start with a trip to memory.  x = fmask: bit e = is_first at time t0 + e.  y = rmask: bit e =
+// the state that flows into the step at time t0 + e is dropped -- forward: the step's own flag; reverse:
+// the flag of the next time step (nothing flows in at the sequence end).
 template <bool REV>
-__device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanLds &lds, int tid, int m0, int n0, int tile,
-                                                   const ScanSaved &saved)
+__device__ __forceinline__ uint2 scan_flag_masks(const ScanEpilogue &a, int tid, int m0)
 {
-    constexpr int RC = SCAN_RC, NCH = SCAN_WAVES;
-    static_assert(RC == 16, "flag loads and the powers of Abar below assume 16 steps per lane");
-    const ScanEpilogue &a = g.scan;
-    const int c = tid & 63, q = tid >> 6;
-    const int ql = REV ? NCH - 1 - q : q;                    // chunk index in scan order
-    const int p = n0 / 2 + c;
-    const bool active = p < a.P;
-    // A tile is either one piece of a chain of tiles of one sequence (L a multiple of 128) or holds
-    // 128/L whole sequences (L = 16, 32, 64): then there is no chain, a sequence starts at a chunk
-    // boundary inside the tile and its incoming state is x0 (forward) or zero (reverse).
-    const bool whole_seqs = a.L < SCAN_TILE;
-    const int row0 = m0 + q * RC;                            // token index of this thread's first step
-    const int b = row0 / a.L, t0 = row0 % a.L;               // its sequence and its lowest time index
-    const int tmL = whole_seqs ? 0 : (m0 % a.L) / SCAN_TILE, nt = whole_seqs ? 1 : a.L / SCAN_TILE;
-    const int tn = tile % g.ntn;
-    float2 lam = active ? a.lam[p] : make_float2(0.f, 0.f);
-    if (REV) lam.y = -lam.y;
-
-    float2 val[RC];
-#pragma unroll
-    for (int e = 0; e < RC; ++e) val[e] = *reinterpret_cast<const float2 *>(lds.tile + (q * RC + e) * SCAN_TS + 2 * c);
-    // Reverse: the saved states pass through this launch exactly once, so their largest magnitude is
-    // recorded on the way: dy^T x, in the next launch, stages x under that scale (x0 is not part of x)
-    float xmax = 0.f;
-    if constexpr (REV) {
-        xmax = fmaxf(fabsf(saved.xl.x), fabsf(saved.xl.y));
-#pragma unroll
-        for (int e = 0; e < RC; ++e)
-            if (t0 + e > 0) xmax = fmaxf(xmax, fmaxf(fabsf(saved.xp[e].x), fabsf(saved.xp[e].y)));
-    }
-    // fmask bit e: is_first at time t0 + e
+    constexpr int RC = SCAN_RC;
+    const int row0 = m0 + (tid >> 6) * RC, t0 = row0 % a.L;
     unsigned fmask = 0;
     if (a.is_first) {
         const uint8_t *fp = a.is_first + row0;
@@ -463,152 +416,228 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
             for (int j = 0; j < RC; ++j) fmask |= (unsigned)(fp[j] != 0) << j;
         }
     }
-    // rmask bit e: the state that flows into the step at time t0 + e is dropped.  Forward: the
-    // step's own flag.  Reverse: the flag of the next time step (nothing flows in at the sequence end).
     unsigned rmask = fmask;
     if (REV) {
         unsigned next = 1;
         if (t0 + RC < a.L) next = a.is_first ? (unsigned)(a.is_first[(long)row0 + RC] != 0) : 0u;
         rmask = (fmask >> 1) | (next << (RC - 1));
     }
-    // pass 1: state after the thread's steps for zero incoming state (a reset zeroes the multiplier)
-    float2 S = make_float2(0.f, 0.f);
+    return make_uint2(fmask, rmask);
+}
+
+// tid: 0 .. 64*SCAN_WAVES-1 (the consumers and the first producer wavefronts: the scan is bound by
+// the issue rate of dependent multiply-adds, so eight wavefronts with 16 steps per lane finish a pass
+// in about half the time of four with 32); the tile is staged in lds.tile on entry (after the first
+// two barriers).
+// REV: the scan of the gradient pass, chi_t = gx_t + [not is_first_{t+1}] conj(Abar) chi_{t+1}, which
+// walks time backwards (later chunks and later tiles are the predecessors) and also reduces
+// dAbar += [not is_first_t] conj(x_{t-1}) chi_t per tile and writes dx0.
+// PASSIVE: a wavefront of the workgroup that does not scan (producers beyond the eighth wavefront).  It
+// runs through the same function and so meets the others at every workgroup barrier: all barriers stand
+// at the top level of this function under conditions that are uniform over the workgroup, all work
+// sits in blocks that a passive wavefront skips.
+template <bool REV, bool PASSIVE>
+__device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanLds &lds, int tid, int m0, int n0, int tile,
+                                                   const ScanSaved &saved, uint2 masks)
+{
+    constexpr int RC = SCAN_RC, NCH = SCAN_WAVES;
+    constexpr bool ACTIVE = !PASSIVE;
+    static_assert(RC == 16, "flag loads and the powers of Abar below assume 16 steps per lane");
+    const ScanEpilogue &a = g.scan;
+    const int c = tid & 63, q = PASSIVE ? 0 : tid >> 6;
+    const int ql = REV ? NCH - 1 - q : q;                    // chunk index in scan order
+    const int p = n0 / 2 + c;
+    const bool active = ACTIVE && p < a.P;
+    // A tile is either one piece of a chain of tiles of one sequence (L a multiple of 128) or holds
+    // 128/L whole sequences (L = 16, 32, 64): then there is no chain, a sequence starts at a chunk
+    // boundary inside the tile and its incoming state is x0 (forward) or zero (reverse).
+    const bool whole_seqs = a.L < SCAN_TILE;
+    const int row0 = m0 + q * RC;                            // token index of this thread's first step
+    const int b = row0 / a.L, t0 = row0 % a.L;               // its sequence and its lowest time index
+    const int tmL = whole_seqs ? 0 : (m0 % a.L) / SCAN_TILE, nt = whole_seqs ? 1 : a.L / SCAN_TILE;
+    const int tn = tile % g.ntn;
+    const int npred = REV ? nt - 1 - tmL : tmL;              // tiles of the chain that come earlier in scan order (uniform)
+    const bool leader = ACTIVE && (ql == NCH - 1) && !whole_seqs;
+
+    // state of a thread that lives across the barriers
+    float2 lam = make_float2(0.f, 0.f), val[RC], S = make_float2(0.f, 0.f), lrc, l128;
+    float2 Aex = make_float2(1.f, 0.f), Sex = make_float2(0.f, 0.f), X = make_float2(0.f, 0.f);
+    float xmax = 0.f, amax = 0.f;                            // largest magnitude of the saved states read / of the values stored
+    unsigned fmask = 0, rmask = 0;
+
+    if constexpr (ACTIVE) {
+        if (active) lam = a.lam[p];
+        if (REV) lam.y = -lam.y;
 #pragma unroll
-    for (int i = 0; i < RC; ++i) {
-        const int e = REV ? RC - 1 - i : i;
-        const bool r = (rmask >> e) & 1u;
-        const float2 le = make_float2(r ? 0.f : lam.x, r ? 0.f : lam.y);
-        S = cfma(le, S, val[e]);
-    }
-    float2 lrc = cmul(lam, lam);                             // Abar^16 by four squarings
-    lrc = cmul(lrc, lrc); lrc = cmul(lrc, lrc); lrc = cmul(lrc, lrc);
-    lds.cS[ql * 64 + c] = S;
-    lds.cAny[ql * 64 + c] = rmask != 0;
-    __syncthreads();                                                                       // barrier 3
-    // exclusive combine over the chunks of the same sequence that come earlier in scan order
-    const int before = whole_seqs ? (REV ? (a.L - RC - t0) / RC : t0 / RC) : ql;
-    const int ql_first = ql - before;
-    float2 Aex = make_float2(1.f, 0.f), Sex = make_float2(0.f, 0.f);
+        for (int e = 0; e < RC; ++e) val[e] = *reinterpret_cast<const float2 *>(lds.tile + (q * RC + e) * SCAN_TS + 2 * c);
+        // Reverse: the saved states pass through this launch exactly once, so their largest magnitude is
+        // recorded on the way: dy^T x, in the next launch, stages x under that scale (x0 is not part of x)
+        if constexpr (REV) {
+            xmax = fmaxf(fabsf(saved.xl.x), fabsf(saved.xl.y));
 #pragma unroll
-    for (int j = 0; j < NCH - 1; ++j) {
-        const float2 Sj = lds.cS[j * 64 + c];
-        const float2 Aj = lds.cAny[j * 64 + c] ? make_float2(0.f, 0.f) : lrc;
-        const float2 nS = cfma(Aj, Sex, Sj), nA = cmul(Aj, Aex);
-        if (j >= ql_first && j < ql) { Sex = nS; Aex = nA; }
+            for (int e = 0; e < RC; ++e)
+                if (t0 + e > 0) xmax = fmaxf(xmax, fmaxf(fabsf(saved.xp[e].x), fabsf(saved.xp[e].y)));
+        }
+        fmask = masks.x; rmask = masks.y;
+        // pass 1: state after the thread's steps for zero incoming state (a reset zeroes the multiplier)
+#pragma unroll
+        for (int i = 0; i < RC; ++i) {
+            const int e = REV ? RC - 1 - i : i;
+            const bool r = (rmask >> e) & 1u;
+            const float2 le = make_float2(r ? 0.f : lam.x, r ? 0.f : lam.y);
+            S = cfma(le, S, val[e]);
+        }
+        lrc = cmul(lam, lam);                                // Abar^16 by four squarings
+        lrc = cmul(lrc, lrc); lrc = cmul(lrc, lrc); lrc = cmul(lrc, lrc);
+        l128 = cmul(lrc, lrc);                               // Abar^128 by three more
+        l128 = cmul(l128, l128); l128 = cmul(l128, l128);
+        lds.cS[ql * 64 + c] = S;
+        lds.cAny[ql * 64 + c] = rmask != 0;
     }
-    const bool leader = (ql == NCH - 1) && !whole_seqs;
-    const int npred = REV ? nt - 1 - tmL : tmL;              // tiles of the chain that come earlier in scan order
-    const bool has_succ = REV ? (tmL > 0) : (tmL + 1 < nt);
-    float2 l128 = cmul(lrc, lrc);                            // Abar^128 by three more squarings
-    l128 = cmul(l128, l128); l128 = cmul(l128, l128);
-    if (leader) {
-        const float2 Ath = (rmask != 0) ? make_float2(0.f, 0.f) : lrc;
-        const float2 Stile = cfma(Ath, Sex, S);
-        const bool any_tile = (rmask != 0) || (Aex.x == 0.f && Aex.y == 0.f);
-        if (active && has_succ) {
-            unsigned long long *mine = a.desc + ((size_t)tile * 64 + c) * 2;
-            publish_word(mine, Stile.x, any_tile ? 2u : 1u);
-            publish_word(mine + 1, Stile.y, any_tile ? 2u : 1u);
+    __syncthreads();                                         // the chunk states are in LDS
+    if constexpr (ACTIVE) {
+        // exclusive combine over the chunks of the same sequence that come earlier in scan order
+        const int before = whole_seqs ? (REV ? (a.L - RC - t0) / RC : t0 / RC) : ql;
+        const int ql_first = ql - before;
+#pragma unroll
+        for (int j = 0; j < NCH - 1; ++j) {
+            const float2 Sj = lds.cS[j * 64 + c];
+            const float2 Aj = lds.cAny[j * 64 + c] ? make_float2(0.f, 0.f) : lrc;
+            const float2 nS = cfma(Aj, Sex, Sj), nA = cmul(Aj, Aex);
+            if (j >= ql_first && j < ql) { Sex = nS; Aex = nA; }
+        }
+        if (leader) {
+            // the tile's aggregate goes out before anything is waited for
+            const bool has_succ = REV ? (tmL > 0) : (tmL + 1 < nt);
+            const float2 Ath = (rmask != 0) ? make_float2(0.f, 0.f) : lrc;
+            const float2 Stile = cfma(Ath, Sex, S);
+            const bool any_tile = (rmask != 0) || (Aex.x == 0.f && Aex.y == 0.f);
+            if (active && has_succ) {
+                unsigned long long *mine = a.desc + ((size_t)tile * 64 + c) * 2;
+                publish_word(mine, Stile.x, any_tile ? 2u : 1u);
+                publish_word(mine + 1, Stile.y, any_tile ? 2u : 1u);
+            }
+            if (!REV && a.x0 && active) X = a.x0[(long)b * a.P + p];
         }
     }
-    if (npred > 0) {
-        // thread (c, q) fetches the aggregates of predecessors q, q+NCH, ... (k-th predecessor in scan
-        // order = tile k of the sequence forward, tile nt-1-k in reverse)
-        for (int k = q; k < npred; k += NCH) {
-            float2 Sj = make_float2(0.f, 0.f);
-            unsigned tag = 2;
-            if (active) {
-                const int j = REV ? nt - 1 - k : k;
-                const size_t ptile = (size_t)(b * nt + j) * g.ntn + tn;
-                if (!wait_pair(a.desc + (ptile * 64 + c) * 2, 1u, a.spin_limit, Sj, tag)) {
-                    // gave up: flag it, hand on NaN (every state that depends on the missing aggregate
-                    // becomes NaN, so the failure cannot pass as data) and finish anyway
-                    atomicOr(a.err, 1u);
-                    Sj = make_float2(__builtin_nanf(""), __builtin_nanf("")); tag = 2;
+    // The aggregates of the earlier tiles of the chain, eight at a time in scan order (the k-th predecessor
+    // = tile k of the sequence forward, tile nt-1-k in reverse): wavefront q fetches predecessor k0 + q, the
+    // leader folds the batch over the incoming state.  One canonical order, whatever the timing.
+    for (int k0 = 0; k0 < npred; k0 += NCH) {
+        if constexpr (ACTIVE) {
+            const int k = k0 + q;
+            if (k < npred) {
+                float2 Sj = make_float2(0.f, 0.f);
+                unsigned tag = 2;
+                if (active) {
+                    const int j = REV ? nt - 1 - k : k;
+                    const size_t ptile = (size_t)(b * nt + j) * g.ntn + tn;
+                    if (!wait_pair(a.desc + (ptile * 64 + c) * 2, 1u, a.spin_limit, Sj, tag)) {
+                        // gave up: flag it, hand on NaN (every state that depends on the missing aggregate
+                        // becomes NaN, so the failure cannot pass as data) and finish anyway
+                        atomicOr(a.err, 1u);
+                        Sj = make_float2(__builtin_nanf(""), __builtin_nanf("")); tag = 2;
+                    }
+                }
+                lds.pS[q * 64 + c] = Sj;
+                lds.pAny[q * 64 + c] = (tag == 2u);
+            }
+        }
+        __syncthreads();                                     // the batch is in LDS
+        if constexpr (ACTIVE) {
+            if (leader) {
+                const int n = min(NCH, npred - k0);
+                for (int j = 0; j < n; ++j) {
+                    const float2 Aj = lds.pAny[j * 64 + c] ? make_float2(0.f, 0.f) : l128;
+                    X = cfma(Aj, X, lds.pS[j * 64 + c]);
                 }
             }
-            lds.pS[k * 64 + c] = Sj;
-            lds.pAny[k * 64 + c] = (tag == 2u);
         }
-        __syncthreads();                                                                   // barrier 4 (only with predecessors)
+        if (k0 + NCH < npred) __syncthreads();               // the next batch may overwrite the slots
     }
-    if (leader) {
-        float2 X = (!REV && a.x0 && active) ? a.x0[(long)b * a.P + p] : make_float2(0.f, 0.f);
-        for (int k = 0; k < npred; ++k) {
-            const float2 Aj = lds.pAny[k * 64 + c] ? make_float2(0.f, 0.f) : l128;
-            X = cfma(Aj, X, lds.pS[k * 64 + c]);
-        }
-        lds.sX[c] = X;
+    if constexpr (ACTIVE) {
+        if (leader) lds.sX[c] = X;
     }
-    __syncthreads();                                                                       // barrier 5
-    // pass 2: the states themselves
-    float2 Xin = lds.sX[c];
-    if (whole_seqs) Xin = (!REV && a.x0 && active) ? a.x0[(long)b * a.P + p] : make_float2(0.f, 0.f);
-    float2 xs = cfma(Aex, Xin, Sex);
-    float2 *dst = reinterpret_cast<float2 *>(g.C) + (long)row0 * a.P + p;
-    float amax = 0.f;                                        // largest magnitude this thread stores
-    unsigned rm[RC];                                         // and per step (row of the tile), for rowmax_out
-    if (!REV) {
+    __syncthreads();                                         // the incoming state of the tile is in LDS
+    unsigned rm[RC];                                         // largest magnitude per step (row of the tile), for rowmax_out
+    float2 acc = make_float2(0.f, 0.f);
+    if constexpr (ACTIVE) {
+        // pass 2: the states themselves
+        float2 Xin = lds.sX[c];
+        if (whole_seqs) Xin = (!REV && a.x0 && active) ? a.x0[(long)b * a.P + p] : make_float2(0.f, 0.f);
+        float2 xs = cfma(Aex, Xin, Sex);
+        float2 *dst = reinterpret_cast<float2 *>(g.C) + (long)row0 * a.P + p;
+        if (!REV) {
 #pragma unroll
-        for (int e = 0; e < RC; ++e) {
-            const bool r = (rmask >> e) & 1u;
-            const float2 le = make_float2(r ? 0.f : lam.x, r ? 0.f : lam.y);
-            xs = cfma(le, xs, val[e]);
-            if (active) dst[(long)e * a.P] = xs;
-            const float me = fmaxf(fabsf(xs.x), fabsf(xs.y));
-            rm[e] = active ? __float_as_uint(me) : 0u;
-            amax = fmaxf(amax, me);
-        }
-        if (active && a.x_last && t0 + RC == a.L) a.x_last[(long)b * a.P + p] = xs;
-    } else {
-        // also dAbar += [not is_first_t] conj(x_{t-1}) chi_t
-        float2 acc = make_float2(0.f, 0.f);
+            for (int e = 0; e < RC; ++e) {
+                const bool r = (rmask >> e) & 1u;
+                const float2 le = make_float2(r ? 0.f : lam.x, r ? 0.f : lam.y);
+                xs = cfma(le, xs, val[e]);
+                if (active) dst[(long)e * a.P] = xs;
+                const float me = fmaxf(fabsf(xs.x), fabsf(xs.y));
+                rm[e] = active ? __float_as_uint(me) : 0u;
+                amax = fmaxf(amax, me);
+            }
+            if (active && a.x_last && t0 + RC == a.L) a.x_last[(long)b * a.P + p] = xs;
+        } else {
+            // also dAbar += [not is_first_t] conj(x_{t-1}) chi_t
 #pragma unroll
-        for (int e = RC - 1; e >= 0; --e) {
-            const bool r = (rmask >> e) & 1u;
-            const float2 le = make_float2(r ? 0.f : lam.x, r ? 0.f : lam.y);
-            xs = cfma(le, xs, val[e]);
-            if (active) dst[(long)e * a.P] = xs;
-            const float me = fmaxf(fabsf(xs.x), fabsf(xs.y));
-            rm[e] = active ? __float_as_uint(me) : 0u;
-            amax = fmaxf(amax, me);
-            const bool m = (fmask >> e) & 1u;
-            const float2 qv = make_float2(m ? 0.f : saved.xp[e].x, m ? 0.f : saved.xp[e].y);
-            acc.x = fmaf(qv.x, xs.x, fmaf(qv.y, xs.y, acc.x));
-            acc.y = fmaf(qv.x, xs.y, fmaf(-qv.y, xs.x, acc.y));
-        }
-        // lam holds conj(Abar) here: dx0 = [not is_first_0] conj(Abar) chi_0
-        if (active && a.dx0 && t0 == 0) a.dx0[(long)b * a.P + p] = (fmask & 1u) ? make_float2(0.f, 0.f) : cmul(lam, xs);
-        lds.cS[q * 64 + c] = acc;                          // (barrier 5 is behind every reader of cS)
-        __syncthreads();                                                                   // barrier 6 (reverse only)
-        if (q == 0 && active) {
-            float2 sum = make_float2(0.f, 0.f);
-            for (int j = 0; j < NCH; ++j) { sum.x += lds.cS[j * 64 + c].x; sum.y += lds.cS[j * 64 + c].y; }
-            a.partial[(size_t)(m0 / SCAN_TILE) * a.P + p] = sum;
+            for (int e = RC - 1; e >= 0; --e) {
+                const bool r = (rmask >> e) & 1u;
+                const float2 le = make_float2(r ? 0.f : lam.x, r ? 0.f : lam.y);
+                xs = cfma(le, xs, val[e]);
+                if (active) dst[(long)e * a.P] = xs;
+                const float me = fmaxf(fabsf(xs.x), fabsf(xs.y));
+                rm[e] = active ? __float_as_uint(me) : 0u;
+                amax = fmaxf(amax, me);
+                const bool m = (fmask >> e) & 1u;
+                const float2 qv = make_float2(m ? 0.f : saved.xp[e].x, m ? 0.f : saved.xp[e].y);
+                acc.x = fmaf(qv.x, xs.x, fmaf(qv.y, xs.y, acc.x));
+                acc.y = fmaf(qv.x, xs.y, fmaf(-qv.y, xs.x, acc.y));
+            }
+            // lam holds conj(Abar) here: dx0 = [not is_first_0] conj(Abar) chi_0
+            if (active && a.dx0 && t0 == 0) a.dx0[(long)b * a.P + p] = (fmask & 1u) ? make_float2(0.f, 0.f) : cmul(lam, xs);
+            lds.cS[q * 64 + c] = acc;                      // (every reader of cS is behind the barriers above)
         }
     }
-    if (a.rowmax_out) {
-        // largest magnitude of every row within this column tile, stored as [column tile][row] (the consumer
-        // of C takes the maximum over the column tiles): lane l < 16 ends up with the row rows16_index(l) of
-        // the thread's 16
-        const unsigned r = rows16_wave_max(rm, c);
-        if (c < RC) a.rowmax_out[(size_t)tn * g.M + row0 + rows16_index(c)] = r;
+    if (REV) {
+        __syncthreads();                                     // the chunks' contributions to dAbar are in LDS
+        if constexpr (ACTIVE) {
+            if (q == 0 && active) {
+                float2 sum = make_float2(0.f, 0.f);
+                for (int j = 0; j < NCH; ++j) { sum.x += lds.cS[j * 64 + c].x; sum.y += lds.cS[j * 64 + c].y; }
+                a.partial[(size_t)(m0 / SCAN_TILE) * a.P + p] = sum;
+            }
+        }
+    }
+    if constexpr (ACTIVE) {
+        if (a.rowmax_out) {
+            // largest magnitude of every row within this column tile, stored as [column tile][row] (the consumer
+            // of C takes the maximum over the column tiles): lane l < 16 ends up with the row rows16_index(l) of
+            // the thread's 16
+            const unsigned r = rows16_wave_max(rm, c);
+            if (c < RC) a.rowmax_out[(size_t)tn * g.M + row0 + rows16_index(c)] = r;
+        }
     }
     if (a.amax_out) {
         // one atomic per workgroup, spread over ABSMAX_SLOTS addresses (the bit patterns of non-negative
-        // floats order like unsigned integers); cAny is free since barrier 5
+        // floats order like unsigned integers); cAny is free since the incoming state was published
         unsigned v = active ? __float_as_uint(amax) : 0u, vx = active ? __float_as_uint(xmax) : 0u;
+        if constexpr (ACTIVE) {
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) {
-            v = max(v, (unsigned)__shfl_xor((int)v, o));
-            if (REV) vx = max(vx, (unsigned)__shfl_xor((int)vx, o));
+            for (int o = 32; o > 0; o >>= 1) {
+                v = max(v, (unsigned)__shfl_xor((int)v, o));
+                if (REV) vx = max(vx, (unsigned)__shfl_xor((int)vx, o));
+            }
+            if (c == 0) { lds.cAny[q] = v; lds.cAny[NCH + q] = vx; }
         }
-        if (c == 0) { lds.cAny[q] = v; lds.cAny[NCH + q] = vx; }
-        __syncthreads();                                                                   // barrier 7 (with amax_out only)
-        if (tid == 0) {
-            for (int j = 1; j < NCH; ++j) { v = max(v, lds.cAny[j]); vx = max(vx, lds.cAny[NCH + j]); }
-            atomicMax(a.amax_out + (unsigned)tile % ABSMAX_SLOTS, v);
-            if (REV && a.xmax_out) atomicMax(a.xmax_out + (unsigned)tile % ABSMAX_SLOTS, vx);
+        __syncthreads();                                     // the wavefronts' maxima are in LDS
+        if constexpr (ACTIVE) {
+            if (tid == 0) {
+                for (int j = 1; j < NCH; ++j) { v = max(v, lds.cAny[j]); vx = max(vx, lds.cAny[NCH + j]); }
+                atomicMax(a.amax_out + (unsigned)tile % ABSMAX_SLOTS, v);
+                if (REV && a.xmax_out) atomicMax(a.xmax_out + (unsigned)tile % ABSMAX_SLOTS, vx);
+            }
         }
     }
 }
@@ -626,6 +655,7 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
                                                     int kbeg, int kend, int scan_tile)
 {
     constexpr int NC = WGM * WGN;                 // consumer wavefronts
+    constexpr bool SAVED_EARLY = NP >= 8;         // one workgroup per CU: registers to spare during the K loop
     constexpr int PF = 2;                         // K tiles of global loads in flight per producer
                                                   // (3, 4 and 6 measured: 1-5 % slower)
     constexpr int PT = 64 * NP;                   // producer threads
@@ -707,8 +737,13 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
             for (int i = 0; i < LA::NV; ++i) sca[i] = pow2f(rowexp(AKC ? LA::unit_row(ptid, i) : 0));
         }
         // the scanning producers of the reverse scan ask for their saved states behind the first tile loads
+        // (with two workgroups per CU the 34 registers are not there: then behind the K loop)
         ScanSaved saved;
-        if constexpr (EPI == 8) {
+        uint2 masks = make_uint2(0u, 0u);
+        if constexpr (EPI == 7 || EPI == 8) {
+            if (wave < SCAN_WAVES) masks = scan_flag_masks<EPI == 8>(g.scan, tid, m0);
+        }
+        if constexpr (EPI == 8 && SAVED_EARLY) {
             if (wave < SCAN_WAVES) saved = scan_request_saved(g.scan, tid, m0, n0);
         }
         // prologue: tiles 0 .. NS-2 into their stages
@@ -737,13 +772,18 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
         }
         if constexpr (EPI == 7 || EPI == 8) {
             static_assert(EPI < 7 || (NC + NP >= SCAN_WAVES && NC <= SCAN_WAVES), "wavefronts of the scan epilogue");
+            if constexpr (EPI == 8 && !SAVED_EARLY) {
+                if (wave < SCAN_WAVES) saved = scan_request_saved(g.scan, tid, m0, n0);
+            }
             if (wave < SCAN_WAVES) {
                 // the first producers scan with the consumers: barriers 1 and 2 frame the staging of the tile
                 __syncthreads();
                 __syncthreads();
-                scan_epilogue_body<EPI == 8>(g, ScanLds(smem), tid, m0, n0, scan_tile, saved);
+                scan_epilogue_body<EPI == 8, false>(g, ScanLds(smem), tid, m0, n0, scan_tile, saved, masks);
             } else {
-                scan_epilogue_barriers<EPI == 8>(g, m0);
+                __syncthreads();
+                __syncthreads();
+                scan_epilogue_body<EPI == 8, true>(g, ScanLds(smem), tid, m0, n0, scan_tile, saved, masks);
             }
         }
         return;
@@ -816,7 +856,9 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
     };
 
     ScanSaved saved;
-    if constexpr (EPI == 8) saved = scan_request_saved(g.scan, tid, m0, n0);     // (see the producers)
+    uint2 masks = make_uint2(0u, 0u);
+    if constexpr (EPI == 7 || EPI == 8) masks = scan_flag_masks<EPI == 8>(g.scan, tid, m0);     // (see the producers)
+    if constexpr (EPI == 8 && SAVED_EARLY) saved = scan_request_saved(g.scan, tid, m0, n0);
     if constexpr (NPL == 2) __syncthreads();      // the producers have put log2 of the scales into rowexp
     __syncthreads();
     if (nk > 0) fetch_frags(0, 0, 0);
@@ -872,6 +914,7 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
     if constexpr (EPI == 7 || EPI == 8) {
         static_assert(BM == SCAN_TILE && BN == SCAN_TILE && NC == 4, "scan epilogue: 128x128 tile, 4 consumers");
         const ScanLds lds(smem);
+        if constexpr (EPI == 8 && !SAVED_EARLY) saved = scan_request_saved(g.scan, tid, m0, n0);
         __syncthreads();                             // barrier 1: every wavefront has left the K loop, LDS is free
 #pragma unroll
         for (int i = 0; i < MI; ++i)
@@ -881,7 +924,7 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
                 for (int r = 0; r < 16; ++r)
                     lds.tile[(wm * WM + i * 32 + 8 * (r / 4) + 4 * hh + (r % 4)) * SCAN_TS + wn * WN + j * 32 + li] = acc[i][j][r];
         __syncthreads();                             // barrier 2: the tile is staged
-        scan_epilogue_body<EPI == 8>(g, lds, tid, m0, n0, scan_tile, saved);
+        scan_epilogue_body<EPI == 8, false>(g, lds, tid, m0, n0, scan_tile, saved, masks);
         return;
     }
     float *Cz = g.C + (long)z * g.M * g.ldc;
