@@ -39,7 +39,15 @@ PEAK_F16_MFMA_TFLOPS = 2500.0  # MI355X dense fp16 / bf16 matrix
 # counters read for a copy-like kernel of known size (profiles/gemm_scan_cfg2_fwd_bwd.md, which names the
 # commit it was taken at).  Counters cannot be read from inside this process: these are constants of that
 # profile, not measurements of this run.
-PROFILE_TRAFFIC = None         # filled in from profiles/ once the profile of this build exists
+PROFILE_TRAFFIC = {
+    "source": "profiles/gemm_scan_cfg2_fwd_bwd.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE at commit 4328bc8, counters scaled by "
+              "a 64 MiB element-wise kernel of the same run); constants of that profile, not measured by this run",
+    "read_bytes": 278.0 * 2 ** 20, "write_bytes": 126.3 * 2 ** 20, "total_bytes": 404.3 * 2 ** 20,
+    "algorithmic_bytes": 88.1e6, "total_over_algorithmic": 4.8,
+    "dominant_launch_bytes": (94.7 + 43.9) * 2 ** 20,
+    "dominant_launch_algorithmic_bytes": (74 + 40) * 2 ** 20,
+    "dominant_launch_mfma_busy": 0.419,
+}
 
 
 def main():
@@ -50,6 +58,10 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="index into the benchmark configurations")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--profile-iters", type=int, default=30)
+    ap.add_argument("--counter-calibration", action="store_true",
+                    help="also run torch's element-wise add on 64 MiB (reads 64 MiB, writes 64 MiB) a few times, so that "
+                         "a rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of this command holds a kernel of known traffic "
+                         "to scale the counters by")
     ap.add_argument("--path-only", action="store_true",
                     help="skip the sections beside the hot path (scan kernels alone, block_ops, step_mode, s5_block): "
                          "used for the rocprofv3 runs so that every kernel in the trace belongs to one role")
@@ -90,6 +102,13 @@ def main():
                              out=out_b, profile=profile)
         return f, b
 
+    if args.counter_calibration:
+        src = torch.randn(16 << 20, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.add(src, 1.0, out=dst)              # an element-wise kernel (a same-type copy_ would be a memcpy)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
