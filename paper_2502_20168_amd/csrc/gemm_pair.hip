@@ -1,8 +1,11 @@
 // Instantiations of the projection kernel that carry several independent problems in one launch
 // (128x128x32 tiles).  The launches of the gradient pass:
 //   shapes whose projections scan their own tiles (every operand brings its largest magnitude: two
-//   scaled fp16 planes):
+//   scaled fp16 planes), with at least as many scanning tiles as CUs:
 //     Re(Bbar^H chi) + D dy                         with  chi^T u  and  dy^T x  (K = T reductions in slabs)
+//   the same with fewer scanning tiles (C^H dy alone would leave CUs idle):
+//     C^H dy that scans its own tiles               with  dy^T x
+//     Re(Bbar^H chi) + D dy                         with  chi^T u
 //   other shapes (three bf16 planes):
 //     C^H dy                                        with  dy^T x
 //     Re(Bbar^H chi) + D dy                         with  chi^T u
@@ -13,10 +16,15 @@
 namespace ssm {
 
 namespace {
-constexpr int NN0 = gemm_layout(true, false, 0), NN1 = gemm_layout(true, false, 1), TN0 = gemm_layout(false, false, 0);
+constexpr int NN0 = gemm_layout(true, false, 0), NN1 = gemm_layout(true, false, 1), NN8 = gemm_layout(true, false, 8),
+              TN0 = gemm_layout(false, false, 0);
 bool plain_problem(const GemmArgs &g)
 {
     return g.M > 0 && g.N > 0 && g.K > 0 && !(g.splits > 1 && g.epilogue);
+}
+long items128(const GemmArgs &g)
+{
+    return (long)((g.M + 127) / 128) * ((g.N + 127) / 128) * (g.splits < 1 ? 1 : g.splits);
 }
 }  // namespace
 
@@ -26,6 +34,20 @@ hipError_t launch_gemm_pair(const GemmArgs &a, const GemmArgs &b, hipStream_t s,
     const int la = gemm_layout_of(a), lb = gemm_layout_of(b);
     const int swapped[3] = {1, 0, 2};
     const int *order = second_first ? swapped : nullptr;
+    const bool two = gemm_use_two_planes(a) && gemm_use_two_planes(b);
+    if (two && lb == TN0) {
+        // C^H dy that scans its own tiles, with the dC slabs (shapes with fewer scanning tiles than CUs: the
+        // slabs fill the rest of the chip)
+        if (la == NN8) {
+            if (!gemm_scan_args_ok(a)) return hipErrorInvalidValue;
+            return launch_gemm_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, NN8, TN0>(a, s, &b, nullptr, order);
+        }
+        // Re(Bbar^H chi) + D dy with the dBbar slabs: two workgroups per CU when there is more than one round
+        // of work items (see launch_gemm_triple)
+        if (la == NN1 && items128(a) + items128(b) > 288)
+            return launch_gemm_ws_variant<128, 128, 32, 2, 2, 4, 2, 2, NN1, TN0, 4>(a, s, &b, nullptr, order);
+        if (la == NN1) return launch_gemm_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, NN1, TN0>(a, s, &b, nullptr, order);
+    }
     if (!gemm_use_two_planes(a) && !gemm_use_two_planes(b) && lb == TN0) {
         if (la == NN0) return launch_gemm_ws_variant<128, 128, 32, 2, 2, 8, 2, 3, NN0, TN0>(a, s, &b, nullptr, order);
         if (la == NN1) return launch_gemm_ws_variant<128, 128, 32, 2, 2, 8, 2, 3, NN1, TN0>(a, s, &b, nullptr, order);

@@ -77,6 +77,10 @@ inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 struct Layout {
     ScanPlan plan;
     int splitC, splitB, nslab;
+    // scanning shapes with fewer scanning tiles than CUs: the dC slabs share the launch of C^H dy (they need
+    // the largest magnitude of the saved states from a pass of the prep launch); otherwise they wait for the
+    // launch of Re(Bbar^H chi), and the reverse scan records that magnitude on its way
+    bool dc_early;
     size_t hdr, lam, Bri, Cc, xbuf, chi, ticket, desc, dCpart, dBpart, dApart, dDpart, fdesc, fdesc_bytes, yhalves, total;
     // largest magnitudes of the operands of the products (shapes whose projections scan their own tiles):
     // amax_atomic: 2 x ABSMAX_SLOTS words gathered with atomics, directly before fdesc so that one range is
@@ -105,7 +109,8 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
     o.plan = plan_scan(Bt, L, P);
     if (o.plan.nblocks > 0x7fffffffLL) return SSM_ERR_UNSUPPORTED;
     const int64_t rows128 = ((int64_t)T + 127) / 128;
-    if (gemm_scan_shape_ok(Bt, L, P)) {
+    o.dc_early = gemm_scan_shape_ok(Bt, L, P) && rows128 * ((2 * P + 127) / 128) <= 192;
+    if (gemm_scan_shape_ok(Bt, L, P) && !o.dc_early) {
         // dy^T x and chi^T u share the launch of Re(Bbar^H chi): K splits that make their work items as
         // long as that product's (its whole K = 2P, or one K half), at least 256 rows each
         const int64_t k_du = gemm_out_split_shape((int64_t)T, H, P) ? P : 2 * P;      // (half of K where the product has few tiles)
@@ -360,14 +365,17 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     unsigned *am_bbar = reinterpret_cast<unsigned *>(ws + lo.amax_slots), *am_cc = am_bbar + P, *am_pass = am_cc + H;
     unsigned *am_dy = am_pass + 2 * PREP_PASS_BLOCKS, *am_u = am_dy + lo.amax_cd;
     unsigned *rowmax = reinterpret_cast<unsigned *>(ws + lo.rowmax), *rowpart = reinterpret_cast<unsigned *>(ws + lo.rowpart);
+    const int x_pieces = pass_pieces((size_t)T * 2 * P);
     if (two_planes) {
         pa.bbar_max = am_bbar; pa.cc_max = am_cc; pa.cd_amax = am_dy; pa.cd_bmax = am_u;
         pa.cd_arow = rowmax;                 // [ceil(H/64)][T]: rows of dy, measured where the dD column dots read it
+        if (lo.dc_early) { pa.pass[0].x = xf; pa.pass[0].n = (size_t)T * 2 * P; pa.pass[0].slots = am_pass; pa.pass[0].nblocks = x_pieces; }
     }
     // dy and chi enter C^H dy and Bbar^H chi with tokens as rows (a scale per token); the sums over tokens
     // (dC, dBbar) take one scale per matrix
     const AbsMax mx_dy{am_dy, lo.amax_cd, nullptr, 0, 0}, mx_u{am_u, lo.amax_cd, nullptr, 0, 0},
-                 mx_x{am_xsaved, ABSMAX_SLOTS, nullptr, 0, 0}, mx_chi{am_atomic, ABSMAX_SLOTS, nullptr, 0, 0},
+                 mx_x{lo.dc_early ? am_pass : am_xsaved, lo.dc_early ? x_pieces : ABSMAX_SLOTS, nullptr, 0, 0},
+                 mx_chi{am_atomic, ABSMAX_SLOTS, nullptr, 0, 0},
                  mx_bbar{am_bbar, (int)P, nullptr, 0, 0}, mx_cc{am_cc, (int)H, nullptr, 0, 0},
                  mx_dy_rows{nullptr, 0, rowmax, (int)((H + 63) / 64), T}, mx_chi_rows{nullptr, 0, rowpart, lo.row_parts, T};
     HIP_TRY(launch_prep(pa, s));
@@ -396,8 +404,9 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
         g3.scan.desc = reinterpret_cast<unsigned long long *>(ws + lo.fdesc); g3.scan.err = &hdr->err;
         g3.scan.L = (int)L; g3.scan.P = (int)P; g3.scan.spin_limit = spin_limit();
         g3.amaxA = mx_dy_rows; g3.amaxB = mx_cc;
-        g3.scan.amax_out = am_atomic; g3.scan.xmax_out = am_xsaved; g3.scan.rowmax_out = rowpart;
-        HIP_TRY(launch_gemm(g3, s));
+        g3.scan.amax_out = am_atomic; g3.scan.xmax_out = lo.dc_early ? nullptr : am_xsaved; g3.scan.rowmax_out = rowpart;
+        if (lo.dc_early) { g4.amaxA = mx_dy; g4.amaxB = mx_x; HIP_TRY(launch_gemm_pair(g3, g4, s)); }
+        else HIP_TRY(launch_gemm(g3, s));
     } else {
         // dC needs only dy and the saved states: it shares the launch
         HIP_TRY(launch_gemm_pair(g3, g4, s));
@@ -440,8 +449,8 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     } else {
         g5.C = du; g5.ldc = H; g5.diag = D; g5.E = dy; g5.lde = H; g5.epilogue = 1; g5.splits = 1;
     }
-    if (fused) HIP_TRY(launch_gemm_triple(g5, g6, g4, s));          // three products, two workgroups per CU
-    else HIP_TRY(launch_gemm_pair(g5, g6, s, lo.yhalves != 0));    // the long work items of the slabs first
+    if (fused && !lo.dc_early) HIP_TRY(launch_gemm_triple(g5, g6, g4, s));   // three products, two workgroups per CU
+    else HIP_TRY(launch_gemm_pair(g5, g6, s, lo.yhalves != 0));              // (two K halves: the long work items of the slabs first)
     MARK();
     MARK();
 
