@@ -368,9 +368,16 @@ def step_mode(ssm, torch, d, H, P, Bt=1024, horizon=10):
 
     f_ms = graph_time_ms(torch, rollout, 5) / horizon
     b_ms = graph_time_ms(torch, adjoint, 5) / horizon
+    flops = 2 * 2.0 * Bt * (2 * P) * H                      # two products per step, forward and adjoint alike
+    exe = lambda ms: 6 * flops / (ms * 1e-3) / 1e12          # three bf16 planes: six products per multiply-add
     return {"shape": "Bt=%d H=%d P=%d horizon=%d" % (Bt, H, P, horizon), "fwd_us_per_step": round(f_ms * 1e3, 2),
             "bwd_us_per_step": round(b_ms * 1e3, 2),
-            "note": "dependent steps (two GEMM launches each), replayed as one HIP graph; latency bound"}
+            "roofline": {"bound": "mfma", "unit": "TFLOP/s", "peak": PEAK_F16_MFMA_TFLOPS,
+                         "fwd_achieved": round(exe(f_ms), 1), "fwd_frac": round(exe(f_ms) / PEAK_F16_MFMA_TFLOPS, 4),
+                         "bwd_achieved": round(exe(b_ms), 1), "bwd_frac": round(exe(b_ms) / PEAK_F16_MFMA_TFLOPS, 4),
+                         "fp32_equivalent_tflops_fwd": round(flops / (f_ms * 1e-3) / 1e12, 1)},
+            "note": "dependent steps (two GEMM launches each on 64x64x64 tiles, three bf16 planes), replayed as one HIP "
+                    "graph; bound by the latency of two dependent launches, not by throughput"}
 
 
 def s5_block(ssm, torch, wl, d, Bt, L, H, P, iters=10):
@@ -384,8 +391,15 @@ def s5_block(ssm, torch, wl, d, Bt, L, H, P, iters=10):
     b_ms = graph_time_ms(torch, lambda i: ssm.ssm_block_bwd(*par, d["u"], d["is_first"], d["x0"], f["x"], f["y"], f["gate"],
                                                             d["dy"], workspace=ws_b), iters)
     T = Bt * L
+    # forward: the layer's two products (two fp16 planes: three partial products each) and the gate's (three bf16
+    # planes: six); gradient pass: the layer's four and the gate's two
+    exe_f = (2 * 3 * 2.0 * T * 2 * P * H + 6 * 2.0 * T * H * H) / (f_ms * 1e-3) / 1e12
+    exe_b = (4 * 3 * 2.0 * T * 2 * P * H + 2 * 6 * 2.0 * T * H * H) / (b_ms * 1e-3) / 1e12
     return {"shape": "Bt=%d L=%d H=%d P=%d" % (Bt, L, H, P), "fwd_us": round(f_ms * 1e3, 1), "bwd_us": round(b_ms * 1e3, 1),
             "Mtokens_per_s": round(T / ((f_ms + b_ms) * 1e-3) / 1e6, 2),
+            "roofline": {"bound": "mfma", "unit": "TFLOP/s", "peak": PEAK_F16_MFMA_TFLOPS,
+                         "fwd_achieved": round(exe_f, 1), "fwd_frac": round(exe_f / PEAK_F16_MFMA_TFLOPS, 4),
+                         "bwd_achieved": round(exe_b, 1), "bwd_frac": round(exe_b / PEAK_F16_MFMA_TFLOPS, 4)},
             "note": "layer + gate, forward and gradient pass, replayed as HIP graphs (includes the binding's output "
                     "allocations inside the graph); GELU of the layer output is formed where the output projection's result is stored (in the sum of its two K halves at this shape)"}
 
@@ -413,12 +427,21 @@ def block_ops(ssm, torch, wl, T, H, iters=20):
     return {"half_glu": {"shape": "T=%d H=%d" % (T, H), "fwd_us": round(f_ms * 1e3, 2), "bwd_us": round(b_ms * 1e3, 2),
                          "fwd_fp32_equivalent_tflops": round(flops / (f_ms * 1e-3) / 1e12, 1),
                          "bwd_fp32_equivalent_tflops": round(2 * flops / (b_ms * 1e-3) / 1e12, 1),
+                         "roofline": {"bound": "mfma", "unit": "TFLOP/s", "peak": PEAK_F16_MFMA_TFLOPS,
+                                      "fwd_achieved": round(6 * flops / (f_ms * 1e-3) / 1e12, 1),
+                                      "fwd_frac": round(6 * flops / (f_ms * 1e-3) / 1e12 / PEAK_F16_MFMA_TFLOPS, 4),
+                                      "bwd_achieved": round(6 * 2 * flops / (b_ms * 1e-3) / 1e12, 1),
+                                      "bwd_frac": round(6 * 2 * flops / (b_ms * 1e-3) / 1e12 / PEAK_F16_MFMA_TFLOPS, 4),
+                                      "note": "six bf16 partial products per multiply-add (three planes per operand)"},
                          "note": "fwd = GELU pass + one product with the gate in its store; bwd = element-wise "
                                  "pass + two products + slab sum"},
             "lambda_return": {"shape": "T=%d N=%d (time-major)" % (hor, ntraj), "fwd_us": round(lf_ms * 1e3, 2),
                               "bwd_us": round(lb_ms * 1e3, 2),
                               "fwd_GBs": round(16.0 * n / (lf_ms * 1e-3) / 1e9, 1),
                               "bwd_GBs": round(28.0 * n / (lb_ms * 1e-3) / 1e9, 1),
+                              "roofline": {"bound": "hbm", "unit": "GB/s", "peak": PEAK_HBM_GBS,
+                                           "fwd_frac": round(16.0 * n / (lf_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                                           "bwd_frac": round(28.0 * n / (lb_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)},
                               "note": "algorithmic bytes: fwd 3 reads + 1 write, bwd 4 reads + 3 writes of 4 B per "
                                       "(step, trajectory); buffers stay in the last-level cache (warm)"}}
 
