@@ -25,6 +25,32 @@ int gemm_pick_splits(int64_t M, int64_t N, int64_t K, int64_t partner_tiles)
     return (int)s;
 }
 
+// A product over T tokens with N columns that has few 128x128 tiles shares its launch with a K = T
+// reduction on 64x64x64 tiles: a quarter of the multiply-adds per workgroup, so that the chain of K
+// steps a small shape waits for is short.
+#ifndef SSM_SMALL_PAIR_ITEMS
+#define SSM_SMALL_PAIR_ITEMS 64
+#endif
+bool gemm_small_pair(int64_t T, int64_t N)
+{
+    return ((T + 127) / 128) * ((N + 127) / 128) <= SSM_SMALL_PAIR_ITEMS;
+}
+
+// K splits of an M x N reduction over K rows that shares such a launch with a product whose K loop is
+// k_main long: work items about as long as that product's, at most two rounds of workgroups in all
+int gemm_pick_splits_small(int64_t M, int64_t N, int64_t K, int64_t partner_tiles64, int64_t k_main)
+{
+    const int64_t tiles = ((M + 63) / 64) * ((N + 63) / 64);
+    int64_t s = (K + k_main / 2) / (k_main < 64 ? 64 : k_main);
+    const int64_t room = (512 - partner_tiles64) / tiles;
+    if (s > room) s = room;
+    const int64_t maxs = (K + 63) / 64;
+    if (s > maxs) s = maxs;
+    if (s > 64) s = 64;
+    if (s < 1) s = 1;
+    return (int)s;
+}
+
 // Layout code of a problem, or -1 when the projection kernel has no instantiation for it.
 int gemm_layout_of(const GemmArgs &a)
 {

@@ -49,6 +49,11 @@ hipError_t launch_gemm_pair(const GemmArgs &a, const GemmArgs &b, hipStream_t s,
         if (la == NN1) return launch_gemm_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, NN1, TN0>(a, s, &b, nullptr, order);
     }
     if (!gemm_use_two_planes(a) && !gemm_use_two_planes(b) && lb == TN0) {
+        if (gemm_small_pair(a.M, a.N)) {
+            // few tiles: 64x64x64 tiles, so that no workgroup walks a long K loop while most CUs idle
+            if (la == NN0) return launch_gemm_ws_variant<64, 64, 64, 2, 2, 8, 2, 3, NN0, TN0>(a, s, &b, nullptr, order);
+            if (la == NN1) return launch_gemm_ws_variant<64, 64, 64, 2, 2, 8, 2, 3, NN1, TN0>(a, s, &b, nullptr, order);
+        }
         if (la == NN0) return launch_gemm_ws_variant<128, 128, 32, 2, 2, 8, 2, 3, NN0, TN0>(a, s, &b, nullptr, order);
         if (la == NN1) return launch_gemm_ws_variant<128, 128, 32, 2, 2, 8, 2, 3, NN1, TN0>(a, s, &b, nullptr, order);
     }

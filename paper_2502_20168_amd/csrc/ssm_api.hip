@@ -74,6 +74,9 @@ namespace {
 constexpr size_t ALIGN = 256;
 inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
+#ifndef SSM_SMALL_HALVES_MIN_P
+#define SSM_SMALL_HALVES_MIN_P 256
+#endif
 struct Layout {
     ScanPlan plan;
     int splitC, splitB, nslab;
@@ -109,6 +112,7 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
     o.plan = plan_scan(Bt, L, P);
     if (o.plan.nblocks > 0x7fffffffLL) return SSM_ERR_UNSUPPORTED;
     const int64_t rows128 = ((int64_t)T + 127) / 128;
+    bool du_small_halves = false;     // a small du on 64x64x64 tiles as two K halves (summed in the parameter epilogue's launch)
     o.dc_early = gemm_scan_shape_ok(Bt, L, P) && rows128 * ((2 * P + 127) / 128) <= 192;
     if (gemm_scan_shape_ok(Bt, L, P) && !o.dc_early) {
         // dy^T x and chi^T u share the launch of Re(Bbar^H chi): K splits that make their work items as
@@ -122,6 +126,15 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
     } else {
         o.splitC = gemm_pick_splits(H, 2 * P, (int64_t)T, rows128 * ((2 * P + 127) / 128));   // shares C^H dy's launch
         o.splitB = gemm_pick_splits(2 * P, H, (int64_t)T, rows128 * ((H + 127) / 128));       // shares Bbar^H chi's launch
+        const int64_t rows64 = ((int64_t)T + 63) / 64;
+        if (gemm_small_pair((int64_t)T, 2 * P))
+            o.splitC = gemm_pick_splits_small(H, 2 * P, (int64_t)T, rows64 * ((2 * P + 63) / 64), H);
+        if (gemm_small_pair((int64_t)T, H)) {
+            // (measured: a gain when both halves keep four K steps and fit one round of workgroups with room for the slabs)
+            du_small_halves = bwd && P >= SSM_SMALL_HALVES_MIN_P && 2 * rows64 * ((H + 63) / 64) <= 256;
+            o.splitB = du_small_halves ? gemm_pick_splits_small(2 * P, H, (int64_t)T, 2 * rows64 * ((H + 63) / 64), P)
+                                       : gemm_pick_splits_small(2 * P, H, (int64_t)T, rows64 * ((H + 63) / 64), 2 * P);
+        }
     }
     o.nslab = coldot_slabs((int64_t)T);
     size_t off = 0;
@@ -159,7 +172,7 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
         o.dDpart = off; off += up((size_t)o.nslab * H * 4);
         // two K halves of du, where it shares its launch with the dBbar slabs only (at the scanning shapes it
         // runs whole, first in a launch of three problems with two workgroups per CU)
-        if (!gemm_scan_shape_ok(Bt, L, P) && gemm_out_split_shape((int64_t)T, H, P)) { o.yhalves = off; off += up(2 * T * H * 4); }
+        if (!gemm_scan_shape_ok(Bt, L, P) && (gemm_out_split_shape((int64_t)T, H, P) || du_small_halves)) { o.yhalves = off; off += up(2 * T * H * 4); }
     }
     o.total = off;
     return SSM_OK;

@@ -97,6 +97,10 @@ hipError_t launch_gemm_triple(const GemmArgs &a, const GemmArgs &b, const GemmAr
 // number of K splits for a reduction over K rows with an M x N result that shares its launch
 // with a product of partner_tiles 128x128 tiles
 int gemm_pick_splits(int64_t M, int64_t N, int64_t K, int64_t partner_tiles);
+// a product over T tokens with N columns has so few tiles that it and the reduction in its launch run on
+// 64x64x64 tiles; the K splits of that reduction (partner_tiles64: the product's 64x64 tiles, k_main: its K)
+bool gemm_small_pair(int64_t T, int64_t N);
+int gemm_pick_splits_small(int64_t M, int64_t N, int64_t K, int64_t partner_tiles64, int64_t k_main);
 
 // ---------------------------------------------------------------------------------------------
 // Resettable scan over the sequence dimension (forward and reverse time).
