@@ -22,9 +22,9 @@ SSM_ERR_HIP = 4
 SSM_ERR_SCAN_TIMEOUT = 5
 SSM_ERR_SCRATCH_LIMIT = 6
 SSM_NOALLOC_SCRATCH_BYTES = 8 << 20
-SSM_FWD_STAGES = 5
+SSM_FWD_STAGES = 4
 SSM_BWD_STAGES = 6
-FWD_STAGE_NAMES = ("discretize_pack", "project_in", "scan", "project_out", "sum_out_halves")
+FWD_STAGE_NAMES = ("discretize_pack", "project_in", "scan", "project_out")
 BWD_STAGE_NAMES = ("discretize_pack_dD", "gx", "reverse_scan", "du_dBbar_dC_partials", "sum_du_halves",
                    "param_epilogue")
 

@@ -113,11 +113,12 @@ size_t gemm_scan_desc_bytes(int64_t Bt, int64_t L, int64_t P)
 
 // The output projection y = x Cc^T + D u has only M/128 * H/128 tiles of 128x128.  When they would
 // fill less than the chip but twice as many would, the product runs as two halves of K (256
-// workgroups of the efficient 128x128 tile instead of 64x128 tiles) into two slabs, and a streaming
-// kernel adds them and applies the store function.
+// workgroups of the efficient 128x128 tile instead of 64x128 tiles).  The halves of a tile meet inside
+// the launch (KJoin: the layer's forward pass), or go to two slabs that a streaming kernel adds while
+// it applies the store function (launch_gemm_halved: the gate).
 bool gemm_out_split_shape(int64_t T, int64_t H, int64_t P)
 {
-    // a half must still be long enough (8 K tiles) to pay for the streaming pass
+    // a half must still be long enough (8 K tiles) to pay for the hand-over
     const int64_t tiles = ((T + 127) / 128) * ((H + 127) / 128);
     return tiles < 200 && 2 * tiles >= 200 && P >= 256 && (2 * P) % 64 == 0;
 }
@@ -176,14 +177,6 @@ static hipError_t launch_sum(SumHalves a, hipStream_t s)
     return hipGetLastError();
 }
 
-hipError_t launch_sum_halves(const float *s0, const float *s1, const float *D, const float *u, float *y, float *gelu_y,
-                             int64_t T, int64_t H, hipStream_t s)
-{
-    SumHalves a{};
-    a.s0 = s0; a.s1 = s1; a.D = D; a.e = u; a.out = y; a.out2 = gelu_y; a.n = (long)T * H; a.H = (int)H; a.mode = 1;
-    return launch_sum(a, s);
-}
-
 // A product with a store function (epilogue 1, 3, 4 or 6) that runs as two K halves into `halves`
 // ([2][M][N] floats) plus the streaming pass above when its shape calls for it and `halves` is given;
 // otherwise the plain launch.
@@ -214,7 +207,11 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
         if (!gemm_scan_args_ok(a) || gemm_layout_of(a) < 0) return hipErrorInvalidValue;
         return two ? gemm_dispatch_two_planes(a, 0, s) : gemm_dispatch_three_planes(a, 0, s);
     }
-    if (a.splits > 1 && a.epilogue) return hipErrorInvalidValue;
+    // a store function with K splits: only as two halves that meet inside the launch
+    const bool joined = a.join.tiles != nullptr && a.splits == 2;
+    if (a.splits > 1 && a.epilogue && !joined) return hipErrorInvalidValue;
+    if (joined && (!a.join.flags || !a.join.err || !(a.epilogue == 1 || a.epilogue == 3 || a.epilogue == 4 || a.epilogue == 6)))
+        return hipErrorInvalidValue;
     if (a.epilogue < 0 || a.epilogue > 6 || (a.epilogue && a.epilogue != 5 && !a.E)) return hipErrorInvalidValue;
     if (a.epilogue == 5 && a.C2 && !a.diag) return hipErrorInvalidValue;
     if ((a.epilogue == 1 || a.epilogue == 2 || a.epilogue == 6) && !a.diag) return hipErrorInvalidValue;
@@ -228,6 +225,7 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
     const long tiles128 = (long)((a.M + 127) / 128) * ((a.N + 127) / 128) * splits;
     const long tiles64x128 = (long)((a.M + 63) / 64) * ((a.N + 127) / 128) * splits;
     const int tier = tiles128 >= 200 ? 0 : (tiles64x128 >= 200 ? 1 : 2);
+    if (joined && tier != 0) return hipErrorInvalidValue;      // (the hand-over exists for 128x128 tiles)
     return two ? gemm_dispatch_two_planes(a, tier, s) : gemm_dispatch_three_planes(a, tier, s);
 }
 

@@ -31,6 +31,7 @@ struct GemmDev {
     ScanEpilogue scan;
     int sc_nt, sc_cpu, sc_ncg, sc_units, sc_rev;
     AbsMax amaxA, amaxB;    // two-plane fp16 staging only
+    KJoin join;             // two K halves that meet inside the launch (see ssm_internal.h)
 };
 
 // Value stored for an output element whose accumulated product is v.

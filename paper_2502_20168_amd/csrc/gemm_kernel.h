@@ -927,7 +927,49 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
         scan_epilogue_body<EPI == 8, false>(g, lds, tid, m0, n0, scan_tile, saved, masks);
         return;
     }
-    float *Cz = g.C + (long)z * g.M * g.ldc;
+    if constexpr (BM == 128 && BN == 128 && NC == 4 && (EPI == 1 || EPI == 3 || EPI == 4 || EPI == 6)) {
+        if (g.join.tiles) {
+            // Two K halves of one tile meet here.  Split 0 sits in the lower workgroup id of the pair
+            // (placement mode 2), so it is dispatched first and never waits: it hands its accumulators
+            // over in register order (thread t of the partner reads what thread t wrote: coalesced both
+            // ways) with device-scope stores that go through to memory, and raises its wavefront's flag
+            // once they have completed.  Split 1 adds them to its own (one fixed order) and stores.
+            float *part = g.join.tiles + (size_t)scan_tile * (64 * 256) + tid;
+            unsigned *flag = g.join.flags + scan_tile * 4 + wave;
+            if (z == 0) {
+#pragma unroll
+                for (int i = 0; i < MI; ++i)
+#pragma unroll
+                    for (int j = 0; j < NI; ++j)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r)
+                            __hip_atomic_store(part + ((i * NI + j) * 16 + r) * 256, acc[i][j][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_s_waitcnt(0);           // every store of this wavefront has completed
+                asm volatile("" ::: "memory");
+                if (l == 0) __hip_atomic_store(flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                return;
+            }
+            unsigned polls = 0;
+            bool there = true;
+            while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
+                __builtin_amdgcn_s_sleep(1);
+                if (++polls > g.join.spin_limit) { there = false; break; }
+            }
+            asm volatile("" ::: "memory");
+            if (!there && l == 0) atomicOr(g.join.err, 1u);
+#pragma unroll
+            for (int i = 0; i < MI; ++i)
+#pragma unroll
+                for (int j = 0; j < NI; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const float w = __hip_atomic_load(part + ((i * NI + j) * 16 + r) * 256, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        acc[i][j][r] = there ? w + acc[i][j][r] : __builtin_nanf("");     // (gave up: the failure must not pass as data)
+                    }
+        }
+    }
+    float *Cz = (g.join.tiles ? g.C : g.C + (long)z * g.M * g.ldc);
     if constexpr (EPI == 1 || EPI == 6) {
         // sum + diag (.) E: the 16 values of E that a 32x32 block needs are loaded before its first store
         // (the compiler may not move a load of E above an earlier store to C, so a load-compute-store loop
@@ -1162,6 +1204,7 @@ inline GemmDev make_gemm_dev(const GemmArgs &a)
     else { g.mode = 3; g.mpar = 0; g.nx = (int)((ntiles * splits + 7) / 8); }
     g.scan = a.scan;
     g.amaxA = a.amaxA; g.amaxB = a.amaxB;
+    g.join = (BM == 128 && BN == 128 && splits == 2) ? a.join : KJoin{nullptr, nullptr, nullptr, 0};
     g.sc_nt = g.sc_cpu = g.sc_ncg = g.sc_units = g.sc_rev = 0;
     if ((a.epilogue == 7 || a.epilogue == 8) && a.scan.L >= BM) {
         g.sc_rev = a.epilogue == 8;

@@ -56,6 +56,19 @@ struct ScanEpilogue {
     unsigned spin_limit;
 };
 
+// A product that runs as two K halves whose partial tiles meet inside the launch (128x128 tiles only):
+// the half that is dispatched first writes its accumulators to `tiles` with device-scope write-through
+// stores and raises a flag per wavefront; the other half waits for the flag (bounded), adds them to its
+// own (a fixed order: bitwise reproducible) and runs the store function.  No second launch, no slabs.
+struct KJoin {
+    float *tiles;                 // [ceil(M/128) * ceil(N/128)][64][256] floats; null: not joined
+    unsigned *flags;              // [tiles][4], zero on entry
+    unsigned *err;                // set when the bounded wait gives up (the tile is then stored as NaN)
+    unsigned spin_limit;
+};
+inline size_t gemm_join_tile_bytes(int64_t M, int64_t N) { return (size_t)((M + 127) / 128) * ((N + 127) / 128) * 64 * 256 * 4; }
+inline size_t gemm_join_flag_bytes(int64_t M, int64_t N) { return (size_t)((M + 127) / 128) * ((N + 127) / 128) * 4 * 4; }
+
 struct GemmArgs {
     const float *A; int64_t lda; int a_kcontig;
     const float *B; int64_t ldb; int b_kcontig;
@@ -66,6 +79,7 @@ struct GemmArgs {
     int M, N, K, splits;
     ScanEpilogue scan;                               // epilogues 7 and 8
     AbsMax amaxA, amaxB;                             // largest magnitudes of A and B when known
+    KJoin join;                                      // splits == 2 with a store function (epilogue 1, 3, 4, 6)
 };
 // the input projection (epilogue 7) and C^H dy (epilogue 8, the reverse scan of the gradient pass) scan
 // their own output tiles at this shape
@@ -83,9 +97,6 @@ hipError_t gemm_dispatch_two_planes(const GemmArgs &g, int tier, hipStream_t s);
 hipError_t gemm_dispatch_three_planes(const GemmArgs &g, int tier, hipStream_t s);
 // the output projection runs as two K halves into two slabs plus a streaming sum at this shape
 bool gemm_out_split_shape(int64_t T, int64_t H, int64_t P);
-// y = s0 + s1 + D (.) u, and GELU(y) to gelu_y when it is not null
-hipError_t launch_sum_halves(const float *s0, const float *s1, const float *D, const float *u, float *y, float *gelu_y,
-                             int64_t T, int64_t H, hipStream_t s);
 // a product with a store function (epilogue 1, 3, 4, 6): as two K halves into halves[2][M][N] plus a
 // streaming pass when gemm_out_split_shape(M, N, K/2) says so and halves is not null; else launch_gemm
 hipError_t launch_gemm_halved(const GemmArgs &g, float *halves, hipStream_t s);
