@@ -31,7 +31,7 @@ namespace ssm {
 // (written by the kernel that produced the matrix, or by a pass over it), or, for a matrix whose
 // rows are tokens, per row: rows[j * row_stride + r], j < row_parts, are patterns whose maximum is the
 // largest magnitude of row r.  A product whose two operands both carry one may stage them as two
-// scaled fp16 planes (see gemm_bf16x3_kernel.h); per-row maxima (k-contiguous A operand only) give
+// scaled fp16 planes (see gemm_kernel.h); per-row maxima (k-contiguous A operand only) give
 // every row its own scale.
 constexpr int ABSMAX_SLOTS = 512;            // slots of a maximum that is gathered with atomics
 struct AbsMax {
