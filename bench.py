@@ -50,6 +50,12 @@ PROFILE_TRAFFIC = {
 }
 
 
+def gate_products(T, H):
+    """Partial products per multiply-add of the gate's products: two scaled fp16 planes per operand (three) at
+    widths that are multiples of 64 from 512 on with enough tokens, else three bf16 planes (six)."""
+    return 3 if (H % 64 == 0 and H >= 512 and ((T + 63) // 64) * ((H + 127) // 128) >= 200) else 6
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -391,10 +397,11 @@ def s5_block(ssm, torch, wl, d, Bt, L, H, P, iters=10):
     b_ms = graph_time_ms(torch, lambda i: ssm.ssm_block_bwd(*par, d["u"], d["is_first"], d["x0"], f["x"], f["y"], f["gate"],
                                                             d["dy"], workspace=ws_b), iters)
     T = Bt * L
-    # forward: the layer's two products (two fp16 planes: three partial products each) and the gate's (three bf16
-    # planes: six); gradient pass: the layer's four and the gate's two
-    exe_f = (2 * 3 * 2.0 * T * 2 * P * H + 6 * 2.0 * T * H * H) / (f_ms * 1e-3) / 1e12
-    exe_b = (4 * 3 * 2.0 * T * 2 * P * H + 2 * 6 * 2.0 * T * H * H) / (b_ms * 1e-3) / 1e12
+    # forward: the layer's two products and the gate's; gradient pass: the layer's four and the gate's two (two fp16
+    # planes everywhere at this shape: three partial products per multiply-add; else three bf16 planes: six)
+    gp = gate_products(T, H)
+    exe_f = (2 * 3 * 2.0 * T * 2 * P * H + gp * 2.0 * T * H * H) / (f_ms * 1e-3) / 1e12
+    exe_b = (4 * 3 * 2.0 * T * 2 * P * H + 2 * gp * 2.0 * T * H * H) / (b_ms * 1e-3) / 1e12
     return {"shape": "Bt=%d L=%d H=%d P=%d" % (Bt, L, H, P), "fwd_us": round(f_ms * 1e3, 1), "bwd_us": round(b_ms * 1e3, 1),
             "Mtokens_per_s": round(T / ((f_ms + b_ms) * 1e-3) / 1e6, 2),
             "roofline": {"bound": "mfma", "unit": "TFLOP/s", "peak": PEAK_F16_MFMA_TFLOPS,
@@ -416,6 +423,7 @@ def block_ops(ssm, torch, wl, T, H, iters=20):
     b_ms = graph_time_ms(torch, lambda i: ssm.ssm_half_glu_bwd(d["u"], d["W"], gate, d["dy"], workspace=ws_b,
                                                                 du=du, dW=dW), iters)
     flops = 2.0 * T * H * H
+    gp = gate_products(T, H)
     hor, ntraj = 16, 65536
     r = {k: torch.from_numpy(v).cuda() for k, v in wl.gen_returns(hor, ntraj, seed=0).items()}
     ret = torch.empty_like(r["reward"])
@@ -428,11 +436,11 @@ def block_ops(ssm, torch, wl, T, H, iters=20):
                          "fwd_fp32_equivalent_tflops": round(flops / (f_ms * 1e-3) / 1e12, 1),
                          "bwd_fp32_equivalent_tflops": round(2 * flops / (b_ms * 1e-3) / 1e12, 1),
                          "roofline": {"bound": "mfma", "unit": "TFLOP/s", "peak": PEAK_F16_MFMA_TFLOPS,
-                                      "fwd_achieved": round(6 * flops / (f_ms * 1e-3) / 1e12, 1),
-                                      "fwd_frac": round(6 * flops / (f_ms * 1e-3) / 1e12 / PEAK_F16_MFMA_TFLOPS, 4),
-                                      "bwd_achieved": round(6 * 2 * flops / (b_ms * 1e-3) / 1e12, 1),
-                                      "bwd_frac": round(6 * 2 * flops / (b_ms * 1e-3) / 1e12 / PEAK_F16_MFMA_TFLOPS, 4),
-                                      "note": "six bf16 partial products per multiply-add (three planes per operand)"},
+                                      "fwd_achieved": round(gp * flops / (f_ms * 1e-3) / 1e12, 1),
+                                      "fwd_frac": round(gp * flops / (f_ms * 1e-3) / 1e12 / PEAK_F16_MFMA_TFLOPS, 4),
+                                      "bwd_achieved": round(gp * 2 * flops / (b_ms * 1e-3) / 1e12, 1),
+                                      "bwd_frac": round(gp * 2 * flops / (b_ms * 1e-3) / 1e12 / PEAK_F16_MFMA_TFLOPS, 4),
+                                      "note": "%d partial products per multiply-add (%s)" % (gp, "two scaled fp16 planes per operand" if gp == 3 else "three bf16 planes per operand")},
                          "note": "fwd = GELU pass + one product with the gate in its store; bwd = element-wise "
                                  "pass + two products + slab sum"},
             "lambda_return": {"shape": "T=%d N=%d (time-major)" % (hor, ntraj), "fwd_us": round(lf_ms * 1e3, 2),

@@ -122,6 +122,122 @@ __global__ void __launch_bounds__(256) gate_bwd_prep_kernel(const float *__restr
     }
 }
 
+// The same two passes for widths that are multiples of 64, where the products behind them stage their
+// operands as two scaled fp16 planes (three matrix instructions per k block instead of six): they also
+// measure the largest magnitudes that scale those planes -- of every token row of the product's first
+// operand in pieces of 64 columns (rowmax[piece][row]; 16 neighbouring lanes hold one piece), of a whole
+// operand per workgroup (slots[workgroup]), and of W by the extra workgroups behind the first main_blocks.
+__device__ __forceinline__ unsigned abs_bits4(float4 v)
+{
+    return __float_as_uint(fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+}
+__device__ __forceinline__ unsigned max16(unsigned v)
+{
+#pragma unroll
+    for (int o = 8; o > 0; o >>= 1) v = max(v, (unsigned)__shfl_xor((int)v, o));
+    return v;
+}
+// maximum over the 256 threads of the workgroup, valid in thread 0 (red: 4 words of LDS)
+__device__ __forceinline__ unsigned block_max(unsigned v, unsigned *red)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = max(v, (unsigned)__shfl_xor((int)v, o));
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return max(max(red[0], red[1]), max(red[2], red[3]));
+}
+__device__ __forceinline__ void weight_max_block(const float *__restrict__ W, long nW, unsigned *__restrict__ wslots,
+                                                 int b, int nb, unsigned *red)
+{
+    unsigned m = 0;
+    if ((reinterpret_cast<uintptr_t>(W) & 15) == 0 && nW % 4 == 0) {
+        const float4 *W4 = reinterpret_cast<const float4 *>(W);
+        for (long j = (long)b * 256 + threadIdx.x; j < nW / 4; j += (long)nb * 256) m = max(m, abs_bits4(W4[j]));
+    } else {
+        for (long j = (long)b * 256 + threadIdx.x; j < nW; j += (long)nb * 256) m = max(m, __float_as_uint(fabsf(W[j])));
+    }
+    m = block_max(m, red);
+    if (threadIdx.x == 0) wslots[b] = m;
+}
+
+__global__ void __launch_bounds__(256) gelu_max_kernel(const float4 *__restrict__ u, float4 *__restrict__ x1, long n4,
+                                                       int H, long T, unsigned *__restrict__ rowmax,
+                                                       const float *__restrict__ W, long nW,
+                                                       unsigned *__restrict__ wslots, int w_blocks)
+{
+    __shared__ unsigned red[4];
+    if ((int)blockIdx.x < w_blocks) {                    // (first in the grid: their short chains of loads start at once)
+        weight_max_block(W, nW, wslots, (int)blockIdx.x, w_blocks, red);
+        return;
+    }
+    const long i = (long)(blockIdx.x - w_blocks) * 256 + threadIdx.x;
+    unsigned m = 0;
+    if (i < n4) {                                        // (n4 is a multiple of 16: a row piece is in or out as a whole)
+        const float4 a = u[i];
+        const float4 g = make_float4(gelu_exact(a.x), gelu_exact(a.y), gelu_exact(a.z), gelu_exact(a.w));
+        x1[i] = g;
+        m = abs_bits4(g);
+    }
+    m = max16(m);
+    if ((threadIdx.x & 15) == 0 && i < n4) {
+        const long e0 = i * 4, row = e0 / H;
+        rowmax[(size_t)((e0 - row * H) / 64) * T + row] = m;
+    }
+}
+
+__global__ void __launch_bounds__(256) gate_bwd_prep_max_kernel(const float *__restrict__ u, const float *__restrict__ s,
+                                                                const float *__restrict__ dy, float *__restrict__ x1,
+                                                                float *__restrict__ dz, long n, int H, long T,
+                                                                unsigned *__restrict__ dz_rowmax,
+                                                                unsigned *__restrict__ x1_slots, unsigned *__restrict__ dz_slots,
+                                                                const float *__restrict__ W, long nW,
+                                                                unsigned *__restrict__ wslots, int w_blocks)
+{
+    __shared__ unsigned red[4];
+    if ((int)blockIdx.x < w_blocks) {
+        weight_max_block(W, nW, wslots, (int)blockIdx.x, w_blocks, red);
+        return;
+    }
+    const int b = (int)blockIdx.x - w_blocks, main_blocks = (int)gridDim.x - w_blocks;
+    const long stride = (long)main_blocks * 1024;
+    unsigned mx = 0, mz = 0;
+    for (long base = ((long)b * 256 + threadIdx.x) * 4; base < n; base += 4 * stride) {
+        // the inputs of four pieces first, so that their loads are in flight together
+        float4 a[4], g[4], d[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const long i0 = base + k * stride;
+            if (i0 < n) {
+                a[k] = *reinterpret_cast<const float4 *>(u + i0);
+                g[k] = *reinterpret_cast<const float4 *>(s + i0);
+                d[k] = *reinterpret_cast<const float4 *>(dy + i0);
+            }
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const long i0 = base + k * stride;
+            if (i0 < n) {                                // (n is a multiple of 64: the 16 lanes of a piece stay together)
+                const float4 xo = make_float4(gelu_exact(a[k].x), gelu_exact(a[k].y), gelu_exact(a[k].z), gelu_exact(a[k].w));
+                const float4 zo = make_float4(d[k].x * a[k].x * (g[k].x * (1.f - g[k].x)), d[k].y * a[k].y * (g[k].y * (1.f - g[k].y)),
+                                              d[k].z * a[k].z * (g[k].z * (1.f - g[k].z)), d[k].w * a[k].w * (g[k].w * (1.f - g[k].w)));
+                *reinterpret_cast<float4 *>(x1 + i0) = xo;
+                *reinterpret_cast<float4 *>(dz + i0) = zo;
+                const unsigned bz = abs_bits4(zo);
+                mx = max(mx, abs_bits4(xo)); mz = max(mz, bz);
+                const unsigned piece = max16(bz);
+                if ((threadIdx.x & 15) == 0) {
+                    const long row = i0 / H;
+                    dz_rowmax[(size_t)((i0 - row * H) / 64) * T + row] = piece;
+                }
+            }
+        }
+    }
+    mx = block_max(mx, red);
+    __syncthreads();
+    mz = block_max(mz, red);
+    if (threadIdx.x == 0) { x1_slots[b] = mx; dz_slots[b] = mz; }
+}
+
 // fixed-order sum of the K-split slabs of a product
 __global__ void __launch_bounds__(256) sum_slabs_kernel(const float *__restrict__ part, long n, int nslab,
                                                         float *__restrict__ out)
@@ -133,7 +249,13 @@ __global__ void __launch_bounds__(256) sum_slabs_kernel(const float *__restrict_
     out[i] = acc;
 }
 
-struct GluLayout { size_t x1, dz, dWpart, halves, total; int splits; };
+constexpr int GLU_MAX_SLOTS = 512;      // workgroups of the element-wise pass that report a maximum each
+constexpr int GLU_W_BLOCKS = 256;       // workgroups that measure W
+struct GluLayout {
+    size_t x1, dz, dWpart, halves, total; int splits;
+    // widths that are multiples of 64: two scaled fp16 planes per operand, with their largest magnitudes
+    bool two_planes; size_t rowmax, slots; int row_parts, main_blocks;
+};
 
 bool make_glu_layout(int64_t T, int64_t H, bool bwd, GluLayout &o)
 {
@@ -148,6 +270,15 @@ bool make_glu_layout(int64_t T, int64_t H, bool bwd, GluLayout &o)
         o.dz = off; off += up((size_t)T * H * 4);
         o.splits = gemm_pick_splits(H, H, T, 0);
         o.dWpart = off; off += up((size_t)o.splits * H * H * 4);
+    }
+    o.two_planes = gate_two_planes_shape(T, H);
+    o.rowmax = o.slots = 0; o.row_parts = o.main_blocks = 0;
+    if (o.two_planes) {
+        o.row_parts = (int)(H / 64);
+        const int64_t blocks = (T * H / 4 + 255) / 256;
+        o.main_blocks = (int)(bwd ? (blocks < GLU_MAX_SLOTS ? blocks : GLU_MAX_SLOTS) : blocks);
+        o.rowmax = off; off += up((size_t)o.row_parts * T * 4);
+        o.slots = off; off += up((size_t)(2 * GLU_MAX_SLOTS + GLU_W_BLOCKS) * 4);     // x1, dz, W
     }
     o.total = off;
     return true;
@@ -210,9 +341,17 @@ ssm_status ssm_half_glu_fwd(const float *u, const float *W, int64_t T, int64_t H
     hipStream_t s = static_cast<hipStream_t>(stream);
     float *x1 = reinterpret_cast<float *>(static_cast<char *>(workspace) + lo.x1);
     const long n = (long)T * H, n4 = n / 4;
-    const long threads = n4 > 4 ? n4 : 4;
-    hipLaunchKernelGGL(gelu_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s,
-                       reinterpret_cast<const float4 *>(u), reinterpret_cast<float4 *>(x1), n4, u, x1, n);
+    unsigned *rowmax = reinterpret_cast<unsigned *>(static_cast<char *>(workspace) + lo.rowmax);
+    unsigned *wslots = reinterpret_cast<unsigned *>(static_cast<char *>(workspace) + lo.slots) + 2 * GLU_MAX_SLOTS;
+    if (lo.two_planes) {
+        hipLaunchKernelGGL(gelu_max_kernel, dim3((unsigned)(lo.main_blocks + GLU_W_BLOCKS)), dim3(256), 0, s,
+                           reinterpret_cast<const float4 *>(u), reinterpret_cast<float4 *>(x1), n4, (int)H, (long)T, rowmax,
+                           W, (long)H * H, wslots, GLU_W_BLOCKS);
+    } else {
+        const long threads = n4 > 4 ? n4 : 4;
+        hipLaunchKernelGGL(gelu_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s,
+                           reinterpret_cast<const float4 *>(u), reinterpret_cast<float4 *>(x1), n4, u, x1, n);
+    }
     HIP_TRY(hipGetLastError());
     // y[t, j] = u[t, j] sigmoid(sum_i x1[t, i] W[i, j])
     GemmArgs g{};
@@ -220,6 +359,7 @@ ssm_status ssm_half_glu_fwd(const float *u, const float *W, int64_t T, int64_t H
     g.B = W; g.ldb = H; g.b_kcontig = 0;
     g.C = y; g.ldc = H; g.E = u; g.lde = H; g.C2 = gate; g.epilogue = 3;
     g.M = (int)T; g.N = (int)H; g.K = (int)H; g.splits = 1;
+    if (lo.two_planes) { g.amaxA = AbsMax{nullptr, 0, rowmax, lo.row_parts, (long)T}; g.amaxB = AbsMax{wslots, GLU_W_BLOCKS, nullptr, 0, 0}; }
     float *halves = lo.halves ? reinterpret_cast<float *>(static_cast<char *>(workspace) + lo.halves) : nullptr;
     HIP_TRY(launch_gemm_halved(g, halves, s));
     return SSM_OK;
@@ -243,8 +383,15 @@ ssm_status ssm_half_glu_bwd(const float *u, const float *W, const float *gate, c
     float *dz = reinterpret_cast<float *>(ws + lo.dz);
     float *dWpart = reinterpret_cast<float *>(ws + lo.dWpart);
     const long n = (long)T * H;
-    hipLaunchKernelGGL(gate_bwd_prep_kernel, dim3((unsigned)(((n + 3) / 4 + 255) / 256)), dim3(256), 0, s, u, gate, dy, x1,
-                       dz, n);
+    unsigned *rowmax = reinterpret_cast<unsigned *>(ws + lo.rowmax);
+    unsigned *x1_slots = reinterpret_cast<unsigned *>(ws + lo.slots), *dz_slots = x1_slots + GLU_MAX_SLOTS, *wslots = dz_slots + GLU_MAX_SLOTS;
+    if (lo.two_planes) {
+        hipLaunchKernelGGL(gate_bwd_prep_max_kernel, dim3((unsigned)(lo.main_blocks + GLU_W_BLOCKS)), dim3(256), 0, s, u, gate, dy,
+                           x1, dz, n, (int)H, (long)T, rowmax, x1_slots, dz_slots, W, (long)H * H, wslots, GLU_W_BLOCKS);
+    } else {
+        hipLaunchKernelGGL(gate_bwd_prep_kernel, dim3((unsigned)(((n + 3) / 4 + 255) / 256)), dim3(256), 0, s, u, gate, dy, x1,
+                           dz, n);
+    }
     HIP_TRY(hipGetLastError());
     // du[t, i] = dy[t, i] s[t, i] + GELU'(u[t, i]) sum_j dz[t, j] W[i, j]
     GemmArgs g{};
@@ -252,6 +399,7 @@ ssm_status ssm_half_glu_bwd(const float *u, const float *W, const float *gate, c
     g.B = W; g.ldb = H; g.b_kcontig = 1;
     g.C = du; g.ldc = H; g.E = dy; g.E2 = gate; g.E3 = u; g.lde = H; g.epilogue = 4;
     g.M = (int)T; g.N = (int)H; g.K = (int)H; g.splits = 1;
+    if (lo.two_planes) { g.amaxA = AbsMax{nullptr, 0, rowmax, lo.row_parts, (long)T}; g.amaxB = AbsMax{wslots, GLU_W_BLOCKS, nullptr, 0, 0}; }
     HIP_TRY(launch_gemm_halved(g, lo.halves ? reinterpret_cast<float *>(ws + lo.halves) : nullptr, s));
     // dW[i, j] = sum_t x1[t, i] dz[t, j]: reduction over tokens in K slabs, then a fixed-order sum
     GemmArgs h{};
@@ -259,6 +407,7 @@ ssm_status ssm_half_glu_bwd(const float *u, const float *W, const float *gate, c
     h.B = dz; h.ldb = H; h.b_kcontig = 0;
     h.C = dWpart; h.ldc = H;
     h.M = (int)H; h.N = (int)H; h.K = (int)T; h.splits = lo.splits;
+    if (lo.two_planes) { h.amaxA = AbsMax{x1_slots, lo.main_blocks, nullptr, 0, 0}; h.amaxB = AbsMax{dz_slots, lo.main_blocks, nullptr, 0, 0}; }
     HIP_TRY(launch_gemm(h, s));
     const long nw = (long)H * H;
     hipLaunchKernelGGL(sum_slabs_kernel, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, s, dWpart, nw, lo.splits, dW);

@@ -198,6 +198,14 @@ hipError_t launch_gemm_halved(const GemmArgs &a, float *halves, hipStream_t s)
     return launch_sum(q, s);
 }
 
+int gemm_tile_tier(int64_t M, int64_t N, int splits_in)
+{
+    const int64_t splits = splits_in < 1 ? 1 : splits_in;
+    const int64_t tiles128 = ((M + 127) / 128) * ((N + 127) / 128) * splits;
+    const int64_t tiles64x128 = ((M + 63) / 64) * ((N + 127) / 128) * splits;
+    return tiles128 >= 200 ? 0 : (tiles64x128 >= 200 ? 1 : 2);
+}
+
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
 {
     if (a.M <= 0 || a.N <= 0 || a.K <= 0) return hipErrorInvalidValue;
@@ -221,10 +229,7 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
     // measured on MI355X: 128x128x32 tiles with 4 consumer and 8 producer wavefronts when they give
     // (nearly) every CU a workgroup; else 64x128x32 tiles (staging per multiply-add is 1.5x there);
     // else, for the small products of step mode, 64x64x64 tiles (fewer, longer K steps)
-    const long splits = a.splits < 1 ? 1 : a.splits;
-    const long tiles128 = (long)((a.M + 127) / 128) * ((a.N + 127) / 128) * splits;
-    const long tiles64x128 = (long)((a.M + 63) / 64) * ((a.N + 127) / 128) * splits;
-    const int tier = tiles128 >= 200 ? 0 : (tiles64x128 >= 200 ? 1 : 2);
+    const int tier = gemm_tile_tier(a.M, a.N, a.splits);
     if (joined && tier != 0) return hipErrorInvalidValue;      // (the hand-over exists for 128x128 tiles)
     return two ? gemm_dispatch_two_planes(a, tier, s) : gemm_dispatch_three_planes(a, tier, s);
 }

@@ -350,6 +350,44 @@ __device__ __forceinline__ unsigned rows16_wave_max(unsigned (&v)[16], int lane)
 // the row whose maximum lane `lane` (< 16) holds after rows16_wave_max
 __device__ __forceinline__ int rows16_index(int lane) { return ((lane >> 2) & 3) + 4 * ((lane >> 1) & 1) + 8 * (lane & 1); }
 
+// v[e], e < 16, per lane -> the maximum over the 32 lanes that share lane bit 5 of v[rows16_half_index(lane)]
+// (the two halves of a wavefront hold different rows of a 32x32 accumulator block): the same halving
+// exchanges, then one full exchange between the two rows of 16 lanes.
+__device__ __forceinline__ unsigned rows16_half_max(unsigned (&v)[16], int lane)
+{
+    {
+        const bool up = lane & 1;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const unsigned keep = up ? v[k + 8] : v[k], send = up ? v[k] : v[k + 8];
+            v[k] = max(keep, dpp_move<0xb1>(send));
+        }
+    }
+    {
+        const bool up = (lane >> 1) & 1;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const unsigned keep = up ? v[k + 4] : v[k], send = up ? v[k] : v[k + 4];
+            v[k] = max(keep, dpp_move<0x4e>(send));
+        }
+    }
+    {
+        const bool up = (lane >> 2) & 1;
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {
+            const unsigned keep = up ? v[k + 2] : v[k], send = up ? v[k] : v[k + 2];
+            v[k] = max(keep, (unsigned)__shfl_xor((int)send, 4));
+        }
+    }
+    {
+        const bool up = (lane >> 3) & 1;
+        const unsigned keep = up ? v[1] : v[0], send = up ? v[0] : v[1];
+        v[0] = max(keep, (unsigned)__shfl_xor((int)send, 8));
+    }
+    return max(v[0], (unsigned)__shfl_xor((int)v[0], 16));
+}
+__device__ __forceinline__ int rows16_half_index(int lane) { return 8 * (lane & 1) + 4 * ((lane >> 1) & 1) + 2 * ((lane >> 2) & 1) + ((lane >> 3) & 1); }
+
 struct ScanLds {
     float *tile; float2 *cS; unsigned *cAny; float2 *pS; unsigned *pAny; float2 *sX;
     __device__ explicit ScanLds(void *base)
@@ -976,7 +1014,10 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
         // would pay one memory latency per element); the scheduling barrier keeps the loads of the next
         // block from being hoisted as well, which would not fit the register budget
 #pragma unroll
-        for (int i = 0; i < MI; ++i)
+        for (int i = 0; i < MI; ++i) {
+            unsigned gmax[16];                           // EPI 6: largest |GELU(y)| of the thread's 16 rows so far
+#pragma unroll
+            for (int r = 0; r < 16; ++r) gmax[r] = 0u;
 #pragma unroll
             for (int j = 0; j < NI; ++j) {
                 const int col = n0 + wn * WN + j * 32 + li;
@@ -994,11 +1035,26 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
                     if (FAST || (row < g.M && col < g.N)) {
                         const float y = fmaf(dcol, e[r], acc[i][j][r]);
                         Cz[row * g.ldc + col] = y;
-                        if constexpr (EPI == 6) g.C2[row * g.ldc + col] = gelu_value(y);
+                        if constexpr (EPI == 6) {
+                            const float gy = gelu_value(y);
+                            g.C2[row * g.ldc + col] = gy;
+                            gmax[r] = max(gmax[r], __float_as_uint(fabsf(gy)));
+                        }
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
+            if constexpr (EPI == 6 && WN == 64) {
+                // the product that consumes C2 stages its rows under a scale each: the largest magnitude of
+                // every row within this wavefront's 64 columns, as [piece of 64 columns][row]
+                if (g.c2_rowmax) {
+                    const unsigned m = rows16_half_max(gmax, l);
+                    const int r = rows16_half_index(l);
+                    const long row = m0 + wm * WM + i * 32 + 4 * hh + 8 * (r / 4) + (r % 4);
+                    if ((l & 16) == 0 && row < g.M) g.c2_rowmax[(size_t)((n0 + wn * WN) / 64) * g.M + row] = m;
+                }
+            }
+        }
         return;
     }
     if constexpr (EPI == 3) {
@@ -1204,6 +1260,7 @@ inline GemmDev make_gemm_dev(const GemmArgs &a)
     else { g.mode = 3; g.mpar = 0; g.nx = (int)((ntiles * splits + 7) / 8); }
     g.scan = a.scan;
     g.amaxA = a.amaxA; g.amaxB = a.amaxB;
+    g.c2_rowmax = a.c2_rowmax;
     g.join = (BM == 128 && BN == 128 && splits == 2) ? a.join : KJoin{nullptr, nullptr, nullptr, 0};
     g.sc_nt = g.sc_cpu = g.sc_ncg = g.sc_units = g.sc_rev = 0;
     if ((a.epilogue == 7 || a.epilogue == 8) && a.scan.L >= BM) {

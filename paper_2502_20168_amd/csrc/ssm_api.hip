@@ -226,10 +226,16 @@ struct StageTimer {
 #define MARK() do { if (timer) timer->mark(); } while (0)
 #define HIP_TRY(expr) do { if ((expr) != hipSuccess) return SSM_ERR_HIP; } while (0)
 
+// The S5 block: the gate's product consumes GELU(y) and W as two scaled fp16 planes, so the layer's forward
+// pass measures them on its way: the rows of GELU(y) where the output projection stores it, W in a pass
+// of the prep launch.
+struct GateMax { unsigned *x1_rowmax; const float *W; size_t nW; unsigned *wslots; int nwslots; };
+
 ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, const float *D,
                    const float *log_delta, const float *u, const uint8_t *is_first, const ssm_c64 *x0,
                    int64_t Bt, int64_t L, int64_t H, int64_t P, float *y, ssm_c64 *x, ssm_c64 *x_last,
-                   void *workspace, size_t ws_bytes, hipStream_t s, StageTimer *timer, float *gelu_y = nullptr)
+                   void *workspace, size_t ws_bytes, hipStream_t s, StageTimer *timer, float *gelu_y = nullptr,
+                   const GateMax *gate_max = nullptr)
 {
     if (!Lambda || !B || !C || !D || !log_delta || !u || !y) return SSM_ERR_INVALID_ARG;
     Layout lo;
@@ -274,6 +280,10 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
         pa.pass[0].x = u; pa.pass[0].n = (size_t)T * H; pa.pass[0].slots = rowmax; pa.pass[0].rowlen = (int)H;
         pa.pass[0].nblocks = pass_pieces((size_t)T * H);
     }
+    if (gate_max) {
+        pa.pass[1].x = gate_max->W; pa.pass[1].n = gate_max->nW; pa.pass[1].slots = gate_max->wslots;
+        pa.pass[1].nblocks = gate_max->nwslots; pa.pass[1].rowlen = 0;
+    }
     HIP_TRY(launch_prep(pa, s));
     MARK();
 
@@ -317,6 +327,7 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     if (two_planes) { g2.amaxA = AbsMax{nullptr, 0, rowpart, lo.row_parts, T}; g2.amaxB = AbsMax{am_cc, (int)H, nullptr, 0, 0}; }
     g2.C = y; g2.ldc = H; g2.diag = D; g2.E = u; g2.lde = H; g2.epilogue = 1;
     if (gelu_y) { g2.epilogue = 6; g2.C2 = gelu_y; }       // the S5 block: GELU(y) for the gate, same store
+    if (gelu_y && gate_max) g2.c2_rowmax = gate_max->x1_rowmax;
     g2.splits = 1;
     if (lo.jtiles) {
         // too few 128x128 tiles for the chip: two K halves (twice the workgroups, half as long) that meet
@@ -757,7 +768,12 @@ ssm_status ssm_step_bwd(const void *plan, size_t plan_bytes, const float *D, con
 }
 
 namespace {
-struct BlockLayout { size_t ssm, x1, glu, dypre, gate_halves, total; };
+struct BlockLayout {
+    size_t ssm, x1, glu, dypre, gate_halves, total;
+    // forward: the gate's product on two scaled fp16 planes (width a multiple of 64 and an output projection
+    // whose wavefronts own 64 columns): rows of GELU(y) in pieces of 64 columns, pieces of W
+    bool gate_two_planes; size_t x1_rowmax, wslots; int nwslots;
+};
 bool make_block_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, BlockLayout &o)
 {
     Layout lo;
@@ -766,9 +782,16 @@ bool make_block_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, Bl
     size_t off = 0;
     o.ssm = off; off += up(lo.total);
     o.x1 = o.glu = o.dypre = o.gate_halves = 0;
+    o.gate_two_planes = false; o.x1_rowmax = o.wslots = 0; o.nwslots = 0;
     if (!bwd) {
         o.x1 = off; off += TH;
         if (H % 2 == 0 && gemm_out_split_shape(Bt * L, H, H / 2)) { o.gate_halves = off; off += 2 * TH; }   // gate product as two K halves
+        o.gate_two_planes = gate_two_planes_shape(Bt * L, H) && gemm_tile_tier(Bt * L, H, lo.jtiles ? 2 : 1) <= 1;
+        if (o.gate_two_planes) {
+            o.nwslots = pass_pieces((size_t)H * H);
+            o.x1_rowmax = off; off += up((size_t)(H / 64) * Bt * L * 4);
+            o.wslots = off; off += up((size_t)o.nwslots * 4);
+        }
     } else {
         const size_t g = ssm_half_glu_workspace_bytes(Bt * L, H, 1);
         if (g == 0) return false;
@@ -803,8 +826,9 @@ ssm_status ssm_block_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 
     hipStream_t s = static_cast<hipStream_t>(stream);
     float *x1 = reinterpret_cast<float *>(ws + bl.x1);
     // the layer; its output projection also stores x1 = GELU(y)
+    GateMax gm{reinterpret_cast<unsigned *>(ws + bl.x1_rowmax), W, (size_t)H * H, reinterpret_cast<unsigned *>(ws + bl.wslots), bl.nwslots};
     st = run_fwd(Lambda, B, C, D, log_delta, u, is_first, x0, Bt, L, H, P, y, x, x_last, ws + bl.ssm, bl.x1 - bl.ssm, s,
-                 nullptr, x1);
+                 nullptr, x1, bl.gate_two_planes ? &gm : nullptr);
     if (st != SSM_OK) return st;
     // out[t, j] = y[t, j] sigmoid(sum_i x1[t, i] W[i, j])
     GemmArgs g{};
@@ -812,6 +836,10 @@ ssm_status ssm_block_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 
     g.B = W; g.ldb = H; g.b_kcontig = 0;
     g.C = out; g.ldc = H; g.E = y; g.lde = H; g.C2 = gate; g.epilogue = 3;
     g.M = (int)(Bt * L); g.N = (int)H; g.K = (int)H; g.splits = 1;
+    if (bl.gate_two_planes) {
+        g.amaxA = AbsMax{nullptr, 0, gm.x1_rowmax, (int)(H / 64), (long)(Bt * L)};
+        g.amaxB = AbsMax{gm.wslots, gm.nwslots, nullptr, 0, 0};
+    }
     HIP_TRY(launch_gemm_halved(g, bl.gate_halves ? reinterpret_cast<float *>(ws + bl.gate_halves) : nullptr, s));
     return SSM_OK;
 }

@@ -80,7 +80,16 @@ struct GemmArgs {
     ScanEpilogue scan;                               // epilogues 7 and 8
     AbsMax amaxA, amaxB;                             // largest magnitudes of A and B when known
     KJoin join;                                      // splits == 2 with a store function (epilogue 1, 3, 4, 6)
+    unsigned *c2_rowmax;                             // epilogue 6, tile tiers 0 and 1: [ceil(N/64)][M] words, the largest
+                                                     // magnitude of every row of C2 per piece of 64 columns; or null
 };
+// The gate's products stage two scaled fp16 planes per operand (and the passes before them measure the
+// largest magnitudes) at widths that are multiples of 64 from 512 on, with enough tokens that a T x H
+// product runs on tiles whose wavefronts own 64 columns (measured on 4096 tokens: -13 % at H = 1024, even
+// at H = 512; +2 % at 1024 tokens, H = 256, where the passes cost more than the shorter K loops save)
+inline bool gate_two_planes_shape(int64_t T, int64_t H) { return H % 64 == 0 && H >= 512 && ((T + 63) / 64) * ((H + 127) / 128) >= 200; }
+// tile tier launch_gemm picks for an M x N product with `splits` K splits: 0 = 128x128x32 tiles, 1 = 64x128x32, 2 = 64x64x64
+int gemm_tile_tier(int64_t M, int64_t N, int splits);
 // the input projection (epilogue 7) and C^H dy (epilogue 8, the reverse scan of the gradient pass) scan
 // their own output tiles at this shape
 bool gemm_scan_shape_ok(int64_t Bt, int64_t L, int64_t P);

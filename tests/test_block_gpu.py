@@ -59,8 +59,8 @@ def test_lambda_return_extremes_of_lambda():
 
 
 # (T, H): the benchmark shape, ragged tiles, a width that is no multiple of 4 (scalar tails and the
-# guarded GEMM path), the vision width
-GLU_SHAPES = [(4096, 512), (128, 32), (300, 96), (1000, 257), (2048, 1024), (5, 3)]
+# guarded GEMM path), the vision width, ragged token tiles at a width that takes two fp16 planes
+GLU_SHAPES = [(4096, 512), (128, 32), (300, 96), (1000, 257), (2048, 1024), (5, 3), (3333, 576)]
 
 
 @pytest.mark.parametrize("T,H", GLU_SHAPES)
@@ -105,7 +105,9 @@ def test_half_glu_is_bitwise_repeatable():
     assert all(torch.equal(a, b) for a, b in zip(*outs))
 
 
-@pytest.mark.parametrize("Bt,L,H,P", [(16, 256, 512, 512), (3, 129, 50, 33), (2, 600, 96, 40)])
+# the benchmark shape (the K halves of y meet in the launch; the gate on two fp16 planes), two small ragged ones,
+# and one whose output projection runs on 64x128 tiles and hands the gate its row maxima from there
+@pytest.mark.parametrize("Bt,L,H,P", [(16, 256, 512, 512), (3, 129, 50, 33), (2, 600, 96, 40), (8, 512, 512, 64)])
 def test_s5_block_matches_oracle_composition(Bt, L, H, P):
     """SSM layer + half-GLU gate in one call (GELU of the layer's output formed in the output
     projection's store) against the two oracles composed: forward outputs, then every gradient."""
