@@ -967,8 +967,11 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
     }
     if constexpr (BM == 128 && BN == 128 && NC == 4 && (EPI == 1 || EPI == 3 || EPI == 4 || EPI == 6)) {
         if (g.join.tiles) {
-            // Two K halves of one tile meet here.  Split 0 sits in the lower workgroup id of the pair
-            // (placement mode 2), so it is dispatched first and never waits: it hands its accumulators
+            // Two K halves of one tile meet here.  Placement mode 2 puts split 0 on the even XCDs and split 1 on
+            // the odd ones (the pair in neighbouring workgroup ids, split 0 first): the halves that wait and the
+            // halves they wait for never compete for a CU, and split 0 never waits, so every wait ends whatever
+            // else runs on the GPU.  (Both halves of a tile on one XCD were measured: 2.5 us slower per launch,
+            // every XCD then reads all of B.)  Split 0 hands its accumulators
             // over in register order (thread t of the partner reads what thread t wrote: coalesced both
             // ways) with device-scope stores that go through to memory, and raises its wavefront's flag
             // once they have completed.  Split 1 adds them to its own (one fixed order) and stores.
