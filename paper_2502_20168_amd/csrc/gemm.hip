@@ -28,12 +28,11 @@ int gemm_pick_splits(int64_t M, int64_t N, int64_t K, int64_t partner_tiles)
 // A product over T tokens with N columns that has few 128x128 tiles shares its launch with a K = T
 // reduction on 64x64x64 tiles: a quarter of the multiply-adds per workgroup, so that the chain of K
 // steps a small shape waits for is short.
-#ifndef SSM_SMALL_PAIR_ITEMS
-#define SSM_SMALL_PAIR_ITEMS 64
-#endif
+// (measured: 16 and 32 leave gains on the table, 128 doubles the step at 40 x 100 tokens, H = P = 256)
+constexpr int64_t SMALL_PAIR_ITEMS = 64;
 bool gemm_small_pair(int64_t T, int64_t N)
 {
-    return ((T + 127) / 128) * ((N + 127) / 128) <= SSM_SMALL_PAIR_ITEMS;
+    return ((T + 127) / 128) * ((N + 127) / 128) <= SMALL_PAIR_ITEMS;
 }
 
 // K splits of an M x N reduction over K rows that shares such a launch with a product whose K loop is
@@ -84,11 +83,9 @@ bool gemm_scan_shape_ok(int64_t Bt, int64_t L, int64_t P)
     if (!chain && !whole) return false;
     // (measured: from 64 tiles on -- a quarter of the CUs -- the scanning tile with its two fp16 planes beats
     // smaller tiles plus a scan kernel: +2 % at 64 tiles, +7..13 % at 96-128; no difference at 32-48)
-#ifndef SSM_SCAN_MIN_TILES
-#define SSM_SCAN_MIN_TILES 64
-#endif
+    constexpr int64_t SCAN_MIN_TILES = 64;
     const int64_t tiles = (Bt * L / SCAN_TILE) * ((2 * P + SCAN_TILE - 1) / SCAN_TILE);
-    return tiles >= SSM_SCAN_MIN_TILES && tiles * 64 <= 0x7fffffffLL;
+    return tiles >= SCAN_MIN_TILES && tiles * 64 <= 0x7fffffffLL;
 }
 
 // argument checks shared by the two scanning epilogues

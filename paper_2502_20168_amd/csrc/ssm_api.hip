@@ -74,9 +74,7 @@ namespace {
 constexpr size_t ALIGN = 256;
 inline size_t up(size_t v) { return (v + ALIGN - 1) / ALIGN * ALIGN; }
 
-#ifndef SSM_SMALL_HALVES_MIN_P
-#define SSM_SMALL_HALVES_MIN_P 256
-#endif
+constexpr int64_t SMALL_HALVES_MIN_P = 256;      // a small du as two K halves: each half keeps four K steps of 64
 struct Layout {
     ScanPlan plan;
     int splitC, splitB, nslab;
@@ -134,7 +132,7 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
             o.splitC = gemm_pick_splits_small(H, 2 * P, (int64_t)T, rows64 * ((2 * P + 63) / 64), H);
         if (gemm_small_pair((int64_t)T, H)) {
             // (measured: a gain when both halves keep four K steps and fit one round of workgroups with room for the slabs)
-            du_small_halves = bwd && P >= SSM_SMALL_HALVES_MIN_P && 2 * rows64 * ((H + 63) / 64) <= 256;
+            du_small_halves = bwd && P >= SMALL_HALVES_MIN_P && 2 * rows64 * ((H + 63) / 64) <= 256;
             o.splitB = du_small_halves ? gemm_pick_splits_small(2 * P, H, (int64_t)T, 2 * rows64 * ((H + 63) / 64), P)
                                        : gemm_pick_splits_small(2 * P, H, (int64_t)T, rows64 * ((H + 63) / 64), 2 * P);
         }
