@@ -386,18 +386,39 @@ hipError_t launch_clear(WsHeader *hdr, void *scratch, size_t scratch_bytes, hipS
     return hipGetLastError();
 }
 
-__global__ void __launch_bounds__(256) reduce_partials_kernel(const float2 *partial, long n, long P, float2 *out)
+// out[p] = sum_i partial[i * P + p] in one fixed order: a workgroup owns 64 states, its four wavefronts
+// take the rows i = w, w + 4, ... (eight loads in flight each), and the four sums are added in order.
+__global__ void __launch_bounds__(256) reduce_partials_kernel(const float2 *__restrict__ partial, long n, long P,
+                                                              float2 *__restrict__ out)
 {
-    const long p = (long)blockIdx.x * 256 + threadIdx.x;
-    if (p >= P) return;
+    __shared__ float2 part[4][64];
+    const int w = threadIdx.x >> 6, l = threadIdx.x & 63;
+    const long p = (long)blockIdx.x * 64 + l;
     float2 s = make_float2(0.f, 0.f);
-    for (long i = 0; i < n; ++i) { s.x += partial[i * P + p].x; s.y += partial[i * P + p].y; }
-    out[p] = s;
+    if (p < P) {
+        long i = w;
+        for (; i + 28 < n; i += 32) {
+            float2 v[8];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) v[k] = partial[(i + 4 * k) * P + p];
+#pragma unroll
+            for (int k = 0; k < 8; ++k) { s.x += v[k].x; s.y += v[k].y; }
+        }
+        for (; i < n; i += 4) { const float2 v = partial[i * P + p]; s.x += v.x; s.y += v.y; }
+    }
+    part[w][l] = s;
+    __syncthreads();
+    if (w == 0 && p < P) {
+        float2 t = part[0][l];
+#pragma unroll
+        for (int k = 1; k < 4; ++k) { t.x += part[k][l].x; t.y += part[k][l].y; }
+        out[p] = t;
+    }
 }
 
 hipError_t launch_reduce_partials(const float2 *partial, int64_t n, int64_t P, float2 *out, hipStream_t s)
 {
-    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((P + 255) / 256)), dim3(256), 0, s,
+    hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((P + 63) / 64)), dim3(256), 0, s,
                        partial, (long)n, (long)P, out);
     return hipGetLastError();
 }
