@@ -50,6 +50,28 @@ int gemm_pick_splits_small(int64_t M, int64_t N, int64_t K, int64_t partner_tile
     return (int)s;
 }
 
+// K splits of an M x N reduction over K rows that shares a launch of 128x128x32 tiles with a product of
+// main_tiles tiles whose K loop is k_main long: work items about as long as that product's (so that no
+// item outlasts the rest of the launch), and among the counts near that the one whose rounds of
+// workgroups on the 256 CUs, times the longer kind of item, come out shortest.
+int gemm_pick_splits_balanced(int64_t M, int64_t N, int64_t K, int64_t main_tiles, int64_t k_main)
+{
+    const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
+    const int64_t a = (k_main + 31) / 32;
+    int64_t maxs = K / 256;
+    maxs = maxs > 64 ? 64 : (maxs < 1 ? 1 : maxs);
+    int64_t sp0 = (K + k_main / 2) / (k_main < 32 ? 32 : k_main);
+    sp0 = sp0 > maxs ? maxs : (sp0 < 1 ? 1 : sp0);
+    int64_t best = sp0, best_est = -1;
+    for (int64_t sp = sp0 > 2 ? sp0 - 2 : 1; sp <= sp0 + 2 && sp <= maxs; ++sp) {
+        const int64_t b = ((K + sp - 1) / sp + 31) / 32;
+        const int64_t rounds = (main_tiles + tiles * sp + 255) / 256;
+        const int64_t est = rounds * (a > b ? a : b);
+        if (best_est < 0 || est < best_est) { best = sp; best_est = est; }
+    }
+    return (int)best;
+}
+
 // Layout code of a problem, or -1 when the projection kernel has no instantiation for it.
 int gemm_layout_of(const GemmArgs &a)
 {

@@ -127,6 +127,13 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
     } else {
         o.splitC = gemm_pick_splits(H, 2 * P, (int64_t)T, rows128 * ((2 * P + 127) / 128));   // shares C^H dy's launch
         o.splitB = gemm_pick_splits(2 * P, H, (int64_t)T, rows128 * ((H + 127) / 128));       // shares Bbar^H chi's launch
+        if (!gemm_scan_shape_ok(Bt, L, P)) {
+            // separate scan kernels: a launch of two products with several rounds of work items
+            o.splitC = gemm_pick_splits_balanced(H, 2 * P, (int64_t)T, rows128 * ((2 * P + 127) / 128), H);
+            const bool du_halves = gemm_out_split_shape((int64_t)T, H, P);     // du as two K halves (see yhalves below)
+            o.splitB = gemm_pick_splits_balanced(2 * P, H, (int64_t)T, rows128 * ((H + 127) / 128) * (du_halves ? 2 : 1),
+                                                 du_halves ? P : 2 * P);
+        }
         const int64_t rows64 = ((int64_t)T + 63) / 64;
         if (gemm_small_pair((int64_t)T, 2 * P))
             o.splitC = gemm_pick_splits_small(H, 2 * P, (int64_t)T, rows64 * ((2 * P + 63) / 64), H);
@@ -435,8 +442,8 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
         if (lo.dc_early) { g4.amaxA = mx_dy; g4.amaxB = mx_x; HIP_TRY(launch_gemm_pair(g3, g4, s)); }
         else HIP_TRY(launch_gemm(g3, s));
     } else {
-        // dC needs only dy and the saved states: it shares the launch
-        HIP_TRY(launch_gemm_pair(g3, g4, s));
+        // dC needs only dy and the saved states: it shares the launch (the longer kind of work item first)
+        HIP_TRY(launch_gemm_pair(g3, g4, s, (T + lo.splitC - 1) / lo.splitC > H));
     }
     MARK();
 
@@ -477,7 +484,11 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
         g5.C = du; g5.ldc = H; g5.diag = D; g5.E = dy; g5.lde = H; g5.epilogue = 1; g5.splits = 1;
     }
     if (fused && !lo.dc_early) HIP_TRY(launch_gemm_triple(g5, g6, g4, s));   // three products, two workgroups per CU
-    else HIP_TRY(launch_gemm_pair(g5, g6, s, lo.yhalves != 0));              // (two K halves: the long work items of the slabs first)
+    else {
+        // (the longer kind of work item first: the slabs when du runs as two K halves or their K range is the longer one)
+        const int64_t k_du = lo.yhalves ? P : 2 * P;
+        HIP_TRY(launch_gemm_pair(g5, g6, s, lo.yhalves != 0 || (!fused && (T + lo.splitB - 1) / lo.splitB > k_du)));
+    }
     MARK();
     MARK();
 
