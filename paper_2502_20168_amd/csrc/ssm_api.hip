@@ -82,6 +82,7 @@ struct Layout {
     // the largest magnitude of the saved states from a pass of the prep launch); otherwise they wait for the
     // launch of Re(Bbar^H chi), and the reverse scan records that magnitude on its way
     bool dc_early;
+    bool slabs_first;        // launch of three products: the slabs' work items are the longer kind and go first
     size_t hdr, lam, Bri, Cc, xbuf, chi, ticket, desc, dCpart, dBpart, dApart, dDpart, fdesc, fdesc_bytes, yhalves, total;
     // forward pass, output projection with too few tiles for the chip: two K halves that meet inside the launch
     // (flags directly behind fdesc, so that one range is cleared; partial tiles)
@@ -94,6 +95,58 @@ struct Layout {
     // rowpart [ceil(2P/128), T] (x forward, chi gradient pass: one word per column tile of the scanning projection)
     size_t rowmax, rowpart; int row_parts;
 };
+
+// Longest-first list scheduling of nl work items of l K tiles and then ns items of s <= l K tiles on the
+// 256 CUs (a CU's two workgroups share its throughput, so a CU is one machine): the K tiles the busiest
+// CU ends up with.  Loads are kept as (level, number of CUs) pairs; a batch of items goes to all CUs of
+// the lowest level at once.
+int64_t lpt_makespan(int64_t nl, int64_t l, int64_t ns, int64_t s)
+{
+    constexpr int64_t CUS = 256;
+    constexpr int MAXLV = 16;
+    int64_t lv[MAXLV], cnt[MAXLV];
+    int n = 0;
+    const int64_t q = nl / CUS, r = nl % CUS;
+    lv[n] = q * l; cnt[n] = CUS - r; ++n;                    // ascending levels
+    if (r) { lv[n] = (q + 1) * l; cnt[n] = r; ++n; }
+    while (ns > 0) {
+        const int64_t k = cnt[0] < ns ? cnt[0] : ns;
+        const int64_t target = lv[0] + s;
+        ns -= k;
+        cnt[0] -= k;
+        if (cnt[0] == 0) { for (int i = 1; i < n; ++i) { lv[i - 1] = lv[i]; cnt[i - 1] = cnt[i]; } --n; }
+        int pos = 0;
+        while (pos < n && lv[pos] < target) ++pos;
+        if (pos < n && lv[pos] == target) { cnt[pos] += k; continue; }
+        if (n == MAXLV) { lv[n - 1] = lv[n - 1] > target ? lv[n - 1] : target; cnt[n - 1] += k; continue; }   // (never with two item lengths)
+        for (int i = n; i > pos; --i) { lv[i] = lv[i - 1]; cnt[i] = cnt[i - 1]; }
+        lv[pos] = target; cnt[pos] = k; ++n;
+    }
+    return lv[n - 1];
+}
+
+// K splits of the two K = T reductions that share the launch of du (shapes whose projections scan their
+// own tiles, more scanning tiles than 192): the count that minimises the busiest CU's K tiles plus what
+// every further pair of slabs costs (their bytes are written by that launch and read by the epilogue's:
+// measured 1.4 us, about 1.4 K tiles, per split at 2 MiB per slab).  slabs_first: their work items are
+// the longer kind and take the first slots of the launch.
+int pick_triple_splits(int64_t T, int64_t H, int64_t P, bool &slabs_first)
+{
+    static const int cand[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64};
+    const int64_t n_du = ((T + 127) / 128) * ((H + 127) / 128), a = (2 * P + 31) / 32;
+    const int64_t slab_tiles = 2 * ((2 * P + 127) / 128) * ((H + 127) / 128);
+    const double per_split = 0.2 + 1.2 * (double)(2 * P * H * 4) / (double)(2 << 20);
+    int best = 1;
+    double best_cost = -1.0;
+    for (int sp : cand) {
+        if (sp > 1 && sp > T / 256) break;
+        const int64_t b = (((T + sp - 1) / sp) + 31) / 32;
+        const int64_t m = b > a ? lpt_makespan(slab_tiles * sp, b, n_du, a) : lpt_makespan(n_du, a, slab_tiles * sp, b);
+        const double cost = (double)m + per_split * sp;
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = sp; slabs_first = b > a; }
+    }
+    return best;
+}
 
 ssm_status check_dims(int64_t Bt, int64_t L, int64_t H, int64_t P)
 {
@@ -114,16 +167,11 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
     if (o.plan.nblocks > 0x7fffffffLL) return SSM_ERR_UNSUPPORTED;
     const int64_t rows128 = ((int64_t)T + 127) / 128;
     bool du_small_halves = false;     // a small du on 64x64x64 tiles as two K halves (summed in the parameter epilogue's launch)
+    o.slabs_first = false;
     o.dc_early = gemm_scan_shape_ok(Bt, L, P) && rows128 * ((2 * P + 127) / 128) <= 192;
     if (gemm_scan_shape_ok(Bt, L, P) && !o.dc_early) {
-        // dy^T x and chi^T u share the launch of Re(Bbar^H chi): K splits that make their work items as
-        // long as that product's (its whole K = 2P, or one K half), at least 256 rows each
-        const int64_t k_du = gemm_out_split_shape((int64_t)T, H, P) ? P : 2 * P;      // (half of K where the product has few tiles)
-        int64_t sp = ((int64_t)T + k_du / 2) / k_du;
-        const int64_t maxs = ((int64_t)T + 255) / 256;
-        sp = sp > maxs ? maxs : sp;
-        sp = sp > 64 ? 64 : (sp < 1 ? 1 : sp);
-        o.splitC = o.splitB = (int)sp;
+        // dy^T x and chi^T u share the launch of Re(Bbar^H chi)
+        o.splitC = o.splitB = pick_triple_splits((int64_t)T, H, P, o.slabs_first);
     } else {
         o.splitC = gemm_pick_splits(H, 2 * P, (int64_t)T, rows128 * ((2 * P + 127) / 128));   // shares C^H dy's launch
         o.splitB = gemm_pick_splits(2 * P, H, (int64_t)T, rows128 * ((H + 127) / 128));       // shares Bbar^H chi's launch
@@ -483,7 +531,7 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     } else {
         g5.C = du; g5.ldc = H; g5.diag = D; g5.E = dy; g5.lde = H; g5.epilogue = 1; g5.splits = 1;
     }
-    if (fused && !lo.dc_early) HIP_TRY(launch_gemm_triple(g5, g6, g4, s));   // three products, two workgroups per CU
+    if (fused && !lo.dc_early) HIP_TRY(launch_gemm_triple(g5, g6, g4, s, lo.slabs_first));   // three products, two workgroups per CU
     else {
         // (the longer kind of work item first: the slabs when du runs as two K halves or their K range is the longer one)
         const int64_t k_du = lo.yhalves ? P : 2 * P;

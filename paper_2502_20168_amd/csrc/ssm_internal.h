@@ -113,7 +113,8 @@ hipError_t launch_gemm_halved(const GemmArgs &g, float *halves, hipStream_t s);
 // paired instantiation)
 hipError_t launch_gemm_pair(const GemmArgs &a, const GemmArgs &b, hipStream_t s, bool second_first = false);
 // three independent problems in one launch: a product over the state dimension and two K = T reductions
-hipError_t launch_gemm_triple(const GemmArgs &a, const GemmArgs &b, const GemmArgs &c, hipStream_t s);
+// (slabs_first: b and c take the first slots of the launch, a the last)
+hipError_t launch_gemm_triple(const GemmArgs &a, const GemmArgs &b, const GemmArgs &c, hipStream_t s, bool slabs_first = false);
 // number of K splits for a reduction over K rows with an M x N result that shares its launch
 // with a product of partner_tiles 128x128 tiles
 int gemm_pick_splits(int64_t M, int64_t N, int64_t K, int64_t partner_tiles);
