@@ -50,26 +50,69 @@ int gemm_pick_splits_small(int64_t M, int64_t N, int64_t K, int64_t partner_tile
     return (int)s;
 }
 
-// K splits of an M x N reduction over K rows that shares a launch of 128x128x32 tiles with a product of
-// main_tiles tiles whose K loop is k_main long: work items about as long as that product's (so that no
-// item outlasts the rest of the launch), and among the counts near that the one whose rounds of
-// workgroups on the 256 CUs, times the longer kind of item, come out shortest.
-int gemm_pick_splits_balanced(int64_t M, int64_t N, int64_t K, int64_t main_tiles, int64_t k_main)
+// List scheduling of nl work items of l K tiles and then ns items of s K tiles on the 256 CUs, as the
+// dispatcher hands out workgroups in slot order to CUs as they fall free (a CU's two workgroups share its
+// throughput, so a CU is one machine): the K tiles the busiest CU ends up with.  Loads are kept as (level, number of CUs) pairs; a batch of items goes to all CUs of
+// the lowest level at once.
+int64_t lpt_makespan(int64_t nl, int64_t l, int64_t ns, int64_t s)
 {
-    const int64_t tiles = ((M + 127) / 128) * ((N + 127) / 128);
-    const int64_t a = (k_main + 31) / 32;
-    int64_t maxs = K / 256;
-    maxs = maxs > 64 ? 64 : (maxs < 1 ? 1 : maxs);
-    int64_t sp0 = (K + k_main / 2) / (k_main < 32 ? 32 : k_main);
-    sp0 = sp0 > maxs ? maxs : (sp0 < 1 ? 1 : sp0);
-    int64_t best = sp0, best_est = -1;
-    for (int64_t sp = sp0 > 2 ? sp0 - 2 : 1; sp <= sp0 + 2 && sp <= maxs; ++sp) {
-        const int64_t b = ((K + sp - 1) / sp + 31) / 32;
-        const int64_t rounds = (main_tiles + tiles * sp + 255) / 256;
-        const int64_t est = rounds * (a > b ? a : b);
-        if (best_est < 0 || est < best_est) { best = sp; best_est = est; }
+    constexpr int64_t CUS = 256;
+    constexpr int MAXLV = 16;
+    int64_t lv[MAXLV], cnt[MAXLV];
+    int n = 0;
+    const int64_t q = nl / CUS, r = nl % CUS;
+    lv[n] = q * l; cnt[n] = CUS - r; ++n;                    // ascending levels
+    if (r) { lv[n] = (q + 1) * l; cnt[n] = r; ++n; }
+    while (ns > 0) {
+        const int64_t k = cnt[0] < ns ? cnt[0] : ns;
+        const int64_t target = lv[0] + s;
+        ns -= k;
+        cnt[0] -= k;
+        if (cnt[0] == 0) { for (int i = 1; i < n; ++i) { lv[i - 1] = lv[i]; cnt[i - 1] = cnt[i]; } --n; }
+        int pos = 0;
+        while (pos < n && lv[pos] < target) ++pos;
+        if (pos < n && lv[pos] == target) { cnt[pos] += k; continue; }
+        if (n == MAXLV) { lv[n - 1] = lv[n - 1] > target ? lv[n - 1] : target; cnt[n - 1] += k; continue; }   // (never with two item lengths)
+        for (int i = n; i > pos; --i) { lv[i] = lv[i - 1]; cnt[i] = cnt[i - 1]; }
+        lv[pos] = target; cnt[pos] = k; ++n;
     }
-    return (int)best;
+    return lv[n - 1];
+}
+
+// K splits of the K = T reductions (red_tiles tiles of 128x128 in all, split_bytes of slabs per split in
+// all) that share a launch of 128x128x32 tiles with a product of main_tiles tiles whose K loop is k_main
+// long: the count that minimises the busiest CU's K tiles plus what every further set of slabs costs (their
+// bytes are written by this launch and read by the parameter epilogue's: measured 1.4 us, about 1.4 K
+// tiles, per split of two reductions with 2 MiB slabs).  red_first: the reductions' work items belong in the
+// first slots of the launch.  One workgroup per CU: whichever order the schedule model finishes earlier,
+// the product first on a tie (measured on ten shapes with separate scan kernels: the model's choice was
+// the faster order on every one, by up to 5 % of the step).  Two workgroups per CU: the reductions first
+// when their items are at least twice as long as the product's (then a CU holds one of each kind for most
+// of the launch instead of ending on single long items; 1024 x 16 tokens, H = P = 512: 0.469 against 0.482 ms).
+int gemm_pick_splits_model(int64_t T, int64_t main_tiles, int64_t k_main, int64_t red_tiles, size_t split_bytes, bool two_per_cu,
+                           bool &red_first)
+{
+    static const int cand[] = {1, 2, 3, 4, 5, 6, 8, 10, 12, 16, 24, 32, 48, 64};
+    const int64_t a = (k_main + 31) / 32;
+    const double per_split = 0.2 + 0.6 * (double)split_bytes / (double)(2 << 20);
+    int best = 1;
+    double best_cost = -1.0;
+    red_first = false;
+    for (int sp : cand) {
+        if (sp > 1 && sp > T / 256) break;
+        const int64_t b = (((T + sp - 1) / sp) + 31) / 32;
+        const int64_t m_main = lpt_makespan(main_tiles, a, red_tiles * sp, b), m_red = lpt_makespan(red_tiles * sp, b, main_tiles, a);
+        const int64_t m = m_red < m_main ? m_red : m_main;
+        const double cost = (double)m + per_split * sp;
+        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = sp; red_first = two_per_cu ? b >= 2 * a : m_red < m_main; }
+    }
+    return best;
+}
+
+// (one reduction of M x N over K rows beside a product of main_tiles tiles, one workgroup per CU)
+int gemm_pick_splits_balanced(int64_t M, int64_t N, int64_t K, int64_t main_tiles, int64_t k_main, bool &red_first)
+{
+    return gemm_pick_splits_model(K, main_tiles, k_main, ((M + 127) / 128) * ((N + 127) / 128), (size_t)M * N * 4, false, red_first);
 }
 
 // Layout code of a problem, or -1 when the projection kernel has no instantiation for it.

@@ -82,7 +82,8 @@ struct Layout {
     // the largest magnitude of the saved states from a pass of the prep launch); otherwise they wait for the
     // launch of Re(Bbar^H chi), and the reverse scan records that magnitude on its way
     bool dc_early;
-    bool slabs_first;        // launch of three products: the slabs' work items are the longer kind and go first
+    bool slabs_first;        // launch of three products: the slabs' work items go first
+    bool dc_first, db_first; // launches of two products (separate scan kernels): the slab items go first
     size_t hdr, lam, Bri, Cc, xbuf, chi, ticket, desc, dCpart, dBpart, dApart, dDpart, fdesc, fdesc_bytes, yhalves, total;
     // forward pass, output projection with too few tiles for the chip: two K halves that meet inside the launch
     // (flags directly behind fdesc, so that one range is cleared; partial tiles)
@@ -96,56 +97,14 @@ struct Layout {
     size_t rowmax, rowpart; int row_parts;
 };
 
-// Longest-first list scheduling of nl work items of l K tiles and then ns items of s <= l K tiles on the
-// 256 CUs (a CU's two workgroups share its throughput, so a CU is one machine): the K tiles the busiest
-// CU ends up with.  Loads are kept as (level, number of CUs) pairs; a batch of items goes to all CUs of
-// the lowest level at once.
-int64_t lpt_makespan(int64_t nl, int64_t l, int64_t ns, int64_t s)
-{
-    constexpr int64_t CUS = 256;
-    constexpr int MAXLV = 16;
-    int64_t lv[MAXLV], cnt[MAXLV];
-    int n = 0;
-    const int64_t q = nl / CUS, r = nl % CUS;
-    lv[n] = q * l; cnt[n] = CUS - r; ++n;                    // ascending levels
-    if (r) { lv[n] = (q + 1) * l; cnt[n] = r; ++n; }
-    while (ns > 0) {
-        const int64_t k = cnt[0] < ns ? cnt[0] : ns;
-        const int64_t target = lv[0] + s;
-        ns -= k;
-        cnt[0] -= k;
-        if (cnt[0] == 0) { for (int i = 1; i < n; ++i) { lv[i - 1] = lv[i]; cnt[i - 1] = cnt[i]; } --n; }
-        int pos = 0;
-        while (pos < n && lv[pos] < target) ++pos;
-        if (pos < n && lv[pos] == target) { cnt[pos] += k; continue; }
-        if (n == MAXLV) { lv[n - 1] = lv[n - 1] > target ? lv[n - 1] : target; cnt[n - 1] += k; continue; }   // (never with two item lengths)
-        for (int i = n; i > pos; --i) { lv[i] = lv[i - 1]; cnt[i] = cnt[i - 1]; }
-        lv[pos] = target; cnt[pos] = k; ++n;
-    }
-    return lv[n - 1];
-}
-
 // K splits of the two K = T reductions that share the launch of du (shapes whose projections scan their
-// own tiles, more scanning tiles than 192): the count that minimises the busiest CU's K tiles plus what
-// every further pair of slabs costs (their bytes are written by that launch and read by the epilogue's:
-// measured 1.4 us, about 1.4 K tiles, per split at 2 MiB per slab).  slabs_first: their work items are
-// the longer kind and take the first slots of the launch.
+// own tiles, more scanning tiles than 192), two workgroups per CU; slabs_first: their work items take the
+// first slots of the launch.
 int pick_triple_splits(int64_t T, int64_t H, int64_t P, bool &slabs_first)
 {
-    static const int cand[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64};
-    const int64_t n_du = ((T + 127) / 128) * ((H + 127) / 128), a = (2 * P + 31) / 32;
+    const int64_t n_du = ((T + 127) / 128) * ((H + 127) / 128);
     const int64_t slab_tiles = 2 * ((2 * P + 127) / 128) * ((H + 127) / 128);
-    const double per_split = 0.2 + 1.2 * (double)(2 * P * H * 4) / (double)(2 << 20);
-    int best = 1;
-    double best_cost = -1.0;
-    for (int sp : cand) {
-        if (sp > 1 && sp > T / 256) break;
-        const int64_t b = (((T + sp - 1) / sp) + 31) / 32;
-        const int64_t m = b > a ? lpt_makespan(slab_tiles * sp, b, n_du, a) : lpt_makespan(n_du, a, slab_tiles * sp, b);
-        const double cost = (double)m + per_split * sp;
-        if (best_cost < 0 || cost < best_cost) { best_cost = cost; best = sp; slabs_first = b > a; }
-    }
-    return best;
+    return gemm_pick_splits_model(T, n_du, 2 * P, slab_tiles, (size_t)2 * 2 * P * H * 4, true, slabs_first);
 }
 
 ssm_status check_dims(int64_t Bt, int64_t L, int64_t H, int64_t P)
@@ -167,7 +126,7 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
     if (o.plan.nblocks > 0x7fffffffLL) return SSM_ERR_UNSUPPORTED;
     const int64_t rows128 = ((int64_t)T + 127) / 128;
     bool du_small_halves = false;     // a small du on 64x64x64 tiles as two K halves (summed in the parameter epilogue's launch)
-    o.slabs_first = false;
+    o.slabs_first = o.dc_first = o.db_first = false;
     o.dc_early = gemm_scan_shape_ok(Bt, L, P) && rows128 * ((2 * P + 127) / 128) <= 192;
     if (gemm_scan_shape_ok(Bt, L, P) && !o.dc_early) {
         // dy^T x and chi^T u share the launch of Re(Bbar^H chi)
@@ -177,10 +136,10 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
         o.splitB = gemm_pick_splits(2 * P, H, (int64_t)T, rows128 * ((H + 127) / 128));       // shares Bbar^H chi's launch
         if (!gemm_scan_shape_ok(Bt, L, P)) {
             // separate scan kernels: a launch of two products with several rounds of work items
-            o.splitC = gemm_pick_splits_balanced(H, 2 * P, (int64_t)T, rows128 * ((2 * P + 127) / 128), H);
+            o.splitC = gemm_pick_splits_balanced(H, 2 * P, (int64_t)T, rows128 * ((2 * P + 127) / 128), H, o.dc_first);
             const bool du_halves = gemm_out_split_shape((int64_t)T, H, P);     // du as two K halves (see yhalves below)
             o.splitB = gemm_pick_splits_balanced(2 * P, H, (int64_t)T, rows128 * ((H + 127) / 128) * (du_halves ? 2 : 1),
-                                                 du_halves ? P : 2 * P);
+                                                 du_halves ? P : 2 * P, o.db_first);
         }
         const int64_t rows64 = ((int64_t)T + 63) / 64;
         if (gemm_small_pair((int64_t)T, 2 * P))
@@ -490,8 +449,8 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
         if (lo.dc_early) { g4.amaxA = mx_dy; g4.amaxB = mx_x; HIP_TRY(launch_gemm_pair(g3, g4, s)); }
         else HIP_TRY(launch_gemm(g3, s));
     } else {
-        // dC needs only dy and the saved states: it shares the launch (the longer kind of work item first)
-        HIP_TRY(launch_gemm_pair(g3, g4, s, (T + lo.splitC - 1) / lo.splitC > H));
+        // dC needs only dy and the saved states: it shares the launch (whichever kind of work item the schedule model puts first)
+        HIP_TRY(launch_gemm_pair(g3, g4, s, lo.dc_first));
     }
     MARK();
 
@@ -533,9 +492,8 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     }
     if (fused && !lo.dc_early) HIP_TRY(launch_gemm_triple(g5, g6, g4, s, lo.slabs_first));   // three products, two workgroups per CU
     else {
-        // (the longer kind of work item first: the slabs when du runs as two K halves or their K range is the longer one)
-        const int64_t k_du = lo.yhalves ? P : 2 * P;
-        HIP_TRY(launch_gemm_pair(g5, g6, s, lo.yhalves != 0 || (!fused && (T + lo.splitB - 1) / lo.splitB > k_du)));
+        // (the slabs first when du runs as two K halves, or where the schedule model says so)
+        HIP_TRY(launch_gemm_pair(g5, g6, s, lo.yhalves != 0 || (!fused && lo.db_first)));
     }
     MARK();
     MARK();

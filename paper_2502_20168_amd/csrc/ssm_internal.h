@@ -118,9 +118,13 @@ hipError_t launch_gemm_triple(const GemmArgs &a, const GemmArgs &b, const GemmAr
 // number of K splits for a reduction over K rows with an M x N result that shares its launch
 // with a product of partner_tiles 128x128 tiles
 int gemm_pick_splits(int64_t M, int64_t N, int64_t K, int64_t partner_tiles);
-// the same for launches of several rounds of work items: items about as long as the partner product's
-// (main_tiles tiles, K loop of k_main), fewest rounds
-int gemm_pick_splits_balanced(int64_t M, int64_t N, int64_t K, int64_t main_tiles, int64_t k_main);
+// the same for launches of several rounds of work items (a schedule model of the launch; red_first: the
+// reduction's work items belong in the first slots); the model behind it: reductions over T rows with red_tiles
+// tiles of 128x128 in all (split_bytes of slabs per split in all) beside a product of main_tiles tiles with a
+// K loop of k_main, one or two workgroups per CU
+int gemm_pick_splits_balanced(int64_t M, int64_t N, int64_t K, int64_t main_tiles, int64_t k_main, bool &red_first);
+int gemm_pick_splits_model(int64_t T, int64_t main_tiles, int64_t k_main, int64_t red_tiles, size_t split_bytes, bool two_per_cu,
+                           bool &red_first);
 // a product over T tokens with N columns has so few tiles that it and the reduction in its launch run on
 // 64x64x64 tiles; the K splits of that reduction (partner_tiles64: the product's 64x64 tiles, k_main: its K)
 bool gemm_small_pair(int64_t T, int64_t N);
