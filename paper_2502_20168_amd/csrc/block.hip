@@ -99,10 +99,14 @@ __global__ void __launch_bounds__(256) gelu_kernel(const float4 *__restrict__ u,
     if (i < 4 && j < n) x1t[j] = gelu_exact(ut[j]);
 }
 
-// x1 = GELU(u) and dz = dy u s (1 - s) in one pass (s = the gate saved by the forward call)
+// One pass over the inputs of the gate's adjoint (s = the gate saved by the forward call): x1 = GELU(u) and
+// dz = dy u s (1 - s), the operands of the two products, and the two terms that the store of dz W^T needs,
+// ds = dy s and gd = GELU'(u) (du = ds + (dz W^T) gd): formed here, where u, s and dy pass anyway, they cost
+// that store two loads per value and no error function.
 __global__ void __launch_bounds__(256) gate_bwd_prep_kernel(const float *__restrict__ u, const float *__restrict__ s,
                                                             const float *__restrict__ dy, float *__restrict__ x1,
-                                                            float *__restrict__ dz, long n)
+                                                            float *__restrict__ dz, float *__restrict__ ds,
+                                                            float *__restrict__ gd, long n)
 {
     const long i0 = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
     if (i0 + 4 <= n) {
@@ -114,10 +118,15 @@ __global__ void __launch_bounds__(256) gate_bwd_prep_kernel(const float *__restr
         *reinterpret_cast<float4 *>(dz + i0) =
             make_float4(d.x * a.x * (g.x * (1.f - g.x)), d.y * a.y * (g.y * (1.f - g.y)),
                         d.z * a.z * (g.z * (1.f - g.z)), d.w * a.w * (g.w * (1.f - g.w)));
+        *reinterpret_cast<float4 *>(ds + i0) = make_float4(d.x * g.x, d.y * g.y, d.z * g.z, d.w * g.w);
+        *reinterpret_cast<float4 *>(gd + i0) =
+            make_float4(gelu_derivative(a.x), gelu_derivative(a.y), gelu_derivative(a.z), gelu_derivative(a.w));
     } else {
         for (long i = i0; i < n; ++i) {
             x1[i] = gelu_exact(u[i]);
             dz[i] = dy[i] * u[i] * (s[i] * (1.f - s[i]));
+            ds[i] = dy[i] * s[i];
+            gd[i] = gelu_derivative(u[i]);
         }
     }
 }
@@ -187,7 +196,8 @@ __global__ void __launch_bounds__(256) gelu_max_kernel(const float4 *__restrict_
 
 __global__ void __launch_bounds__(256) gate_bwd_prep_max_kernel(const float *__restrict__ u, const float *__restrict__ s,
                                                                 const float *__restrict__ dy, float *__restrict__ x1,
-                                                                float *__restrict__ dz, long n, int H, long T,
+                                                                float *__restrict__ dz, float *__restrict__ ds,
+                                                                float *__restrict__ gd, long n, int H, long T,
                                                                 unsigned *__restrict__ dz_rowmax,
                                                                 unsigned *__restrict__ x1_slots, unsigned *__restrict__ dz_slots,
                                                                 const float *__restrict__ W, long nW,
@@ -222,6 +232,9 @@ __global__ void __launch_bounds__(256) gate_bwd_prep_max_kernel(const float *__r
                                               d[k].z * a[k].z * (g[k].z * (1.f - g[k].z)), d[k].w * a[k].w * (g[k].w * (1.f - g[k].w)));
                 *reinterpret_cast<float4 *>(x1 + i0) = xo;
                 *reinterpret_cast<float4 *>(dz + i0) = zo;
+                *reinterpret_cast<float4 *>(ds + i0) = make_float4(d[k].x * g[k].x, d[k].y * g[k].y, d[k].z * g[k].z, d[k].w * g[k].w);
+                *reinterpret_cast<float4 *>(gd + i0) =
+                    make_float4(gelu_derivative(a[k].x), gelu_derivative(a[k].y), gelu_derivative(a[k].z), gelu_derivative(a[k].w));
                 const unsigned bz = abs_bits4(zo);
                 mx = max(mx, abs_bits4(xo)); mz = max(mz, bz);
                 const unsigned piece = max16(bz);
@@ -252,9 +265,10 @@ __global__ void __launch_bounds__(256) sum_slabs_kernel(const float *__restrict_
 constexpr int GLU_MAX_SLOTS = 512;      // workgroups of the element-wise pass that report a maximum each
 constexpr int GLU_W_BLOCKS = 256;       // workgroups that measure W
 struct GluLayout {
-    size_t x1, dz, dWpart, halves, total; int splits;
+    size_t x1, dz, ds, gd, dWpart, halves, total; int splits;
     // widths that are multiples of 64: two scaled fp16 planes per operand, with their largest magnitudes
     bool two_planes; size_t rowmax, slots; int row_parts, main_blocks;
+    bool paired, dw_first;     // gradient pass: dz W^T and the slabs of x1^T dz in one launch (dW's work items first)
 };
 
 bool make_glu_layout(int64_t T, int64_t H, bool bwd, GluLayout &o)
@@ -262,16 +276,23 @@ bool make_glu_layout(int64_t T, int64_t H, bool bwd, GluLayout &o)
     if (T <= 0 || H <= 0 || H > SSM_MAX_WIDTH || T > SSM_MAX_TOKENS || T > SSM_MAX_ELEMS / H) return false;
     size_t off = 0;
     o.x1 = off; off += up((size_t)T * H * 4);
-    o.dz = o.dWpart = o.halves = 0; o.splits = 1;
-    if (gemm_out_split_shape(T, H, H / 2) && H % 2 == 0) {      // the gate products as two K halves
+    o.dz = o.ds = o.gd = o.dWpart = o.halves = 0; o.splits = 1;
+    o.two_planes = gate_two_planes_shape(T, H);
+    // gradient pass on two planes: both products wait for the same element-wise pass and share one launch, the
+    // K splits of the reduction from the schedule model of that launch (no K halves of du then: the slabs
+    // fill the chip beside it)
+    o.paired = bwd && o.two_planes; o.dw_first = false;
+    if (!o.paired && gemm_out_split_shape(T, H, H / 2) && H % 2 == 0) {      // the gate products as two K halves
         o.halves = off; off += up((size_t)2 * T * H * 4);
     }
     if (bwd) {
         o.dz = off; off += up((size_t)T * H * 4);
-        o.splits = gemm_pick_splits(H, H, T, 0);
-        o.dWpart = off; off += up((size_t)o.splits * H * H * 4);
+        o.ds = off; off += up((size_t)T * H * 4);
+        o.gd = off; off += up((size_t)T * H * 4);
+        o.splits = o.paired ? gemm_pick_splits_balanced(H, H, T, ((T + 127) / 128) * ((H + 127) / 128), H, o.dw_first)
+                            : gemm_pick_splits(H, H, T, 0);
     }
-    o.two_planes = gate_two_planes_shape(T, H);
+    if (bwd) { o.dWpart = off; off += up((size_t)o.splits * H * H * 4); }
     o.rowmax = o.slots = 0; o.row_parts = o.main_blocks = 0;
     if (o.two_planes) {
         o.row_parts = (int)(H / 64);
@@ -381,26 +402,27 @@ ssm_status ssm_half_glu_bwd(const float *u, const float *W, const float *gate, c
     char *ws = static_cast<char *>(workspace);
     float *x1 = reinterpret_cast<float *>(ws + lo.x1);
     float *dz = reinterpret_cast<float *>(ws + lo.dz);
+    float *ds = reinterpret_cast<float *>(ws + lo.ds), *gd = reinterpret_cast<float *>(ws + lo.gd);
     float *dWpart = reinterpret_cast<float *>(ws + lo.dWpart);
     const long n = (long)T * H;
     unsigned *rowmax = reinterpret_cast<unsigned *>(ws + lo.rowmax);
     unsigned *x1_slots = reinterpret_cast<unsigned *>(ws + lo.slots), *dz_slots = x1_slots + GLU_MAX_SLOTS, *wslots = dz_slots + GLU_MAX_SLOTS;
     if (lo.two_planes) {
         hipLaunchKernelGGL(gate_bwd_prep_max_kernel, dim3((unsigned)(lo.main_blocks + GLU_W_BLOCKS)), dim3(256), 0, s, u, gate, dy,
-                           x1, dz, n, (int)H, (long)T, rowmax, x1_slots, dz_slots, W, (long)H * H, wslots, GLU_W_BLOCKS);
+                           x1, dz, ds, gd, n, (int)H, (long)T, rowmax, x1_slots, dz_slots, W, (long)H * H, wslots, GLU_W_BLOCKS);
     } else {
         hipLaunchKernelGGL(gate_bwd_prep_kernel, dim3((unsigned)(((n + 3) / 4 + 255) / 256)), dim3(256), 0, s, u, gate, dy, x1,
-                           dz, n);
+                           dz, ds, gd, n);
     }
     HIP_TRY(hipGetLastError());
-    // du[t, i] = dy[t, i] s[t, i] + GELU'(u[t, i]) sum_j dz[t, j] W[i, j]
+    // du[t, i] = ds[t, i] + gd[t, i] sum_j dz[t, j] W[i, j]
     GemmArgs g{};
     g.A = dz; g.lda = H; g.a_kcontig = 1;
     g.B = W; g.ldb = H; g.b_kcontig = 1;
-    g.C = du; g.ldc = H; g.E = dy; g.E2 = gate; g.E3 = u; g.lde = H; g.epilogue = 4;
+    g.C = du; g.ldc = H; g.E = ds; g.E2 = gd; g.lde = H; g.epilogue = 4;
     g.M = (int)T; g.N = (int)H; g.K = (int)H; g.splits = 1;
     if (lo.two_planes) { g.amaxA = AbsMax{nullptr, 0, rowmax, lo.row_parts, (long)T}; g.amaxB = AbsMax{wslots, GLU_W_BLOCKS, nullptr, 0, 0}; }
-    HIP_TRY(launch_gemm_halved(g, lo.halves ? reinterpret_cast<float *>(ws + lo.halves) : nullptr, s));
+    if (!lo.paired) HIP_TRY(launch_gemm_halved(g, lo.halves ? reinterpret_cast<float *>(ws + lo.halves) : nullptr, s));
     // dW[i, j] = sum_t x1[t, i] dz[t, j]: reduction over tokens in K slabs, then a fixed-order sum
     GemmArgs h{};
     h.A = x1; h.lda = H; h.a_kcontig = 0;
@@ -408,7 +430,8 @@ ssm_status ssm_half_glu_bwd(const float *u, const float *W, const float *gate, c
     h.C = dWpart; h.ldc = H;
     h.M = (int)H; h.N = (int)H; h.K = (int)T; h.splits = lo.splits;
     if (lo.two_planes) { h.amaxA = AbsMax{x1_slots, lo.main_blocks, nullptr, 0, 0}; h.amaxB = AbsMax{dz_slots, lo.main_blocks, nullptr, 0, 0}; }
-    HIP_TRY(launch_gemm(h, s));
+    if (lo.paired) HIP_TRY(launch_gemm_pair(g, h, s, lo.dw_first));
+    else HIP_TRY(launch_gemm(h, s));
     const long nw = (long)H * H;
     hipLaunchKernelGGL(sum_slabs_kernel, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, s, dWpart, nw, lo.splits, dW);
     HIP_TRY(hipGetLastError());

@@ -188,18 +188,18 @@ bool gemm_out_split_shape(int64_t T, int64_t H, int64_t P)
 // The store function of a product that ran as two K halves, applied to v = s0 + s1 (n = rows * H elements):
 //   mode 1: out = v + D (.) e                      (epilogue 1; out2 = GELU(out) when given: epilogue 6)
 //   mode 3: out = e (.) sigmoid(v), out2 = sigmoid(v) when given                       (epilogue 3)
-//   mode 4: out = e (.) e2 + v (.) GELU'(e3)                                            (epilogue 4)
-__device__ __forceinline__ float sum_halves_apply(int mode, bool want2, float v, float d, float e, float e2, float e3,
+//   mode 4: out = e + v (.) e2                                                         (epilogue 4)
+__device__ __forceinline__ float sum_halves_apply(int mode, bool want2, float v, float d, float e, float e2,
                                                   float &second)
 {
     if (mode == 1) { const float r = fmaf(d, e, v); second = want2 ? gelu_value(r) : 0.f; return r; }
     if (mode == 3) { const float sg = sigmoidf(v); second = sg; return e * sg; }
     second = 0.f;
-    return fmaf(v, gelu_derivative(e3), e * e2);
+    return fmaf(v, e2, e);
 }
 
 struct SumHalves {
-    const float *s0, *s1, *D, *e, *e2, *e3; float *out, *out2; long n; int H, mode, vec;
+    const float *s0, *s1, *D, *e, *e2; float *out, *out2; long n; int H, mode, vec;
 };
 
 __global__ void __launch_bounds__(256) sum_halves_kernel(SumHalves a)
@@ -212,18 +212,17 @@ __global__ void __launch_bounds__(256) sum_halves_kernel(SumHalves a)
         const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
         const float4 d = a.mode == 1 ? *reinterpret_cast<const float4 *>(a.D + i % a.H) : zero;
         const float4 e2 = a.mode == 4 ? *reinterpret_cast<const float4 *>(a.e2 + i) : zero;
-        const float4 e3 = a.mode == 4 ? *reinterpret_cast<const float4 *>(a.e3 + i) : zero;
         float4 r, q;
-        r.x = sum_halves_apply(a.mode, a.out2 != nullptr, x.x + y.x, d.x, e.x, e2.x, e3.x, q.x);
-        r.y = sum_halves_apply(a.mode, a.out2 != nullptr, x.y + y.y, d.y, e.y, e2.y, e3.y, q.y);
-        r.z = sum_halves_apply(a.mode, a.out2 != nullptr, x.z + y.z, d.z, e.z, e2.z, e3.z, q.z);
-        r.w = sum_halves_apply(a.mode, a.out2 != nullptr, x.w + y.w, d.w, e.w, e2.w, e3.w, q.w);
+        r.x = sum_halves_apply(a.mode, a.out2 != nullptr, x.x + y.x, d.x, e.x, e2.x, q.x);
+        r.y = sum_halves_apply(a.mode, a.out2 != nullptr, x.y + y.y, d.y, e.y, e2.y, q.y);
+        r.z = sum_halves_apply(a.mode, a.out2 != nullptr, x.z + y.z, d.z, e.z, e2.z, q.z);
+        r.w = sum_halves_apply(a.mode, a.out2 != nullptr, x.w + y.w, d.w, e.w, e2.w, q.w);
         *reinterpret_cast<float4 *>(a.out + i) = r;
         if (a.out2) *reinterpret_cast<float4 *>(a.out2 + i) = q;
     } else {
         float q;
         const float r = sum_halves_apply(a.mode, a.out2 != nullptr, a.s0[i] + a.s1[i], a.mode == 1 ? a.D[i % a.H] : 0.f, a.e[i],
-                                         a.mode == 4 ? a.e2[i] : 0.f, a.mode == 4 ? a.e3[i] : 0.f, q);
+                                         a.mode == 4 ? a.e2[i] : 0.f, q);
         a.out[i] = r;
         if (a.out2) a.out2[i] = q;
     }
@@ -232,7 +231,7 @@ __global__ void __launch_bounds__(256) sum_halves_kernel(SumHalves a)
 static hipError_t launch_sum(SumHalves a, hipStream_t s)
 {
     auto al16 = [](const void *p) { return !p || (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
-    a.vec = a.H % 4 == 0 && al16(a.s0) && al16(a.s1) && al16(a.D) && al16(a.e) && al16(a.e2) && al16(a.e3) && al16(a.out) &&
+    a.vec = a.H % 4 == 0 && al16(a.s0) && al16(a.s1) && al16(a.D) && al16(a.e) && al16(a.e2) && al16(a.out) &&
             al16(a.out2);
     const long threads = a.vec ? a.n / 4 : a.n;
     hipLaunchKernelGGL(sum_halves_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, a);
@@ -249,11 +248,11 @@ hipError_t launch_gemm_halved(const GemmArgs &a, float *halves, hipStream_t s)
         a.K % 2 != 0)
         return launch_gemm(a, s);
     GemmArgs g = a;
-    g.C = halves; g.ldc = a.N; g.splits = 2; g.epilogue = 0; g.diag = nullptr; g.E = nullptr; g.E2 = g.E3 = nullptr; g.C2 = nullptr;
+    g.C = halves; g.ldc = a.N; g.splits = 2; g.epilogue = 0; g.diag = nullptr; g.E = nullptr; g.E2 = nullptr; g.C2 = nullptr;
     hipError_t e = launch_gemm(g, s);
     if (e != hipSuccess) return e;
     SumHalves q{};
-    q.s0 = halves; q.s1 = halves + (size_t)a.M * a.N; q.D = a.diag; q.e = a.E; q.e2 = a.E2; q.e3 = a.E3;
+    q.s0 = halves; q.s1 = halves + (size_t)a.M * a.N; q.D = a.diag; q.e = a.E; q.e2 = a.E2;
     q.out = a.C; q.out2 = a.C2; q.n = (long)a.M * a.N; q.H = a.N;
     q.mode = (a.epilogue == 6) ? 1 : a.epilogue;
     if (a.epilogue == 1) q.out2 = nullptr;
@@ -286,7 +285,7 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
     if (a.epilogue == 5 && a.C2 && !a.diag) return hipErrorInvalidValue;
     if ((a.epilogue == 1 || a.epilogue == 2 || a.epilogue == 6) && !a.diag) return hipErrorInvalidValue;
     if (a.epilogue == 6 && !a.C2) return hipErrorInvalidValue;
-    if (a.epilogue == 4 && (!a.E2 || !a.E3)) return hipErrorInvalidValue;
+    if (a.epilogue == 4 && !a.E2) return hipErrorInvalidValue;
     if (gemm_layout_of(a) < 0) return hipErrorInvalidValue;
     // measured on MI355X: 128x128x32 tiles with 4 consumer and 8 producer wavefronts when they give
     // (nearly) every CU a workgroup; else 64x128x32 tiles (staging per multiply-add is 1.5x there);

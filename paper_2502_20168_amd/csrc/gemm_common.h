@@ -19,7 +19,7 @@ struct GemmDev {
     const float *B; long ldb;
     float *C; long ldc;
     const float *diag; const float *E; long lde;
-    const float *E2; const float *E3; float *C2;    // gate epilogues (pitch lde / ldc)
+    const float *E2; float *C2;                     // gate epilogues (pitch lde / ldc)
     const uint8_t *rowflag;
     int M, N, K, kper;      // kper: K range per split (multiple of the K tile)
     int ntm, ntn, per_xcd;
@@ -43,8 +43,8 @@ struct GemmDev {
 //          state Abar x_{t-1} of one recurrence step (Eq. 3, first line)
 //   EPI 3: half-GLU gate (S5 sequence layer appendix): s = sigmoid(v) is kept in C2 when asked
 //          and the stored value is E[row, col] * s        (E = the gated input u)
-//   EPI 4: adjoint of the gate with respect to its input: E * E2 + v * GELU'(E3)
-//          (E = dy, E2 = the saved gate s, E3 = u; v = the product dz W^T)
+//   EPI 4: adjoint of the gate with respect to its input: E + v * E2
+//          (E = dy (.) s and E2 = GELU'(u), both formed by the element-wise pass before the product; v = dz W^T)
 //   EPI 6: v + diag[col] * E[row, col] as EPI 1, and GELU of that value into C2 (the output
 //          projection feeding the half-GLU gate of the S5 block)
 //   EPI 5 (bf16x3 kernel only, handled where the tile is stored because it needs the partner
@@ -89,7 +89,7 @@ __device__ __forceinline__ float gemm_epilogue_apply(const GemmDev &g, long row,
     }
     if (EPI == 4) {
         const long i = row * g.lde + col;
-        return fmaf(v, gelu_derivative(g.E3[i]), g.E[i] * g.E2[i]);
+        return fmaf(v, g.E2[i], g.E[i]);
     }
     if (EPI == 6) {
         const float y = fmaf(g.diag[col], g.E[row * g.lde + col], v);

@@ -1061,8 +1061,7 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
         return;
     }
     if constexpr (EPI == 3) {
-        // half-GLU gate: the same order (the adjoint of the gate, three inputs per value and the error
-        // function in its store, stays with the plain loop: it has no registers to spare)
+        // half-GLU gate: the same order
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -1083,6 +1082,31 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
                         if (g.C2) g.C2[row * g.ldc + col] = sg;
                         Cz[row * g.ldc + col] = e[r] * sg;
                     }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        return;
+    }
+    if constexpr (EPI == 4) {
+        // adjoint of the gate, E + acc (.) E2: the inputs of a 32x32 block first, as above
+#pragma unroll
+        for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j) {
+                const int col = n0 + wn * WN + j * 32 + li;
+                const long rbase = m0 + wm * WM + i * 32 + 4 * hh;
+                float e[16], e2[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const long row = rbase + 8 * (r / 4) + (r % 4);
+                    const bool inb = FAST || (row < g.M && col < g.N);
+                    e[r] = inb ? g.E[row * g.lde + col] : 0.f;
+                    e2[r] = inb ? g.E2[row * g.lde + col] : 0.f;
+                }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const long row = rbase + 8 * (r / 4) + (r % 4);
+                    if (FAST || (row < g.M && col < g.N)) Cz[row * g.ldc + col] = fmaf(acc[i][j][r], e2[r], e[r]);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -1245,7 +1269,7 @@ inline GemmDev make_gemm_dev(const GemmArgs &a)
     GemmDev g;
     g.A = a.A; g.lda = a.lda; g.B = a.B; g.ldb = a.ldb; g.C = a.C; g.ldc = a.ldc;
     g.diag = a.diag; g.E = a.E; g.lde = a.lde; g.rowflag = a.rowflag;
-    g.E2 = a.E2; g.E3 = a.E3; g.C2 = a.C2;
+    g.E2 = a.E2; g.C2 = a.C2;
     g.M = a.M; g.N = a.N; g.K = a.K;
     const int splits = a.splits < 1 ? 1 : a.splits;
     int kper = (a.K + splits - 1) / splits;

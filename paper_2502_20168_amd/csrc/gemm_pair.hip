@@ -9,6 +9,8 @@
 //   other shapes (three bf16 planes):
 //     C^H dy                                        with  dy^T x
 //     Re(Bbar^H chi) + D dy                         with  chi^T u
+// and of the gate's (two scaled fp16 planes):
+//     dz W^T with the adjoint of the gate in its store   with  x1^T dz
 // The products of a launch have their inputs ready at the same time, and one of them alone would
 // leave compute units idle.
 #include "gemm_kernel.h"
@@ -17,7 +19,7 @@ namespace ssm {
 
 namespace {
 constexpr int NN0 = gemm_layout(true, false, 0), NN1 = gemm_layout(true, false, 1), NN8 = gemm_layout(true, false, 8),
-              TN0 = gemm_layout(false, false, 0);
+              TN0 = gemm_layout(false, false, 0), NT4 = gemm_layout(true, true, 4);
 bool plain_problem(const GemmArgs &g)
 {
     return g.M > 0 && g.N > 0 && g.K > 0 && !(g.splits > 1 && g.epilogue);
@@ -47,6 +49,8 @@ hipError_t launch_gemm_pair(const GemmArgs &a, const GemmArgs &b, hipStream_t s,
         if (la == NN1 && items128(a) + items128(b) > 288)
             return launch_gemm_ws_variant<128, 128, 32, 2, 2, 4, 2, 2, NN1, TN0, 4>(a, s, &b, nullptr, order);
         if (la == NN1) return launch_gemm_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, NN1, TN0>(a, s, &b, nullptr, order);
+        // the adjoint of the gate: dz W^T with its store function, and the slabs of x1^T dz
+        if (la == NT4) return launch_gemm_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, NT4, TN0>(a, s, &b, nullptr, order);
     }
     if (!gemm_use_two_planes(a) && !gemm_use_two_planes(b) && lb == TN0) {
         if (gemm_small_pair(a.M, a.N)) {

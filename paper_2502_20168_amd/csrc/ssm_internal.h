@@ -13,7 +13,7 @@ namespace ssm {
 // epilogue 0: none; 1: + diag[n] * E[m,n]; 2: + [not rowflag[m]] * (Abar (.) E)[m,n] with diag = Abar
 // as interleaved complex and the columns of C and E interleaved (re, im) pairs (one recurrence step);
 // 3: C = E (.) sigmoid(product), sigmoid kept in C2 when non-null (half-GLU gate);
-// 4: C = E (.) E2 + product (.) GELU'(E3) (adjoint of the gate with respect to its input);
+// 4: C = E + product (.) E2 (adjoint of the gate with respect to its input: E = dy (.) s, E2 = GELU'(u));
 // 6: as 1, and C2 = GELU(C) (output projection that feeds the half-GLU gate);
 // 7: the resettable scan over the rows of the output tile (see ScanEpilogue): C = states;
 // 8: the reverse-time scan of the gradient pass over the rows of the output tile: C = chi;
@@ -75,7 +75,7 @@ struct GemmArgs {
     float *C; int64_t ldc;
     const float *diag; const float *E; int64_t lde;
     int epilogue; const uint8_t *rowflag;
-    const float *E2; const float *E3; float *C2;     // epilogues 3 and 4 (gate), pitch lde / ldc
+    const float *E2; float *C2;                      // epilogues 3 and 4 (gate), pitch lde / ldc
     int M, N, K, splits;
     ScanEpilogue scan;                               // epilogues 7 and 8
     AbsMax amaxA, amaxB;                             // largest magnitudes of A and B when known
