@@ -265,7 +265,7 @@ __global__ void __launch_bounds__(256) sum_slabs_kernel(const float *__restrict_
 constexpr int GLU_MAX_SLOTS = 512;      // workgroups of the element-wise pass that report a maximum each
 constexpr int GLU_W_BLOCKS = 256;       // workgroups that measure W
 struct GluLayout {
-    size_t x1, dz, ds, gd, dWpart, halves, total; int splits;
+    size_t x1, dz, ds, gd, dWpart, total; int splits;
     // widths that are multiples of 64: two scaled fp16 planes per operand, with their largest magnitudes
     bool two_planes; size_t rowmax, slots; int row_parts, main_blocks;
     bool paired, dw_first;     // gradient pass: dz W^T and the slabs of x1^T dz in one launch (dW's work items first)
@@ -276,15 +276,12 @@ bool make_glu_layout(int64_t T, int64_t H, bool bwd, GluLayout &o)
     if (T <= 0 || H <= 0 || H > SSM_MAX_WIDTH || T > SSM_MAX_TOKENS || T > SSM_MAX_ELEMS / H) return false;
     size_t off = 0;
     o.x1 = off; off += up((size_t)T * H * 4);
-    o.dz = o.ds = o.gd = o.dWpart = o.halves = 0; o.splits = 1;
+    o.dz = o.ds = o.gd = o.dWpart = 0; o.splits = 1;
     o.two_planes = gate_two_planes_shape(T, H);
     // gradient pass on two planes: both products wait for the same element-wise pass and share one launch, the
     // K splits of the reduction from the schedule model of that launch (no K halves of du then: the slabs
     // fill the chip beside it)
     o.paired = bwd && o.two_planes; o.dw_first = false;
-    if (!o.paired && gemm_out_split_shape(T, H, H / 2) && H % 2 == 0) {      // the gate products as two K halves
-        o.halves = off; off += up((size_t)2 * T * H * 4);
-    }
     if (bwd) {
         o.dz = off; off += up((size_t)T * H * 4);
         o.ds = off; off += up((size_t)T * H * 4);
@@ -381,8 +378,7 @@ ssm_status ssm_half_glu_fwd(const float *u, const float *W, int64_t T, int64_t H
     g.C = y; g.ldc = H; g.E = u; g.lde = H; g.C2 = gate; g.epilogue = 3;
     g.M = (int)T; g.N = (int)H; g.K = (int)H; g.splits = 1;
     if (lo.two_planes) { g.amaxA = AbsMax{nullptr, 0, rowmax, lo.row_parts, (long)T}; g.amaxB = AbsMax{wslots, GLU_W_BLOCKS, nullptr, 0, 0}; }
-    float *halves = lo.halves ? reinterpret_cast<float *>(static_cast<char *>(workspace) + lo.halves) : nullptr;
-    HIP_TRY(launch_gemm_halved(g, halves, s));
+    HIP_TRY(launch_gemm(g, s));
     return SSM_OK;
 }
 
@@ -422,7 +418,7 @@ ssm_status ssm_half_glu_bwd(const float *u, const float *W, const float *gate, c
     g.C = du; g.ldc = H; g.E = ds; g.E2 = gd; g.lde = H; g.epilogue = 4;
     g.M = (int)T; g.N = (int)H; g.K = (int)H; g.splits = 1;
     if (lo.two_planes) { g.amaxA = AbsMax{nullptr, 0, rowmax, lo.row_parts, (long)T}; g.amaxB = AbsMax{wslots, GLU_W_BLOCKS, nullptr, 0, 0}; }
-    if (!lo.paired) HIP_TRY(launch_gemm_halved(g, lo.halves ? reinterpret_cast<float *>(ws + lo.halves) : nullptr, s));
+    if (!lo.paired) HIP_TRY(launch_gemm(g, s));
     // dW[i, j] = sum_t x1[t, i] dz[t, j]: reduction over tokens in K slabs, then a fixed-order sum
     GemmArgs h{};
     h.A = x1; h.lda = H; h.a_kcontig = 0;

@@ -175,88 +175,13 @@ size_t gemm_scan_desc_bytes(int64_t Bt, int64_t L, int64_t P)
 
 // The output projection y = x Cc^T + D u has only M/128 * H/128 tiles of 128x128.  When they would
 // fill less than the chip but twice as many would, the product runs as two halves of K (256
-// workgroups of the efficient 128x128 tile instead of 64x128 tiles).  The halves of a tile meet inside
-// the launch (KJoin: the layer's forward pass), or go to two slabs that a streaming kernel adds while
-// it applies the store function (launch_gemm_halved: the gate).
+// workgroups of the efficient 128x128 tile instead of 64x128 tiles) and the halves of a tile meet inside
+// the launch (KJoin).
 bool gemm_out_split_shape(int64_t T, int64_t H, int64_t P)
 {
     // a half must still be long enough (8 K tiles) to pay for the hand-over
     const int64_t tiles = ((T + 127) / 128) * ((H + 127) / 128);
     return tiles < 200 && 2 * tiles >= 200 && P >= 256 && (2 * P) % 64 == 0;
-}
-
-// The store function of a product that ran as two K halves, applied to v = s0 + s1 (n = rows * H elements):
-//   mode 1: out = v + D (.) e                      (epilogue 1; out2 = GELU(out) when given: epilogue 6)
-//   mode 3: out = e (.) sigmoid(v), out2 = sigmoid(v) when given                       (epilogue 3)
-//   mode 4: out = e + v (.) e2                                                         (epilogue 4)
-__device__ __forceinline__ float sum_halves_apply(int mode, bool want2, float v, float d, float e, float e2,
-                                                  float &second)
-{
-    if (mode == 1) { const float r = fmaf(d, e, v); second = want2 ? gelu_value(r) : 0.f; return r; }
-    if (mode == 3) { const float sg = sigmoidf(v); second = sg; return e * sg; }
-    second = 0.f;
-    return fmaf(v, e2, e);
-}
-
-struct SumHalves {
-    const float *s0, *s1, *D, *e, *e2; float *out, *out2; long n; int H, mode, vec;
-};
-
-__global__ void __launch_bounds__(256) sum_halves_kernel(SumHalves a)
-{
-    const long i = ((long)blockIdx.x * 256 + threadIdx.x) * (a.vec ? 4 : 1);
-    if (i >= a.n) return;
-    if (a.vec) {
-        const float4 x = *reinterpret_cast<const float4 *>(a.s0 + i), y = *reinterpret_cast<const float4 *>(a.s1 + i);
-        const float4 e = *reinterpret_cast<const float4 *>(a.e + i);
-        const float4 zero = make_float4(0.f, 0.f, 0.f, 0.f);
-        const float4 d = a.mode == 1 ? *reinterpret_cast<const float4 *>(a.D + i % a.H) : zero;
-        const float4 e2 = a.mode == 4 ? *reinterpret_cast<const float4 *>(a.e2 + i) : zero;
-        float4 r, q;
-        r.x = sum_halves_apply(a.mode, a.out2 != nullptr, x.x + y.x, d.x, e.x, e2.x, q.x);
-        r.y = sum_halves_apply(a.mode, a.out2 != nullptr, x.y + y.y, d.y, e.y, e2.y, q.y);
-        r.z = sum_halves_apply(a.mode, a.out2 != nullptr, x.z + y.z, d.z, e.z, e2.z, q.z);
-        r.w = sum_halves_apply(a.mode, a.out2 != nullptr, x.w + y.w, d.w, e.w, e2.w, q.w);
-        *reinterpret_cast<float4 *>(a.out + i) = r;
-        if (a.out2) *reinterpret_cast<float4 *>(a.out2 + i) = q;
-    } else {
-        float q;
-        const float r = sum_halves_apply(a.mode, a.out2 != nullptr, a.s0[i] + a.s1[i], a.mode == 1 ? a.D[i % a.H] : 0.f, a.e[i],
-                                         a.mode == 4 ? a.e2[i] : 0.f, q);
-        a.out[i] = r;
-        if (a.out2) a.out2[i] = q;
-    }
-}
-
-static hipError_t launch_sum(SumHalves a, hipStream_t s)
-{
-    auto al16 = [](const void *p) { return !p || (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
-    a.vec = a.H % 4 == 0 && al16(a.s0) && al16(a.s1) && al16(a.D) && al16(a.e) && al16(a.e2) && al16(a.out) &&
-            al16(a.out2);
-    const long threads = a.vec ? a.n / 4 : a.n;
-    hipLaunchKernelGGL(sum_halves_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, a);
-    return hipGetLastError();
-}
-
-// A product with a store function (epilogue 1, 3, 4 or 6) that runs as two K halves into `halves`
-// ([2][M][N] floats) plus the streaming pass above when its shape calls for it and `halves` is given;
-// otherwise the plain launch.
-hipError_t launch_gemm_halved(const GemmArgs &a, float *halves, hipStream_t s)
-{
-    const bool store_fn = a.epilogue == 1 || a.epilogue == 3 || a.epilogue == 4 || a.epilogue == 6;
-    if (!halves || !store_fn || a.splits > 1 || a.ldc != a.N || (a.E && a.lde != a.N) || !gemm_out_split_shape(a.M, a.N, a.K / 2) ||
-        a.K % 2 != 0)
-        return launch_gemm(a, s);
-    GemmArgs g = a;
-    g.C = halves; g.ldc = a.N; g.splits = 2; g.epilogue = 0; g.diag = nullptr; g.E = nullptr; g.E2 = nullptr; g.C2 = nullptr;
-    hipError_t e = launch_gemm(g, s);
-    if (e != hipSuccess) return e;
-    SumHalves q{};
-    q.s0 = halves; q.s1 = halves + (size_t)a.M * a.N; q.D = a.diag; q.e = a.E; q.e2 = a.E2;
-    q.out = a.C; q.out2 = a.C2; q.n = (long)a.M * a.N; q.H = a.N;
-    q.mode = (a.epilogue == 6) ? 1 : a.epilogue;
-    if (a.epilogue == 1) q.out2 = nullptr;
-    return launch_sum(q, s);
 }
 
 int gemm_tile_tier(int64_t M, int64_t N, int splits_in)

@@ -784,7 +784,7 @@ ssm_status ssm_step_bwd(const void *plan, size_t plan_bytes, const float *D, con
 
 namespace {
 struct BlockLayout {
-    size_t ssm, x1, glu, dypre, gate_halves, total;
+    size_t ssm, x1, glu, dypre, total;
     // forward: the gate's product on two scaled fp16 planes (width a multiple of 64 and an output projection
     // whose wavefronts own 64 columns): rows of GELU(y) in pieces of 64 columns, pieces of W
     bool gate_two_planes; size_t x1_rowmax, wslots; int nwslots;
@@ -796,11 +796,10 @@ bool make_block_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, Bl
     const size_t TH = up((size_t)Bt * L * H * 4);
     size_t off = 0;
     o.ssm = off; off += up(lo.total);
-    o.x1 = o.glu = o.dypre = o.gate_halves = 0;
+    o.x1 = o.glu = o.dypre = 0;
     o.gate_two_planes = false; o.x1_rowmax = o.wslots = 0; o.nwslots = 0;
     if (!bwd) {
         o.x1 = off; off += TH;
-        if (H % 2 == 0 && gemm_out_split_shape(Bt * L, H, H / 2)) { o.gate_halves = off; off += 2 * TH; }   // gate product as two K halves
         o.gate_two_planes = gate_two_planes_shape(Bt * L, H) && gemm_tile_tier(Bt * L, H, lo.jtiles ? 2 : 1) <= 1;
         if (o.gate_two_planes) {
             o.nwslots = pass_pieces((size_t)H * H);
@@ -855,7 +854,7 @@ ssm_status ssm_block_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 
         g.amaxA = AbsMax{nullptr, 0, gm.x1_rowmax, (int)(H / 64), (long)(Bt * L)};
         g.amaxB = AbsMax{gm.wslots, gm.nwslots, nullptr, 0, 0};
     }
-    HIP_TRY(launch_gemm_halved(g, bl.gate_halves ? reinterpret_cast<float *>(ws + bl.gate_halves) : nullptr, s));
+    HIP_TRY(launch_gemm(g, s));
     return SSM_OK;
 }
 

@@ -106,9 +106,6 @@ hipError_t gemm_dispatch_two_planes(const GemmArgs &g, int tier, hipStream_t s);
 hipError_t gemm_dispatch_three_planes(const GemmArgs &g, int tier, hipStream_t s);
 // the output projection runs as two K halves into two slabs plus a streaming sum at this shape
 bool gemm_out_split_shape(int64_t T, int64_t H, int64_t P);
-// a product with a store function (epilogue 1, 3, 4, 6): as two K halves into halves[2][M][N] plus a
-// streaming pass when gemm_out_split_shape(M, N, K/2) says so and halves is not null; else launch_gemm
-hipError_t launch_gemm_halved(const GemmArgs &g, float *halves, hipStream_t s);
 // two independent problems in one launch (falls back to two launches for layouts without a
 // paired instantiation)
 hipError_t launch_gemm_pair(const GemmArgs &a, const GemmArgs &b, hipStream_t s, bool second_first = false);
