@@ -176,7 +176,7 @@ def main():
     if scans:
         launches = [
             {"role": "input projection + forward scan in the tile (S2 + S3)", "gemms": 1, "ms": fs[1]},
-            {"role": "output projection" + (" + D u as two K halves that meet inside the launch" if out_split else " + D u")
+            {"role": "output projection" + (" + D u on 64x128 tiles" if out_split else " + D u")
                      + " (S4)", "gemms": 1, "ms": fs[3]},
             {"role": "C^H dy + reverse scan in the tile (S5 + S6)", "gemms": 1, "ms": bs[1]},
             {"role": "Re(Bbar^H chi) + D dy, the dBbar slabs and the dC slabs, one launch, two workgroups per CU (S7 + S5)",
@@ -408,7 +408,7 @@ def s5_block(ssm, torch, wl, d, Bt, L, H, P, iters=10):
                          "fwd_achieved": round(exe_f, 1), "fwd_frac": round(exe_f / PEAK_F16_MFMA_TFLOPS, 4),
                          "bwd_achieved": round(exe_b, 1), "bwd_frac": round(exe_b / PEAK_F16_MFMA_TFLOPS, 4)},
             "note": "layer + gate, forward and gradient pass, replayed as HIP graphs (includes the binding's output "
-                    "allocations inside the graph); GELU of the layer output is formed where the output projection's result is stored (by the half that finishes the tile at this shape)"}
+                    "allocations inside the graph); GELU of the layer output is formed where the output projection's result is stored (on 64x128 tiles at this shape)"}
 
 
 def block_ops(ssm, torch, wl, T, H, iters=20):

@@ -18,8 +18,7 @@ extern "C" {
 
 /* The same code path as ssm_scan_fwd / ssm_scan_bwd.  They wait for the stream before returning and
  * write the milliseconds of each stage to the HOST array stage_ms:
- *   forward : [0] discretise+pack, [1] input projection, [2] scan, [3] output projection (as two K
- *             halves that meet inside the launch where it has too few tiles for the chip)
+ *   forward : [0] discretise+pack, [1] input projection, [2] scan, [3] output projection
  *   backward: [0] discretise+pack and dD partials, [1] gx = C^H dy (with the reverse scan in its tiles
  *             where the shape allows), [2] reverse scan kernel, [3] du with the dBbar and dC partials
  *             (one launch), [4] empty (the sum of the two halves of du shares the next launch),

@@ -173,23 +173,31 @@ size_t gemm_scan_desc_bytes(int64_t Bt, int64_t L, int64_t P)
     return (size_t)tiles * 64 * 2 * sizeof(unsigned long long);
 }
 
-// The output projection y = x Cc^T + D u has only M/128 * H/128 tiles of 128x128.  When they would
-// fill less than the chip but twice as many would, the product runs as two halves of K (256
-// workgroups of the efficient 128x128 tile instead of 64x128 tiles) and the halves of a tile meet inside
-// the launch (KJoin).
+// du = Re(Bbar^H chi) + D dy has only M/128 * H/128 tiles of 128x128.  Where they would fill less than the
+// chip but twice as many would (and the launch is shared with the dBbar slabs on three bf16 planes), it
+// runs as two halves of K into two slabs that the parameter epilogue's launch adds.
 bool gemm_out_split_shape(int64_t T, int64_t H, int64_t P)
 {
-    // a half must still be long enough (8 K tiles) to pay for the hand-over
+    // a half must still be long enough (8 K tiles) to pay for the sum
     const int64_t tiles = ((T + 127) / 128) * ((H + 127) / 128);
     return tiles < 200 && 2 * tiles >= 200 && P >= 256 && (2 * P) % 64 == 0;
 }
 
+// Tile tier of an M x N product with `splits` K splits: 0 = 128x128x32 tiles, 1 = 64x128x32, 2 = 64x64x64.
+// The launch takes about (rounds of workgroups on the 256 CUs) x (K steps) x (time of a K step); a K step of a
+// 64x128x32 tile takes as long as one of a 128x128x32 tile, one of a 64x64x64 tile 1.2 times as long for twice
+// the K range (measured), so per unit of K the tiers cost rounds x 1, 1 and 0.6.  The cheapest wins, the
+// smaller tile on a tie (more CUs share the work).  (The rule before, "the largest tile that still gives 200
+// workgroups", took 64x128 tiles for 192 tiles of 128x128: two rounds instead of one, 40 us instead of 24.)
 int gemm_tile_tier(int64_t M, int64_t N, int splits_in)
 {
     const int64_t splits = splits_in < 1 ? 1 : splits_in;
-    const int64_t tiles128 = ((M + 127) / 128) * ((N + 127) / 128) * splits;
-    const int64_t tiles64x128 = ((M + 63) / 64) * ((N + 127) / 128) * splits;
-    return tiles128 >= 200 ? 0 : (tiles64x128 >= 200 ? 1 : 2);
+    const int64_t r0 = (((M + 127) / 128) * ((N + 127) / 128) * splits + 255) / 256;
+    const int64_t r1 = (((M + 63) / 64) * ((N + 127) / 128) * splits + 255) / 256;
+    const int64_t r2 = (((M + 63) / 64) * ((N + 63) / 64) * splits + 255) / 256;
+    const int64_t c0 = 10 * r0, c1 = 10 * r1, c2 = 6 * r2;
+    if (c2 < c0 && c2 < c1) return 2;
+    return c1 <= c0 ? 1 : 0;
 }
 
 hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
@@ -201,22 +209,14 @@ hipError_t launch_gemm(const GemmArgs &a, hipStream_t s)
         if (!gemm_scan_args_ok(a) || gemm_layout_of(a) < 0) return hipErrorInvalidValue;
         return two ? gemm_dispatch_two_planes(a, 0, s) : gemm_dispatch_three_planes(a, 0, s);
     }
-    // a store function with K splits: only as two halves that meet inside the launch
-    const bool joined = a.join.tiles != nullptr && a.splits == 2;
-    if (a.splits > 1 && a.epilogue && !joined) return hipErrorInvalidValue;
-    if (joined && (!a.join.flags || !a.join.err || !(a.epilogue == 1 || a.epilogue == 3 || a.epilogue == 4 || a.epilogue == 6)))
-        return hipErrorInvalidValue;
+    if (a.splits > 1 && a.epilogue) return hipErrorInvalidValue;
     if (a.epilogue < 0 || a.epilogue > 6 || (a.epilogue && a.epilogue != 5 && !a.E)) return hipErrorInvalidValue;
     if (a.epilogue == 5 && a.C2 && !a.diag) return hipErrorInvalidValue;
     if ((a.epilogue == 1 || a.epilogue == 2 || a.epilogue == 6) && !a.diag) return hipErrorInvalidValue;
     if (a.epilogue == 6 && !a.C2) return hipErrorInvalidValue;
     if (a.epilogue == 4 && !a.E2) return hipErrorInvalidValue;
     if (gemm_layout_of(a) < 0) return hipErrorInvalidValue;
-    // measured on MI355X: 128x128x32 tiles with 4 consumer and 8 producer wavefronts when they give
-    // (nearly) every CU a workgroup; else 64x128x32 tiles (staging per multiply-add is 1.5x there);
-    // else, for the small products of step mode, 64x64x64 tiles (fewer, longer K steps)
     const int tier = gemm_tile_tier(a.M, a.N, a.splits);
-    if (joined && tier != 0) return hipErrorInvalidValue;      // (the hand-over exists for 128x128 tiles)
     return two ? gemm_dispatch_two_planes(a, tier, s) : gemm_dispatch_three_planes(a, tier, s);
 }
 

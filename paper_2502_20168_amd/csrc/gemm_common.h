@@ -31,7 +31,6 @@ struct GemmDev {
     ScanEpilogue scan;
     int sc_nt, sc_cpu, sc_ncg, sc_units, sc_rev;
     AbsMax amaxA, amaxB;    // two-plane fp16 staging only
-    KJoin join;             // two K halves that meet inside the launch (see ssm_internal.h)
     unsigned *c2_rowmax;    // epilogue 6 on tiles whose wavefronts own 64 columns: [ceil(N/64)][M] largest magnitudes of C2, or null
 };
 

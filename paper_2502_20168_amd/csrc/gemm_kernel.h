@@ -193,7 +193,10 @@ struct SplitLoader {
     // k-contiguous source: the tile row that unit i of this thread belongs to
     static __device__ __forceinline__ int unit_row(int tid, int i) { return kc_row((tid + i * NT) / (BK / 4)); }
 
-    template <bool FAST>
+    // FAST 0: every element guarded (4-byte loads); 1: 16-byte loads of a tile that lies inside the operand;
+    // 2: 16-byte loads of a k-contiguous operand whose tile hangs over the last row (that row is re-read:
+    // the values only reach output rows or columns that are never stored)
+    template <int FAST>
     __device__ __forceinline__ void load(const float *__restrict__ X, long ld, int row0, int rows, int k0,
                                          int kend, int tid)
     {
@@ -204,8 +207,10 @@ struct SplitLoader {
                 const int row = kc_row(idx / (BK / 4)), kq = idx % (BK / 4);
                 const long gr = row0 + row;
                 const int k = k0 + 4 * kq;
-                if (FAST) {
+                if (FAST == 1) {
                     r[i] = *reinterpret_cast<const float4 *>(X + gr * ld + k);
+                } else if (FAST == 2) {
+                    r[i] = *reinterpret_cast<const float4 *>(X + (gr < rows ? gr : (long)rows - 1) * ld + k);
                 } else {
                     float t[4];
 #pragma unroll
@@ -215,7 +220,7 @@ struct SplitLoader {
             } else {
                 const int kk = idx / (R / 4), rq = idx % (R / 4);
                 const long k = k0 + kk, gr = row0 + 4 * rq;
-                if (FAST) {
+                if (FAST != 0) {
                     r[i] = *reinterpret_cast<const float4 *>(X + k * ld + gr);
                 } else {
                     float t[4];
@@ -688,7 +693,7 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
 // LDS holds NS stages; in iteration kt the producers fill the stage of tile kt+NS-1 while the
 // consumers work on tile kt, with one workgroup barrier per K tile.
 // ---------------------------------------------------------------------------------------------
-template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL, bool AKC, bool BKC, int EPI, bool FAST>
+template <int BM, int BN, int BK, int WGM, int WGN, int NP, int NS, int NPL, bool AKC, bool BKC, int EPI, int FAST>
 __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int m0, int n0, int z,
                                                     int kbeg, int kend, int scan_tile)
 {
@@ -719,6 +724,7 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
     const int tid = threadIdx.x;
     const int wave = tid >> 6;
     const int nk = (kend > kbeg) ? (kend - kbeg + BK - 1) / BK : 0;
+    const bool full = (m0 + BM <= g.M) && (n0 + BN <= g.N);      // no store of this tile needs a bounds check
 
     if (wave >= NC) {
         // ------------------------------------------------------------------ producers
@@ -965,52 +971,7 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
         scan_epilogue_body<EPI == 8, false>(g, lds, tid, m0, n0, scan_tile, saved, masks);
         return;
     }
-    if constexpr (BM == 128 && BN == 128 && NC == 4 && (EPI == 1 || EPI == 3 || EPI == 4 || EPI == 6)) {
-        if (g.join.tiles) {
-            // Two K halves of one tile meet here.  Placement mode 2 puts split 0 on the even XCDs and split 1 on
-            // the odd ones (the pair in neighbouring workgroup ids, split 0 first): the halves that wait and the
-            // halves they wait for never compete for a CU, and split 0 never waits, so every wait ends whatever
-            // else runs on the GPU.  (Both halves of a tile on one XCD were measured: 2.5 us slower per launch,
-            // every XCD then reads all of B.)  Split 0 hands its accumulators
-            // over in register order (thread t of the partner reads what thread t wrote: coalesced both
-            // ways) with device-scope stores that go through to memory, and raises its wavefront's flag
-            // once they have completed.  Split 1 adds them to its own (one fixed order) and stores.
-            float *part = g.join.tiles + (size_t)scan_tile * (64 * 256) + tid;
-            unsigned *flag = g.join.flags + scan_tile * 4 + wave;
-            if (z == 0) {
-#pragma unroll
-                for (int i = 0; i < MI; ++i)
-#pragma unroll
-                    for (int j = 0; j < NI; ++j)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r)
-                            __hip_atomic_store(part + ((i * NI + j) * 16 + r) * 256, acc[i][j][r], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                asm volatile("" ::: "memory");
-                __builtin_amdgcn_s_waitcnt(0);           // every store of this wavefront has completed
-                asm volatile("" ::: "memory");
-                if (l == 0) __hip_atomic_store(flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                return;
-            }
-            unsigned polls = 0;
-            bool there = true;
-            while (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) {
-                __builtin_amdgcn_s_sleep(1);
-                if (++polls > g.join.spin_limit) { there = false; break; }
-            }
-            asm volatile("" ::: "memory");
-            if (!there && l == 0) atomicOr(g.join.err, 1u);
-#pragma unroll
-            for (int i = 0; i < MI; ++i)
-#pragma unroll
-                for (int j = 0; j < NI; ++j)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const float w = __hip_atomic_load(part + ((i * NI + j) * 16 + r) * 256, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        acc[i][j][r] = there ? w + acc[i][j][r] : __builtin_nanf("");     // (gave up: the failure must not pass as data)
-                    }
-        }
-    }
-    float *Cz = (g.join.tiles ? g.C : g.C + (long)z * g.M * g.ldc);
+    float *Cz = g.C + (long)z * g.M * g.ldc;
     if constexpr (EPI == 1 || EPI == 6) {
         // sum + diag (.) E: the 16 values of E that a 32x32 block needs are loaded before its first store
         // (the compiler may not move a load of E above an earlier store to C, so a load-compute-store loop
@@ -1029,13 +990,13 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const long row = rbase + 8 * (r / 4) + (r % 4);
-                    e[r] = (FAST || (row < g.M && col < g.N)) ? g.E[row * g.lde + col] : 0.f;
+                    e[r] = (full || (row < g.M && col < g.N)) ? g.E[row * g.lde + col] : 0.f;
                 }
-                const float dcol = (FAST || col < g.N) ? g.diag[col] : 0.f;
+                const float dcol = (full || col < g.N) ? g.diag[col] : 0.f;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const long row = rbase + 8 * (r / 4) + (r % 4);
-                    if (FAST || (row < g.M && col < g.N)) {
+                    if (full || (row < g.M && col < g.N)) {
                         const float y = fmaf(dcol, e[r], acc[i][j][r]);
                         Cz[row * g.ldc + col] = y;
                         if constexpr (EPI == 6) {
@@ -1072,12 +1033,12 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const long row = rbase + 8 * (r / 4) + (r % 4);
-                    e[r] = (FAST || (row < g.M && col < g.N)) ? g.E[row * g.lde + col] : 0.f;
+                    e[r] = (full || (row < g.M && col < g.N)) ? g.E[row * g.lde + col] : 0.f;
                 }
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const long row = rbase + 8 * (r / 4) + (r % 4);
-                    if (FAST || (row < g.M && col < g.N)) {
+                    if (full || (row < g.M && col < g.N)) {
                         const float sg = sigmoidf(acc[i][j][r]);
                         if (g.C2) g.C2[row * g.ldc + col] = sg;
                         Cz[row * g.ldc + col] = e[r] * sg;
@@ -1099,14 +1060,14 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const long row = rbase + 8 * (r / 4) + (r % 4);
-                    const bool inb = FAST || (row < g.M && col < g.N);
+                    const bool inb = full || (row < g.M && col < g.N);
                     e[r] = inb ? g.E[row * g.lde + col] : 0.f;
                     e2[r] = inb ? g.E2[row * g.lde + col] : 0.f;
                 }
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const long row = rbase + 8 * (r / 4) + (r % 4);
-                    if (FAST || (row < g.M && col < g.N)) Cz[row * g.ldc + col] = fmaf(acc[i][j][r], e2[r], e[r]);
+                    if (full || (row < g.M && col < g.N)) Cz[row * g.ldc + col] = fmaf(acc[i][j][r], e2[r], e[r]);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -1121,13 +1082,13 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
             for (int j = 0; j < NI; ++j) {
                 const int col = n0 + wn * WN + j * 32 + li;
                 const long rbase = m0 + wm * WM + i * 32 + 4 * hh;
-                const bool colok = FAST || col < g.N;
+                const bool colok = full || col < g.N;
                 float e[16];
                 bool dropped[16];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const long row = rbase + 8 * (r / 4) + (r % 4);
-                    const bool inb = colok && (FAST || row < g.M);
+                    const bool inb = colok && (full || row < g.M);
                     e[r] = (inb && (EPI == 2 || g.E)) ? g.E[row * g.lde + col] : 0.f;
                     dropped[r] = inb && g.rowflag && g.rowflag[row];
                 }
@@ -1136,7 +1097,7 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const long row = rbase + 8 * (r / 4) + (r % 4);
-                    const bool inb = colok && (FAST || row < g.M);
+                    const bool inb = colok && (full || row < g.M);
                     if constexpr (EPI == 2) {
                         // the carried state Abar x_{t-1} of the step, unless the step resets
                         const float own = e[r], other = __shfl_xor(own, 1);
@@ -1164,7 +1125,7 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const long row = m0 + wm * WM + i * 32 + 8 * (r / 4) + 4 * hh + (r % 4);
-                const bool inb = FAST || (row < g.M && col < g.N);
+                const bool inb = full || (row < g.M && col < g.N);
                 if constexpr (EPI == 5) {
                     // the partner column (col ^ 1) of a complex pair lives in the neighbouring lane
                     float v = acc[i][j][r];
@@ -1233,13 +1194,18 @@ __device__ __forceinline__ void gemm_ws_problem(const GemmDev &g, __bf16 *smem, 
     const int m0 = tm * BM, n0 = tn * BN;
     const int kbeg = z * g.kper;
     const int kend = min(g.K, kbeg + g.kper);
+    // 16-byte loads of both operands: aligned sources, whole K tiles, and whole tiles along the rows of an
+    // operand whose rows are contiguous in memory (a k-contiguous operand may hang over its last row)
     const bool fast = (g.lda % 4 == 0) && ((reinterpret_cast<uintptr_t>(g.A) & 15) == 0) &&
                       (g.ldb % 4 == 0) && ((reinterpret_cast<uintptr_t>(g.B) & 15) == 0) &&
-                      (m0 + BM <= g.M) && (n0 + BN <= g.N) && ((kend - kbeg) % BK == 0);
-    if (fast)
-        gemm_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, NPL, AKC, BKC, EPI, true>(g, smem, m0, n0, z, kbeg, kend, tile);
+                      (AKC || m0 + BM <= g.M) && (BKC || n0 + BN <= g.N) && ((kend - kbeg) % BK == 0);
+    const bool inside = (m0 + BM <= g.M) && (n0 + BN <= g.N);
+    if (fast && inside)
+        gemm_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, NPL, AKC, BKC, EPI, 1>(g, smem, m0, n0, z, kbeg, kend, tile);
+    else if (fast && (AKC || BKC))
+        gemm_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, NPL, AKC, BKC, EPI, 2>(g, smem, m0, n0, z, kbeg, kend, tile);
     else
-        gemm_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, NPL, AKC, BKC, EPI, false>(g, smem, m0, n0, z, kbeg, kend, tile);
+        gemm_ws_tile<BM, BN, BK, WGM, WGN, NP, NS, NPL, AKC, BKC, EPI, 0>(g, smem, m0, n0, z, kbeg, kend, tile);
 }
 
 // One launch carries one problem (LAY1 < 0), two, or three independent ones (the third has the layout
@@ -1288,7 +1254,6 @@ inline GemmDev make_gemm_dev(const GemmArgs &a)
     g.scan = a.scan;
     g.amaxA = a.amaxA; g.amaxB = a.amaxB;
     g.c2_rowmax = a.c2_rowmax;
-    g.join = (BM == 128 && BN == 128 && splits == 2) ? a.join : KJoin{nullptr, nullptr, nullptr, 0};
     g.sc_nt = g.sc_cpu = g.sc_ncg = g.sc_units = g.sc_rev = 0;
     if ((a.epilogue == 7 || a.epilogue == 8) && a.scan.L >= BM) {
         g.sc_rev = a.epilogue == 8;

@@ -85,9 +85,6 @@ struct Layout {
     bool slabs_first;        // launch of three products: the slabs' work items go first
     bool dc_first, db_first; // launches of two products (separate scan kernels): the slab items go first
     size_t hdr, lam, Bri, Cc, xbuf, chi, ticket, desc, dCpart, dBpart, dApart, dDpart, fdesc, fdesc_bytes, yhalves, total;
-    // forward pass, output projection with too few tiles for the chip: two K halves that meet inside the launch
-    // (flags directly behind fdesc, so that one range is cleared; partial tiles)
-    size_t jflags, jflag_bytes, jtiles;
     // largest magnitudes of the operands of the products (shapes whose projections scan their own tiles):
     // amax_atomic: 2 x ABSMAX_SLOTS words gathered with atomics, directly before fdesc so that one range is
     // cleared; amax_slots: [P] Bbar, [H] Cc, then 2 x PREP_PASS_BLOCKS and 2 x amax_cd words of the passes
@@ -162,16 +159,11 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
     o.xbuf = o.chi = o.dCpart = o.dBpart = o.dApart = o.dDpart = o.fdesc = o.fdesc_bytes = 0;
     size_t dA_elems = o.plan.partial_elems;
     o.amax_atomic = o.amax_slots = o.rowmax = o.rowpart = 0; o.amax_cd = o.row_parts = 0;
-    o.jflags = o.jflag_bytes = o.jtiles = 0;
-    const bool join_y = !bwd && gemm_out_split_shape((int64_t)T, H, P);
-    if (join_y && !gemm_scan_shape_ok(Bt, L, P)) { o.jflag_bytes = gemm_join_flag_bytes((int64_t)T, H); o.jflags = off; off += up(o.jflag_bytes); }
     if (gemm_scan_shape_ok(Bt, L, P)) {              // tagged words of a projection that scans its own output
         static_assert(ABSMAX_SLOTS * 4 % ALIGN == 0, "the atomic slots and the tagged words are cleared as one range");
         o.amax_atomic = off; off += 2 * ABSMAX_SLOTS * 4;            // chi, then the saved states (gradient pass)
         o.fdesc_bytes = gemm_scan_desc_bytes(Bt, L, P);
         o.fdesc = off; off += up(o.fdesc_bytes);
-        // (1 KB of tagged words per tile: the flags of the joined K halves follow them without a gap)
-        if (join_y) { o.jflag_bytes = gemm_join_flag_bytes((int64_t)T, H); o.jflags = off; off += up(o.jflag_bytes); }
         o.amax_cd = o.nslab * (int)((H + 63) / 64);
         o.amax_slots = off; off += up((size_t)(P + H + 2 * PREP_PASS_BLOCKS + 2 * o.amax_cd) * 4);
         o.row_parts = (int)((2 * P + 127) / 128);
@@ -182,7 +174,6 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
     }
     o.yhalves = 0;
     if (!bwd) {
-        if (join_y) { o.jtiles = off; off += up(gemm_join_tile_bytes((int64_t)T, H)); }   // the partial tiles of one K half of y
         o.xbuf = off; off += up(T * P * 8);
     } else {
         o.chi = off; off += up(T * P * 8);
@@ -280,8 +271,7 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     pa.P = (int)P; pa.H = (int)H; pa.lam_bar = lam; pa.Bbar_ri = Bri; pa.Cc = Cc; pa.Bbar_c64 = nullptr;
     pa.hdr = (fused || lo.plan.nTB == 1) ? hdr : nullptr;
     // the atomic slots and the tagged words behind them are cleared in the same launch
-    if (fused) { pa.zero16 = reinterpret_cast<uint4 *>(ws + lo.amax_atomic); pa.n16 = (2 * ABSMAX_SLOTS * 4 + lo.fdesc_bytes + lo.jflag_bytes) / 16; }
-    else if (lo.jflags) { pa.zero16 = reinterpret_cast<uint4 *>(ws + lo.jflags); pa.n16 = lo.jflag_bytes / 16; }
+    if (fused) { pa.zero16 = reinterpret_cast<uint4 *>(ws + lo.amax_atomic); pa.n16 = (2 * ABSMAX_SLOTS * 4 + lo.fdesc_bytes) / 16; }
     // two scaled fp16 planes per operand: every operand of the two products brings its largest magnitude
     const bool two_planes = fused;
     unsigned *am_bbar = reinterpret_cast<unsigned *>(ws + lo.amax_slots), *am_cc = am_bbar + P;
@@ -341,12 +331,6 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     if (gelu_y) { g2.epilogue = 6; g2.C2 = gelu_y; }       // the S5 block: GELU(y) for the gate, same store
     if (gelu_y && gate_max) g2.c2_rowmax = gate_max->x1_rowmax;
     g2.splits = 1;
-    if (lo.jtiles) {
-        // too few 128x128 tiles for the chip: two K halves (twice the workgroups, half as long) that meet
-        // inside the launch; the second one of a pair adds the first one's partial tile and stores
-        g2.splits = 2;
-        g2.join = KJoin{reinterpret_cast<float *>(ws + lo.jtiles), reinterpret_cast<unsigned *>(ws + lo.jflags), &hdr->err, spin_limit()};
-    }
     HIP_TRY(launch_gemm(g2, s));
     MARK();
     return SSM_OK;
@@ -800,7 +784,7 @@ bool make_block_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, Bl
     o.gate_two_planes = false; o.x1_rowmax = o.wslots = 0; o.nwslots = 0;
     if (!bwd) {
         o.x1 = off; off += TH;
-        o.gate_two_planes = gate_two_planes_shape(Bt * L, H) && gemm_tile_tier(Bt * L, H, lo.jtiles ? 2 : 1) <= 1;
+        o.gate_two_planes = gate_two_planes_shape(Bt * L, H) && gemm_tile_tier(Bt * L, H, 1) <= 1;
         if (o.gate_two_planes) {
             o.nwslots = pass_pieces((size_t)H * H);
             o.x1_rowmax = off; off += up((size_t)(H / 64) * Bt * L * 4);

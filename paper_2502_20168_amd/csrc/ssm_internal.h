@@ -56,19 +56,6 @@ struct ScanEpilogue {
     unsigned spin_limit;
 };
 
-// A product that runs as two K halves whose partial tiles meet inside the launch (128x128 tiles only):
-// the half that is dispatched first writes its accumulators to `tiles` with device-scope write-through
-// stores and raises a flag per wavefront; the other half waits for the flag (bounded), adds them to its
-// own (a fixed order: bitwise reproducible) and runs the store function.  No second launch, no slabs.
-struct KJoin {
-    float *tiles;                 // [ceil(M/128) * ceil(N/128)][64][256] floats; null: not joined
-    unsigned *flags;              // [tiles][4], zero on entry
-    unsigned *err;                // set when the bounded wait gives up (the tile is then stored as NaN)
-    unsigned spin_limit;
-};
-inline size_t gemm_join_tile_bytes(int64_t M, int64_t N) { return (size_t)((M + 127) / 128) * ((N + 127) / 128) * 64 * 256 * 4; }
-inline size_t gemm_join_flag_bytes(int64_t M, int64_t N) { return (size_t)((M + 127) / 128) * ((N + 127) / 128) * 4 * 4; }
-
 struct GemmArgs {
     const float *A; int64_t lda; int a_kcontig;
     const float *B; int64_t ldb; int b_kcontig;
@@ -79,7 +66,6 @@ struct GemmArgs {
     int M, N, K, splits;
     ScanEpilogue scan;                               // epilogues 7 and 8
     AbsMax amaxA, amaxB;                             // largest magnitudes of A and B when known
-    KJoin join;                                      // splits == 2 with a store function (epilogue 1, 3, 4, 6)
     unsigned *c2_rowmax;                             // epilogue 6, tile tiers 0 and 1: [ceil(N/64)][M] words, the largest
                                                      // magnitude of every row of C2 per piece of 64 columns; or null
 };

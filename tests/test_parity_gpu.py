@@ -153,44 +153,12 @@ def test_resets_on_the_edges_of_tiles_and_chunks():
 
 @pytest.mark.parametrize("Bt,L,H,P", [(16, 256, 512, 256), (34, 128, 384, 288), (16, 256, 500, 256), (13, 100, 1200, 256)])
 def test_products_with_too_few_tiles_as_two_k_halves(Bt, L, H, P):
-    """y and du have 100-199 tiles of 128 x 128 at these shapes: each runs as two halves of the state
-    dimension (y: the halves of a tile meet inside the launch; du: a streaming sum, vector path and the
-    scalar path for a width that is no multiple of 4).  The last shape has ragged tiles in both
-    directions and separate scan kernels (three bf16 planes)."""
+    """y and du have 100-199 tiles of 128 x 128 at these shapes: y runs on 64 x 128 tiles, du (where it
+    shares its launch with the dBbar slabs only) as two halves of the state dimension that the parameter
+    epilogue's launch adds (vector path, and the scalar path for a width that is no multiple of 4).  The
+    last shape has ragged tiles in both directions and separate scan kernels (three bf16 planes)."""
     print("two K halves", Bt, L, H, P, flush=True)
     check_workload(wl.custom("halves", Bt, L, H, P, p_reset=0.02, with_x0=True, seed=53), backward=True)
-
-
-def test_bounded_wait_where_the_k_halves_of_y_meet():
-    """The half of a tile of y that finishes the tile waits for its partner's partial tile.  With a spin
-    limit of zero that wait gives up unless the partial is already there: the launch must terminate, and
-    either the status call reports it and y holds NaN, or y is right.  (L = 100: separate scan kernels
-    without a chain, so this is the only wait of the pass.)"""
-    import torch
-    w = wl.custom("spin0_join", 13, 100, 1200, 256, p_reset=0.02, seed=59)
-    inp = wl.gen_inputs(w)
-    d = ssm.to_device(inp)
-    par = (d["Lambda"], d["B"], d["C"], d["D"], d["log_delta"])
-    ws = ssm.alloc_workspace(w.Bt, w.L, w.H, w.P, False)
-    ref = orc.run_workload(inp, False)
-    old = ssm.ssm_set_spin_limit(0)
-    try:
-        out = ssm.ssm_scan_fwd(*par, d["u"], d["is_first"], d["x0"], workspace=ws)
-        status = ssm.ssm_workspace_status(ws)
-    finally:
-        ssm.ssm_set_spin_limit(old)
-    assert status in (ssm.SSM_OK, ssm.SSM_ERR_SCAN_TIMEOUT)
-    if status == ssm.SSM_OK:
-        assert_close(out["y"].cpu().numpy(), ref["y"], TOL_FWD, "spin0 join y")
-    else:
-        assert bool(torch.isnan(out["y"]).any()), "a give-up must poison its outputs"
-    assert not bool(torch.isnan(out["x"].real).any())          # the states do not depend on that wait
-    # with the default limit the same call on the same workspace is clean, right, and repeats bit for bit
-    a = ssm.ssm_scan_fwd(*par, d["u"], d["is_first"], d["x0"], workspace=ws)
-    assert ssm.ssm_workspace_status(ws) == ssm.SSM_OK
-    assert_close(a["y"].cpu().numpy(), ref["y"], TOL_FWD, "join y")
-    b = ssm.ssm_scan_fwd(*par, d["u"], d["is_first"], d["x0"], workspace=ws)
-    assert torch.equal(a["y"], b["y"])
 
 
 def test_flag_array_at_an_odd_address():
