@@ -979,11 +979,12 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
         // block from being hoisted as well, which would not fit the register budget
 #pragma unroll
         for (int i = 0; i < MI; ++i) {
-            unsigned gmax[16];                           // EPI 6: largest |GELU(y)| of the thread's 16 rows so far
-#pragma unroll
-            for (int r = 0; r < 16; ++r) gmax[r] = 0u;
+            unsigned rowmax = 0u;                        // EPI 6: largest |GELU(y)| of row rows16_half_index(l) so far
 #pragma unroll
             for (int j = 0; j < NI; ++j) {
+                unsigned gmax[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) gmax[r] = 0u;
                 const int col = n0 + wn * WN + j * 32 + li;
                 const long rbase = m0 + wm * WM + i * 32 + 4 * hh;
                 float e[16];
@@ -1002,9 +1003,13 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
                         if constexpr (EPI == 6) {
                             const float gy = gelu_value(y);
                             g.C2[row * g.ldc + col] = gy;
-                            gmax[r] = max(gmax[r], __float_as_uint(fabsf(gy)));
+                            gmax[r] = __float_as_uint(fabsf(gy));
                         }
                     }
+                }
+                // (reduced block by block: sixteen values per thread alive for one block only)
+                if constexpr (EPI == 6 && WN == 64) {
+                    if (g.c2_rowmax) rowmax = max(rowmax, rows16_half_max(gmax, l));
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -1012,7 +1017,7 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
                 // the product that consumes C2 stages its rows under a scale each: the largest magnitude of
                 // every row within this wavefront's 64 columns, as [piece of 64 columns][row]
                 if (g.c2_rowmax) {
-                    const unsigned m = rows16_half_max(gmax, l);
+                    const unsigned m = rowmax;
                     const int r = rows16_half_index(l);
                     const long row = m0 + wm * WM + i * 32 + 4 * hh + 8 * (r / 4) + (r % 4);
                     if ((l & 16) == 0 && row < g.M) g.c2_rowmax[(size_t)((n0 + wn * WN) / 64) * g.M + row] = m;
