@@ -49,6 +49,8 @@ hipError_t launch_gemm_pair(const GemmArgs &a, const GemmArgs &b, hipStream_t s,
         if (la == NN1 && items128(a) + items128(b) > 288)
             return launch_gemm_ws_variant<128, 128, 32, 2, 2, 4, 2, 2, NN1, TN0, 4>(a, s, &b, nullptr, order);
         if (la == NN1) return launch_gemm_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, NN1, TN0>(a, s, &b, nullptr, order);
+        // C^H dy with the dC slabs, or two K halves of Re(Bbar^H chi) with the dBbar slabs (separate scan kernels)
+        if (la == NN0) return launch_gemm_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, NN0, TN0>(a, s, &b, nullptr, order);
         // the adjoint of the gate: dz W^T with its store function, and the slabs of x1^T dz
         if (la == NT4) return launch_gemm_ws_variant<128, 128, 32, 2, 2, 8, 2, 2, NT4, TN0>(a, s, &b, nullptr, order);
     }

@@ -35,7 +35,28 @@ __device__ __forceinline__ float2 pow_block(float2 lam, int cy)
     return make_float2((float)r, (float)i);
 }
 
-template <bool REV>
+// v[e], e < 16, per lane -> the maximum over the 16 lanes of a group (lanes 16g .. 16g+15) of
+// v[group16_index(lane)]: halving exchanges between lanes that differ in bit 0, 1, 2, 3.
+__device__ __forceinline__ unsigned group16_max(unsigned (&v)[16], int lane)
+{
+#pragma unroll
+    for (int bit = 0; bit < 4; ++bit) {
+        const int n = 8 >> bit;
+        const bool up = (lane >> bit) & 1;
+#pragma unroll
+        for (int k = 0; k < n; ++k) {
+            const unsigned keep = up ? v[k + n] : v[k], send = up ? v[k] : v[k + n];
+            v[k] = max(keep, (unsigned)__shfl_xor((int)send, 1 << bit));
+        }
+    }
+    return v[0];
+}
+__device__ __forceinline__ int group16_index(int lane) { return 8 * (lane & 1) + 4 * ((lane >> 1) & 1) + 2 * ((lane >> 2) & 1) + ((lane >> 3) & 1); }
+
+// MAXOUT: the kernel also records the largest magnitude of every token row of its output (atomic maxima
+// into a.rowmax_out, zero on entry: the product that consumes the output stages every token under its own
+// scale) and of the whole output (a.amax_out, ABSMAX_SLOTS slots, zero on entry).
+template <bool REV, bool MAXOUT>
 __global__ void __launch_bounds__(SCAN_THREADS) scan_kernel(ScanArgs a)
 {
     constexpr int E = SCAN_E;
@@ -260,6 +281,11 @@ __global__ void __launch_bounds__(SCAN_THREADS) scan_kernel(ScanArgs a)
     // ---- level 1, second pass: the states themselves
     float2 xs = cfma(Aex, sX[lane], Sex);
     float2 acc = make_float2(0.f, 0.f);
+    unsigned rm[MAXOUT ? E : 1];                     // MAXOUT: magnitude of the value stored at step e
+    if constexpr (MAXOUT) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) rm[e] = 0u;
+    }
     if (full) {
         float2 *dst = a.out + first;
         if (plain) {
@@ -267,6 +293,7 @@ __global__ void __launch_bounds__(SCAN_THREADS) scan_kernel(ScanArgs a)
             for (int e = 0; e < E; ++e) {
                 xs = cfma(lam, xs, val[e]);
                 dst[e * stride] = xs;
+                if constexpr (MAXOUT) rm[e] = __float_as_uint(fmaxf(fabsf(xs.x), fabsf(xs.y)));
                 if constexpr (REV) {
                     // conj(x_{t-1}) * chi_t
                     acc.x = fmaf(xp[e].x, xs.x, fmaf(xp[e].y, xs.y, acc.x));
@@ -280,6 +307,7 @@ __global__ void __launch_bounds__(SCAN_THREADS) scan_kernel(ScanArgs a)
                 const float2 le = make_float2(r ? 0.f : lam.x, r ? 0.f : lam.y);
                 xs = cfma(le, xs, val[e]);
                 dst[e * stride] = xs;
+                if constexpr (MAXOUT) rm[e] = __float_as_uint(fmaxf(fabsf(xs.x), fabsf(xs.y)));
                 if constexpr (REV) {
                     const bool m = (mmask >> e) & 1u;
                     const float2 q = make_float2(m ? 0.f : xp[e].x, m ? 0.f : xp[e].y);
@@ -303,6 +331,7 @@ __global__ void __launch_bounds__(SCAN_THREADS) scan_kernel(ScanArgs a)
                 xs = ((rmask >> e) & 1u) ? val[e] : cfma(lam, xs, val[e]);
                 if (active) {
                     a.out[(rowbase + t) * a.P + p] = xs;
+                    if constexpr (MAXOUT) rm[e] = __float_as_uint(fmaxf(fabsf(xs.x), fabsf(xs.y)));
                     if constexpr (REV) {
                         if (!((mmask >> e) & 1u)) {
                             // conj(x_{t-1}) * chi_t
@@ -320,6 +349,21 @@ __global__ void __launch_bounds__(SCAN_THREADS) scan_kernel(ScanArgs a)
         }
     }
 
+    if constexpr (MAXOUT) {
+        // a group of 16 lanes holds 16 neighbouring states of the same 16 steps: one atomic per step and group
+        unsigned all = 0;
+#pragma unroll
+        for (int e = 0; e < E; ++e) all = max(all, rm[e]);
+        const unsigned m = group16_max(rm, tid);
+        const int e = group16_index(tid);
+        if (e < len) {
+            const int t = REV ? (L - 1 - (s0 + e)) : (s0 + e);
+            atomicMax(a.rowmax_out + rowbase + t, m);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) all = max(all, (unsigned)__shfl_xor((int)all, o));
+        if ((tid & 63) == 0) atomicMax(a.amax_out + (blockIdx.x * 4 + (tid >> 6)) % ABSMAX_SLOTS, all);
+    }
     if (REV) {
         // sum the chunks' contributions to dAbar; one partial row per (sequence, workgroup in time)
         sA[tid] = acc;
@@ -358,10 +402,12 @@ hipError_t launch_scan(const ScanArgs &a, bool reverse, hipStream_t s)
 {
     const int64_t nblocks = (int64_t)a.nPX * a.Bt * a.nTB;
     if (nblocks <= 0 || nblocks > 0x7fffffffLL || a.pxb * a.cy != SCAN_THREADS) return hipErrorInvalidValue;
-    if (reverse)
-        hipLaunchKernelGGL(scan_kernel<true>, dim3((unsigned)nblocks), dim3(SCAN_THREADS), 0, s, a);
-    else
-        hipLaunchKernelGGL(scan_kernel<false>, dim3((unsigned)nblocks), dim3(SCAN_THREADS), 0, s, a);
+    const bool maxout = a.rowmax_out != nullptr;
+    if (maxout && !a.amax_out) return hipErrorInvalidValue;
+    if (reverse && maxout) hipLaunchKernelGGL((scan_kernel<true, true>), dim3((unsigned)nblocks), dim3(SCAN_THREADS), 0, s, a);
+    else if (reverse) hipLaunchKernelGGL((scan_kernel<true, false>), dim3((unsigned)nblocks), dim3(SCAN_THREADS), 0, s, a);
+    else if (maxout) hipLaunchKernelGGL((scan_kernel<false, true>), dim3((unsigned)nblocks), dim3(SCAN_THREADS), 0, s, a);
+    else hipLaunchKernelGGL((scan_kernel<false, false>), dim3((unsigned)nblocks), dim3(SCAN_THREADS), 0, s, a);
     return hipGetLastError();
 }
 

@@ -82,6 +82,9 @@ struct Layout {
     // the largest magnitude of the saved states from a pass of the prep launch); otherwise they wait for the
     // launch of Re(Bbar^H chi), and the reverse scan records that magnitude on its way
     bool dc_early;
+    // separate scan kernels, products of more than 64 tiles: two scaled fp16 planes there too (the scan kernels
+    // record the largest magnitude of every token row of x and chi with atomics, the prep launch measures the rest)
+    bool planes2_unfused;
     bool slabs_first;        // launch of three products: the slabs' work items go first
     bool dc_first, db_first; // launches of two products (separate scan kernels): the slab items go first
     size_t hdr, lam, Bri, Cc, xbuf, chi, ticket, desc, dCpart, dBpart, dApart, dDpart, fdesc, fdesc_bytes, yhalves, total;
@@ -159,6 +162,19 @@ ssm_status make_layout(int64_t Bt, int64_t L, int64_t H, int64_t P, bool bwd, La
     o.xbuf = o.chi = o.dCpart = o.dBpart = o.dApart = o.dDpart = o.fdesc = o.fdesc_bytes = 0;
     size_t dA_elems = o.plan.partial_elems;
     o.amax_atomic = o.amax_slots = o.rowmax = o.rowpart = 0; o.amax_cd = o.row_parts = 0;
+    // (measured on eleven shapes: a gain of 6-16 % per step where both contraction lengths are long, H >= 512 and
+    // 2P >= 1024; with shorter ones the maxima the scan kernels and the prep launch then record cost more than the
+    // third fewer matrix instructions save: 3-9 % slower)
+    o.planes2_unfused = !gemm_scan_shape_ok(Bt, L, P) && !gemm_small_pair((int64_t)T, 2 * P) && !gemm_small_pair((int64_t)T, H) &&
+                        H >= 512 && P >= 512;
+    if (o.planes2_unfused) {
+        o.amax_atomic = off; off += 2 * ABSMAX_SLOTS * 4;            // chi / x (atomic slots of the scan kernels)
+        o.row_parts = 1;
+        o.rowpart = off; off += up(T * 4);                           // rows of x / chi, directly behind: one range is cleared
+        o.amax_cd = o.nslab * (int)((H + 63) / 64);
+        o.amax_slots = off; off += up((size_t)(P + H + 2 * PREP_PASS_BLOCKS + 2 * o.amax_cd) * 4);
+        o.rowmax = off; off += up(T * (size_t)((H + 63) / 64) * 4);
+    }
     if (gemm_scan_shape_ok(Bt, L, P)) {              // tagged words of a projection that scans its own output
         static_assert(ABSMAX_SLOTS * 4 % ALIGN == 0, "the atomic slots and the tagged words are cleared as one range");
         o.amax_atomic = off; off += 2 * ABSMAX_SLOTS * 4;            // chi, then the saved states (gradient pass)
@@ -272,8 +288,9 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     pa.hdr = (fused || lo.plan.nTB == 1) ? hdr : nullptr;
     // the atomic slots and the tagged words behind them are cleared in the same launch
     if (fused) { pa.zero16 = reinterpret_cast<uint4 *>(ws + lo.amax_atomic); pa.n16 = (2 * ABSMAX_SLOTS * 4 + lo.fdesc_bytes) / 16; }
+    if (lo.planes2_unfused) { pa.zero16 = reinterpret_cast<uint4 *>(ws + lo.amax_atomic); pa.n16 = (2 * ABSMAX_SLOTS * 4 + up((size_t)T * 4)) / 16; }
     // two scaled fp16 planes per operand: every operand of the two products brings its largest magnitude
-    const bool two_planes = fused;
+    const bool two_planes = fused || lo.planes2_unfused;
     unsigned *am_bbar = reinterpret_cast<unsigned *>(ws + lo.amax_slots), *am_cc = am_bbar + P;
     unsigned *rowmax = reinterpret_cast<unsigned *>(ws + lo.rowmax), *rowpart = reinterpret_cast<unsigned *>(ws + lo.rowpart);
     if (two_planes) {
@@ -305,6 +322,8 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
             g1.amaxA = AbsMax{nullptr, 0, rowmax, 1, T}; g1.amaxB = AbsMax{am_bbar, (int)P, nullptr, 0, 0};
             g1.scan.rowmax_out = rowpart;                    // of the states, for the output projection
         }
+    } else if (two_planes) {
+        g1.amaxA = AbsMax{nullptr, 0, rowmax, 1, T}; g1.amaxB = AbsMax{am_bbar, (int)P, nullptr, 0, 0};
     }
     HIP_TRY(launch_gemm(g1, s));
     MARK();
@@ -317,6 +336,10 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
         sa.Bt = (int)Bt; sa.L = (int)L; sa.P = (int)P;
         sa.pxb = lo.plan.pxb; sa.cy = lo.plan.cy; sa.nPX = lo.plan.nPX; sa.nTB = lo.plan.nTB;
         sa.spin_limit = spin_limit();
+        if (two_planes) {                                    // rows of the states, for the output projection
+            sa.rowmax_out = rowpart;
+            sa.amax_out = reinterpret_cast<unsigned *>(ws + lo.amax_atomic) + ABSMAX_SLOTS;
+        }
         HIP_TRY(launch_scan(sa, false, s));
     }
     MARK();
@@ -381,11 +404,13 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     pa.P = (int)P; pa.H = (int)H; pa.lam_bar = lam; pa.Bbar_ri = Bri; pa.Cc = Cc; pa.Bbar_c64 = nullptr;
     pa.hdr = (fused || lo.plan.nTB == 1) ? hdr : nullptr;
     if (fused) { pa.zero16 = reinterpret_cast<uint4 *>(ws + lo.amax_atomic); pa.n16 = (2 * ABSMAX_SLOTS * 4 + lo.fdesc_bytes) / 16; }
+    if (lo.planes2_unfused) { pa.zero16 = reinterpret_cast<uint4 *>(ws + lo.amax_atomic); pa.n16 = (2 * ABSMAX_SLOTS * 4 + up((size_t)T * 4)) / 16; }
     // dD slabs: sum_t dy[t,h] u[t,h] over row slabs, in the same launch
     pa.cd.a = dy; pa.cd.b = u; pa.cd.T = T; pa.cd.H = (int)H; pa.cd.nslab = lo.nslab; pa.cd.partial = dDpart;
     // two scaled fp16 planes per operand: dy and u are measured where dD reads them, chi and the saved
     // states where the reverse scan stores / reads them
-    const bool two_planes = fused;
+    const bool two_planes = fused || lo.planes2_unfused;
+    const bool x_pass = lo.dc_early || lo.planes2_unfused;       // the largest magnitude of the saved states from a pass of the prep launch
     unsigned *am_atomic = reinterpret_cast<unsigned *>(ws + lo.amax_atomic), *am_xsaved = am_atomic + ABSMAX_SLOTS;
     unsigned *am_bbar = reinterpret_cast<unsigned *>(ws + lo.amax_slots), *am_cc = am_bbar + P, *am_pass = am_cc + H;
     unsigned *am_dy = am_pass + 2 * PREP_PASS_BLOCKS, *am_u = am_dy + lo.amax_cd;
@@ -394,12 +419,12 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
     if (two_planes) {
         pa.bbar_max = am_bbar; pa.cc_max = am_cc; pa.cd_amax = am_dy; pa.cd_bmax = am_u;
         pa.cd_arow = rowmax;                 // [ceil(H/64)][T]: rows of dy, measured where the dD column dots read it
-        if (lo.dc_early) { pa.pass[0].x = xf; pa.pass[0].n = (size_t)T * 2 * P; pa.pass[0].slots = am_pass; pa.pass[0].nblocks = x_pieces; }
+        if (x_pass) { pa.pass[0].x = xf; pa.pass[0].n = (size_t)T * 2 * P; pa.pass[0].slots = am_pass; pa.pass[0].nblocks = x_pieces; }
     }
     // dy and chi enter C^H dy and Bbar^H chi with tokens as rows (a scale per token); the sums over tokens
     // (dC, dBbar) take one scale per matrix
     const AbsMax mx_dy{am_dy, lo.amax_cd, nullptr, 0, 0}, mx_u{am_u, lo.amax_cd, nullptr, 0, 0},
-                 mx_x{lo.dc_early ? am_pass : am_xsaved, lo.dc_early ? x_pieces : ABSMAX_SLOTS, nullptr, 0, 0},
+                 mx_x{x_pass ? am_pass : am_xsaved, x_pass ? x_pieces : ABSMAX_SLOTS, nullptr, 0, 0},
                  mx_chi{am_atomic, ABSMAX_SLOTS, nullptr, 0, 0},
                  mx_bbar{am_bbar, (int)P, nullptr, 0, 0}, mx_cc{am_cc, (int)H, nullptr, 0, 0},
                  mx_dy_rows{nullptr, 0, rowmax, (int)((H + 63) / 64), T}, mx_chi_rows{nullptr, 0, rowpart, lo.row_parts, T};
@@ -434,6 +459,7 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
         else HIP_TRY(launch_gemm(g3, s));
     } else {
         // dC needs only dy and the saved states: it shares the launch (whichever kind of work item the schedule model puts first)
+        if (two_planes) { g3.amaxA = mx_dy_rows; g3.amaxB = mx_cc; g4.amaxA = mx_dy; g4.amaxB = mx_x; }
         HIP_TRY(launch_gemm_pair(g3, g4, s, lo.dc_first));
     }
     MARK();
@@ -448,6 +474,7 @@ ssm_status run_bwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
         sa.Bt = (int)Bt; sa.L = (int)L; sa.P = (int)P;
         sa.pxb = lo.plan.pxb; sa.cy = lo.plan.cy; sa.nPX = lo.plan.nPX; sa.nTB = lo.plan.nTB;
         sa.spin_limit = spin_limit();
+        if (two_planes) { sa.rowmax_out = rowpart; sa.amax_out = am_atomic; }      // rows of chi for du, all of chi for dBbar
         HIP_TRY(launch_scan(sa, true, s));
     }
     MARK();

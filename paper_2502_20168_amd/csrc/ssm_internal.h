@@ -159,6 +159,8 @@ struct ScanArgs {
     uint32_t *err;           // &WsHeader::err (the magic word follows it)
     int Bt, L, P, pxb, cy, nPX, nTB;
     uint32_t spin_limit;
+    unsigned *rowmax_out;    // [Bt*L] or null: atomic maximum of the magnitudes of every token row of `out`, zero on entry
+    unsigned *amax_out;      // [ABSMAX_SLOTS] (with rowmax_out): atomic maximum of the magnitudes of `out`, zero on entry
 };
 hipError_t launch_scan(const ScanArgs &a, bool reverse, hipStream_t s);
 // workspace layout of the scan-level entry points: header, ticket counters, descriptors, partial rows

@@ -161,6 +161,37 @@ def test_products_with_too_few_tiles_as_two_k_halves(Bt, L, H, P):
     check_workload(wl.custom("halves", Bt, L, H, P, p_reset=0.02, with_x0=True, seed=53), backward=True)
 
 
+@pytest.mark.parametrize("Bt,L,H,P", [(40, 100, 512, 512), (23, 100, 640, 512), (12, 300, 1024, 512)])
+def test_separate_scan_kernels_with_two_fp16_planes(Bt, L, H, P):
+    """Sequences that are not whole 128-step tiles, with long contraction lengths (H >= 512, P >= 512) and more
+    than 64 tiles per product: the scan kernels record the largest magnitude of every token row of x and chi,
+    and all six products stage two scaled fp16 planes.  Whole tiles, ragged token tiles, and a chain of scan
+    workgroups along time (L = 300)."""
+    print("unfused two planes", Bt, L, H, P, flush=True)
+    check_workload(wl.custom("unfused2", Bt, L, H, P, p_reset=0.02, with_x0=True, seed=61), backward=True)
+
+
+def test_separate_scan_kernels_two_planes_wide_range_between_tokens():
+    """The same path with token magnitudes spread over six decades (every token row of u, x, dy and chi gets its
+    own scale): per-tensor checks would hide the small tokens, so du and y are compared row by row."""
+    w = wl.custom("unfused2_range", 40, 100, 512, 512, p_reset=0.02, with_x0=False, seed=67)
+    inp = wl.gen_inputs(w)
+    rng = np.random.Generator(np.random.PCG64(5))
+    scale = (10.0 ** rng.uniform(-3, 3, size=(w.Bt, 1, 1))).astype(np.float32)      # one magnitude per sequence
+    inp["u"] = (inp["u"] * scale).astype(np.float32)
+    inp["dy"] = (inp["dy"] * scale).astype(np.float32)
+    d = ssm.to_device(inp)
+    par = (d["Lambda"], d["B"], d["C"], d["D"], d["log_delta"])
+    f = ssm.ssm_scan_fwd(*par, d["u"], d["is_first"], d["x0"])
+    g = ssm.ssm_scan_bwd(*par, d["u"], d["is_first"], d["x0"], f["x"], d["dy"])
+    ref = orc.run_workload(inp, True)
+    for name, got, tol in (("y", f["y"], TOL_FWD), ("du", g["du"], TOL_GRAD)):
+        a = got.cpu().numpy().astype(np.float64).reshape(w.Bt, -1)
+        r = ref[name].astype(np.float64).reshape(w.Bt, -1)
+        rel = np.linalg.norm(a - r, axis=1) / np.linalg.norm(r, axis=1)
+        assert rel.max() <= tol, "%s: worst sequence %d, relative error %.3e" % (name, int(rel.argmax()), rel.max())
+
+
 def test_flag_array_at_an_odd_address():
     """is_first only needs byte alignment: the 16-byte flag loads of the scanning tiles and of the
     scan kernel must fall back to byte loads for a buffer that starts at an odd address."""
