@@ -90,7 +90,8 @@ hipError_t launch_gemm(const GemmArgs &g, hipStream_t s);
 // the instantiations of the kernel for one problem per launch (tier 0: 128x128x32 tiles, 1: 64x128x32, 2: 64x64x64)
 hipError_t gemm_dispatch_two_planes(const GemmArgs &g, int tier, hipStream_t s);
 hipError_t gemm_dispatch_three_planes(const GemmArgs &g, int tier, hipStream_t s);
-// the output projection runs as two K halves into two slabs plus a streaming sum at this shape
+// a T x H product with a K loop of 2P has 100-199 tiles of 128x128 and a K loop long enough to halve (du next to
+// the dBbar slabs at shapes with separate scan kernels runs as two K halves then)
 bool gemm_out_split_shape(int64_t T, int64_t H, int64_t P);
 // two independent problems in one launch (falls back to two launches for layouts without a
 // paired instantiation)
