@@ -40,8 +40,12 @@
  *     product, the weights and the operands of the sums over tokens one per matrix.  Under one scale
  *     with largest magnitude m an element a is held with an absolute error of at most
  *     max(2^-22 |a|, 2^-39 m): elements more than 2^17 below m are fixed-point, not floating-point.
+ *     The same staging is used at other sequence lengths when H >= 512, P >= 512 and Bt * L is large
+ *     enough that every product has more than 64 tiles of 128 x 128 (the scan kernels then record the
+ *     largest magnitudes of x and chi), and by ssm_half_glu_* / ssm_block_* for the gate's products at
+ *     widths that are multiples of 64 from 512 on with at least 200 tiles of 64 tokens x 128 columns.
  *     Everywhere else every operand is split exactly into three bf16 planes (six partial products).
- *     At the shapes named above the input projection and C^H dy also scan their own output tiles
+ *     At the shapes named first the input projection and C^H dy also scan their own output tiles
  *     (no scan kernel, no round trip of Bbar u and C^H dy through memory).  Infinite inputs give NaN.
  */
 #ifndef SSM_H_
