@@ -746,13 +746,15 @@ def test_step_mode_adjoint_rollout_equals_oracle_gradient(Bt, H, P, steps):
     assert_close(du1.cpu().numpy()[:, None], ref1["du"], TOL_GRAD, "step du (single)")
 
 
-@pytest.mark.parametrize("Bt,L,H,P", [(4, 256, 128, 96), (2, 1500, 64, 80), (4, 512, 32, 840), (128, 16, 32, 1024)])
+@pytest.mark.parametrize("Bt,L,H,P", [(4, 256, 128, 96), (2, 1500, 64, 80), (4, 512, 32, 840), (128, 16, 32, 1024),
+                                      (24, 100, 512, 512)])
 def test_captured_graph_replays_equal_eager(Bt, L, H, P):
     """The non-profiled entry points only enqueue kernels (no allocation, no memset, no wait), so
     one forward + gradient pass can be captured into a HIP graph.  Every replay, with eager work
     and synchronisations of the program in between, must reproduce the eager results bit for bit
     (second shape: several workgroups along time, i.e. the clear kernel and the look-back; third and
-    fourth: the projections scan their own tiles, as a chain of tiles and with whole sequences per tile)."""
+    fourth: the projections scan their own tiles, as a chain of tiles and with whole sequences per tile; fifth:
+    separate scan kernels that record the row maxima of their output with atomics, two fp16 planes)."""
     import torch
     w = wl.custom("graph", Bt, L, H, P, backward=True, p_reset=0.01, with_x0=True, seed=61)
     d = ssm.to_device(wl.gen_inputs(w))
