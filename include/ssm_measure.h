@@ -42,6 +42,21 @@ ssm_status ssm_scan_bwd_profiled(const ssm_c64 *Lambda, const ssm_c64 *B, const 
                                  void *workspace, size_t ws_bytes, void *stream,
                                  float *stage_ms /* host, [SSM_BWD_STAGES] */);
 
+/* What ssm_scan_fwd / ssm_scan_bwd would launch for a shape: host logic only, no GPU call.  Writes
+ * SSM_PLAN_FIELDS int32 values to the HOST array out:
+ *   [0] 1 when the input projection and C^H dy scan their own output tiles (no scan kernel)
+ *   [1] planes per operand of the layer's products: 2 (scaled fp16) or 3 (bf16)
+ *   [2] K slabs of dC, [3] K slabs of dBbar
+ *   [4] gradient pass: 3 = du, dBbar slabs and dC slabs in one launch; 2 = two launches of two products
+ *   [5] 1 when the slab work items take the first slots of the launch of [4] == 3
+ *   [6], [7] the same for the launches of C^H dy with dC and of du with dBbar when [4] == 2
+ *   [8] 1 when du runs as two K halves that the parameter epilogue's launch adds
+ *   [9] tile tier of the input projection, [10] of the output projection (0: 128x128x32, 1: 64x128x32, 2: 64x64x64)
+ *   [11] workgroups along time of the scan kernels (1: no look-back; unused when [0] == 1)
+ * Returns SSM_ERR_INVALID_ARG / SSM_ERR_UNSUPPORTED for shapes the library does not take.           */
+#define SSM_PLAN_FIELDS 12
+ssm_status ssm_plan_describe(int64_t Bt, int64_t L, int64_t H, int64_t P, int32_t *out /* host */);
+
 #ifdef __cplusplus
 }
 #endif

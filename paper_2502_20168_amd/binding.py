@@ -33,7 +33,7 @@ EXPORTS = ("ssm_strerror", "ssm_version", "ssm_workspace_bytes", "ssm_discretize
            "ssm_scan_bwd_profiled", "ssm_workspace_status", "ssm_step_plan_bytes", "ssm_step_prepare", "ssm_step",
            "ssm_step_bwd", "ssm_lambda_return", "ssm_lambda_return_bwd", "ssm_half_glu_workspace_bytes", "ssm_half_glu_fwd",
            "ssm_half_glu_bwd", "ssm_block_workspace_bytes", "ssm_block_fwd", "ssm_block_bwd", "ssm_set_spin_limit",
-           "ssm_scan_states_noalloc", "ssm_scan_states_noalloc_status")
+           "ssm_scan_states_noalloc", "ssm_scan_states_noalloc_status", "ssm_plan_describe")
 
 _lib = None
 _vp, _i64, _sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_size_t
@@ -516,6 +516,23 @@ def ssm_block_bwd(Lambda, B, C, D, log_delta, W, u, is_first, x0, x, y, gate, do
     if rc != SSM_OK:
         raise SsmError(rc, "ssm_block_bwd")
     return o
+
+
+SSM_PLAN_FIELDS = 12
+PLAN_FIELD_NAMES = ("scans_in_projections", "planes", "slabs_dC", "slabs_dBbar", "products_per_gradient_launch",
+                    "slabs_first", "dC_first", "dBbar_first", "du_as_two_k_halves", "tier_in", "tier_out", "scan_time_blocks")
+
+
+def ssm_plan_describe(Bt: int, L: int, H: int, P: int) -> Dict[str, int]:
+    """What ssm_scan_fwd / ssm_scan_bwd would launch for a shape (host logic only, needs no GPU)."""
+    out = (ctypes.c_int32 * SSM_PLAN_FIELDS)()
+    fn = lib().ssm_plan_describe
+    fn.restype = ctypes.c_int
+    fn.argtypes = [_i64, _i64, _i64, _i64, ctypes.POINTER(ctypes.c_int32)]
+    rc = fn(Bt, L, H, P, out)
+    if rc != SSM_OK:
+        raise SsmError(rc, "ssm_plan_describe")
+    return dict(zip(PLAN_FIELD_NAMES, [int(v) for v in out]))
 
 
 def ssm_workspace_status(workspace, stream=None) -> int:

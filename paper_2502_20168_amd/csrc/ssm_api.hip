@@ -633,6 +633,28 @@ ssm_status ssm_scan_bwd_profiled(const ssm_c64 *Lambda, const ssm_c64 *B, const 
     return ok ? SSM_OK : SSM_ERR_HIP;
 }
 
+ssm_status ssm_plan_describe(int64_t Bt, int64_t L, int64_t H, int64_t P, int32_t *out)
+{
+    if (!out) return SSM_ERR_INVALID_ARG;
+    Layout lo;
+    ssm_status st = make_layout(Bt, L, H, P, true, lo);
+    if (st != SSM_OK) return st;
+    const bool fused = gemm_scan_shape_ok(Bt, L, P);
+    const int64_t T = Bt * L;
+    out[0] = fused ? 1 : 0;
+    out[1] = (fused || lo.planes2_unfused) ? 2 : 3;
+    out[2] = lo.splitC; out[3] = lo.splitB;
+    out[4] = (fused && !lo.dc_early) ? 3 : 2;
+    out[5] = lo.slabs_first ? 1 : 0;
+    out[6] = (!fused && lo.dc_first) ? 1 : 0;
+    out[7] = (lo.yhalves != 0 || (!fused && lo.db_first)) ? 1 : 0;
+    out[8] = lo.yhalves != 0 ? 1 : 0;
+    out[9] = fused ? 0 : gemm_tile_tier(T, 2 * P, 1);
+    out[10] = gemm_tile_tier(T, H, 1);
+    out[11] = lo.plan.nTB;
+    return SSM_OK;
+}
+
 ssm_status ssm_scan_states(const ssm_c64 *A_bar, ssm_c64 *v, const uint8_t *is_first,
                            const ssm_c64 *x0, int64_t Bt, int64_t L, int64_t P, ssm_c64 *x_last,
                            void *workspace, size_t ws_bytes, void *stream)
