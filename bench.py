@@ -71,6 +71,9 @@ def main():
     ap.add_argument("--path-only", action="store_true",
                     help="skip the sections beside the hot path (scan kernels alone, block_ops, step_mode, s5_block): "
                          "used for the rocprofv3 runs so that every kernel in the trace belongs to one role")
+    ap.add_argument("--scan-only", action="store_true",
+                    help="run only the two scan kernels at working sets past the last-level cache (scan_large) and print "
+                         "their figures: the command behind profiles/scan_kernels_large_working_set.md")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -85,6 +88,16 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     ssm.lib()                                  # fail loudly if the HIP library is missing
+    if args.scan_only:
+        if args.counter_calibration:
+            src = torch.randn(16 << 20, device="cuda")
+            dst = torch.empty_like(src)
+            for _ in range(5):
+                torch.add(src, 1.0, out=dst)
+            torch.cuda.synchronize()
+            del src, dst
+        print(json.dumps({"scan_large": scan_large(ssm, torch, wl)}))
+        return
     w = wl.CONFIGS[args.config]
     Bt, L, H, P = w.Bt, w.L, w.H, w.P
     T = w.tokens
