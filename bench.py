@@ -163,7 +163,7 @@ def main():
     # it matters at the small shapes, where the eight or nine launches of a step are shorter than their enqueue
     graph_ms = graph_time_ms(torch, lambda i: step(), 10)
     graph_replay = {"ms_per_step": round(graph_ms, 4), "Mtokens_per_s": round(T / (graph_ms * 1e-3) / 1e6, 3),
-                    "note": "ten steps captured into one HIP graph, one replay timed with events; not the headline value"}
+                    "note": "ten steps captured into one HIP graph, the median of five replays timed with events; not the headline value"}
 
     # ---- per-kernel durations from HIP events recorded on the launch stream (library side)
     fs = np.zeros(ssm.SSM_FWD_STAGES)
@@ -345,7 +345,8 @@ def graph_time_ms(torch, fn, iters):
     """Average duration of one fn(i) call, i = 0 .. iters-1, on the GPU: the calls are captured into
     one HIP graph and the graph is replayed, so the launches follow each other without the host's
     per-call cost (argument marshalling takes about as long as one of the small kernels runs).
-    Events bracket one replay."""
+    Events bracket one replay; the median of five replays is reported (a single replay now and then
+    takes several times as long as the others)."""
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     graph = torch.cuda.CUDAGraph()
@@ -359,12 +360,15 @@ def graph_time_ms(torch, fn, iters):
     torch.cuda.synchronize()
     graph.replay()
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    graph.replay()
-    e1.record()
-    torch.cuda.synchronize()
-    return e0.elapsed_time(e1) / iters
+    times = []
+    for _ in range(5):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        times.append(e0.elapsed_time(e1))
+    return sorted(times)[len(times) // 2] / iters
 
 
 def step_mode(ssm, torch, d, H, P, Bt=1024, horizon=10):
