@@ -542,12 +542,24 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
         // exclusive combine over the chunks of the same sequence that come earlier in scan order
         const int before = whole_seqs ? (REV ? (a.L - RC - t0) / RC : t0 / RC) : ql;
         const int ql_first = ql - before;
+        // (all chunk states are read first, whether this thread folds them or not: left inside the
+        // condition below, the reads end up in its branch and a thread waits for LDS once per chunk
+        // it folds, the last chunk's wavefront seven times in a row, and the tile's aggregate goes out late)
+        float2 Sc[NCH - 1];
+        unsigned Rc[NCH - 1];
 #pragma unroll
         for (int j = 0; j < NCH - 1; ++j) {
-            const float2 Sj = lds.cS[j * 64 + c];
-            const float2 Aj = lds.cAny[j * 64 + c] ? make_float2(0.f, 0.f) : lrc;
-            const float2 nS = cfma(Aj, Sex, Sj), nA = cmul(Aj, Aex);
-            if (j >= ql_first && j < ql) { Sex = nS; Aex = nA; }
+            Sc[j] = lds.cS[j * 64 + c];
+            Rc[j] = lds.cAny[j * 64 + c];
+            asm volatile("" : "+v"(Sc[j].x), "+v"(Sc[j].y), "+v"(Rc[j]));
+        }
+#pragma unroll
+        for (int j = 0; j < NCH - 1; ++j) {
+            const float2 Aj = Rc[j] ? make_float2(0.f, 0.f) : lrc;
+            const float2 nS = cfma(Aj, Sex, Sc[j]), nA = cmul(Aj, Aex);
+            const bool take = j >= ql_first && j < ql;
+            Sex = make_float2(take ? nS.x : Sex.x, take ? nS.y : Sex.y);
+            Aex = make_float2(take ? nA.x : Aex.x, take ? nA.y : Aex.y);
         }
         if (leader) {
             // the tile's aggregate goes out before anything is waited for
