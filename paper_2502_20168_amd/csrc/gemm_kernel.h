@@ -954,17 +954,16 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
     }
 
     if constexpr (NPL == 2) {
-        // the power of two that takes both operand scales off again, in two factors (either alone stays a
-        // normal number whenever the result does)
+        // the power of two that takes both operand scales off again (their sum can leave the exponent range of
+        // a single factor: one exponent adjustment per element, exact like a multiplication by the power)
+        const int eb = rowexp(BM);
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int st = rowexp(wm * WM + i * 32 + 8 * (r / 4) + 4 * hh + (r % 4)) + rowexp(BM);
-                const int s1 = st >> 1;
-                const float f1 = pow2f(-s1), f2 = pow2f(s1 - st);
+                const int st = rowexp(wm * WM + i * 32 + 8 * (r / 4) + 4 * hh + (r % 4)) + eb;
 #pragma unroll
-                for (int j = 0; j < NI; ++j) acc[i][j][r] = (acc[i][j][r] * f1) * f2;
+                for (int j = 0; j < NI; ++j) acc[i][j][r] = __builtin_ldexpf(acc[i][j][r], -st);
             }
     }
     if constexpr (EPI == 7 || EPI == 8) {
