@@ -37,6 +37,16 @@ hipError_t gemm_dispatch_two_planes(const GemmArgs &a, int tier, hipStream_t s)
         return launch_gemm_ws_variant<128, 128, 32, 2, 2, 8, 2, NPL, gemm_layout(true, false, 8)>(a, s);
     }
     // (a plain product with several rounds of long work items gains nothing from two workgroups per CU: measured)
+    // The output projection (both operands k-contiguous, D u added in the store; K = 2P is its longest
+    // contraction) walks K in steps of 64 on 64x128 tiles where K allows: half the workgroup barriers per
+    // product (16 x 256 tokens, H = P = 512: -2 to -3 us per step; the other layouts of this tier gain nothing)
+    const int lay = gemm_layout_of(a);
+    const bool out_like = lay == gemm_layout(true, true, 1) || lay == gemm_layout(true, true, 6);
+    if (tier == 1 && out_like && a.K % 64 == 0 && a.splits <= 1) {
+        if (lay == gemm_layout(true, true, 1)) return launch_gemm_ws_variant<64, 128, 64, 2, 2, 8, 2, NPL, gemm_layout(true, true, 1)>(a, s);
+        return launch_gemm_ws_variant<64, 128, 64, 2, 2, 8, 2, NPL, gemm_layout(true, true, 6)>(a, s);
+    }
+    // (the same on 128x128 tiles: no change, measured)
     if (tier == 0) return dispatch_tile<128, 128, 32>(a, s);
     if (tier == 1) return dispatch_tile<64, 128, 32>(a, s);
     return dispatch_tile<64, 64, 64>(a, s);
