@@ -479,7 +479,9 @@ __device__ __forceinline__ uint2 scan_flag_masks(const ScanEpilogue &a, int tid,
 // runs through the same function and so meets the others at every workgroup barrier: all barriers stand
 // at the top level of this function under conditions that are uniform over the workgroup, all work
 // sits in blocks that a passive wavefront skips.
-template <bool REV, bool PASSIVE>
+// REREAD (reverse scan): the second pass reads the tile's values from LDS again instead of keeping them in
+// registers across the wait for the predecessors (for the register budget of two workgroups per CU).
+template <bool REV, bool PASSIVE, bool REREAD = false>
 __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanLds &lds, int tid, int m0, int n0, int tile,
                                                    const ScanSaved &saved, uint2 masks)
 {
@@ -635,6 +637,15 @@ __device__ __forceinline__ void scan_epilogue_body(const GemmDev &g, const ScanL
             }
             if (active && a.x_last && t0 + RC == a.L) a.x_last[(long)b * a.P + p] = xs;
         } else {
+            if constexpr (REREAD) {
+                // (kept in registers across the wait for the predecessors, the values would crowd out the saved
+                // states: 193 spilled registers instead of 66 within a budget of 128)
+#pragma unroll
+                for (int e = 0; e < RC; ++e) {
+                    val[e] = *reinterpret_cast<const float2 *>(lds.tile + (q * RC + e) * SCAN_TS + 2 * c);
+                    asm volatile("" : "+v"(val[e].x), "+v"(val[e].y));
+                }
+            }
             // also dAbar += [not is_first_t] conj(x_{t-1}) chi_t
 #pragma unroll
             for (int e = RC - 1; e >= 0; --e) {
@@ -835,11 +846,11 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
                 // the first producers scan with the consumers: barriers 1 and 2 frame the staging of the tile
                 __syncthreads();
                 __syncthreads();
-                scan_epilogue_body<EPI == 8, false>(g, ScanLds(smem), tid, m0, n0, scan_tile, saved, masks);
+                scan_epilogue_body<EPI == 8, false, EPI == 8 && !SAVED_EARLY>(g, ScanLds(smem), tid, m0, n0, scan_tile, saved, masks);
             } else {
                 __syncthreads();
                 __syncthreads();
-                scan_epilogue_body<EPI == 8, true>(g, ScanLds(smem), tid, m0, n0, scan_tile, saved, masks);
+                scan_epilogue_body<EPI == 8, true, EPI == 8 && !SAVED_EARLY>(g, ScanLds(smem), tid, m0, n0, scan_tile, saved, masks);
             }
         }
         return;
@@ -979,7 +990,7 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
                 for (int r = 0; r < 16; ++r)
                     lds.tile[(wm * WM + i * 32 + 8 * (r / 4) + 4 * hh + (r % 4)) * SCAN_TS + wn * WN + j * 32 + li] = acc[i][j][r];
         __syncthreads();                             // barrier 2: the tile is staged
-        scan_epilogue_body<EPI == 8, false>(g, lds, tid, m0, n0, scan_tile, saved, masks);
+        scan_epilogue_body<EPI == 8, false, EPI == 8 && !SAVED_EARLY>(g, lds, tid, m0, n0, scan_tile, saved, masks);
         return;
     }
     float *Cz = g.C + (long)z * g.M * g.ldc;
