@@ -108,6 +108,8 @@ SCANNING_TILES = [
     ("seven_sequences", 7, 512, 20, 520, 0.0, False, True),
     ("every_step_resets", 8, 256, 16, 1024, 1.0, True, True),
     ("no_reset_no_x0", 8, 384, 16, 640, 0.0, False, False),
+    # more tiles than CUs with chains: both projections run two workgroups per CU
+    ("chains_in_more_than_one_round_of_tiles", 5, 1024, 24, 520, 0.01, False, True),
     # several whole sequences per 128-token tile: no chain, a sequence starts at a chunk inside the tile
     ("eight_sequences_per_tile", 256, 16, 16, 1024, 0.05, False, True),
     ("four_sequences_per_tile", 128, 32, 24, 520, 0.05, True, True),
@@ -534,12 +536,14 @@ def test_bounded_wait_reports_instead_of_hanging():
     assert not bool(torch.isnan(out["y"]).any())
 
 
-def test_bounded_wait_inside_the_scanning_projections():
+@pytest.mark.parametrize("Bt", [1, 2])
+def test_bounded_wait_inside_the_scanning_projections(Bt):
     """The same for the waits along the chain of tiles of a sequence (32 tiles here) inside the input
     projection and inside C^H dy: with a spin limit of zero both passes terminate; each reports and
-    poisons, or is right."""
+    poisons, or is right.  One sequence: 256 tiles, one workgroup per CU; two: 512 tiles, the variants with
+    two workgroups per CU."""
     import torch
-    w = wl.custom("spin0_tiles", 1, 4096, 16, 512, p_reset=0.001, with_x0=True, seed=5)
+    w = wl.custom("spin0_tiles", Bt, 4096, 16, 512, p_reset=0.001, with_x0=True, seed=5)
     inp = wl.gen_inputs(w)
     d = ssm.to_device(inp)
     par = (d["Lambda"], d["B"], d["C"], d["D"], d["log_delta"])
