@@ -110,6 +110,8 @@ SCANNING_TILES = [
     ("no_reset_no_x0", 8, 384, 16, 640, 0.0, False, False),
     # more tiles than CUs with chains: both projections run two workgroups per CU
     ("chains_in_more_than_one_round_of_tiles", 5, 1024, 24, 520, 0.01, False, True),
+    # more tiles than the chip holds at once (2 x 256): later tiles start when earlier ones have left
+    ("chains_in_more_tiles_than_are_resident", 9, 2048, 16, 512, 0.002, False, True),
     # several whole sequences per 128-token tile: no chain, a sequence starts at a chunk inside the tile
     ("eight_sequences_per_tile", 256, 16, 16, 1024, 0.05, False, True),
     ("four_sequences_per_tile", 128, 32, 24, 520, 0.05, True, True),
