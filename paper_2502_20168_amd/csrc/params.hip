@@ -106,6 +106,29 @@ __device__ __forceinline__ void coldot_block(const ColDotArgs &a, int colblock, 
     const int cc = okc ? col : 0;
     unsigned *arow_cb = arow ? arow + (size_t)colblock * a.T : nullptr;
     long t = r0 + ph;
+    for (; t + 60 < r1; t += 64) {           // sixteen independent row pairs in flight (one trip to memory for 64 rows of a slab)
+        float av[16], bv[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            av[j] = a.a[(t + 4 * j) * a.H + cc];
+            bv[j] = a.b[(t + 4 * j) * a.H + cc];
+        }
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {        // the arithmetic in the order of the loop below
+            float a0 = av[4 * g], a1 = av[4 * g + 1], a2 = av[4 * g + 2], a3 = av[4 * g + 3];
+            float b0 = bv[4 * g], b1 = bv[4 * g + 1], b2 = bv[4 * g + 2], b3 = bv[4 * g + 3];
+            if (!okc) { a0 = a1 = a2 = a3 = 0.f; b0 = b1 = b2 = b3 = 0.f; }
+            s = fmaf(a0, b0, s); s = fmaf(a1, b1, s); s = fmaf(a2, b2, s); s = fmaf(a3, b3, s);
+            ma = fmaxf(fmaxf(ma, fmaxf(fabsf(a0), fabsf(a1))), fmaxf(fabsf(a2), fabsf(a3)));
+            mb = fmaxf(fmaxf(mb, fmaxf(fabsf(b0), fabsf(b1))), fmaxf(fabsf(b2), fabsf(b3)));
+            if (arow_cb) {
+                const int l = tid & 63;
+                const unsigned m = wave_max4(__float_as_uint(fabsf(a0)), __float_as_uint(fabsf(a1)), __float_as_uint(fabsf(a2)),
+                                             __float_as_uint(fabsf(a3)), l);
+                if (l < 4) arow_cb[t + 16 * g + 4 * (2 * (l & 1) + (l >> 1))] = m;
+            }
+        }
+    }
     for (; t + 12 < r1; t += 16) {           // four independent row pairs in flight
         float a0 = a.a[t * a.H + cc], b0 = a.b[t * a.H + cc];
         float a1 = a.a[(t + 4) * a.H + cc], b1 = a.b[(t + 4) * a.H + cc];
@@ -144,54 +167,65 @@ __device__ __forceinline__ void coldot_block(const ColDotArgs &a, int colblock, 
     }
 }
 
-// slots[row] = largest magnitude of row `row` of x[n / rowlen][rowlen]: a wavefront takes four rows at a
-// time (all loads of the four rows in flight before the first reduction)
+// slots[row] = largest magnitude of row `row` of x[n / rowlen][rowlen].  A wavefront takes RW rows at a time
+// (all their loads in flight before the first reduction): one row each while there are at least as many
+// wavefronts as rows, else four -- measured on 4096 cold rows of 512 values: 2.9 us with one row per
+// wavefront in 1024 workgroups, 4.7 us with four rows per wavefront in 256.
+template <int RW>
+__device__ __forceinline__ void absmax_rows_batch(const PrepArgs::Pass &q, size_t row0, size_t rows, int lane)
+{
+    float m[RW];
+#pragma unroll
+    for (int r = 0; r < RW; ++r) m[r] = 0.f;
+    if (q.vec && q.rowlen <= 512) {
+        // up to two float4 per lane and row: 2 RW independent loads
+        float4 a[RW][2];
+#pragma unroll
+        for (int r = 0; r < RW; ++r)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int i = lane + 64 * h;
+                const bool ok = row0 + r < rows && i < q.rowlen / 4;
+                const float4 *x4 = reinterpret_cast<const float4 *>(q.x + (ok ? row0 + r : 0) * (size_t)q.rowlen);
+                const float4 t = x4[ok ? i : 0];
+                a[r][h] = ok ? t : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+        for (int r = 0; r < RW; ++r)
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+                m[r] = fmaxf(m[r], fmaxf(fmaxf(fabsf(a[r][h].x), fabsf(a[r][h].y)), fmaxf(fabsf(a[r][h].z), fabsf(a[r][h].w))));
+    } else {
+#pragma unroll
+        for (int r = 0; r < RW; ++r) {
+            if (row0 + r >= rows) break;
+            const float *x = q.x + (row0 + r) * (size_t)q.rowlen;
+            if (q.vec) {
+                const float4 *x4 = reinterpret_cast<const float4 *>(x);
+                for (int i = lane; i < q.rowlen / 4; i += 64) {
+                    const float4 t = x4[i];
+                    m[r] = fmaxf(m[r], fmaxf(fmaxf(fabsf(t.x), fabsf(t.y)), fmaxf(fabsf(t.z), fabsf(t.w))));
+                }
+            } else {
+                for (int i = lane; i < q.rowlen; i += 64) m[r] = fmaxf(m[r], fabsf(x[i]));
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < RW; ++r) {
+        const unsigned u = wave_max_lane63(__float_as_uint(m[r]));
+        if (lane == 63 && row0 + r < rows) q.slots[row0 + r] = u;
+    }
+}
 __device__ __forceinline__ void absmax_rows_block(const PrepArgs::Pass &q, int piece)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const size_t rows = q.n / (size_t)q.rowlen;
     const size_t wid = (size_t)piece * 4 + wave, nw = (size_t)q.nblocks * 4;
-    for (size_t row0 = wid * 4; row0 < rows; row0 += nw * 4) {
-        float m[4] = {0.f, 0.f, 0.f, 0.f};
-        if (q.vec && q.rowlen <= 512) {
-            // up to two float4 per lane and row: eight independent loads
-            float4 a[4][2];
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int i = lane + 64 * h;
-                    const bool ok = row0 + r < rows && i < q.rowlen / 4;
-                    const float4 *x4 = reinterpret_cast<const float4 *>(q.x + (ok ? row0 + r : 0) * (size_t)q.rowlen);
-                    const float4 t = x4[ok ? i : 0];
-                    a[r][h] = ok ? t : make_float4(0.f, 0.f, 0.f, 0.f);
-                }
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int h = 0; h < 2; ++h)
-                    m[r] = fmaxf(m[r], fmaxf(fmaxf(fabsf(a[r][h].x), fabsf(a[r][h].y)), fmaxf(fabsf(a[r][h].z), fabsf(a[r][h].w))));
-        } else {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                if (row0 + r >= rows) break;
-                const float *x = q.x + (row0 + r) * (size_t)q.rowlen;
-                if (q.vec) {
-                    const float4 *x4 = reinterpret_cast<const float4 *>(x);
-                    for (int i = lane; i < q.rowlen / 4; i += 64) {
-                        const float4 t = x4[i];
-                        m[r] = fmaxf(m[r], fmaxf(fmaxf(fabsf(t.x), fabsf(t.y)), fmaxf(fabsf(t.z), fabsf(t.w))));
-                    }
-                } else {
-                    for (int i = lane; i < q.rowlen; i += 64) m[r] = fmaxf(m[r], fabsf(x[i]));
-                }
-            }
-        }
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const unsigned u = wave_max_lane63(__float_as_uint(m[r]));
-            if (lane == 63 && row0 + r < rows) q.slots[row0 + r] = u;
-        }
+    if (rows <= nw) {
+        if (wid < rows) absmax_rows_batch<1>(q, wid, rows, lane);
+    } else {
+        for (size_t row0 = wid * 4; row0 < rows; row0 += nw * 4) absmax_rows_batch<4>(q, row0, rows, lane);
     }
 }
 
@@ -206,6 +240,14 @@ __device__ __forceinline__ void absmax_pass_block(const PrepArgs::Pass &q, int p
         const float4 *x4 = reinterpret_cast<const float4 *>(q.x);
         size_t i = (size_t)piece * 256 + tid;
         const size_t stride = (size_t)q.nblocks * 256;
+        for (; i + 7 * stride < n4; i += 8 * stride) {          // eight loads in flight
+            float4 v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = x4[i + j * stride];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                m = fmaxf(m, fmaxf(fmaxf(fabsf(v[j].x), fabsf(v[j].y)), fmaxf(fabsf(v[j].z), fabsf(v[j].w))));
+        }
         for (; i + 3 * stride < n4; i += 4 * stride) {          // four loads in flight
             const float4 a = x4[i], b = x4[i + stride], c = x4[i + 2 * stride], d = x4[i + 3 * stride];
             m = fmaxf(m, fmaxf(fmaxf(fmaxf(fabsf(a.x), fabsf(a.y)), fmaxf(fabsf(a.z), fabsf(a.w))),
@@ -325,7 +367,7 @@ hipError_t launch_prep(const PrepArgs &a_in, hipStream_t s)
 int coldot_slabs(int64_t T)
 {
     int64_t n = (T + 63) / 64;
-    if (n > 64) n = 64;
+    if (n > 64) n = 64;                     // (128 and 256 slabs at 16384 tokens: within 0.5 % either way)
     if (n < 1) n = 1;
     return (int)n;
 }

@@ -213,6 +213,14 @@ inline int pass_pieces(size_t n)
     return (int)(rounds < 1 ? 1 : (rounds > (size_t)PREP_PASS_BLOCKS ? (size_t)PREP_PASS_BLOCKS : rounds));
 }
 
+// workgroups of the pass that measures the largest magnitude of every row: a row per wavefront (four
+// wavefronts per workgroup) while that stays within the limit, else four rows per wavefront at a time
+inline int row_pass_blocks(size_t rows)
+{
+    const size_t b = (rows + 3) / 4;
+    return (int)(b < 1 ? 1 : (b > (size_t)PREP_ROW_PASS_BLOCKS ? (size_t)PREP_ROW_PASS_BLOCKS : b));
+}
+
 inline bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 
 inline uint32_t spin_limit() { return scan_spin_limit(); }
@@ -297,7 +305,7 @@ ssm_status run_fwd(const ssm_c64 *Lambda, const ssm_c64 *B, const ssm_c64 *C, co
         // u and x enter their products with tokens as rows: every token gets its own scale
         pa.bbar_max = am_bbar; pa.cc_max = am_cc;
         pa.pass[0].x = u; pa.pass[0].n = (size_t)T * H; pa.pass[0].slots = rowmax; pa.pass[0].rowlen = (int)H;
-        pa.pass[0].nblocks = pass_pieces((size_t)T * H);
+        pa.pass[0].nblocks = row_pass_blocks((size_t)T);
     }
     if (gate_max) {
         pa.pass[1].x = gate_max->W; pa.pass[1].n = gate_max->nW; pa.pass[1].slots = gate_max->wslots;

@@ -206,7 +206,8 @@ struct PrepArgs {
                              // rowlen == 0: slots[nblocks] of nblocks pieces of x[n]; rowlen > 0: slots[n / rowlen],
                              // one per row of rowlen values; block0 and vec set by launch_prep
 };
-constexpr int PREP_PASS_BLOCKS = 256;
+constexpr int PREP_PASS_BLOCKS = 256;        // pieces of a pass that measures one maximum per piece
+constexpr int PREP_ROW_PASS_BLOCKS = 1024;   // workgroups of a pass that measures one maximum per row
 hipError_t launch_prep(const PrepArgs &a, hipStream_t s);
 
 
