@@ -405,10 +405,9 @@ __device__ void psi_prime(double zr, double zi, double er, double ei, double &pr
 }
 
 // fixed-order sum of n slabs (stride apart) with up to eight loads in flight
-__device__ __forceinline__ float sum_slabs(const float *base, long stride, int n)
+__device__ __forceinline__ float sum_slabs(const float *base, long stride, int n, int i = 0, float s = 0.f)
 {
-    float s = 0.f;
-    int i = 0;
+    // (i, s: continue behind the first i slabs, whose sum in the same order is s)
     for (; i + 8 <= n; i += 8) {
         float v[8];
 #pragma unroll
@@ -425,17 +424,27 @@ __device__ __forceinline__ float sum_slabs(const float *base, long stride, int n
     return s;
 }
 
-// deterministic tree sum of one double pair per thread; result valid in thread 0
+// deterministic sum of one double pair per thread over the 256 threads of a workgroup; result valid in thread 0.
+// Inside a wavefront a fixed butterfly of lane exchanges, then the four wavefront sums in order through LDS
+// (two barriers; a tree over all 256 values through LDS took eight and ~0.9 us).
+__device__ __forceinline__ double shfl_xor_double(double v, int mask)
+{
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __shfl_xor(lo, mask); hi = __shfl_xor(hi, mask);
+    return __hiloint2double(hi, lo);
+}
 __device__ __forceinline__ void block_sum2(double *red_r, double *red_i, double &r, double &i, int tid)
 {
-    __syncthreads();
-    red_r[tid] = r; red_i[tid] = i;
-    __syncthreads();
-    for (int w = 128; w > 0; w >>= 1) {
-        if (tid < w) { red_r[tid] += red_r[tid + w]; red_i[tid] += red_i[tid + w]; }
-        __syncthreads();
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        r += shfl_xor_double(r, o);
+        i += shfl_xor_double(i, o);
     }
-    r = red_r[0]; i = red_i[0];
+    __syncthreads();                                   // (red_r, red_i may still be read from an earlier call)
+    if ((tid & 63) == 0) { red_r[tid >> 6] = r; red_i[tid >> 6] = i; }
+    __syncthreads();
+    r = (red_r[0] + red_r[1]) + (red_r[2] + red_r[3]);
+    i = (red_i[0] + red_i[1]) + (red_i[2] + red_i[3]);
 }
 
 // 2048 elements per workgroup (eight per thread, as two float4 where alignment allows)
@@ -473,31 +482,56 @@ __global__ void __launch_bounds__(256) epilogue_kernel(EpilogueArgs a)
     const int blk = blockIdx.x - a.sum.nblocks;
     const long PH2 = 2L * a.P * a.H;
     if (blk < a.P) {
+        // The workgroups of this launch are all resident at once, so it lasts as long as the chain of dependent
+        // steps of one of them.  The loads that need nothing from the discretisation are requested first (the
+        // first partial row of dAbar, the slabs of the thread's first column), so that its double-precision
+        // transcendentals, and psi' behind them, run while those are under way.
         const int p = blk;
+        const float2 apart0 = tid < a.npart ? a.dAbar_part[(long)tid * a.P + p] : make_float2(0.f, 0.f);
+        constexpr int EARLY = 8;                      // slabs of the first column requested ahead
+        const int hc = tid < a.H ? tid : 0;
+        const int nearly = a.nsplit_B < EARLY ? a.nsplit_B : EARLY;
+        float vr[EARLY], vi[EARLY];
+#pragma unroll
+        for (int j = 0; j < EARLY; ++j) {
+            const long o = (long)(j < nearly ? j : 0) * PH2;
+            vr[j] = a.dBbar_part[o + (long)(2 * p) * a.H + hc];
+            vi[j] = a.dBbar_part[o + (long)(2 * p + 1) * a.H + hc];
+        }
+        const float2 bv0 = a.B[(long)p * a.H + hc];
         const Zoh z = zoh_discretize(a.Lambda[p], a.log_delta[p]);
+        double pr, pi;
+        psi_prime(z.zr, z.zi, z.lr, z.li, pr, pi);
+        // (the barrier keeps the waits for the loads above behind the arithmetic above)
+        __builtin_amdgcn_sched_barrier(0);
+        float sr0 = 0.f, si0 = 0.f;
+#pragma unroll
+        for (int j = 0; j < EARLY; ++j)
+            if (j < nearly) { sr0 += vr[j]; si0 += vi[j]; }
+        sr0 = sum_slabs(a.dBbar_part + (long)(2 * p) * a.H + hc, PH2, a.nsplit_B, nearly, sr0);
+        si0 = sum_slabs(a.dBbar_part + (long)(2 * p + 1) * a.H + hc, PH2, a.nsplit_B, nearly, si0);
         const float gr = (float)z.gr, gi = (float)z.gi;
         double dgr = 0.0, dgi = 0.0;
         for (int h = tid; h < a.H; h += 256) {
-            const float sr = sum_slabs(a.dBbar_part + (long)(2 * p) * a.H + h, PH2, a.nsplit_B);
-            const float si = sum_slabs(a.dBbar_part + (long)(2 * p + 1) * a.H + h, PH2, a.nsplit_B);
+            const bool first = h == tid;
+            const float sr = first ? sr0 : sum_slabs(a.dBbar_part + (long)(2 * p) * a.H + h, PH2, a.nsplit_B);
+            const float si = first ? si0 : sum_slabs(a.dBbar_part + (long)(2 * p + 1) * a.H + h, PH2, a.nsplit_B);
             // conj(g) * dBbar
             a.dB[(long)p * a.H + h] = make_float2(gr * sr + gi * si, gr * si - gi * sr);
-            const float2 bv = a.B[(long)p * a.H + h];
+            const float2 bv = first ? bv0 : a.B[(long)p * a.H + h];
             // conj(B) * dBbar
             dgr += (double)bv.x * sr + (double)bv.y * si;
             dgi += (double)bv.x * si - (double)bv.y * sr;
         }
         block_sum2(red_r, red_i, dgr, dgi, tid);
-        double ar = 0.0, ai = 0.0;                    // dAbar: partial rows of the reverse scan
-        for (long i = tid; i < a.npart; i += 256) {
+        double ar = (double)apart0.x, ai = (double)apart0.y;     // dAbar: partial rows of the reverse scan
+        for (long i = tid + 256; i < a.npart; i += 256) {
             ar += (double)a.dAbar_part[i * a.P + p].x;
             ai += (double)a.dAbar_part[i * a.P + p].y;
         }
         block_sum2(red_r, red_i, ar, ai, tid);
         if (tid == 0) {
             const double Lr = a.Lambda[p].x, Li = a.Lambda[p].y, d = z.delta;
-            double pr, pi;
-            psi_prime(z.zr, z.zi, z.lr, z.li, pr, pi);
             // conj(d * Abar) * dAbar + conj(d^2 psi') * dg
             const double c1r = d * z.lr, c1i = d * z.li, c2r = d * d * pr, c2i = d * d * pi;
             const double dLr = (c1r * ar + c1i * ai) + (c2r * dgr + c2i * dgi);
