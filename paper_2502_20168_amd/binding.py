@@ -52,6 +52,10 @@ def lib():
         if not os.path.exists(LIB_PATH):
             raise ImportError("libssmscan.so is not built: run `python -c \"import __graft_entry__ as g; "
                               "g.build()\"` or `python paper_2502_20168_amd/build.py` first")
+        # torch first: it brings its own copy of the HIP runtime, and the library must bind to that one.  Loaded
+        # before torch, the library would pull in the system's copy, torch a second one afterwards, and
+        # every launch on torch's memory and streams would fail (status SSM_ERR_HIP)
+        _torch()
         L = ctypes.CDLL(LIB_PATH)
         L.ssm_strerror.restype = ctypes.c_char_p
         L.ssm_strerror.argtypes = [ctypes.c_int]

@@ -800,3 +800,22 @@ def test_captured_graph_replays_equal_eager(Bt, L, H, P):
         for k, v in list(out_f.items()) + list(out_b.items()):
             assert torch.equal(v, ref[k]), "replay %d differs from the eager result in %s" % (rep, k)
         assert ssm.ssm_workspace_status(ws_f) == ssm.SSM_OK and ssm.ssm_workspace_status(ws_b) == ssm.SSM_OK
+
+
+def test_host_only_call_before_torch_does_not_break_later_launches():
+    """A fresh interpreter that asks for a plan (host logic only) before it ever imports torch, then runs a
+    forward pass: the launches work on torch's memory (one copy of the HIP runtime in the process)."""
+    import os, subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = ("import sys; sys.path.insert(0, %r)\n"
+            "from paper_2502_20168_amd import binding as ssm, workloads as wl\n"
+            "ssm.ssm_plan_describe(32, 32, 512, 510)\n"
+            "import torch\n"
+            "d = ssm.to_device(wl.gen_inputs(wl.custom('order', 4, 32, 24, 40, p_reset=0.05, seed=3)))\n"
+            "out = ssm.ssm_scan_fwd(d['Lambda'], d['B'], d['C'], d['D'], d['log_delta'], d['u'], d['is_first'], d['x0'])\n"
+            "torch.cuda.synchronize()\n"
+            "assert bool(torch.isfinite(out['y']).all())\n"
+            "print('ok')\n" % root)
+    out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
+    assert out.returncode == 0, out.stderr[-2000:]
+    assert out.stdout.strip().splitlines()[-1] == "ok"

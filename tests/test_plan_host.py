@@ -116,3 +116,19 @@ def test_plan_rejects_what_the_library_rejects():
         ssm.ssm_plan_describe(0, 16, 8, 8)
     with pytest.raises(ssm.SsmError):
         ssm.ssm_plan_describe(1, 16, 1 << 20, 8)
+
+
+def test_the_binding_loads_torch_before_the_library():
+    """A host-only call (no GPU work) must not bind the library to the system's copy of the HIP runtime: torch
+    brings its own, and with two copies in the process every later launch on torch's memory fails.  In a fresh
+    interpreter, a plan query before any `import torch` leaves torch loaded first."""
+    import os, subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = ("import sys; sys.path.insert(0, %r)\n"
+            "from paper_2502_20168_amd import binding as ssm\n"
+            "assert 'torch' not in sys.modules\n"
+            "print(ssm.ssm_plan_describe(16, 256, 512, 512)['planes'])\n"
+            "assert 'torch' in sys.modules\n" % root)
+    out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
+    assert out.returncode == 0, out.stderr
+    assert out.stdout.strip().splitlines()[-1] == "2"
