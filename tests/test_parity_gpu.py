@@ -89,6 +89,45 @@ def test_seeded_random_shapes(case):
     check_workload(wl.custom(name, Bt, L, H, P, p_reset=pr, force_first=ff, with_x0=x0, seed=seed), backward=True)
 
 
+def _random_large_shapes(n, seed):
+    """Seeded shapes on the paths that small random shapes never reach: separate scan kernels with two scaled
+    fp16 planes (H, P >= 512, L no multiple of 128), more scanning tiles than CUs (two workgroups per CU in
+    both projections), and 64-255 scanning tiles with layer widths around the K-step rule of the output
+    projection."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    out = []
+    for i in range(n):
+        kind = i % 3
+        if kind == 0:
+            L = int(rng.choice([50, 100, 200, 300, 77, 130]))
+            Bt = int(rng.integers(max(1, 1500 // L), max(2, 5000 // L)))
+            H = int(rng.choice([512, 576, 640, 768, 1024, 520, 1100]))
+            P = int(rng.choice([512, 520, 600, 640, 768, 1000]))
+        elif kind == 1:
+            L = int(rng.choice([16, 32, 64, 128, 256, 512, 1024, 2048, 4096]))
+            Bt = max(1, int(rng.choice([4096, 8192, 6144])) // L)
+            H = int(rng.choice([rng.integers(8, 200), 64 * rng.integers(1, 9)]))
+            P = int(rng.choice([320, 384, 500, 512, 640, 700]))
+        else:
+            L = int(rng.choice([32, 64, 128, 256, 512]))
+            Bt = max(1, int(rng.choice([1024, 2048, 4096])) // L)
+            H = int(rng.choice([256, 320, 512, 576, 1024, 130]))
+            P = int(rng.choice([256, 288, 480, 510, 512]))
+        out.append(("large%d" % i, Bt, L, H, P, float(rng.choice([0.0, 0.01, 0.2])), bool(rng.integers(0, 2)),
+                    bool(rng.integers(0, 2)), 300 + i))
+    return out
+
+
+RANDOM_LARGE_SHAPES = _random_large_shapes(12, 20250221)
+
+
+@pytest.mark.parametrize("case", RANDOM_LARGE_SHAPES, ids=["%s_%dx%dx%dx%d" % c[:5] for c in RANDOM_LARGE_SHAPES])
+def test_seeded_random_shapes_on_the_large_paths(case):
+    name, Bt, L, H, P, pr, ff, x0, seed = case
+    print("random large shape", case, ssm.ssm_plan_describe(Bt, L, H, P), flush=True)
+    check_workload(wl.custom(name, Bt, L, H, P, p_reset=pr, force_first=ff, with_x0=x0, seed=seed), backward=True)
+
+
 @pytest.mark.parametrize("Bt,L,H,P", [(2, 5, 8, 65536), (2, 5, 65536, 4), (1, 300, 4, 8192)])
 def test_maximum_widths(Bt, L, H, P):
     """The widest state and layer the library accepts (SSM_MAX_WIDTH = 65536) with few tokens: index
