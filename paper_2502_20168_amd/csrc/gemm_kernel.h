@@ -1042,7 +1042,9 @@ __device__ __forceinline__ void gemm_ws_tile(const GemmDev &g, __bf16 *smem, int
                     const unsigned m = rowmax;
                     const int r = rows16_half_index(l);
                     const long row = m0 + wm * WM + i * 32 + 4 * hh + 8 * (r / 4) + (r % 4);
-                    if ((l & 16) == 0 && row < g.M) g.c2_rowmax[(size_t)((n0 + wn * WN) / 64) * g.M + row] = m;
+                    // (a wavefront whose 64 columns lie past N entirely has no piece: the last column tile of a
+                    // width that is an odd multiple of 64)
+                    if ((l & 16) == 0 && row < g.M && n0 + wn * WN < g.N) g.c2_rowmax[(size_t)((n0 + wn * WN) / 64) * g.M + row] = m;
                 }
             }
         }

@@ -107,7 +107,10 @@ def test_half_glu_is_bitwise_repeatable():
 
 # the benchmark shape (the K halves of y meet in the launch; the gate on two fp16 planes), two small ragged ones,
 # and one whose output projection runs on 64x128 tiles and hands the gate its row maxima from there
-@pytest.mark.parametrize("Bt,L,H,P", [(16, 256, 512, 512), (3, 129, 50, 33), (2, 600, 96, 40), (8, 512, 512, 64)])
+# ... and two whose width is an odd multiple of 64 (the last column tile of the output projection has a wavefront
+# with no columns at all: no row maxima from there), with separate scan kernels and with scanning projections
+@pytest.mark.parametrize("Bt,L,H,P", [(16, 256, 512, 512), (3, 129, 50, 33), (2, 600, 96, 40), (8, 512, 512, 64),
+                                      (81, 50, 576, 288), (16, 256, 576, 512)])
 def test_s5_block_matches_oracle_composition(Bt, L, H, P):
     """SSM layer + half-GLU gate in one call (GELU of the layer's output formed in the output
     projection's store) against the two oracles composed: forward outputs, then every gradient."""
