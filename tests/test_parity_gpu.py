@@ -858,3 +858,38 @@ def test_host_only_call_before_torch_does_not_break_later_launches():
     out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
     assert out.returncode == 0, out.stderr[-2000:]
     assert out.stdout.strip().splitlines()[-1] == "ok"
+
+
+@pytest.mark.parametrize("Bt,L,H,P", [(16, 256, 512, 512), (24, 100, 512, 512), (6, 200, 100, 96)])
+def test_operands_at_addresses_that_are_only_element_aligned_on_a_side_stream(Bt, L, H, P):
+    """Every input (and the saved states handed to the gradient pass) one to three elements behind an aligned
+    allocation -- 4-byte aligned floats, 8-byte aligned complex values, nothing more, which is what the header
+    asks for -- and the calls on a stream of their own: the 16-byte loaders step aside, the results hold."""
+    import torch
+    rng = np.random.Generator(np.random.PCG64(Bt + L))
+
+    def shifted(t, off):
+        if t is None:
+            return None
+        flat = torch.empty(t.numel() + 8, dtype=t.dtype, device=t.device)
+        v = flat[off:off + t.numel()].view(t.shape)
+        v.copy_(t)
+        return v
+
+    w = wl.custom("offsets", Bt, L, H, P, p_reset=0.02, force_first=True, with_x0=True, seed=61)
+    inp = wl.gen_inputs(w)
+    ref = orc.run_workload(inp, True, nthreads=8)
+    d = ssm.to_device(inp)
+    e = {k: shifted(v, int(rng.integers(1, 4))) for k, v in d.items()}
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        fwd = ssm.ssm_scan_fwd(e["Lambda"], e["B"], e["C"], e["D"], e["log_delta"], e["u"], e["is_first"], e["x0"], stream=side)
+        xs = shifted(fwd["x"], 1)
+        bwd = ssm.ssm_scan_bwd(e["Lambda"], e["B"], e["C"], e["D"], e["log_delta"], e["u"], e["is_first"], e["x0"], xs,
+                               e["dy"], stream=side)
+    torch.cuda.synchronize()
+    for k in ("y", "x", "x_last"):
+        assert_close(fwd[k].cpu().numpy(), ref[k], TOL_FWD, "offsets " + k)
+    for k in GRAD_KEYS:
+        assert_close(bwd[k].cpu().numpy(), ref[k], TOL_GRAD, "offsets " + k)
