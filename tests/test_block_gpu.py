@@ -160,3 +160,44 @@ def test_half_glu_seeded_random_shapes(T, H):
                                  np.random.Generator(np.random.PCG64(7)).integers([1, 1], [70, 9000], size=(8, 2))])
 def test_lambda_return_seeded_random_shapes(T, N):
     test_lambda_return_matches_oracle(T, N)
+
+
+@pytest.mark.parametrize("Bt,L,H,P", [(16, 256, 512, 512), (81, 50, 576, 288), (16, 256, 576, 512), (4, 4096, 256, 256),
+                                      (24, 100, 512, 512), (13, 100, 1200, 256), (3, 129, 50, 33), (64, 16, 704, 520),
+                                      (292, 7, 668, 128), (16, 64, 256, 256)])
+def test_no_call_writes_outside_its_workspace(Bt, L, H, P):
+    """Layer, S5 block and gate, forward and gradient pass, each on a workspace of exactly the size the library
+    asks for, between two guard zones filled with a pattern: the zones are untouched afterwards."""
+    import torch
+    from paper_2502_20168_amd import binding as ssm
+    guard = 1 << 16
+
+    def guarded(nbytes):
+        buf = torch.full((guard + nbytes + guard,), 0xA5, dtype=torch.uint8, device="cuda")
+        return buf, buf[guard:guard + nbytes]
+
+    def check(buf, nbytes, what):
+        assert bool((buf[:guard] == 0xA5).all()), "write below the workspace: " + what
+        assert bool((buf[guard + nbytes:] == 0xA5).all()), "write past the workspace: " + what
+
+    w = wl.custom("guard", Bt, L, H, P, backward=True, p_reset=0.02, force_first=True, with_x0=True, seed=5)
+    d = ssm.to_device(wl.gen_inputs(w))
+    par = (d["Lambda"], d["B"], d["C"], d["D"], d["log_delta"])
+    Wd = torch.from_numpy(wl.gen_half_glu(4, H, seed=7)["W"]).cuda()
+    T = Bt * L
+    sizes = {"layer": (ssm.ssm_workspace_bytes(Bt, L, H, P, False), ssm.ssm_workspace_bytes(Bt, L, H, P, True)),
+             "block": (ssm.ssm_block_workspace_bytes(Bt, L, H, P, False), ssm.ssm_block_workspace_bytes(Bt, L, H, P, True)),
+             "gate": (ssm.ssm_half_glu_workspace_bytes(T, H, False), ssm.ssm_half_glu_workspace_bytes(T, H, True))}
+    bufs = {k: (guarded(nf), guarded(nb)) for k, (nf, nb) in sizes.items()}
+    f = ssm.ssm_scan_fwd(*par, d["u"], d["is_first"], d["x0"], workspace=bufs["layer"][0][1])
+    ssm.ssm_scan_bwd(*par, d["u"], d["is_first"], d["x0"], f["x"], d["dy"], workspace=bufs["layer"][1][1])
+    fb = ssm.ssm_block_fwd(*par, Wd, d["u"], d["is_first"], d["x0"], workspace=bufs["block"][0][1])
+    ssm.ssm_block_bwd(*par, Wd, d["u"], d["is_first"], d["x0"], fb["x"], fb["y"], fb["gate"], d["dy"],
+                      workspace=bufs["block"][1][1])
+    u2 = d["u"].reshape(T, H)
+    y, gate = ssm.ssm_half_glu_fwd(u2, Wd, workspace=bufs["gate"][0][1])
+    ssm.ssm_half_glu_bwd(u2, Wd, gate, d["dy"].reshape(T, H), workspace=bufs["gate"][1][1])
+    torch.cuda.synchronize()
+    for k, (nf, nb) in sizes.items():
+        check(bufs[k][0][0], nf, k + " forward")
+        check(bufs[k][1][0], nb, k + " gradient pass")
