@@ -29,6 +29,10 @@
  *     dl/dRe(q) + i dl/dIm(q).
  *   - The library reads no environment variable and keeps no state between calls other than the
  *     poll bound of ssm_set_spin_limit below.
+ *   - The device pointers and the stream must belong to the copy of the HIP runtime the library is
+ *     bound to.  A process that takes its memory from a framework which ships its own copy (PyTorch
+ *     does) loads that framework before this library, so that both use one copy; bound to another,
+ *     every launch fails with SSM_ERR_HIP.
  *   - Arithmetic of the projections: inputs, outputs and accumulation are fp32; the products run on
  *     the 16-bit matrix cores with both operands split while they are staged.  Where the largest
  *     magnitude of every operand is measured on the device as part of the call (ssm_scan_fwd /
