@@ -893,3 +893,30 @@ def test_operands_at_addresses_that_are_only_element_aligned_on_a_side_stream(Bt
         assert_close(fwd[k].cpu().numpy(), ref[k], TOL_FWD, "offsets " + k)
     for k in GRAD_KEYS:
         assert_close(bwd[k].cpu().numpy(), ref[k], TOL_GRAD, "offsets " + k)
+
+
+def test_two_million_tokens_are_512_copies_of_the_benchmark_batch():
+    """Index arithmetic past 2^31 elements (x has 2^31 floats here, 8 GiB): the benchmark batch repeated 512 times
+    along the batch.  Sequences are independent and every token row carries its own scale, so every copy's y, x,
+    x_last, du and dx0 must equal the first copy's bit for bit, and the first copy's must equal the results on
+    the batch alone; the parameter gradients are 512 times the batch's within the accumulation error."""
+    import torch
+    Bt0, L, H, P, copies = 16, 256, 512, 512, 512
+    w = wl.custom("big", Bt0, L, H, P, p_reset=0.01, force_first=True, with_x0=True, seed=3)
+    d = ssm.to_device(wl.gen_inputs(w))
+    par = (d["Lambda"], d["B"], d["C"], d["D"], d["log_delta"])
+    small_f = ssm.ssm_scan_fwd(*par, d["u"], d["is_first"], d["x0"])
+    small_b = ssm.ssm_scan_bwd(*par, d["u"], d["is_first"], d["x0"], small_f["x"], d["dy"])
+    rep = lambda t: t.repeat((copies,) + (1,) * (t.dim() - 1)).contiguous()
+    u, flags, x0, dy = rep(d["u"]), rep(d["is_first"]), rep(d["x0"]), rep(d["dy"])
+    f = ssm.ssm_scan_fwd(*par, u, flags, x0)
+    b = ssm.ssm_scan_bwd(*par, u, flags, x0, f["x"], dy)
+    torch.cuda.synchronize()
+    for big, small, name in [(f[k], small_f[k], k) for k in ("y", "x", "x_last")] + [(b[k], small_b[k], k) for k in ("du", "dx0")]:
+        v = big.view((copies,) + tuple(small.shape))
+        assert torch.equal(v[0], small), name + ": the first copy differs from the batch alone"
+        assert bool((v == v[0:1]).all()), name + ": a copy differs from the first"
+    for k in ("dLambda", "dB", "dC", "dD", "dlog_delta"):
+        ref = small_b[k].to(torch.complex128 if small_b[k].is_complex() else torch.float64) * copies
+        err = float((b[k].to(ref.dtype) - ref).abs().max()) / float(ref.abs().max())
+        assert err < 1e-3, "%s: %.2e" % (k, err)
