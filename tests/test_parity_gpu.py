@@ -920,3 +920,46 @@ def test_two_million_tokens_are_512_copies_of_the_benchmark_batch():
         ref = small_b[k].to(torch.complex128 if small_b[k].is_complex() else torch.float64) * copies
         err = float((b[k].to(ref.dtype) - ref).abs().max()) / float(ref.abs().max())
         assert err < 1e-3, "%s: %.2e" % (k, err)
+
+
+def test_concurrent_calls_from_four_host_threads_on_their_own_streams_and_workspaces():
+    """The header's promise: concurrent calls are safe as long as they use distinct workspaces.  Four host
+    threads (the binding's calls release the interpreter lock), each with a stream and two workspaces of its
+    own, repeat the forward and the gradient pass of their shape; every result equals the single-threaded one
+    bit for bit."""
+    import threading
+    import torch
+    shapes = [(16, 256, 512, 512), (24, 100, 512, 512), (8, 100, 256, 256), (4, 4096, 256, 256)]
+    data = []
+    for i, shp in enumerate(shapes):
+        d = ssm.to_device(wl.gen_inputs(wl.custom("thr%d" % i, *shp, p_reset=0.01, force_first=True, with_x0=True, seed=10 + i)))
+        par = (d["Lambda"], d["B"], d["C"], d["D"], d["log_delta"])
+        f = ssm.ssm_scan_fwd(*par, d["u"], d["is_first"], d["x0"])
+        b = ssm.ssm_scan_bwd(*par, d["u"], d["is_first"], d["x0"], f["x"], d["dy"])
+        torch.cuda.synchronize()
+        data.append((shp, d, par, f, b))
+    errors = []
+
+    def worker(tid):
+        try:
+            st = torch.cuda.Stream()
+            shp, d, par, f0, b0 = data[tid]
+            ws_f, ws_b = ssm.alloc_workspace(*shp, False), ssm.alloc_workspace(*shp, True)
+            for it in range(10):
+                with torch.cuda.stream(st):
+                    f = ssm.ssm_scan_fwd(*par, d["u"], d["is_first"], d["x0"], workspace=ws_f, stream=st)
+                    b = ssm.ssm_scan_bwd(*par, d["u"], d["is_first"], d["x0"], f["x"], d["dy"], workspace=ws_b, stream=st)
+                st.synchronize()
+                errors.extend((tid, it, k) for k in ("y", "x", "x_last") if not torch.equal(f[k], f0[k]))
+                errors.extend((tid, it, k) for k in GRAD_KEYS if not torch.equal(b[k], b0[k]))
+                if ssm.ssm_workspace_status(ws_f, st) != ssm.SSM_OK or ssm.ssm_workspace_status(ws_b, st) != ssm.SSM_OK:
+                    errors.append((tid, it, "status"))
+        except Exception as e:          # a thread's exception must fail the test, not vanish
+            errors.append((tid, repr(e)))
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(len(shapes))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors[:10]
